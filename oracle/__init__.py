@@ -1,0 +1,170 @@
+"""ctypes front end of the CPU oracle (``sw_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by the tests, by the smoke check and by the
+benchmark's CPU-baseline leg.  The GPU library never imports this package and
+this package never imports the GPU library.
+
+Every function takes numpy arrays, widens nothing itself (the C code widens
+fp32 to fp64 exactly) and returns ``(y, D)`` in float64, where ``D`` is the
+per-output magnitude sum ``sum |x*w|`` that the parity tolerance is relative
+to.  The int8 function returns exact int32 sums.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sw_oracle.c")
+_LIB = os.path.join(_HERE, "libsw_oracle.so")
+_lib = None
+
+POOL_AVG = 0
+POOL_MAX = 1
+
+
+def build(force: bool = False) -> str:
+    """Compile ``sw_oracle.c`` with the host gcc (no fast-math) and return the path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        cmd = ["gcc", "-std=c11", "-O2", "-fopenmp", "-fno-fast-math", "-ffp-contract=off",
+               "-shared", "-fPIC", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    i64, vp = ctypes.c_int64, ctypes.c_void_p
+    lib.oracle_out_dim.restype = i64
+    lib.oracle_out_dim.argtypes = [i64] * 4
+    lib.oracle_max_threads.restype = ctypes.c_int
+    lib.oracle_set_threads.argtypes = [ctypes.c_int]
+    lib.oracle_conv2d.restype = ctypes.c_int
+    lib.oracle_conv2d.argtypes = [vp] * 4 + [i64] * 9
+    lib.oracle_conv2d_depthwise.restype = ctypes.c_int
+    lib.oracle_conv2d_depthwise.argtypes = [vp] * 4 + [i64] * 8
+    lib.oracle_conv1d.restype = ctypes.c_int
+    lib.oracle_conv1d.argtypes = [vp] * 4 + [i64] * 5
+    lib.oracle_pool1d.restype = ctypes.c_int
+    lib.oracle_pool1d.argtypes = [vp] * 3 + [i64] * 4 + [ctypes.c_int]
+    lib.oracle_conv2d_s8.restype = ctypes.c_int
+    lib.oracle_conv2d_s8.argtypes = [vp] * 3 + [i64] * 9
+    _lib = lib
+    return lib
+
+
+def _p(a: np.ndarray) -> ctypes.c_void_p:
+    return ctypes.c_void_p(a.ctypes.data)
+
+
+def _as(a, dtype, ndim) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {np.dtype(dtype)}, got {a.dtype}")
+    if a.ndim != ndim:
+        raise ValueError(f"expected {ndim} dimensions, got shape {a.shape}")
+    return a
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().oracle_set_threads(int(n))
+
+
+def out_dim(n_in: int, k: int, stride: int, pad: int) -> int:
+    return int(_load().oracle_out_dim(n_in, k, stride, pad))
+
+
+def conv2d(x, w, stride: int = 1, pad: int = 0):
+    x = _as(x, np.float32, 4)
+    w = _as(w, np.float32, 4)
+    N, C_in, H, W = x.shape
+    C_out, C_in_w, R, S = w.shape
+    if C_in_w != C_in:
+        raise ValueError("channel mismatch")
+    Ho, Wo = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("filter does not fit the padded input")
+    y = np.empty((N, C_out, Ho, Wo), np.float64)
+    d = np.empty_like(y)
+    rc = _load().oracle_conv2d(_p(x), _p(w), _p(y), _p(d), N, C_in, C_out, H, W, R, S, stride, pad)
+    if rc:
+        raise ValueError(f"oracle_conv2d rejected the arguments (code {rc})")
+    return y, d
+
+
+def conv2d_depthwise(x, w, stride: int = 1, pad: int = 0):
+    x = _as(x, np.float32, 4)
+    w = _as(w, np.float32, 4)
+    N, C, H, W = x.shape
+    Cw, one, R, S = w.shape
+    if Cw != C or one != 1:
+        raise ValueError("depthwise weights must be [C,1,R,S]")
+    Ho, Wo = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("filter does not fit the padded input")
+    y = np.empty((N, C, Ho, Wo), np.float64)
+    d = np.empty_like(y)
+    rc = _load().oracle_conv2d_depthwise(_p(x), _p(w), _p(y), _p(d), N, C, H, W, R, S, stride, pad)
+    if rc:
+        raise ValueError(f"oracle_conv2d_depthwise rejected the arguments (code {rc})")
+    return y, d
+
+
+def conv1d(x, w, stride: int = 1, pad: int = 0):
+    x = _as(x, np.float32, 2)
+    w = _as(w, np.float32, 1)
+    rows, length = x.shape
+    k = w.shape[0]
+    Lo = out_dim(length, k, stride, pad)
+    if Lo <= 0:
+        raise ValueError("filter does not fit the padded input")
+    y = np.empty((rows, Lo), np.float64)
+    d = np.empty_like(y)
+    rc = _load().oracle_conv1d(_p(x), _p(w), _p(y), _p(d), rows, length, k, stride, pad)
+    if rc:
+        raise ValueError(f"oracle_conv1d rejected the arguments (code {rc})")
+    return y, d
+
+
+def pool1d(x, window: int, stride: int = 1, mode: int = POOL_AVG):
+    x = _as(x, np.float32, 2)
+    rows, length = x.shape
+    Lo = out_dim(length, window, stride, 0)
+    if Lo <= 0:
+        raise ValueError("window does not fit the input")
+    y = np.empty((rows, Lo), np.float64)
+    d = np.empty_like(y)
+    rc = _load().oracle_pool1d(_p(x), _p(y), _p(d), rows, length, window, stride, mode)
+    if rc:
+        raise ValueError(f"oracle_pool1d rejected the arguments (code {rc})")
+    return y, d
+
+
+def conv2d_s8(x, w, stride: int = 1, pad: int = 0):
+    x = _as(x, np.int8, 4)
+    w = _as(w, np.int8, 4)
+    N, C_in, H, W = x.shape
+    C_out, C_in_w, R, S = w.shape
+    if C_in_w != C_in:
+        raise ValueError("channel mismatch")
+    Ho, Wo = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("filter does not fit the padded input")
+    y = np.empty((N, C_out, Ho, Wo), np.int32)
+    rc = _load().oracle_conv2d_s8(_p(x), _p(w), _p(y), N, C_in, C_out, H, W, R, S, stride, pad)
+    if rc == 2:
+        raise OverflowError("an exact sum does not fit int32")
+    if rc:
+        raise ValueError(f"oracle_conv2d_s8 rejected the arguments (code {rc})")
+    return y

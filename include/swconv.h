@@ -1,0 +1,128 @@
+/*
+ * swconv -- Sliding Window Sum convolution and pooling for AMD Instinct MI355X (gfx950).
+ *
+ * C ABI of libswconv.so.  Every entry point evaluates a DNN convolution or a
+ * pooling directly on the unmodified input: a tile of the input plus its halo
+ * is brought on chip once and the filter taps are accumulated over shifted
+ * windows of that tile.  No column matrix (im2col) and no other workspace is
+ * ever written (paper, section 1: the column matrix is k times the input;
+ * section 2: the sliding kernel works on the unmodified input).
+ *
+ * Conventions common to all calls
+ * -------------------------------
+ *  - "Convolution" is the DNN one: cross-correlation, the filter is not flipped.
+ *  - Layout: dense row-major NCHW activations, OIHW weights.
+ *  - Padding is symmetric zero padding; output extent per axis is
+ *        out = floor((in + 2*pad - k) / stride) + 1        (see sw_out_dim).
+ *  - Every pointer is a DEVICE pointer owned by the caller.  The library never
+ *    allocates, frees or keeps device memory.  x and w are only read; y is
+ *    only written, and every element of y is written.
+ *  - Alignment: fp32 / int32 pointers must be 4-byte aligned (SW_ERR_ALIGN
+ *    otherwise).  16-byte alignment of x and y selects the vectorised paths;
+ *    anything less aligned still computes the same values.
+ *  - y must not overlap x or w (SW_ERR_ALIAS when the byte ranges intersect).
+ *  - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *    A call validates its arguments on the host, enqueues its kernel on that
+ *    stream and returns; it never synchronises.  Argument errors are detected
+ *    before anything is enqueued.
+ *  - Return value: an sw_status.  No exceptions, no abort.
+ *  - fp32 results are accumulated in fp32 (order unspecified); int8 results
+ *    are the exact int32 sums.
+ */
+#ifndef SWCONV_H
+#define SWCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SW_OK = 0,
+    SW_ERR_NULL = 1,        /* a required pointer is NULL                             */
+    SW_ERR_SHAPE = 2,       /* dim <= 0, stride <= 0, pad < 0, filter > padded input,  */
+                            /* or an element count beyond 2^31-1 per tensor            */
+    SW_ERR_UNSUPPORTED = 3, /* a valid problem the library has no kernel for           */
+    SW_ERR_ALIGN = 4,       /* pointer not aligned to its element size                 */
+    SW_ERR_ALIAS = 5,       /* y overlaps x or w                                       */
+    SW_ERR_LAUNCH = 6       /* the HIP runtime refused the launch (or no device)       */
+} sw_status;
+
+typedef enum { SW_POOL_AVG = 0, SW_POOL_MAX = 1 } sw_pool_mode;
+
+/*
+ * 1-D convolution as a sliding window sum (paper, abstract and section 2).
+ *     y[row, i] = sum_{j<k} w[j] * xz[row, i*stride + j - pad]
+ * x: [rows, len] fp32;  w: [k] fp32, one tap vector shared by all rows;
+ * y: [rows, len_out] fp32, len_out = sw_out_dim(len, k, stride, pad).
+ * Supported: 1 <= k <= 64, pad < k.  Otherwise SW_ERR_UNSUPPORTED.
+ */
+int sw_conv1d(const float* x, const float* w, float* y,
+              int64_t rows, int64_t len, int k, int stride, int pad, void* hip_stream);
+
+/*
+ * 1-D pooling with the same kernel structure (paper, abstract).
+ *     avg: y[row, i] = (1/window) * sum_{j<window} x[row, i*stride + j]
+ *     max: y[row, i] = max_{j<window} x[row, i*stride + j]
+ * No padding, so the average always divides by window.  The maximum is
+ * bit-exact; NaN inputs are outside the contract.
+ * x: [rows, len];  y: [rows, sw_out_dim(len, window, stride, 0)].
+ * Supported: 1 <= window <= 64.  mode is an sw_pool_mode (else SW_ERR_UNSUPPORTED).
+ */
+int sw_pool1d(const float* x, float* y, int64_t rows, int64_t len,
+              int window, int stride, int mode, void* hip_stream);
+
+/*
+ * 2-D convolution (paper, section 2: the 2-D sliding window convolution; for
+ * C_in > 1 every tap is a small C_out x C_in matrix product accumulated into
+ * the output tile, the re-formulation section 3 asks for).
+ *     y[n,co,i,j] = sum_{ci,r,s} w[co,ci,r,s] * xz[n,ci,i*stride+r-pad, j*stride+s-pad]
+ * x: [N,C_in,H,W] fp32;  w: [C_out,C_in,R,S] fp32;  y: [N,C_out,H_out,W_out] fp32.
+ * Supported: any shape with R,S <= 64 (generic kernel); C_in % 16 == 0,
+ * C_out % 64 == 0, 3x3, stride 1, pad 1 runs on the matrix cores.
+ */
+int sw_conv2d(const float* x, const float* w, float* y,
+              int N, int C_in, int C_out, int H, int W, int R, int S,
+              int stride, int pad, void* hip_stream);
+
+/*
+ * Depthwise 2-D convolution: one R x S filter per channel (paper, section 1.2,
+ * depthwise separable convolutions) -- a pure sliding sum, no C_in reduction.
+ *     y[n,c,i,j] = sum_{r,s} w[c,0,r,s] * xz[n,c,i*stride+r-pad, j*stride+s-pad]
+ * x: [N,C,H,W];  w: [C,1,R,S];  y: [N,C,H_out,W_out].
+ * Supported: any shape with R,S <= 64; 3x3, 5x5 and 7x7 at stride 1 have
+ * fixed-size kernels (the paper's "custom" kernels, section 2).
+ */
+int sw_conv2d_depthwise(const float* x, const float* w, float* y,
+                        int N, int C, int H, int W, int R, int S,
+                        int stride, int pad, void* hip_stream);
+
+/*
+ * Quantised 2-D convolution (paper, sections 1.1 and 3: quantisation applies to
+ * the sliding formulation as it does to GEMM).  int8 activations and weights,
+ * exact int32 sums, no requantisation.  Shapes as sw_conv2d.
+ * The caller guarantees C_in*R*S <= 131071 so that no sum can leave int32
+ * (SW_ERR_SHAPE otherwise).  x and w need no alignment; y is 4-byte aligned.
+ */
+int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y,
+                 int N, int C_in, int C_out, int H, int W, int R, int S,
+                 int stride, int pad, void* hip_stream);
+
+/* Output extent of one axis; <= 0 means the filter does not fit (or bad arguments). */
+int64_t sw_out_dim(int64_t in, int k, int stride, int pad);
+
+/* Device workspace the library needs: always 0 (paper, sections 1 and 2). */
+size_t sw_workspace_bytes(void);
+
+/* Static, NUL-terminated description of an sw_status value. */
+const char* sw_status_string(int status);
+
+/* major*10000 + minor*100 + patch */
+int sw_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWCONV_H */

@@ -1,0 +1,184 @@
+"""Thin ctypes binding of libswconv.so: argument marshalling only.
+
+PyTorch supplies device memory and the current HIP stream; every step of the computation runs in
+the library's kernels.  The functions carry the names of the C entry points they call.  If the
+library has not been built they raise: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libswconv.so")
+
+SW_OK = 0
+SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN, SW_ERR_ALIAS, SW_ERR_LAUNCH = 1, 2, 3, 4, 5, 6
+SW_POOL_AVG, SW_POOL_MAX = 0, 1
+
+EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
+           "sw_out_dim", "sw_workspace_bytes", "sw_status_string", "sw_version")
+
+_lib = None
+
+
+class SwError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        super().__init__(f"{what}: status {status} ({status_string(status)})")
+        self.status = status
+
+
+def lib() -> ctypes.CDLL:
+    """Load libswconv.so (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2310_05218_amd.build` first")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64
+    L.sw_conv1d.restype = i32
+    L.sw_conv1d.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp]
+    L.sw_pool1d.restype = i32
+    L.sw_pool1d.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp]
+    L.sw_conv2d.restype = i32
+    L.sw_conv2d.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
+    L.sw_conv2d_depthwise.restype = i32
+    L.sw_conv2d_depthwise.argtypes = [vp, vp, vp] + [i32] * 8 + [vp]
+    L.sw_conv2d_s8.restype = i32
+    L.sw_conv2d_s8.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
+    L.sw_out_dim.restype = i64
+    L.sw_out_dim.argtypes = [i64, i32, i32, i32]
+    L.sw_workspace_bytes.restype = ctypes.c_size_t
+    L.sw_workspace_bytes.argtypes = []
+    L.sw_status_string.restype = ctypes.c_char_p
+    L.sw_status_string.argtypes = [i32]
+    L.sw_version.restype = i32
+    L.sw_version.argtypes = []
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().sw_status_string(int(status)).decode()
+
+
+def sw_out_dim(n_in: int, k: int, stride: int, pad: int) -> int:
+    return int(lib().sw_out_dim(n_in, k, stride, pad))
+
+
+def sw_workspace_bytes() -> int:
+    return int(lib().sw_workspace_bytes())
+
+
+def sw_version() -> int:
+    return int(lib().sw_version())
+
+
+def _stream(stream):
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev(t, dtype, ndim, name):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.dtype != dtype or t.dim() != ndim or not t.is_contiguous():
+        raise ValueError(f"{name}: expected contiguous {dtype} with {ndim} dims, got {t.dtype} {tuple(t.shape)}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _check(rc: int, what: str):
+    if rc != SW_OK:
+        raise SwError(rc, what)
+
+
+def _out_shape(what, *dims):
+    if min(dims) <= 0:
+        raise SwError(SW_ERR_SHAPE, what)
+    return dims
+
+
+def sw_conv1d(x, w, stride: int = 1, pad: int = 0, out=None, stream=None):
+    """x [rows, len] fp32, w [k] fp32 -> y [rows, len_out] fp32 (device tensors)."""
+    import torch
+
+    rows, length = x.shape
+    k = w.shape[0]
+    if out is None:
+        out = torch.empty(_out_shape("sw_conv1d", rows, sw_out_dim(length, k, stride, pad)),
+                          dtype=torch.float32, device=x.device)
+    rc = lib().sw_conv1d(_dev(x, torch.float32, 2, "x"), _dev(w, torch.float32, 1, "w"),
+                         _dev(out, torch.float32, 2, "y"), rows, length, k, stride, pad, _stream(stream))
+    _check(rc, "sw_conv1d")
+    return out
+
+
+def sw_pool1d(x, window: int, stride: int = 1, mode: int = SW_POOL_AVG, out=None, stream=None):
+    """x [rows, len] fp32 -> y [rows, len_out] fp32; mode SW_POOL_AVG or SW_POOL_MAX."""
+    import torch
+
+    rows, length = x.shape
+    if out is None:
+        out = torch.empty(_out_shape("sw_pool1d", rows, sw_out_dim(length, window, stride, 0)),
+                          dtype=torch.float32, device=x.device)
+    rc = lib().sw_pool1d(_dev(x, torch.float32, 2, "x"), _dev(out, torch.float32, 2, "y"), rows, length,
+                         window, stride, mode, _stream(stream))
+    _check(rc, "sw_pool1d")
+    return out
+
+
+def sw_conv2d(x, w, stride: int = 1, pad: int = 0, out=None, stream=None):
+    """x [N,C_in,H,W] fp32, w [C_out,C_in,R,S] fp32 -> y [N,C_out,H_out,W_out] fp32."""
+    import torch
+
+    N, C_in, H, W = x.shape
+    C_out, C_in_w, R, S = w.shape
+    if C_in_w != C_in:
+        raise ValueError("channel mismatch between x and w")
+    if out is None:
+        out = torch.empty(_out_shape("sw_conv2d", N, C_out, sw_out_dim(H, R, stride, pad),
+                                     sw_out_dim(W, S, stride, pad)), dtype=torch.float32, device=x.device)
+    rc = lib().sw_conv2d(_dev(x, torch.float32, 4, "x"), _dev(w, torch.float32, 4, "w"),
+                         _dev(out, torch.float32, 4, "y"), N, C_in, C_out, H, W, R, S, stride, pad,
+                         _stream(stream))
+    _check(rc, "sw_conv2d")
+    return out
+
+
+def sw_conv2d_depthwise(x, w, stride: int = 1, pad: int = 0, out=None, stream=None):
+    """x [N,C,H,W] fp32, w [C,1,R,S] fp32 -> y [N,C,H_out,W_out] fp32."""
+    import torch
+
+    N, C, H, W = x.shape
+    Cw, one, R, S = w.shape
+    if Cw != C or one != 1:
+        raise ValueError("depthwise weights must be [C,1,R,S]")
+    if out is None:
+        out = torch.empty(_out_shape("sw_conv2d_depthwise", N, C, sw_out_dim(H, R, stride, pad),
+                                     sw_out_dim(W, S, stride, pad)), dtype=torch.float32, device=x.device)
+    rc = lib().sw_conv2d_depthwise(_dev(x, torch.float32, 4, "x"), _dev(w, torch.float32, 4, "w"),
+                                   _dev(out, torch.float32, 4, "y"), N, C, H, W, R, S, stride, pad,
+                                   _stream(stream))
+    _check(rc, "sw_conv2d_depthwise")
+    return out
+
+
+def sw_conv2d_s8(x, w, stride: int = 1, pad: int = 0, out=None, stream=None):
+    """x [N,C_in,H,W] int8, w [C_out,C_in,R,S] int8 -> y [N,C_out,H_out,W_out] int32 (exact sums)."""
+    import torch
+
+    N, C_in, H, W = x.shape
+    C_out, C_in_w, R, S = w.shape
+    if C_in_w != C_in:
+        raise ValueError("channel mismatch between x and w")
+    if out is None:
+        out = torch.empty(_out_shape("sw_conv2d_s8", N, C_out, sw_out_dim(H, R, stride, pad),
+                                     sw_out_dim(W, S, stride, pad)), dtype=torch.int32, device=x.device)
+    rc = lib().sw_conv2d_s8(_dev(x, torch.int8, 4, "x"), _dev(w, torch.int8, 4, "w"),
+                            _dev(out, torch.int32, 4, "y"), N, C_in, C_out, H, W, R, S, stride, pad,
+                            _stream(stream))
+    _check(rc, "sw_conv2d_s8")
+    return out

@@ -1,0 +1,130 @@
+// Direct kernels: one thread per output element, taps accumulated straight from global memory.
+// They cover every valid shape (any stride, padding, filter extent) and serve the shapes the
+// tiled sliding kernels do not specialise; they also read the unmodified input and write
+// nothing but the output (paper, section 2).
+#include "swconv_internal.h"
+
+namespace swconv {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+inline int grid_for(int64_t total)
+{
+    int64_t g = (total + kThreads - 1) / kThreads;
+    const int64_t cap = 256 * 64;  // grid-stride beyond this
+    return (int)(g < cap ? g : cap);
+}
+
+template <int OP>
+__global__ __launch_bounds__(kThreads) void direct_1d_kernel(const float* __restrict__ x,
+                                                             const float* __restrict__ w,
+                                                             float* __restrict__ y, int64_t rows,
+                                                             int64_t len, int64_t len_out, int k,
+                                                             int stride, int pad)
+{
+    const int64_t total = rows * len_out;
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total;
+         o += (int64_t)gridDim.x * kThreads) {
+        const int64_t row = o / len_out;
+        const int64_t i = o - row * len_out;
+        const float* xr = x + row * len;
+        const int64_t t0 = i * stride - pad;
+        float acc;
+        if (OP == OP_MAX) {
+            acc = xr[t0];
+            for (int j = 1; j < k; ++j) acc = fmaxf(acc, xr[t0 + j]);
+        } else {
+            acc = 0.f;
+            for (int j = 0; j < k; ++j) {
+                const int64_t t = t0 + j;
+                if (t >= 0 && t < len) acc = (OP == OP_CONV) ? fmaf(w[j], xr[t], acc) : acc + xr[t];
+            }
+            if (OP == OP_AVG) acc = acc / (float)k;
+        }
+        y[o] = acc;
+    }
+}
+
+template <typename TI, typename TA, bool DW>
+__global__ __launch_bounds__(kThreads) void direct_conv2d_kernel(const TI* __restrict__ x,
+                                                                 const TI* __restrict__ w,
+                                                                 TA* __restrict__ y, Conv2dShape s)
+{
+    const int64_t plane_o = (int64_t)s.Ho * s.Wo;
+    const int64_t total = (int64_t)s.N * s.C_out * plane_o;
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total;
+         o += (int64_t)gridDim.x * kThreads) {
+        const int64_t nc = o / plane_o;
+        const int pix = (int)(o - nc * plane_o);
+        const int n = (int)(nc / s.C_out);
+        const int co = (int)(nc - (int64_t)n * s.C_out);
+        const int i = pix / s.Wo, j = pix - i * s.Wo;
+        const int h0 = i * s.stride - s.pad, v0 = j * s.stride - s.pad;
+        const int ci_lo = DW ? co : 0;
+        const int ci_hi = DW ? co + 1 : s.C_in;
+        TA acc = 0;
+        for (int ci = ci_lo; ci < ci_hi; ++ci) {
+            const TI* xp = x + ((int64_t)n * s.C_in + ci) * s.H * s.W;
+            const TI* wp = w + ((int64_t)co * (DW ? 1 : s.C_in) + (DW ? 0 : ci)) * s.R * s.S;
+            for (int r = 0; r < s.R; ++r) {
+                const int h = h0 + r;
+                if (h < 0 || h >= s.H) continue;
+                for (int q = 0; q < s.S; ++q) {
+                    const int v = v0 + q;
+                    if (v < 0 || v >= s.W) continue;
+                    acc += (TA)xp[h * s.W + v] * (TA)wp[r * s.S + q];
+                }
+            }
+        }
+        y[o] = acc;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
+                            int64_t len_out, int k, int stride, int pad, Op1D op, hipStream_t st)
+{
+    const int grid = grid_for(rows * len_out);
+    switch (op) {
+        case OP_CONV:
+            hipLaunchKernelGGL(direct_1d_kernel<OP_CONV>, dim3(grid), dim3(kThreads), 0, st, x, w, y, rows,
+                               len, len_out, k, stride, pad);
+            break;
+        case OP_AVG:
+            hipLaunchKernelGGL(direct_1d_kernel<OP_AVG>, dim3(grid), dim3(kThreads), 0, st, x, w, y, rows,
+                               len, len_out, k, stride, pad);
+            break;
+        case OP_MAX:
+            hipLaunchKernelGGL(direct_1d_kernel<OP_MAX>, dim3(grid), dim3(kThreads), 0, st, x, w, y, rows,
+                               len, len_out, k, stride, pad);
+            break;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_direct_conv2d_f32(const float* x, const float* w, float* y, const Conv2dShape& s,
+                                    bool depthwise, hipStream_t st)
+{
+    const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
+    if (depthwise)
+        hipLaunchKernelGGL((direct_conv2d_kernel<float, float, true>), dim3(grid), dim3(kThreads), 0, st, x,
+                           w, y, s);
+    else
+        hipLaunchKernelGGL((direct_conv2d_kernel<float, float, false>), dim3(grid), dim3(kThreads), 0, st, x,
+                           w, y, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_direct_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s,
+                                   hipStream_t st)
+{
+    const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
+    hipLaunchKernelGGL((direct_conv2d_kernel<int8_t, int32_t, false>), dim3(grid), dim3(kThreads), 0, st, x,
+                       w, y, s);
+    return hipGetLastError();
+}
+
+}  // namespace swconv

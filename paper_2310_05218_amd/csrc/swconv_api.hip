@@ -1,0 +1,164 @@
+// C ABI of libswconv.so: host-side validation and kernel selection.  Every argument error is
+// reported before anything is enqueued; nothing here allocates or synchronises.
+#include "../../include/swconv.h"
+
+#include <cstdlib>
+
+#include "swconv_internal.h"
+
+using namespace swconv;
+
+namespace {
+
+constexpr int64_t kMaxElems = 2147483647LL;  // element count per tensor
+constexpr int kMaxTaps1D = 64;
+constexpr int kMaxFilter2D = 64;
+
+bool force_direct()
+{
+    static const bool v = [] {
+        const char* e = std::getenv("SWCONV_FORCE_DIRECT");
+        return e && e[0] == '1';
+    }();
+    return v;
+}
+
+bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
+
+bool overlaps(const void* a, int64_t abytes, const void* b, int64_t bbytes)
+{
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a), b0 = reinterpret_cast<uintptr_t>(b);
+    return a0 < b0 + (uintptr_t)bbytes && b0 < a0 + (uintptr_t)abytes;
+}
+
+int launch_status(hipError_t e) { return e == hipSuccess ? SW_OK : SW_ERR_LAUNCH; }
+
+// Shared validation of the 2-D calls.  esz_in / esz_out are element sizes in bytes.
+int check_conv2d(const void* x, const void* w, const void* y, int N, int C_in, int C_out, int H, int W,
+                 int R, int S, int stride, int pad, bool depthwise, size_t esz_in, size_t esz_out,
+                 Conv2dShape* out)
+{
+    if (!x || !w || !y) return SW_ERR_NULL;
+    if (N <= 0 || C_in <= 0 || C_out <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
+        return SW_ERR_SHAPE;
+    const int64_t Ho = sw_out_dim(H, R, stride, pad), Wo = sw_out_dim(W, S, stride, pad);
+    if (Ho <= 0 || Wo <= 0) return SW_ERR_SHAPE;
+    const int64_t nx = (int64_t)N * C_in * H * W;
+    const int64_t nw = (int64_t)C_out * (depthwise ? 1 : C_in) * R * S;
+    const int64_t ny = (int64_t)N * C_out * Ho * Wo;
+    if (nx > kMaxElems || nw > kMaxElems || ny > kMaxElems) return SW_ERR_SHAPE;
+    if ((int64_t)H + 2 * (int64_t)pad > kMaxElems || (int64_t)W + 2 * (int64_t)pad > kMaxElems)
+        return SW_ERR_SHAPE;
+    if (R > kMaxFilter2D || S > kMaxFilter2D) return SW_ERR_UNSUPPORTED;
+    if (misaligned(x, esz_in) || misaligned(w, esz_in) || misaligned(y, esz_out)) return SW_ERR_ALIGN;
+    if (overlaps(y, ny * (int64_t)esz_out, x, nx * (int64_t)esz_in) ||
+        overlaps(y, ny * (int64_t)esz_out, w, nw * (int64_t)esz_in))
+        return SW_ERR_ALIAS;
+    *out = Conv2dShape{N, C_in, C_out, H, W, R, S, stride, pad, (int)Ho, (int)Wo};
+    return SW_OK;
+}
+
+int run_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len, int k, int stride, int pad,
+           Op1D op, void* hip_stream)
+{
+    if (!x || !y || (op == OP_CONV && !w)) return SW_ERR_NULL;
+    if (rows <= 0 || len <= 0 || k <= 0 || stride <= 0 || pad < 0) return SW_ERR_SHAPE;
+    const int64_t len_out = sw_out_dim(len, k, stride, pad);
+    if (len_out <= 0) return SW_ERR_SHAPE;
+    if (len > kMaxElems / rows || len_out > kMaxElems / rows) return SW_ERR_SHAPE;
+    if (k > kMaxTaps1D || pad >= k) return SW_ERR_UNSUPPORTED;
+    if (misaligned(x, 4) || misaligned(y, 4) || (w && misaligned(w, 4))) return SW_ERR_ALIGN;
+    if (overlaps(y, rows * len_out * 4, x, rows * len * 4) || (w && overlaps(y, rows * len_out * 4, w, k * 4)))
+        return SW_ERR_ALIAS;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (!force_direct() && sliding_1d_supported(len, k, stride, pad))
+        return launch_status(launch_sliding_1d(x, w, y, rows, len, len_out, k, pad, op, st));
+    return launch_status(launch_direct_1d(x, w, y, rows, len, len_out, k, stride, pad, op, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t sw_out_dim(int64_t in, int k, int stride, int pad)
+{
+    if (in <= 0 || k <= 0 || stride <= 0 || pad < 0) return 0;
+    const int64_t span = in + 2 * (int64_t)pad - k;
+    if (span < 0) return 0;
+    return span / stride + 1;
+}
+
+size_t sw_workspace_bytes(void) { return 0; }
+
+const char* sw_status_string(int status)
+{
+    switch (status) {
+        case SW_OK: return "ok";
+        case SW_ERR_NULL: return "a required pointer is NULL";
+        case SW_ERR_SHAPE: return "invalid shape, stride or padding";
+        case SW_ERR_UNSUPPORTED: return "valid problem without a kernel in this library";
+        case SW_ERR_ALIGN: return "pointer not aligned to its element size";
+        case SW_ERR_ALIAS: return "output overlaps an input";
+        case SW_ERR_LAUNCH: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+int sw_version(void) { return 100; }
+
+int sw_conv1d(const float* x, const float* w, float* y, int64_t rows, int64_t len, int k, int stride,
+              int pad, void* hip_stream)
+{
+    return run_1d(x, w, y, rows, len, k, stride, pad, OP_CONV, hip_stream);
+}
+
+int sw_pool1d(const float* x, float* y, int64_t rows, int64_t len, int window, int stride, int mode,
+              void* hip_stream)
+{
+    if (mode != SW_POOL_AVG && mode != SW_POOL_MAX) return x && y ? SW_ERR_UNSUPPORTED : SW_ERR_NULL;
+    return run_1d(x, nullptr, y, rows, len, window, stride, 0, mode == SW_POOL_AVG ? OP_AVG : OP_MAX,
+                  hip_stream);
+}
+
+int sw_conv2d(const float* x, const float* w, float* y, int N, int C_in, int C_out, int H, int W, int R,
+              int S, int stride, int pad, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, 4, 4, &s);
+    if (rc != SW_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (!force_direct()) {
+        if (C_in == 1 && sliding_plane_supported(H, W, R, S, stride, pad))
+            return launch_status(launch_sliding_plane(x, w, y, (int64_t)N * C_out, C_out, C_out, H, W, R, S,
+                                                      pad, s.Ho, s.Wo, st));
+        if (mfma_f32_supported(s)) return launch_status(launch_mfma_f32(x, w, y, s, st));
+    }
+    return launch_status(launch_direct_conv2d_f32(x, w, y, s, false, st));
+}
+
+int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,
+                        int stride, int pad, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s);
+    if (rc != SW_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (!force_direct() && sliding_plane_supported(H, W, R, S, stride, pad))
+        return launch_status(
+            launch_sliding_plane(x, w, y, (int64_t)N * C, 1, C, H, W, R, S, pad, s.Ho, s.Wo, st));
+    return launch_status(launch_direct_conv2d_f32(x, w, y, s, true, st));
+}
+
+int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, int N, int C_in, int C_out, int H, int W,
+                 int R, int S, int stride, int pad, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, 1, 4, &s);
+    if (rc != SW_OK) return rc;
+    if ((int64_t)C_in * R * S > 131071) return SW_ERR_SHAPE;  // 131072 * 2^14 = 2^31 leaves int32
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (!force_direct() && mfma_s8_supported(s)) return launch_status(launch_mfma_s8(x, w, y, s, st));
+    return launch_status(launch_direct_conv2d_s8(x, w, y, s, st));
+}
+
+}  // extern "C"

@@ -1,0 +1,44 @@
+// Internal declarations shared by the translation units of libswconv.so.
+// Launchers take validated arguments, enqueue on the given stream and return
+// the HIP error of the launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace swconv {
+
+enum Op1D { OP_CONV = 0, OP_AVG = 1, OP_MAX = 2 };
+
+struct Conv2dShape {
+    int N, C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
+};
+
+// ---- direct (one thread per output) kernels: any valid shape -------------------------------
+hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
+                            int64_t len_out, int k, int stride, int pad, Op1D op, hipStream_t st);
+hipError_t launch_direct_conv2d_f32(const float* x, const float* w, float* y, const Conv2dShape& s,
+                                    bool depthwise, hipStream_t st);
+hipError_t launch_direct_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s,
+                                   hipStream_t st);
+
+// ---- sliding 1-D kernel (stride 1): LDS tile + halo, register window ---------------------------
+bool       sliding_1d_supported(int64_t len, int k, int stride, int pad);
+hipError_t launch_sliding_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
+                             int64_t len_out, int k, int pad, Op1D op, hipStream_t st);
+
+// ---- sliding plane kernel (stride 1): one filter per plane (single channel, depthwise) --------
+// x plane index for output plane p is p / planes_per_x (conv2d with C_in == 1: C_out filters share
+// one input plane; depthwise: 1); filter index is p % n_filters.
+bool       sliding_plane_supported(int H, int W, int R, int S, int stride, int pad);
+hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes,
+                                int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
+                                int Ho, int Wo, hipStream_t st);
+
+// ---- multi-channel kernels on the matrix cores (stride 1) --------------------------------------
+bool       mfma_f32_supported(const Conv2dShape& s);
+hipError_t launch_mfma_f32(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
+bool       mfma_s8_supported(const Conv2dShape& s);
+hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st);
+
+}  // namespace swconv

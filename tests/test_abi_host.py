@@ -1,0 +1,124 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2310_05218_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2310_05218_amd import build
+        build.build()
+    return B.lib()
+
+
+def test_every_declared_symbol_is_exported(L):
+    header = open(os.path.join(ROOT, "include", "swconv.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(sw_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert getattr(L, name) is not None
+
+
+def test_out_dim_and_constants(L):
+    assert B.sw_workspace_bytes() == 0
+    assert B.sw_version() >= 100
+    assert B.sw_out_dim(56, 3, 1, 1) == 56
+    assert B.sw_out_dim(65536, 9, 1, 0) == 65528
+    assert B.sw_out_dim(7, 3, 2, 1) == 4
+    assert B.sw_out_dim(2, 3, 1, 0) <= 0
+    assert B.sw_out_dim(0, 3, 1, 0) <= 0 and B.sw_out_dim(5, 3, 0, 0) <= 0 and B.sw_out_dim(5, 3, 1, -1) <= 0
+    for s in range(0, 8):
+        assert len(B.status_string(s)) > 0
+
+
+# Fake, never dereferenced device addresses: every call below must fail on the host.
+X, W_, Y = 0x100000, 0x900000, 0x1100000
+
+
+def test_conv1d_argument_errors(L):
+    f = L.sw_conv1d
+    assert f(None, W_, Y, 4, 100, 9, 1, 0, None) == B.SW_ERR_NULL
+    assert f(X, None, Y, 4, 100, 9, 1, 0, None) == B.SW_ERR_NULL
+    assert f(X, W_, None, 4, 100, 9, 1, 0, None) == B.SW_ERR_NULL
+    assert f(X, W_, Y, 0, 100, 9, 1, 0, None) == B.SW_ERR_SHAPE
+    assert f(X, W_, Y, 4, 0, 9, 1, 0, None) == B.SW_ERR_SHAPE
+    assert f(X, W_, Y, 4, 100, 0, 1, 0, None) == B.SW_ERR_SHAPE
+    assert f(X, W_, Y, 4, 100, 9, 0, 0, None) == B.SW_ERR_SHAPE
+    assert f(X, W_, Y, 4, 100, 9, 1, -1, None) == B.SW_ERR_SHAPE
+    assert f(X, W_, Y, 4, 5, 9, 1, 0, None) == B.SW_ERR_SHAPE          # filter longer than the row
+    assert f(X, W_, Y, 1 << 20, 1 << 20, 9, 1, 0, None) == B.SW_ERR_SHAPE  # too many elements
+    assert f(X, W_, Y, 4, 100, 65, 1, 0, None) == B.SW_ERR_UNSUPPORTED
+    assert f(X, W_, Y, 4, 100, 9, 1, 9, None) == B.SW_ERR_UNSUPPORTED  # pad >= k
+    assert f(X + 2, W_, Y, 4, 100, 9, 1, 0, None) == B.SW_ERR_ALIGN
+    assert f(X, W_, Y + 1, 4, 100, 9, 1, 0, None) == B.SW_ERR_ALIGN
+    assert f(X, W_, X + 4 * 50, 4, 100, 9, 1, 0, None) == B.SW_ERR_ALIAS
+    assert f(X, Y + 16, Y, 4, 100, 9, 1, 0, None) == B.SW_ERR_ALIAS
+
+
+def test_pool1d_argument_errors(L):
+    f = L.sw_pool1d
+    assert f(None, Y, 4, 100, 8, 1, 0, None) == B.SW_ERR_NULL
+    assert f(X, None, 4, 100, 8, 1, 1, None) == B.SW_ERR_NULL
+    assert f(X, Y, 4, 100, 8, 1, 2, None) == B.SW_ERR_UNSUPPORTED       # unknown mode
+    assert f(X, Y, 4, 100, 101, 1, 0, None) == B.SW_ERR_SHAPE
+    assert f(X, Y, 4, 100, 8, 0, 0, None) == B.SW_ERR_SHAPE
+    assert f(X, Y, 4, 1000, 65, 1, 0, None) == B.SW_ERR_UNSUPPORTED
+    assert f(X, X, 4, 100, 8, 1, 0, None) == B.SW_ERR_ALIAS
+
+
+@pytest.mark.parametrize("name", ["sw_conv2d", "sw_conv2d_s8"])
+def test_conv2d_argument_errors(L, name):
+    f = getattr(L, name)
+    ok = (2, 16, 16, 8, 8, 3, 3, 1, 1)
+    assert f(None, W_, Y, *ok, None) == B.SW_ERR_NULL
+    assert f(X, None, Y, *ok, None) == B.SW_ERR_NULL
+    assert f(X, W_, None, *ok, None) == B.SW_ERR_NULL
+    for i in range(8):                       # N, C_in, C_out, H, W, R, S, stride <= 0
+        bad = list(ok)
+        bad[i] = 0
+        assert f(X, W_, Y, *bad, None) == B.SW_ERR_SHAPE, i
+    assert f(X, W_, Y, 2, 16, 16, 8, 8, 3, 3, 1, -1, None) == B.SW_ERR_SHAPE
+    assert f(X, W_, Y, 2, 16, 16, 2, 8, 5, 3, 1, 1, None) == B.SW_ERR_SHAPE       # filter > padded input
+    assert f(X, W_, Y, 4096, 4096, 16, 64, 64, 3, 3, 1, 1, None) == B.SW_ERR_SHAPE  # > 2^31-1 elements
+    assert f(X, W_, Y, 2, 16, 16, 100, 100, 65, 3, 1, 1, None) == B.SW_ERR_UNSUPPORTED
+    assert f(X, W_, Y + 2, *ok, None) == B.SW_ERR_ALIGN
+    assert f(X, W_, X, *ok, None) == B.SW_ERR_ALIAS
+    assert f(X, Y + 64, Y, *ok, None) == B.SW_ERR_ALIAS
+
+
+def test_conv2d_f32_alignment_and_s8_accumulator_bound(L):
+    ok = (2, 16, 16, 8, 8, 3, 3, 1, 1)
+    assert L.sw_conv2d(X + 2, W_, Y, *ok, None) == B.SW_ERR_ALIGN
+    assert L.sw_conv2d(X, W_ + 1, Y, *ok, None) == B.SW_ERR_ALIGN
+    # int8 inputs need no alignment, so odd addresses get as far as the shape checks
+    assert L.sw_conv2d_s8(X + 1, W_ + 3, Y, 1, 16384, 1, 8, 8, 3, 3, 1, 1, None) == B.SW_ERR_SHAPE  # 147456 terms
+
+
+def test_depthwise_argument_errors(L):
+    f = L.sw_conv2d_depthwise
+    ok = (2, 16, 8, 8, 3, 3, 1, 1)
+    assert f(None, W_, Y, *ok, None) == B.SW_ERR_NULL
+    for i in range(7):
+        bad = list(ok)
+        bad[i] = 0
+        assert f(X, W_, Y, *bad, None) == B.SW_ERR_SHAPE, i
+    assert f(X, W_, Y, 2, 16, 4, 4, 7, 7, 1, 0, None) == B.SW_ERR_SHAPE
+    assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
+
+
+def test_binding_refuses_host_tensors(L):
+    import torch
+
+    x = torch.zeros(2, 16)
+    w = torch.zeros(3)
+    with pytest.raises(ValueError):
+        B.sw_conv1d(x, w)

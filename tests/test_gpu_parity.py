@@ -1,0 +1,291 @@
+"""GPU parity: libswconv.so (through the C ABI) against the CPU oracle, element by element, on the
+same seeded inputs.  fp32: max |y_gpu - y_oracle| / sum|x*w| <= 2e-5 per output; maximum pooling and
+the int8 path: bit-exact."""
+import numpy as np
+import pytest
+
+from paper_2310_05218_amd import inputs
+from parity import assert_f32_parity, assert_guards_intact, guarded_empty
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as _t
+
+    assert _t.cuda.is_available(), "these tests need the GPU"
+    return _t
+
+
+@pytest.fixture(scope="module")
+def sw():
+    import paper_2310_05218_amd as _sw
+    from paper_2310_05218_amd import binding
+
+    binding.lib()            # fails loudly if the library is not built
+    return _sw
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+# ----------------------------------------------------------------------------- 1-D ---------------
+
+CONV1D_CASES = [
+    # rows, len, k, stride, pad
+    (1, 9, 9, 1, 0),            # a single output
+    (3, 17, 3, 1, 0),
+    (2, 4173, 9, 1, 0),         # two tiles and a ragged tail, row length not a multiple of 4
+    (3, 6144 + 8, 9, 1, 0),     # output length an exact multiple of the tile
+    (5, 5000, 1, 1, 0),
+    (4, 5000, 2, 1, 1),
+    (4, 4100, 5, 1, 4),
+    (2, 4096, 16, 1, 7),
+    (2, 4099, 17, 1, 16),
+    (2, 4500, 18, 1, 3),        # beyond the unrolled sizes: run-time tap count
+    (3, 3000, 33, 1, 32),
+    (2, 2500, 64, 1, 63),
+    (2, 2049, 12, 1, 0),
+    (3, 1000, 9, 2, 0),         # strided: direct kernel
+    (3, 1001, 4, 3, 2),
+]
+
+
+@pytest.mark.parametrize("case", CONV1D_CASES)
+def test_conv1d(torch, sw, oracle, case):
+    rows, length, k, stride, pad = case
+    x = inputs.normal_f32((rows, length), 1001)
+    w = inputs.normal_f32((k,), 1002)
+    y_ref, d = oracle.conv1d(x, w, stride, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv1d(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"conv1d {case}")
+
+
+POOL_CASES = [(1, 8, 8, 1), (3, 4173, 8, 1), (2, 6144 + 7, 8, 1), (4, 5000, 3, 1), (2, 5000, 1, 1),
+              (2, 4100, 17, 1), (2, 4100, 40, 1), (2, 3000, 64, 1), (3, 1000, 8, 2), (3, 1001, 3, 3)]
+
+
+@pytest.mark.parametrize("case", POOL_CASES)
+@pytest.mark.parametrize("mode", [0, 1])
+def test_pool1d(torch, sw, oracle, case, mode):
+    rows, length, window, stride = case
+    x = inputs.normal_f32((rows, length), 1011)
+    y_ref, d = oracle.pool1d(x, window, stride, mode)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_pool1d(dev(torch, x), window, stride, mode, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    y = out.cpu().numpy()
+    if mode == 1:
+        assert np.array_equal(y.astype(np.float64), y_ref), f"max pool {case} is not bit-exact"
+    else:
+        assert_f32_parity(y, y_ref, d, f"avg pool {case}")
+
+
+def test_avg_pool_equals_conv1d_with_constant_taps(torch, sw):
+    x = dev(torch, inputs.normal_f32((4, 5000), 1021))
+    w = torch.full((8,), 0.125, device="cuda")
+    a = sw.sw_pool1d(x, 8, 1, 0)
+    c = sw.sw_conv1d(x, w, 1, 0)
+    assert float((a - c).abs().max()) <= 2e-6
+
+
+def test_workload2_full_size(torch, sw, oracle):
+    x, w = inputs.workload2()
+    xd, wd = dev(torch, x), dev(torch, w)
+    y_ref, d = oracle.conv1d(x, w, 1, 0)
+    assert_f32_parity(sw.sw_conv1d(xd, wd).cpu().numpy(), y_ref, d, "workload 2 conv1d")
+    y_ref, d = oracle.pool1d(x, 8, 1, 0)
+    assert_f32_parity(sw.sw_pool1d(xd, 8, 1, 0).cpu().numpy(), y_ref, d, "workload 2 avg")
+    y_ref, _ = oracle.pool1d(x, 8, 1, 1)
+    assert np.array_equal(sw.sw_pool1d(xd, 8, 1, 1).cpu().numpy().astype(np.float64), y_ref)
+
+
+# ----------------------------------------------------------------------------- 2-D single filter per plane
+
+PLANE_CASES = [
+    # N, C, H, W, R, S, stride, pad
+    (1, 1, 3, 3, 3, 3, 1, 0),       # a single output
+    (2, 3, 56, 56, 3, 3, 1, 1),
+    (2, 3, 56, 56, 5, 5, 1, 2),
+    (2, 3, 56, 56, 7, 7, 1, 3),
+    (1, 2, 57, 59, 3, 3, 1, 1),     # ragged tiles
+    (1, 2, 61, 70, 7, 7, 1, 3),
+    (1, 2, 130, 131, 5, 5, 1, 0),
+    (1, 2, 33, 47, 3, 3, 1, 0),
+    (2, 2, 28, 28, 3, 3, 1, 1),
+    (1, 3, 20, 21, 2, 6, 1, 1),     # filter extent without a fixed-size kernel
+    (1, 2, 40, 40, 9, 9, 1, 4),
+    (1, 2, 30, 30, 17, 17, 1, 8),
+    (1, 3, 21, 23, 3, 3, 2, 1),     # strided: direct kernel
+    (1, 2, 7, 5, 7, 5, 1, 0),
+    (1, 2, 16, 16, 3, 3, 1, 2),     # padding wider than the usual (R-1)/2
+]
+
+
+@pytest.mark.parametrize("case", PLANE_CASES)
+def test_depthwise(torch, sw, oracle, case):
+    N, C, H, W, R, S, stride, pad = case
+    x = inputs.normal_f32((N, C, H, W), 2001)
+    w = inputs.normal_f32((C, 1, R, S), 2002)
+    y_ref, d = oracle.conv2d_depthwise(x, w, stride, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_depthwise(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"depthwise {case}")
+
+
+@pytest.mark.parametrize("case", PLANE_CASES)
+def test_conv2d_single_input_channel(torch, sw, oracle, case):
+    N, C_out, H, W, R, S, stride, pad = case
+    x = inputs.normal_f32((N, 1, H, W), 2011)
+    w = inputs.normal_f32((C_out, 1, R, S), 2012)
+    y_ref, d = oracle.conv2d(x, w, stride, pad)
+    y = sw.sw_conv2d(dev(torch, x), dev(torch, w), stride, pad)
+    assert_f32_parity(y.cpu().numpy(), y_ref, d, f"conv2d C_in=1 {case}")
+
+
+def test_workload1_full_size(torch, sw, oracle):
+    x, w = inputs.workload1()
+    y_ref, d = oracle.conv2d(x, w, 1, 0)
+    y = sw.sw_conv2d(dev(torch, x), dev(torch, w), 1, 0)
+    assert y.shape == (1, 1, 254, 254)
+    assert_f32_parity(y.cpu().numpy(), y_ref, d, "workload 1")
+
+
+def test_impulse_reproduces_filter_on_gpu(torch, sw):
+    x = np.zeros((1, 1, 40, 40), np.float32)
+    x[0, 0, 20, 21] = 1.0
+    w = inputs.uniform_f32((1, 1, 7, 7), 2021)
+    y = sw.sw_conv2d_depthwise(dev(torch, x), dev(torch, w), 1, 3).cpu().numpy()
+    expect = np.zeros_like(y)
+    for r in range(7):
+        for s in range(7):
+            expect[0, 0, 20 - r + 3, 21 - s + 3] = w[0, 0, r, s]
+    assert np.array_equal(y, expect)
+
+
+@pytest.mark.parametrize("which", ["3x3", "7x7"])
+def test_workload4_full_size(torch, sw, oracle, which):
+    x, w3, w7 = inputs.workload4()
+    w, pad = (w3, 1) if which == "3x3" else (w7, 3)
+    y_ref, d = oracle.conv2d_depthwise(x, w, 1, pad)
+    y = sw.sw_conv2d_depthwise(dev(torch, x), dev(torch, w), 1, pad)
+    assert_f32_parity(y.cpu().numpy(), y_ref, d, f"workload 4 {which}")
+
+
+# ----------------------------------------------------------------------------- 2-D multi-channel fp32
+
+CONV2D_CASES = [
+    # N, C_in, C_out, H, W, R, S, stride, pad
+    (1, 3, 5, 9, 11, 3, 3, 1, 1),        # small odd shapes: direct kernel
+    (2, 4, 3, 12, 10, 2, 5, 2, 2),
+    (1, 7, 2, 8, 8, 1, 1, 1, 0),
+    (2, 16, 64, 56, 56, 3, 3, 1, 1),     # matrix-core path, one channel block
+    (1, 64, 64, 56, 56, 3, 3, 1, 1),
+    (2, 32, 128, 28, 28, 3, 3, 1, 1),    # two output-channel blocks
+    (1, 32, 64, 30, 41, 3, 3, 1, 1),     # ragged row bands and widths
+    (1, 16, 64, 9, 100, 3, 3, 1, 1),
+    (1, 48, 64, 14, 14, 3, 3, 1, 0),     # valid mode
+    (1, 16, 64, 20, 20, 5, 5, 1, 2),
+    (1, 16, 64, 12, 12, 1, 1, 1, 0),
+    (1, 32, 64, 17, 19, 3, 3, 2, 1),     # strided: direct kernel
+]
+
+
+@pytest.mark.parametrize("case", CONV2D_CASES)
+def test_conv2d(torch, sw, oracle, case):
+    N, C_in, C_out, H, W, R, S, stride, pad = case
+    x = inputs.normal_f32((N, C_in, H, W), 3001)
+    w = inputs.normal_f32((C_out, C_in, R, S), 3002, (2.0 / (C_in * R * S)) ** 0.5)
+    y_ref, d = oracle.conv2d(x, w, stride, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"conv2d {case}")
+
+
+def test_workload3_full_size(torch, sw, oracle):
+    x, w = inputs.workload3()
+    y_ref, d = oracle.conv2d(x, w, 1, 1)
+    y = sw.sw_conv2d(dev(torch, x), dev(torch, w), 1, 1)
+    assert_f32_parity(y.cpu().numpy(), y_ref, d, "workload 3")
+
+
+# ----------------------------------------------------------------------------- 2-D int8
+
+S8_CASES = [
+    (1, 3, 5, 9, 11, 3, 3, 1, 1),
+    (2, 4, 3, 12, 10, 2, 5, 2, 2),
+    (1, 128, 128, 28, 28, 3, 3, 1, 1),
+    (2, 64, 64, 28, 28, 3, 3, 1, 1),
+    (1, 128, 64, 13, 17, 3, 3, 1, 1),    # ragged
+    (1, 64, 128, 30, 9, 3, 3, 1, 0),
+    (1, 192, 64, 10, 10, 5, 5, 1, 2),
+    (1, 64, 64, 15, 15, 3, 3, 2, 1),
+]
+
+
+@pytest.mark.parametrize("case", S8_CASES)
+def test_conv2d_s8(torch, sw, oracle, case):
+    N, C_in, C_out, H, W, R, S, stride, pad = case
+    x = inputs.uniform_s8((N, C_in, H, W), 5001)
+    w = inputs.uniform_s8((C_out, C_in, R, S), 5002)
+    y_ref = oracle.conv2d_s8(x, w, stride, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.int32)
+    sw.sw_conv2d_s8(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert np.array_equal(out.cpu().numpy(), y_ref), f"s8 {case} is not bit-exact"
+
+
+def test_s8_extreme_values(torch, sw):
+    x = np.full((1, 128, 28, 28), -128, np.int8)
+    w = np.full((128, 128, 3, 3), -128, np.int8)
+    y = sw.sw_conv2d_s8(dev(torch, x), dev(torch, w), 1, 1).cpu().numpy()
+    assert y[0, 5, 10, 10] == 18874368 and y[0, 0, 0, 0] == 128 * 4 * 16384 and y[0, 127, 27, 13] == 128 * 6 * 16384
+    w[:] = 127
+    y = sw.sw_conv2d_s8(dev(torch, x), dev(torch, w), 1, 1).cpu().numpy()
+    assert y[0, 64, 14, 14] == 1152 * (-128 * 127)
+
+
+def test_workload5_full_size(torch, sw, oracle):
+    x, w = inputs.workload5()
+    y_ref = oracle.conv2d_s8(x, w, 1, 1)
+    y = sw.sw_conv2d_s8(dev(torch, x), dev(torch, w), 1, 1)
+    assert np.array_equal(y.cpu().numpy(), y_ref)
+
+
+# ----------------------------------------------------------------------------- contract
+
+def test_no_device_allocation_and_side_stream(torch, sw, oracle):
+    x, w = inputs.workload3(N=2)
+    xd, wd = dev(torch, x), dev(torch, w)
+    out = torch.empty((2, 64, 56, 56), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    before = torch.cuda.memory_allocated()
+    free_before, _ = torch.cuda.mem_get_info()
+    with torch.cuda.stream(side):
+        sw.sw_conv2d(xd, wd, 1, 1, out=out, stream=side)
+    side.synchronize()
+    assert torch.cuda.memory_allocated() == before
+    assert torch.cuda.mem_get_info()[0] == free_before       # no hipMalloc behind torch's back either
+    y_ref, d = oracle.conv2d(x, w, 1, 1)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, "side stream")
+
+
+def test_bad_arguments_raise(torch, sw):
+    x = torch.zeros((2, 16), device="cuda")
+    w = torch.zeros((32,), device="cuda")
+    with pytest.raises(sw.SwError):
+        sw.sw_conv1d(x, w)                       # filter longer than the row
+    with pytest.raises(sw.SwError):
+        sw.sw_pool1d(x, 4, 1, 7)                 # unknown mode

@@ -1,7 +1,5 @@
 #include "swconv_internal.h"
 namespace swconv {
-bool sliding_plane_supported(int, int, int, int, int, int) { return false; }
-hipError_t launch_sliding_plane(const float*, const float*, float*, int64_t, int, int, int, int, int, int, int, int, int, hipStream_t) { return hipErrorInvalidValue; }
 bool mfma_f32_supported(const Conv2dShape&) { return false; }
 hipError_t launch_mfma_f32(const float*, const float*, float*, const Conv2dShape&, hipStream_t) { return hipErrorInvalidValue; }
 bool mfma_s8_supported(const Conv2dShape&) { return false; }

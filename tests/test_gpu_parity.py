@@ -270,6 +270,10 @@ def test_no_device_allocation_and_side_stream(torch, sw, oracle):
     xd, wd = dev(torch, x), dev(torch, w)
     out = torch.empty((2, 64, 56, 56), dtype=torch.float32, device="cuda")
     side = torch.cuda.Stream()
+    # first use of a stream and of a kernel makes the HIP runtime set up its own resources
+    sw.sw_conv2d(xd, wd, 1, 1, out=out, stream=side)
+    torch.cuda.synchronize()
+    out.zero_()
     torch.cuda.synchronize()
     before = torch.cuda.memory_allocated()
     free_before, _ = torch.cuda.mem_get_info()

@@ -1,0 +1,219 @@
+#!/usr/bin/env python3
+"""Benchmark of the sliding-window convolution / pooling library on one MI355X.
+
+A *step* is one pass of the whole hot path over one batch of synthetic input: the eight kernel
+launches that cover the five workloads (single-channel 3x3; 1-D conv + avg + max pooling;
+multi-channel fp32 3x3; depthwise 3x3 and 7x7; int8 3x3).  Inputs are resident in HBM before the
+timed region starts.  Steps rotate over several buffer sets so that the ~0.44 GB a step touches
+is not served from the 256 MB Infinity Cache.
+
+Prints ONE JSON line.  `value` is useful operations per second over the whole step (2 per
+multiply-add of the direct definition, window-1 adds/compares per pooled output ... the counts
+are in WORK below); `roofline` is for the kernel that takes the largest share of a step, timed
+with HIP events on the launch stream inside the timed region; `cpu_baseline` is the CPU oracle
+(naive fp64 / int64 loops, OpenMP) on the same step, timed on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+HBM_GBS = 8000.0
+MFMA_F32_TFLOPS = 157.3
+MFMA_I8_TOPS = 5000.0
+VALU_F32_TFLOPS = 78.6     # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz, no packed FP32
+
+
+def work_table():
+    """name -> (useful ops per launch, algorithmic bytes per launch, bound, peak, unit)."""
+    f = 4
+    t = {}
+    t["conv2d_1ch_3x3"] = (2 * 9 * 254 * 254, 256 * 256 * f + 9 * f + 254 * 254 * f, "hbm", HBM_GBS, "GB/s")
+    t["conv1d_k9"] = (2 * 9 * 64 * 65528, 64 * 65536 * f + 9 * f + 64 * 65528 * f, "hbm", HBM_GBS, "GB/s")
+    t["avgpool1d_w8"] = (8 * 64 * 65529, 64 * 65536 * f + 64 * 65529 * f, "hbm", HBM_GBS, "GB/s")
+    t["maxpool1d_w8"] = (7 * 64 * 65529, 64 * 65536 * f + 64 * 65529 * f, "hbm", HBM_GBS, "GB/s")
+    px = 32 * 56 * 56
+    t["conv2d_64x64_3x3"] = (2 * 64 * 64 * 9 * px, 2 * 64 * px * f + 64 * 64 * 9 * f, "mfma", MFMA_F32_TFLOPS, "TFLOP/s")
+    t["depthwise_3x3"] = (2 * 9 * 256 * px, 2 * 256 * px * f + 256 * 9 * f, "hbm", HBM_GBS, "GB/s")
+    t["depthwise_7x7"] = (2 * 49 * 256 * px, 2 * 256 * px * f + 256 * 49 * f, "hbm", HBM_GBS, "GB/s")
+    px8 = 32 * 28 * 28
+    t["conv2d_s8_128x128_3x3"] = (2 * 128 * 128 * 9 * px8, 128 * px8 + 128 * 128 * 9 + 128 * px8 * 4, "mfma",
+                                  MFMA_I8_TOPS, "TOP/s")
+    return t
+
+
+def make_sets(torch, nsets):
+    from paper_2310_05218_amd import inputs
+
+    host = {}
+    host["x1"], host["w1"] = inputs.workload1()
+    host["x2"], host["w2"] = inputs.workload2()
+    host["x3"], host["w3"] = inputs.workload3()
+    host["x4"], host["w4a"], host["w4b"] = inputs.workload4()
+    host["x5"], host["w5"] = inputs.workload5()
+    sets = []
+    for _ in range(nsets):
+        d = {k: torch.from_numpy(v).cuda() for k, v in host.items()}
+        e = lambda *s, dt=torch.float32: torch.empty(s, dtype=dt, device="cuda")
+        d["y1"] = e(1, 1, 254, 254)
+        d["y2a"], d["y2b"], d["y2c"] = e(64, 65528), e(64, 65529), e(64, 65529)
+        d["y3"] = e(32, 64, 56, 56)
+        d["y4a"], d["y4b"] = e(32, 256, 56, 56), e(32, 256, 56, 56)
+        d["y5"] = e(32, 128, 28, 28, dt=torch.int32)
+        sets.append(d)
+    return host, sets
+
+
+def launches(sw):
+    return [
+        ("conv2d_1ch_3x3", lambda d: sw.sw_conv2d(d["x1"], d["w1"], 1, 0, out=d["y1"])),
+        ("conv1d_k9", lambda d: sw.sw_conv1d(d["x2"], d["w2"], 1, 0, out=d["y2a"])),
+        ("avgpool1d_w8", lambda d: sw.sw_pool1d(d["x2"], 8, 1, sw.SW_POOL_AVG, out=d["y2b"])),
+        ("maxpool1d_w8", lambda d: sw.sw_pool1d(d["x2"], 8, 1, sw.SW_POOL_MAX, out=d["y2c"])),
+        ("conv2d_64x64_3x3", lambda d: sw.sw_conv2d(d["x3"], d["w3"], 1, 1, out=d["y3"])),
+        ("depthwise_3x3", lambda d: sw.sw_conv2d_depthwise(d["x4"], d["w4a"], 1, 1, out=d["y4a"])),
+        ("depthwise_7x7", lambda d: sw.sw_conv2d_depthwise(d["x4"], d["w4b"], 1, 3, out=d["y4b"])),
+        ("conv2d_s8_128x128_3x3", lambda d: sw.sw_conv2d_s8(d["x5"], d["w5"], 1, 1, out=d["y5"])),
+    ]
+
+
+def time_kernel(torch, fn, sets, reps, batches=5):
+    """Median over batches of (elapsed between two events around `reps` back-to-back launches)/reps, in us."""
+    out = []
+    for _ in range(batches):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(reps):
+            fn(sets[i % len(sets)])
+        e1.record()
+        e1.synchronize()
+        out.append(e0.elapsed_time(e1) * 1e3 / reps)
+    out.sort()
+    return out[len(out) // 2]
+
+
+def cpu_baseline(host, total_ops):
+    import oracle
+
+    oracle.build()
+    t0 = time.perf_counter()
+    oracle.conv2d(host["x1"], host["w1"], 1, 0)
+    oracle.conv1d(host["x2"], host["w2"], 1, 0)
+    oracle.pool1d(host["x2"], 8, 1, oracle.POOL_AVG)
+    oracle.pool1d(host["x2"], 8, 1, oracle.POOL_MAX)
+    oracle.conv2d(host["x3"], host["w3"], 1, 1)
+    oracle.conv2d_depthwise(host["x4"], host["w4a"], 1, 1)
+    oracle.conv2d_depthwise(host["x4"], host["w4b"], 1, 3)
+    oracle.conv2d_s8(host["x5"], host["w5"], 1, 1)
+    dt = time.perf_counter() - t0
+    return {"value": total_ops / dt / 1e9, "unit": "GFLOP/s", "cores": oracle.max_threads(), "kind": "oracle",
+            "sample": "one full step (all eight launches at full size), single run, %.2f s; naive fp64/int64 "
+                      "loops with OpenMP, not a tuned CPU library" % dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--sets", type=int, default=3, help="buffer sets rotated over (cold-cache timing)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-detail", action="store_true", help="skip the per-kernel hot/cold table")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+
+    import paper_2310_05218_amd as sw
+    from paper_2310_05218_amd import binding
+
+    binding.lib()     # raises if libswconv.so has not been built: there is no fallback
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    work = work_table()
+    host, sets = make_sets(torch, args.sets)
+    ls = launches(sw)
+    total_ops = sum(work[n][0] for n, _ in ls)
+
+    def step(i):
+        d = sets[i % len(sets)]
+        for _, fn in ls:
+            fn(d)
+
+    # pick the kernel with the largest share of a step (cold buffers)
+    for i in range(3):
+        step(i)
+    torch.cuda.synchronize()
+    probe = {n: time_kernel(torch, fn, sets, 20, 3) for n, fn in ls}
+    dominant = max(probe, key=probe.get)
+
+    for i in range(args.warmup):
+        step(i)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        d = sets[i % len(sets)]
+        for n, fn in ls:
+            if n == dominant:
+                ev[i][0].record()
+                fn(d)
+                ev[i][1].record()
+            else:
+                fn(d)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    dom_us = sum(a.elapsed_time(b) for a, b in ev) * 1e3 / args.steps
+
+    ops, nbytes, bound, peak, unit = work[dominant]
+    achieved = (nbytes / dom_us / 1e3) if bound == "hbm" else (ops / dom_us / 1e6)   # GB/s or T(FL)OP/s
+    roofline = {"kernel": dominant, "bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "avg_launch_us": round(dom_us, 2), "traffic": None}
+
+    result = {
+        "metric": "conv GFLOP/s (or GB/s for 1-D/depthwise) and % of roofline, 1 MI355X",
+        "value": round(total_ops / (dt / args.steps) / 1e9, 1),
+        "unit": "GFLOP/s (useful ops of the direct definition, int8 multiply-adds counted as 2)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32 (int8 -> int32 for the quantised launch)", "data": "synthetic",
+        "config": {"workload": "all five workloads back to back, 8 launches per step: 1x1x256x256 3x3; "
+                               "64x65536 conv1d k=9 + avg/max pool w=8; 32x64x56x56->64 3x3; depthwise "
+                               "32x256x56x56 3x3 and 7x7; int8 32x128x28x28->128 3x3",
+                   "buffer_sets": args.sets},
+        "roofline": roofline,
+    }
+
+    if not args.no_detail:
+        table = []
+        for n, fn in ls:
+            ops, nbytes, bound, peak, unit = work[n]
+            reps = 200 if probe[n] < 200 else 50
+            cold = time_kernel(torch, fn, sets, reps)
+            hot = time_kernel(torch, fn, sets[:1], reps)
+            row = {"kernel": n, "us_cold": round(cold, 2), "us_hot": round(hot, 2),
+                   "gflops_cold": round(ops / cold / 1e3, 1), "gbs_cold": round(nbytes / cold / 1e3, 1),
+                   "bound": bound}
+            row["frac_cold"] = round((nbytes / cold / 1e3) / peak if bound == "hbm" else (ops / cold / 1e6) / peak, 4)
+            row["frac_hot"] = round((nbytes / hot / 1e3) / peak if bound == "hbm" else (ops / hot / 1e6) / peak, 4)
+            table.append(row)
+        result["kernels"] = table
+
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(host, total_ops)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

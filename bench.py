@@ -85,17 +85,30 @@ def launches(sw):
 
 
 def time_kernel(torch, fn, sets, reps, batches=5):
-    """Median over batches of (elapsed between two events around `reps` back-to-back launches)/reps, in us."""
-    out = []
-    for _ in range(batches):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        torch.cuda.synchronize()
-        e0.record()
-        for i in range(reps):
-            fn(sets[i % len(sets)])
-        e1.record()
-        e1.synchronize()
-        out.append(e0.elapsed_time(e1) * 1e3 / reps)
+    """Per-launch time in us: `reps` back-to-back launches (rotating over `sets`) are captured into one HIP
+    graph, so that the host's launch cost does not bound microsecond kernels; each batch replays the graph
+    between two events on the launch stream.  Median over batches."""
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(st):
+        for i in range(len(sets)):
+            fn(sets[i])                      # warm-up outside capture
+        st.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            for i in range(reps):
+                fn(sets[i % len(sets)])
+        out = []
+        g.replay()
+        st.synchronize()
+        for _ in range(batches):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(st)
+            g.replay()
+            e1.record(st)
+            e1.synchronize()
+            out.append(e0.elapsed_time(e1) * 1e3 / reps)
+    torch.cuda.current_stream().wait_stream(st)
     out.sort()
     return out[len(out) // 2]
 

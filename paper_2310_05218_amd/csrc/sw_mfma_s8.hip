@@ -1,0 +1,314 @@
+// Quantised multi-channel convolution: int8 x int8 -> exact int32, 3x3, stride 1, on the matrix cores
+// (paper, sections 1.1 and 3: quantisation applied to the sliding formulation; taps as small matrix
+// products).  Every tap (r, s) contributes W_rs[co, ci] times the input tile shifted by (r, s); the
+// shift is an address offset into the tile staged in LDS, so no column matrix exists.
+//
+// Workgroup = 4 wavefronts = 64 output channels x a tile of TH x TW (<= 208) output pixels of one
+// image; input channels are consumed in chunks of 64, one v_mfma_i32_16x16x64_i8 K step per tap.
+// The matrix instruction wants 16 consecutive K bytes per lane, i.e. channel-contiguous operands,
+// while both tensors arrive channel-strided (NCHW, OIHW).  Both are therefore transposed on their
+// way into LDS with byte permutes in registers:
+//   input   global [ci][row][col]  -> 16 channels x 4 pixels per lane -> LDS [pixel][ci], 80-byte pitch
+//   weights global [co][ci][tap]   -> coalesced copy to an LDS staging area, then 16 channels x 9
+//                                     taps per lane -> LDS [tap][co][ci], 80-byte pitch
+// The 80-byte pitch spreads the 16-byte operand reads of 16 consecutive pixels (or output channels)
+// evenly over the banks.  The wavefronts split the tile 2 x 2: 32 output channels x 7 pixel blocks
+// each, 56 accumulator registers.  The next chunk is fetched from HBM/L2 into registers while the
+// current one is multiplied.
+#include "swconv_internal.h"
+
+namespace swconv {
+
+namespace {
+
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32;
+
+constexpr int kCK = 64;            // input channels per chunk
+constexpr int kPitch = 80;         // bytes per pixel / per weight row in LDS
+constexpr int kNB = 13;            // 16-pixel blocks per tile
+constexpr int kNBW = 7;            // pixel blocks per wavefront
+constexpr int kTilePx = kNB * 16;
+constexpr int kLdsPx = 320;        // pixels of the staged input window
+constexpr int kXItems = 2;         // (16-channel group, row, column quad) items per thread and chunk
+constexpr int kXBytes = kLdsPx * kPitch;            // 25600
+constexpr int kWBytes = 9 * 64 * kPitch;            // 46080
+constexpr int kRawBytes = 64 * kCK * 9;             // 36864
+constexpr int kLdsBytes = kXBytes + kWBytes + kRawBytes;
+
+// byte k of the result = byte sel_k of the 8-byte value {hi, lo} (lo = bytes 0..3)
+__device__ __forceinline__ u32 perm(u32 hi, u32 lo, u32 sel) { return __builtin_amdgcn_perm(hi, lo, sel); }
+
+// Gathers bytes P0..P3 (byte positions in the dword array r) into one dword.
+template <int P0, int P1, int P2, int P3>
+__device__ __forceinline__ u32 gather4(const u32* r)
+{
+    const u32 t01 = perm(r[P1 >> 2], r[P0 >> 2], (u32)(P0 & 3) | ((u32)(4 + (P1 & 3)) << 8));
+    const u32 t23 = perm(r[P3 >> 2], r[P2 >> 2], (u32)(P2 & 3) | ((u32)(4 + (P3 & 3)) << 8));
+    return perm(t23, t01, 0x05040100u);
+}
+
+// out[tap][a] = channels 4a..4a+3 of tap `tap`, from raw = 16 channels x 9 taps (tap fastest)
+template <int TAP, int A>
+__device__ __forceinline__ u32 wgather(const u32* raw)
+{
+    return gather4<(4 * A) * 9 + TAP, (4 * A + 1) * 9 + TAP, (4 * A + 2) * 9 + TAP, (4 * A + 3) * 9 + TAP>(raw);
+}
+
+template <int TAP>
+__device__ __forceinline__ intx4 wgather_tap(const u32* raw)
+{
+    intx4 v;
+    v.x = (int)wgather<TAP, 0>(raw);
+    v.y = (int)wgather<TAP, 1>(raw);
+    v.z = (int)wgather<TAP, 2>(raw);
+    v.w = (int)wgather<TAP, 3>(raw);
+    return v;
+}
+
+// 16 channels x 4 pixels (one dword per channel) -> pixel PX's 16 channel bytes
+template <int PX>
+__device__ __forceinline__ intx4 xgather_px(const u32* in)
+{
+    intx4 v;
+    v.x = (int)gather4<0 * 4 + PX, 1 * 4 + PX, 2 * 4 + PX, 3 * 4 + PX>(in);
+    v.y = (int)gather4<4 * 4 + PX, 5 * 4 + PX, 6 * 4 + PX, 7 * 4 + PX>(in);
+    v.z = (int)gather4<8 * 4 + PX, 9 * 4 + PX, 10 * 4 + PX, 11 * 4 + PX>(in);
+    v.w = (int)gather4<12 * 4 + PX, 13 * 4 + PX, 14 * 4 + PX, 15 * 4 + PX>(in);
+    return v;
+}
+
+__global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restrict__ x,
+                                                         const int8_t* __restrict__ w,
+                                                         int32_t* __restrict__ y, int C_in, int C_out,
+                                                         int H, int W, int pad, int Ho, int Wo, int TH,
+                                                         int TW, int tiles_x, int tiles_y)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* lx = smem;                       // [pixel][ci]      pitch 80
+    unsigned char* lw = smem + kXBytes;             // [tap][co][ci]    pitch 80
+    unsigned char* lraw = smem + kXBytes + kWBytes; // [co][ci][tap]    as in global memory
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int lq = lane >> 4, lj = lane & 15;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    int b = blockIdx.x;
+    const int tx = b % tiles_x; b /= tiles_x;
+    const int ty = b % tiles_y; b /= tiles_y;
+    const int mblocks = C_out >> 6;
+    const int mb = b % mblocks;
+    const int n = b / mblocks;
+
+    const int row0 = ty * TH, col0 = tx * TW;
+    const int IH = TH + 2, IW = TW + 2;
+    const int HW = H * W;
+    const int8_t* xn = x + (int64_t)n * C_in * HW;
+
+    // ---- zero the input window once: halo and out-of-image cells are never written again ----------
+    for (int i = tid; i < kXBytes / 16; i += 256) reinterpret_cast<intx4*>(lx)[i] = intx4{0, 0, 0, 0};
+
+    // ---- input staging plan: item = (16-channel group, window row, image column quad) ---------------
+    const int wc0 = col0 - pad;                        // image column of window column 0
+    const int g_lo = wc0 >> 2;                         // arithmetic shift: floor for negatives
+    const int nq = ((wc0 + IW - 1) >> 2) - g_lo + 1;
+    const int nitems = 4 * IH * nq;
+    int xoff[kXItems];      // byte offset of (channel 16*c16, row, 4g) in the image; < 0: skip item
+    int xlds[kXItems];      // byte address in lx of window column (4g - wc0) of that row, channel 16*c16
+    int xc[kXItems];        // window column of the quad's first pixel (may be < 0)
+#pragma unroll
+    for (int k = 0; k < kXItems; ++k) {
+        const int idx = tid + 256 * k;
+        const int g = idx % nq;
+        const int t = idx / nq;
+        const int e = t % IH;
+        const int c16 = t / IH;
+        const int gr = row0 - pad + e;
+        const int gc = 4 * (g_lo + g);
+        const bool ok = idx < nitems && gr >= 0 && gr < H && gc >= 0 && gc + 3 < W;
+        xoff[k] = ok ? (16 * c16 * H + gr) * W + gc : -1;
+        xc[k] = gc - wc0;
+        xlds[k] = (e * IW + xc[k]) * kPitch + 16 * c16;
+    }
+
+    // ---- weight staging: the workgroup's 64 x 576-byte block is copied in 16-byte pieces, piece
+    //      i*256 + tid per thread (coalesced); afterwards thread (co = tid/4, 16-channel group tid%4)
+    //      transposes its 144 bytes
+    const int wco = tid >> 2, wc16 = tid & 3;
+    const int8_t* wblk = w + (int64_t)(mb << 6) * C_in * 9;
+    int woff[9];
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+        const int piece = i * 256 + tid;
+        woff[i] = (piece / 36) * C_in * 9 + (piece % 36) * 16;
+    }
+
+    u32 xv[kXItems][16];
+    intx4 wv[9];
+    auto fetch = [&](int c0) {
+        const int8_t* xcp = xn + (int64_t)c0 * HW;
+#pragma unroll
+        for (int k = 0; k < kXItems; ++k) {
+#pragma unroll
+            for (int c = 0; c < 16; ++c)
+                xv[k][c] = xoff[k] >= 0 ? *reinterpret_cast<const u32*>(xcp + xoff[k] + c * HW) : 0u;
+        }
+        const int8_t* ws = wblk + (int64_t)c0 * 9;
+#pragma unroll
+        for (int i = 0; i < 9; ++i) wv[i] = *reinterpret_cast<const intx4*>(ws + woff[i]);
+    };
+
+    // ---- operand addresses ---------------------------------------------------------------------
+    const int tile_px = TH * TW;
+    int boff[kNBW];
+#pragma unroll
+    for (int i = 0; i < kNBW; ++i) {
+        int p = (wn * kNBW + i) * 16 + lj;
+        if (p >= tile_px) p = 0;
+        const int pi = p / TW, pj = p - pi * TW;
+        boff[i] = (pi * IW + pj) * kPitch + 16 * lq;
+    }
+    const int aoff = (32 * wm + lj) * kPitch + 16 * lq;
+
+    intx4 acc[2][kNBW];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int i = 0; i < kNBW; ++i) acc[m][i] = intx4{0, 0, 0, 0};
+
+    fetch(0);
+    __syncthreads();   // window zeroed
+    const int chunks = C_in / kCK;
+    for (int ch = 0; ch < chunks; ++ch) {
+        // input: transpose 16 channels x 4 pixels in registers, one 16-byte write per pixel
+#pragma unroll
+        for (int k = 0; k < kXItems; ++k) {
+            if (xoff[k] >= 0) {
+                const int c = xc[k];
+                if (c >= 0 && c < IW) *reinterpret_cast<intx4*>(lx + xlds[k]) = xgather_px<0>(xv[k]);
+                if (c + 1 >= 0 && c + 1 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + kPitch) = xgather_px<1>(xv[k]);
+                if (c + 2 >= 0 && c + 2 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + 2 * kPitch) = xgather_px<2>(xv[k]);
+                if (c + 3 >= 0 && c + 3 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + 3 * kPitch) = xgather_px<3>(xv[k]);
+            }
+        }
+        // weights: coalesced copy into the staging area, then every thread picks up its 144 bytes
+#pragma unroll
+        for (int i = 0; i < 9; ++i) *reinterpret_cast<intx4*>(lraw + (i * 256 + tid) * 16) = wv[i];
+        __syncthreads();
+        u32 raw[36];
+#pragma unroll
+        for (int i = 0; i < 9; ++i) {
+            const intx4 v = *reinterpret_cast<const intx4*>(lraw + (wco * 4 + wc16) * 144 + 16 * i);
+            raw[4 * i + 0] = (u32)v.x; raw[4 * i + 1] = (u32)v.y; raw[4 * i + 2] = (u32)v.z; raw[4 * i + 3] = (u32)v.w;
+        }
+        unsigned char* wdst = lw + wco * kPitch + 16 * wc16;
+        *reinterpret_cast<intx4*>(wdst + 0 * 64 * kPitch) = wgather_tap<0>(raw);
+        *reinterpret_cast<intx4*>(wdst + 1 * 64 * kPitch) = wgather_tap<1>(raw);
+        *reinterpret_cast<intx4*>(wdst + 2 * 64 * kPitch) = wgather_tap<2>(raw);
+        *reinterpret_cast<intx4*>(wdst + 3 * 64 * kPitch) = wgather_tap<3>(raw);
+        *reinterpret_cast<intx4*>(wdst + 4 * 64 * kPitch) = wgather_tap<4>(raw);
+        *reinterpret_cast<intx4*>(wdst + 5 * 64 * kPitch) = wgather_tap<5>(raw);
+        *reinterpret_cast<intx4*>(wdst + 6 * 64 * kPitch) = wgather_tap<6>(raw);
+        *reinterpret_cast<intx4*>(wdst + 7 * 64 * kPitch) = wgather_tap<7>(raw);
+        *reinterpret_cast<intx4*>(wdst + 8 * 64 * kPitch) = wgather_tap<8>(raw);
+        __syncthreads();
+        if (ch + 1 < chunks) fetch((ch + 1) * kCK);
+
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+#pragma unroll
+            for (int s = 0; s < 3; ++s) {
+                const int tap = r * 3 + s;
+                const int toff = (r * IW + s) * kPitch;
+                const intx4 a0 = *reinterpret_cast<const intx4*>(lw + aoff + tap * 64 * kPitch);
+                const intx4 a1 = *reinterpret_cast<const intx4*>(lw + aoff + tap * 64 * kPitch + 16 * kPitch);
+                intx4 bv[kNBW];
+#pragma unroll
+                for (int i = 0; i < kNBW; ++i) bv[i] = *reinterpret_cast<const intx4*>(lx + boff[i] + toff);
+#pragma unroll
+                for (int i = 0; i < kNBW; ++i) {
+                    acc[0][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bv[i], acc[0][i], 0, 0, 0);
+                    acc[1][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bv[i], acc[1][i], 0, 0, 0);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- store: lane holds channels co4..co4+3 of pixel p ------------------------------------------
+    const int HoWo = Ho * Wo;
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int co4 = (mb << 6) + 32 * wm + 16 * m + 4 * lq;
+        int32_t* yn = y + ((int64_t)n * C_out + co4) * HoWo;
+#pragma unroll
+        for (int i = 0; i < kNBW; ++i) {
+            const int p = (wn * kNBW + i) * 16 + lj;
+            const int pi = p / TW, pj = p - pi * TW;
+            const int oi = row0 + pi, oj = col0 + pj;
+            if (p < tile_px && oi < Ho && oj < Wo) {
+                int32_t* dst = yn + oi * Wo + oj;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) dst[v * HoWo] = acc[m][i][v];
+            }
+        }
+    }
+}
+
+struct Tiling {
+    int TH, TW, tiles_x, tiles_y;
+};
+
+Tiling pick_tiling(const Conv2dShape& s)
+{
+    Tiling t;
+    const int splits = (s.Wo + 63) / 64;
+    t.TW = (s.Wo + splits - 1) / splits;
+    t.TH = kTilePx / t.TW;
+    if (t.TH > s.Ho) t.TH = s.Ho;
+    auto fits = [&](int th) {
+        const int IH = th + 2, IW = t.TW + 2;
+        const int nq_max = (IW + 2) / 4 + 1;   // column quads a window can touch
+        return IH * IW <= kLdsPx && 4 * IH * nq_max <= kXItems * 256;
+    };
+    while (t.TH > 1 && !fits(t.TH)) --t.TH;
+    t.tiles_x = (s.Wo + t.TW - 1) / t.TW;
+    t.tiles_y = (s.Ho + t.TH - 1) / t.TH;
+    return t;
+}
+
+bool tiling_ok(const Conv2dShape& s, const Tiling& t)
+{
+    const int IH = t.TH + 2, IW = t.TW + 2;
+    const int nq_max = (IW + 2) / 4 + 1;
+    return t.TH >= 1 && t.TH * t.TW <= kTilePx && IH * IW <= kLdsPx && 4 * IH * nq_max <= kXItems * 256 &&
+           (int64_t)s.N * (s.C_out / 64) * t.tiles_x * t.tiles_y <= 2147483647LL;
+}
+
+}  // namespace
+
+bool mfma_s8_supported(const Conv2dShape& s)
+{
+    if (s.stride != 1 || s.R != 3 || s.S != 3) return false;
+    if (s.C_in % kCK != 0 || s.C_out % 64 != 0 || s.W % 4 != 0) return false;
+    if ((int64_t)s.C_in * s.H * s.W > 2147483647LL) return false;
+    return tiling_ok(s, pick_tiling(s));
+}
+
+hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st)
+{
+    // the vectorised staging reads 4-byte groups of x and 16-byte groups of w
+    if (reinterpret_cast<uintptr_t>(x) % 4 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0)
+        return launch_direct_conv2d_s8(x, w, y, s, st);
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    if (attr != hipSuccess) return attr;
+    const Tiling t = pick_tiling(s);
+    const int64_t blocks = (int64_t)s.N * (s.C_out / 64) * t.tiles_x * t.tiles_y;
+    hipLaunchKernelGGL(mfma_s8_kernel, dim3((unsigned)blocks), dim3(256), kLdsBytes, st, x, w, y, s.C_in, s.C_out,
+                       s.H, s.W, s.pad, s.Ho, s.Wo, t.TH, t.TW, t.tiles_x, t.tiles_y);
+    return hipGetLastError();
+}
+
+}  // namespace swconv

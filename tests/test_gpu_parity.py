@@ -226,7 +226,12 @@ S8_CASES = [
     (2, 4, 3, 12, 10, 2, 5, 2, 2),
     (1, 128, 128, 28, 28, 3, 3, 1, 1),
     (2, 64, 64, 28, 28, 3, 3, 1, 1),
-    (1, 128, 64, 13, 17, 3, 3, 1, 1),    # ragged
+    (1, 128, 64, 13, 17, 3, 3, 1, 1),    # ragged, width not a multiple of 4: direct kernel
+    (1, 128, 64, 13, 20, 3, 3, 1, 1),    # ragged row bands on the matrix-core path
+    (1, 64, 128, 30, 12, 3, 3, 1, 0),    # valid mode
+    (1, 64, 64, 9, 100, 3, 3, 1, 1),     # two column tiles
+    (2, 64, 64, 56, 56, 3, 3, 1, 1),
+    (1, 192, 64, 7, 8, 3, 3, 1, 2),      # padding wider than the filter needs
     (1, 64, 128, 30, 9, 3, 3, 1, 0),
     (1, 192, 64, 10, 10, 5, 5, 1, 2),
     (1, 64, 64, 15, 15, 3, 3, 2, 1),

@@ -21,6 +21,8 @@ namespace swconv {
 
 namespace {
 
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
 constexpr int kB = 7;            // outputs per lane per axis
 constexpr int kTile = 8 * kB;    // 56 outputs per tile per axis
 constexpr int kMaxRS = 17;       // largest filter extent this kernel takes
@@ -28,6 +30,33 @@ constexpr int kOutPitch = kTile;
 
 constexpr int in_pitch(int S) { return (3 + kTile + S - 1) <= 72 ? 72 : 104; }
 constexpr int in_rows(int R) { return kTile + R - 1; }
+
+
+// The lane's 7 x 7 outputs for a filter extent known at compile time.  Input row ir of the lane's
+// window is read once (7 + S - 1 floats) and used by every output row orow with 0 <= ir - orow < R.
+template <int R, int S, int P>
+__device__ __forceinline__ void accumulate_block(const float* __restrict__ win, const float* __restrict__ wf,
+                                                 float (&acc)[kB][kB])
+{
+    float wr[R * S];
+#pragma unroll
+    for (int t = 0; t < R * S; ++t) wr[t] = wf[t];
+#pragma unroll
+    for (int ir = 0; ir < kB + R - 1; ++ir) {
+        float in[kB + S - 1];
+#pragma unroll
+        for (int c = 0; c < kB + S - 1; ++c) in[c] = win[ir * P + c];
+#pragma unroll
+        for (int orow = 0; orow < kB; ++orow) {
+            const int r = ir - orow;
+            if (r < 0 || r >= R) continue;
+#pragma unroll
+            for (int q = 0; q < S; ++q)
+#pragma unroll
+                for (int oc = 0; oc < kB; ++oc) acc[orow][oc] = fmaf(wr[r * S + q], in[oc + q], acc[orow][oc]);
+        }
+    }
+}
 
 // RC, SC > 0: filter extent known at compile time.  RC == 0: extent (R, S) at run time, up to kMaxRS.
 template <int RC, int SC>
@@ -97,25 +126,7 @@ __global__ __launch_bounds__(64) void sliding_plane_kernel(const float* __restri
     const float* win = lds + (kB * by) * P + shift + kB * bx;   // the lane's window origin
 
     if (RC > 0) {
-        float wr[RMAX * SMAX];
-#pragma unroll
-        for (int t = 0; t < RMAX * SMAX; ++t) wr[t] = wf[t];
-#pragma unroll
-        for (int ir = 0; ir < kB + RMAX - 1; ++ir) {
-            float in[kB + SMAX - 1];
-#pragma unroll
-            for (int c = 0; c < kB + SMAX - 1; ++c) in[c] = win[ir * P + c];
-#pragma unroll
-            for (int orow = 0; orow < kB; ++orow) {
-                const int r = ir - orow;
-                if (r < 0 || r >= RMAX) continue;
-#pragma unroll
-                for (int s = 0; s < SMAX; ++s)
-#pragma unroll
-                    for (int oc = 0; oc < kB; ++oc)
-                        acc[orow][oc] = fmaf(wr[r * SMAX + s], in[oc + s], acc[orow][oc]);
-            }
-        }
+        accumulate_block<RMAX, SMAX, P>(win, wf, acc);
     } else {
         for (int r = 0; r < R; ++r) {
             for (int s = 0; s < S; ++s) {
@@ -156,6 +167,108 @@ __global__ __launch_bounds__(64) void sliding_plane_kernel(const float* __restri
     }
 }
 
+
+// Whole-plane variant for planes that fit one tile (H_out, W_out <= 56, padding <= (R-1)/2, widths
+// multiples of 4): the common CNN case.  A wavefront walks over several planes.  The next plane is
+// fetched from HBM into registers (13 x 16 bytes per lane, one contiguous run per wavefront) while
+// the current one is accumulated out of LDS; the zero halo is written once and never touched again,
+// because the finished outputs are staged in the image area of the same LDS window.
+// Orders the LDS traffic of a one-wavefront workgroup: LDS operations of a wavefront complete in
+// order, so waiting for the LDS counter is all it takes.  Unlike __syncthreads() this does not wait
+// for global loads in flight, which is what lets the next plane's fetch overlap the accumulation.
+__device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+// SQ: the plane and its output are exactly 56 x 56 (every slot count is then a compile-time constant).
+template <int R, int S, bool SQ>
+__global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __restrict__ x,
+                                                                const float* __restrict__ w,
+                                                                float* __restrict__ y, int planes,
+                                                                int planes_per_x, int n_filters, int H_rt,
+                                                                int W_rt, int pad, int Ho_rt, int Wo_rt)
+{
+    const int H = SQ ? kTile : H_rt, W = SQ ? kTile : W_rt, Ho = SQ ? kTile : Ho_rt, Wo = SQ ? kTile : Wo_rt;
+    constexpr int P = in_pitch(S);
+    constexpr int ROWS = in_rows(R);
+    constexpr int NSLOT = (kTile * kTile / 4 + 63) / 64;      // 13 16-byte groups per lane at most
+    __shared__ __attribute__((aligned(16))) float lds[ROWS * P];
+
+    const int lane = threadIdx.x;
+    const int pad_up = (pad + 3) & ~3;
+    const int shift = pad_up - pad;
+    const int W4 = W >> 2, Wo4 = Wo >> 2;
+    const int n_in4 = H * W4, n_out4 = Ho * Wo4;
+
+    // slot k of a lane is 16-byte group lane + 64*k of the plane; slots below n*_full are live in
+    // every lane (a wave-uniform test), the one after that in the first n*_rem lanes
+    const int nin_full = n_in4 >> 6, nin_rem = n_in4 & 63;
+    const int nout_full = n_out4 >> 6, nout_rem = n_out4 & 63;
+    int in_slot[NSLOT], out_slot[NSLOT];
+#pragma unroll
+    for (int k = 0; k < NSLOT; ++k) {
+        const int f = lane + 64 * k;
+        const int ri = f / W4, ro = f / Wo4;
+        in_slot[k] = (ri + pad) * P + pad_up + 4 * (f - ri * W4);
+        out_slot[k] = (ro + pad) * P + pad_up + 4 * (f - ro * Wo4);
+    }
+
+    for (int i = lane; i < ROWS * P / 4; i += 64) reinterpret_cast<float4*>(lds)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    const int bx = lane & 7, by = lane >> 3;
+    const float* win = lds + (kB * by) * P + shift + kB * bx;
+    float* stage = lds + (kB * by + pad) * P + pad_up + kB * bx;
+    const bool full = SQ || ((Ho == kTile) && (Wo == kTile));
+
+    floatx4 pre[NSLOT];
+    auto fetch = [&](int plane) {
+        const floatx4* src = reinterpret_cast<const floatx4*>(x + (int64_t)(plane / planes_per_x) * H * W);
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k)
+            if (k < nin_full || (k == nin_full && lane < nin_rem)) pre[k] = src[lane + 64 * k];
+    };
+
+    int plane = blockIdx.x;
+    if (plane < planes) fetch(plane);
+    wave_lds_sync();
+#pragma unroll 1
+    for (; plane < planes; plane += gridDim.x) {
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k)
+            if (k < nin_full || (k == nin_full && lane < nin_rem))
+                *reinterpret_cast<floatx4*>(lds + in_slot[k]) = pre[k];
+        const int next = plane + gridDim.x;
+        if (next < planes) fetch(next);
+        wave_lds_sync();
+
+        float acc[kB][kB];
+#pragma unroll
+        for (int i = 0; i < kB; ++i)
+#pragma unroll
+            for (int j = 0; j < kB; ++j) acc[i][j] = 0.f;
+        accumulate_block<R, S, P>(win, w + (int64_t)(plane % n_filters) * R * S, acc);
+        wave_lds_sync();
+
+        if (full) {
+#pragma unroll
+            for (int i = 0; i < kB; ++i)
+#pragma unroll
+                for (int j = 0; j < kB; ++j) stage[i * P + j] = acc[i][j];
+        } else {
+#pragma unroll
+            for (int i = 0; i < kB; ++i)
+#pragma unroll
+                for (int j = 0; j < kB; ++j)
+                    if (kB * by + i < Ho && kB * bx + j < Wo) stage[i * P + j] = acc[i][j];
+        }
+        wave_lds_sync();
+        floatx4* dst = reinterpret_cast<floatx4*>(y + (int64_t)plane * Ho * Wo);
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k)
+            if (k < nout_full || (k == nout_full && lane < nout_rem))
+                dst[lane + 64 * k] = *reinterpret_cast<const floatx4*>(lds + out_slot[k]);
+        wave_lds_sync();
+    }
+}
+
 }  // namespace
 
 bool sliding_plane_supported(int H, int W, int R, int S, int stride, int pad)
@@ -168,6 +281,29 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int n_filters, int H, int W, int R, int S, int pad, int Ho, int Wo,
                                 hipStream_t st)
 {
+    const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
+    const bool fixed = R == S && (R == 3 || R == 5 || R == 7);
+    if (fixed && aligned && Ho <= kTile && Wo <= kTile && 2 * pad <= R - 1 && W % 4 == 0 && Wo % 4 == 0 &&
+        planes <= 2147483647LL) {
+        // enough wavefronts to fill the chip, each walking over several planes
+        const int64_t want = 256 * 8;
+        dim3 grid((unsigned)(planes < want ? planes : want)), block(64);
+#define SW_FULL(RC)                                                                                          \
+    do {                                                                                                     \
+        if (sq)                                                                                              \
+            hipLaunchKernelGGL((sliding_plane_full_kernel<RC, RC, true>), grid, block, 0, st, x, w, y,       \
+                               (int)planes, planes_per_x, n_filters, H, W, pad, Ho, Wo);                     \
+        else                                                                                                 \
+            hipLaunchKernelGGL((sliding_plane_full_kernel<RC, RC, false>), grid, block, 0, st, x, w, y,      \
+                               (int)planes, planes_per_x, n_filters, H, W, pad, Ho, Wo);                     \
+    } while (0)
+        const bool sq = H == kTile && W == kTile && Ho == kTile && Wo == kTile;
+        if (R == 3) SW_FULL(3);
+        else if (R == 5) SW_FULL(5);
+        else SW_FULL(7);
+#undef SW_FULL
+        return hipGetLastError();
+    }
     const int tiles_x = (Wo + kTile - 1) / kTile, tiles_y = (Ho + kTile - 1) / kTile;
     const int64_t blocks = planes * tiles_x * tiles_y;
     if (blocks > 2147483647LL) return hipErrorInvalidValue;

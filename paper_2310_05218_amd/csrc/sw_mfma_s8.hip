@@ -4,7 +4,9 @@
 // shift is an address offset into the tile staged in LDS, so no column matrix exists.
 //
 // Workgroup = 4 wavefronts = 64 output channels x a tile of TH x TW (<= 208) output pixels of one
-// image; input channels are consumed in chunks of 64, one v_mfma_i32_16x16x64_i8 K step per tap.
+// image; input channels are consumed in chunks of 64, two v_mfma_i32_32x32x32_i8 K steps per tap
+// (the 32x32x32 form sustains the matrix cores' peak from one wavefront per SIMD; the 16x16x64 form
+// does not).
 // The matrix instruction wants 16 consecutive K bytes per lane, i.e. channel-contiguous operands,
 // while both tensors arrive channel-strided (NCHW, OIHW).  Both are therefore transposed on their
 // way into LDS with byte permutes in registers:
@@ -12,9 +14,9 @@
 //   weights global [co][ci][tap]   -> coalesced copy to an LDS staging area, then 16 channels x 9
 //                                     taps per lane -> LDS [tap][co][ci], 80-byte pitch
 // The 80-byte pitch spreads the 16-byte operand reads of 16 consecutive pixels (or output channels)
-// evenly over the banks.  The wavefronts split the tile 2 x 2: 32 output channels x 7 pixel blocks
-// each, 56 accumulator registers.  The next chunk is fetched from HBM/L2 into registers while the
-// current one is multiplied.
+// evenly over the banks.  The wavefronts split the tile 2 x 2: 32 output channels x 4 blocks of 32
+// pixels each, 64 accumulator registers.  Two chunks are kept in flight from HBM/L2 into registers,
+// so a 128-channel problem issues every global load before its first multiplication.
 #include "swconv_internal.h"
 
 namespace swconv {
@@ -22,13 +24,14 @@ namespace swconv {
 namespace {
 
 typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32;
 
 constexpr int kCK = 64;            // input channels per chunk
 constexpr int kPitch = 80;         // bytes per pixel / per weight row in LDS
-constexpr int kNB = 13;            // 16-pixel blocks per tile
-constexpr int kNBW = 7;            // pixel blocks per wavefront
-constexpr int kTilePx = kNB * 16;
+constexpr int kNBW = 4;            // 32-pixel blocks per wavefront
+constexpr int kNB = 2 * kNBW;      // 32-pixel blocks per tile
+constexpr int kTilePx = kNB * 32;
 constexpr int kLdsPx = 320;        // pixels of the staged input window
 constexpr int kXItems = 2;         // (16-channel group, row, column quad) items per thread and chunk
 constexpr int kXBytes = kLdsPx * kPitch;            // 25600
@@ -78,12 +81,17 @@ __device__ __forceinline__ intx4 xgather_px(const u32* in)
     return v;
 }
 
+struct S8Params {
+    int C_in, C_out, H, W, pad, Ho, Wo, TH, TW, nq_max, wide_store;
+    FastDiv by_tiles_x, by_TW, by_IH, by_nq_max, by_pieces;
+};
+
 __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restrict__ x,
                                                          const int8_t* __restrict__ w,
-                                                         int32_t* __restrict__ y, int C_in, int C_out,
-                                                         int H, int W, int pad, int Ho, int Wo, int TH,
-                                                         int TW, int tiles_x, int tiles_y)
+                                                         int32_t* __restrict__ y, const S8Params P)
 {
+    const int C_in = P.C_in, C_out = P.C_out, H = P.H, W = P.W, pad = P.pad, Ho = P.Ho, Wo = P.Wo;
+    const int TH = P.TH, TW = P.TW;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* lx = smem;                       // [pixel][ci]      pitch 80
     unsigned char* lw = smem + kXBytes;             // [tap][co][ci]    pitch 80
@@ -91,15 +99,13 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int lq = lane >> 4, lj = lane & 15;
+    const int lg = lane >> 5, lj = lane & 31;      // K half and row/column inside a 32 x 32 block
     const int wm = wave >> 1, wn = wave & 1;
 
-    int b = blockIdx.x;
-    const int tx = b % tiles_x; b /= tiles_x;
-    const int ty = b % tiles_y; b /= tiles_y;
-    const int mblocks = C_out >> 6;
-    const int mb = b % mblocks;
-    const int n = b / mblocks;
+    const int ty = fast_div(blockIdx.x, P.by_tiles_x);
+    const int tx = blockIdx.x - ty * (int)P.by_tiles_x.d;
+    const int mb = blockIdx.y;
+    const int n = blockIdx.z;
 
     const int row0 = ty * TH, col0 = tx * TW;
     const int IH = TH + 2, IW = TW + 2;
@@ -113,20 +119,20 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
     const int wc0 = col0 - pad;                        // image column of window column 0
     const int g_lo = wc0 >> 2;                         // arithmetic shift: floor for negatives
     const int nq = ((wc0 + IW - 1) >> 2) - g_lo + 1;
-    const int nitems = 4 * IH * nq;
+    const int nitems = 4 * IH * P.nq_max;
     int xoff[kXItems];      // byte offset of (channel 16*c16, row, 4g) in the image; < 0: skip item
     int xlds[kXItems];      // byte address in lx of window column (4g - wc0) of that row, channel 16*c16
     int xc[kXItems];        // window column of the quad's first pixel (may be < 0)
 #pragma unroll
     for (int k = 0; k < kXItems; ++k) {
         const int idx = tid + 256 * k;
-        const int g = idx % nq;
-        const int t = idx / nq;
-        const int e = t % IH;
-        const int c16 = t / IH;
+        const int t = fast_div(idx, P.by_nq_max);
+        const int g = idx - t * P.nq_max;
+        const int c16 = fast_div(t, P.by_IH);
+        const int e = t - c16 * IH;
         const int gr = row0 - pad + e;
         const int gc = 4 * (g_lo + g);
-        const bool ok = idx < nitems && gr >= 0 && gr < H && gc >= 0 && gc + 3 < W;
+        const bool ok = idx < nitems && g < nq && gr >= 0 && gr < H && gc >= 0 && gc + 3 < W;
         xoff[k] = ok ? (16 * c16 * H + gr) * W + gc : -1;
         xc[k] = gc - wc0;
         xlds[k] = (e * IW + xc[k]) * kPitch + 16 * c16;
@@ -144,9 +150,10 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         woff[i] = (piece / 36) * C_in * 9 + (piece % 36) * 16;
     }
 
-    u32 xv[kXItems][16];
-    intx4 wv[9];
-    auto fetch = [&](int c0) {
+    // two register sets, each holding one chunk on its way from global memory to LDS
+    u32 xv0[kXItems][16], xv1[kXItems][16];
+    intx4 wv0[9], wv1[9];
+    auto fetch = [&](u32 (&xv)[kXItems][16], intx4 (&wv)[9], int c0) {
         const int8_t* xcp = xn + (int64_t)c0 * HW;
 #pragma unroll
         for (int k = 0; k < kXItems; ++k) {
@@ -164,24 +171,21 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
     int boff[kNBW];
 #pragma unroll
     for (int i = 0; i < kNBW; ++i) {
-        int p = (wn * kNBW + i) * 16 + lj;
+        int p = (wn * kNBW + i) * 32 + lj;
         if (p >= tile_px) p = 0;
-        const int pi = p / TW, pj = p - pi * TW;
-        boff[i] = (pi * IW + pj) * kPitch + 16 * lq;
+        const int pi = fast_div(p, P.by_TW), pj = p - pi * TW;
+        boff[i] = (pi * IW + pj) * kPitch + 16 * lg;
     }
-    const int aoff = (32 * wm + lj) * kPitch + 16 * lq;
+    const int aoff = (32 * wm + lj) * kPitch + 16 * lg;
 
-    intx4 acc[2][kNBW];
+    intx16 acc[kNBW];
 #pragma unroll
-    for (int m = 0; m < 2; ++m)
+    for (int i = 0; i < kNBW; ++i)
 #pragma unroll
-        for (int i = 0; i < kNBW; ++i) acc[m][i] = intx4{0, 0, 0, 0};
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0;
 
-    fetch(0);
-    __syncthreads();   // window zeroed
-    const int chunks = C_in / kCK;
-    for (int ch = 0; ch < chunks; ++ch) {
-        // input: transpose 16 channels x 4 pixels in registers, one 16-byte write per pixel
+    // registers -> LDS (with the byte transposes), then the chunk's 9 taps x 2 K steps
+    auto stage = [&](u32 (&xv)[kXItems][16], intx4 (&wv)[9]) {
 #pragma unroll
         for (int k = 0; k < kXItems; ++k) {
             if (xoff[k] >= 0) {
@@ -192,7 +196,6 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
                 if (c + 3 >= 0 && c + 3 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + 3 * kPitch) = xgather_px<3>(xv[k]);
             }
         }
-        // weights: coalesced copy into the staging area, then every thread picks up its 144 bytes
 #pragma unroll
         for (int i = 0; i < 9; ++i) *reinterpret_cast<intx4*>(lraw + (i * 256 + tid) * 16) = wv[i];
         __syncthreads();
@@ -213,45 +216,86 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         *reinterpret_cast<intx4*>(wdst + 7 * 64 * kPitch) = wgather_tap<7>(raw);
         *reinterpret_cast<intx4*>(wdst + 8 * 64 * kPitch) = wgather_tap<8>(raw);
         __syncthreads();
-        if (ch + 1 < chunks) fetch((ch + 1) * kCK);
+    };
+    // 18 steps (9 taps x 2 K halves); the operands of step t+1 are read from LDS while step t multiplies
+    auto load_step = [&](int step, intx4& a, intx4 (&bv)[kNBW]) {
+        const int tap = step >> 1, kk = step & 1;
+        const int r = tap / 3, q = tap - 3 * r;
+        const int toff = (r * IW + q) * kPitch + 32 * kk;
+        a = *reinterpret_cast<const intx4*>(lw + aoff + tap * 64 * kPitch + 32 * kk);
+#pragma unroll
+        for (int i = 0; i < kNBW; ++i) bv[i] = *reinterpret_cast<const intx4*>(lx + boff[i] + toff);
+    };
+    auto multiply = [&]() {
+        intx4 a[2];
+        intx4 bv[2][kNBW];
+        load_step(0, a[0], bv[0]);
+#pragma unroll
+        for (int step = 0; step < 18; ++step) {
+            const int cur = step & 1;
+            if (step + 1 < 18) load_step(step + 1, a[cur ^ 1], bv[cur ^ 1]);
+            __builtin_amdgcn_sched_barrier(0);      // keep the reads ahead of the multiplications
+#pragma unroll
+            for (int i = 0; i < kNBW; ++i)
+                acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[cur], bv[cur][i], acc[i], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        __syncthreads();
+    };
 
+    const int chunks = C_in / kCK;
+    fetch(xv0, wv0, 0);
+    if (chunks > 1) fetch(xv1, wv1, kCK);
+    __syncthreads();   // window zeroed
+    for (int ch = 0; ch < chunks; ch += 2) {
+        stage(xv0, wv0);
+        if (ch + 2 < chunks) fetch(xv0, wv0, (ch + 2) * kCK);
+        multiply();
+        if (ch + 1 < chunks) {
+            stage(xv1, wv1);
+            if (ch + 3 < chunks) fetch(xv1, wv1, (ch + 3) * kCK);
+            multiply();
+        }
+    }
+
+    // ---- store: register v of a lane is channel 8*(v/4) + 4*lg + v%4 of the block, pixel lj ---------
+    const int HoWo = Ho * Wo;
+    if (P.wide_store) {
+        // Full-width tiles: the tile of one channel is one contiguous run of y.  The accumulators go
+        // through LDS ([channel][pixel]; the operands are dead by now) and leave as 16-byte stores.
+        const int valid_px = min(TH, Ho - row0) * Wo;          // multiple of 4
+        const int pitch = tile_px + 4;
+        int* lo = reinterpret_cast<int*>(smem);
 #pragma unroll
-        for (int r = 0; r < 3; ++r) {
+        for (int i = 0; i < kNBW; ++i) {
+            const int p = (wn * kNBW + i) * 32 + lj;
+            if (p < tile_px) {
 #pragma unroll
-            for (int s = 0; s < 3; ++s) {
-                const int tap = r * 3 + s;
-                const int toff = (r * IW + s) * kPitch;
-                const intx4 a0 = *reinterpret_cast<const intx4*>(lw + aoff + tap * 64 * kPitch);
-                const intx4 a1 = *reinterpret_cast<const intx4*>(lw + aoff + tap * 64 * kPitch + 16 * kPitch);
-                intx4 bv[kNBW];
-#pragma unroll
-                for (int i = 0; i < kNBW; ++i) bv[i] = *reinterpret_cast<const intx4*>(lx + boff[i] + toff);
-#pragma unroll
-                for (int i = 0; i < kNBW; ++i) {
-                    acc[0][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bv[i], acc[0][i], 0, 0, 0);
-                    acc[1][i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bv[i], acc[1][i], 0, 0, 0);
-                }
+                for (int v = 0; v < 16; ++v) lo[(32 * wm + 8 * (v >> 2) + 4 * lg + (v & 3)) * pitch + p] = acc[i][v];
             }
         }
         __syncthreads();
+        const int pieces = valid_px >> 2;                       // 16-byte pieces per channel
+        int32_t* yt = y + ((int64_t)n * C_out + (mb << 6)) * HoWo + row0 * Wo;
+        for (int idx = tid; idx < 64 * (int)P.by_pieces.d; idx += 256) {
+            const int c = fast_div(idx, P.by_pieces);
+            const int q = idx - c * (int)P.by_pieces.d;
+            if (q < pieces)
+                *reinterpret_cast<intx4*>(yt + (int64_t)c * HoWo + 4 * q) = *reinterpret_cast<const intx4*>(lo + c * pitch + 4 * q);
+        }
+        return;
     }
-
-    // ---- store: lane holds channels co4..co4+3 of pixel p ------------------------------------------
-    const int HoWo = Ho * Wo;
+    const int co0 = (mb << 6) + 32 * wm + 4 * lg;
+    int32_t* yn = y + ((int64_t)n * C_out + co0) * HoWo;
 #pragma unroll
-    for (int m = 0; m < 2; ++m) {
-        const int co4 = (mb << 6) + 32 * wm + 16 * m + 4 * lq;
-        int32_t* yn = y + ((int64_t)n * C_out + co4) * HoWo;
+    for (int i = 0; i < kNBW; ++i) {
+        const int p = (wn * kNBW + i) * 32 + lj;
+        const int pi = fast_div(p, P.by_TW), pj = p - pi * TW;
+        const int oi = row0 + pi, oj = col0 + pj;
+        if (p < tile_px && oi < Ho && oj < Wo) {
+            int32_t* dst = yn + oi * Wo + oj;
 #pragma unroll
-        for (int i = 0; i < kNBW; ++i) {
-            const int p = (wn * kNBW + i) * 16 + lj;
-            const int pi = p / TW, pj = p - pi * TW;
-            const int oi = row0 + pi, oj = col0 + pj;
-            if (p < tile_px && oi < Ho && oj < Wo) {
-                int32_t* dst = yn + oi * Wo + oj;
-#pragma unroll
-                for (int v = 0; v < 4; ++v) dst[v * HoWo] = acc[m][i][v];
-            }
+            for (int v = 0; v < 16; ++v) dst[(8 * (v >> 2) + (v & 3)) * HoWo] = acc[i][v];
         }
     }
 }
@@ -267,12 +311,14 @@ Tiling pick_tiling(const Conv2dShape& s)
     t.TW = (s.Wo + splits - 1) / splits;
     t.TH = kTilePx / t.TW;
     if (t.TH > s.Ho) t.TH = s.Ho;
+    auto even = [&](int th) { const int bands = (s.Ho + th - 1) / th; return (s.Ho + bands - 1) / bands; };
     auto fits = [&](int th) {
         const int IH = th + 2, IW = t.TW + 2;
         const int nq_max = (IW + 2) / 4 + 1;   // column quads a window can touch
         return IH * IW <= kLdsPx && 4 * IH * nq_max <= kXItems * 256;
     };
     while (t.TH > 1 && !fits(t.TH)) --t.TH;
+    t.TH = even(t.TH);      // equal row bands: same tile count, no nearly empty last band
     t.tiles_x = (s.Wo + t.TW - 1) / t.TW;
     t.tiles_y = (s.Ho + t.TH - 1) / t.TH;
     return t;
@@ -283,7 +329,7 @@ bool tiling_ok(const Conv2dShape& s, const Tiling& t)
     const int IH = t.TH + 2, IW = t.TW + 2;
     const int nq_max = (IW + 2) / 4 + 1;
     return t.TH >= 1 && t.TH * t.TW <= kTilePx && IH * IW <= kLdsPx && 4 * IH * nq_max <= kXItems * 256 &&
-           (int64_t)s.N * (s.C_out / 64) * t.tiles_x * t.tiles_y <= 2147483647LL;
+           (int64_t)t.tiles_x * t.tiles_y <= 65535 && s.C_out / 64 <= 65535 && s.N <= 65535;
 }
 
 }  // namespace
@@ -305,9 +351,20 @@ hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Co
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr != hipSuccess) return attr;
     const Tiling t = pick_tiling(s);
-    const int64_t blocks = (int64_t)s.N * (s.C_out / 64) * t.tiles_x * t.tiles_y;
-    hipLaunchKernelGGL(mfma_s8_kernel, dim3((unsigned)blocks), dim3(256), kLdsBytes, st, x, w, y, s.C_in, s.C_out,
-                       s.H, s.W, s.pad, s.Ho, s.Wo, t.TH, t.TW, t.tiles_x, t.tiles_y);
+    S8Params P;
+    P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
+    P.TH = t.TH; P.TW = t.TW;
+    P.nq_max = (t.TW + 2 + 2) / 4 + 1;
+    // 16-byte stores need full-width tiles whose runs of y start and end on 16-byte boundaries
+    P.wide_store = t.tiles_x == 1 && s.Wo % 4 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0 &&
+                   64 * (t.TH * t.TW + 4) * 4 <= kLdsBytes;
+    P.by_tiles_x = make_fastdiv(t.tiles_x);
+    P.by_TW = make_fastdiv(t.TW);
+    P.by_IH = make_fastdiv(t.TH + 2);
+    P.by_nq_max = make_fastdiv(P.nq_max);
+    P.by_pieces = make_fastdiv(t.TH * s.Wo / 4 > 0 ? t.TH * s.Wo / 4 : 1);
+    dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)(s.C_out / 64), (unsigned)s.N);
+    hipLaunchKernelGGL(mfma_s8_kernel, grid, dim3(256), kLdsBytes, st, x, w, y, P);
     return hipGetLastError();
 }
 

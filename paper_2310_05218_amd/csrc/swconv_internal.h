@@ -10,6 +10,16 @@ namespace swconv {
 
 enum Op1D { OP_CONV = 0, OP_AVG = 1, OP_MAX = 2 };
 
+// Division by a run-time constant without the integer divide sequence: exact while n * d < 2^32.
+struct FastDiv {
+    uint32_t d, magic;
+};
+inline FastDiv make_fastdiv(int d)
+{
+    return FastDiv{(uint32_t)d, d == 1 ? 0u : (uint32_t)(0x100000000ULL / (uint32_t)d) + 1u};
+}
+__device__ __forceinline__ int fast_div(int n, FastDiv f) { return f.magic ? (int)__umulhi((uint32_t)n, f.magic) : n; }
+
 struct Conv2dShape {
     int N, C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
 };

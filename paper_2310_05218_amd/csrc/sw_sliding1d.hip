@@ -7,13 +7,19 @@
 // that is the padding).  Each lane then owns four consecutive outputs.  It keeps an 8-float window
 // of the input in registers; the four taps j..j+3 are accumulated against the window shifted by
 // 0..3 elements (a register rename, no data movement), then the window slides on by four elements
-// with one 16-byte LDS read.  Outputs leave through 16-byte stores when the output row is
-// 16-byte aligned, otherwise through LDS as fully coalesced 4-byte stores.
+// with one 16-byte LDS read.  Outputs leave through 16-byte stores: directly when every output row is
+// 16-byte aligned, otherwise through LDS, re-grouped so that each store is aligned in memory.
 #include "swconv_internal.h"
 
 namespace swconv {
 
 namespace {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// Inputs are read once and outputs written once: both bypass the caches' retention (nontemporal).
+__device__ __forceinline__ floatx4 stream_load4(const float* p) { return __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(p)); }
+__device__ __forceinline__ void stream_store4(float* p, floatx4 v) { __builtin_nontemporal_store(v, reinterpret_cast<floatx4*>(p)); }
 
 constexpr int kThreads = 256;
 constexpr int kSub = kThreads * 4;      // outputs per pass over the workgroup
@@ -63,16 +69,16 @@ __global__ __launch_bounds__(kThreads) void sliding_1d_kernel(const float* __res
     if (x_vec_ok) {
         for (int f = tid; f < n_in4; f += kThreads) {
             const int t = t0 + 4 * f;
-            float4 v;
+            floatx4 v;
             if (t >= 0 && t + 3 < len) {
-                v = *reinterpret_cast<const float4*>(xr + t);
+                v = stream_load4(xr + t);
             } else {
                 v.x = (t >= 0 && t < len) ? xr[t] : 0.f;
                 v.y = (t + 1 >= 0 && t + 1 < len) ? xr[t + 1] : 0.f;
                 v.z = (t + 2 >= 0 && t + 2 < len) ? xr[t + 2] : 0.f;
                 v.w = (t + 3 >= 0 && t + 3 < len) ? xr[t + 3] : 0.f;
             }
-            *reinterpret_cast<float4*>(s_in + 4 * f) = v;
+            *reinterpret_cast<floatx4*>(s_in + 4 * f) = v;
         }
     } else {
         for (int e = tid; e < 4 * n_in4; e += kThreads) {
@@ -138,7 +144,7 @@ __global__ __launch_bounds__(kThreads) void sliding_1d_kernel(const float* __res
             }
             if (y_vec_ok) {
                 if (base + 3 < n_out) {
-                    *reinterpret_cast<float4*>(yr + base) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+                    stream_store4(yr + base, floatx4{acc[0], acc[1], acc[2], acc[3]});
                 } else {
 #pragma unroll
                     for (int p = 0; p < 4; ++p)
@@ -149,8 +155,18 @@ __global__ __launch_bounds__(kThreads) void sliding_1d_kernel(const float* __res
         if (!y_vec_ok) *reinterpret_cast<float4*>(s_out + base) = make_float4(acc[0], acc[1], acc[2], acc[3]);
     }
     if (!y_vec_ok) {
+        // The output row does not start on a 16-byte boundary: peel up to three elements, then store
+        // 16-byte groups that are aligned in memory (read from LDS at the matching odd offset).
         __syncthreads();
-        for (int e = tid; e < n_out; e += kThreads) yr[e] = s_out[e];
+        const int head = min(n_out, (int)(((16u - (unsigned)(reinterpret_cast<uintptr_t>(yr) & 15u)) & 15u) >> 2));
+        const int body4 = (n_out - head) >> 2;
+        const int tail0 = head + 4 * body4;
+        if (tid < head) yr[tid] = s_out[tid];
+        for (int f = tid; f < body4; f += kThreads) {
+            const int e = head + 4 * f;
+            stream_store4(yr + e, floatx4{s_out[e], s_out[e + 1], s_out[e + 2], s_out[e + 3]});
+        }
+        if (tid < n_out - tail0) yr[tail0 + tid] = s_out[tail0 + tid];
     }
 }
 

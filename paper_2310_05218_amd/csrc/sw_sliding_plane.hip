@@ -41,11 +41,18 @@ __device__ __forceinline__ void accumulate_block(const float* __restrict__ win, 
     float wr[R * S];
 #pragma unroll
     for (int t = 0; t < R * S; ++t) wr[t] = wf[t];
+    constexpr int N = kB + S - 1;
+    float in[2][N];
+#pragma unroll
+    for (int c = 0; c < N; ++c) in[0][c] = win[c];
 #pragma unroll
     for (int ir = 0; ir < kB + R - 1; ++ir) {
-        float in[kB + S - 1];
+        // the next row is on its way from LDS while this one is accumulated
+        if (ir + 1 < kB + R - 1) {
 #pragma unroll
-        for (int c = 0; c < kB + S - 1; ++c) in[c] = win[ir * P + c];
+            for (int c = 0; c < N; ++c) in[(ir + 1) & 1][c] = win[(ir + 1) * P + c];
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int orow = 0; orow < kB; ++orow) {
             const int r = ir - orow;
@@ -53,8 +60,10 @@ __device__ __forceinline__ void accumulate_block(const float* __restrict__ win, 
 #pragma unroll
             for (int q = 0; q < S; ++q)
 #pragma unroll
-                for (int oc = 0; oc < kB; ++oc) acc[orow][oc] = fmaf(wr[r * S + q], in[oc + q], acc[orow][oc]);
+                for (int oc = 0; oc < kB; ++oc)
+                    acc[orow][oc] = fmaf(wr[r * S + q], in[ir & 1][oc + q], acc[orow][oc]);
         }
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -223,7 +232,7 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
         const floatx4* src = reinterpret_cast<const floatx4*>(x + (int64_t)(plane / planes_per_x) * H * W);
 #pragma unroll
         for (int k = 0; k < NSLOT; ++k)
-            if (k < nin_full || (k == nin_full && lane < nin_rem)) pre[k] = src[lane + 64 * k];
+            if (k < nin_full || (k == nin_full && lane < nin_rem)) pre[k] = __builtin_nontemporal_load(src + lane + 64 * k);
     };
 
     int plane = blockIdx.x;
@@ -264,7 +273,7 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
 #pragma unroll
         for (int k = 0; k < NSLOT; ++k)
             if (k < nout_full || (k == nout_full && lane < nout_rem))
-                dst[lane + 64 * k] = *reinterpret_cast<const floatx4*>(lds + out_slot[k]);
+                __builtin_nontemporal_store(*reinterpret_cast<const floatx4*>(lds + out_slot[k]), dst + lane + 64 * k);
         wave_lds_sync();
     }
 }

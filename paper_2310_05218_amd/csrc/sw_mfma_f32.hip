@@ -62,8 +62,10 @@ __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restric
 
     const int ty = fast_div(blockIdx.x, P.by_tiles_x);
     const int tx = blockIdx.x - ty * (int)P.by_tiles_x.d;
-    const int mb = blockIdx.y;
-    const int n = blockIdx.z;
+    // image index before channel block: workgroups that share an input tile get linear ids that are equal
+    // modulo 8 when the tile count divides 8, i.e. they land on the same XCD and share its L2
+    const int n = blockIdx.y;
+    const int mb = blockIdx.z;
 
     const int row0 = ty * TH, col0 = tx * TW;
     const int IH = TH + R - 1, IW = TW + S - 1;
@@ -241,7 +243,7 @@ hipError_t launch(const float* x, const float* w, float* y, const Conv2dShape& s
     P.by_TW = make_fastdiv(t.TW);
     P.by_IW = make_fastdiv(t.TW + S - 1);
     P.by_npx = make_fastdiv((t.TH + R - 1) * (t.TW + S - 1));
-    dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)(s.C_out / 64), (unsigned)s.N);
+    dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)s.N, (unsigned)(s.C_out / 64));
     hipLaunchKernelGGL((mfma_f32_kernel<R, S>), grid, dim3(256), bytes, st, x, w, y, P);
     return hipGetLastError();
 }

@@ -104,8 +104,10 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
 
     const int ty = fast_div(blockIdx.x, P.by_tiles_x);
     const int tx = blockIdx.x - ty * (int)P.by_tiles_x.d;
-    const int mb = blockIdx.y;
-    const int n = blockIdx.z;
+    // image index before channel block: workgroups that share an input tile get linear ids that are equal
+    // modulo 8 when the tile count divides 8, i.e. they land on the same XCD and share its L2
+    const int n = blockIdx.y;
+    const int mb = blockIdx.z;
 
     const int row0 = ty * TH, col0 = tx * TW;
     const int IH = TH + 2, IW = TW + 2;
@@ -363,7 +365,7 @@ hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Co
     P.by_IH = make_fastdiv(t.TH + 2);
     P.by_nq_max = make_fastdiv(P.nq_max);
     P.by_pieces = make_fastdiv(t.TH * s.Wo / 4 > 0 ? t.TH * s.Wo / 4 : 1);
-    dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)(s.C_out / 64), (unsigned)s.N);
+    dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)s.N, (unsigned)(s.C_out / 64));
     hipLaunchKernelGGL(mfma_s8_kernel, grid, dim3(256), kLdsBytes, st, x, w, y, P);
     return hipGetLastError();
 }

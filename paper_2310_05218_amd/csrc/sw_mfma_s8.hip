@@ -17,6 +17,13 @@
 // evenly over the banks.  The wavefronts split the tile 2 x 2: 32 output channels x 4 blocks of 32
 // pixels each, 64 accumulator registers.  Two chunks are kept in flight from HBM/L2 into registers,
 // so a 128-channel problem issues every global load before its first multiplication.
+//
+// Resident variant (C_in == 128, the whole K range fits LDS at once: 39 KB of input window, 83 KB of
+// transposed weights): both chunks are staged first, each wavefront then keeps its 36 A operands in
+// registers and walks over its pixel blocks two at a time, all 36 K steps per pair, and stores a pair
+// as soon as it is complete.  The int32 output is 79 % of this problem's memory traffic and the device
+// absorbs writes at roughly half the HBM peak, so letting the stores of one pair drain under the
+// multiplications of the next is what this order is for; no barrier separates the wavefronts here.
 #include "swconv_internal.h"
 
 namespace swconv {
@@ -28,16 +35,18 @@ typedef int intx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32;
 
 constexpr int kCK = 64;            // input channels per chunk
-constexpr int kPitch = 80;         // bytes per pixel / per weight row in LDS
+constexpr int kPitchChunk = 80;    // bytes per pixel / per weight row in LDS, chunked variant
 constexpr int kNBW = 4;            // 32-pixel blocks per wavefront
 constexpr int kNB = 2 * kNBW;      // 32-pixel blocks per tile
 constexpr int kTilePx = kNB * 32;
 constexpr int kLdsPx = 320;        // pixels of the staged input window
 constexpr int kXItems = 2;         // (16-channel group, row, column quad) items per thread and chunk
-constexpr int kXBytes = kLdsPx * kPitch;            // 25600
-constexpr int kWBytes = 9 * 64 * kPitch;            // 46080
+constexpr int kXBytesChunk = kLdsPx * kPitchChunk;  // 25600
+constexpr int kWBytesChunk = 9 * 64 * kPitchChunk;  // 46080
 constexpr int kRawBytes = 64 * kCK * 9;             // 36864
-constexpr int kLdsBytes = kXBytes + kWBytes + kRawBytes;
+constexpr int kLdsBytes = kXBytesChunk + kWBytesChunk + kRawBytes;
+constexpr int kLdsPxRes = 270;     // window pixels of the resident variant (9 rows x 30)
+constexpr int kLdsBytesRes = kLdsPxRes * 144 + 9 * 64 * 144 + kRawBytes;   // 158688 of 163840
 
 // byte k of the result = byte sel_k of the 8-byte value {hi, lo} (lo = bytes 0..3)
 __device__ __forceinline__ u32 perm(u32 hi, u32 lo, u32 sel) { return __builtin_amdgcn_perm(hi, lo, sel); }
@@ -86,15 +95,20 @@ struct S8Params {
     FastDiv by_tiles_x, by_TW, by_IH, by_nq_max, by_pieces;
 };
 
+// RES == 0: input channels in chunks of 64 through LDS.  RES == 128: C_in == 128, all of K resident in LDS.
+template <int RES>
 __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restrict__ x,
                                                          const int8_t* __restrict__ w,
                                                          int32_t* __restrict__ y, const S8Params P)
 {
+    constexpr int kPitch = RES ? RES + 16 : kPitchChunk;            // bytes per pixel / weight row
+    constexpr int kXBytes = RES ? kLdsPxRes * kPitch : kXBytesChunk;
+    constexpr int kWBytes = 9 * 64 * kPitch;
     const int C_in = P.C_in, C_out = P.C_out, H = P.H, W = P.W, pad = P.pad, Ho = P.Ho, Wo = P.Wo;
     const int TH = P.TH, TW = P.TW;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char* lx = smem;                       // [pixel][ci]      pitch 80
-    unsigned char* lw = smem + kXBytes;             // [tap][co][ci]    pitch 80
+    unsigned char* lx = smem;                       // [pixel][ci]
+    unsigned char* lw = smem + kXBytes;             // [tap][co][ci]
     unsigned char* lraw = smem + kXBytes + kWBytes; // [co][ci][tap]    as in global memory
 
     const int tid = threadIdx.x;
@@ -187,15 +201,15 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         for (int v = 0; v < 16; ++v) acc[i][v] = 0;
 
     // registers -> LDS (with the byte transposes), then the chunk's 9 taps x 2 K steps
-    auto stage = [&](u32 (&xv)[kXItems][16], intx4 (&wv)[9]) {
+    auto stage = [&](u32 (&xv)[kXItems][16], intx4 (&wv)[9], int coff) {
 #pragma unroll
         for (int k = 0; k < kXItems; ++k) {
             if (xoff[k] >= 0) {
                 const int c = xc[k];
-                if (c >= 0 && c < IW) *reinterpret_cast<intx4*>(lx + xlds[k]) = xgather_px<0>(xv[k]);
-                if (c + 1 >= 0 && c + 1 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + kPitch) = xgather_px<1>(xv[k]);
-                if (c + 2 >= 0 && c + 2 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + 2 * kPitch) = xgather_px<2>(xv[k]);
-                if (c + 3 >= 0 && c + 3 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + 3 * kPitch) = xgather_px<3>(xv[k]);
+                if (c >= 0 && c < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + coff) = xgather_px<0>(xv[k]);
+                if (c + 1 >= 0 && c + 1 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + coff + kPitch) = xgather_px<1>(xv[k]);
+                if (c + 2 >= 0 && c + 2 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + coff + 2 * kPitch) = xgather_px<2>(xv[k]);
+                if (c + 3 >= 0 && c + 3 < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + coff + 3 * kPitch) = xgather_px<3>(xv[k]);
             }
         }
 #pragma unroll
@@ -207,7 +221,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
             const intx4 v = *reinterpret_cast<const intx4*>(lraw + (wco * 4 + wc16) * 144 + 16 * i);
             raw[4 * i + 0] = (u32)v.x; raw[4 * i + 1] = (u32)v.y; raw[4 * i + 2] = (u32)v.z; raw[4 * i + 3] = (u32)v.w;
         }
-        unsigned char* wdst = lw + wco * kPitch + 16 * wc16;
+        unsigned char* wdst = lw + wco * kPitch + 16 * wc16 + coff;
         *reinterpret_cast<intx4*>(wdst + 0 * 64 * kPitch) = wgather_tap<0>(raw);
         *reinterpret_cast<intx4*>(wdst + 1 * 64 * kPitch) = wgather_tap<1>(raw);
         *reinterpret_cast<intx4*>(wdst + 2 * 64 * kPitch) = wgather_tap<2>(raw);
@@ -245,23 +259,92 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         __syncthreads();
     };
 
+    const int HoWo = Ho * Wo;
+    if constexpr (RES != 0) {
+        constexpr int KS = RES / 32;            // K steps per tap
+        constexpr int NSTEP = 9 * KS;
+        fetch(xv0, wv0, 0);
+        fetch(xv1, wv1, kCK);
+        __syncthreads();   // window zeroed
+        stage(xv0, wv0, 0);
+        stage(xv1, wv1, kCK);
+        intx4 a[NSTEP];    // this wavefront's A operands for the whole K range
+#pragma unroll
+        for (int st = 0; st < NSTEP; ++st)
+            a[st] = *reinterpret_cast<const intx4*>(lw + aoff + (st / KS) * 64 * kPitch + 32 * (st % KS));
+        int32_t* yres = y + ((int64_t)n * C_out + (mb << 6) + 32 * wm + 4 * lg) * HoWo;
+        auto b_at = [&](int i, int st) {
+            const int tap = st / KS, kk = st % KS;
+            const int r = tap / 3, q = tap - 3 * r;
+            return *reinterpret_cast<const intx4*>(lx + boff[i] + (r * IW + q) * kPitch + 32 * kk);
+        };
+        auto store_block = [&](int i, const intx16& c) {
+            const int p = (wn * kNBW + i) * 32 + lj;
+            const int pi = fast_div(p, P.by_TW), pj = p - pi * TW;
+            const int oi = row0 + pi, oj = col0 + pj;
+            if (p < tile_px && oi < Ho && oj < Wo) {
+                int32_t* dst = yres + oi * Wo + oj;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) dst[(8 * (v >> 2) + (v & 3)) * HoWo] = c[v];
+            }
+        };
+#pragma unroll
+        for (int pr = 0; pr < kNBW; pr += 2) {
+            const int first_px = __builtin_amdgcn_readfirstlane((wn * kNBW + pr) * 32);
+            if (first_px >= tile_px) break;
+            if (first_px + 32 < tile_px) {          // two live blocks: two independent accumulators
+                intx16 c0, c1;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) { c0[v] = 0; c1[v] = 0; }
+                intx4 b0[2], b1[2];
+                b0[0] = b_at(pr, 0); b1[0] = b_at(pr + 1, 0);
+#pragma unroll
+                for (int st = 0; st < NSTEP; ++st) {
+                    const int cur = st & 1;
+                    if (st + 1 < NSTEP) { b0[cur ^ 1] = b_at(pr, st + 1); b1[cur ^ 1] = b_at(pr + 1, st + 1); }
+                    __builtin_amdgcn_sched_barrier(0);
+                    c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b0[cur], c0, 0, 0, 0);
+                    c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b1[cur], c1, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                store_block(pr, c0);
+                store_block(pr + 1, c1);
+            } else {                                // a single live block
+                intx16 c0;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) c0[v] = 0;
+                intx4 b0[2];
+                b0[0] = b_at(pr, 0);
+#pragma unroll
+                for (int st = 0; st < NSTEP; ++st) {
+                    const int cur = st & 1;
+                    if (st + 1 < NSTEP) b0[cur ^ 1] = b_at(pr, st + 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                    c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b0[cur], c0, 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                store_block(pr, c0);
+            }
+        }
+        return;
+    }
+
     const int chunks = C_in / kCK;
     fetch(xv0, wv0, 0);
     if (chunks > 1) fetch(xv1, wv1, kCK);
     __syncthreads();   // window zeroed
     for (int ch = 0; ch < chunks; ch += 2) {
-        stage(xv0, wv0);
+        stage(xv0, wv0, 0);
         if (ch + 2 < chunks) fetch(xv0, wv0, (ch + 2) * kCK);
         multiply();
         if (ch + 1 < chunks) {
-            stage(xv1, wv1);
+            stage(xv1, wv1, 0);
             if (ch + 3 < chunks) fetch(xv1, wv1, (ch + 3) * kCK);
             multiply();
         }
     }
 
     // ---- store: register v of a lane is channel 8*(v/4) + 4*lg + v%4 of the block, pixel lj ---------
-    const int HoWo = Ho * Wo;
     if (P.wide_store) {
         // Full-width tiles: the tile of one channel is one contiguous run of y.  The accumulators go
         // through LDS ([channel][pixel]; the operands are dead by now) and leave as 16-byte stores.
@@ -349,9 +432,12 @@ hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Co
     // the vectorised staging reads 4-byte groups of x and 16-byte groups of w
     if (reinterpret_cast<uintptr_t>(x) % 4 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0)
         return launch_direct_conv2d_s8(x, w, y, s, st);
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<0>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
     if (attr != hipSuccess) return attr;
+    static const hipError_t attr_res = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<128>),
+                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesRes);
+    if (attr_res != hipSuccess) return attr_res;
     const Tiling t = pick_tiling(s);
     S8Params P;
     P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
@@ -359,14 +445,17 @@ hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Co
     P.nq_max = (t.TW + 2 + 2) / 4 + 1;
     // 16-byte stores need full-width tiles whose runs of y start and end on 16-byte boundaries
     P.wide_store = t.tiles_x == 1 && s.Wo % 4 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0 &&
-                   64 * (t.TH * t.TW + 4) * 4 <= kLdsBytes;
+                   64 * (t.TH * t.TW + 4) * 4 <= kLdsBytes;   // (chunked variant only)
     P.by_tiles_x = make_fastdiv(t.tiles_x);
     P.by_TW = make_fastdiv(t.TW);
     P.by_IH = make_fastdiv(t.TH + 2);
     P.by_nq_max = make_fastdiv(P.nq_max);
     P.by_pieces = make_fastdiv(t.TH * s.Wo / 4 > 0 ? t.TH * s.Wo / 4 : 1);
     dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)s.N, (unsigned)(s.C_out / 64));
-    hipLaunchKernelGGL(mfma_s8_kernel, grid, dim3(256), kLdsBytes, st, x, w, y, P);
+    if (s.C_in == 128 && (t.TH + 2) * (t.TW + 2) <= kLdsPxRes)
+        hipLaunchKernelGGL(mfma_s8_kernel<128>, grid, dim3(256), kLdsBytesRes, st, x, w, y, P);
+    else
+        hipLaunchKernelGGL(mfma_s8_kernel<0>, grid, dim3(256), kLdsBytes, st, x, w, y, P);
     return hipGetLastError();
 }
 

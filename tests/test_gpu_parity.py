@@ -232,6 +232,9 @@ S8_CASES = [
     (1, 64, 64, 9, 100, 3, 3, 1, 1),     # two column tiles
     (2, 64, 64, 56, 56, 3, 3, 1, 1),
     (1, 192, 64, 7, 8, 3, 3, 1, 2),      # padding wider than the filter needs
+    (2, 128, 64, 20, 28, 3, 3, 1, 1),    # all of K resident in LDS; last row band ragged
+    (1, 128, 128, 9, 12, 3, 3, 1, 0),    # resident, tile with a single live pixel block pair
+    (1, 128, 64, 5, 40, 3, 3, 1, 1),     # resident, odd block count
     (1, 64, 128, 30, 9, 3, 3, 1, 0),
     (1, 192, 64, 10, 10, 5, 5, 1, 2),
     (1, 64, 64, 15, 15, 3, 3, 2, 1),

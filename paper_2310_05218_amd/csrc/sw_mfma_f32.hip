@@ -41,12 +41,15 @@ struct F32Params {
     FastDiv by_tiles_x, by_TW, by_IW, by_npx;
 };
 
-template <int R, int S>
+// DB: two LDS buffers, the next chunk is copied in while the current one is multiplied.
+template <int R, int S, bool DB>
 __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restrict__ x,
                                                           const float* __restrict__ w,
                                                           float* __restrict__ y, const F32Params P)
 {
     constexpr int RS = R * S;
+    constexpr int kBufBytes = kXBytes + RS * 4 * kWGroupBytes;      // one buffer: input window + weights
+    constexpr int kSumOffset = (DB ? 2 : 1) * kBufBytes;            // 8 KB for the swing block's halves
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     floatx4* lx = reinterpret_cast<floatx4*>(smem);                 // [quad][pixel]
     unsigned char* lw = smem + kXBytes;                             // [tap][quad][co] floatx4, skewed
@@ -114,56 +117,95 @@ __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restric
 
     float xr[kXItems][4];
     floatx4 wr[RS];        // element t*RS + tap of the run <-> (channel t of the quad, tap)
-    auto fetch = [&](int c0) {
+    // A chunk travels global -> registers -> LDS in kXItems parts (one input item and a share of the weight
+    // run each), so that the copies can be spread over the matrix instructions of the previous chunk.
+    constexpr int WP = (RS + kXItems - 1) / kXItems;       // 16-byte weight groups per part
+    auto fetch_part = [&](int c0, int part) {
         const float* xc = xn + (int64_t)c0 * HW;
 #pragma unroll
-        for (int k = 0; k < kXItems; ++k) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) xr[k][t] = goff[k] >= 0 ? xc[goff[k] + t * HW] : 0.f;
-        }
+        for (int t = 0; t < 4; ++t) xr[part][t] = goff[part] >= 0 ? xc[goff[part] + t * HW] : 0.f;
         const floatx4* ws = reinterpret_cast<const floatx4*>(wsrc + (int64_t)c0 * RS);
 #pragma unroll
-        for (int i = 0; i < RS; ++i) wr[i] = ws[i];
+        for (int i = part * WP; i < (part + 1) * WP; ++i)
+            if (i < RS) wr[i] = ws[i];
+    };
+    // registers -> LDS buffer `buf` (input window as it is, weights regrouped per tap: element t*RS + tap of
+    // the run is channel t of the quad at that tap)
+    auto stage_part = [&](int buf, int part) {
+        if (loff[part] >= 0)
+            lx[buf * (kBufBytes / 16) + loff[part]] = floatx4{xr[part][0], xr[part][1], xr[part][2], xr[part][3]};
+#pragma unroll
+        for (int tap = part * WP; tap < (part + 1) * WP; ++tap) {
+            if (tap < RS)
+                *reinterpret_cast<floatx4*>(wdst + buf * kBufBytes + tap * 4 * kWGroupBytes) =
+                    floatx4{wr[tap / 4][tap % 4], wr[(RS + tap) / 4][(RS + tap) % 4],
+                            wr[(2 * RS + tap) / 4][(2 * RS + tap) % 4], wr[(3 * RS + tap) / 4][(3 * RS + tap) % 4]};
+        }
     };
 
-    // operands of one (tap, octet) step: A for four K steps, B for the six whole blocks and the swing block
-    auto load_step = [&](int step, floatx4& a, floatx4 (&b)[kNFix + 1]) {
+    // operands of one (tap, octet) step from the LDS buffer at byte offset bofs: A for four K steps,
+    // B for the six whole blocks and the swing block
+    auto load_step = [&](int step, int bofs, floatx4& a, floatx4 (&b)[kNFix + 1]) {
         const int tap = step >> 1, o = step & 1;
         const int r = tap / S, q = tap - S * r;
-        a = *reinterpret_cast<const floatx4*>(aptr + (tap * 4 + 2 * o) * kWGroupBytes);
-        const int toff = 2 * o * kLdsPx + r * IW + q;
+        a = *reinterpret_cast<const floatx4*>(aptr + bofs + (tap * 4 + 2 * o) * kWGroupBytes);
+        const int toff = (bofs >> 4) + 2 * o * kLdsPx + r * IW + q;
 #pragma unroll
         for (int i = 0; i <= kNFix; ++i) b[i] = lx[boff[i] + toff];
     };
+    auto load_swing = [&](int step, int bofs, floatx4& a, floatx4& b) {
+        const int tap = step >> 1, o = step & 1;
+        const int r = tap / S, q = tap - S * r;
+        a = *reinterpret_cast<const floatx4*>(aptr + bofs + (tap * 4 + 2 * o) * kWGroupBytes);
+        b = lx[boff[kNFix] + (bofs >> 4) + 2 * o * kLdsPx + r * IW + q];
+    };
+    auto load_pair = [&](int step, int pr, int bofs, floatx4& a, floatx4& b0, floatx4& b1) {
+        const int tap = step >> 1, o = step & 1;
+        const int r = tap / S, q = tap - S * r;
+        a = *reinterpret_cast<const floatx4*>(aptr + bofs + (tap * 4 + 2 * o) * kWGroupBytes);
+        const int toff = (bofs >> 4) + 2 * o * kLdsPx + r * IW + q;
+        b0 = lx[boff[pr] + toff];
+        b1 = lx[boff[pr + 1] + toff];
+    };
 
-    fetch(0);
-    const int chunks = C_in / kCK;
-    for (int ch = 0; ch < chunks; ++ch) {
+    const int HoWo = Ho * Wo;
+    float* yn = y + ((int64_t)n * C_out + (mb << 6) + 32 * wm + 4 * lg) * HoWo;
+    auto store_block = [&](int nb, const floatx16& c) {
+        const int p = nb * 32 + lj;
+        const int pi = fast_div(p, P.by_TW), pj = p - pi * TW;
+        const int oi = row0 + pi, oj = col0 + pj;
+        if (p < tile_px && oi < Ho && oj < Wo) {
+            float* dst = yn + oi * Wo + oj;
 #pragma unroll
-        for (int k = 0; k < kXItems; ++k)
-            if (loff[k] >= 0) lx[loff[k]] = floatx4{xr[k][0], xr[k][1], xr[k][2], xr[k][3]};
-        {
-            float f[4 * RS];
-#pragma unroll
-            for (int i = 0; i < RS; ++i) {
-                f[4 * i + 0] = wr[i].x; f[4 * i + 1] = wr[i].y; f[4 * i + 2] = wr[i].z; f[4 * i + 3] = wr[i].w;
-            }
-#pragma unroll
-            for (int tap = 0; tap < RS; ++tap)
-                *reinterpret_cast<floatx4*>(wdst + tap * 4 * kWGroupBytes) =
-                    floatx4{f[tap], f[RS + tap], f[2 * RS + tap], f[3 * RS + tap]};
+            for (int v = 0; v < 16; ++v) dst[(8 * (v >> 2) + (v & 3)) * HoWo] = c[v];
         }
-        __syncthreads();
-        if (ch + 1 < chunks) fetch((ch + 1) * kCK);
+    };
 
+    constexpr int NSTEP = 2 * RS;
+    // steps FETCH_AT .. +kXItems-1 issue the next chunk's global loads, one part each; with two LDS buffers
+    // steps STAGE_AT .. +kXItems-1 copy them into the other buffer
+    constexpr int FETCH_AT = 0;
+    constexpr int STAGE_AT = NSTEP - kXItems;
+    static_assert(STAGE_AT >= FETCH_AT + kXItems || !DB, "a part must be fetched before it is staged");
+    const int chunks = C_in / kCK;
+#pragma unroll
+    for (int part = 0; part < kXItems; ++part) fetch_part(0, part);
+#pragma unroll
+    for (int part = 0; part < kXItems; ++part) stage_part(0, part);
+    __syncthreads();
+    for (int ch = 0; ch + 1 < chunks; ++ch) {
+        const int buf = DB ? (ch & 1) : 0;
+        const int bofs = buf * kBufBytes;
         floatx4 a[2];
         floatx4 b[2][kNFix + 1];
-        load_step(0, a[0], b[0]);
+        load_step(0, bofs, a[0], b[0]);
 #pragma unroll
-        for (int step = 0; step < 2 * RS; ++step) {
+        for (int step = 0; step < NSTEP; ++step) {
             const int cur = step & 1;
-            if (step + 1 < 2 * RS) load_step(step + 1, a[cur ^ 1], b[cur ^ 1]);
-            __builtin_amdgcn_sched_barrier(0);      // keep the reads ahead of the matrix instructions
+            if (step + 1 < NSTEP) load_step(step + 1, bofs, a[cur ^ 1], b[cur ^ 1]);
+            if (step >= FETCH_AT && step < FETCH_AT + kXItems) fetch_part((ch + 1) * kCK, step - FETCH_AT);
+            if (DB && step >= STAGE_AT) stage_part(buf ^ 1, step - STAGE_AT);
+            __builtin_amdgcn_sched_barrier(0);      // keep reads and copies ahead of the matrix instructions
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
 #pragma unroll
@@ -175,35 +217,61 @@ __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restric
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
+        if (!DB) {
+#pragma unroll
+            for (int part = 0; part < kXItems; ++part) stage_part(0, part);
+            __syncthreads();
+        }
     }
 
-    // ---- the two octet halves of the swing block meet in LDS -------------------------------------------
-    float* lsum = reinterpret_cast<float*>(smem);
-    if (wn == 1) {
+    // ---- last chunk: block by block, so that finished blocks are stored while the next ones multiply ----
+    {
+        const int bofs = (DB ? ((chunks - 1) & 1) : 0) * kBufBytes;
+        // swing block first: this wavefront's octet, then the two octet halves meet in LDS
+        {
+            floatx4 a[2], bs[2];
+            load_swing(wn, bofs, a[0], bs[0]);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) lsum[(wm * 16 + v) * 64 + lane] = acc[kNFix][v];
-    }
-    __syncthreads();
-    if (wn == 0) {
+            for (int tap = 0; tap < RS; ++tap) {
+                const int cur = tap & 1;
+                if (tap + 1 < RS) load_swing(2 * (tap + 1) + wn, bofs, a[cur ^ 1], bs[cur ^ 1]);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) acc[kNFix][v] += lsum[(wm * 16 + v) * 64 + lane];
-    }
-
-    // ---- store: register v of a lane is channel 8*(v/4) + 4*lg + v%4 of the block, pixel lj ---------------
-    const int HoWo = Ho * Wo;
-    float* yn = y + ((int64_t)n * C_out + (mb << 6) + 32 * wm + 4 * lg) * HoWo;
+                for (int t = 0; t < 4; ++t)
+                    acc[kNFix] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][t], bs[cur][t], acc[kNFix], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        float* lsum = reinterpret_cast<float*>(smem + kSumOffset);
+        if (wn == 1) {
 #pragma unroll
-    for (int i = 0; i <= kNFix; ++i) {
-        if (i == kNFix && wn != 0) break;
-        const int nb = i < kNFix ? wn * kNFix + i : kSwing;
-        const int p = nb * 32 + lj;
-        const int pi = fast_div(p, P.by_TW), pj = p - pi * TW;
-        const int oi = row0 + pi, oj = col0 + pj;
-        if (p < tile_px && oi < Ho && oj < Wo) {
-            float* dst = yn + oi * Wo + oj;
+            for (int v = 0; v < 16; ++v) lsum[(wm * 16 + v) * 64 + lane] = acc[kNFix][v];
+        }
+        __syncthreads();
+        if (wn == 0) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v)
-                dst[(8 * (v >> 2) + (v & 3)) * HoWo] = acc[i][v];
+            for (int v = 0; v < 16; ++v) acc[kNFix][v] += lsum[(wm * 16 + v) * 64 + lane];
+            store_block(kSwing, acc[kNFix]);
+        }
+        // whole blocks in pairs: two independent accumulators alternate
+#pragma unroll
+        for (int pr = 0; pr < kNFix; pr += 2) {
+            floatx4 a[2], b0[2], b1[2];
+            load_pair(0, pr, bofs, a[0], b0[0], b1[0]);
+#pragma unroll
+            for (int step = 0; step < NSTEP; ++step) {
+                const int cur = step & 1;
+                if (step + 1 < NSTEP) load_pair(step + 1, pr, bofs, a[cur ^ 1], b0[cur ^ 1], b1[cur ^ 1]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    acc[pr] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][t], b0[cur][t], acc[pr], 0, 0, 0);
+                    acc[pr + 1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][t], b1[cur][t], acc[pr + 1], 0, 0, 0);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            store_block(wn * kNFix + pr, acc[pr]);
+            store_block(wn * kNFix + pr + 1, acc[pr + 1]);
         }
     }
 }
@@ -227,13 +295,17 @@ Tiling pick_tiling(const Conv2dShape& s)
     return t;
 }
 
-int lds_bytes(int RS) { return kXBytes + RS * 4 * kWGroupBytes; }
+constexpr int kLdsMax = 160 * 1024;
+constexpr int kSumBytes = 2 * 16 * 64 * 4;
+constexpr int buf_bytes(int RS) { return kXBytes + RS * 4 * kWGroupBytes; }
 
 template <int R, int S>
 hipError_t launch(const float* x, const float* w, float* y, const Conv2dShape& s, const Tiling& t, hipStream_t st)
 {
-    const int bytes = lds_bytes(R * S);
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_f32_kernel<R, S>),
+    constexpr bool DB = 2 * buf_bytes(R * S) + kSumBytes <= kLdsMax;
+    constexpr int bytes = (DB ? 2 : 1) * buf_bytes(R * S) + kSumBytes;
+    static_assert(bytes <= kLdsMax, "LDS budget");
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_f32_kernel<R, S, DB>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (attr != hipSuccess) return attr;
     F32Params P;
@@ -244,7 +316,7 @@ hipError_t launch(const float* x, const float* w, float* y, const Conv2dShape& s
     P.by_IW = make_fastdiv(t.TW + S - 1);
     P.by_npx = make_fastdiv((t.TH + R - 1) * (t.TW + S - 1));
     dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)s.N, (unsigned)(s.C_out / 64));
-    hipLaunchKernelGGL((mfma_f32_kernel<R, S>), grid, dim3(256), bytes, st, x, w, y, P);
+    hipLaunchKernelGGL((mfma_f32_kernel<R, S, DB>), grid, dim3(256), bytes, st, x, w, y, P);
     return hipGetLastError();
 }
 

@@ -146,6 +146,39 @@ def time_kernel(torch, fn, sets, reps, batches=5):
     return out[len(out) // 2]
 
 
+def filter_size_sweep(torch, sw):
+    """Throughput against filter size on one plane-per-filter workload (N=32, C=64, 56x56, stride 1, 'same'
+    padding, fp32 N(0,1), weights N(0, 1/k^2)): sizes 3, 5, 7 run the fixed-size kernels, up to 17 the first
+    generic kernel, beyond that the wide-window generic kernel.  Each size is first checked against the CPU
+    oracle on two planes."""
+    import numpy as np
+
+    import oracle
+    from paper_2310_05218_amd import inputs
+
+    N, C, H = 32, 64, 56
+    x = inputs.normal_f32((N, C, H, H), inputs.seed_for(6, 0))
+    sets = [{"x": torch.from_numpy(x).cuda(), "y": torch.empty((N, C, H, H), device="cuda")} for _ in range(4)]
+    rows = []
+    for k in (3, 5, 7, 9, 11, 13, 15, 17, 21, 25, 29, 33, 37, 45, 51):
+        w = inputs.normal_f32((C, 1, k, k), inputs.seed_for(6, k), 1.0 / k)
+        wd = torch.from_numpy(w).cuda()
+        pad = (k - 1) // 2
+        y = sw.sw_conv2d_depthwise(sets[0]["x"][:1, :2].contiguous(), wd[:2].contiguous(), 1, pad).cpu().numpy()
+        y_ref, d = oracle.conv2d_depthwise(x[:1, :2], w[:2], 1, pad)
+        err = float(np.max(np.abs(y - y_ref) / d))
+        assert err <= 2e-5, (k, err)
+        us = time_kernel(torch, lambda s_: sw.sw_conv2d_depthwise(s_["x"], wd, 1, pad, out=s_["y"]), sets,
+                         50 if k < 20 else 10)
+        flop = 2.0 * k * k * N * C * H * H
+        nbytes = 2 * N * C * H * H * 4 + C * k * k * 4
+        rows.append({"filter": k, "us": round(us, 2), "gflops": round(flop / us / 1e3, 1),
+                     "gbs": round(nbytes / us / 1e3, 1), "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4),
+                     "frac_alu_f32_plain_fma": round(flop / us / 1e6 / VALU_F32_TFLOPS, 4),
+                     "max_norm_err": float("%.2e" % err)})
+    return {"sweep": "depthwise-shaped 32x64x56x56 fp32, square filter, stride 1, same padding", "rows": rows}
+
+
 def cpu_baseline(host, total_ops):
     import oracle
 
@@ -178,6 +211,9 @@ def main():
     ap.add_argument("--sets", type=int, default=3, help="buffer sets rotated over (cold-cache timing)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-detail", action="store_true", help="skip the per-kernel hot/cold table")
+    ap.add_argument("--sweep", action="store_true",
+                    help="filter-size sweep (the paper's experiment axis, section 2): depthwise-shaped "
+                         "32x64x56x56 fp32, square filters 3..51, 'same' padding; prints one JSON line")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for counter runs under rocprofv3 --pmc: one 64 MiB device copy (calibration), then "
                          "every kernel of the step twice; prints nothing but a marker line")
@@ -193,6 +229,10 @@ def main():
     binding.lib()     # raises if libswconv.so has not been built: there is no fallback
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+
+    if args.sweep:
+        print(json.dumps(filter_size_sweep(torch, sw)))
+        return
 
     work = work_table()
     host, sets = make_sets(torch, args.sets)

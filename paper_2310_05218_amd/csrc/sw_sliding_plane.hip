@@ -25,10 +25,11 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kB = 7;            // outputs per lane per axis
 constexpr int kTile = 8 * kB;    // 56 outputs per tile per axis
-constexpr int kMaxRS = 17;       // largest filter extent this kernel takes
+constexpr int kMaxRS = 17;       // largest filter extent of the first generic kernel
+constexpr int kMaxRSWide = 51;   // largest filter extent of the second one (a wider LDS window)
 constexpr int kOutPitch = kTile;
 
-constexpr int in_pitch(int S) { return (3 + kTile + S - 1) <= 72 ? 72 : 104; }
+constexpr int in_pitch(int S) { return (3 + kTile + S - 1) <= 72 ? 72 : (3 + kTile + S - 1) <= 104 ? 104 : 136; }
 constexpr int in_rows(int R) { return kTile + R - 1; }
 
 
@@ -67,8 +68,35 @@ __device__ __forceinline__ void accumulate_block(const float* __restrict__ win, 
     }
 }
 
-// RC, SC > 0: filter extent known at compile time.  RC == 0: extent (R, S) at run time, up to kMaxRS.
-template <int RC, int SC>
+// One step of the run-time-extent kernel: input row ir of the lane's window, tap columns s0 .. s0+NT-1.
+// ALL: every output row 0..6 meets this input row (0 <= ir - orow < R for all of them).
+template <int NT, bool ALL>
+__device__ __forceinline__ void generic_step(const float* __restrict__ src, const float* __restrict__ wf, int R,
+                                             int S, int ir, int s0, float (&acc)[kB][kB])
+{
+    // taps first, as one batch of scalar loads (row index clamped into the filter where a guard follows)
+    float wv[kB][NT];
+#pragma unroll
+    for (int orow = 0; orow < kB; ++orow) {
+        const int rc = ALL ? ir - orow : min(max(ir - orow, 0), R - 1);
+#pragma unroll
+        for (int jj = 0; jj < NT; ++jj) wv[orow][jj] = wf[rc * S + s0 + jj];
+    }
+    float in[kB + NT - 1];
+#pragma unroll
+    for (int c = 0; c < kB + NT - 1; ++c) in[c] = src[c];
+#pragma unroll
+    for (int orow = 0; orow < kB; ++orow) {
+        if (!ALL && (ir - orow < 0 || ir - orow >= R)) continue;
+#pragma unroll
+        for (int jj = 0; jj < NT; ++jj)
+#pragma unroll
+            for (int oc = 0; oc < kB; ++oc) acc[orow][oc] = fmaf(wv[orow][jj], in[oc + jj], acc[orow][oc]);
+    }
+}
+
+// RC, SC > 0: filter extent known at compile time.  RC == 0: extent (R, S) at run time, up to MAXRS.
+template <int RC, int SC, int MAXRS>
 __global__ __launch_bounds__(64) void sliding_plane_kernel(const float* __restrict__ x,
                                                            const float* __restrict__ w,
                                                            float* __restrict__ y, int planes_per_x,
@@ -77,8 +105,8 @@ __global__ __launch_bounds__(64) void sliding_plane_kernel(const float* __restri
                                                            int tiles_x, int tiles_y, int x_vec_ok,
                                                            int y_vec_ok)
 {
-    constexpr int RMAX = RC > 0 ? RC : kMaxRS;
-    constexpr int SMAX = RC > 0 ? SC : kMaxRS;
+    constexpr int RMAX = RC > 0 ? RC : MAXRS;
+    constexpr int SMAX = RC > 0 ? SC : MAXRS;
     constexpr int P = in_pitch(SMAX);
     constexpr int F4_PER_ROW = (3 + kTile + SMAX - 1 + 3) / 4;   // 16-byte groups loaded per row
     static_assert(F4_PER_ROW * 4 <= P, "pitch too small");
@@ -137,15 +165,23 @@ __global__ __launch_bounds__(64) void sliding_plane_kernel(const float* __restri
     if (RC > 0) {
         accumulate_block<RMAX, SMAX, P>(win, wf, acc);
     } else {
-        for (int r = 0; r < R; ++r) {
-            for (int s = 0; s < S; ++s) {
-                const float wv = wf[r * S + s];
-                const float* src = win + r * P + s;
-#pragma unroll
-                for (int orow = 0; orow < kB; ++orow)
-#pragma unroll
-                    for (int oc = 0; oc < kB; ++oc)
-                        acc[orow][oc] = fmaf(wv, src[orow * P + oc], acc[orow][oc]);
+        // Run-time extents: the same sliding order in pieces.  For every input row of the lane's window
+        // and every group of four tap columns, ten floats are read once and slid (register rename) under
+        // the taps of each filter row that the input row meets.  Input rows 6 .. R-1 meet all seven
+        // output rows and run without a test; the first and last six rows take the guarded form.
+        const int full = S & ~3, rem = S & 3;
+        for (int ir = 0; ir < kB + R - 1; ++ir) {
+            const float* row = win + ir * P;
+            if (ir >= kB - 1 && ir < R) {
+                for (int s0 = 0; s0 < full; s0 += 4) generic_step<4, true>(row + s0, wf, R, S, ir, s0, acc);
+                if (rem == 1) generic_step<1, true>(row + full, wf, R, S, ir, full, acc);
+                if (rem == 2) generic_step<2, true>(row + full, wf, R, S, ir, full, acc);
+                if (rem == 3) generic_step<3, true>(row + full, wf, R, S, ir, full, acc);
+            } else {
+                for (int s0 = 0; s0 < full; s0 += 4) generic_step<4, false>(row + s0, wf, R, S, ir, s0, acc);
+                if (rem == 1) generic_step<1, false>(row + full, wf, R, S, ir, full, acc);
+                if (rem == 2) generic_step<2, false>(row + full, wf, R, S, ir, full, acc);
+                if (rem == 3) generic_step<3, false>(row + full, wf, R, S, ir, full, acc);
             }
         }
     }
@@ -283,7 +319,7 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
 bool sliding_plane_supported(int H, int W, int R, int S, int stride, int pad)
 {
     (void)H; (void)W;
-    return stride == 1 && R <= kMaxRS && S <= kMaxRS && pad >= 0 && pad <= 2 * kMaxRS;
+    return stride == 1 && R <= kMaxRSWide && S <= kMaxRSWide && pad >= 0;
 }
 
 hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x,
@@ -319,13 +355,14 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
     const int x_vec_ok = reinterpret_cast<uintptr_t>(x) % 16 == 0 && W % 4 == 0;
     const int y_vec_ok = reinterpret_cast<uintptr_t>(y) % 16 == 0 && Wo % 4 == 0;
     dim3 grid((unsigned)blocks), block(64);
-#define SW_PLANE(RC, SC)                                                                                  \
-    hipLaunchKernelGGL((sliding_plane_kernel<RC, SC>), grid, block, 0, st, x, w, y, planes_per_x, n_filters, \
-                       H, W, R, S, pad, Ho, Wo, tiles_x, tiles_y, x_vec_ok, y_vec_ok)
-    if (R == 3 && S == 3) SW_PLANE(3, 3);
-    else if (R == 5 && S == 5) SW_PLANE(5, 5);
-    else if (R == 7 && S == 7) SW_PLANE(7, 7);
-    else SW_PLANE(0, 0);
+#define SW_PLANE(RC, SC, MAXRS)                                                                          \
+    hipLaunchKernelGGL((sliding_plane_kernel<RC, SC, MAXRS>), grid, block, 0, st, x, w, y, planes_per_x,      \
+                       n_filters, H, W, R, S, pad, Ho, Wo, tiles_x, tiles_y, x_vec_ok, y_vec_ok)
+    if (R == 3 && S == 3) SW_PLANE(3, 3, 0);
+    else if (R == 5 && S == 5) SW_PLANE(5, 5, 0);
+    else if (R == 7 && S == 7) SW_PLANE(7, 7, 0);
+    else if (R <= kMaxRS && S <= kMaxRS) SW_PLANE(0, 0, kMaxRS);
+    else SW_PLANE(0, 0, kMaxRSWide);
 #undef SW_PLANE
     return hipGetLastError();
 }

@@ -122,6 +122,10 @@ PLANE_CASES = [
     (1, 3, 20, 21, 2, 6, 1, 1),     # filter extent without a fixed-size kernel
     (1, 2, 40, 40, 9, 9, 1, 4),
     (1, 2, 30, 30, 17, 17, 1, 8),
+    (1, 2, 60, 61, 21, 21, 1, 10),  # beyond 17: the wide-window generic kernel
+    (1, 1, 70, 64, 33, 29, 1, 14),
+    (1, 1, 56, 56, 51, 51, 1, 25),
+    (1, 2, 64, 64, 13, 4, 1, 0),
     (1, 3, 21, 23, 3, 3, 2, 1),     # strided: direct kernel
     (1, 2, 7, 5, 7, 5, 1, 0),
     (1, 2, 16, 16, 3, 3, 1, 2),     # padding wider than the usual (R-1)/2

@@ -322,6 +322,15 @@ bool sliding_plane_supported(int H, int W, int R, int S, int stride, int pad)
     return stride == 1 && R <= kMaxRSWide && S <= kMaxRSWide && pad >= 0;
 }
 
+// Launch-latency regime: with fewer than 64 tiles (a quarter of the CUs) and a small filter the whole
+// problem is a few hundred KB, nothing is bandwidth- or ALU-bound, and one wavefront walking through a
+// 56 x 56 tile takes longer (8.3 us at 1x1x256x256, 3x3) than one thread per output (3.0 us).
+bool sliding_plane_worthwhile(int64_t planes, int Ho, int Wo, int R, int S)
+{
+    const int64_t tiles = planes * ((Ho + kTile - 1) / kTile) * ((Wo + kTile - 1) / kTile);
+    return tiles >= 64 || R * S > 25;
+}
+
 hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x,
                                 int n_filters, int H, int W, int R, int S, int pad, int Ho, int Wo,
                                 hipStream_t st)

@@ -128,7 +128,8 @@ int sw_conv2d(const float* x, const float* w, float* y, int N, int C_in, int C_o
     if (rc != SW_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (!force_direct()) {
-        if (C_in == 1 && sliding_plane_supported(H, W, R, S, stride, pad))
+        if (C_in == 1 && sliding_plane_supported(H, W, R, S, stride, pad) &&
+            sliding_plane_worthwhile((int64_t)N * C_out, s.Ho, s.Wo, R, S))
             return launch_status(launch_sliding_plane(x, w, y, (int64_t)N * C_out, C_out, C_out, H, W, R, S,
                                                       pad, s.Ho, s.Wo, st));
         if (mfma_f32_supported(s)) return launch_status(launch_mfma_f32(x, w, y, s, st));
@@ -143,7 +144,8 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, 
     const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s);
     if (rc != SW_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (!force_direct() && sliding_plane_supported(H, W, R, S, stride, pad))
+    if (!force_direct() && sliding_plane_supported(H, W, R, S, stride, pad) &&
+        sliding_plane_worthwhile((int64_t)N * C, s.Ho, s.Wo, R, S))
         return launch_status(
             launch_sliding_plane(x, w, y, (int64_t)N * C, 1, C, H, W, R, S, pad, s.Ho, s.Wo, st));
     return launch_status(launch_direct_conv2d_f32(x, w, y, s, true, st));

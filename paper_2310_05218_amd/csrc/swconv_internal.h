@@ -41,6 +41,7 @@ hipError_t launch_sliding_1d(const float* x, const float* w, float* y, int64_t r
 // x plane index for output plane p is p / planes_per_x (conv2d with C_in == 1: C_out filters share
 // one input plane; depthwise: 1); filter index is p % n_filters.
 bool       sliding_plane_supported(int H, int W, int R, int S, int stride, int pad);
+bool       sliding_plane_worthwhile(int64_t planes, int Ho, int Wo, int R, int S);
 hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes,
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st);

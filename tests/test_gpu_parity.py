@@ -132,9 +132,20 @@ PLANE_CASES = [
 ]
 
 
+def _enough_planes_for_the_sliding_kernel(N, C, H, W, R, S, stride, pad):
+    """The library sends problems of fewer than 64 tiles with small filters to the one-thread-per-output
+    kernel (launch-latency regime).  Returns a batch size that keeps the case on the sliding kernel."""
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - S) // stride + 1
+    tiles = -(-Ho // 56) * -(-Wo // 56)
+    return N * -(-64 // (N * C * tiles))
+
+
+@pytest.mark.parametrize("batch", ["as given", "sliding-kernel batch"])
 @pytest.mark.parametrize("case", PLANE_CASES)
-def test_depthwise(torch, sw, oracle, case):
+def test_depthwise(torch, sw, oracle, case, batch):
     N, C, H, W, R, S, stride, pad = case
+    if batch != "as given":
+        N = _enough_planes_for_the_sliding_kernel(*case)
     x = inputs.normal_f32((N, C, H, W), 2001)
     w = inputs.normal_f32((C, 1, R, S), 2002)
     y_ref, d = oracle.conv2d_depthwise(x, w, stride, pad)
@@ -145,9 +156,12 @@ def test_depthwise(torch, sw, oracle, case):
     assert_f32_parity(out.cpu().numpy(), y_ref, d, f"depthwise {case}")
 
 
+@pytest.mark.parametrize("batch", ["as given", "sliding-kernel batch"])
 @pytest.mark.parametrize("case", PLANE_CASES)
-def test_conv2d_single_input_channel(torch, sw, oracle, case):
+def test_conv2d_single_input_channel(torch, sw, oracle, case, batch):
     N, C_out, H, W, R, S, stride, pad = case
+    if batch != "as given":
+        N = _enough_planes_for_the_sliding_kernel(*case)
     x = inputs.normal_f32((N, 1, H, W), 2011)
     w = inputs.normal_f32((C_out, 1, R, S), 2012)
     y_ref, d = oracle.conv2d(x, w, stride, pad)
@@ -164,14 +178,14 @@ def test_workload1_full_size(torch, sw, oracle):
 
 
 def test_impulse_reproduces_filter_on_gpu(torch, sw):
-    x = np.zeros((1, 1, 40, 40), np.float32)
-    x[0, 0, 20, 21] = 1.0
-    w = inputs.uniform_f32((1, 1, 7, 7), 2021)
+    x = np.zeros((1, 64, 40, 40), np.float32)      # 64 planes: runs on the sliding kernel
+    x[0, :, 20, 21] = 1.0
+    w = inputs.uniform_f32((64, 1, 7, 7), 2021)
     y = sw.sw_conv2d_depthwise(dev(torch, x), dev(torch, w), 1, 3).cpu().numpy()
     expect = np.zeros_like(y)
     for r in range(7):
         for s in range(7):
-            expect[0, 0, 20 - r + 3, 21 - s + 3] = w[0, 0, r, s]
+            expect[0, :, 20 - r + 3, 21 - s + 3] = w[:, 0, r, s]
     assert np.array_equal(y, expect)
 
 

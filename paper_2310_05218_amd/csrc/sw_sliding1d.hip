@@ -7,8 +7,9 @@
 // that is the padding).  Each lane then owns four consecutive outputs.  It keeps an 8-float window
 // of the input in registers; the four taps j..j+3 are accumulated against the window shifted by
 // 0..3 elements (a register rename, no data movement), then the window slides on by four elements
-// with one 16-byte LDS read.  Outputs leave through 16-byte stores: directly when every output row is
-// 16-byte aligned, otherwise through LDS, re-grouped so that each store is aligned in memory.
+// with one 16-byte LDS read.  Outputs leave as 16-byte stores that are aligned in memory whatever the row
+// length: the groups of four are laid out from the row's own alignment, and that offset, like the padding,
+// becomes a compile-time register offset inside the window (so LDS reads stay aligned 16-byte reads too).
 #include "swconv_internal.h"
 
 namespace swconv {
@@ -26,7 +27,7 @@ constexpr int kSub = kThreads * 4;      // outputs per pass over the workgroup
 constexpr int kPasses = 2;
 constexpr int kTile = kSub * kPasses;   // outputs per workgroup
 constexpr int kMaxK = 64;
-constexpr int kLdsIn = kTile + kMaxK + 8;  // tile + halo + alignment shift, multiple of 4
+constexpr int kLdsIn = kTile + kMaxK + 16;  // tile + halo + alignment offset + read-ahead, multiple of 4
 
 template <int OP>
 __device__ __forceinline__ float accumulate(float acc, float wj, float xv)
@@ -36,6 +37,76 @@ __device__ __forceinline__ float accumulate(float acc, float wj, float xv)
     return fmaxf(acc, xv);
 }
 
+// The lane's four outputs from LDS.  src is 16-byte aligned; the first input the lane needs sits SH
+// floats further on (SH = 0..3 folds the padding and the misalignment of the output row into a register
+// offset, so every LDS read stays an aligned 16-byte read).  buf holds 8 or 12 consecutive floats; taps
+// j..j+3 are accumulated against buf[SH + p + jj], then buf slides on by four with one more read.
+template <int OP, int KC, int SH>
+__device__ __forceinline__ void slide4(const float* __restrict__ src, const float* __restrict__ w, int k,
+                                       float (&acc)[4])
+{
+    constexpr int N = SH <= 1 ? 8 : 12;      // SH + 3 + 3 is the largest index a group of four taps touches
+    float buf[N];
+#pragma unroll
+    for (int c = 0; c < N / 4; ++c) {
+        const floatx4 v = *reinterpret_cast<const floatx4*>(src + 4 * c);
+        buf[4 * c + 0] = v.x; buf[4 * c + 1] = v.y; buf[4 * c + 2] = v.z; buf[4 * c + 3] = v.w;
+    }
+    int j = 0;
+#pragma unroll
+    for (; j + 4 <= k; j += 4) {
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+            const float wj = (OP == OP_CONV) ? w[j + jj] : 0.f;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) acc[p] = accumulate<OP>(acc[p], wj, buf[SH + p + jj]);
+        }
+#pragma unroll
+        for (int e = 0; e < N - 4; ++e) buf[e] = buf[e + 4];
+        if (j + 4 < k) {
+            const floatx4 v = *reinterpret_cast<const floatx4*>(src + j + N);
+            buf[N - 4] = v.x; buf[N - 3] = v.y; buf[N - 2] = v.z; buf[N - 1] = v.w;
+        }
+    }
+#pragma unroll
+    for (int jj = 0; jj < 3; ++jj) {
+        if (j + jj < k) {
+            const float wj = (OP == OP_CONV) ? w[j + jj] : 0.f;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) acc[p] = accumulate<OP>(acc[p], wj, buf[SH + p + jj]);
+        }
+    }
+}
+
+// Both passes of a lane over the staged tile, for one register offset SH.
+template <int OP, int KC, int SH>
+__device__ __forceinline__ void tile_outputs(const float* __restrict__ s_in, const float* __restrict__ w, int k,
+                                             float* __restrict__ yrow, int o0, int o_end, int tid)
+{
+    const float inv_k = 1.0f / (float)k;
+#pragma unroll
+    for (int pass = 0; pass < kPasses; ++pass) {
+        const int q = pass * kSub + 4 * tid;           // first of this lane's four outputs, tile-relative
+        const int o = o0 + q;                          // ... and row-relative (may be < 0 in the first tile)
+        if (o + 3 < 0 || o >= o_end) continue;
+        float acc[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) acc[p] = (OP == OP_MAX) ? -__builtin_inff() : 0.f;
+        slide4<OP, KC, SH>(s_in + q, w, k, acc);
+        if (OP == OP_AVG) {
+#pragma unroll
+            for (int p = 0; p < 4; ++p) acc[p] *= inv_k;
+        }
+        if (o >= 0 && o + 3 < o_end) {
+            stream_store4(yrow + o, floatx4{acc[0], acc[1], acc[2], acc[3]});
+        } else {
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+                if (o + p >= 0 && o + p < o_end) yrow[o + p] = acc[p];
+        }
+    }
+}
+
 // KC > 0: tap count known at compile time (fully unrolled, taps in scalar registers).
 // KC == 0: tap count k at run time.
 template <int OP, int KC>
@@ -43,27 +114,29 @@ __global__ __launch_bounds__(kThreads) void sliding_1d_kernel(const float* __res
                                                               const float* __restrict__ w,
                                                               float* __restrict__ y, int len,
                                                               int len_out, int k_rt, int pad,
-                                                              int tiles_per_row, int x_vec_ok,
-                                                              int y_vec_ok)
+                                                              int tiles_per_row, int x_vec_ok)
 {
     __shared__ __attribute__((aligned(16))) float s_in[kLdsIn];
-    __shared__ __attribute__((aligned(16))) float s_out[kTile];
 
     const int k = KC > 0 ? KC : k_rt;
     const int tid = threadIdx.x;
     const int row = blockIdx.x / tiles_per_row;
     const int tile = blockIdx.x - row * tiles_per_row;
-    const int o0 = tile * kTile;                       // first output of this tile
-    const int n_out = min(kTile, len_out - o0);
     const float* xr = x + (int64_t)row * len;
-    float* yr = y + (int64_t)row * len_out + o0;
+    float* yrow = y + (int64_t)row * len_out;
 
-    // LDS element e holds input position t0 + e; t0 is a multiple of 4 so that 16-byte global
-    // loads stay aligned whatever the padding is.
-    const int pad_up = (pad + 3) & ~3;
-    const int shift = pad_up - pad;                    // first needed input sits at LDS element shift
-    const int t0 = o0 - pad_up;
-    const int n_in = n_out + k - 1 + shift;            // LDS elements the outputs read
+    // Outputs are grouped so that every group of four starts on a 16-byte boundary in memory: with `a` the
+    // misalignment (in floats) of the row's first output, the tile owns outputs o0 .. o0 + kTile - 1 with
+    // o0 = tile * kTile - a (the first tile of a misaligned row starts before output 0).
+    const int a = (int)((reinterpret_cast<uintptr_t>(yrow) >> 2) & 3);
+    const int o0 = tile * kTile - a;
+    // LDS element e holds input position t0 + e; t0 is a multiple of 4 so that 16-byte global loads stay
+    // aligned.  Output o0 + q reads inputs from position o0 + q - pad, i.e. LDS element q + sh.
+    const int lead = (a + pad + 3) & ~3;
+    const int sh = lead - a - pad;                     // 0..3
+    const int t0 = tile * kTile - lead;
+    const int o_end = min(o0 + kTile, len_out);        // one past the tile's last real output
+    const int n_in = (o_end - o0) + k - 1 + sh;        // LDS elements the outputs read
     const int n_in4 = (n_in + 3) >> 2;
 
     if (x_vec_ok) {
@@ -88,85 +161,11 @@ __global__ __launch_bounds__(kThreads) void sliding_1d_kernel(const float* __res
     }
     __syncthreads();
 
-    const float inv_k = 1.0f / (float)k;
-#pragma unroll
-    for (int pass = 0; pass < kPasses; ++pass) {
-        const int base = pass * kSub + 4 * tid;        // first of this lane's four outputs
-        float acc[4];
-#pragma unroll
-        for (int p = 0; p < 4; ++p) acc[p] = (OP == OP_MAX) ? -__builtin_inff() : 0.f;
-        if (base < n_out) {
-            // window[0..7] = inputs base+j .. base+j+7 (relative to the first needed input)
-            float win[8];
-            const float* src = s_in + shift + base;
-            if (shift == 0) {
-                const float4 a = *reinterpret_cast<const float4*>(src);
-                const float4 b = *reinterpret_cast<const float4*>(src + 4);
-                win[0] = a.x; win[1] = a.y; win[2] = a.z; win[3] = a.w;
-                win[4] = b.x; win[5] = b.y; win[6] = b.z; win[7] = b.w;
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) win[e] = src[e];
-            }
-            int j = 0;
-#pragma unroll
-            for (; j + 4 <= k; j += 4) {
-#pragma unroll
-                for (int jj = 0; jj < 4; ++jj) {
-                    const float wj = (OP == OP_CONV) ? w[j + jj] : 0.f;
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) acc[p] = accumulate<OP>(acc[p], wj, win[p + jj]);
-                }
-                // slide by four
-#pragma unroll
-                for (int e = 0; e < 4; ++e) win[e] = win[e + 4];
-                if (j + 4 < k) {
-                    if (shift == 0) {
-                        const float4 b = *reinterpret_cast<const float4*>(src + j + 8);
-                        win[4] = b.x; win[5] = b.y; win[6] = b.z; win[7] = b.w;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) win[4 + e] = src[j + 8 + e];
-                    }
-                }
-            }
-#pragma unroll
-            for (int jj = 0; jj < 3; ++jj) {
-                if (j + jj < k) {
-                    const float wj = (OP == OP_CONV) ? w[j + jj] : 0.f;
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) acc[p] = accumulate<OP>(acc[p], wj, win[p + jj]);
-                }
-            }
-            if (OP == OP_AVG) {
-#pragma unroll
-                for (int p = 0; p < 4; ++p) acc[p] *= inv_k;
-            }
-            if (y_vec_ok) {
-                if (base + 3 < n_out) {
-                    stream_store4(yr + base, floatx4{acc[0], acc[1], acc[2], acc[3]});
-                } else {
-#pragma unroll
-                    for (int p = 0; p < 4; ++p)
-                        if (base + p < n_out) yr[base + p] = acc[p];
-                }
-            }
-        }
-        if (!y_vec_ok) *reinterpret_cast<float4*>(s_out + base) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    }
-    if (!y_vec_ok) {
-        // The output row does not start on a 16-byte boundary: peel up to three elements, then store
-        // 16-byte groups that are aligned in memory (read from LDS at the matching odd offset).
-        __syncthreads();
-        const int head = min(n_out, (int)(((16u - (unsigned)(reinterpret_cast<uintptr_t>(yr) & 15u)) & 15u) >> 2));
-        const int body4 = (n_out - head) >> 2;
-        const int tail0 = head + 4 * body4;
-        if (tid < head) yr[tid] = s_out[tid];
-        for (int f = tid; f < body4; f += kThreads) {
-            const int e = head + 4 * f;
-            stream_store4(yr + e, floatx4{s_out[e], s_out[e + 1], s_out[e + 2], s_out[e + 3]});
-        }
-        if (tid < n_out - tail0) yr[tail0 + tid] = s_out[tail0 + tid];
+    switch (sh) {
+        case 0: tile_outputs<OP, KC, 0>(s_in, w, k, yrow, o0, o_end, tid); break;
+        case 1: tile_outputs<OP, KC, 1>(s_in, w, k, yrow, o0, o_end, tid); break;
+        case 2: tile_outputs<OP, KC, 2>(s_in, w, k, yrow, o0, o_end, tid); break;
+        default: tile_outputs<OP, KC, 3>(s_in, w, k, yrow, o0, o_end, tid); break;
     }
 }
 
@@ -174,22 +173,22 @@ template <int OP>
 hipError_t launch_op(const float* x, const float* w, float* y, int64_t rows, int len, int len_out, int k,
                      int pad, hipStream_t st)
 {
-    const int tiles_per_row = (len_out + kTile - 1) / kTile;
+    // up to three outputs of misalignment per row are absorbed by the first tile
+    const int tiles_per_row = (len_out + 3 + kTile - 1) / kTile;
     const int64_t blocks = rows * tiles_per_row;
     const int x_vec_ok = (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (len % 4 == 0 || rows == 1);
-    const int y_vec_ok = (reinterpret_cast<uintptr_t>(y) % 16 == 0) && (len_out % 4 == 0 || rows == 1);
     dim3 grid((unsigned)blocks), block(kThreads);
 #define SW_CASE(KC)                                                                                      \
     case KC:                                                                                             \
         hipLaunchKernelGGL((sliding_1d_kernel<OP, KC>), grid, block, 0, st, x, w, y, len, len_out, k,    \
-                           pad, tiles_per_row, x_vec_ok, y_vec_ok);                                      \
+                           pad, tiles_per_row, x_vec_ok);                                                \
         break;
     switch (k) {
         SW_CASE(2) SW_CASE(3) SW_CASE(4) SW_CASE(5) SW_CASE(6) SW_CASE(7) SW_CASE(8) SW_CASE(9)
         SW_CASE(11) SW_CASE(13) SW_CASE(15) SW_CASE(16) SW_CASE(17)
         default:
             hipLaunchKernelGGL((sliding_1d_kernel<OP, 0>), grid, block, 0, st, x, w, y, len, len_out, k, pad,
-                               tiles_per_row, x_vec_ok, y_vec_ok);
+                               tiles_per_row, x_vec_ok);
     }
 #undef SW_CASE
     return hipGetLastError();
@@ -205,7 +204,7 @@ bool sliding_1d_supported(int64_t len, int k, int stride, int pad)
 hipError_t launch_sliding_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
                              int64_t len_out, int k, int pad, Op1D op, hipStream_t st)
 {
-    const int64_t tiles = (len_out + kTile - 1) / kTile;
+    const int64_t tiles = (len_out + 3 + kTile - 1) / kTile;
     if (rows * tiles > 2147483647LL) return hipErrorInvalidValue;
     switch (op) {
         case OP_CONV: return launch_op<OP_CONV>(x, w, y, rows, (int)len, (int)len_out, k, pad, st);

@@ -316,10 +316,20 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
 
 }  // namespace
 
+bool sliding_plane_whole(const float* x, const float* y, int W, int R, int S, int pad, int Ho, int Wo);
+
 bool sliding_plane_supported(int H, int W, int R, int S, int stride, int pad)
 {
     (void)H; (void)W;
     return stride == 1 && R <= kMaxRSWide && S <= kMaxRSWide && pad >= 0;
+}
+
+// True when the persistent whole-plane kernel takes the problem (planes that fit one 56 x 56 tile).
+bool sliding_plane_whole(const float* x, const float* y, int W, int R, int S, int pad, int Ho, int Wo)
+{
+    const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
+    const bool fixed = R == S && (R == 3 || R == 5 || R == 7);
+    return fixed && aligned && Ho <= kTile && Wo <= kTile && 2 * pad <= R - 1 && W % 4 == 0 && Wo % 4 == 0;
 }
 
 // Launch-latency regime: with fewer than 64 tiles (a quarter of the CUs) and a small filter the whole
@@ -335,10 +345,7 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int n_filters, int H, int W, int R, int S, int pad, int Ho, int Wo,
                                 hipStream_t st)
 {
-    const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
-    const bool fixed = R == S && (R == 3 || R == 5 || R == 7);
-    if (fixed && aligned && Ho <= kTile && Wo <= kTile && 2 * pad <= R - 1 && W % 4 == 0 && Wo % 4 == 0 &&
-        planes <= 2147483647LL) {
+    if (sliding_plane_whole(x, y, W, R, S, pad, Ho, Wo) && planes <= 2147483647LL) {
         // enough wavefronts to fill the chip, each walking over several planes
         const int64_t want = 256 * 8;
         dim3 grid((unsigned)(planes < want ? planes : want)), block(64);

@@ -23,6 +23,15 @@ bool force_direct()
     return v;
 }
 
+bool no_rows_kernel()      // A/B switch: keep one-filter-per-plane problems off the register-only rows kernel
+{
+    static const bool v = [] {
+        const char* e = std::getenv("SWCONV_NO_ROWS");
+        return e && e[0] == '1';
+    }();
+    return v;
+}
+
 bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
 bool overlaps(const void* a, int64_t abytes, const void* b, int64_t bbytes)
@@ -32,6 +41,24 @@ bool overlaps(const void* a, int64_t abytes, const void* b, int64_t bbytes)
 }
 
 int launch_status(hipError_t e) { return e == hipSuccess ? SW_OK : SW_ERR_LAUNCH; }
+
+// One filter per plane (single input channel, depthwise): picks among the whole-plane kernel (many planes
+// that fit a 56 x 56 tile), the register-only rows kernel (3x3 / 5x5), the tile kernel and the direct kernel.
+int run_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
+              const Conv2dShape& s, bool depthwise, hipStream_t st)
+{
+    if (!force_direct() && s.stride == 1) {
+        const bool whole = sliding_plane_whole(x, y, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) && planes >= 512;
+        if (!whole && !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad))
+            return launch_status(launch_sliding_rows(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
+                                                     s.pad, s.Ho, s.Wo, st));
+        if (sliding_plane_supported(s.H, s.W, s.R, s.S, s.stride, s.pad) &&
+            sliding_plane_worthwhile(planes, s.Ho, s.Wo, s.R, s.S))
+            return launch_status(launch_sliding_plane(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
+                                                      s.pad, s.Ho, s.Wo, st));
+    }
+    return launch_status(launch_direct_conv2d_f32(x, w, y, s, depthwise, st));
+}
 
 // Shared validation of the 2-D calls.  esz_in / esz_out are element sizes in bytes.
 int check_conv2d(const void* x, const void* w, const void* y, int N, int C_in, int C_out, int H, int W,
@@ -127,13 +154,8 @@ int sw_conv2d(const float* x, const float* w, float* y, int N, int C_in, int C_o
     const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, 4, 4, &s);
     if (rc != SW_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (!force_direct()) {
-        if (C_in == 1 && sliding_plane_supported(H, W, R, S, stride, pad) &&
-            sliding_plane_worthwhile((int64_t)N * C_out, s.Ho, s.Wo, R, S))
-            return launch_status(launch_sliding_plane(x, w, y, (int64_t)N * C_out, C_out, C_out, H, W, R, S,
-                                                      pad, s.Ho, s.Wo, st));
-        if (mfma_f32_supported(s)) return launch_status(launch_mfma_f32(x, w, y, s, st));
-    }
+    if (C_in == 1) return run_plane(x, w, y, (int64_t)N * C_out, C_out, C_out, s, false, st);
+    if (!force_direct() && mfma_f32_supported(s)) return launch_status(launch_mfma_f32(x, w, y, s, st));
     return launch_status(launch_direct_conv2d_f32(x, w, y, s, false, st));
 }
 
@@ -144,11 +166,7 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, 
     const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s);
     if (rc != SW_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (!force_direct() && sliding_plane_supported(H, W, R, S, stride, pad) &&
-        sliding_plane_worthwhile((int64_t)N * C, s.Ho, s.Wo, R, S))
-        return launch_status(
-            launch_sliding_plane(x, w, y, (int64_t)N * C, 1, C, H, W, R, S, pad, s.Ho, s.Wo, st));
-    return launch_status(launch_direct_conv2d_f32(x, w, y, s, true, st));
+    return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
 }
 
 int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, int N, int C_in, int C_out, int H, int W,

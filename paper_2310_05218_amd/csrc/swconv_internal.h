@@ -42,6 +42,12 @@ hipError_t launch_sliding_1d(const float* x, const float* w, float* y, int64_t r
 // one input plane; depthwise: 1); filter index is p % n_filters.
 bool       sliding_plane_supported(int H, int W, int R, int S, int stride, int pad);
 bool       sliding_plane_worthwhile(int64_t planes, int Ho, int Wo, int R, int S);
+bool       sliding_plane_whole(const float* x, const float* y, int W, int R, int S, int pad, int Ho, int Wo);
+
+// ---- sliding rows kernel (stride 1, 3x3 / 5x5): registers only, DPP wavefront shifts for the halo -------
+bool       sliding_rows_supported(const float* x, int H, int W, int R, int S, int stride, int pad);
+hipError_t launch_sliding_rows(const float* x, const float* w, float* y, int64_t planes, int planes_per_x,
+                               int n_filters, int H, int W, int R, int S, int pad, int Ho, int Wo, hipStream_t st);
 hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes,
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st);

@@ -126,6 +126,12 @@ PLANE_CASES = [
     (1, 1, 70, 64, 33, 29, 1, 14),
     (1, 1, 56, 56, 51, 51, 1, 25),
     (1, 2, 64, 64, 13, 4, 1, 0),
+    (1, 2, 20, 520, 3, 3, 1, 1),    # rows kernel, three overlapping strips
+    (1, 1, 30, 260, 5, 5, 1, 2),    # rows kernel, second strip of one lane
+    (2, 1, 37, 512, 3, 3, 1, 0),
+    (1, 3, 19, 256, 5, 5, 1, 1),
+    (1, 2, 11, 252, 5, 5, 1, 0),
+    (8, 64, 64, 64, 3, 3, 1, 1),    # rows kernel, 8-row bands
     (1, 3, 21, 23, 3, 3, 2, 1),     # strided: direct kernel
     (1, 2, 7, 5, 7, 5, 1, 0),
     (1, 2, 16, 16, 3, 3, 1, 2),     # padding wider than the usual (R-1)/2

@@ -24,6 +24,8 @@
 // as soon as it is complete.  The int32 output is 79 % of this problem's memory traffic and the device
 // absorbs writes at roughly half the HBM peak, so letting the stores of one pair drain under the
 // multiplications of the next is what this order is for; no barrier separates the wavefronts here.
+#include <algorithm>
+
 #include "swconv_internal.h"
 
 namespace swconv {
@@ -96,7 +98,8 @@ struct S8Params {
 };
 
 // RES == 0: input channels in chunks of 64 through LDS.  RES == 128: C_in == 128, all of K resident in LDS.
-template <int RES>
+// XI: input staging items per thread and chunk (1 when 4 * rows * column quads <= 256).
+template <int RES, int XI>
 __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restrict__ x,
                                                          const int8_t* __restrict__ w,
                                                          int32_t* __restrict__ y, const S8Params P)
@@ -133,14 +136,15 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
 
     // ---- input staging plan: item = (16-channel group, window row, image column quad) ---------------
     const int wc0 = col0 - pad;                        // image column of window column 0
-    const int g_lo = wc0 >> 2;                         // arithmetic shift: floor for negatives
-    const int nq = ((wc0 + IW - 1) >> 2) - g_lo + 1;
+    // column quads of the image that the window touches (quads outside the image stay zero)
+    const int g_lo = max(wc0 >> 2, 0);                 // arithmetic shift: floor for negatives
+    const int nq = min((wc0 + IW - 1) >> 2, (W >> 2) - 1) - g_lo + 1;
     const int nitems = 4 * IH * P.nq_max;
-    int xoff[kXItems];      // byte offset of (channel 16*c16, row, 4g) in the image; < 0: skip item
-    int xlds[kXItems];      // byte address in lx of window column (4g - wc0) of that row, channel 16*c16
-    int xc[kXItems];        // window column of the quad's first pixel (may be < 0)
+    int xoff[XI];      // byte offset of (channel 16*c16, row, 4g) in the image; < 0: skip item
+    int xlds[XI];      // byte address in lx of window column (4g - wc0) of that row, channel 16*c16
+    int xc[XI];        // window column of the quad's first pixel (may be < 0)
 #pragma unroll
-    for (int k = 0; k < kXItems; ++k) {
+    for (int k = 0; k < XI; ++k) {
         const int idx = tid + 256 * k;
         const int t = fast_div(idx, P.by_nq_max);
         const int g = idx - t * P.nq_max;
@@ -167,15 +171,15 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
     }
 
     // two register sets, each holding one chunk on its way from global memory to LDS
-    u32 xv0[kXItems][16], xv1[kXItems][16];
+    u32 xv0[XI][16], xv1[XI][16];
     intx4 wv0[9], wv1[9];
-    auto fetch = [&](u32 (&xv)[kXItems][16], intx4 (&wv)[9], int c0) {
+    auto fetch = [&](u32 (&xv)[XI][16], intx4 (&wv)[9], int c0) {
         const int8_t* xcp = xn + (int64_t)c0 * HW;
 #pragma unroll
-        for (int k = 0; k < kXItems; ++k) {
+        for (int k = 0; k < XI; ++k) {
 #pragma unroll
-            for (int c = 0; c < 16; ++c)
-                xv[k][c] = xoff[k] >= 0 ? *reinterpret_cast<const u32*>(xcp + xoff[k] + c * HW) : 0u;
+            for (int c = 0; c < 16; ++c)      // skipped items read a valid dummy address; stage() ignores them
+                xv[k][c] = *reinterpret_cast<const u32*>(xcp + max(xoff[k], 0) + c * HW);
         }
         const int8_t* ws = wblk + (int64_t)c0 * 9;
 #pragma unroll
@@ -201,9 +205,9 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         for (int v = 0; v < 16; ++v) acc[i][v] = 0;
 
     // registers -> LDS (with the byte transposes), then the chunk's 9 taps x 2 K steps
-    auto stage = [&](u32 (&xv)[kXItems][16], intx4 (&wv)[9], int coff) {
+    auto stage = [&](u32 (&xv)[XI][16], intx4 (&wv)[9], int coff) {
 #pragma unroll
-        for (int k = 0; k < kXItems; ++k) {
+        for (int k = 0; k < XI; ++k) {
             if (xoff[k] >= 0) {
                 const int c = xc[k];
                 if (c >= 0 && c < IW) *reinterpret_cast<intx4*>(lx + xlds[k] + coff) = xgather_px<0>(xv[k]);
@@ -278,53 +282,62 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
             const int r = tap / 3, q = tap - 3 * r;
             return *reinterpret_cast<const intx4*>(lx + boff[i] + (r * IW + q) * kPitch + 32 * kk);
         };
-        auto store_block = [&](int i, const intx16& c) {
+        // destination of this lane's pixel in block i (nullptr when the pixel lies outside the tile/image)
+        auto block_dst = [&](int i) -> int32_t* {
             const int p = (wn * kNBW + i) * 32 + lj;
             const int pi = fast_div(p, P.by_TW), pj = p - pi * TW;
             const int oi = row0 + pi, oj = col0 + pj;
-            if (p < tile_px && oi < Ho && oj < Wo) {
-                int32_t* dst = yres + oi * Wo + oj;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) dst[(8 * (v >> 2) + (v & 3)) * HoWo] = c[v];
-            }
+            return (p < tile_px && oi < Ho && oj < Wo) ? yres + oi * Wo + oj : nullptr;
         };
+        auto store_reg = [&](int32_t* dst, const intx16& c, int v) {
+            if (dst) dst[(8 * (v >> 2) + (v & 3)) * HoWo] = c[v];
+        };
+        // Pair 0 (blocks 0, 1), then pair 1 (blocks 2, 3) with the 32 stores of pair 0 spread between its
+        // matrix instructions, then the stores of pair 1.
+        const int live = __builtin_amdgcn_readfirstlane(min(kNBW, (tile_px - wn * kNBW * 32 + 31) >> 5));
+        intx16 c0, c1, d0, d1;
 #pragma unroll
-        for (int pr = 0; pr < kNBW; pr += 2) {
-            const int first_px = __builtin_amdgcn_readfirstlane((wn * kNBW + pr) * 32);
-            if (first_px >= tile_px) break;
-            if (first_px + 32 < tile_px) {          // two live blocks: two independent accumulators
-                intx16 c0, c1;
+        for (int v = 0; v < 16; ++v) { c0[v] = 0; c1[v] = 0; d0[v] = 0; d1[v] = 0; }
+        if (live >= 1) {
+            intx4 b0[2], b1[2];
+            b0[0] = b_at(0, 0); b1[0] = b_at(1, 0);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) { c0[v] = 0; c1[v] = 0; }
-                intx4 b0[2], b1[2];
-                b0[0] = b_at(pr, 0); b1[0] = b_at(pr + 1, 0);
-#pragma unroll
-                for (int st = 0; st < NSTEP; ++st) {
-                    const int cur = st & 1;
-                    if (st + 1 < NSTEP) { b0[cur ^ 1] = b_at(pr, st + 1); b1[cur ^ 1] = b_at(pr + 1, st + 1); }
-                    __builtin_amdgcn_sched_barrier(0);
-                    c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b0[cur], c0, 0, 0, 0);
-                    c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b1[cur], c1, 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                store_block(pr, c0);
-                store_block(pr + 1, c1);
-            } else {                                // a single live block
-                intx16 c0;
-#pragma unroll
-                for (int v = 0; v < 16; ++v) c0[v] = 0;
-                intx4 b0[2];
-                b0[0] = b_at(pr, 0);
-#pragma unroll
-                for (int st = 0; st < NSTEP; ++st) {
-                    const int cur = st & 1;
-                    if (st + 1 < NSTEP) b0[cur ^ 1] = b_at(pr, st + 1);
-                    __builtin_amdgcn_sched_barrier(0);
-                    c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b0[cur], c0, 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                store_block(pr, c0);
+            for (int st = 0; st < NSTEP; ++st) {
+                const int cur = st & 1;
+                if (st + 1 < NSTEP) { b0[cur ^ 1] = b_at(0, st + 1); b1[cur ^ 1] = b_at(1, st + 1); }
+                __builtin_amdgcn_sched_barrier(0);
+                c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b0[cur], c0, 0, 0, 0);
+                c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b1[cur], c1, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        }
+        int32_t* dst0 = live >= 1 ? block_dst(0) : nullptr;
+        int32_t* dst1 = live >= 2 ? block_dst(1) : nullptr;
+        if (live >= 3) {
+            intx4 b0[2], b1[2];
+            b0[0] = b_at(2, 0); b1[0] = b_at(3, 0);
+#pragma unroll
+            for (int st = 0; st < NSTEP; ++st) {
+                const int cur = st & 1;
+                if (st + 1 < NSTEP) { b0[cur ^ 1] = b_at(2, st + 1); b1[cur ^ 1] = b_at(3, st + 1); }
+                if (st >= 2 && st < 18) store_reg(dst0, c0, st - 2);
+                if (st >= 18 && st < 34) store_reg(dst1, c1, st - 18);
+                __builtin_amdgcn_sched_barrier(0);
+                d0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b0[cur], d0, 0, 0, 0);
+                d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b1[cur], d1, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            int32_t* dst2 = block_dst(2);
+            int32_t* dst3 = live >= 4 ? block_dst(3) : nullptr;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) store_reg(dst2, d0, v);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) store_reg(dst3, d1, v);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) store_reg(dst0, c0, v);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) store_reg(dst1, c1, v);
         }
         return;
     }
@@ -399,7 +412,7 @@ Tiling pick_tiling(const Conv2dShape& s)
     auto even = [&](int th) { const int bands = (s.Ho + th - 1) / th; return (s.Ho + bands - 1) / bands; };
     auto fits = [&](int th) {
         const int IH = th + 2, IW = t.TW + 2;
-        const int nq_max = (IW + 2) / 4 + 1;   // column quads a window can touch
+        const int nq_max = std::min((IW + 2) / 4 + 1, s.W / 4);   // column quads a window can touch
         return IH * IW <= kLdsPx && 4 * IH * nq_max <= kXItems * 256;
     };
     while (t.TH > 1 && !fits(t.TH)) --t.TH;
@@ -412,7 +425,7 @@ Tiling pick_tiling(const Conv2dShape& s)
 bool tiling_ok(const Conv2dShape& s, const Tiling& t)
 {
     const int IH = t.TH + 2, IW = t.TW + 2;
-    const int nq_max = (IW + 2) / 4 + 1;
+    const int nq_max = std::min((IW + 2) / 4 + 1, s.W / 4);
     return t.TH >= 1 && t.TH * t.TW <= kTilePx && IH * IW <= kLdsPx && 4 * IH * nq_max <= kXItems * 256 &&
            (int64_t)t.tiles_x * t.tiles_y <= 65535 && s.C_out / 64 <= 65535 && s.N <= 65535;
 }
@@ -432,17 +445,26 @@ hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Co
     // the vectorised staging reads 4-byte groups of x and 16-byte groups of w
     if (reinterpret_cast<uintptr_t>(x) % 4 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0)
         return launch_direct_conv2d_s8(x, w, y, s, st);
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<0>),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+    static const hipError_t attr = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<0, 1>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<0, 2>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<128, 1>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesRes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<128, 2>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesRes);
+        return e;
+    }();
     if (attr != hipSuccess) return attr;
-    static const hipError_t attr_res = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<128>),
-                                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesRes);
-    if (attr_res != hipSuccess) return attr_res;
     const Tiling t = pick_tiling(s);
     S8Params P;
     P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
     P.TH = t.TH; P.TW = t.TW;
-    P.nq_max = (t.TW + 2 + 2) / 4 + 1;
+    P.nq_max = std::min((t.TW + 2 + 2) / 4 + 1, s.W / 4);
     // 16-byte stores need full-width tiles whose runs of y start and end on 16-byte boundaries
     P.wide_store = t.tiles_x == 1 && s.Wo % 4 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0 &&
                    64 * (t.TH * t.TW + 4) * 4 <= kLdsBytes;   // (chunked variant only)
@@ -452,10 +474,16 @@ hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Co
     P.by_nq_max = make_fastdiv(P.nq_max);
     P.by_pieces = make_fastdiv(t.TH * s.Wo / 4 > 0 ? t.TH * s.Wo / 4 : 1);
     dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)s.N, (unsigned)(s.C_out / 64));
-    if (s.C_in == 128 && (t.TH + 2) * (t.TW + 2) <= kLdsPxRes)
-        hipLaunchKernelGGL(mfma_s8_kernel<128>, grid, dim3(256), kLdsBytesRes, st, x, w, y, P);
+    const bool one_item = 4 * (t.TH + 2) * P.nq_max <= 256;
+    const bool resident = s.C_in == 128 && (t.TH + 2) * (t.TW + 2) <= kLdsPxRes;
+    if (resident && one_item)
+        hipLaunchKernelGGL((mfma_s8_kernel<128, 1>), grid, dim3(256), kLdsBytesRes, st, x, w, y, P);
+    else if (resident)
+        hipLaunchKernelGGL((mfma_s8_kernel<128, 2>), grid, dim3(256), kLdsBytesRes, st, x, w, y, P);
+    else if (one_item)
+        hipLaunchKernelGGL((mfma_s8_kernel<0, 1>), grid, dim3(256), kLdsBytes, st, x, w, y, P);
     else
-        hipLaunchKernelGGL(mfma_s8_kernel<0>, grid, dim3(256), kLdsBytes, st, x, w, y, P);
+        hipLaunchKernelGGL((mfma_s8_kernel<0, 2>), grid, dim3(256), kLdsBytes, st, x, w, y, P);
     return hipGetLastError();
 }
 

@@ -123,7 +123,10 @@ __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restric
     auto fetch_part = [&](int c0, int part) {
         const float* xc = xn + (int64_t)c0 * HW;
 #pragma unroll
-        for (int t = 0; t < 4; ++t) xr[part][t] = goff[part] >= 0 ? xc[goff[part] + t * HW] : 0.f;
+        for (int t = 0; t < 4; ++t) {     // unconditional load at a clamped offset, then a select: no branch
+            const float v = xc[max(goff[part], 0) + t * HW];
+            xr[part][t] = goff[part] >= 0 ? v : 0.f;
+        }
         const floatx4* ws = reinterpret_cast<const floatx4*>(wsrc + (int64_t)c0 * RS);
 #pragma unroll
         for (int i = part * WP; i < (part + 1) * WP; ++i)

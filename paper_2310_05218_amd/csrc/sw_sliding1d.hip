@@ -27,6 +27,7 @@ constexpr int kSub = kThreads * 4;      // outputs per pass over the workgroup
 constexpr int kPasses = 2;
 constexpr int kTile = kSub * kPasses;   // outputs per workgroup
 constexpr int kMaxK = 64;
+constexpr int kMaxBlocks = 256 * 32;     // workgroups per launch; beyond that a workgroup walks over several tiles
 constexpr int kLdsIn = kTile + kMaxK + 16;  // tile + halo + alignment offset + read-ahead, multiple of 4
 
 template <int OP>
@@ -107,65 +108,117 @@ __device__ __forceinline__ void tile_outputs(const float* __restrict__ s_in, con
     }
 }
 
+// Geometry of one tile (all wave-uniform).
+struct Tile1D {
+    const float* xr;   // the row's input
+    float* yrow;       // the row's output
+    int o0;            // first output of the tile, row-relative (may be < 0 in the first tile of a row)
+    int o_end;         // one past its last real output
+    int t0;            // input position held by LDS element 0 (multiple of 4)
+    int sh;            // register offset 0..3 (padding and output misalignment)
+    int n_in4;         // 16-byte groups of input the tile reads
+};
+
+__device__ __forceinline__ Tile1D tile_geometry(const float* x, float* y, int tile_id, int tiles_per_row,
+                                                int len, int len_out, int k, int pad)
+{
+    Tile1D g;
+    const int row = tile_id / tiles_per_row;          // (tile counts are checked to fit 31 bits on the host)
+    const int tile = tile_id - row * tiles_per_row;
+    g.xr = x + (int64_t)row * len;
+    g.yrow = y + (int64_t)row * len_out;
+    // Outputs are grouped so that every group of four starts on a 16-byte boundary in memory: with `a` the
+    // misalignment (in floats) of the row's first output, the tile owns outputs o0 .. o0 + kTile - 1 with
+    // o0 = tile * kTile - a.
+    const int a = (int)((reinterpret_cast<uintptr_t>(g.yrow) >> 2) & 3);
+    g.o0 = tile * kTile - a;
+    // LDS element e holds input position t0 + e; t0 is a multiple of 4 so that 16-byte global loads stay
+    // aligned.  Output o0 + q reads inputs from position o0 + q - pad, i.e. LDS element q + sh.
+    const int lead = (a + pad + 3) & ~3;
+    g.sh = lead - a - pad;
+    g.t0 = tile * kTile - lead;
+    g.o_end = min(g.o0 + kTile, len_out);
+    g.n_in4 = ((g.o_end - g.o0) + k - 1 + g.sh + 3) >> 2;
+    return g;
+}
+
+// One 16-byte group of a row's input, zero outside the row.
+__device__ __forceinline__ floatx4 load_group(const float* __restrict__ xr, int t, int len)
+{
+    if (t >= 0 && t + 3 < len) return stream_load4(xr + t);
+    floatx4 v;
+    v.x = (t >= 0 && t < len) ? xr[t] : 0.f;
+    v.y = (t + 1 >= 0 && t + 1 < len) ? xr[t + 1] : 0.f;
+    v.z = (t + 2 >= 0 && t + 2 < len) ? xr[t + 2] : 0.f;
+    v.w = (t + 3 >= 0 && t + 3 < len) ? xr[t + 3] : 0.f;
+    return v;
+}
+
+// Workgroup barrier that orders LDS traffic only: unlike __syncthreads() it does not wait for global loads
+// in flight, which is what lets the next tile's fetch overlap this tile's arithmetic and stores.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+constexpr int kPre = (kLdsIn / 4 + kThreads - 1) / kThreads;    // 16-byte groups a lane prefetches per tile
+
 // KC > 0: tap count known at compile time (fully unrolled, taps in scalar registers).
 // KC == 0: tap count k at run time.
+// A workgroup walks over tiles blockIdx.x, blockIdx.x + gridDim.x, ...; the next tile's input is on its way
+// from HBM into registers while the current tile is accumulated and stored.
 template <int OP, int KC>
 __global__ __launch_bounds__(kThreads) void sliding_1d_kernel(const float* __restrict__ x,
                                                               const float* __restrict__ w,
                                                               float* __restrict__ y, int len,
                                                               int len_out, int k_rt, int pad,
-                                                              int tiles_per_row, int x_vec_ok)
+                                                              int tiles_per_row, int tiles, int x_vec_ok)
 {
     __shared__ __attribute__((aligned(16))) float s_in[kLdsIn];
 
     const int k = KC > 0 ? KC : k_rt;
     const int tid = threadIdx.x;
-    const int row = blockIdx.x / tiles_per_row;
-    const int tile = blockIdx.x - row * tiles_per_row;
-    const float* xr = x + (int64_t)row * len;
-    float* yrow = y + (int64_t)row * len_out;
+    int tile_id = blockIdx.x;
+    Tile1D g = tile_geometry(x, y, tile_id, tiles_per_row, len, len_out, k, pad);
 
-    // Outputs are grouped so that every group of four starts on a 16-byte boundary in memory: with `a` the
-    // misalignment (in floats) of the row's first output, the tile owns outputs o0 .. o0 + kTile - 1 with
-    // o0 = tile * kTile - a (the first tile of a misaligned row starts before output 0).
-    const int a = (int)((reinterpret_cast<uintptr_t>(yrow) >> 2) & 3);
-    const int o0 = tile * kTile - a;
-    // LDS element e holds input position t0 + e; t0 is a multiple of 4 so that 16-byte global loads stay
-    // aligned.  Output o0 + q reads inputs from position o0 + q - pad, i.e. LDS element q + sh.
-    const int lead = (a + pad + 3) & ~3;
-    const int sh = lead - a - pad;                     // 0..3
-    const int t0 = tile * kTile - lead;
-    const int o_end = min(o0 + kTile, len_out);        // one past the tile's last real output
-    const int n_in = (o_end - o0) + k - 1 + sh;        // LDS elements the outputs read
-    const int n_in4 = (n_in + 3) >> 2;
-
+    floatx4 pre[kPre];
     if (x_vec_ok) {
-        for (int f = tid; f < n_in4; f += kThreads) {
-            const int t = t0 + 4 * f;
-            floatx4 v;
-            if (t >= 0 && t + 3 < len) {
-                v = stream_load4(xr + t);
-            } else {
-                v.x = (t >= 0 && t < len) ? xr[t] : 0.f;
-                v.y = (t + 1 >= 0 && t + 1 < len) ? xr[t + 1] : 0.f;
-                v.z = (t + 2 >= 0 && t + 2 < len) ? xr[t + 2] : 0.f;
-                v.w = (t + 3 >= 0 && t + 3 < len) ? xr[t + 3] : 0.f;
-            }
-            *reinterpret_cast<floatx4*>(s_in + 4 * f) = v;
-        }
-    } else {
-        for (int e = tid; e < 4 * n_in4; e += kThreads) {
-            const int t = t0 + e;
-            s_in[e] = (t >= 0 && t < len) ? xr[t] : 0.f;
-        }
+#pragma unroll
+        for (int i = 0; i < kPre; ++i)
+            if (tid + i * kThreads < g.n_in4) pre[i] = load_group(g.xr, g.t0 + 4 * (tid + i * kThreads), len);
     }
-    __syncthreads();
+    while (true) {
+        if (x_vec_ok) {
+#pragma unroll
+            for (int i = 0; i < kPre; ++i)
+                if (tid + i * kThreads < g.n_in4) *reinterpret_cast<floatx4*>(s_in + 4 * (tid + i * kThreads)) = pre[i];
+        } else {
+            for (int e = tid; e < 4 * g.n_in4; e += kThreads) {
+                const int t = g.t0 + e;
+                s_in[e] = (t >= 0 && t < len) ? g.xr[t] : 0.f;
+            }
+        }
+        lds_barrier();
 
-    switch (sh) {
-        case 0: tile_outputs<OP, KC, 0>(s_in, w, k, yrow, o0, o_end, tid); break;
-        case 1: tile_outputs<OP, KC, 1>(s_in, w, k, yrow, o0, o_end, tid); break;
-        case 2: tile_outputs<OP, KC, 2>(s_in, w, k, yrow, o0, o_end, tid); break;
-        default: tile_outputs<OP, KC, 3>(s_in, w, k, yrow, o0, o_end, tid); break;
+        const int next_id = tile_id + (int)gridDim.x;
+        const bool more = next_id < tiles;
+        Tile1D gn = g;
+        if (more) {
+            gn = tile_geometry(x, y, next_id, tiles_per_row, len, len_out, k, pad);
+            if (x_vec_ok) {
+#pragma unroll
+                for (int i = 0; i < kPre; ++i)
+                    if (tid + i * kThreads < gn.n_in4) pre[i] = load_group(gn.xr, gn.t0 + 4 * (tid + i * kThreads), len);
+            }
+        }
+
+        switch (g.sh) {
+            case 0: tile_outputs<OP, KC, 0>(s_in, w, k, g.yrow, g.o0, g.o_end, tid); break;
+            case 1: tile_outputs<OP, KC, 1>(s_in, w, k, g.yrow, g.o0, g.o_end, tid); break;
+            case 2: tile_outputs<OP, KC, 2>(s_in, w, k, g.yrow, g.o0, g.o_end, tid); break;
+            default: tile_outputs<OP, KC, 3>(s_in, w, k, g.yrow, g.o0, g.o_end, tid); break;
+        }
+        if (!more) break;
+        lds_barrier();      // every lane is done reading this tile before the next one is written
+        tile_id = next_id;
+        g = gn;
     }
 }
 
@@ -175,20 +228,22 @@ hipError_t launch_op(const float* x, const float* w, float* y, int64_t rows, int
 {
     // up to three outputs of misalignment per row are absorbed by the first tile
     const int tiles_per_row = (len_out + 3 + kTile - 1) / kTile;
-    const int64_t blocks = rows * tiles_per_row;
+    const int64_t tiles = rows * tiles_per_row;
+    // enough workgroups to fill the chip several times over in flight, each walking over >= 1 tiles
+    const int64_t blocks = tiles < kMaxBlocks ? tiles : kMaxBlocks;
     const int x_vec_ok = (reinterpret_cast<uintptr_t>(x) % 16 == 0) && (len % 4 == 0 || rows == 1);
     dim3 grid((unsigned)blocks), block(kThreads);
 #define SW_CASE(KC)                                                                                      \
     case KC:                                                                                             \
         hipLaunchKernelGGL((sliding_1d_kernel<OP, KC>), grid, block, 0, st, x, w, y, len, len_out, k,    \
-                           pad, tiles_per_row, x_vec_ok);                                                \
+                           pad, tiles_per_row, (int)tiles, x_vec_ok);                                    \
         break;
     switch (k) {
         SW_CASE(2) SW_CASE(3) SW_CASE(4) SW_CASE(5) SW_CASE(6) SW_CASE(7) SW_CASE(8) SW_CASE(9)
         SW_CASE(11) SW_CASE(13) SW_CASE(15) SW_CASE(16) SW_CASE(17)
         default:
             hipLaunchKernelGGL((sliding_1d_kernel<OP, 0>), grid, block, 0, st, x, w, y, len, len_out, k, pad,
-                               tiles_per_row, x_vec_ok);
+                               tiles_per_row, (int)tiles, x_vec_ok);
     }
 #undef SW_CASE
     return hipGetLastError();

@@ -66,6 +66,15 @@ def test_conv1d(torch, sw, oracle, case):
     assert_f32_parity(out.cpu().numpy(), y_ref, d, f"conv1d {case}")
 
 
+def test_conv1d_more_tiles_than_workgroups(torch, sw, oracle):
+    # 9000 tiles of 2048 outputs > 8192 workgroups: some workgroups walk over two tiles (prefetch path)
+    x = inputs.normal_f32((9000, 2051), 1003)
+    w = inputs.normal_f32((5,), 1004)
+    y_ref, d = oracle.conv1d(x, w, 1, 1)
+    y = sw.sw_conv1d(dev(torch, x), dev(torch, w), 1, 1)
+    assert_f32_parity(y.cpu().numpy(), y_ref, d, "conv1d 9000 x 2051")
+
+
 POOL_CASES = [(1, 8, 8, 1), (3, 4173, 8, 1), (2, 6144 + 7, 8, 1), (4, 5000, 3, 1), (2, 5000, 1, 1),
               (2, 4100, 17, 1), (2, 4100, 40, 1), (2, 3000, 64, 1), (3, 1000, 8, 2), (3, 1001, 3, 3)]
 

@@ -244,17 +244,27 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
     const int n_in4 = H * W4, n_out4 = Ho * Wo4;
 
     // slot k of a lane is 16-byte group lane + 64*k of the plane; slots below n*_full are live in
-    // every lane (a wave-uniform test), the one after that in the first n*_rem lanes
+    // every lane (a wave-uniform test), the one after that in the first n*_rem lanes.  In the 56 x 56
+    // case the last slot is moved back to the plane's last 64 groups instead (it repeats 48 groups of
+    // the slot before it with the same values), so that every slot is unconditional: the number of
+    // loads and stores in flight is then the same on every path, and the wait for a prefetch does
+    // not have to include the stores issued after it.
     const int nin_full = n_in4 >> 6, nin_rem = n_in4 & 63;
     const int nout_full = n_out4 >> 6, nout_rem = n_out4 & 63;
+    auto group = [&](int k) { return SQ && k == NSLOT - 1 ? kTile * kTile / 4 - 64 + lane : lane + 64 * k; };
+    auto in_live = [&](int k) { return SQ || k < nin_full || (k == nin_full && lane < nin_rem); };
+    auto out_live = [&](int k) { return SQ || k < nout_full || (k == nout_full && lane < nout_rem); };
     int in_slot[NSLOT], out_slot[NSLOT];
 #pragma unroll
     for (int k = 0; k < NSLOT; ++k) {
-        const int f = lane + 64 * k;
+        const int f = group(k);
         const int ri = f / W4, ro = f / Wo4;
         in_slot[k] = (ri + pad) * P + pad_up + 4 * (f - ri * W4);
         out_slot[k] = (ro + pad) * P + pad_up + 4 * (f - ro * Wo4);
     }
+
+    int plane = blockIdx.x;
+    if (plane >= planes) return;
 
     for (int i = lane; i < ROWS * P / 4; i += 64) reinterpret_cast<float4*>(lds)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
 
@@ -264,26 +274,27 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
     const bool full = SQ || ((Ho == kTile) && (Wo == kTile));
 
     floatx4 pre[NSLOT];
-    auto fetch = [&](int plane) {
-        const floatx4* src = reinterpret_cast<const floatx4*>(x + (int64_t)(plane / planes_per_x) * H * W);
+    auto fetch = [&](int pl) {
+        const floatx4* src = reinterpret_cast<const floatx4*>(x + (int64_t)(pl / planes_per_x) * H * W);
 #pragma unroll
         for (int k = 0; k < NSLOT; ++k)
-            if (k < nin_full || (k == nin_full && lane < nin_rem)) pre[k] = __builtin_nontemporal_load(src + lane + 64 * k);
+            if (in_live(k)) pre[k] = __builtin_nontemporal_load(src + group(k));
+    };
+    auto fill = [&]() {
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k)
+            if (in_live(k)) *reinterpret_cast<floatx4*>(lds + in_slot[k]) = pre[k];
     };
 
-    int plane = blockIdx.x;
-    if (plane < planes) fetch(plane);
+    // The loop is entered with the plane in LDS and the next one's loads in flight; a turn stores its
+    // results first and only then waits for those loads, which are older than the stores.
+    fetch(plane);
+    fill();
+    int next = plane + gridDim.x;
+    if (next < planes) fetch(next);
     wave_lds_sync();
 #pragma unroll 1
-    for (; plane < planes; plane += gridDim.x) {
-#pragma unroll
-        for (int k = 0; k < NSLOT; ++k)
-            if (k < nin_full || (k == nin_full && lane < nin_rem))
-                *reinterpret_cast<floatx4*>(lds + in_slot[k]) = pre[k];
-        const int next = plane + gridDim.x;
-        if (next < planes) fetch(next);
-        wave_lds_sync();
-
+    for (;;) {
         float acc[kB][kB];
 #pragma unroll
         for (int i = 0; i < kB; ++i)
@@ -308,8 +319,15 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
         floatx4* dst = reinterpret_cast<floatx4*>(y + (int64_t)plane * Ho * Wo);
 #pragma unroll
         for (int k = 0; k < NSLOT; ++k)
-            if (k < nout_full || (k == nout_full && lane < nout_rem))
-                __builtin_nontemporal_store(*reinterpret_cast<const floatx4*>(lds + out_slot[k]), dst + lane + 64 * k);
+            if (out_live(k))
+                __builtin_nontemporal_store(*reinterpret_cast<const floatx4*>(lds + out_slot[k]), dst + group(k));
+        wave_lds_sync();
+
+        if (next >= planes) break;
+        plane = next;
+        fill();
+        next = plane + gridDim.x;
+        if (next < planes) fetch(next);
         wave_lds_sync();
     }
 }

@@ -54,6 +54,8 @@ def _load():
     lib.oracle_conv1d.argtypes = [vp] * 4 + [i64] * 5
     lib.oracle_pool1d.restype = ctypes.c_int
     lib.oracle_pool1d.argtypes = [vp] * 3 + [i64] * 4 + [ctypes.c_int]
+    lib.oracle_pool2d.restype = ctypes.c_int
+    lib.oracle_pool2d.argtypes = [vp] * 3 + [i64] * 7 + [ctypes.c_int]
     lib.oracle_conv2d_s8.restype = ctypes.c_int
     lib.oracle_conv2d_s8.argtypes = [vp] * 3 + [i64] * 9
     _lib = lib
@@ -148,6 +150,22 @@ def pool1d(x, window: int, stride: int = 1, mode: int = POOL_AVG):
     rc = _load().oracle_pool1d(_p(x), _p(y), _p(d), rows, length, window, stride, mode)
     if rc:
         raise ValueError(f"oracle_pool1d rejected the arguments (code {rc})")
+    return y, d
+
+
+def pool2d(x, R: int, S: int, stride: int = 1, pad: int = 0, mode: int = POOL_AVG):
+    """x [N, C, H, W] -> (y, D) [N, C, H_out, W_out]; average over zero padding with divisor R*S,
+    maximum over the positions inside the plane."""
+    x = _as(x, np.float32, 4)
+    N, C, H, W = x.shape
+    Ho, Wo = out_dim(H, R, stride, pad), out_dim(W, S, stride, pad)
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("window does not fit the padded input")
+    y = np.empty((N, C, Ho, Wo), np.float64)
+    d = np.empty_like(y)
+    rc = _load().oracle_pool2d(_p(x), _p(y), _p(d), N * C, H, W, R, S, stride, pad, mode)
+    if rc:
+        raise ValueError(f"oracle_pool2d rejected the arguments (code {rc})")
     return y, d
 
 

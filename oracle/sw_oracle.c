@@ -16,6 +16,8 @@
  *   conv1d     y[row,i]    = sum_{j<k}    w[j]         * xz[row,i*st+j-pad]
  *   avg pool   y[row,i]    = (1/window) * sum_{j<window} x[row,i*st+j]
  *   max pool   y[row,i]    = max_{j<window} x[row,i*st+j]
+ *   avg pool2d y[p,i,j]    = (1/(R*S)) * sum_{r,s} xz[p,i*st+r-pad,j*st+s-pad]
+ *   max pool2d y[p,i,j]    = max over the (r,s) whose position lies inside the plane
  *
  * xz is x inside the tensor and 0 outside (zero padding); no filter flip
  * (cross-correlation, as DNN frameworks define "convolution"); output extent
@@ -192,6 +194,53 @@ int oracle_pool1d(const float *x, double *y, double *d,
         }
     }
     return 0;
+}
+
+/* Pooling over R x S windows of each of `planes` H x W planes (abstract: pooling is a sliding sum).
+ * mode 0 = average: the sliding sum of the zero-padded plane times 1/(R*S); the divisor is R*S
+ * everywhere, padded positions count as zeros.  mode 1 = maximum over the window positions that
+ * lie inside the plane (padding never wins); a window with no position inside is an error (3).
+ * d: average -> sum |x| / (R*S); maximum -> |y|. */
+int oracle_pool2d(const float *x, double *y, double *d, int64_t planes, int64_t H, int64_t W,
+                  int64_t R, int64_t S, int64_t stride, int64_t pad, int mode)
+{
+    const int64_t Ho = oracle_out_dim(H, R, stride, pad);
+    const int64_t Wo = oracle_out_dim(W, S, stride, pad);
+    if (planes <= 0 || Ho <= 0 || Wo <= 0 || (mode != 0 && mode != 1)) return 1;
+    int empty = 0;
+#pragma omp parallel for schedule(static) reduction(| : empty)
+    for (int64_t p = 0; p < planes; ++p) {
+        const float *xp = x + p * H * W;
+        for (int64_t i = 0; i < Ho; ++i) {
+            for (int64_t j = 0; j < Wo; ++j) {
+                double acc = 0.0, mag = 0.0, m = 0.0;
+                int64_t inside = 0;
+                for (int64_t r = 0; r < R; ++r) {
+                    const int64_t h = i * stride + r - pad;
+                    if (h < 0 || h >= H) continue;
+                    for (int64_t s = 0; s < S; ++s) {
+                        const int64_t v = j * stride + s - pad;
+                        if (v < 0 || v >= W) continue;
+                        const double e = (double)xp[h * W + v];
+                        acc += e;
+                        mag += fabs(e);
+                        if (inside == 0 || e > m) m = e;
+                        ++inside;
+                    }
+                }
+                const int64_t o = (p * Ho + i) * Wo + j;
+                if (mode == 0) {
+                    y[o] = acc / (double)(R * S);
+                    if (d) d[o] = mag / (double)(R * S);
+                } else {
+                    if (inside == 0) empty = 1;
+                    y[o] = m;
+                    if (d) d[o] = fabs(m);
+                }
+            }
+        }
+    }
+    return empty ? 3 : 0;
 }
 
 /* int8 x int8 -> exact integer sum; returns 2 if any sum leaves the int32 range. */

@@ -8,6 +8,7 @@ import shutil
 import pytest
 
 import test_oracle_pins as pins
+import test_oracle_pool2d_pins as pool_pins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "sw_oracle.c")
@@ -30,6 +31,11 @@ MUTANTS = [
     ("pooling stride ignored", "const float *p = x + row * len + i * stride;", "const float *p = x + row * len + i;", 0),
     ("int8 read as unsigned", "acc += (int64_t)x[((n * C_in + ci) * H + h) * W + v] *", "acc += (int64_t)(uint8_t)x[((n * C_in + ci) * H + h) * W + v] *", 0),
     ("int8 accumulator 16 bits wide", "y[((n * C_out + co) * Ho + i) * Wo + j] = (int32_t)acc;", "y[((n * C_out + co) * Ho + i) * Wo + j] = (int32_t)(int16_t)acc;", 0),
+    ("pool2d average divides by the positions inside", "y[o] = acc / (double)(R * S);", "y[o] = acc / (double)inside;", 0),
+    ("pool2d padding takes part in the maximum", "if (inside == 0 || e > m) m = e;", "if (e > m) m = e;", 0),
+    ("pool2d window transposed", "for (int64_t s = 0; s < S; ++s) {\n                        const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", "for (int64_t s = 0; s < R; ++s) {\n                        const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", 0),
+    ("pool2d stride ignored on columns", "const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", "const int64_t v = j + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", 0),
+    ("pool2d padding sign", "const int64_t h = i * stride + r - pad;\n                    if (h < 0 || h >= H) continue;\n                    for (int64_t s = 0; s < S; ++s) {\n                        const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", "const int64_t h = i * stride + r + pad;\n                    if (h < 0 || h >= H) continue;\n                    for (int64_t s = 0; s < S; ++s) {\n                        const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", 0),
     ("int8 overflow never reported", "return overflow ? 2 : 0;", "return 0;", 0),
 ]
 
@@ -74,6 +80,11 @@ def _battery(o):
     pins.test_s8_overflow_is_refused(o)
     pins.test_out_dim_formula(o)
     pins.test_entry_points_agree_with_each_other(o)
+    for case in pool_pins.CASES:
+        pool_pins.test_average_matches_scatter_brute_force(o, case)
+        pool_pins.test_maximum_matches_slices_of_a_minus_infinity_padded_copy(o, case)
+    pool_pins.test_closed_forms(o)
+    pool_pins.test_special_cases_reduce_to_the_other_entry_points(o)
 
 
 def test_unmutated_copy_passes_the_battery(tmp_path, oracle):

@@ -75,6 +75,23 @@ int sw_pool1d(const float* x, float* y, int64_t rows, int64_t len,
               int window, int stride, int mode, void* hip_stream);
 
 /*
+ * 2-D pooling over R x S windows of every plane, again as a sliding window sum
+ * (paper, abstract: pooling and convolution share the kernel structure).
+ *     avg: y[n,c,i,j] = (1/(R*S)) * sum_{r,s} xz[n,c,i*stride+r-pad, j*stride+s-pad]
+ *     max: y[n,c,i,j] = max over the (r,s) whose position lies inside the plane
+ * The average is the sliding sum of the zero-padded plane with the constant
+ * divisor R*S (padded positions count as zeros); padding never wins a maximum.
+ * x: [N,C,H,W];  y: [N,C,H_out,W_out], extents by sw_out_dim.
+ * Supported: R,S <= 64 and 2*pad <= min(R,S) (so that no window lies wholly in
+ * the padding), else SW_ERR_UNSUPPORTED; mode as in sw_pool1d.  2x2 stride 2 and
+ * 3x3 stride 1 or 2 with W % 4 == 0 and 16-byte aligned x run in the register-only
+ * kernel, every other case in the one-thread-per-output kernel.
+ * The maximum is bit-exact; NaN inputs are outside the contract.
+ */
+int sw_pool2d(const float* x, float* y, int N, int C, int H, int W, int R, int S,
+              int stride, int pad, int mode, void* hip_stream);
+
+/*
  * 2-D convolution (paper, section 2: the 2-D sliding window convolution; for
  * C_in > 1 every tap is a small C_out x C_in matrix product accumulated into
  * the output tile, the re-formulation section 3 asks for).

@@ -16,7 +16,7 @@ SW_OK = 0
 SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN, SW_ERR_ALIAS, SW_ERR_LAUNCH = 1, 2, 3, 4, 5, 6
 SW_POOL_AVG, SW_POOL_MAX = 0, 1
 
-EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
+EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
            "sw_out_dim", "sw_workspace_bytes", "sw_status_string", "sw_version")
 
 _lib = None
@@ -41,6 +41,8 @@ def lib() -> ctypes.CDLL:
     L.sw_conv1d.argtypes = [vp, vp, vp, i64, i64, i32, i32, i32, vp]
     L.sw_pool1d.restype = i32
     L.sw_pool1d.argtypes = [vp, vp, i64, i64, i32, i32, i32, vp]
+    L.sw_pool2d.restype = i32
+    L.sw_pool2d.argtypes = [vp, vp] + [i32] * 9 + [vp]
     L.sw_conv2d.restype = i32
     L.sw_conv2d.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.sw_conv2d_depthwise.restype = i32
@@ -127,6 +129,20 @@ def sw_pool1d(x, window: int, stride: int = 1, mode: int = SW_POOL_AVG, out=None
     rc = lib().sw_pool1d(_dev(x, torch.float32, 2, "x"), _dev(out, torch.float32, 2, "y"), rows, length,
                          window, stride, mode, _stream(stream))
     _check(rc, "sw_pool1d")
+    return out
+
+
+def sw_pool2d(x, R: int, S: int, stride: int = 1, pad: int = 0, mode: int = SW_POOL_AVG, out=None, stream=None):
+    """x [N,C,H,W] fp32 -> y [N,C,H_out,W_out] fp32; mode SW_POOL_AVG (divisor R*S) or SW_POOL_MAX."""
+    import torch
+
+    N, C, H, W = x.shape
+    if out is None:
+        out = torch.empty(_out_shape("sw_pool2d", N, C, sw_out_dim(H, R, stride, pad), sw_out_dim(W, S, stride, pad)),
+                          dtype=torch.float32, device=x.device)
+    rc = lib().sw_pool2d(_dev(x, torch.float32, 4, "x"), _dev(out, torch.float32, 4, "y"), N, C, H, W, R, S,
+                         stride, pad, mode, _stream(stream))
+    _check(rc, "sw_pool2d")
     return out
 
 

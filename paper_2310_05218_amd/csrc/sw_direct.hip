@@ -4,6 +4,8 @@
 // nothing but the output (paper, section 2).
 #include "swconv_internal.h"
 
+#include <cmath>
+
 namespace swconv {
 
 namespace {
@@ -82,6 +84,35 @@ __global__ __launch_bounds__(kThreads) void direct_conv2d_kernel(const TI* __res
     }
 }
 
+// 2-D pooling, one thread per output: the average sums the zero-padded window and scales by 1/(R*S),
+// the maximum runs over the window positions inside the plane.
+template <bool MAXIMUM>
+__global__ __launch_bounds__(kThreads) void direct_pool2d_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                                 int64_t planes, int H, int W, int R, int S,
+                                                                 int stride, int pad, int Ho, int Wo)
+{
+    const int64_t plane_o = (int64_t)Ho * Wo;
+    const int64_t total = planes * plane_o;
+    const float scale = 1.0f / (float)(R * S);
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total;
+         o += (int64_t)gridDim.x * kThreads) {
+        const int64_t p = o / plane_o;
+        const int pix = (int)(o - p * plane_o);
+        const int i = pix / Wo, j = pix - i * Wo;
+        const float* xp = x + p * H * W;
+        const int h0 = i * stride - pad, v0 = j * stride - pad;
+        const int r_lo = h0 < 0 ? -h0 : 0, r_hi = H - h0 < R ? H - h0 : R;
+        const int s_lo = v0 < 0 ? -v0 : 0, s_hi = W - v0 < S ? W - v0 : S;
+        float acc = MAXIMUM ? -INFINITY : 0.f;
+        for (int r = r_lo; r < r_hi; ++r)
+            for (int q = s_lo; q < s_hi; ++q) {
+                const float e = xp[(int64_t)(h0 + r) * W + v0 + q];
+                acc = MAXIMUM ? fmaxf(acc, e) : acc + e;
+            }
+        y[o] = MAXIMUM ? acc : acc * scale;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
@@ -124,6 +155,19 @@ hipError_t launch_direct_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y,
     const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
     hipLaunchKernelGGL((direct_conv2d_kernel<int8_t, int32_t, false>), dim3(grid), dim3(kThreads), 0, st, x,
                        w, y, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_direct_pool2d(const float* x, float* y, int64_t planes, int H, int W, int R, int S, int stride,
+                                int pad, int Ho, int Wo, bool maximum, hipStream_t st)
+{
+    const int grid = grid_for(planes * Ho * Wo);
+    if (maximum)
+        hipLaunchKernelGGL(direct_pool2d_kernel<true>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
+                           stride, pad, Ho, Wo);
+    else
+        hipLaunchKernelGGL(direct_pool2d_kernel<false>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
+                           stride, pad, Ho, Wo);
     return hipGetLastError();
 }
 

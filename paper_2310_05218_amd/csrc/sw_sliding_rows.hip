@@ -1,46 +1,69 @@
-// 2-D sliding window sums with one filter per plane, stride 1, small fixed filters (3x3, 5x5), held
-// entirely in registers: no LDS (paper, section 2: the "custom" kernels for widths 3 and 5).
+// 2-D sliding window sums with one filter per plane (or none: pooling), small fixed windows, stride 1
+// or 2, held entirely in registers: no LDS (paper, section 2: the "custom" kernels for small fixed
+// sizes; abstract: pooling and convolution are the same sliding sum).
 //
 // A wavefront owns a strip of 256 input columns (one aligned 16-byte load per lane and input row: 1 KB
-// per row, fully coalesced) and a band of TR output rows.  A lane's four outputs of a row sit at the
-// same columns as its four inputs, so loads and stores are both aligned; the taps that reach across the
-// lane boundary take `pad` values from the left neighbour and S - 1 - pad from the right one, moved with
-// DPP wavefront shifts (v_mov_b32_dpp wave_shr:1 / wave_shl:1) -- the row shift of the sliding sum.
+// per row, fully coalesced) and a band of TR output rows.  At stride 1 a lane's four outputs of a row
+// sit at the same columns as its four inputs, at stride 2 its two outputs sit at half that column, so
+// loads and stores are both aligned; the taps that reach across the lane boundary take `pad` values
+// from the left neighbour and the rest from the right one, moved with DPP wavefront shifts
+// (v_mov_b32_dpp wave_shr:1 / wave_shl:1) -- the row shift of the sliding sum.
 // Vertically every input row is loaded once per band and accumulated into each output row it meets
 // (choice of accumulator row).  Strips overlap by one lane on each inner side, because the edge lanes
-// have no neighbour to take the halo from; at the image border the shifted-in zero is the padding.
-// All TR + R - 1 row loads of a band are issued before the first use, so a band costs one memory
-// round trip: this is the kernel for planes that are too few or too ragged for the 56 x 56 tile kernel.
+// have no neighbour to take the halo from; at the image border the shifted-in value is the padding
+// itself (zero for sums, minus infinity for the maximum, which padding must never win).
+// All row loads of a band are issued before the first use, so a band costs one memory round trip: this
+// is the kernel for planes that are too few or too ragged for the 56 x 56 tile kernel.
 #include "swconv_internal.h"
+
+#include <cmath>
 
 namespace swconv {
 
 namespace {
 
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 constexpr int kStripIn = 256;             // input columns per wavefront
-constexpr int kStripOut0 = 252;           // output columns of the first strip (lanes 0..62)
-constexpr int kStripOut = 248;            // ... of the following strips (lanes 1..62)
+constexpr int kStripFirst = 252;          // input columns whose lanes have both neighbours, first strip
+constexpr int kStripStep = 248;           // distance between strip origins (lanes 1..62 of later strips)
 
-__device__ __forceinline__ float from_left(float v)   // lane i receives lane i-1's value, lane 0 receives 0
+enum RowsOp { ROWS_CONV = 0, ROWS_AVG = 1, ROWS_MAX = 2 };
+
+// lane i receives lane i-1's value (from_left) or lane i+1's (from_right); the lane without such a
+// neighbour receives FILL
+template <int OP>
+__device__ __forceinline__ float from_left(float v)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x138, 0xF, 0xF, true));
+    if constexpr (OP == ROWS_MAX)
+        return __int_as_float(__builtin_amdgcn_update_dpp((int)0xff800000, __float_as_int(v), 0x138, 0xF, 0xF, false));
+    else
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x138, 0xF, 0xF, true));
 }
-__device__ __forceinline__ float from_right(float v)  // lane i receives lane i+1's value, lane 63 receives 0
+template <int OP>
+__device__ __forceinline__ float from_right(float v)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xF, 0xF, true));
+    if constexpr (OP == ROWS_MAX)
+        return __int_as_float(__builtin_amdgcn_update_dpp((int)0xff800000, __float_as_int(v), 0x130, 0xF, 0xF, false));
+    else
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x130, 0xF, 0xF, true));
 }
 
-// PADC: padding (compile time, 0 <= PADC <= S - 1, PADC <= 4, S - 1 - PADC <= 4).
-template <int R, int S, int PADC, int TR>
+// PADC: padding (compile time).  ST: stride, 1 or 2.  OP: weighted sum, average or maximum.
+template <int R, int S, int PADC, int TR, int ST, int OP>
 __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restrict__ x,
                                                            const float* __restrict__ w,
                                                            float* __restrict__ y, int planes_per_x,
                                                            int n_filters, int H, int W, int Ho, int Wo,
                                                            int strips, int bands, int64_t waves, int y_vec_ok)
 {
-    constexpr int LEFT = PADC, RIGHT = S - 1 - PADC;
+    constexpr int NOUT = 4 / ST;                                   // outputs per lane and output row
+    constexpr int LEFT = PADC;
+    constexpr int RIGHT = ST * (NOUT - 1) + S - 1 - PADC - 3 > 0 ? ST * (NOUT - 1) + S - 1 - PADC - 3 : 0;
+    constexpr int NIN = ST * (TR - 1) + R;                         // input rows of a band
+    static_assert(LEFT <= 4 && RIGHT <= 4, "halo wider than one neighbour lane");
+    const float FILL = OP == ROWS_MAX ? -INFINITY : 0.f;
     const int lane = threadIdx.x & 63;
     const int64_t wv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (wv >= waves) return;
@@ -49,92 +72,113 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
     const int band = (int)(t % bands);
     const int plane = (int)(t / bands);
 
-    const int c0 = strip * kStripOut;                 // first input column of the strip
-    const int col = c0 + 4 * lane;                    // this lane's columns (inputs and outputs)
+    const int c0 = strip * kStripStep;                // first input column of the strip
+    const int col = c0 + 4 * lane;                    // this lane's input columns
+    const int ocol = col / ST;                        // its first output column
     const int i0 = band * TR;                         // first output row of the band
     const float* xp = x + (int64_t)(plane / planes_per_x) * H * W;
-    const float* wf = w + (int64_t)(plane % n_filters) * R * S;
     float* yp = y + (int64_t)plane * Ho * Wo;
 
     float wr[R * S];
+    if constexpr (OP == ROWS_CONV) {
+        const float* wf = w + (int64_t)(plane % n_filters) * R * S;
 #pragma unroll
-    for (int k = 0; k < R * S; ++k) wr[k] = wf[k];
+        for (int k = 0; k < R * S; ++k) wr[k] = wf[k];
+    }
 
-    // every input row of the band, one aligned 16-byte load each (zero outside the image)
-    floatx4 in[TR + R - 1];
+    // every input row of the band, one aligned 16-byte load each (padding outside the image)
+    floatx4 in[NIN];
 #pragma unroll
-    for (int e = 0; e < TR + R - 1; ++e) {
-        const int gr = i0 - PADC + e;
-        in[e] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int e = 0; e < NIN; ++e) {
+        const int gr = ST * i0 - PADC + e;
+        in[e] = floatx4{FILL, FILL, FILL, FILL};
         if (gr >= 0 && gr < H && col < W) in[e] = *reinterpret_cast<const floatx4*>(xp + (int64_t)gr * W + col);
     }
 
-    float acc[TR][4];
+    float acc[TR][NOUT];
 #pragma unroll
     for (int i = 0; i < TR; ++i)
 #pragma unroll
-        for (int p = 0; p < 4; ++p) acc[i][p] = 0.f;
+        for (int p = 0; p < NOUT; ++p) acc[i][p] = FILL;
 
 #pragma unroll
-    for (int e = 0; e < TR + R - 1; ++e) {
+    for (int e = 0; e < NIN; ++e) {
         // v[LEFT + c] = input column col + c, c = -LEFT .. 3 + RIGHT
         float v[LEFT + 4 + RIGHT];
         v[LEFT + 0] = in[e].x; v[LEFT + 1] = in[e].y; v[LEFT + 2] = in[e].z; v[LEFT + 3] = in[e].w;
 #pragma unroll
-        for (int c = 0; c < LEFT; ++c) v[LEFT - 1 - c] = from_left(in[e][3 - c]);
+        for (int c = 0; c < LEFT; ++c) v[LEFT - 1 - c] = from_left<OP>(in[e][3 - c]);
 #pragma unroll
-        for (int c = 0; c < RIGHT; ++c) v[LEFT + 4 + c] = from_right(in[e][c]);
+        for (int c = 0; c < RIGHT; ++c) v[LEFT + 4 + c] = from_right<OP>(in[e][c]);
 #pragma unroll
         for (int orow = 0; orow < TR; ++orow) {
-            const int r = e - orow;
+            const int r = e - ST * orow;
             if (r < 0 || r >= R) continue;
 #pragma unroll
             for (int q = 0; q < S; ++q)
 #pragma unroll
-                for (int p = 0; p < 4; ++p) acc[orow][p] = fmaf(wr[r * S + q], v[p + q], acc[orow][p]);
+                for (int p = 0; p < NOUT; ++p) {
+                    const float e_in = v[ST * p + q];
+                    if constexpr (OP == ROWS_CONV) acc[orow][p] = fmaf(wr[r * S + q], e_in, acc[orow][p]);
+                    else if constexpr (OP == ROWS_AVG) acc[orow][p] += e_in;
+                    else acc[orow][p] = fmaxf(acc[orow][p], e_in);
+                }
         }
     }
 
     // lanes without a neighbour inside the strip have no halo: they only feed their neighbours, unless
-    // the missing neighbour lies outside the image, where the shifted-in zero is the padding itself
-    const bool left_ok = LEFT == 0 || lane > 0 || c0 == 0;
-    const bool right_ok = RIGHT == 0 || lane < 63 || c0 + kStripIn >= W;
-    if (!left_ok || !right_ok || col >= Wo) return;
+    // the missing neighbour lies outside the image, where the shifted-in value is the padding itself
+    const bool left_ok = lane > 0 || c0 == 0;
+    const bool right_ok = lane < 63 || c0 + kStripIn >= W;
+    if (!left_ok || !right_ok || ocol >= Wo) return;
+    constexpr float kScale = 1.0f / (float)(R * S);
 #pragma unroll
     for (int orow = 0; orow < TR; ++orow) {
         const int oi = i0 + orow;
         if (oi >= Ho) break;
-        float* dst = yp + (int64_t)oi * Wo + col;
-        if (y_vec_ok && col + 3 < Wo) {
-            *reinterpret_cast<floatx4*>(dst) = floatx4{acc[orow][0], acc[orow][1], acc[orow][2], acc[orow][3]};
+        if constexpr (OP == ROWS_AVG) {
+#pragma unroll
+            for (int p = 0; p < NOUT; ++p) acc[orow][p] *= kScale;
+        }
+        float* dst = yp + (int64_t)oi * Wo + ocol;
+        if (y_vec_ok && ocol + NOUT - 1 < Wo) {
+            if constexpr (NOUT == 4)
+                *reinterpret_cast<floatx4*>(dst) = floatx4{acc[orow][0], acc[orow][1], acc[orow][2], acc[orow][3]};
+            else
+                *reinterpret_cast<floatx2*>(dst) = floatx2{acc[orow][0], acc[orow][1]};
         } else {
 #pragma unroll
-            for (int p = 0; p < 4; ++p)
-                if (col + p < Wo) dst[p] = acc[orow][p];
+            for (int p = 0; p < NOUT; ++p)
+                if (ocol + p < Wo) dst[p] = acc[orow][p];
         }
     }
 }
 
-template <int R, int S, int PADC>
+template <int R, int S, int PADC, int ST, int OP>
 hipError_t launch_rows(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
                        int H, int W, int Ho, int Wo, hipStream_t st)
 {
-    const int strips = Wo <= kStripOut0 + 4 && W <= kStripIn ? 1 : 1 + (Wo - kStripOut0 + kStripOut - 1) / kStripOut;
-    const int y_vec_ok = reinterpret_cast<uintptr_t>(y) % 16 == 0 && Wo % 4 == 0;
+    // input columns whose lanes produce an output
+    const int64_t need = (int64_t)ST * Wo;
+    const int Wc = (int)(need < W ? (need + 3) & ~(int64_t)3 : W);
+    const int strips = W <= kStripIn || Wc <= kStripFirst ? 1 : 1 + (Wc - kStripFirst + kStripStep - 1) / kStripStep;
+    constexpr int NOUT = 4 / ST;
+    const int y_vec_ok = reinterpret_cast<uintptr_t>(y) % (4 * NOUT) == 0 && Wo % NOUT == 0;
     // short bands when the launch would otherwise leave most of the chip idle
-    const bool small = planes * strips * ((Ho + 7) / 8) < 2048;
-    const int TR = small ? 4 : 8;
+    constexpr int TR_BIG = 8 / ST, TR_SMALL = 4 / ST;
+    const bool small = planes * strips * ((Ho + TR_BIG - 1) / TR_BIG) < 2048;
+    const int TR = small ? TR_SMALL : TR_BIG;
     const int bands = (Ho + TR - 1) / TR;
     const int64_t waves = planes * strips * bands;
     const int64_t blocks = (waves + 3) / 4;
     if (blocks > 2147483647LL) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(256);
     if (small)
-        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, 4>), grid, block, 0, st, x, w, y, planes_per_x, n_filters,
-                           H, W, Ho, Wo, strips, bands, waves, y_vec_ok);
+        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_SMALL, ST, OP>), grid, block, 0, st, x, w, y,
+                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, y_vec_ok);
     else
-        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, 8>), grid, block, 0, st, x, w, y, planes_per_x, n_filters,
-                           H, W, Ho, Wo, strips, bands, waves, y_vec_ok);
+        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_BIG, ST, OP>), grid, block, 0, st, x, w, y,
+                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, y_vec_ok);
     return hipGetLastError();
 }
 
@@ -143,22 +187,45 @@ hipError_t launch_rows(const float* x, const float* w, float* y, int64_t planes,
 bool sliding_rows_supported(const float* x, int H, int W, int R, int S, int stride, int pad)
 {
     (void)H;
-    if (stride != 1 || R != S || (R != 3 && R != 5) || pad > (R - 1) / 2 || pad < 0) return false;
+    if ((stride != 1 && stride != 2) || R != S || (R != 3 && R != 5) || pad > (R - 1) / 2 || pad < 0) return false;
     // (padding beyond (R-1)/2 would need more than the compiled halo widths)
     return W % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0;
 }
 
 hipError_t launch_sliding_rows(const float* x, const float* w, float* y, int64_t planes, int planes_per_x,
-                               int n_filters, int H, int W, int R, int S, int pad, int Ho, int Wo, hipStream_t st)
+                               int n_filters, int H, int W, int R, int S, int stride, int pad, int Ho, int Wo,
+                               hipStream_t st)
 {
     (void)S;
-#define SW_ROWS(RC, PC) return launch_rows<RC, RC, PC>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st)
-    if (R == 3 && pad == 0) SW_ROWS(3, 0);
-    if (R == 3 && pad == 1) SW_ROWS(3, 1);
-    if (R == 5 && pad == 0) SW_ROWS(5, 0);
-    if (R == 5 && pad == 1) SW_ROWS(5, 1);
-    if (R == 5 && pad == 2) SW_ROWS(5, 2);
+#define SW_ROWS(RC, PC)                                                                                        \
+    if (R == RC && pad == PC) {                                                                                \
+        if (stride == 1)                                                                                       \
+            return launch_rows<RC, RC, PC, 1, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st); \
+        return launch_rows<RC, RC, PC, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);     \
+    }
+    SW_ROWS(3, 0) SW_ROWS(3, 1) SW_ROWS(5, 0) SW_ROWS(5, 1) SW_ROWS(5, 2)
 #undef SW_ROWS
+    return hipErrorInvalidValue;
+}
+
+// Pooling windows with a register-only kernel: 2x2 and 3x3, stride 1 or 2, padding up to half the window.
+bool pool_rows_supported(const float* x, int W, int R, int S, int stride, int pad)
+{
+    if ((stride != 1 && stride != 2) || R != S || (R != 2 && R != 3) || pad < 0 || pad > (R == 3 ? 1 : 0)) return false;
+    if (R == 2 && stride == 1) return false;       // (no compiled variant; the direct kernel takes it)
+    return W % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0;
+}
+
+hipError_t launch_pool_rows(const float* x, float* y, int64_t planes, int H, int W, int R, int stride, int pad,
+                            int Ho, int Wo, bool maximum, hipStream_t st)
+{
+#define SW_POOL(RC, PC, SC)                                                                                    \
+    if (R == RC && pad == PC && stride == SC) {                                                                \
+        if (maximum) return launch_rows<RC, RC, PC, SC, ROWS_MAX>(x, nullptr, y, planes, 1, 1, H, W, Ho, Wo, st); \
+        return launch_rows<RC, RC, PC, SC, ROWS_AVG>(x, nullptr, y, planes, 1, 1, H, W, Ho, Wo, st);           \
+    }
+    SW_POOL(2, 0, 2) SW_POOL(3, 0, 1) SW_POOL(3, 1, 1) SW_POOL(3, 0, 2) SW_POOL(3, 1, 2)
+#undef SW_POOL
     return hipErrorInvalidValue;
 }
 

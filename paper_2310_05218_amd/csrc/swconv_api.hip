@@ -47,11 +47,11 @@ int launch_status(hipError_t e) { return e == hipSuccess ? SW_OK : SW_ERR_LAUNCH
 int run_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
               const Conv2dShape& s, bool depthwise, hipStream_t st)
 {
-    if (!force_direct() && s.stride == 1) {
-        const bool whole = sliding_plane_whole(x, y, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) && planes >= 512;
+    if (!force_direct()) {
+        const bool whole = s.stride == 1 && sliding_plane_whole(x, y, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) && planes >= 512;
         if (!whole && !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad))
             return launch_status(launch_sliding_rows(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
-                                                     s.pad, s.Ho, s.Wo, st));
+                                                     s.stride, s.pad, s.Ho, s.Wo, st));
         if (sliding_plane_supported(s.H, s.W, s.R, s.S, s.stride, s.pad) &&
             sliding_plane_worthwhile(planes, s.Ho, s.Wo, s.R, s.S))
             return launch_status(launch_sliding_plane(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
@@ -145,6 +145,28 @@ int sw_pool1d(const float* x, float* y, int64_t rows, int64_t len, int window, i
     if (mode != SW_POOL_AVG && mode != SW_POOL_MAX) return x && y ? SW_ERR_UNSUPPORTED : SW_ERR_NULL;
     return run_1d(x, nullptr, y, rows, len, window, stride, 0, mode == SW_POOL_AVG ? OP_AVG : OP_MAX,
                   hip_stream);
+}
+
+int sw_pool2d(const float* x, float* y, int N, int C, int H, int W, int R, int S, int stride, int pad, int mode,
+              void* hip_stream)
+{
+    if (!x || !y) return SW_ERR_NULL;
+    if (N <= 0 || C <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return SW_ERR_SHAPE;
+    const int64_t Ho = sw_out_dim(H, R, stride, pad), Wo = sw_out_dim(W, S, stride, pad);
+    if (Ho <= 0 || Wo <= 0) return SW_ERR_SHAPE;
+    const int64_t planes = (int64_t)N * C;
+    const int64_t nx = planes * H * W, ny = planes * Ho * Wo;
+    if (nx > kMaxElems || ny > kMaxElems) return SW_ERR_SHAPE;
+    if (mode != SW_POOL_AVG && mode != SW_POOL_MAX) return SW_ERR_UNSUPPORTED;
+    if (R > kMaxFilter2D || S > kMaxFilter2D) return SW_ERR_UNSUPPORTED;
+    if (2 * pad > (R < S ? R : S)) return SW_ERR_UNSUPPORTED;   // a window could lie wholly in the padding
+    if (misaligned(x, 4) || misaligned(y, 4)) return SW_ERR_ALIGN;
+    if (overlaps(y, ny * 4, x, nx * 4)) return SW_ERR_ALIAS;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const bool maximum = mode == SW_POOL_MAX;
+    if (!force_direct() && pool_rows_supported(x, W, R, S, stride, pad))
+        return launch_status(launch_pool_rows(x, y, planes, H, W, R, stride, pad, (int)Ho, (int)Wo, maximum, st));
+    return launch_status(launch_direct_pool2d(x, y, planes, H, W, R, S, stride, pad, (int)Ho, (int)Wo, maximum, st));
 }
 
 int sw_conv2d(const float* x, const float* w, float* y, int N, int C_in, int C_out, int H, int W, int R,

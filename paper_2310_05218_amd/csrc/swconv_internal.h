@@ -31,6 +31,8 @@ hipError_t launch_direct_conv2d_f32(const float* x, const float* w, float* y, co
                                     bool depthwise, hipStream_t st);
 hipError_t launch_direct_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s,
                                    hipStream_t st);
+hipError_t launch_direct_pool2d(const float* x, float* y, int64_t planes, int H, int W, int R, int S, int stride,
+                                int pad, int Ho, int Wo, bool maximum, hipStream_t st);
 
 // ---- sliding 1-D kernel (stride 1): LDS tile + halo, register window ---------------------------
 bool       sliding_1d_supported(int64_t len, int k, int stride, int pad);
@@ -44,10 +46,15 @@ bool       sliding_plane_supported(int H, int W, int R, int S, int stride, int p
 bool       sliding_plane_worthwhile(int64_t planes, int Ho, int Wo, int R, int S);
 bool       sliding_plane_whole(const float* x, const float* y, int W, int R, int S, int pad, int Ho, int Wo);
 
-// ---- sliding rows kernel (stride 1, 3x3 / 5x5): registers only, DPP wavefront shifts for the halo -------
+// ---- sliding rows kernel (stride 1 or 2; 3x3 / 5x5 filters, 2x2 / 3x3 pooling windows): registers only,
+// DPP wavefront shifts for the halo ---------------------------------------------------------------
 bool       sliding_rows_supported(const float* x, int H, int W, int R, int S, int stride, int pad);
 hipError_t launch_sliding_rows(const float* x, const float* w, float* y, int64_t planes, int planes_per_x,
-                               int n_filters, int H, int W, int R, int S, int pad, int Ho, int Wo, hipStream_t st);
+                               int n_filters, int H, int W, int R, int S, int stride, int pad, int Ho, int Wo,
+                               hipStream_t st);
+bool       pool_rows_supported(const float* x, int W, int R, int S, int stride, int pad);
+hipError_t launch_pool_rows(const float* x, float* y, int64_t planes, int H, int W, int R, int stride, int pad,
+                            int Ho, int Wo, bool maximum, hipStream_t st);
 hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes,
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st);

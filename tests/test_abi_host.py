@@ -75,6 +75,26 @@ def test_pool1d_argument_errors(L):
     assert f(X, X, 4, 100, 8, 1, 0, None) == B.SW_ERR_ALIAS
 
 
+def test_pool2d_argument_errors(L):
+    f = L.sw_pool2d
+    ok = (2, 16, 8, 8, 3, 3, 2, 1)
+    assert f(None, Y, *ok, 0, None) == B.SW_ERR_NULL
+    assert f(X, None, *ok, 1, None) == B.SW_ERR_NULL
+    for i in range(7):                       # N, C, H, W, R, S, stride <= 0
+        bad = list(ok)
+        bad[i] = 0
+        assert f(X, Y, *bad, 0, None) == B.SW_ERR_SHAPE, i
+    assert f(X, Y, 2, 16, 8, 8, 3, 3, 2, -1, 0, None) == B.SW_ERR_SHAPE
+    assert f(X, Y, 2, 16, 2, 8, 5, 3, 1, 1, 0, None) == B.SW_ERR_SHAPE          # window > padded plane
+    assert f(X, Y, 4096, 4096, 64, 64, 3, 3, 1, 1, 0, None) == B.SW_ERR_SHAPE   # > 2^31-1 elements
+    assert f(X, Y, *ok, 2, None) == B.SW_ERR_UNSUPPORTED                        # unknown mode
+    assert f(X, Y, 2, 16, 100, 100, 65, 3, 1, 1, 0, None) == B.SW_ERR_UNSUPPORTED
+    assert f(X, Y, 2, 16, 8, 8, 3, 3, 1, 2, 1, None) == B.SW_ERR_UNSUPPORTED    # 2*pad > window
+    assert f(X + 2, Y, *ok, 0, None) == B.SW_ERR_ALIGN
+    assert f(X, Y + 1, *ok, 0, None) == B.SW_ERR_ALIGN
+    assert f(X, X + 64, *ok, 0, None) == B.SW_ERR_ALIAS
+
+
 @pytest.mark.parametrize("name", ["sw_conv2d", "sw_conv2d_s8"])
 def test_conv2d_argument_errors(L, name):
     f = getattr(L, name)

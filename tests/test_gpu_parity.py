@@ -141,7 +141,15 @@ PLANE_CASES = [
     (1, 3, 19, 256, 5, 5, 1, 1),
     (1, 2, 11, 252, 5, 5, 1, 0),
     (8, 64, 64, 64, 3, 3, 1, 1),    # rows kernel, 8-row bands
-    (1, 3, 21, 23, 3, 3, 2, 1),     # strided: direct kernel
+    (1, 3, 21, 23, 3, 3, 2, 1),     # strided, W not a multiple of 4: direct kernel
+    (2, 3, 56, 56, 3, 3, 2, 1),     # strided rows kernel
+    (1, 2, 57, 60, 3, 3, 2, 0),
+    (1, 2, 30, 64, 5, 5, 2, 2),
+    (1, 3, 23, 260, 5, 5, 2, 1),    # ... a second strip of one lane
+    (1, 2, 21, 520, 3, 3, 2, 1),    # ... three strips
+    (1, 1, 18, 252, 5, 5, 2, 0),
+    (4, 64, 112, 112, 3, 3, 2, 1),  # ... 4-row bands
+    (1, 2, 9, 8, 3, 3, 3, 1),       # stride 3: direct kernel
     (1, 2, 7, 5, 7, 5, 1, 0),
     (1, 2, 16, 16, 3, 3, 1, 2),     # padding wider than the usual (R-1)/2
 ]
@@ -182,6 +190,69 @@ def test_conv2d_single_input_channel(torch, sw, oracle, case, batch):
     y_ref, d = oracle.conv2d(x, w, stride, pad)
     y = sw.sw_conv2d(dev(torch, x), dev(torch, w), stride, pad)
     assert_f32_parity(y.cpu().numpy(), y_ref, d, f"conv2d C_in=1 {case}")
+
+
+# ----------------------------------------------------------------------------- 2-D pooling
+
+POOL2D_CASES = [
+    # N, C, H, W, R, S, stride, pad
+    (1, 1, 2, 4, 2, 2, 2, 0),       # a row of two outputs
+    (2, 3, 56, 56, 2, 2, 2, 0),     # register-only kernel
+    (2, 3, 56, 56, 3, 3, 2, 1),
+    (1, 2, 57, 60, 3, 3, 2, 0),
+    (1, 2, 31, 64, 3, 3, 1, 1),
+    (1, 2, 30, 44, 3, 3, 1, 0),
+    (1, 2, 21, 520, 3, 3, 2, 1),    # ... three strips
+    (1, 3, 23, 260, 2, 2, 2, 0),    # ... a second strip of one lane
+    (1, 1, 19, 256, 3, 3, 1, 1),
+    (4, 64, 112, 112, 3, 3, 2, 1),  # ... long bands
+    (2, 16, 112, 112, 2, 2, 2, 0),
+    (1, 3, 21, 23, 3, 3, 2, 1),     # W not a multiple of 4: one thread per output
+    (1, 2, 20, 20, 2, 2, 1, 0),
+    (1, 2, 20, 24, 5, 3, 2, 1),
+    (1, 2, 14, 14, 14, 14, 1, 0),   # global pooling
+    (1, 2, 17, 16, 4, 4, 4, 2),
+    (1, 2, 9, 12, 1, 1, 2, 0),
+]
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("case", POOL2D_CASES)
+def test_pool2d(torch, sw, oracle, case, mode):
+    N, C, H, W, R, S, stride, pad = case
+    x = inputs.normal_f32((N, C, H, W), 2101)
+    if mode == 1:
+        x = x - 3.0          # mostly negative: padding must not win the maximum with a zero
+    y_ref, d = oracle.pool2d(x, R, S, stride, pad, mode)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_pool2d(dev(torch, x), R, S, stride, pad, mode, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    y = out.cpu().numpy()
+    if mode == 1:
+        assert np.array_equal(y.astype(np.float64), y_ref), f"max pool2d {case}"
+    else:
+        assert_f32_parity(y, y_ref, d, f"avg pool2d {case}")
+
+
+def test_pool2d_misaligned_views(torch, sw, oracle):
+    """Input and output that start 4 bytes off a 16-byte boundary: the one-thread-per-output kernel (input)
+    and the scalar stores of the register-only kernel (output) give the same values."""
+    x = inputs.normal_f32((2, 4, 24, 32), 2102)
+    for mode in (0, 1):
+        y_ref, d = oracle.pool2d(x, 3, 3, 2, 1, mode)
+        xb = torch.empty(x.size + 1, dtype=torch.float32, device="cuda")
+        xv = xb[1:].view(x.shape)
+        xv.copy_(torch.from_numpy(x))
+        y1 = sw.sw_pool2d(xv, 3, 3, 2, 1, mode).cpu().numpy()
+        yb = torch.empty(y_ref.size + 1, dtype=torch.float32, device="cuda")
+        yv = yb[1:].view(y_ref.shape)
+        sw.sw_pool2d(dev(torch, x), 3, 3, 2, 1, mode, out=yv)
+        for y in (y1, yv.cpu().numpy()):
+            if mode == 1:
+                assert np.array_equal(y.astype(np.float64), y_ref)
+            else:
+                assert_f32_parity(y, y_ref, d, "avg pool2d, misaligned")
 
 
 def test_workload1_full_size(torch, sw, oracle):

@@ -200,6 +200,63 @@ def filter_size_sweep(torch, sw):
     return {"sweep": "depthwise-shaped 32x64x56x56 fp32, square filter, stride 1, same padding", "rows": rows}
 
 
+def strided_and_pooling_table(torch, sw):
+    """2-D pooling and stride-2 layers of common CNN shapes (fp32 N(0,1) activations), timed cold like the
+    step's kernels; each is first checked against the CPU oracle on two planes.  All are bound by HBM:
+    bytes = input once + output once (+ filters)."""
+    import numpy as np
+
+    import oracle
+    from paper_2310_05218_amd import inputs
+
+    layers = [  # name, kind, (N, C, H, W), R, stride, pad
+        ("maxpool_3x3_s2", "max", (32, 64, 112, 112), 3, 2, 1),
+        ("maxpool_2x2_s2", "max", (32, 64, 112, 112), 2, 2, 0),
+        ("avgpool_2x2_s2", "avg", (32, 64, 112, 112), 2, 2, 0),
+        ("avgpool_3x3_s1", "avg", (32, 64, 56, 56), 3, 1, 1),
+        ("depthwise_3x3_s2", "dw", (32, 128, 112, 112), 3, 2, 1),
+        ("depthwise_5x5_s2", "dw", (32, 128, 112, 112), 5, 2, 2),
+        ("global_avgpool_7x7", "avg", (32, 2048, 7, 7), 7, 1, 0),
+    ]
+    rows = []
+    for idx, (name, kind, shape, R, stride, pad) in enumerate(layers):
+        N, C, H, W = shape
+        Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+        x = inputs.normal_f32(shape, inputs.seed_for(7, idx))
+        in_bytes, out_bytes = x.nbytes, N * C * Ho * Wo * 4
+        nsets = min(32, max(3, -(-COLD_ROTATION_BYTES // (in_bytes + out_bytes))))
+        xs = torch.from_numpy(x).cuda()
+        sets = [{"x": xs if i == 0 else xs.clone(), "y": torch.empty((N, C, Ho, Wo), device="cuda")}
+                for i in range(nsets)]
+        if kind == "dw":
+            w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R)
+            wd = torch.from_numpy(w).cuda()
+            fn = lambda s_: sw.sw_conv2d_depthwise(s_["x"], wd, stride, pad, out=s_["y"])
+            y = sw.sw_conv2d_depthwise(xs[:1, :2].contiguous(), wd[:2].contiguous(), stride, pad).cpu().numpy()
+            y_ref, d = oracle.conv2d_depthwise(x[:1, :2], w[:2], stride, pad)
+            err = float(np.max(np.abs(y - y_ref) / d))
+            ops, extra = 2.0 * R * R * N * C * Ho * Wo, w.nbytes
+        else:
+            mode = sw.SW_POOL_MAX if kind == "max" else sw.SW_POOL_AVG
+            fn = lambda s_: sw.sw_pool2d(s_["x"], R, R, stride, pad, mode, out=s_["y"])
+            y = sw.sw_pool2d(xs[:1, :2].contiguous(), R, R, stride, pad, mode).cpu().numpy()
+            y_ref, d = oracle.pool2d(x[:1, :2], R, R, stride, pad, mode)
+            err = float(np.max(np.abs(y - y_ref) / np.maximum(d, 1e-300)))
+            if kind == "max":
+                assert np.array_equal(y.astype(np.float64), y_ref), name
+            ops, extra = float(R * R * N * C * Ho * Wo), 0
+        assert err <= 2e-5, (name, err)
+        us = time_kernel(torch, fn, sets, 4 * nsets)
+        nbytes = in_bytes + out_bytes + extra
+        rows.append({"layer": name, "shape": list(shape), "us_cold": round(us, 2), "gbs": round(nbytes / us / 1e3, 1),
+                     "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4), "gops": round(ops / us / 1e3, 1),
+                     "max_norm_err": float("%.2e" % err)})
+        del sets, xs
+        torch.cuda.empty_cache()
+    return {"table": "2-D pooling and stride-2 layers, fp32, cold (rotation larger than the Infinity Cache)",
+            "rows": rows}
+
+
 def cpu_baseline(host, total_ops):
     import oracle
 
@@ -235,6 +292,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="filter-size sweep (the paper's experiment axis, section 2): depthwise-shaped "
                          "32x64x56x56 fp32, square filters 3..51, 'same' padding; prints one JSON line")
+    ap.add_argument("--layers", action="store_true",
+                    help="2-D pooling and stride-2 layers of common CNN shapes; prints one JSON line")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for counter runs under rocprofv3 --pmc: one 64 MiB device copy (calibration), then "
                          "every kernel of the step twice; prints nothing but a marker line")
@@ -253,6 +312,9 @@ def main():
 
     if args.sweep:
         print(json.dumps(filter_size_sweep(torch, sw)))
+        return
+    if args.layers:
+        print(json.dumps(strided_and_pooling_table(torch, sw)))
         return
 
     work = work_table()

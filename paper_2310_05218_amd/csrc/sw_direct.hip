@@ -113,6 +113,43 @@ __global__ __launch_bounds__(kThreads) void direct_pool2d_kernel(const float* __
     }
 }
 
+// Pooling with large windows (global pooling above all), one wavefront per output: the lanes stride over
+// the window positions, which lie in runs of S consecutive addresses, and a butterfly of lane exchanges
+// folds the 64 partial results.
+template <bool MAXIMUM>
+__global__ __launch_bounds__(kThreads) void wave_pool2d_kernel(const float* __restrict__ x, float* __restrict__ y,
+                                                               int64_t planes, int H, int W, int R, int S,
+                                                               int stride, int pad, int Ho, int Wo)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t plane_o = (int64_t)Ho * Wo;
+    const int64_t total = planes * plane_o;
+    const float scale = 1.0f / (float)(R * S);
+    for (int64_t o = (int64_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6); o < total;
+         o += (int64_t)gridDim.x * (kThreads / 64)) {
+        const int64_t p = o / plane_o;
+        const int pix = (int)(o - p * plane_o);
+        const int i = pix / Wo, j = pix - i * Wo;
+        const float* xp = x + p * H * W;
+        const int h0 = i * stride - pad, v0 = j * stride - pad;
+        float acc = MAXIMUM ? -INFINITY : 0.f;
+        for (int t = lane; t < R * S; t += 64) {
+            const int r = t / S, q = t - r * S;
+            const int h = h0 + r, v = v0 + q;
+            if (h >= 0 && h < H && v >= 0 && v < W) {
+                const float e = xp[(int64_t)h * W + v];
+                acc = MAXIMUM ? fmaxf(acc, e) : acc + e;
+            }
+        }
+#pragma unroll
+        for (int m = 32; m >= 1; m >>= 1) {
+            const float other = __shfl_xor(acc, m, 64);
+            acc = MAXIMUM ? fmaxf(acc, other) : acc + other;
+        }
+        if (lane == 0) y[o] = MAXIMUM ? acc : acc * scale;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
@@ -161,6 +198,18 @@ hipError_t launch_direct_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y,
 hipError_t launch_direct_pool2d(const float* x, float* y, int64_t planes, int H, int W, int R, int S, int stride,
                                 int pad, int Ho, int Wo, bool maximum, hipStream_t st)
 {
+    if (R * S >= 32) {      // large windows: a wavefront per output
+        const int64_t waves = planes * Ho * Wo;
+        const int64_t g = (waves + kThreads / 64 - 1) / (kThreads / 64);
+        const int grid = (int)(g < 256 * 256 ? g : 256 * 256);
+        if (maximum)
+            hipLaunchKernelGGL(wave_pool2d_kernel<true>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
+                               stride, pad, Ho, Wo);
+        else
+            hipLaunchKernelGGL(wave_pool2d_kernel<false>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
+                               stride, pad, Ho, Wo);
+        return hipGetLastError();
+    }
     const int grid = grid_for(planes * Ho * Wo);
     if (maximum)
         hipLaunchKernelGGL(direct_pool2d_kernel<true>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,

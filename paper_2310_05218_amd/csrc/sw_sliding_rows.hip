@@ -51,12 +51,16 @@ __device__ __forceinline__ float from_right(float v)
 }
 
 // PADC: padding (compile time).  ST: stride, 1 or 2.  OP: weighted sum, average or maximum.
-template <int R, int S, int PADC, int TR, int ST, int OP>
+// SEGL: lanes per work item.  64: the wavefront walks strips of a wide plane.  8, 16 or 32: planes narrower
+// than 4 * SEGL columns, one (plane, band) item per group of SEGL lanes; the lanes of a group beyond the
+// plane's width hold padding, which is exactly what the neighbouring group's edge lane must shift in.
+template <int R, int S, int PADC, int TR, int ST, int OP, int SEGL>
 __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restrict__ x,
                                                            const float* __restrict__ w,
                                                            float* __restrict__ y, int planes_per_x,
                                                            int n_filters, int H, int W, int Ho, int Wo,
-                                                           int strips, int bands, int64_t waves, int y_vec_ok)
+                                                           int strips, int bands, int64_t waves, int64_t items,
+                                                           int y_vec_ok)
 {
     constexpr int NOUT = 4 / ST;                                   // outputs per lane and output row
     constexpr int LEFT = PADC;
@@ -67,14 +71,26 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
     const int lane = threadIdx.x & 63;
     const int64_t wv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (wv >= waves) return;
-    const int strip = (int)(wv % strips);
-    const int64_t t = wv / strips;
-    const int band = (int)(t % bands);
-    const int plane = (int)(t / bands);
-
-    const int c0 = strip * kStripStep;                // first input column of the strip
-    const int col = c0 + 4 * lane;                    // this lane's input columns
-    const int ocol = col / ST;                        // its first output column
+    int c0, col, band, plane;
+    bool live = true;
+    if constexpr (SEGL == 64) {
+        const int strip = (int)(wv % strips);
+        const int64_t t = wv / strips;
+        band = (int)(t % bands);
+        plane = (int)(t / bands);
+        c0 = strip * kStripStep;                      // first input column of the strip
+        col = c0 + 4 * lane;                          // this lane's input columns
+    } else {
+        // the last wavefront may hold fewer than 64 / SEGL items: its idle groups load and store nothing
+        const int64_t item = wv * (64 / SEGL) + lane / SEGL;
+        live = item < items;
+        const int64_t it = live ? item : 0;
+        band = (int)(it % bands);
+        plane = (int)(it / bands);
+        c0 = 0;
+        col = 4 * (lane % SEGL);
+    }
+    const int ocol = col / ST;                        // the lane's first output column
     const int i0 = band * TR;                         // first output row of the band
     const float* xp = x + (int64_t)(plane / planes_per_x) * H * W;
     float* yp = y + (int64_t)plane * Ho * Wo;
@@ -92,7 +108,7 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
     for (int e = 0; e < NIN; ++e) {
         const int gr = ST * i0 - PADC + e;
         in[e] = floatx4{FILL, FILL, FILL, FILL};
-        if (gr >= 0 && gr < H && col < W) in[e] = *reinterpret_cast<const floatx4*>(xp + (int64_t)gr * W + col);
+        if (gr >= 0 && gr < H && col < W && live) in[e] = *reinterpret_cast<const floatx4*>(xp + (int64_t)gr * W + col);
     }
 
     float acc[TR][NOUT];
@@ -128,9 +144,9 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
 
     // lanes without a neighbour inside the strip have no halo: they only feed their neighbours, unless
     // the missing neighbour lies outside the image, where the shifted-in value is the padding itself
-    const bool left_ok = lane > 0 || c0 == 0;
-    const bool right_ok = lane < 63 || c0 + kStripIn >= W;
-    if (!left_ok || !right_ok || ocol >= Wo) return;
+    const bool left_ok = SEGL != 64 || lane > 0 || c0 == 0;
+    const bool right_ok = SEGL != 64 || lane < 63 || c0 + kStripIn >= W;
+    if (!left_ok || !right_ok || ocol >= Wo || !live) return;
     constexpr float kScale = 1.0f / (float)(R * S);
 #pragma unroll
     for (int orow = 0; orow < TR; ++orow) {
@@ -142,10 +158,12 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
         }
         float* dst = yp + (int64_t)oi * Wo + ocol;
         if (y_vec_ok && ocol + NOUT - 1 < Wo) {
+            // (streaming stores: the output is not read again by this kernel)
             if constexpr (NOUT == 4)
-                *reinterpret_cast<floatx4*>(dst) = floatx4{acc[orow][0], acc[orow][1], acc[orow][2], acc[orow][3]};
+                __builtin_nontemporal_store(floatx4{acc[orow][0], acc[orow][1], acc[orow][2], acc[orow][3]},
+                                            reinterpret_cast<floatx4*>(dst));
             else
-                *reinterpret_cast<floatx2*>(dst) = floatx2{acc[orow][0], acc[orow][1]};
+                __builtin_nontemporal_store(floatx2{acc[orow][0], acc[orow][1]}, reinterpret_cast<floatx2*>(dst));
         } else {
 #pragma unroll
             for (int p = 0; p < NOUT; ++p)
@@ -154,32 +172,52 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
     }
 }
 
-template <int R, int S, int PADC, int ST, int OP>
-hipError_t launch_rows(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
-                       int H, int W, int Ho, int Wo, hipStream_t st)
+template <int R, int S, int PADC, int ST, int OP, int SEGL>
+hipError_t launch_rows_seg(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
+                           int H, int W, int Ho, int Wo, hipStream_t st)
 {
-    // input columns whose lanes produce an output
-    const int64_t need = (int64_t)ST * Wo;
-    const int Wc = (int)(need < W ? (need + 3) & ~(int64_t)3 : W);
-    const int strips = W <= kStripIn || Wc <= kStripFirst ? 1 : 1 + (Wc - kStripFirst + kStripStep - 1) / kStripStep;
     constexpr int NOUT = 4 / ST;
     const int y_vec_ok = reinterpret_cast<uintptr_t>(y) % (4 * NOUT) == 0 && Wo % NOUT == 0;
+    int strips = 1;
+    if (SEGL == 64 && W > kStripIn) {
+        // input columns whose lanes produce an output
+        const int64_t need = (int64_t)ST * Wo;
+        const int Wc = (int)(need < W ? (need + 3) & ~(int64_t)3 : W);
+        if (Wc > kStripFirst) strips = 1 + (Wc - kStripFirst + kStripStep - 1) / kStripStep;
+    }
     // short bands when the launch would otherwise leave most of the chip idle
     constexpr int TR_BIG = 8 / ST, TR_SMALL = 4 / ST;
-    const bool small = planes * strips * ((Ho + TR_BIG - 1) / TR_BIG) < 2048;
+    constexpr int PER_WAVE = 64 / SEGL;
+    const bool small = (planes * strips * ((Ho + TR_BIG - 1) / TR_BIG) + PER_WAVE - 1) / PER_WAVE < 8192;
     const int TR = small ? TR_SMALL : TR_BIG;
     const int bands = (Ho + TR - 1) / TR;
-    const int64_t waves = planes * strips * bands;
+    const int64_t items = planes * strips * bands;
+    const int64_t waves = (items + PER_WAVE - 1) / PER_WAVE;
     const int64_t blocks = (waves + 3) / 4;
     if (blocks > 2147483647LL) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(256);
     if (small)
-        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_SMALL, ST, OP>), grid, block, 0, st, x, w, y,
-                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, y_vec_ok);
+        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_SMALL, ST, OP, SEGL>), grid, block, 0, st, x, w, y,
+                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, items, y_vec_ok);
     else
-        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_BIG, ST, OP>), grid, block, 0, st, x, w, y,
-                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, y_vec_ok);
+        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_BIG, ST, OP, SEGL>), grid, block, 0, st, x, w, y,
+                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, items, y_vec_ok);
     return hipGetLastError();
+}
+
+// Narrow planes share a wavefront: the group must be at least one lane wider than the plane (W / 4 lanes), so
+// that the lane between two planes holds padding.
+template <int R, int S, int PADC, int ST, int OP>
+hipError_t launch_rows(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
+                       int H, int W, int Ho, int Wo, hipStream_t st)
+{
+    const int lanes = W / 4 + 1;
+#define SW_SEG(L) return launch_rows_seg<R, S, PADC, ST, OP, L>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st)
+    if (lanes <= 8) SW_SEG(8);
+    if (lanes <= 16) SW_SEG(16);
+    if (lanes <= 32) SW_SEG(32);
+    SW_SEG(64);
+#undef SW_SEG
 }
 
 }  // namespace

@@ -32,6 +32,15 @@ bool no_rows_kernel()      // A/B switch: keep one-filter-per-plane problems off
     return v;
 }
 
+bool no_whole_plane_kernel()   // A/B switch: keep 3x3 / 5x5 problems off the persistent whole-plane kernel
+{
+    static const bool v = [] {
+        const char* e = std::getenv("SWCONV_NO_WHOLE");
+        return e && e[0] == '1';
+    }();
+    return v;
+}
+
 bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
 bool overlaps(const void* a, int64_t abytes, const void* b, int64_t bbytes)
@@ -48,7 +57,8 @@ int run_plane(const float* x, const float* w, float* y, int64_t planes, int plan
               const Conv2dShape& s, bool depthwise, hipStream_t st)
 {
     if (!force_direct()) {
-        const bool whole = s.stride == 1 && sliding_plane_whole(x, y, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) && planes >= 512;
+        const bool whole = s.stride == 1 && sliding_plane_whole(x, y, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) &&
+                           planes >= 512 && !(no_whole_plane_kernel() && s.R < 7);
         if (!whole && !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad))
             return launch_status(launch_sliding_rows(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
                                                      s.stride, s.pad, s.Ho, s.Wo, st));
@@ -164,6 +174,8 @@ int sw_pool2d(const float* x, float* y, int N, int C, int H, int W, int R, int S
     if (overlaps(y, ny * 4, x, nx * 4)) return SW_ERR_ALIAS;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const bool maximum = mode == SW_POOL_MAX;
+    if (!force_direct() && global_pool_supported(H, W, R, S, pad))
+        return launch_status(launch_global_pool(x, y, planes, H * W, maximum, st));
     if (!force_direct() && pool_rows_supported(x, W, R, S, stride, pad))
         return launch_status(launch_pool_rows(x, y, planes, H, W, R, stride, pad, (int)Ho, (int)Wo, maximum, st));
     return launch_status(launch_direct_pool2d(x, y, planes, H, W, R, S, stride, pad, (int)Ho, (int)Wo, maximum, st));

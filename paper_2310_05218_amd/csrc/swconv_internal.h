@@ -59,6 +59,10 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st);
 
+// ---- global pooling of planes of at most 256 elements: 64 planes per wavefront through LDS ----------------
+bool       global_pool_supported(int H, int W, int R, int S, int pad);
+hipError_t launch_global_pool(const float* x, float* y, int64_t planes, int HW, bool maximum, hipStream_t st);
+
 // ---- multi-channel kernels on the matrix cores (stride 1) --------------------------------------
 bool       mfma_f32_supported(const Conv2dShape& s);
 hipError_t launch_mfma_f32(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);

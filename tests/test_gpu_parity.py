@@ -210,7 +210,13 @@ POOL2D_CASES = [
     (1, 3, 21, 23, 3, 3, 2, 1),     # W not a multiple of 4: one thread per output
     (1, 2, 20, 20, 2, 2, 1, 0),
     (1, 2, 20, 24, 5, 3, 2, 1),
-    (1, 2, 14, 14, 14, 14, 1, 0),   # global pooling
+    (1, 2, 14, 14, 14, 14, 1, 0),   # global pooling of small planes: 64 planes per wavefront
+    (3, 40, 7, 7, 7, 7, 1, 0),
+    (2, 100, 16, 16, 16, 16, 1, 0),
+    (1, 65, 3, 5, 3, 5, 1, 0),
+    (1, 3, 20, 20, 20, 20, 1, 0),   # global pooling of larger planes: a wavefront per output
+    (1, 2, 30, 33, 9, 11, 2, 4),    # ... large windows with padding and stride
+    (1, 1, 70, 66, 64, 64, 1, 1),
     (1, 2, 17, 16, 4, 4, 4, 2),
     (1, 2, 9, 12, 1, 1, 2, 0),
 ]

@@ -59,14 +59,14 @@ SECOND_ROOF = {"depthwise_7x7": (VALU_F32_TFLOPS, "frac_alu_f32_plain_fma"),
 # profiles/hbm_traffic_all_kernels.txt), with the kernel source and its sha256 prefix at the time the
 # counters were taken.  A kernel whose source has changed since reports traffic = null.
 TRAFFIC = {
-    "conv2d_1ch_3x3": (787444, "sw_sliding_plane.hip", "20f2e4c0f6fe2221"),
-    "conv1d_k9": (33879936, "sw_sliding1d.hip", "6a0040fe93108318"),
-    "avgpool1d_w8": (33965826, "sw_sliding1d.hip", "6a0040fe93108318"),
-    "maxpool1d_w8": (33965505, "sw_sliding1d.hip", "6a0040fe93108318"),
-    "conv2d_64x64_3x3": (61534745, "sw_mfma_f32.hip", "20cba8ead230b54b"),
-    "depthwise_3x3": (205655982, "sw_sliding_plane.hip", "20f2e4c0f6fe2221"),
-    "depthwise_7x7": (206030266, "sw_sliding_plane.hip", "20f2e4c0f6fe2221"),
-    "conv2d_s8_128x128_3x3": (20551756, "sw_mfma_s8.hip", "5a613c6c662a0712"),
+    "conv2d_1ch_3x3": (637795, "sw_sliding_rows.hip", "1183d74112b4cf49"),
+    "conv1d_k9": (33932955, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
+    "avgpool1d_w8": (34176570, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
+    "maxpool1d_w8": (34175194, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
+    "conv2d_64x64_3x3": (62469883, "sw_mfma_f32.hip", "92e3afdd59a9d250"),
+    "depthwise_3x3": (206847393, "sw_sliding_plane.hip", "12d7b9e73893c6ae"),
+    "depthwise_7x7": (206140934, "sw_sliding_plane.hip", "12d7b9e73893c6ae"),
+    "conv2d_s8_128x128_3x3": (21059791, "sw_mfma_s8.hip", "7425273640eeae94"),
 }
 
 

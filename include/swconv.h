@@ -97,8 +97,10 @@ int sw_pool2d(const float* x, float* y, int N, int C, int H, int W, int R, int S
  * the output tile, the re-formulation section 3 asks for).
  *     y[n,co,i,j] = sum_{ci,r,s} w[co,ci,r,s] * xz[n,ci,i*stride+r-pad, j*stride+s-pad]
  * x: [N,C_in,H,W] fp32;  w: [C_out,C_in,R,S] fp32;  y: [N,C_out,H_out,W_out] fp32.
- * Supported: any shape with R,S <= 64 (generic kernel); C_in % 16 == 0,
- * C_out % 64 == 0, 3x3, stride 1, pad 1 runs on the matrix cores.
+ * Supported: any shape with R,S <= 64 (SW_ERR_UNSUPPORTED beyond).  3x3 and
+ * 5x5 at stride 1 with C_in % 16 == 0, C_out % 64 == 0 and 16-byte aligned w run
+ * on the matrix cores; C_in == 1 runs the one-filter-per-plane kernels of
+ * sw_conv2d_depthwise; every other case one thread per output.
  */
 int sw_conv2d(const float* x, const float* w, float* y,
               int N, int C_in, int C_out, int H, int W, int R, int S,
@@ -109,8 +111,10 @@ int sw_conv2d(const float* x, const float* w, float* y,
  * depthwise separable convolutions) -- a pure sliding sum, no C_in reduction.
  *     y[n,c,i,j] = sum_{r,s} w[c,0,r,s] * xz[n,c,i*stride+r-pad, j*stride+s-pad]
  * x: [N,C,H,W];  w: [C,1,R,S];  y: [N,C,H_out,W_out].
- * Supported: any shape with R,S <= 64; 3x3, 5x5 and 7x7 at stride 1 have
- * fixed-size kernels (the paper's "custom" kernels, section 2).
+ * Supported: any shape with R,S <= 64 (SW_ERR_UNSUPPORTED beyond).  3x3, 5x5
+ * and 7x7 at stride 1, and 3x3 and 5x5 at stride 2, have fixed-size kernels (the
+ * paper's "custom" kernels, section 2); other extents up to 51 x 51 at stride 1
+ * run the generic sliding kernel; every other case one thread per output.
  */
 int sw_conv2d_depthwise(const float* x, const float* w, float* y,
                         int N, int C, int H, int W, int R, int S,
@@ -122,6 +126,9 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y,
  * exact int32 sums, no requantisation.  Shapes as sw_conv2d.
  * The caller guarantees C_in*R*S <= 131071 so that no sum can leave int32
  * (SW_ERR_SHAPE otherwise).  x and w need no alignment; y is 4-byte aligned.
+ * 3x3 at stride 1 with C_in % 64 == 0, C_out % 64 == 0, W % 4 == 0, 4-byte
+ * aligned x and 16-byte aligned w runs on the matrix cores; every other case
+ * one thread per output.
  */
 int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y,
                  int N, int C_in, int C_out, int H, int W, int R, int S,

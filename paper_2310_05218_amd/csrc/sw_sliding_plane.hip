@@ -68,36 +68,42 @@ __device__ __forceinline__ void accumulate_block(const float* __restrict__ win, 
     }
 }
 
-// One step of the run-time-extent kernel: input row ir of the lane's window, tap columns s0 .. s0+NT-1.
-// ALL: every output row 0..6 meets this input row (0 <= ir - orow < R for all of them).
-template <int NT, bool ALL>
-__device__ __forceinline__ void generic_step(const float* __restrict__ src, const float* __restrict__ wf, int R,
-                                             int S, int ir, int s0, float (&acc)[kB][kB])
+// One step of the run-time-extent kernel: filter row r, tap columns s0 .. s0+NT-1, all seven output rows.
+// Only the NT taps of this step are live (scalars); output row orow reads input row orow + r of the lane's
+// window (7 + NT - 1 floats, the next row already on its way) and slides it under the taps by register rename.
+// An input row is read once per filter row it meets instead of once in all, which is what keeps the taps
+// of any R x S out of the register file; LDS has the bandwidth to spare (one 8-byte read per 7 to 8 FMAs).
+template <int NT>
+__device__ __forceinline__ void row_step(const float* __restrict__ src, const float* __restrict__ taps, int P,
+                                         float (&acc)[kB][kB])
 {
-    // taps first, as one batch of scalar loads (row index clamped into the filter where a guard follows)
-    float wv[kB][NT];
+    float wr[NT];
+#pragma unroll
+    for (int jj = 0; jj < NT; ++jj) wr[jj] = taps[jj];
+    constexpr int N = kB + NT - 1;
+    float in[2][N];
+#pragma unroll
+    for (int c = 0; c < N; ++c) in[0][c] = src[c];
 #pragma unroll
     for (int orow = 0; orow < kB; ++orow) {
-        const int rc = ALL ? ir - orow : min(max(ir - orow, 0), R - 1);
+        if (orow + 1 < kB) {
 #pragma unroll
-        for (int jj = 0; jj < NT; ++jj) wv[orow][jj] = wf[rc * S + s0 + jj];
-    }
-    float in[kB + NT - 1];
-#pragma unroll
-    for (int c = 0; c < kB + NT - 1; ++c) in[c] = src[c];
-#pragma unroll
-    for (int orow = 0; orow < kB; ++orow) {
-        if (!ALL && (ir - orow < 0 || ir - orow >= R)) continue;
+            for (int c = 0; c < N; ++c) in[(orow + 1) & 1][c] = src[(orow + 1) * P + c];
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int jj = 0; jj < NT; ++jj)
 #pragma unroll
-            for (int oc = 0; oc < kB; ++oc) acc[orow][oc] = fmaf(wv[orow][jj], in[oc + jj], acc[orow][oc]);
+            for (int oc = 0; oc < kB; ++oc) acc[orow][oc] = fmaf(wr[jj], in[orow & 1][oc + jj], acc[orow][oc]);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-// RC, SC > 0: filter extent known at compile time.  RC == 0: extent (R, S) at run time, up to MAXRS.
+// RC, SC > 0: filter extent known at compile time, one wavefront per tile.  RC == 0: extent (R, S) at run
+// time, up to MAXRS; four wavefronts share the tile's LDS window (which is what limits how many tiles a CU
+// holds), each takes every fourth filter row, and the four partial 7 x 7 blocks are summed through LDS.
 template <int RC, int SC, int MAXRS>
-__global__ __launch_bounds__(64) void sliding_plane_kernel(const float* __restrict__ x,
+__global__ __launch_bounds__(RC > 0 ? 64 : 256) void sliding_plane_kernel(const float* __restrict__ x,
                                                            const float* __restrict__ w,
                                                            float* __restrict__ y, int planes_per_x,
                                                            int n_filters, int H, int W, int R_rt,
@@ -110,12 +116,16 @@ __global__ __launch_bounds__(64) void sliding_plane_kernel(const float* __restri
     constexpr int P = in_pitch(SMAX);
     constexpr int F4_PER_ROW = (3 + kTile + SMAX - 1 + 3) / 4;   // 16-byte groups loaded per row
     static_assert(F4_PER_ROW * 4 <= P, "pitch too small");
+    constexpr int NW = RC > 0 ? 1 : 4;                            // wavefronts per tile
+    constexpr int NT = 64 * NW;
     constexpr int LDS_FLOATS = in_rows(RMAX) * P > kTile * kOutPitch ? in_rows(RMAX) * P : kTile * kOutPitch;
+    static_assert(NW == 1 || LDS_FLOATS >= 2 * 64 * kB * kB, "window too small for two partial blocks");
     __shared__ __attribute__((aligned(16))) float lds[LDS_FLOATS];
 
     const int R = RC > 0 ? RC : R_rt;
     const int S = RC > 0 ? SC : S_rt;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
     int b = blockIdx.x;
     const int tx = b % tiles_x; b /= tiles_x;
     const int ty = b % tiles_y; b /= tiles_y;
@@ -132,7 +142,7 @@ __global__ __launch_bounds__(64) void sliding_plane_kernel(const float* __restri
     const int grow0 = row0 - pad;
     const int rows_in = kTile + R - 1;
 
-    for (int idx = lane; idx < rows_in * F4_PER_ROW; idx += 64) {
+    for (int idx = threadIdx.x; idx < rows_in * F4_PER_ROW; idx += NT) {
         const int e = idx / F4_PER_ROW;
         const int c4 = idx - e * F4_PER_ROW;
         const int gr = grow0 + e;
@@ -165,37 +175,64 @@ __global__ __launch_bounds__(64) void sliding_plane_kernel(const float* __restri
     if (RC > 0) {
         accumulate_block<RMAX, SMAX, P>(win, wf, acc);
     } else {
-        // Run-time extents: the same sliding order in pieces.  For every input row of the lane's window
-        // and every group of four tap columns, ten floats are read once and slid (register rename) under
-        // the taps of each filter row that the input row meets.  Input rows 6 .. R-1 meet all seven
-        // output rows and run without a test; the first and last six rows take the guarded form.
-        const int full = S & ~3, rem = S & 3;
-        for (int ir = 0; ir < kB + R - 1; ++ir) {
-            const float* row = win + ir * P;
-            if (ir >= kB - 1 && ir < R) {
-                for (int s0 = 0; s0 < full; s0 += 4) generic_step<4, true>(row + s0, wf, R, S, ir, s0, acc);
-                if (rem == 1) generic_step<1, true>(row + full, wf, R, S, ir, full, acc);
-                if (rem == 2) generic_step<2, true>(row + full, wf, R, S, ir, full, acc);
-                if (rem == 3) generic_step<3, true>(row + full, wf, R, S, ir, full, acc);
-            } else {
-                for (int s0 = 0; s0 < full; s0 += 4) generic_step<4, false>(row + s0, wf, R, S, ir, s0, acc);
-                if (rem == 1) generic_step<1, false>(row + full, wf, R, S, ir, full, acc);
-                if (rem == 2) generic_step<2, false>(row + full, wf, R, S, ir, full, acc);
-                if (rem == 3) generic_step<3, false>(row + full, wf, R, S, ir, full, acc);
+        // Run-time extents: filter rows one at a time (every NW-th row in this wavefront), tap columns in
+        // groups of eight.
+        const int full = S & ~7, rem = S & 7;
+#pragma unroll 1
+        for (int r = wave; r < R; r += NW) {
+            const float* row = win + r * P;
+            const float* taps = wf + r * S;
+#pragma unroll 1
+            for (int s0 = 0; s0 < full; s0 += 8) row_step<8>(row + s0, taps + s0, P, acc);
+            switch (rem) {
+                case 1: row_step<1>(row + full, taps + full, P, acc); break;
+                case 2: row_step<2>(row + full, taps + full, P, acc); break;
+                case 3: row_step<3>(row + full, taps + full, P, acc); break;
+                case 4: row_step<4>(row + full, taps + full, P, acc); break;
+                case 5: row_step<5>(row + full, taps + full, P, acc); break;
+                case 6: row_step<6>(row + full, taps + full, P, acc); break;
+                case 7: row_step<7>(row + full, taps + full, P, acc); break;
+                default: break;
             }
         }
     }
 
-    __syncthreads();   // every lane has finished reading the window; reuse LDS for the output tile
+    __syncthreads();   // every lane has finished reading the window; reuse LDS
+    if constexpr (NW == 4) {
+        // partial blocks of wavefronts 2 and 3 into 0 and 1, then 1 into 0 (element k of lane l at k * 64 + l)
+        float* slot = lds + (wave & 1) * (64 * kB * kB) + lane;
+        if (wave >= 2) {
 #pragma unroll
-    for (int i = 0; i < kB; ++i)
+            for (int k = 0; k < kB * kB; ++k) slot[k * 64] = acc[k / kB][k % kB];
+        }
+        __syncthreads();
+        if (wave < 2) {
 #pragma unroll
-        for (int j = 0; j < kB; ++j) lds[(kB * by + i) * kOutPitch + kB * bx + j] = acc[i][j];
+            for (int k = 0; k < kB * kB; ++k) acc[k / kB][k % kB] += slot[k * 64];
+        }
+        __syncthreads();
+        if (wave == 1) {
+#pragma unroll
+            for (int k = 0; k < kB * kB; ++k) lds[k * 64 + lane] = acc[k / kB][k % kB];
+        }
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int k = 0; k < kB * kB; ++k) acc[k / kB][k % kB] += lds[k * 64 + lane];
+        }
+        __syncthreads();
+    }
+    if (wave == 0) {
+#pragma unroll
+        for (int i = 0; i < kB; ++i)
+#pragma unroll
+            for (int j = 0; j < kB; ++j) lds[(kB * by + i) * kOutPitch + kB * bx + j] = acc[i][j];
+    }
     __syncthreads();
 
     const int rows_out = min(kTile, Ho - row0);
     const int cols_out = min(kTile, Wo - col0);
-    for (int idx = lane; idx < rows_out * (kTile / 4); idx += 64) {
+    for (int idx = threadIdx.x; idx < rows_out * (kTile / 4); idx += NT) {
         const int e = idx / (kTile / 4);
         const int c = 4 * (idx - e * (kTile / 4));
         if (c >= cols_out) continue;
@@ -295,6 +332,14 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
     wave_lds_sync();
 #pragma unroll 1
     for (;;) {
+        // The wavefronts of a SIMD are served oldest first, which lets the older one run ahead and leaves the
+        // younger one alone at the end, with nobody to fill its stalls.  A wavefront with more planes still to
+        // go therefore asks for the higher issue priority: the two stay level.
+        const int left = (planes - 1 - plane) / (int)gridDim.x;
+        if (left >= 3) __builtin_amdgcn_s_setprio(3);
+        else if (left == 2) __builtin_amdgcn_s_setprio(2);
+        else if (left == 1) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
         float acc[kB][kB];
 #pragma unroll
         for (int i = 0; i < kB; ++i)
@@ -388,9 +433,9 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
     if (blocks > 2147483647LL) return hipErrorInvalidValue;
     const int x_vec_ok = reinterpret_cast<uintptr_t>(x) % 16 == 0 && W % 4 == 0;
     const int y_vec_ok = reinterpret_cast<uintptr_t>(y) % 16 == 0 && Wo % 4 == 0;
-    dim3 grid((unsigned)blocks), block(64);
+    dim3 grid((unsigned)blocks);
 #define SW_PLANE(RC, SC, MAXRS)                                                                          \
-    hipLaunchKernelGGL((sliding_plane_kernel<RC, SC, MAXRS>), grid, block, 0, st, x, w, y, planes_per_x,      \
+    hipLaunchKernelGGL((sliding_plane_kernel<RC, SC, MAXRS>), grid, dim3(RC > 0 ? 64 : 256), 0, st, x, w, y, planes_per_x, \
                        n_filters, H, W, R, S, pad, Ho, Wo, tiles_x, tiles_y, x_vec_ok, y_vec_ok)
     if (R == 3 && S == 3) SW_PLANE(3, 3, 0);
     else if (R == 5 && S == 5) SW_PLANE(5, 5, 0);

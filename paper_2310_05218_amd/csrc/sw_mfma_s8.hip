@@ -131,8 +131,11 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
     const int HW = H * W;
     const int8_t* xn = x + (int64_t)n * C_in * HW;
 
-    // ---- zero the input window once: halo and out-of-image cells are never written again ----------
-    for (int i = tid; i < kXBytes / 16; i += 256) reinterpret_cast<intx4*>(lx)[i] = intx4{0, 0, 0, 0};
+    // zeroes the input window once: halo and out-of-image cells are never written again.  Called after the
+    // first global loads have been issued, so that it runs under their latency.
+    auto zero_window = [&]() {
+        for (int i = tid; i < kXBytes / 16; i += 256) reinterpret_cast<intx4*>(lx)[i] = intx4{0, 0, 0, 0};
+    };
 
     // ---- input staging plan: item = (16-channel group, window row, image column quad) ---------------
     const int wc0 = col0 - pad;                        // image column of window column 0
@@ -269,6 +272,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         constexpr int NSTEP = 9 * KS;
         fetch(xv0, wv0, 0);
         fetch(xv1, wv1, kCK);
+        zero_window();
         __syncthreads();   // window zeroed
         stage(xv0, wv0, 0);
         stage(xv1, wv1, kCK);
@@ -345,6 +349,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
     const int chunks = C_in / kCK;
     fetch(xv0, wv0, 0);
     if (chunks > 1) fetch(xv1, wv1, kCK);
+    zero_window();
     __syncthreads();   // window zeroed
     for (int ch = 0; ch < chunks; ch += 2) {
         stage(xv0, wv0, 0);

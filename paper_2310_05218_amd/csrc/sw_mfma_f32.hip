@@ -335,6 +335,12 @@ bool mfma_f32_supported(const Conv2dShape& s)
     return (int64_t)t.tiles_x * t.tiles_y <= 65535 && s.C_out / 64 <= 65535 && s.N <= 65535;
 }
 
+int64_t mfma_f32_workgroups(const Conv2dShape& s)
+{
+    const Tiling t = pick_tiling(s);
+    return (int64_t)t.tiles_x * t.tiles_y * s.N * (s.C_out / 64);
+}
+
 hipError_t launch_mfma_f32(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st)
 {
     if (reinterpret_cast<uintptr_t>(w) % 16 != 0) return launch_direct_conv2d_f32(x, w, y, s, false, st);

@@ -41,6 +41,15 @@ bool no_whole_plane_kernel()   // A/B switch: keep 3x3 / 5x5 problems off the pe
     return v;
 }
 
+bool no_large_tile_mfma()      // A/B switch: keep fp32 multi-channel problems off the fixed 3x3 / 5x5 kernel
+{
+    static const bool v = [] {
+        const char* e = std::getenv("SWCONV_NO_LARGE_TILE");
+        return e && e[0] == '1';
+    }();
+    return v;
+}
+
 bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
 bool overlaps(const void* a, int64_t abytes, const void* b, int64_t bbytes)
@@ -189,7 +198,10 @@ int sw_conv2d(const float* x, const float* w, float* y, int N, int C_in, int C_o
     if (rc != SW_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (C_in == 1) return run_plane(x, w, y, (int64_t)N * C_out, C_out, C_out, s, false, st);
-    if (!force_direct() && mfma_f32_supported(s)) return launch_status(launch_mfma_f32(x, w, y, s, st));
+    if (!force_direct()) {
+        if (mfma_f32_supported(s) && !no_large_tile_mfma()) return launch_status(launch_mfma_f32(x, w, y, s, st));
+        if (mfma_f32_any_supported(s)) return launch_status(launch_mfma_f32_any(x, w, y, s, st));
+    }
     return launch_status(launch_direct_conv2d_f32(x, w, y, s, false, st));
 }
 

@@ -294,7 +294,7 @@ def test_workload4_full_size(torch, sw, oracle, which):
 
 CONV2D_CASES = [
     # N, C_in, C_out, H, W, R, S, stride, pad
-    (1, 3, 5, 9, 11, 3, 3, 1, 1),        # small odd shapes: direct kernel
+    (1, 3, 5, 9, 11, 3, 3, 1, 1),        # small odd shapes: the any-shape matrix-core kernel
     (2, 4, 3, 12, 10, 2, 5, 2, 2),
     (1, 7, 2, 8, 8, 1, 1, 1, 0),
     (2, 16, 64, 56, 56, 3, 3, 1, 1),     # matrix-core path, one channel block
@@ -305,7 +305,18 @@ CONV2D_CASES = [
     (1, 48, 64, 14, 14, 3, 3, 1, 0),     # valid mode
     (1, 16, 64, 20, 20, 5, 5, 1, 2),
     (1, 16, 64, 12, 12, 1, 1, 1, 0),
-    (1, 32, 64, 17, 19, 3, 3, 2, 1),     # strided: direct kernel
+    (1, 32, 64, 17, 19, 3, 3, 2, 1),     # strided: the any-shape matrix-core kernel
+    (2, 3, 10, 23, 21, 3, 3, 1, 1),      # odd channel counts on both sides (zero-filled in LDS)
+    (1, 3, 64, 60, 60, 7, 7, 2, 3),      # a CNN stem: 7x7, stride 2, three input channels
+    (1, 3, 70, 35, 35, 11, 11, 4, 2),    # 11x11 stride 4
+    (2, 5, 33, 12, 150, 3, 3, 1, 1),     # output rows wider than a tile: column tiles
+    (1, 7, 65, 40, 9, 5, 3, 1, 2),       # rectangular filter, padding beyond (S-1)/2
+    (3, 64, 96, 7, 7, 3, 3, 1, 1),       # small images
+    (2, 40, 64, 14, 14, 1, 1, 1, 0),     # pointwise, C_in not a multiple of 8
+    (1, 24, 64, 14, 14, 1, 1, 2, 0),     # pointwise with stride
+    (1, 6, 8, 30, 30, 13, 13, 1, 6),     # 169 taps: channel chunks of two
+    (1, 2, 4, 5, 5, 5, 5, 1, 0),         # a single output pixel
+    (1, 9, 130, 16, 16, 2, 2, 2, 0),     # even filter, three channel blocks with a ragged last one
 ]
 
 

@@ -97,10 +97,13 @@ int sw_pool2d(const float* x, float* y, int N, int C, int H, int W, int R, int S
  * the output tile, the re-formulation section 3 asks for).
  *     y[n,co,i,j] = sum_{ci,r,s} w[co,ci,r,s] * xz[n,ci,i*stride+r-pad, j*stride+s-pad]
  * x: [N,C_in,H,W] fp32;  w: [C_out,C_in,R,S] fp32;  y: [N,C_out,H_out,W_out] fp32.
- * Supported: any shape with R,S <= 64 (SW_ERR_UNSUPPORTED beyond).  3x3 and
- * 5x5 at stride 1 with C_in % 16 == 0, C_out % 64 == 0 and 16-byte aligned w run
- * on the matrix cores; C_in == 1 runs the one-filter-per-plane kernels of
- * sw_conv2d_depthwise; every other case one thread per output.
+ * Supported: any shape with R,S <= 64 (SW_ERR_UNSUPPORTED beyond).  C_in >= 2
+ * runs on the matrix cores: 3x3 and 5x5 at stride 1 with C_in % 16 == 0,
+ * C_out % 64 == 0 and 16-byte aligned w in a large-tile kernel when the problem
+ * fills the chip with such tiles, every other extent, stride, padding and channel
+ * count in an any-shape kernel (one thread per output only when its window or
+ * filter does not fit 64 KB of LDS).  C_in == 1 runs the one-filter-per-plane
+ * kernels of sw_conv2d_depthwise.
  */
 int sw_conv2d(const float* x, const float* w, float* y,
               int N, int C_in, int C_out, int H, int W, int R, int S,

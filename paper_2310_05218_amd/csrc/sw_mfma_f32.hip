@@ -338,6 +338,7 @@ bool mfma_f32_supported(const Conv2dShape& s)
 int64_t mfma_f32_workgroups(const Conv2dShape& s)
 {
     const Tiling t = pick_tiling(s);
+    if (t.TH * t.TW < kTilePx / 2) return 0;       // images so small that a tile stays half empty
     return (int64_t)t.tiles_x * t.tiles_y * s.N * (s.C_out / 64);
 }
 

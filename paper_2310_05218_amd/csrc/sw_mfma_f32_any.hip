@@ -6,7 +6,8 @@
 // reach.  A workgroup of four wavefronts computes 64 output channels x up to 128 output pixels (whole output
 // rows of one image).  The input channels are walked in chunks of CK: the chunk's input window (tile + halo,
 // zero outside the image and beyond C_in: that is the padding) and the chunk's filters are staged in LDS
-// once; then every tap (r, s) is one small matrix product per pixel block,
+// once (filters as they lie in memory, so staging is a row copy); then every tap (r, s) is one small matrix
+// product per pixel block,
 //     ACC[co, p] += W_rs[co, ci] * X[ci, p shifted by (r, s)],
 // on v_mfma_f32_32x32x2_f32, the shift being nothing but an LDS address offset of the B operand (stride is
 // a multiplier in the pixel's window address).  No column matrix exists anywhere.  Small LDS footprints let
@@ -20,27 +21,31 @@ namespace swconv {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kTilePx = 128;           // output pixels per workgroup: one 32-pixel block per wavefront
-constexpr int kWPitch = 65;            // floats per (tap, channel) row of the staged filters: 64 channels + 1
 constexpr int kLdsBudget = 64 * 1024;  // keeps at least two workgroups on a CU
-constexpr int kBatch = 8;              // staging loads in flight per thread
+constexpr int kXS = 16;                // register-prefetch slots per thread: input window (floats) ...
+constexpr int kWS = 6;                 // ... and filters (16-byte groups)
 
 struct AnyParams {
     int C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
-    int TH, TW, IH, IW, tiles_x;
-    FastDiv by_tiles_x, by_TW, by_IW, by_win, by_RS, by_CKRS;
+    int TH, TW, IH, IW, tiles_x, wpitch;
+    FastDiv by_tiles_x, by_TW, by_IW, by_win, by_span, by_span4;
 };
 
-template <int CK>
+// XS > 0: the next chunk travels global memory -> registers while this chunk multiplies (needs 16-byte aligned
+// filter rows and at most XS / kWS staging slots per thread); XS == 0: a chunk is staged, then multiplied.
+template <int CK, int XS>
 __global__ __launch_bounds__(256) void mfma_f32_any_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                            float* __restrict__ y, const AnyParams P)
 {
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const int RS = P.R * P.S;
     const int WP = P.IH * P.IW;                 // window pixels per channel
+    const int span = CK * RS;                   // filter floats per output channel and chunk, contiguous in w
     float* xs = smem;                           // [CK][WP]
-    float* ws = smem + CK * WP;                 // [RS][CK][kWPitch]
+    float* ws = smem + ((CK * WP + 3) & ~3);    // [co][CK][RS] as in memory, rows P.wpitch floats apart
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -68,71 +73,116 @@ __global__ __launch_bounds__(256) void mfma_f32_any_kernel(const float* __restri
     const int HW = P.H * P.W;
     const float* xn = x + (int64_t)n * P.C_in * HW;
     const int64_t wrow = (int64_t)P.C_in * RS;                  // floats per output channel in w
+    const float* wb = w + (int64_t)co0 * wrow;
 
-    for (int ci0 = 0; ci0 < P.C_in; ci0 += CK) {
-        // ---- stage the chunk: input window (coalesced along image rows) ...  Loads go out in batches of
-        //      kBatch per thread before the first LDS write, so a batch costs one memory round trip.
-        for (int base = tid; base < CK * WP; base += 256 * kBatch) {
-            float v[kBatch];
+    // every tap is a 64 x CK by CK x 32 product per wavefront; the shift is the offset toff
+    auto multiply = [&]() {
+        if (!wave_live) return;
+        const float* bsrc = xs + kk * WP + pixoff;
+        const float* asrc = ws + lj * P.wpitch + kk * RS;
+        int toff = 0, s = 0;
+#pragma unroll 1
+        for (int tap = 0; tap < RS; ++tap) {
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int idx = base + 256 * u;
+            for (int c2 = 0; c2 < CK / 2; ++c2) {
+                const float b = bsrc[2 * c2 * WP + toff];
+                const float a0 = asrc[2 * c2 * RS + tap];
+                const float a1 = asrc[32 * P.wpitch + 2 * c2 * RS + tap];
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b, acc1, 0, 0, 0);
+            }
+            ++toff;
+            if (++s == P.S) { s = 0; toff += P.IW - P.S; }
+        }
+    };
+
+    if constexpr (XS > 0) {
+        // staging plan, the same for every chunk: slot u of the window is float tid + 256 u, slot u of the
+        // filters is 16-byte group tid + 256 u of the 64 rows
+        int xo[XS];           // offset inside channel ci0's plane stack, < 0: padding
+        int wo[kWS], wd[kWS], wq[kWS];  // offset from wb + ci0 * RS (< 0: nothing), LDS float index, offset in the row
+        const int span4 = span >> 2;
+#pragma unroll
+        for (int u = 0; u < XS; ++u) {
+            const int idx = tid + 256 * u;
+            const int c = fast_div(idx, P.by_win);
+            const int q = idx - c * WP;
+            const int e = fast_div(q, P.by_IW), f = q - e * P.IW;
+            const int gr = grow0 + e, gc = gcol0 + f;
+            xo[u] = (idx < CK * WP && gr >= 0 && gr < P.H && gc >= 0 && gc < P.W) ? c * HW + gr * P.W + gc : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < kWS; ++u) {
+            const int idx = tid + 256 * u;
+            const int co_l = fast_div(idx, P.by_span4);
+            const int q4 = idx - co_l * span4;
+            wo[u] = (idx < 64 * span4 && co0 + co_l < P.C_out) ? co_l * (int)wrow + 4 * q4 : -1;
+            wd[u] = co_l * P.wpitch + 4 * q4;
+            wq[u] = 4 * q4;
+        }
+        float xv[XS];
+        floatx4 wv[kWS];
+        auto fetch = [&](int ci0) {
+            const float* xc0 = xn + (int64_t)ci0 * HW;
+            const float* wc0 = wb + (int64_t)ci0 * RS;
+            const int left = (P.C_in - ci0) * RS;               // filter floats that exist from ci0 on
+#pragma unroll
+            for (int u = 0; u < XS; ++u) {
+                xv[u] = 0.f;
+                if (xo[u] >= 0 && ci0 + fast_div(tid + 256 * u, P.by_win) < P.C_in) xv[u] = xc0[xo[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < kWS; ++u) {
+                wv[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+                // (span and the row length are multiples of 4, so a group lies wholly inside or outside)
+                if (wo[u] >= 0 && wq[u] < left)
+                    wv[u] = *reinterpret_cast<const floatx4*>(wc0 + wo[u]);
+            }
+        };
+        auto stage = [&]() {
+#pragma unroll
+            for (int u = 0; u < XS; ++u)
+                if (tid + 256 * u < CK * WP) xs[tid + 256 * u] = xv[u];
+#pragma unroll
+            for (int u = 0; u < kWS; ++u)
+                if (tid + 256 * u < 64 * span4) {       // (rows sit an odd number of floats apart: four 4-byte writes)
+                    ws[wd[u] + 0] = wv[u].x; ws[wd[u] + 1] = wv[u].y; ws[wd[u] + 2] = wv[u].z; ws[wd[u] + 3] = wv[u].w;
+                }
+        };
+        fetch(0);
+        for (int ci0 = 0; ci0 < P.C_in; ci0 += CK) {
+            stage();
+            __syncthreads();
+            if (ci0 + CK < P.C_in) fetch(ci0 + CK);
+            multiply();
+            __syncthreads();
+        }
+    } else {
+        for (int ci0 = 0; ci0 < P.C_in; ci0 += CK) {
+            // input window (coalesced along image rows), zero outside the image and beyond C_in
+            for (int idx = tid; idx < CK * WP; idx += 256) {
                 const int c = fast_div(idx, P.by_win);
                 const int q = idx - c * WP;
                 const int e = fast_div(q, P.by_IW), f = q - e * P.IW;
                 const int gr = grow0 + e, gc = gcol0 + f;
-                v[u] = 0.f;
-                if (idx < CK * WP && ci0 + c < P.C_in && gr >= 0 && gr < P.H && gc >= 0 && gc < P.W)
-                    v[u] = xn[(int64_t)(ci0 + c) * HW + gr * P.W + gc];
+                float v = 0.f;
+                if (ci0 + c < P.C_in && gr >= 0 && gr < P.H && gc >= 0 && gc < P.W)
+                    v = xn[(int64_t)(ci0 + c) * HW + gr * P.W + gc];
+                xs[idx] = v;
             }
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u)
-                if (base + 256 * u < CK * WP) xs[base + 256 * u] = v[u];
-        }
-        // ---- ... and filters: for one output channel the chunk's CK * RS floats are contiguous in memory;
-        //      they land transposed, [tap][channel][co], with an odd pitch so that neither these writes nor
-        //      the operand reads collide on a bank
-        const int span = CK * RS;
-        const int left = (P.C_in - ci0) * RS;                   // floats that exist from ci0 on
-        for (int base = tid; base < 64 * span; base += 256 * kBatch) {
-            float v[kBatch];
-            int dst[kBatch];
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int idx = base + 256 * u;
-                const int co_l = fast_div(idx, P.by_CKRS);
+            // filters: for one output channel the chunk's span floats are contiguous in memory
+            const int left = (P.C_in - ci0) * RS;
+            for (int idx = tid; idx < 64 * span; idx += 256) {
+                const int co_l = fast_div(idx, P.by_span);
                 const int q = idx - co_l * span;
-                const int c = fast_div(q, P.by_RS), tap = q - c * RS;
-                v[u] = 0.f;
-                dst[u] = idx < 64 * span ? (tap * CK + c) * kWPitch + co_l : -1;
-                if (dst[u] >= 0 && co0 + co_l < P.C_out && q < left) v[u] = w[(co0 + co_l) * wrow + (int64_t)ci0 * RS + q];
+                float v = 0.f;
+                if (co0 + co_l < P.C_out && q < left) v = wb[co_l * wrow + (int64_t)ci0 * RS + q];
+                ws[co_l * P.wpitch + q] = v;
             }
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u)
-                if (dst[u] >= 0) ws[dst[u]] = v[u];
+            __syncthreads();
+            multiply();
+            __syncthreads();
         }
-        __syncthreads();
-
-        // ---- every tap is a 64 x CK by CK x 32 product per wavefront; the shift is the offset toff
-        if (wave_live) {
-            const float* bsrc = xs + kk * WP + pixoff;
-            const float* asrc = ws + kk * kWPitch + lj;
-            int toff = 0, s = 0;
-#pragma unroll 1
-            for (int tap = 0; tap < RS; ++tap) {
-#pragma unroll
-                for (int c2 = 0; c2 < CK / 2; ++c2) {
-                    const float b = bsrc[2 * c2 * WP + toff];
-                    const float a0 = asrc[(tap * CK + 2 * c2) * kWPitch];
-                    const float a1 = asrc[(tap * CK + 2 * c2) * kWPitch + 32];
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b, acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b, acc1, 0, 0, 0);
-                }
-                ++toff;
-                if (++s == P.S) { s = 0; toff += P.IW - P.S; }
-            }
-        }
-        __syncthreads();
     }
 
     // ---- store: register v of a lane is output channel 8*(v/4) + 4*kk + v%4 of the block, pixel lj
@@ -148,12 +198,12 @@ __global__ __launch_bounds__(256) void mfma_f32_any_kernel(const float* __restri
 }
 
 struct AnyPlan {
-    int TH, TW, IH, IW, CK, tiles_x, tiles_y;
+    int TH, TW, IH, IW, CK, tiles_x, tiles_y, wpitch;
     size_t lds;
-    bool ok;
+    bool ok, prefetch;
 };
 
-AnyPlan plan_any(const Conv2dShape& s)
+AnyPlan plan_any(const Conv2dShape& s, const float* w)
 {
     AnyPlan a{};
     const int RS = s.R * s.S;
@@ -163,11 +213,13 @@ AnyPlan plan_any(const Conv2dShape& s)
     if (a.TH < 1) a.TH = 1;
     // channels per chunk: about a hundred (tap, channel) rows of filters per barrier pair, no more than exist
     a.CK = 32;
-    while (a.CK > 2 && (a.CK * RS > 100 || a.CK >= 2 * s.C_in)) a.CK /= 2;
+    while (a.CK > 2 && (a.CK * RS > 96 || a.CK >= 2 * s.C_in)) a.CK /= 2;
     auto bytes = [&]() {
         a.IH = (a.TH - 1) * s.stride + s.R;
         a.IW = (a.TW - 1) * s.stride + s.S;
-        return ((size_t)a.CK * a.IH * a.IW + (size_t)RS * a.CK * kWPitch) * sizeof(float);
+        const int span = a.CK * RS;
+        a.wpitch = span | 1;     // odd: the 32 rows an operand read touches fall into 32 banks
+        return ((((size_t)a.CK * a.IH * a.IW + 3) & ~(size_t)3) + (size_t)64 * a.wpitch) * sizeof(float);
     };
     while (bytes() > (size_t)kLdsBudget) {
         if (a.CK > 2) a.CK /= 2;
@@ -175,14 +227,26 @@ AnyPlan plan_any(const Conv2dShape& s)
         else if (a.TW > 32) a.TW = (a.TW + 1) / 2;
         else break;
     }
+    // with 16-byte aligned filter rows the next chunk can be prefetched into registers, if the window is
+    // small enough for the slots a thread has: trade channels per chunk for that
+    const bool vec = ((int64_t)s.C_in * RS) % 4 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 && w != nullptr;
+    if (vec) {
+        bytes();
+        while (a.CK > 4 && ((a.CK * RS) % 4 != 0 || (int64_t)a.CK * a.IH * a.IW > 256 * kXS ||
+                            64 * (a.CK * RS / 4) > 256 * kWS))
+            a.CK /= 2;
+    }
     a.lds = bytes();
     a.tiles_x = (s.Wo + a.TW - 1) / a.TW;
     a.tiles_y = (s.Ho + a.TH - 1) / a.TH;
+    const int64_t span = (int64_t)a.CK * RS;
     a.ok = a.lds <= (size_t)kLdsBudget && (int64_t)a.tiles_x * a.tiles_y * a.tiles_x < 2147483647LL && s.N <= 65535 &&
            (s.C_out + 63) / 64 <= 65535 &&
-           // 32-bit index arithmetic inside one image / one output channel's filters, and exact fast division
-           (int64_t)s.C_in * s.H * s.W <= 2147483647LL && (int64_t)64 * a.CK * RS < 65536 &&
-           (int64_t)a.CK * a.IH * a.IW < 65536;
+           // 32-bit index arithmetic inside one image / 64 output channels' filters, and exact fast division
+           (int64_t)s.C_in * s.H * s.W <= 2147483647LL && (int64_t)64 * s.C_in * RS <= 2147483647LL &&
+           64 * span < 65536 && (int64_t)a.CK * a.IH * a.IW < 65536;
+    a.prefetch = span % 4 == 0 && ((int64_t)s.C_in * RS) % 4 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 &&
+                 (int64_t)a.CK * a.IH * a.IW <= 256 * kXS && 64 * (span / 4) <= 256 * kWS;
     return a;
 }
 
@@ -192,25 +256,30 @@ hipError_t launch_any(const float* x, const float* w, float* y, const Conv2dShap
     AnyParams P;
     P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.R = s.R; P.S = s.S; P.stride = s.stride;
     P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
-    P.TH = a.TH; P.TW = a.TW; P.IH = a.IH; P.IW = a.IW; P.tiles_x = a.tiles_x;
+    P.TH = a.TH; P.TW = a.TW; P.IH = a.IH; P.IW = a.IW; P.tiles_x = a.tiles_x; P.wpitch = a.wpitch;
     P.by_tiles_x = make_fastdiv(a.tiles_x);
     P.by_TW = make_fastdiv(a.TW);
     P.by_IW = make_fastdiv(a.IW);
     P.by_win = make_fastdiv(a.IH * a.IW);
-    P.by_RS = make_fastdiv(s.R * s.S);
-    P.by_CKRS = make_fastdiv(CK * s.R * s.S);
+    P.by_span = make_fastdiv(CK * s.R * s.S);
+    P.by_span4 = make_fastdiv(a.prefetch ? CK * s.R * s.S / 4 : 1);
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
-    hipLaunchKernelGGL((mfma_f32_any_kernel<CK>), grid, dim3(256), a.lds, st, x, w, y, P);
+    if (a.prefetch && CK * a.IH * a.IW <= 256 * 8)
+        hipLaunchKernelGGL((mfma_f32_any_kernel<CK, 8>), grid, dim3(256), a.lds, st, x, w, y, P);
+    else if (a.prefetch)
+        hipLaunchKernelGGL((mfma_f32_any_kernel<CK, kXS>), grid, dim3(256), a.lds, st, x, w, y, P);
+    else
+        hipLaunchKernelGGL((mfma_f32_any_kernel<CK, 0>), grid, dim3(256), a.lds, st, x, w, y, P);
     return hipGetLastError();
 }
 
 }  // namespace
 
-bool mfma_f32_any_supported(const Conv2dShape& s) { return s.C_in >= 2 && plan_any(s).ok; }
+bool mfma_f32_any_supported(const Conv2dShape& s) { return s.C_in >= 2 && plan_any(s, nullptr).ok; }
 
 hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st)
 {
-    const AnyPlan a = plan_any(s);
+    const AnyPlan a = plan_any(s, w);
     if (!a.ok) return hipErrorInvalidValue;
     switch (a.CK) {
         case 32: return launch_any<32>(x, w, y, s, a, st);

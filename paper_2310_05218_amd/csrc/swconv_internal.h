@@ -66,7 +66,7 @@ hipError_t launch_global_pool(const float* x, float* y, int64_t planes, int HW, 
 // ---- multi-channel kernels on the matrix cores (stride 1) --------------------------------------
 bool       mfma_f32_supported(const Conv2dShape& s);
 hipError_t launch_mfma_f32(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
-int64_t    mfma_f32_workgroups(const Conv2dShape& s);     // of the fixed 3x3 / 5x5 kernel, one per CU at a time
+int64_t    mfma_f32_workgroups(const Conv2dShape& s);     // of the fixed 3x3 / 5x5 kernel, one per CU at a time; 0: tiles half empty
 bool       mfma_f32_any_supported(const Conv2dShape& s);  // any extent, stride and channel count (C_in >= 2)
 hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
 bool       mfma_s8_supported(const Conv2dShape& s);

@@ -129,9 +129,11 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y,
  * exact int32 sums, no requantisation.  Shapes as sw_conv2d.
  * The caller guarantees C_in*R*S <= 131071 so that no sum can leave int32
  * (SW_ERR_SHAPE otherwise).  x and w need no alignment; y is 4-byte aligned.
- * 3x3 at stride 1 with C_in % 64 == 0, C_out % 64 == 0, W % 4 == 0, 4-byte
- * aligned x and 16-byte aligned w runs on the matrix cores; every other case
- * one thread per output.
+ * All shapes run on the matrix cores: 3x3 at stride 1 with C_in % 64 == 0,
+ * C_out % 64 == 0, W % 4 == 0, 4-byte aligned x and 16-byte aligned w in a
+ * large-tile kernel, every other extent, stride, padding and channel count in an
+ * any-shape kernel (one thread per output only when the filter does not fit the
+ * LDS, about R*S > 40).
  */
 int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y,
                  int N, int C_in, int C_out, int H, int W, int R, int S,

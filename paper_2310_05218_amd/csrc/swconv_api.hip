@@ -228,7 +228,10 @@ int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, int N, int C_in, 
     if (rc != SW_OK) return rc;
     if ((int64_t)C_in * R * S > 131071) return SW_ERR_SHAPE;  // 131072 * 2^14 = 2^31 leaves int32
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (!force_direct() && mfma_s8_supported(s)) return launch_status(launch_mfma_s8(x, w, y, s, st));
+    if (!force_direct()) {
+        if (mfma_s8_supported(s) && !no_large_tile_mfma()) return launch_status(launch_mfma_s8(x, w, y, s, st));
+        if (mfma_s8_any_supported(s)) return launch_status(launch_mfma_s8_any(x, w, y, s, st));
+    }
     return launch_status(launch_direct_conv2d_s8(x, w, y, s, st));
 }
 

@@ -71,5 +71,7 @@ bool       mfma_f32_any_supported(const Conv2dShape& s);  // any extent, stride 
 hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
 bool       mfma_s8_supported(const Conv2dShape& s);
 hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st);
+bool       mfma_s8_any_supported(const Conv2dShape& s);   // any extent, stride and channel count
+hipError_t launch_mfma_s8_any(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st);
 
 }  // namespace swconv

@@ -359,6 +359,15 @@ S8_CASES = [
     (1, 64, 128, 30, 9, 3, 3, 1, 0),
     (1, 192, 64, 10, 10, 5, 5, 1, 2),
     (1, 64, 64, 15, 15, 3, 3, 2, 1),
+    (2, 3, 10, 23, 21, 3, 3, 1, 1),      # any-shape matrix-core kernel: odd channel counts
+    (1, 3, 64, 60, 60, 7, 7, 2, 3),      # ... 7x7 stride 2 stem (channel chunks of 32)
+    (2, 40, 33, 12, 150, 3, 3, 1, 1),    # ... output rows wider than a tile
+    (1, 70, 65, 20, 9, 5, 3, 1, 2),      # ... rectangular filter, two channel chunks, ragged channel block
+    (3, 64, 96, 7, 7, 3, 3, 1, 1),       # ... small images
+    (2, 100, 64, 14, 14, 1, 1, 1, 0),    # ... pointwise
+    (1, 64, 64, 17, 19, 3, 3, 2, 1),     # ... stride 2
+    (1, 2, 4, 5, 5, 5, 5, 1, 0),         # ... a single output pixel
+    (1, 9, 130, 16, 16, 2, 2, 2, 0),
 ]
 
 

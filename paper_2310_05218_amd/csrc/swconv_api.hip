@@ -50,6 +50,15 @@ bool no_large_tile_mfma()      // A/B switch: keep fp32 multi-channel problems o
     return v;
 }
 
+bool no_small_planes_kernel()  // A/B switch: keep small planes off the run-of-planes kernel
+{
+    static const bool v = [] {
+        const char* e = std::getenv("SWCONV_NO_SMALL");
+        return e && e[0] == '1';
+    }();
+    return v;
+}
+
 bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
 bool overlaps(const void* a, int64_t abytes, const void* b, int64_t bbytes)
@@ -66,6 +75,12 @@ int run_plane(const float* x, const float* w, float* y, int64_t planes, int plan
               const Conv2dShape& s, bool depthwise, hipStream_t st)
 {
     if (!force_direct()) {
+        // planes up to 20 x 20, and larger ragged ones (width not a multiple of 4) that the register-only and
+        // whole-plane kernels do not take: a run of planes per workgroup
+        if (!no_small_planes_kernel() && (s.H * s.W <= 400 || s.W % 4 != 0) &&
+            small_planes_supported(planes, planes_per_x, s.H, s.W, s.R, s.S, s.Ho, s.Wo))
+            return launch_status(launch_small_planes(x, w, y, planes, n_filters, s.H, s.W, s.R, s.S, s.stride, s.pad,
+                                                     s.Ho, s.Wo, st));
         const bool whole = s.stride == 1 && sliding_plane_whole(x, y, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) &&
                            planes >= 512 && !(no_whole_plane_kernel() && s.R < 7);
         if (!whole && !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad))

@@ -59,6 +59,11 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st);
 
+// ---- depthwise on small planes (at most 1024 elements): a run of planes per workgroup through LDS --------
+bool       small_planes_supported(int64_t planes, int planes_per_x, int H, int W, int R, int S, int Ho, int Wo);
+hipError_t launch_small_planes(const float* x, const float* w, float* y, int64_t planes, int n_filters, int H, int W,
+                               int R, int S, int stride, int pad, int Ho, int Wo, hipStream_t st);
+
 // ---- global pooling of planes of at most 256 elements: 64 planes per wavefront through LDS ----------------
 bool       global_pool_supported(int H, int W, int R, int S, int pad);
 hipError_t launch_global_pool(const float* x, float* y, int64_t planes, int HW, bool maximum, hipStream_t st);

@@ -150,6 +150,13 @@ PLANE_CASES = [
     (1, 1, 18, 252, 5, 5, 2, 0),
     (4, 64, 112, 112, 3, 3, 2, 1),  # ... 4-row bands
     (1, 2, 9, 8, 3, 3, 3, 1),       # stride 3: direct kernel
+    (2, 70, 14, 14, 3, 3, 1, 1),    # small planes: a run of planes per workgroup
+    (1, 100, 7, 7, 3, 3, 1, 1),
+    (1, 65, 7, 7, 5, 5, 1, 2),
+    (1, 64, 14, 14, 3, 3, 2, 1),
+    (1, 64, 13, 11, 4, 2, 2, 2),    # ... run-time filter extent, padding beyond the filter's need
+    (1, 64, 30, 30, 3, 3, 1, 1),    # ... ragged 30 x 30 planes
+    (3, 50, 5, 9, 5, 7, 1, 3),
     (1, 2, 7, 5, 7, 5, 1, 0),
     (1, 2, 16, 16, 3, 3, 1, 2),     # padding wider than the usual (R-1)/2
 ]

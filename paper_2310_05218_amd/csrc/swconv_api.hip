@@ -81,9 +81,12 @@ int run_plane(const float* x, const float* w, float* y, int64_t planes, int plan
             small_planes_supported(planes, planes_per_x, s.H, s.W, s.R, s.S, s.Ho, s.Wo))
             return launch_status(launch_small_planes(x, w, y, planes, n_filters, s.H, s.W, s.R, s.S, s.stride, s.pad,
                                                      s.Ho, s.Wo, st));
+        const bool rows = !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad);
+        // the whole-plane kernel spends a 56 x 56 tile per plane: planes up to 32 wide leave most of its lanes
+        // idle and go to the rows kernel (lane groups) when that has a variant
         const bool whole = s.stride == 1 && sliding_plane_whole(x, y, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) &&
-                           planes >= 512 && !(no_whole_plane_kernel() && s.R < 7);
-        if (!whole && !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad))
+                           planes >= 512 && !(no_whole_plane_kernel() && s.R < 7) && !(rows && s.W <= 32);
+        if (!whole && rows)
             return launch_status(launch_sliding_rows(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
                                                      s.stride, s.pad, s.Ho, s.Wo, st));
         if (sliding_plane_supported(s.H, s.W, s.R, s.S, s.stride, s.pad) &&

@@ -4,49 +4,62 @@
 //
 // A 56 x 56 tile per wavefront wastes most of its lanes on such planes, and one thread per output reads them
 // with scattered accesses.  Here a workgroup takes a run of consecutive planes -- which is one contiguous run
-// of memory, whatever the plane's width -- and brings it into LDS once with coalesced loads (16 bytes per lane
-// when the run is aligned), together with the planes' filters.  Every thread then produces outputs idx,
-// idx + 256, ... of the run: the window of an output is read from LDS at shifted addresses (positions outside
-// the plane are the zero padding and are skipped), and since consecutive outputs are consecutive in memory
-// the stores are coalesced as they are.
+// of memory, whatever the plane's width -- and brings it into LDS once with coalesced loads, each plane framed
+// by its zero padding, together with the planes' filters.  A thread then owns four consecutive outputs of a
+// column: for every filter column it reads the R + 3 inputs they depend on once and slides them under the
+// taps (register rename), exactly the 1-D sliding sum turned upright; no position needs a bounds test because
+// the padding is in LDS.  Consecutive threads own consecutive columns, so LDS reads fall into distinct banks
+// and every store instruction writes a run of consecutive outputs.
 #include "swconv_internal.h"
 
 namespace swconv {
 
 namespace {
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
 constexpr int kThreads = 256;
 constexpr int kLdsFloats = 12 * 1024;      // 48 KB per workgroup: three workgroups per CU
 
 struct SmallParams {
     int H, W, R, S, stride, pad, Ho, Wo, n_filters, G;
+    int Hp, Wp, QH;                        // framed plane in LDS, groups of four output rows
     int64_t planes;
-    FastDiv by_HoWo, by_Wo;
+    FastDiv by_frame, by_Wp, by_items, by_Wo;
 };
 
-// RC, SC > 0: filter extent at compile time (taps unrolled); 0: at run time.
-template <int RC, int SC>
+// RC, SC, STC > 0: filter extent and stride at compile time (taps unrolled); 0: at run time.
+template <int RC, int SC, int STC>
 __global__ __launch_bounds__(kThreads) void small_planes_kernel(const float* __restrict__ x, const float* __restrict__ w,
-                                                                float* __restrict__ y, const SmallParams P, int x_vec_ok)
+                                                                float* __restrict__ y, const SmallParams P)
 {
     extern __shared__ __attribute__((aligned(16))) float lds[];
-    const int R = RC > 0 ? RC : P.R, S = RC > 0 ? SC : P.S;
+    const int R = RC > 0 ? RC : P.R, S = RC > 0 ? SC : P.S, ST = RC > 0 ? STC : P.stride;
     const int HW = P.H * P.W, RS = R * S, HoWo = P.Ho * P.Wo;
+    const int frame = P.Hp * P.Wp;
     const int tid = threadIdx.x;
     const int64_t p0 = (int64_t)blockIdx.x * P.G;
     const int np = P.planes - p0 < P.G ? (int)(P.planes - p0) : P.G;
-    float* xs = lds;                               // [np][HW]
-    float* ws = lds + ((P.G * HW + 3) & ~3);       // [np][RS]
+    float* xs = lds;                               // [np][Hp][Wp]
+    float* ws = lds + P.G * frame;                 // [np][RS]
 
-    // the run of planes, as it lies in memory
-    const int n = np * HW;
+    // every cell of the framed planes: the image where there is one, zero (the padding) around it; loads go
+    // out eight per thread before the first LDS write, so a batch costs one memory round trip
     const float* src = x + p0 * HW;
-    const int n4 = (x_vec_ok && ((p0 * HW) & 3) == 0) ? n >> 2 : 0;
-    for (int i = tid; i < n4; i += kThreads)
-        reinterpret_cast<floatx4*>(xs)[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(src) + i);
-    for (int i = 4 * n4 + tid; i < n; i += kThreads) xs[i] = src[i];
+    for (int base = tid; base < np * frame; base += kThreads * 8) {
+        float v8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = base + kThreads * u;
+            const int g = fast_div(i, P.by_frame);
+            const int c = i - g * frame;
+            const int hp = fast_div(c, P.by_Wp), vp = c - hp * P.Wp;
+            const int h = hp - P.pad, v = vp - P.pad;
+            v8[u] = 0.f;
+            if (i < np * frame && (unsigned)h < (unsigned)P.H && (unsigned)v < (unsigned)P.W) v8[u] = src[g * HW + h * P.W + v];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (base + kThreads * u < np * frame) xs[base + kThreads * u] = v8[u];
+    }
     // the filters of these planes (plane p uses filter p % n_filters)
     for (int i = tid; i < np * RS; i += kThreads) {
         const int g = i / RS;
@@ -55,42 +68,65 @@ __global__ __launch_bounds__(kThreads) void small_planes_kernel(const float* __r
     __syncthreads();
 
     float* dst = y + p0 * HoWo;
-    for (int idx = tid; idx < np * HoWo; idx += kThreads) {
-        const int g = fast_div(idx, P.by_HoWo);
-        const int pix = idx - g * HoWo;
-        const int oi = fast_div(pix, P.by_Wo), oj = pix - oi * P.Wo;
-        const int h0 = oi * P.stride - P.pad, v0 = oj * P.stride - P.pad;
-        const float* xg = xs + g * HW;
+    const int items = P.QH * P.Wo;                 // groups of four outputs (one column, four rows) per plane
+    for (int idx = tid; idx < np * items; idx += kThreads) {
+        const int g = fast_div(idx, P.by_items);
+        const int it = idx - g * items;
+        const int qi = fast_div(it, P.by_Wo), oj = it - qi * P.Wo;
+        const int oi = 4 * qi;
+        const float* xp = xs + g * frame + (oi * ST) * P.Wp + oj * ST;
         const float* wf = ws + g * RS;
-        float acc = 0.f;
-        if (RC > 0) {
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (RC > 0) {
+            constexpr int N = 3 * STC + RC;        // inputs of a filter column that the four outputs touch
 #pragma unroll
-            for (int r = 0; r < (RC > 0 ? RC : 1); ++r)
+            for (int q = 0; q < SC; ++q) {
+                float in[N];
 #pragma unroll
-                for (int q = 0; q < (SC > 0 ? SC : 1); ++q) {
-                    // (positions outside the plane read element 0 and count as zero: no address leaves the plane)
-                    const bool in = (unsigned)(h0 + r) < (unsigned)P.H && (unsigned)(v0 + q) < (unsigned)P.W;
-                    const float e = xg[in ? (h0 + r) * P.W + v0 + q : 0];
-                    acc = fmaf(wf[r * SC + q], in ? e : 0.f, acc);
+                for (int c = 0; c < N; ++c) in[c] = xp[c * P.Wp + q];
+#pragma unroll
+                for (int r = 0; r < RC; ++r) {
+                    const float tap = wf[r * SC + q];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[j] = fmaf(tap, in[j * STC + r], acc[j]);
                 }
+            }
         } else {
-            const int r_lo = h0 < 0 ? -h0 : 0, r_hi = P.H - h0 < R ? P.H - h0 : R;
-            const int q_lo = v0 < 0 ? -v0 : 0, q_hi = P.W - v0 < S ? P.W - v0 : S;
-            for (int r = r_lo; r < r_hi; ++r)
-                for (int q = q_lo; q < q_hi; ++q) acc = fmaf(wf[r * S + q], xg[(h0 + r) * P.W + v0 + q], acc);
+            for (int r = 0; r < R; ++r)
+                for (int q = 0; q < S; ++q) {
+                    const float tap = wf[r * S + q];
+                    const float* col = xp + r * P.Wp + q;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[j] = fmaf(tap, col[j * ST * P.Wp], acc[j]);
+                }
         }
-        dst[idx] = acc;
+        float* o = dst + g * HoWo + oi * P.Wo + oj;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (oi + j < P.Ho) o[j * P.Wo] = acc[j];
     }
+}
+
+// Frame of a plane in LDS: the rows and columns that outputs (with their four-wide groups) can touch.
+void frame_of(int R, int S, int stride, int Ho, int Wo, int* Hp, int* Wp, int* QH)
+{
+    *QH = (Ho + 3) / 4;
+    *Hp = (4 * *QH - 1) * stride + R;
+    *Wp = (Wo - 1) * stride + S;
 }
 
 }  // namespace
 
-// Planes of at most 1024 elements, at least 8 of them per workgroup's LDS, one input plane per output plane.
-bool small_planes_supported(int64_t planes, int planes_per_x, int H, int W, int R, int S, int Ho, int Wo)
+// Planes of at most 1024 elements, at least 4 of them per workgroup's LDS, one input plane per output plane.
+bool small_planes_supported(int64_t planes, int planes_per_x, int H, int W, int R, int S, int stride, int Ho, int Wo)
 {
-    if (planes_per_x != 1 || (int64_t)H * W > 1024 || planes < 64) return false;
-    const int G = kLdsFloats / (H * W + R * S + 1);
-    return G >= 8 && (int64_t)G * Ho * Wo < 65536 && R * S <= 1024;
+    if (planes_per_x != 1 || (int64_t)H * W > 1024 || planes < 64 || R * S > 1024 || stride > 8) return false;
+    int Hp, Wp, QH;
+    frame_of(R, S, stride, Ho, Wo, &Hp, &Wp, &QH);
+    const int64_t per = (int64_t)Hp * Wp + R * S;
+    if (per > kLdsFloats / 4) return false;
+    const int64_t G = kLdsFloats / per;
+    return G * Hp * Wp < 65536;
 }
 
 hipError_t launch_small_planes(const float* x, const float* w, float* y, int64_t planes, int n_filters, int H, int W,
@@ -99,24 +135,29 @@ hipError_t launch_small_planes(const float* x, const float* w, float* y, int64_t
     SmallParams P;
     P.H = H; P.W = W; P.R = R; P.S = S; P.stride = stride; P.pad = pad; P.Ho = Ho; P.Wo = Wo;
     P.n_filters = n_filters; P.planes = planes;
-    int G = kLdsFloats / (H * W + R * S + 1);
+    frame_of(R, S, stride, Ho, Wo, &P.Hp, &P.Wp, &P.QH);
+    const int per = P.Hp * P.Wp + R * S;
+    int G = kLdsFloats / per;
     // enough workgroups to fill the chip three times over before the groups grow to the LDS limit
-    while (G > 8 && (planes + G - 1) / G < 3 * 256) G = (G + 1) / 2;
+    while (G > 4 && (planes + G - 1) / G < 3 * 256) G = (G + 1) / 2;
     if (G > 64) G = 64;
     P.G = G;
-    P.by_HoWo = make_fastdiv(Ho * Wo);
+    P.by_frame = make_fastdiv(P.Hp * P.Wp);
+    P.by_Wp = make_fastdiv(P.Wp);
+    P.by_items = make_fastdiv(P.QH * Wo);
     P.by_Wo = make_fastdiv(Wo);
     const int64_t groups = (planes + G - 1) / G;
     if (groups > 2147483647LL) return hipErrorInvalidValue;
-    const size_t lds = (size_t)(((G * H * W + 3) & ~3) + G * R * S) * sizeof(float);
-    const int x_vec_ok = reinterpret_cast<uintptr_t>(x) % 16 == 0;
+    const size_t lds = (size_t)G * per * sizeof(float);
     dim3 grid((unsigned)groups), block(kThreads);
-    if (R == 3 && S == 3)
-        hipLaunchKernelGGL((small_planes_kernel<3, 3>), grid, block, lds, st, x, w, y, P, x_vec_ok);
-    else if (R == 5 && S == 5)
-        hipLaunchKernelGGL((small_planes_kernel<5, 5>), grid, block, lds, st, x, w, y, P, x_vec_ok);
-    else
-        hipLaunchKernelGGL((small_planes_kernel<0, 0>), grid, block, lds, st, x, w, y, P, x_vec_ok);
+#define SW_SMALL(RC, STC)                                                                                     \
+    if (R == RC && S == RC && stride == STC) {                                                                \
+        hipLaunchKernelGGL((small_planes_kernel<RC, RC, STC>), grid, block, lds, st, x, w, y, P);             \
+        return hipGetLastError();                                                                             \
+    }
+    SW_SMALL(3, 1) SW_SMALL(3, 2) SW_SMALL(5, 1) SW_SMALL(5, 2) SW_SMALL(7, 1)
+#undef SW_SMALL
+    hipLaunchKernelGGL((small_planes_kernel<0, 0, 0>), grid, block, lds, st, x, w, y, P);
     return hipGetLastError();
 }
 

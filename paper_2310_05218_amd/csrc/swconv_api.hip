@@ -77,8 +77,8 @@ int run_plane(const float* x, const float* w, float* y, int64_t planes, int plan
     if (!force_direct()) {
         // planes up to 20 x 20, and larger ragged ones (width not a multiple of 4) that the register-only and
         // whole-plane kernels do not take: a run of planes per workgroup
-        if (!no_small_planes_kernel() && (s.H * s.W <= 400 || s.W % 4 != 0) &&
-            small_planes_supported(planes, planes_per_x, s.H, s.W, s.R, s.S, s.Ho, s.Wo))
+        if (!no_small_planes_kernel() && (s.H * s.W <= 400 || s.W % 4 != 0 || s.R * s.S >= 25) &&
+            small_planes_supported(planes, planes_per_x, s.H, s.W, s.R, s.S, s.stride, s.Ho, s.Wo))
             return launch_status(launch_small_planes(x, w, y, planes, n_filters, s.H, s.W, s.R, s.S, s.stride, s.pad,
                                                      s.Ho, s.Wo, st));
         const bool rows = !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad);

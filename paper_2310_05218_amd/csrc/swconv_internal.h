@@ -60,7 +60,8 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int Ho, int Wo, hipStream_t st);
 
 // ---- depthwise on small planes (at most 1024 elements): a run of planes per workgroup through LDS --------
-bool       small_planes_supported(int64_t planes, int planes_per_x, int H, int W, int R, int S, int Ho, int Wo);
+bool       small_planes_supported(int64_t planes, int planes_per_x, int H, int W, int R, int S, int stride, int Ho,
+                                  int Wo);
 hipError_t launch_small_planes(const float* x, const float* w, float* y, int64_t planes, int n_filters, int H, int W,
                                int R, int S, int stride, int pad, int Ho, int Wo, hipStream_t st);
 

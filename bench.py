@@ -59,14 +59,14 @@ SECOND_ROOF = {"depthwise_7x7": (VALU_F32_TFLOPS, "frac_alu_f32_plain_fma"),
 # profiles/hbm_traffic_all_kernels.txt), with the kernel source and its sha256 prefix at the time the
 # counters were taken.  A kernel whose source has changed since reports traffic = null.
 TRAFFIC = {
-    "conv2d_1ch_3x3": (637795, "sw_sliding_rows.hip", "1183d74112b4cf49"),
-    "conv1d_k9": (33932955, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
-    "avgpool1d_w8": (34176570, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
-    "maxpool1d_w8": (34175194, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
-    "conv2d_64x64_3x3": (62469883, "sw_mfma_f32.hip", "92e3afdd59a9d250"),
-    "depthwise_3x3": (206847393, "sw_sliding_plane.hip", "12d7b9e73893c6ae"),
-    "depthwise_7x7": (206140934, "sw_sliding_plane.hip", "12d7b9e73893c6ae"),
-    "conv2d_s8_128x128_3x3": (21059791, "sw_mfma_s8.hip", "7425273640eeae94"),
+    "conv2d_64x64_3x3": (62438038, "sw_mfma_f32.hip", "5d43ed48fdbb08a2"),
+    "depthwise_3x3": (207300847, "sw_sliding_plane.hip", "bbd3c61f82b1358d"),
+    "depthwise_7x7": (206193231, "sw_sliding_plane.hip", "bbd3c61f82b1358d"),
+    "conv2d_s8_128x128_3x3": (21150242, "sw_mfma_s8.hip", "e4d62c0d4706586a"),
+    "conv1d_k9": (33992686, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
+    "avgpool1d_w8": (34272782, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
+    "maxpool1d_w8": (34263950, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
+    "conv2d_1ch_3x3": (637797, "sw_sliding_rows.hip", "1183d74112b4cf49"),
 }
 
 

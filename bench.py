@@ -301,7 +301,7 @@ def main():
                          "every kernel of the step twice; prints nothing but a marker line")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit("bench.py: this library runs on one GPU only (no collectives, no sharding); use --gpus 1")
 
     import torch
 

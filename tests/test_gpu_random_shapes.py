@@ -1,0 +1,140 @@
+"""Seeded random shapes through every entry point, each checked element by element against the CPU oracle.
+The shapes are drawn so that every kernel selection rule of the library is crossed many times (small and
+ragged planes, strides, paddings up to the filter extent, odd channel counts, wide rows)."""
+import numpy as np
+import pytest
+
+from paper_2310_05218_amd import inputs
+from parity import assert_f32_parity, guarded_empty, assert_guards_intact
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as t
+    if not t.cuda.is_available():
+        pytest.skip("no GPU")
+    return t
+
+
+@pytest.fixture(scope="module")
+def sw():
+    import paper_2310_05218_amd as m
+    from paper_2310_05218_amd import binding
+    binding.lib()
+    return m
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _shape(rng, max_hw, max_k, max_stride=3):
+    R, S = int(rng.integers(1, max_k + 1)), int(rng.integers(1, max_k + 1))
+    if rng.random() < 0.5:
+        S = R
+    stride = int(rng.integers(1, max_stride + 1))
+    pad = int(rng.integers(0, max(R, S)))
+    H = int(rng.integers(max(1, R - 2 * pad), max_hw + 1))
+    W = int(rng.integers(max(1, S - 2 * pad), max_hw + 1))
+    if rng.random() < 0.4:
+        W = (W + 3) // 4 * 4
+    return H, W, R, S, stride, pad
+
+
+def _cases(seed, n, **kw):
+    rng = np.random.default_rng(seed)
+    return [(i,) + _shape(rng, **kw) + (int(rng.integers(0, 1 << 30)),) for i in range(n)]
+
+
+@pytest.mark.parametrize("case", _cases(71, 40, max_hw=70, max_k=9), ids=lambda c: "x".join(map(str, c[1:7])))
+def test_depthwise_random(torch, sw, oracle, case):
+    _, H, W, R, S, stride, pad, seed = case
+    rng = np.random.default_rng(seed)
+    N, C = int(rng.integers(1, 4)), int(rng.choice([1, 3, 8, 70, 130]))
+    x = inputs.normal_f32((N, C, H, W), seed % 100000)
+    w = inputs.normal_f32((C, 1, R, S), seed % 100000 + 1)
+    y_ref, d = oracle.conv2d_depthwise(x, w, stride, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_depthwise(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"depthwise {case} N={N} C={C}")
+
+
+@pytest.mark.parametrize("case", _cases(72, 40, max_hw=40, max_k=7), ids=lambda c: "x".join(map(str, c[1:7])))
+def test_conv2d_random(torch, sw, oracle, case):
+    _, H, W, R, S, stride, pad, seed = case
+    rng = np.random.default_rng(seed)
+    N = int(rng.integers(1, 3))
+    C_in, C_out = int(rng.choice([1, 2, 3, 7, 16, 24, 33])), int(rng.choice([1, 5, 32, 64, 70]))
+    x = inputs.normal_f32((N, C_in, H, W), seed % 100000)
+    w = inputs.normal_f32((C_out, C_in, R, S), seed % 100000 + 1)
+    y_ref, d = oracle.conv2d(x, w, stride, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"conv2d {case} N={N} C_in={C_in} C_out={C_out}")
+
+
+@pytest.mark.parametrize("case", _cases(73, 30, max_hw=36, max_k=5), ids=lambda c: "x".join(map(str, c[1:7])))
+def test_conv2d_s8_random(torch, sw, oracle, case):
+    _, H, W, R, S, stride, pad, seed = case
+    rng = np.random.default_rng(seed)
+    N = int(rng.integers(1, 3))
+    C_in, C_out = int(rng.choice([1, 3, 16, 40, 64, 100])), int(rng.choice([1, 5, 64, 70]))
+    x = inputs.uniform_s8((N, C_in, H, W), seed % 100000)
+    w = inputs.uniform_s8((C_out, C_in, R, S), seed % 100000 + 1)
+    y_ref = oracle.conv2d_s8(x, w, stride, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.int32)
+    sw.sw_conv2d_s8(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert np.array_equal(out.cpu().numpy(), y_ref), f"conv2d_s8 {case} N={N} C_in={C_in} C_out={C_out}"
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("case", _cases(74, 30, max_hw=70, max_k=6), ids=lambda c: "x".join(map(str, c[1:7])))
+def test_pool2d_random(torch, sw, oracle, case, mode):
+    _, H, W, R, S, stride, pad, seed = case
+    pad = min(pad, min(R, S) // 2)          # the library's contract: no window wholly inside the padding
+    if H + 2 * pad < R or W + 2 * pad < S:
+        pytest.skip("window larger than the padded plane")
+    rng = np.random.default_rng(seed)
+    N, C = int(rng.integers(1, 3)), int(rng.choice([1, 3, 64, 100]))
+    x = inputs.normal_f32((N, C, H, W), seed % 100000) - (2.0 if mode else 0.0)
+    y_ref, d = oracle.pool2d(x, R, S, stride, pad, mode)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_pool2d(dev(torch, x), R, S, stride, pad, mode, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    y = out.cpu().numpy()
+    if mode == 1:
+        assert np.array_equal(y.astype(np.float64), y_ref), f"max pool2d {case}"
+    else:
+        assert_f32_parity(y, y_ref, d, f"avg pool2d {case}")
+
+
+@pytest.mark.parametrize("case", list(range(30)))
+def test_conv1d_and_pool1d_random(torch, sw, oracle, case):
+    rng = np.random.default_rng(7500 + case)
+    rows = int(rng.integers(1, 6))
+    k = int(rng.integers(1, 40))
+    stride = int(rng.choice([1, 1, 1, 2, 3]))
+    pad = int(rng.integers(0, k))
+    length = int(rng.integers(max(1, k - 2 * pad), 9000))
+    x = inputs.normal_f32((rows, length), 7600 + case)
+    w = inputs.normal_f32((k,), 7700 + case)
+    y_ref, d = oracle.conv1d(x, w, stride, pad)
+    y = sw.sw_conv1d(dev(torch, x), dev(torch, w), stride, pad).cpu().numpy()
+    assert_f32_parity(y, y_ref, d, f"conv1d k={k} stride={stride} pad={pad} len={length}")
+    if length >= k:
+        for mode in (0, 1):
+            y_ref, d = oracle.pool1d(x, k, stride, mode)
+            y = sw.sw_pool1d(dev(torch, x), k, stride, mode).cpu().numpy()
+            if mode == 1:
+                assert np.array_equal(y.astype(np.float64), y_ref)
+            else:
+                assert_f32_parity(y, y_ref, d, f"avg pool1d window={k} stride={stride} len={length}")

@@ -202,6 +202,40 @@ def filter_size_sweep(torch, sw):
     return {"sweep": "depthwise-shaped 32x64x56x56 fp32, square filter, stride 1, same padding", "rows": rows}
 
 
+def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, stride, pad, C_out):
+    """One multi-channel layer of the table below (fp32 or int8), checked on one image against the oracle."""
+    N, C, H, W = shape
+    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    s8 = kind == "conv_s8"
+    if s8:
+        x = inputs.uniform_s8(shape, inputs.seed_for(7, idx))
+        w = inputs.uniform_s8((C_out, C, R, R), inputs.seed_for(7, 100 + idx))
+        call, odt, esz = sw.sw_conv2d_s8, torch.int32, 1
+    else:
+        x = inputs.normal_f32(shape, inputs.seed_for(7, idx))
+        w = inputs.normal_f32((C_out, C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
+        call, odt, esz = sw.sw_conv2d, torch.float32, 4
+    xs, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    y = call(xs[:1].contiguous(), wd, stride, pad).cpu().numpy()
+    if s8:
+        assert np.array_equal(y, oracle.conv2d_s8(x[:1], w, stride, pad)), name
+        err = 0.0
+    else:
+        y_ref, d = oracle.conv2d(x[:1], w, stride, pad)
+        err = float(np.max(np.abs(y - y_ref) / d))
+        assert err <= 2e-5, (name, err)
+    nbytes = x.nbytes + w.nbytes + N * C_out * Ho * Wo * 4
+    nsets = min(16, max(3, -(-COLD_ROTATION_BYTES // nbytes)))
+    sets = [{"x": xs if i == 0 else xs.clone(), "y": torch.empty((N, C_out, Ho, Wo), dtype=odt, device="cuda")}
+            for i in range(nsets)]
+    us = time_kernel(torch, lambda s_: call(s_["x"], wd, stride, pad, out=s_["y"]), sets, 2 * nsets)
+    ops = 2.0 * N * C_out * Ho * Wo * C * R * R
+    peak = MFMA_I8_TOPS if s8 else MFMA_F32_TFLOPS
+    return {"layer": name, "shape": list(shape) + [C_out], "us_cold": round(us, 2), "gbs": round(nbytes / us / 1e3, 1),
+            "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4), "gops": round(ops / us / 1e3, 1),
+            "frac_mfma": round(ops / us / 1e6 / peak, 4), "max_norm_err": float("%.2e" % err)}
+
+
 def strided_and_pooling_table(torch, sw):
     """2-D pooling and stride-2 layers of common CNN shapes (fp32 N(0,1) activations), timed cold like the
     step's kernels; each is first checked against the CPU oracle on two planes.  All are bound by HBM:
@@ -219,10 +253,22 @@ def strided_and_pooling_table(torch, sw):
         ("depthwise_3x3_s2", "dw", (32, 128, 112, 112), 3, 2, 1),
         ("depthwise_5x5_s2", "dw", (32, 128, 112, 112), 5, 2, 2),
         ("global_avgpool_7x7", "avg", (32, 2048, 7, 7), 7, 1, 0),
+        ("depthwise_3x3_28x28", "dw", (32, 256, 28, 28), 3, 1, 1),
+        ("depthwise_3x3_14x14", "dw", (32, 512, 14, 14), 3, 1, 1),
+        ("depthwise_7x7_14x14", "dw", (32, 384, 14, 14), 7, 1, 3),
+        ("conv_7x7_s2_3to64", "conv", (32, 3, 224, 224), 7, 2, 3, 64),
+        ("conv_3x3_s2_64to128", "conv", (32, 64, 56, 56), 3, 2, 1, 128),
+        ("conv_1x1_256to64", "conv", (32, 256, 56, 56), 1, 1, 0, 64),
+        ("conv_3x3_14x14_256", "conv", (32, 256, 14, 14), 3, 1, 1, 256),
+        ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
+        ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
     ]
     rows = []
-    for idx, (name, kind, shape, R, stride, pad) in enumerate(layers):
+    for idx, (name, kind, shape, R, stride, pad, *more) in enumerate(layers):
         N, C, H, W = shape
+        if kind in ("conv", "conv_s8"):
+            rows.append(_conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, stride, pad, more[0]))
+            continue
         Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
         x = inputs.normal_f32(shape, inputs.seed_for(7, idx))
         in_bytes, out_bytes = x.nbytes, N * C * Ho * Wo * 4
@@ -255,7 +301,7 @@ def strided_and_pooling_table(torch, sw):
                      "max_norm_err": float("%.2e" % err)})
         del sets, xs
         torch.cuda.empty_cache()
-    return {"table": "2-D pooling and stride-2 layers, fp32, cold (rotation larger than the Infinity Cache)",
+    return {"table": "2-D pooling, stride-2, small-plane and other multi-channel layers, cold (rotation larger than the Infinity Cache)",
             "rows": rows}
 
 

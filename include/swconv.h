@@ -58,6 +58,8 @@ typedef enum { SW_POOL_AVG = 0, SW_POOL_MAX = 1 } sw_pool_mode;
  * x: [rows, len] fp32;  w: [k] fp32, one tap vector shared by all rows;
  * y: [rows, len_out] fp32, len_out = sw_out_dim(len, k, stride, pad).
  * Supported: 1 <= k <= 64, pad < k.  Otherwise SW_ERR_UNSUPPORTED.
+ * Stride 1 runs the sliding kernel, strides 2..8 a tiled kernel that reads each
+ * input once through LDS, larger strides one thread per output.
  */
 int sw_conv1d(const float* x, const float* w, float* y,
               int64_t rows, int64_t len, int k, int stride, int pad, void* hip_stream);
@@ -70,6 +72,9 @@ int sw_conv1d(const float* x, const float* w, float* y,
  * bit-exact; NaN inputs are outside the contract.
  * x: [rows, len];  y: [rows, sw_out_dim(len, window, stride, 0)].
  * Supported: 1 <= window <= 64.  mode is an sw_pool_mode (else SW_ERR_UNSUPPORTED).
+ * Kernels as for sw_conv1d; windows that tile the rows (stride == window in
+ * {2, 4, 8}, len a multiple of 4 and of the window, 16-byte aligned x, 8-byte
+ * aligned y) run a register-only kernel.
  */
 int sw_pool1d(const float* x, float* y, int64_t rows, int64_t len,
               int window, int stride, int mode, void* hip_stream);

@@ -137,6 +137,10 @@ int run_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len, 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (!force_direct() && sliding_1d_supported(len, k, stride, pad))
         return launch_status(launch_sliding_1d(x, w, y, rows, len, len_out, k, pad, op, st));
+    if (!force_direct() && op != OP_CONV && pool_tiles_supported(x, y, len, k, stride))
+        return launch_status(launch_pool_tiles(x, y, rows, len, k, op == OP_MAX, st));
+    if (!force_direct() && strided_1d_supported(rows, len, len_out, k, stride, pad))
+        return launch_status(launch_strided_1d(x, w, y, rows, len, len_out, k, stride, pad, op, st));
     return launch_status(launch_direct_1d(x, w, y, rows, len, len_out, k, stride, pad, op, st));
 }
 

@@ -39,6 +39,16 @@ bool       sliding_1d_supported(int64_t len, int k, int stride, int pad);
 hipError_t launch_sliding_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
                              int64_t len_out, int k, int pad, Op1D op, hipStream_t st);
 
+// ---- 1-D kernel for strides 2..8: contiguous input run per tile through LDS ---------------------------------
+bool       strided_1d_supported(int64_t rows, int64_t len, int64_t len_out, int k, int stride, int pad);
+hipError_t launch_strided_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len, int64_t len_out,
+                             int k, int stride, int pad, Op1D op, hipStream_t st);
+
+// ---- pooling whose windows tile the rows (stride == window in {2, 4, 8}): registers only --------------------
+bool       pool_tiles_supported(const float* x, const float* y, int64_t len, int window, int stride);
+hipError_t launch_pool_tiles(const float* x, float* y, int64_t rows, int64_t len, int window, bool maximum,
+                             hipStream_t st);
+
 // ---- sliding plane kernel (stride 1): one filter per plane (single channel, depthwise) --------
 // x plane index for output plane p is p / planes_per_x (conv2d with C_in == 1: C_out filters share
 // one input plane; depthwise: 1); filter index is p % n_filters.

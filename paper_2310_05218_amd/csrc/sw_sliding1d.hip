@@ -24,7 +24,7 @@ __device__ __forceinline__ void stream_store4(float* p, floatx4 v) { __builtin_n
 
 constexpr int kThreads = 256;
 constexpr int kSub = kThreads * 4;      // outputs per pass over the workgroup
-constexpr int kPasses = 2;
+constexpr int kPasses = 4;
 constexpr int kTile = kSub * kPasses;   // outputs per workgroup
 constexpr int kMaxK = 64;
 constexpr int kMaxBlocks = 256 * 32;     // workgroups per launch; beyond that a workgroup walks over several tiles

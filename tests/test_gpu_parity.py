@@ -38,7 +38,9 @@ CONV1D_CASES = [
     (1, 9, 9, 1, 0),            # a single output
     (3, 17, 3, 1, 0),
     (2, 4173, 9, 1, 0),         # two tiles and a ragged tail, row length not a multiple of 4
-    (3, 6144 + 8, 9, 1, 0),     # output length an exact multiple of the tile
+    (3, 6144 + 8, 9, 1, 0),
+    (2, 8300, 9, 1, 0),         # two tiles of 4096 and a ragged tail
+    (3, 12288 + 8, 9, 1, 0),    # output length an exact multiple of the tile
     (5, 5000, 1, 1, 0),
     (4, 5000, 2, 1, 1),
     (4, 4100, 5, 1, 4),
@@ -71,7 +73,7 @@ def test_conv1d(torch, sw, oracle, case):
 
 
 def test_conv1d_more_tiles_than_workgroups(torch, sw, oracle):
-    # 9000 tiles of 2048 outputs > 8192 workgroups: some workgroups walk over two tiles (prefetch path)
+    # 9000 tiles (one per row) > 8192 workgroups: some workgroups walk over two tiles (prefetch path)
     x = inputs.normal_f32((9000, 2051), 1003)
     w = inputs.normal_f32((5,), 1004)
     y_ref, d = oracle.conv1d(x, w, 1, 1)
@@ -79,7 +81,7 @@ def test_conv1d_more_tiles_than_workgroups(torch, sw, oracle):
     assert_f32_parity(y.cpu().numpy(), y_ref, d, "conv1d 9000 x 2051")
 
 
-POOL_CASES = [(1, 8, 8, 1), (3, 4173, 8, 1), (2, 6144 + 7, 8, 1), (4, 5000, 3, 1), (2, 5000, 1, 1),
+POOL_CASES = [(1, 8, 8, 1), (3, 4173, 8, 1), (2, 6144 + 7, 8, 1), (2, 12288 + 7, 8, 1), (3, 9001, 8, 1), (4, 5000, 3, 1), (2, 5000, 1, 1),
               (3, 4099, 2, 2), (5, 9000, 3, 2), (2, 10001, 4, 4), (2, 30000, 8, 8),
               (3, 4100, 2, 2), (5, 9000, 4, 4), (7, 10008, 8, 8), (1, 8, 8, 8), (64, 8192, 2, 2),   # windows tile the rows
               (2, 4100, 17, 1), (2, 4100, 40, 1), (2, 3000, 64, 1), (3, 1000, 8, 2), (3, 1001, 3, 3)]

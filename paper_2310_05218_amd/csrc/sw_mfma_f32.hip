@@ -156,6 +156,13 @@ __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restric
 #pragma unroll
         for (int i = 0; i <= kNFix; ++i) b[i] = lx[boff[i] + toff];
     };
+    // the same, one 16-byte read at a time: piece 0 is A, piece 1 + i is B of block i
+    auto load_piece = [&](int step, int piece, int bofs, floatx4& a, floatx4 (&b)[kNFix + 1]) {
+        const int tap = step >> 1, o = step & 1;
+        const int r = tap / S, q = tap - S * r;
+        if (piece == 0) a = *reinterpret_cast<const floatx4*>(aptr + bofs + (tap * 4 + 2 * o) * kWGroupBytes);
+        else b[piece - 1] = lx[boff[piece - 1] + (bofs >> 4) + 2 * o * kLdsPx + r * IW + q];
+    };
     auto load_swing = [&](int step, int bofs, floatx4& a, floatx4& b) {
         const int tap = step >> 1, o = step & 1;
         const int r = tap / S, q = tap - S * r;
@@ -205,19 +212,25 @@ __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restric
 #pragma unroll
         for (int step = 0; step < NSTEP; ++step) {
             const int cur = step & 1;
-            if (step + 1 < NSTEP) load_step(step + 1, bofs, a[cur ^ 1], b[cur ^ 1]);
-            if (step >= FETCH_AT && step < FETCH_AT + kXItems) fetch_part((ch + 1) * kCK, step - FETCH_AT);
-            if (DB && step >= STAGE_AT) stage_part(buf ^ 1, step - STAGE_AT);
-            __builtin_amdgcn_sched_barrier(0);      // keep reads and copies ahead of the matrix instructions
+            // Everything that is not a matrix instruction -- the LDS reads of the next step's operands, one part
+            // of the next chunk's global loads, one part of its copy into the other LDS buffer -- is issued one
+            // instruction group at a time between the matrix instructions, whose pipe runs on meanwhile.
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
 #pragma unroll
-                for (int i = 0; i < kNFix; ++i)
+                for (int i = 0; i < kNFix; ++i) {
                     acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][t], b[cur][i][t], acc[i], 0, 0, 0);
+                    const int slot = t * kNFix + i;
+                    if (step + 1 < NSTEP && slot <= kNFix + 1) load_piece(step + 1, slot, bofs, a[cur ^ 1], b[cur ^ 1]);
+                    if (slot == kNFix + 2 && step >= FETCH_AT && step < FETCH_AT + kXItems)
+                        fetch_part((ch + 1) * kCK, step - FETCH_AT);
+                    if (slot == kNFix + 6 && DB && step >= STAGE_AT) stage_part(buf ^ 1, step - STAGE_AT);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 if ((step & 1) == wn)               // the swing block: only this wavefront's octet
                     acc[kNFix] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cur][t], b[cur][kNFix][t], acc[kNFix], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
         if (!DB) {

@@ -225,8 +225,10 @@ hipError_t launch_rows(const float* x, const float* w, float* y, int64_t planes,
 bool sliding_rows_supported(const float* x, int H, int W, int R, int S, int stride, int pad)
 {
     (void)H;
-    if ((stride != 1 && stride != 2) || R != S || (R != 3 && R != 5) || pad > (R - 1) / 2 || pad < 0) return false;
-    // (padding beyond (R-1)/2 would need more than the compiled halo widths)
+    if ((stride != 1 && stride != 2) || R != S || (R != 3 && R != 5 && R != 7) || pad > (R - 1) / 2 || pad < 0) return false;
+    // (padding beyond (R-1)/2 would need more than the compiled halo widths; 7x7 reaches at most four columns into
+    // the right neighbour, which rules out the smallest paddings)
+    if (R == 7 && pad < (stride == 1 ? 2 : 1)) return false;
     return W % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0;
 }
 
@@ -242,6 +244,16 @@ hipError_t launch_sliding_rows(const float* x, const float* w, float* y, int64_t
         return launch_rows<RC, RC, PC, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);     \
     }
     SW_ROWS(3, 0) SW_ROWS(3, 1) SW_ROWS(5, 0) SW_ROWS(5, 1) SW_ROWS(5, 2)
+    if (R == 7 && pad == 3) {
+        if (stride == 1) return launch_rows<7, 7, 3, 1, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
+        return launch_rows<7, 7, 3, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
+    }
+    if (R == 7 && pad == 2) {
+        if (stride == 1) return launch_rows<7, 7, 2, 1, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
+        return launch_rows<7, 7, 2, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
+    }
+    if (R == 7 && pad == 1 && stride == 2)
+        return launch_rows<7, 7, 1, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
 #undef SW_ROWS
     return hipErrorInvalidValue;
 }

@@ -157,6 +157,11 @@ PLANE_CASES = [
     (1, 2, 21, 520, 3, 3, 2, 1),    # ... three strips
     (1, 1, 18, 252, 5, 5, 2, 0),
     (4, 64, 112, 112, 3, 3, 2, 1),  # ... 4-row bands
+    (2, 3, 112, 112, 7, 7, 1, 3),   # rows kernel, 7x7: three columns from either neighbour lane
+    (1, 2, 61, 300, 7, 7, 1, 2),    # ... two strips
+    (1, 2, 64, 68, 7, 7, 2, 3),
+    (1, 2, 33, 520, 7, 7, 2, 1),
+    (1, 2, 64, 64, 7, 7, 1, 1),     # 7x7 with padding 1: tile kernel
     (1, 2, 9, 8, 3, 3, 3, 1),       # stride 3: direct kernel
     (2, 70, 14, 14, 3, 3, 1, 1),    # small planes: a run of planes per workgroup
     (1, 100, 7, 7, 3, 3, 1, 1),

@@ -59,14 +59,14 @@ SECOND_ROOF = {"depthwise_7x7": (VALU_F32_TFLOPS, "frac_alu_f32_plain_fma"),
 # profiles/hbm_traffic_all_kernels.txt), with the kernel source and its sha256 prefix at the time the
 # counters were taken.  A kernel whose source has changed since reports traffic = null.
 TRAFFIC = {
-    "conv2d_64x64_3x3": (62438038, "sw_mfma_f32.hip", "5d43ed48fdbb08a2"),
-    "depthwise_3x3": (207300847, "sw_sliding_plane.hip", "bbd3c61f82b1358d"),
-    "depthwise_7x7": (206193231, "sw_sliding_plane.hip", "bbd3c61f82b1358d"),
-    "conv2d_s8_128x128_3x3": (21150242, "sw_mfma_s8.hip", "e4d62c0d4706586a"),
-    "conv1d_k9": (33992686, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
-    "avgpool1d_w8": (34272782, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
-    "maxpool1d_w8": (34263950, "sw_sliding1d.hip", "2aacac4aebfc11b3"),
-    "conv2d_1ch_3x3": (637797, "sw_sliding_rows.hip", "1183d74112b4cf49"),
+    "conv2d_64x64_3x3": (62424836, "sw_mfma_f32.hip", "79cf8dd0d7c7fbdc"),
+    "depthwise_3x3": (207296878, "sw_sliding_plane.hip", "bbd3c61f82b1358d"),
+    "depthwise_7x7": (206216454, "sw_sliding_plane.hip", "bbd3c61f82b1358d"),
+    "conv2d_s8_128x128_3x3": (21145857, "sw_mfma_s8.hip", "e4d62c0d4706586a"),
+    "conv1d_k9": (33891531, "sw_sliding1d.hip", "eeb6f644a27cb890"),
+    "avgpool1d_w8": (34168735, "sw_sliding1d.hip", "eeb6f644a27cb890"),
+    "maxpool1d_w8": (34141220, "sw_sliding1d.hip", "eeb6f644a27cb890"),
+    "conv2d_1ch_3x3": (655814, "sw_sliding_rows.hip", "8a6fcf2dac8abc29"),
 }
 
 
@@ -309,8 +309,8 @@ def cpu_baseline(host, total_ops):
     import oracle
 
     oracle.build()
-    times = []
-    for _ in range(3):
+
+    def one_step():
         t0 = time.perf_counter()
         oracle.conv2d(host["x1"], host["w1"], 1, 0)
         oracle.conv1d(host["x2"], host["w2"], 1, 0)
@@ -320,13 +320,19 @@ def cpu_baseline(host, total_ops):
         oracle.conv2d_depthwise(host["x4"], host["w4a"], 1, 1)
         oracle.conv2d_depthwise(host["x4"], host["w4b"], 1, 3)
         oracle.conv2d_s8(host["x5"], host["w5"], 1, 1)
-        times.append(time.perf_counter() - t0)
-    dt = min(times)
+        return time.perf_counter() - t0
+
     cores = oracle.max_threads()
+    times = [one_step() for _ in range(3)]
+    dt = min(times)
+    oracle.set_threads(1)                 # the same step once more on a single thread
+    dt1 = one_step()
+    oracle.set_threads(cores)
     return {"value": round(total_ops / dt / 1e9, 2), "unit": "GFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": "one full step (all eight launches at full size) run 3 times, best %.2f s wall on %d OpenMP "
-                      "threads (about %.0f s of CPU work in all); naive fp64/int64 loops, not a tuned CPU library"
-                      % (dt, cores, sum(times) * cores)}
+            "single_thread_value": round(total_ops / dt1 / 1e9, 2),
+            "sample": "one full step (all eight launches at full size) run 3 times on %d OpenMP threads, best %.2f s "
+                      "wall, and once on one thread, %.2f s (about %.0f s of CPU work in all); naive fp64/int64 loops, "
+                      "not a tuned CPU library" % (cores, dt, dt1, sum(times) * cores + dt1)}
 
 
 def main():

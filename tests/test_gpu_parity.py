@@ -281,6 +281,28 @@ def test_pool2d_misaligned_views(torch, sw, oracle):
                 assert_f32_parity(y, y_ref, d, "avg pool2d, misaligned")
 
 
+@pytest.mark.parametrize("layer", [("max", 3, 2, 1), ("avg", 2, 2, 0), ("max", 2, 2, 0), ("dw", 3, 2, 1), ("dw", 5, 2, 2)],
+                         ids=lambda l: "%s%dx%ds%d" % (l[0], l[1], l[1], l[2]))
+def test_strided_layers_full_size(torch, sw, oracle, layer):
+    """The stride-2 layers of the benchmark's layer table at their full size (8 x 64 x 112 x 112 planes here:
+    the same launch configuration, a quarter of the batch), every output against the oracle."""
+    kind, R, stride, pad = layer
+    x = inputs.normal_f32((8, 64, 112, 112), 2201)
+    if kind == "dw":
+        w = inputs.normal_f32((64, 1, R, R), 2202, 1.0 / R)
+        y_ref, d = oracle.conv2d_depthwise(x, w, stride, pad)
+        y = sw.sw_conv2d_depthwise(dev(torch, x), dev(torch, w), stride, pad).cpu().numpy()
+        assert_f32_parity(y, y_ref, d, f"depthwise {layer}")
+    else:
+        mode = 1 if kind == "max" else 0
+        y_ref, d = oracle.pool2d(x, R, R, stride, pad, mode)
+        y = sw.sw_pool2d(dev(torch, x), R, R, stride, pad, mode).cpu().numpy()
+        if mode == 1:
+            assert np.array_equal(y.astype(np.float64), y_ref)
+        else:
+            assert_f32_parity(y, y_ref, d, f"avg pool2d {layer}")
+
+
 def test_workload1_full_size(torch, sw, oracle):
     x, w = inputs.workload1()
     y_ref, d = oracle.conv2d(x, w, 1, 0)

@@ -224,9 +224,11 @@ int sw_conv2d(const float* x, const float* w, float* y, int N, int C_in, int C_o
         // The fixed 3x3 / 5x5 kernel holds a CU with one large tile: it needs enough of them to fill the chip
         // (28 x 28 images and below at batch 32 leave it at 128 or fewer); the any-shape kernel's 128-pixel
         // tiles take over there, and everywhere the fixed kernel has no variant.
-        const bool any_ok = mfma_f32_any_supported(s);
+        const bool quad_ok = mfma_f32_quad_supported(s);
+        const bool any_ok = quad_ok || mfma_f32_any_supported(s);
         if (mfma_f32_supported(s) && !no_large_tile_mfma() && (mfma_f32_workgroups(s) >= 160 || !any_ok))
             return launch_status(launch_mfma_f32(x, w, y, s, st));
+        if (quad_ok) return launch_status(launch_mfma_f32_quad(x, w, y, s, st));
         if (any_ok) return launch_status(launch_mfma_f32_any(x, w, y, s, st));
     }
     return launch_status(launch_direct_conv2d_f32(x, w, y, s, false, st));

@@ -85,6 +85,8 @@ hipError_t launch_mfma_f32(const float* x, const float* w, float* y, const Conv2
 int64_t    mfma_f32_workgroups(const Conv2dShape& s);     // of the fixed 3x3 / 5x5 kernel, one per CU at a time; 0: tiles half empty
 bool       mfma_f32_any_supported(const Conv2dShape& s);  // any extent, stride and channel count (C_in >= 2)
 hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
+bool       mfma_f32_quad_supported(const Conv2dShape& s); // the same for few taps (R * S <= 12): 16-byte operand reads
+hipError_t launch_mfma_f32_quad(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
 bool       mfma_s8_supported(const Conv2dShape& s);
 hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st);
 bool       mfma_s8_any_supported(const Conv2dShape& s);   // any extent, stride and channel count

@@ -56,6 +56,8 @@ def _load():
     lib.oracle_pool1d.argtypes = [vp] * 3 + [i64] * 4 + [ctypes.c_int]
     lib.oracle_pool2d.restype = ctypes.c_int
     lib.oracle_pool2d.argtypes = [vp] * 3 + [i64] * 7 + [ctypes.c_int]
+    lib.oracle_requant_s8.restype = ctypes.c_int
+    lib.oracle_requant_s8.argtypes = [vp] * 4 + [i64] * 3 + [ctypes.c_int]
     lib.oracle_conv2d_s8.restype = ctypes.c_int
     lib.oracle_conv2d_s8.argtypes = [vp] * 3 + [i64] * 9
     _lib = lib
@@ -186,3 +188,25 @@ def conv2d_s8(x, w, stride: int = 1, pad: int = 0):
     if rc:
         raise ValueError(f"oracle_conv2d_s8 rejected the arguments (code {rc})")
     return y
+
+
+def conv2d_s8_requant(x, w, bias, scale, stride: int = 1, pad: int = 0, relu: bool = False):
+    """int8 convolution followed by per-channel requantisation to int8:
+    q = clamp(rne(scale[co] * float(acc + bias[co])), 0 if relu else -128, 127); bias int32 [C_out] or None."""
+    acc = conv2d_s8(x, w, stride, pad)
+    N, C_out, Ho, Wo = acc.shape
+    scale = _as(scale, np.float32, 1)
+    if scale.shape[0] != C_out:
+        raise ValueError("one scale per output channel")
+    if bias is not None:
+        bias = _as(bias, np.int32, 1)
+        if bias.shape[0] != C_out:
+            raise ValueError("one bias per output channel")
+    q = np.empty(acc.shape, np.int8)
+    rc = _load().oracle_requant_s8(_p(acc), _p(bias) if bias is not None else None, _p(scale), _p(q),
+                                   N, C_out, Ho * Wo, 1 if relu else 0)
+    if rc == 2:
+        raise OverflowError("sum plus bias does not fit int32")
+    if rc:
+        raise ValueError(f"oracle_requant_s8 rejected the arguments (code {rc})")
+    return q

@@ -18,6 +18,7 @@
  *   max pool   y[row,i]    = max_{j<window} x[row,i*st+j]
  *   avg pool2d y[p,i,j]    = (1/(R*S)) * sum_{r,s} xz[p,i*st+r-pad,j*st+s-pad]
  *   max pool2d y[p,i,j]    = max over the (r,s) whose position lies inside the plane
+ *   requantise q[n,co,p]   = clamp(rne(scale[co] * float(acc[n,co,p] + bias[co])), lo, 127),  lo = relu ? 0 : -128
  *
  * xz is x inside the tensor and 0 outside (zero padding); no filter flip
  * (cross-correlation, as DNN frameworks define "convolution"); output extent
@@ -273,6 +274,38 @@ int oracle_conv2d_s8(const int8_t *x, const int8_t *w, int32_t *y,
                     if (acc > INT32_MAX || acc < INT32_MIN) overflow |= 1;
                     y[((n * C_out + co) * Ho + i) * Wo + j] = (int32_t)acc;
                 }
+            }
+        }
+    }
+    return overflow ? 2 : 0;
+}
+
+/* Requantisation of exact int32 sums to int8 (section 1.1 of the paper: quantised inference keeps activations
+ * in 8 bits; the paper gives no formula, this is the common per-channel one).  The sum plus the channel's bias is
+ * taken exactly (int64; 2 is returned if it leaves int32), converted to fp32 (round to nearest even), multiplied
+ * by the channel's fp32 scale in fp32, rounded to the nearest integer (ties to even) and clamped to
+ * [relu ? 0 : -128, 127].  The precision of every step is part of the definition: the same steps in the same
+ * precision give the same bits on any IEEE machine.  bias may be NULL (zeros). */
+int oracle_requant_s8(const int32_t *acc, const int32_t *bias, const float *scale, int8_t *q,
+                      int64_t N, int64_t C_out, int64_t pixels, int relu)
+{
+    if (N <= 0 || C_out <= 0 || pixels <= 0) return 1;
+    int overflow = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(| : overflow)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t co = 0; co < C_out; ++co) {
+            const int64_t b = bias ? (int64_t)bias[co] : 0;
+            const float sc = scale[co];
+            for (int64_t p = 0; p < pixels; ++p) {
+                const int64_t t = (int64_t)acc[(n * C_out + co) * pixels + p] + b;
+                if (t > INT32_MAX || t < INT32_MIN) overflow |= 1;
+                const float v = (float)(int32_t)t;
+                const float prod = v * sc;
+                float r = nearbyintf(prod);
+                const float lo = relu ? 0.0f : -128.0f;
+                if (r < lo) r = lo;
+                if (r > 127.0f) r = 127.0f;
+                q[(n * C_out + co) * pixels + p] = (int8_t)r;
             }
         }
     }

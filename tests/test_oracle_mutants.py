@@ -9,6 +9,7 @@ import pytest
 
 import test_oracle_pins as pins
 import test_oracle_pool2d_pins as pool_pins
+import test_oracle_requant_pins as rq_pins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "sw_oracle.c")
@@ -36,6 +37,13 @@ MUTANTS = [
     ("pool2d window transposed", "for (int64_t s = 0; s < S; ++s) {\n                        const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", "for (int64_t s = 0; s < R; ++s) {\n                        const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", 0),
     ("pool2d stride ignored on columns", "const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", "const int64_t v = j + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", 0),
     ("pool2d padding sign", "const int64_t h = i * stride + r - pad;\n                    if (h < 0 || h >= H) continue;\n                    for (int64_t s = 0; s < S; ++s) {\n                        const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", "const int64_t h = i * stride + r + pad;\n                    if (h < 0 || h >= H) continue;\n                    for (int64_t s = 0; s < S; ++s) {\n                        const int64_t v = j * stride + s - pad;\n                        if (v < 0 || v >= W) continue;\n                        const double e", 0),
+    ("requantisation rounds ties away from zero", "float r = nearbyintf(prod);", "float r = roundf(prod);", 0),
+    ("requantisation truncates", "float r = nearbyintf(prod);", "float r = truncf(prod);", 0),
+    ("requantisation multiplies in double", "const float prod = v * sc;\n                float r = nearbyintf(prod);", "const double prod = (double)t * (double)sc;\n                float r = (float)nearbyint(prod);", 0),
+    ("requantisation ignores the bias", "const int64_t b = bias ? (int64_t)bias[co] : 0;", "const int64_t b = 0; (void)bias;", 0),
+    ("requantisation: rectifier clamps at -128", "const float lo = relu ? 0.0f : -128.0f;", "const float lo = -128.0f; (void)relu;", 0),
+    ("requantisation: scale of the neighbouring channel", "const float sc = scale[co];", "const float sc = scale[(co + 1) % C_out];", 0),
+    ("requantisation: upper clamp at 128 wraps", "if (r > 127.0f) r = 127.0f;", "if (r > 128.0f) r = 128.0f;", 0),
     ("int8 overflow never reported", "return overflow ? 2 : 0;", "return 0;", 0),
 ]
 
@@ -84,6 +92,10 @@ def _battery(o):
         pool_pins.test_average_matches_scatter_brute_force(o, case)
         pool_pins.test_maximum_matches_slices_of_a_minus_infinity_padded_copy(o, case)
     pool_pins.test_closed_forms(o)
+    rq_pins.test_hand_worked_ties_and_saturation(o)
+    rq_pins.test_two_channels_use_their_own_scale_and_bias(o)
+    rq_pins.test_conversion_to_fp32_comes_before_the_product(o)
+    rq_pins.test_identity_monotonicity_and_overflow(o)
     pool_pins.test_special_cases_reduce_to_the_other_entry_points(o)
 
 

@@ -144,6 +144,19 @@ int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y,
                  int N, int C_in, int C_out, int H, int W, int R, int S,
                  int stride, int pad, void* hip_stream);
 
+/*
+ * The same convolution with the requantisation of a quantised pipeline fused into the store (paper, section
+ * 1.1: quantised inference keeps activations in 8 bits): the int32 sums never reach memory, the output is int8.
+ *     q[n,co,i,j] = clamp(rne(scale[co] * float(acc[n,co,i,j] + bias[co])), relu ? 0 : -128, 127)
+ * acc is the exact sum of sw_conv2d_s8; acc + bias must fit int32 (caller's guarantee); the conversion to
+ * fp32, the product and the rounding (to nearest, ties to even) are fp32 operations, so the result is the
+ * same bits on every IEEE machine.  bias: [C_out] int32 or NULL (zeros); scale: [C_out] fp32, finite;
+ * y: [N,C_out,H_out,W_out] int8.  Errors as sw_conv2d_s8; scale == NULL is SW_ERR_NULL.
+ */
+int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, const float* scale, int8_t* y,
+                         int N, int C_in, int C_out, int H, int W, int R, int S,
+                         int stride, int pad, int relu, void* hip_stream);
+
 /* Output extent of one axis; <= 0 means the filter does not fit (or bad arguments). */
 int64_t sw_out_dim(int64_t in, int k, int stride, int pad);
 

@@ -17,6 +17,7 @@ SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN, SW_ERR_ALIAS, SW_ER
 SW_POOL_AVG, SW_POOL_MAX = 0, 1
 
 EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
+           "sw_conv2d_s8_requant",
            "sw_out_dim", "sw_workspace_bytes", "sw_status_string", "sw_version")
 
 _lib = None
@@ -49,6 +50,8 @@ def lib() -> ctypes.CDLL:
     L.sw_conv2d_depthwise.argtypes = [vp, vp, vp] + [i32] * 8 + [vp]
     L.sw_conv2d_s8.restype = i32
     L.sw_conv2d_s8.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
+    L.sw_conv2d_s8_requant.restype = i32
+    L.sw_conv2d_s8_requant.argtypes = [vp, vp, vp, vp, vp] + [i32] * 10 + [vp]
     L.sw_out_dim.restype = i64
     L.sw_out_dim.argtypes = [i64, i32, i32, i32]
     L.sw_workspace_bytes.restype = ctypes.c_size_t
@@ -63,6 +66,26 @@ def lib() -> ctypes.CDLL:
 
 def status_string(status: int) -> str:
     return lib().sw_status_string(int(status)).decode()
+
+
+def sw_conv2d_s8_requant(x, w, bias, scale, stride: int = 1, pad: int = 0, relu: bool = False, out=None, stream=None):
+    """x [N,C_in,H,W] int8, w [C_out,C_in,R,S] int8, bias [C_out] int32 or None, scale [C_out] fp32 ->
+    y [N,C_out,H_out,W_out] int8 = clamp(rne(scale * float(acc + bias)), 0 if relu else -128, 127)."""
+    import torch
+
+    N, C_in, H, W = x.shape
+    C_out, C_in_w, R, S = w.shape
+    if C_in_w != C_in:
+        raise ValueError("channel mismatch between x and w")
+    if out is None:
+        out = torch.empty(_out_shape("sw_conv2d_s8_requant", N, C_out, sw_out_dim(H, R, stride, pad),
+                                     sw_out_dim(W, S, stride, pad)), dtype=torch.int8, device=x.device)
+    b = _dev(bias, torch.int32, 1, "bias") if bias is not None else None
+    rc = lib().sw_conv2d_s8_requant(_dev(x, torch.int8, 4, "x"), _dev(w, torch.int8, 4, "w"), b,
+                                    _dev(scale, torch.float32, 1, "scale"), _dev(out, torch.int8, 4, "y"),
+                                    N, C_in, C_out, H, W, R, S, stride, pad, 1 if relu else 0, _stream(stream))
+    _check(rc, "sw_conv2d_s8_requant")
+    return out
 
 
 def sw_out_dim(n_in: int, k: int, stride: int, pad: int) -> int:

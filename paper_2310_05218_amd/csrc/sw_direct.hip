@@ -49,10 +49,13 @@ __global__ __launch_bounds__(kThreads) void direct_1d_kernel(const float* __rest
     }
 }
 
-template <typename TI, typename TA, bool DW>
+// RQ: the int32 sum is requantised to int8 on its way out (y8), see requant_s8.
+template <typename TI, typename TA, bool DW, bool RQ = false>
 __global__ __launch_bounds__(kThreads) void direct_conv2d_kernel(const TI* __restrict__ x,
                                                                  const TI* __restrict__ w,
-                                                                 TA* __restrict__ y, Conv2dShape s)
+                                                                 TA* __restrict__ y, Conv2dShape s,
+                                                                 int8_t* __restrict__ y8 = nullptr,
+                                                                 Requant rq = Requant{nullptr, nullptr, 0})
 {
     const int64_t plane_o = (int64_t)s.Ho * s.Wo;
     const int64_t total = (int64_t)s.N * s.C_out * plane_o;
@@ -80,7 +83,8 @@ __global__ __launch_bounds__(kThreads) void direct_conv2d_kernel(const TI* __res
                 }
             }
         }
-        y[o] = acc;
+        if constexpr (RQ) y8[o] = requant_s8((int)acc, co, rq);
+        else y[o] = acc;
     }
 }
 
@@ -192,6 +196,15 @@ hipError_t launch_direct_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y,
     const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
     hipLaunchKernelGGL((direct_conv2d_kernel<int8_t, int32_t, false>), dim3(grid), dim3(kThreads), 0, st, x,
                        w, y, s);
+    return hipGetLastError();
+}
+
+hipError_t launch_direct_conv2d_s8_requant(const int8_t* x, const int8_t* w, int8_t* y8, const Requant& rq,
+                                           const Conv2dShape& s, hipStream_t st)
+{
+    const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
+    hipLaunchKernelGGL((direct_conv2d_kernel<int8_t, int32_t, false, true>), dim3(grid), dim3(kThreads), 0, st, x,
+                       w, static_cast<int32_t*>(nullptr), s, y8, rq);
     return hipGetLastError();
 }
 

@@ -99,11 +99,15 @@ struct S8Params {
 
 // RES == 0: input channels in chunks of 64 through LDS.  RES == 128: C_in == 128, all of K resident in LDS.
 // XI: input staging items per thread and chunk (1 when 4 * rows * column quads <= 256).
-template <int RES, int XI>
+// RQ (resident variant only): the sums leave requantised to int8 (y8) instead of as int32 (y).
+template <int RES, int XI, bool RQ = false>
 __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restrict__ x,
                                                          const int8_t* __restrict__ w,
-                                                         int32_t* __restrict__ y, const S8Params P)
+                                                         int32_t* __restrict__ y, const S8Params P,
+                                                         int8_t* __restrict__ y8 = nullptr,
+                                                         const Requant rq = Requant{nullptr, nullptr, 0})
 {
+    static_assert(!RQ || RES != 0, "requantised stores exist in the resident variant only");
     constexpr int kPitch = RES ? RES + 16 : kPitchChunk;            // bytes per pixel / weight row
     constexpr int kXBytes = RES ? kLdsPxRes * kPitch : kXBytesChunk;
     constexpr int kWBytes = 9 * 64 * kPitch;
@@ -280,21 +284,26 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
 #pragma unroll
         for (int st = 0; st < NSTEP; ++st)
             a[st] = *reinterpret_cast<const intx4*>(lw + aoff + (st / KS) * 64 * kPitch + 32 * (st % KS));
-        int32_t* yres = y + ((int64_t)n * C_out + (mb << 6) + 32 * wm + 4 * lg) * HoWo;
+        const int co_base = (mb << 6) + 32 * wm + 4 * lg;       // this lane's first output channel
+        const int64_t ybase = ((int64_t)n * C_out + co_base) * HoWo;
         auto b_at = [&](int i, int st) {
             const int tap = st / KS, kk = st % KS;
             const int r = tap / 3, q = tap - 3 * r;
             return *reinterpret_cast<const intx4*>(lx + boff[i] + (r * IW + q) * kPitch + 32 * kk);
         };
-        // destination of this lane's pixel in block i (nullptr when the pixel lies outside the tile/image)
-        auto block_dst = [&](int i) -> int32_t* {
+        // offset of this lane's pixel in block i inside a channel plane (-1 when it lies outside the tile/image)
+        auto block_dst = [&](int i) -> int {
             const int p = (wn * kNBW + i) * 32 + lj;
             const int pi = fast_div(p, P.by_TW), pj = p - pi * TW;
             const int oi = row0 + pi, oj = col0 + pj;
-            return (p < tile_px && oi < Ho && oj < Wo) ? yres + oi * Wo + oj : nullptr;
+            return (p < tile_px && oi < Ho && oj < Wo) ? oi * Wo + oj : -1;
         };
-        auto store_reg = [&](int32_t* dst, const intx16& c, int v) {
-            if (dst) dst[(8 * (v >> 2) + (v & 3)) * HoWo] = c[v];
+        auto store_reg = [&](int dst, const intx16& c, int v) {
+            const int ch = 8 * (v >> 2) + (v & 3);
+            if (dst >= 0) {
+                if constexpr (RQ) y8[ybase + (int64_t)ch * HoWo + dst] = requant_s8(c[v], co_base + ch, rq);
+                else y[ybase + (int64_t)ch * HoWo + dst] = c[v];
+            }
         };
         // Pair 0 (blocks 0, 1), then pair 1 (blocks 2, 3) with the 32 stores of pair 0 spread between its
         // matrix instructions, then the stores of pair 1.
@@ -315,8 +324,8 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        int32_t* dst0 = live >= 1 ? block_dst(0) : nullptr;
-        int32_t* dst1 = live >= 2 ? block_dst(1) : nullptr;
+        const int dst0 = live >= 1 ? block_dst(0) : -1;
+        const int dst1 = live >= 2 ? block_dst(1) : -1;
         if (live >= 3) {
             intx4 b0[2], b1[2];
             b0[0] = b_at(2, 0); b1[0] = b_at(3, 0);
@@ -331,8 +340,8 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
                 d1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[st], b1[cur], d1, 0, 0, 0);
                 __builtin_amdgcn_sched_barrier(0);
             }
-            int32_t* dst2 = block_dst(2);
-            int32_t* dst3 = live >= 4 ? block_dst(3) : nullptr;
+            const int dst2 = block_dst(2);
+            const int dst3 = live >= 4 ? block_dst(3) : -1;
 #pragma unroll
             for (int v = 0; v < 16; ++v) store_reg(dst2, d0, v);
 #pragma unroll
@@ -489,6 +498,47 @@ hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Co
         hipLaunchKernelGGL((mfma_s8_kernel<0, 1>), grid, dim3(256), kLdsBytes, st, x, w, y, P);
     else
         hipLaunchKernelGGL((mfma_s8_kernel<0, 2>), grid, dim3(256), kLdsBytes, st, x, w, y, P);
+    return hipGetLastError();
+}
+
+bool mfma_s8_requant_supported(const Conv2dShape& s)
+{
+    if (!mfma_s8_supported(s) || s.C_in != 128) return false;
+    const Tiling t = pick_tiling(s);
+    return (t.TH + 2) * (t.TW + 2) <= kLdsPxRes;
+}
+
+hipError_t launch_mfma_s8_requant(const int8_t* x, const int8_t* w, int8_t* y8, const Requant& rq, const Conv2dShape& s,
+                                  hipStream_t st)
+{
+    if (reinterpret_cast<uintptr_t>(x) % 4 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0)
+        return launch_mfma_s8_any_requant(x, w, y8, rq, s, st);
+    static const hipError_t attr = [] {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<128, 1, true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesRes);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_kernel<128, 2, true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytesRes);
+        return e;
+    }();
+    if (attr != hipSuccess) return attr;
+    const Tiling t = pick_tiling(s);
+    S8Params P;
+    P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
+    P.TH = t.TH; P.TW = t.TW;
+    P.nq_max = std::min((t.TW + 2 + 2) / 4 + 1, s.W / 4);
+    P.wide_store = 0;
+    P.by_tiles_x = make_fastdiv(t.tiles_x);
+    P.by_TW = make_fastdiv(t.TW);
+    P.by_IH = make_fastdiv(t.TH + 2);
+    P.by_nq_max = make_fastdiv(P.nq_max);
+    P.by_pieces = make_fastdiv(1);
+    dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)s.N, (unsigned)(s.C_out / 64));
+    int32_t* none = nullptr;
+    if (4 * (t.TH + 2) * P.nq_max <= 256)
+        hipLaunchKernelGGL((mfma_s8_kernel<128, 1, true>), grid, dim3(256), kLdsBytesRes, st, x, w, none, P, y8, rq);
+    else
+        hipLaunchKernelGGL((mfma_s8_kernel<128, 2, true>), grid, dim3(256), kLdsBytesRes, st, x, w, none, P, y8, rq);
     return hipGetLastError();
 }
 

@@ -32,9 +32,11 @@ struct S8AnyParams {
     FastDiv by_tiles_x, by_TW, by_IW, by_win, by_RS, by_span, by_span4;
 };
 
-template <int CK>
+// RQ: the sums leave requantised to int8 (y8) instead of as int32 (y).
+template <int CK, bool RQ>
 __global__ __launch_bounds__(256) void mfma_s8_any_kernel(const int8_t* __restrict__ x, const int8_t* __restrict__ w,
-                                                          int32_t* __restrict__ y, const S8AnyParams P)
+                                                          int32_t* __restrict__ y, const S8AnyParams P,
+                                                          int8_t* __restrict__ y8, const Requant rq)
 {
     constexpr int kPitch = CK + 16;             // bytes per pixel row / filter row in LDS (16-byte aligned reads)
     constexpr int G = CK / 4;                   // dwords (groups of four channels) per row
@@ -147,12 +149,17 @@ __global__ __launch_bounds__(256) void mfma_s8_any_kernel(const int8_t* __restri
     // ---- store: register v of a lane is output channel 8*(v/4) + 4*kg + v%4 of the block, pixel lj
     if (!p_ok) return;
     const int HoWo = P.Ho * P.Wo;
-    int32_t* yp = y + ((int64_t)n * P.C_out + co0) * HoWo + (row0 + pi) * P.Wo + col0 + pj;
+    const int64_t o = ((int64_t)n * P.C_out + co0) * HoWo + (row0 + pi) * P.Wo + col0 + pj;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int co = 8 * (v >> 2) + 4 * kg + (v & 3);
-        if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = acc0[v];
-        if (co0 + 32 + co < P.C_out) yp[(int64_t)(32 + co) * HoWo] = acc1[v];
+        if constexpr (RQ) {
+            if (co0 + co < P.C_out) y8[o + (int64_t)co * HoWo] = requant_s8(acc0[v], co0 + co, rq);
+            if (co0 + 32 + co < P.C_out) y8[o + (int64_t)(32 + co) * HoWo] = requant_s8(acc1[v], co0 + 32 + co, rq);
+        } else {
+            if (co0 + co < P.C_out) y[o + (int64_t)co * HoWo] = acc0[v];
+            if (co0 + 32 + co < P.C_out) y[o + (int64_t)(32 + co) * HoWo] = acc1[v];
+        }
     }
 }
 
@@ -195,11 +202,11 @@ S8AnyPlan plan_s8_any(const Conv2dShape& s)
     return a;
 }
 
-template <int CK>
+template <int CK, bool RQ>
 hipError_t launch_s8_any(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, const S8AnyPlan& a,
-                         hipStream_t st)
+                         hipStream_t st, int8_t* y8, const Requant& rq)
 {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_any_kernel<CK>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_any_kernel<CK, RQ>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
     if (attr != hipSuccess) return attr;
     S8AnyParams P;
@@ -217,7 +224,7 @@ hipError_t launch_s8_any(const int8_t* x, const int8_t* w, int32_t* y, const Con
     P.by_span = make_fastdiv(span);
     P.by_span4 = make_fastdiv(P.w_dwords ? span / 4 : 1);
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
-    hipLaunchKernelGGL((mfma_s8_any_kernel<CK>), grid, dim3(256), a.lds, st, x, w, y, P);
+    hipLaunchKernelGGL((mfma_s8_any_kernel<CK, RQ>), grid, dim3(256), a.lds, st, x, w, y, P, y8, rq);
     return hipGetLastError();
 }
 
@@ -229,8 +236,18 @@ hipError_t launch_mfma_s8_any(const int8_t* x, const int8_t* w, int32_t* y, cons
 {
     const S8AnyPlan a = plan_s8_any(s);
     if (!a.ok) return hipErrorInvalidValue;
-    if (a.CK == 64) return launch_s8_any<64>(x, w, y, s, a, st);
-    return launch_s8_any<32>(x, w, y, s, a, st);
+    const Requant none{nullptr, nullptr, 0};
+    if (a.CK == 64) return launch_s8_any<64, false>(x, w, y, s, a, st, nullptr, none);
+    return launch_s8_any<32, false>(x, w, y, s, a, st, nullptr, none);
+}
+
+hipError_t launch_mfma_s8_any_requant(const int8_t* x, const int8_t* w, int8_t* y8, const Requant& rq,
+                                      const Conv2dShape& s, hipStream_t st)
+{
+    const S8AnyPlan a = plan_s8_any(s);
+    if (!a.ok) return hipErrorInvalidValue;
+    if (a.CK == 64) return launch_s8_any<64, true>(x, w, nullptr, s, a, st, y8, rq);
+    return launch_s8_any<32, true>(x, w, nullptr, s, a, st, y8, rq);
 }
 
 }  // namespace swconv

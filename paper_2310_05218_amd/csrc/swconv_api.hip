@@ -259,4 +259,27 @@ int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, int N, int C_in, 
     return launch_status(launch_direct_conv2d_s8(x, w, y, s, st));
 }
 
+int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, const float* scale, int8_t* y, int N,
+                         int C_in, int C_out, int H, int W, int R, int S, int stride, int pad, int relu,
+                         void* hip_stream)
+{
+    if (!scale) return SW_ERR_NULL;
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, 1, 1, &s);
+    if (rc != SW_OK) return rc;
+    if ((int64_t)C_in * R * S > 131071) return SW_ERR_SHAPE;  // 131072 * 2^14 = 2^31 leaves int32
+    if (misaligned(scale, 4) || (bias && misaligned(bias, 4))) return SW_ERR_ALIGN;
+    const int64_t ny = (int64_t)N * C_out * s.Ho * s.Wo;
+    if (overlaps(y, ny, scale, (int64_t)C_out * 4) || (bias && overlaps(y, ny, bias, (int64_t)C_out * 4)))
+        return SW_ERR_ALIAS;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const Requant rq{bias, scale, relu != 0};
+    if (!force_direct()) {
+        if (mfma_s8_requant_supported(s) && !no_large_tile_mfma())
+            return launch_status(launch_mfma_s8_requant(x, w, y, rq, s, st));
+        if (mfma_s8_any_supported(s)) return launch_status(launch_mfma_s8_any_requant(x, w, y, rq, s, st));
+    }
+    return launch_status(launch_direct_conv2d_s8_requant(x, w, y, rq, s, st));
+}
+
 }  // extern "C"

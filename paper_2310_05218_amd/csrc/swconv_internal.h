@@ -24,6 +24,24 @@ struct Conv2dShape {
     int N, C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
 };
 
+// Requantisation of an exact int32 sum to int8, per output channel:
+//     q = clamp(rne(scale[co] * float(acc + bias[co])), relu ? 0 : -128, 127)
+// with the conversion, the product and the rounding in fp32 (v_cvt_f32_i32, v_mul_f32, v_rndne_f32: the
+// same IEEE operations as the definition).  bias may be null.
+struct Requant {
+    const int32_t* bias;
+    const float* scale;
+    int relu;
+};
+__device__ __forceinline__ int8_t requant_s8(int acc, int co, const Requant& rq)
+{
+    const int t = acc + (rq.bias ? rq.bias[co] : 0);
+    float r = rintf(__int2float_rn(t) * rq.scale[co]);
+    r = fmaxf(r, rq.relu ? 0.0f : -128.0f);
+    r = fminf(r, 127.0f);
+    return (int8_t)(int)r;
+}
+
 // ---- direct (one thread per output) kernels: any valid shape -------------------------------
 hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
                             int64_t len_out, int k, int stride, int pad, Op1D op, hipStream_t st);
@@ -89,6 +107,14 @@ bool       mfma_f32_quad_supported(const Conv2dShape& s); // the same for few ta
 hipError_t launch_mfma_f32_quad(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
 bool       mfma_s8_supported(const Conv2dShape& s);
 hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st);
+// the same with the requantisation fused into the store (y8: int8 output)
+bool       mfma_s8_requant_supported(const Conv2dShape& s);
+hipError_t launch_mfma_s8_requant(const int8_t* x, const int8_t* w, int8_t* y8, const Requant& rq, const Conv2dShape& s,
+                                  hipStream_t st);
+hipError_t launch_mfma_s8_any_requant(const int8_t* x, const int8_t* w, int8_t* y8, const Requant& rq,
+                                      const Conv2dShape& s, hipStream_t st);
+hipError_t launch_direct_conv2d_s8_requant(const int8_t* x, const int8_t* w, int8_t* y8, const Requant& rq,
+                                           const Conv2dShape& s, hipStream_t st);
 bool       mfma_s8_any_supported(const Conv2dShape& s);   // any extent, stride and channel count
 hipError_t launch_mfma_s8_any(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st);
 

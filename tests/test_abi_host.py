@@ -123,6 +123,20 @@ def test_conv2d_f32_alignment_and_s8_accumulator_bound(L):
     assert L.sw_conv2d_s8(X + 1, W_ + 3, Y, 1, 16384, 1, 8, 8, 3, 3, 1, 1, None) == B.SW_ERR_SHAPE  # 147456 terms
 
 
+def test_requant_argument_errors(L):
+    f = L.sw_conv2d_s8_requant
+    B_, SC = 0x1900000, 0x1a00000
+    ok = (2, 16, 16, 8, 8, 3, 3, 1, 1)
+    assert f(X, W_, B_, None, Y, *ok, 0, None) == B.SW_ERR_NULL
+    assert f(None, W_, B_, SC, Y, *ok, 0, None) == B.SW_ERR_NULL
+    assert f(X, W_, B_, SC, Y, 2, 16, 16, 8, 8, 0, 3, 1, 1, 0, None) == B.SW_ERR_SHAPE
+    assert f(X, W_, B_, SC, Y, 1, 16384, 1, 8, 8, 3, 3, 1, 1, 0, None) == B.SW_ERR_SHAPE   # 147456 terms
+    assert f(X, W_, B_ + 2, SC, Y, *ok, 0, None) == B.SW_ERR_ALIGN
+    assert f(X, W_, B_, SC + 1, Y, *ok, 0, None) == B.SW_ERR_ALIGN
+    assert f(X, W_, B_, SC, X + 5, *ok, 0, None) == B.SW_ERR_ALIAS
+    assert f(X, W_, B_, Y + 8, Y, *ok, 0, None) == B.SW_ERR_ALIAS
+
+
 def test_depthwise_argument_errors(L):
     f = L.sw_conv2d_depthwise
     ok = (2, 16, 8, 8, 3, 3, 1, 1)

@@ -426,6 +426,49 @@ def test_conv2d_s8(torch, sw, oracle, case):
     assert np.array_equal(out.cpu().numpy(), y_ref), f"s8 {case} is not bit-exact"
 
 
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("case", [
+    (2, 128, 128, 28, 28, 3, 3, 1, 1),    # resident-K kernel
+    (1, 128, 64, 20, 28, 3, 3, 1, 1),     # ... ragged last row band
+    (2, 64, 64, 28, 28, 3, 3, 1, 1),      # any-shape kernel (the chunked large-tile variant has no fused store)
+    (1, 40, 70, 12, 15, 3, 3, 2, 1),      # ... odd channel counts, stride 2
+    (1, 100, 33, 9, 9, 1, 1, 1, 0),       # ... pointwise
+    (1, 8, 5, 20, 20, 7, 7, 1, 3),        # 49 taps: one thread per output
+], ids=lambda c: "x".join(map(str, c)))
+def test_conv2d_s8_requant(torch, sw, oracle, case, relu):
+    N, C_in, C_out, H, W, R, S, stride, pad = case
+    x = inputs.uniform_s8((N, C_in, H, W), 4101)
+    w = inputs.uniform_s8((C_out, C_in, R, S), 4102)
+    rng = np.random.default_rng(4103)
+    bias = rng.integers(-20000, 20000, size=C_out).astype(np.int32)
+    # scales that bring the sums into the int8 range, with a few exact powers of two (ties do occur)
+    std = np.sqrt(C_in * R * S) * 5461.0                   # of the sums: uniform int8 operands have variance 5461
+    scale = (rng.uniform(0.5, 2.0, size=C_out) * 40.0 / std).astype(np.float32)
+    scale[::3] = np.float32(2.0 ** np.round(np.log2(40.0 / std)))
+    q_ref = oracle.conv2d_s8_requant(x, w, bias, scale, stride, pad, relu)
+    buf, out, front, n, s = guarded_empty(torch, q_ref.shape, torch.int8, fill=77)
+    sw.sw_conv2d_s8_requant(dev(torch, x), dev(torch, w), dev(torch, bias), dev(torch, scale), stride, pad, relu, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    q = out.cpu().numpy()
+    assert np.array_equal(q, q_ref), f"requant {case}: {np.count_nonzero(q != q_ref)} of {q.size} differ"
+    assert len(np.unique(q_ref)) > (30 if relu else 60)   # the case exercises the range, not just the clamps
+    # no bias
+    q_ref = oracle.conv2d_s8_requant(x, w, None, scale, stride, pad, relu)
+    q = sw.sw_conv2d_s8_requant(dev(torch, x), dev(torch, w), None, dev(torch, scale), stride, pad, relu).cpu().numpy()
+    assert np.array_equal(q, q_ref)
+
+
+def test_workload5_requantised_full_size(torch, sw, oracle):
+    x, w = inputs.workload5()
+    rng = np.random.default_rng(4104)
+    bias = rng.integers(-50000, 50000, size=128).astype(np.int32)
+    scale = rng.uniform(1.0, 3.0, size=128).astype(np.float32) * np.float32(2.0 ** -18)
+    q_ref = oracle.conv2d_s8_requant(x, w, bias, scale, 1, 1, True)
+    q = sw.sw_conv2d_s8_requant(dev(torch, x), dev(torch, w), dev(torch, bias), dev(torch, scale), 1, 1, True).cpu().numpy()
+    assert np.array_equal(q, q_ref)
+
+
 def test_s8_extreme_values(torch, sw):
     x = np.full((1, 128, 28, 28), -128, np.int8)
     w = np.full((128, 128, 3, 3), -128, np.int8)

@@ -206,25 +206,36 @@ def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, st
     """One multi-channel layer of the table below (fp32 or int8), checked on one image against the oracle."""
     N, C, H, W = shape
     Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
-    s8 = kind == "conv_s8"
+    s8 = kind in ("conv_s8", "conv_s8_rq")
+    rq = kind == "conv_s8_rq"
     if s8:
         x = inputs.uniform_s8(shape, inputs.seed_for(7, idx))
         w = inputs.uniform_s8((C_out, C, R, R), inputs.seed_for(7, 100 + idx))
         call, odt, esz = sw.sw_conv2d_s8, torch.int32, 1
+        if rq:      # workload 5 with the requantisation fused into the store: int8 out instead of int32
+            rng = np.random.default_rng(inputs.seed_for(7, 200 + idx))
+            bias = rng.integers(-50000, 50000, size=C_out).astype(np.int32)
+            scale = (rng.uniform(1.0, 3.0, size=C_out) * 2.0 ** -18).astype(np.float32)
+            bd, sd = torch.from_numpy(bias).cuda(), torch.from_numpy(scale).cuda()
+            call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_s8_requant(a, b, bd, sd, st_, p_, True, out=out)
+            odt = torch.int8
     else:
         x = inputs.normal_f32(shape, inputs.seed_for(7, idx))
         w = inputs.normal_f32((C_out, C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
         call, odt, esz = sw.sw_conv2d, torch.float32, 4
     xs, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
     y = call(xs[:1].contiguous(), wd, stride, pad).cpu().numpy()
-    if s8:
+    if rq:
+        assert np.array_equal(y, oracle.conv2d_s8_requant(x[:1], w, bias, scale, stride, pad, True)), name
+        err = 0.0
+    elif s8:
         assert np.array_equal(y, oracle.conv2d_s8(x[:1], w, stride, pad)), name
         err = 0.0
     else:
         y_ref, d = oracle.conv2d(x[:1], w, stride, pad)
         err = float(np.max(np.abs(y - y_ref) / d))
         assert err <= 2e-5, (name, err)
-    nbytes = x.nbytes + w.nbytes + N * C_out * Ho * Wo * 4
+    nbytes = x.nbytes + w.nbytes + N * C_out * Ho * Wo * (1 if rq else 4)
     nsets = min(16, max(3, -(-COLD_ROTATION_BYTES // nbytes)))
     sets = [{"x": xs if i == 0 else xs.clone(), "y": torch.empty((N, C_out, Ho, Wo), dtype=odt, device="cuda")}
             for i in range(nsets)]
@@ -262,11 +273,12 @@ def strided_and_pooling_table(torch, sw):
         ("conv_3x3_14x14_256", "conv", (32, 256, 14, 14), 3, 1, 1, 256),
         ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
         ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
+        ("conv_s8_requant_3x3_128to128", "conv_s8_rq", (32, 128, 28, 28), 3, 1, 1, 128),
     ]
     rows = []
     for idx, (name, kind, shape, R, stride, pad, *more) in enumerate(layers):
         N, C, H, W = shape
-        if kind in ("conv", "conv_s8"):
+        if kind in ("conv", "conv_s8", "conv_s8_rq"):
             rows.append(_conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, stride, pad, more[0]))
             continue
         Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1

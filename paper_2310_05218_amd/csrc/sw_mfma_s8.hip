@@ -298,11 +298,59 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
             const int oi = row0 + pi, oj = col0 + pj;
             return (p < tile_px && oi < Ho && oj < Wo) ? oi * Wo + oj : -1;
         };
-        auto store_reg = [&](int dst, const intx16& c, int v) {
+        // this lane's sixteen output channels' scales and biases, read once
+        float rq_scale[RQ ? 16 : 1];
+        int rq_bias[RQ ? 16 : 1];
+        if constexpr (RQ) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int co = co_base + 8 * (v >> 2) + (v & 3);
+                rq_scale[v] = rq.scale[co];
+                rq_bias[v] = rq.bias ? rq.bias[co] : 0;
+            }
+        }
+        auto requant_reg = [&](int acc_v, int v) __attribute__((always_inline)) {
+            float r = rintf(__int2float_rn(acc_v + rq_bias[RQ ? v : 0]) * rq_scale[RQ ? v : 0]);
+            r = fminf(fmaxf(r, rq.relu ? 0.0f : -128.0f), 127.0f);
+            return (int)r;
+        };
+        // Requantised output, rows whose groups of four pixels are aligned dwords in y8 (P.wide_store): the four
+        // lanes of a quad hold four pixels x four consecutive channels; two exchange rounds inside the quad
+        // (DPP quad_perm) transpose that, so that lane k ends up with channel k of all four pixels and stores
+        // them as one dword instead of four single bytes.
+        auto store_quad = [&](int dst, const intx16& c, int g) __attribute__((always_inline)) {
+            const int k = lane & 3;
+            int r[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) r[t] = requant_reg(c[4 * g + t], 4 * g + t) & 255;
+            // round 1, partner lane ^ 1: keep the channels whose bit 0 is this lane's bit 0
+            const bool b0 = k & 1, b1 = k & 2;
+            const int keep01 = b0 ? r[1] : r[0], send01 = b0 ? r[0] : r[1];
+            const int keep23 = b0 ? r[3] : r[2], send23 = b0 ? r[2] : r[3];
+            const int got01 = __builtin_amdgcn_mov_dpp(send01, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+            const int got23 = __builtin_amdgcn_mov_dpp(send23, 0xB1, 0xF, 0xF, true);
+            // now (keep01, got01) = channel b0 of pixels (k, k^1), (keep23, got23) = channel 2 + b0 of the same
+            // round 2, partner lane ^ 2: keep the pair whose channel has this lane's bit 1
+            const int own_a = b1 ? keep23 : keep01, own_b = b1 ? got23 : got01;
+            const int snd_a = b1 ? keep01 : keep23, snd_b = b1 ? got01 : got23;
+            const int far_a = __builtin_amdgcn_mov_dpp(snd_a, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+            const int far_b = __builtin_amdgcn_mov_dpp(snd_b, 0x4E, 0xF, 0xF, true);
+            // channel k of pixels k (own_a), k^1 (own_b), k^2 (far_a), k^3 (far_b); byte j of the dword is pixel j
+            const unsigned word = (unsigned)own_a << (8 * k) | (unsigned)own_b << (8 * (k ^ 1)) |
+                                  (unsigned)far_a << (8 * (k ^ 2)) | (unsigned)far_b << (8 * (k ^ 3));
+            if (dst >= 0)
+                *reinterpret_cast<unsigned*>(y8 + ybase + (int64_t)(8 * g + k) * HoWo + (dst - k)) = word;
+        };
+        auto store_reg = [&](int dst, const intx16& c, int v) __attribute__((always_inline)) {
             const int ch = 8 * (v >> 2) + (v & 3);
-            if (dst >= 0) {
-                if constexpr (RQ) y8[ybase + (int64_t)ch * HoWo + dst] = requant_s8(c[v], co_base + ch, rq);
-                else y[ybase + (int64_t)ch * HoWo + dst] = c[v];
+            if constexpr (RQ) {
+                if (P.wide_store) {
+                    if ((v & 3) == 3) store_quad(dst, c, v >> 2);
+                } else if (dst >= 0) {
+                    y8[ybase + (int64_t)ch * HoWo + dst] = (int8_t)requant_reg(c[v], v);
+                }
+            } else {
+                if (dst >= 0) y[ybase + (int64_t)ch * HoWo + dst] = c[v];
             }
         };
         // Pair 0 (blocks 0, 1), then pair 1 (blocks 2, 3) with the 32 stores of pair 0 spread between its
@@ -527,7 +575,8 @@ hipError_t launch_mfma_s8_requant(const int8_t* x, const int8_t* w, int8_t* y8, 
     P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
     P.TH = t.TH; P.TW = t.TW;
     P.nq_max = std::min((t.TW + 2 + 2) / 4 + 1, s.W / 4);
-    P.wide_store = 0;
+    // dword stores of four requantised pixels: groups of four pixels must be aligned dwords of y8
+    P.wide_store = s.Wo % 4 == 0 && t.TW % 4 == 0 && reinterpret_cast<uintptr_t>(y8) % 4 == 0;
     P.by_tiles_x = make_fastdiv(t.tiles_x);
     P.by_TW = make_fastdiv(t.TW);
     P.by_IH = make_fastdiv(t.TH + 2);

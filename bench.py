@@ -105,12 +105,14 @@ def make_sets(torch, nsets):
 
 
 def launches(sw):
-    # The long launches come first: the host enqueues a launch in about 8 us, so it is ahead of the GPU after
-    # them and the short launches that follow never wait for their enqueue.
+    # Order inside a step.  The long launches come first: the host enqueues a launch in about 8 us, so it is ahead
+    # of the GPU after them and the short launches that follow never wait for their enqueue.  The matrix-core fp32
+    # launch follows the 7x7 depthwise one: measured right after a light kernel it takes 70-74 us, right after an
+    # arithmetic-heavy one 66 us (the chip's clock and matrix units are already at their loaded state).
     return [
-        ("conv2d_64x64_3x3", lambda d: sw.sw_conv2d(d["x3"], d["w3"], 1, 1, out=d["y3"])),
         ("depthwise_3x3", lambda d: sw.sw_conv2d_depthwise(d["x4"], d["w4a"], 1, 1, out=d["y4a"])),
         ("depthwise_7x7", lambda d: sw.sw_conv2d_depthwise(d["x4"], d["w4b"], 1, 3, out=d["y4b"])),
+        ("conv2d_64x64_3x3", lambda d: sw.sw_conv2d(d["x3"], d["w3"], 1, 1, out=d["y3"])),
         ("conv2d_s8_128x128_3x3", lambda d: sw.sw_conv2d_s8(d["x5"], d["w5"], 1, 1, out=d["y5"])),
         ("conv1d_k9", lambda d: sw.sw_conv1d(d["x2"], d["w2"], 1, 0, out=d["y2a"])),
         ("avgpool1d_w8", lambda d: sw.sw_pool1d(d["x2"], 8, 1, sw.SW_POOL_AVG, out=d["y2b"])),

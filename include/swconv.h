@@ -47,7 +47,8 @@ typedef enum {
     SW_ERR_UNSUPPORTED = 3, /* a valid problem the library has no kernel for           */
     SW_ERR_ALIGN = 4,       /* pointer not aligned to its element size                 */
     SW_ERR_ALIAS = 5,       /* y overlaps x or w                                       */
-    SW_ERR_LAUNCH = 6       /* the HIP runtime refused the launch (or no device)       */
+    SW_ERR_LAUNCH = 6,      /* the HIP runtime refused the launch (or no device)       */
+    SW_ERR_JIT = 7          /* the run-time compiler refused a generated kernel        */
 } sw_status;
 
 typedef enum { SW_POOL_AVG = 0, SW_POOL_MAX = 1 } sw_pool_mode;
@@ -156,6 +157,40 @@ int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y,
 int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, const float* scale, int8_t* y,
                          int N, int C_in, int C_out, int H, int W, int R, int S,
                          int stride, int pad, int relu, void* hip_stream);
+
+/*
+ * Depthwise 2-D convolution through a kernel generated at run time (paper, section 2:
+ * custom kernels generated at run time for every filter size).  Arguments, layouts,
+ * result and errors as sw_conv2d_depthwise.  For stride 1, an output plane of at
+ * most 56 x 56 (and at least half of that), W and W_out multiples of 4, H*W <= 4096,
+ * 2*pad <= min(R,S)-1, a window of at most 40 KB and x, y 16-byte aligned, the first
+ * call for a geometry (H, W, R, S, pad) compiles a kernel specialised on it (about a
+ * second on the calling thread, host-synchronous; do not make that first call inside
+ * a stream capture -- use sw_jit_prepare_depthwise beforehand), keeps it for the life
+ * of the process and launches it; later calls only launch.  Every other valid shape
+ * runs sw_conv2d_depthwise's precompiled kernels.  SW_ERR_JIT if the compiler
+ * refuses the generated source (its log goes to stderr).  Thread-safe.
+ */
+int sw_conv2d_depthwise_jit(const float* x, const float* w, float* y,
+                            int N, int C, int H, int W, int R, int S,
+                            int stride, int pad, void* hip_stream);
+
+/*
+ * Compiles and loads the generated kernel of a geometry ahead of its first use.
+ * SW_OK; SW_ERR_UNSUPPORTED if sw_conv2d_depthwise_jit would run a precompiled
+ * kernel for it; SW_ERR_SHAPE for invalid extents; SW_ERR_JIT; SW_ERR_LAUNCH
+ * (no device, or the module did not load).
+ */
+int sw_jit_prepare_depthwise(int H, int W, int R, int S, int stride, int pad);
+
+/*
+ * As sw_jit_prepare_depthwise, but only compiles (needs no device, caches
+ * nothing): tells whether the generated source builds for a geometry.
+ */
+int sw_jit_compile_check(int H, int W, int R, int S, int stride, int pad);
+
+/* Number of generated kernels this process holds. */
+int sw_jit_cached_kernels(void);
 
 /* Output extent of one axis; <= 0 means the filter does not fit (or bad arguments). */
 int64_t sw_out_dim(int64_t in, int k, int stride, int pad);

@@ -13,11 +13,12 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libswconv.so")
 
 SW_OK = 0
-SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN, SW_ERR_ALIAS, SW_ERR_LAUNCH = 1, 2, 3, 4, 5, 6
+SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN, SW_ERR_ALIAS, SW_ERR_LAUNCH, SW_ERR_JIT = 1, 2, 3, 4, 5, 6, 7
 SW_POOL_AVG, SW_POOL_MAX = 0, 1
 
 EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
-           "sw_conv2d_s8_requant",
+           "sw_conv2d_s8_requant", "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
+           "sw_jit_cached_kernels",
            "sw_out_dim", "sw_workspace_bytes", "sw_status_string", "sw_version")
 
 _lib = None
@@ -48,6 +49,13 @@ def lib() -> ctypes.CDLL:
     L.sw_conv2d.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.sw_conv2d_depthwise.restype = i32
     L.sw_conv2d_depthwise.argtypes = [vp, vp, vp] + [i32] * 8 + [vp]
+    L.sw_conv2d_depthwise_jit.restype = i32
+    L.sw_conv2d_depthwise_jit.argtypes = [vp, vp, vp] + [i32] * 8 + [vp]
+    for name in ("sw_jit_prepare_depthwise", "sw_jit_compile_check"):
+        getattr(L, name).restype = i32
+        getattr(L, name).argtypes = [i32] * 6
+    L.sw_jit_cached_kernels.restype = i32
+    L.sw_jit_cached_kernels.argtypes = []
     L.sw_conv2d_s8.restype = i32
     L.sw_conv2d_s8.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.sw_conv2d_s8_requant.restype = i32
@@ -203,6 +211,39 @@ def sw_conv2d_depthwise(x, w, stride: int = 1, pad: int = 0, out=None, stream=No
                                    _stream(stream))
     _check(rc, "sw_conv2d_depthwise")
     return out
+
+
+def sw_conv2d_depthwise_jit(x, w, stride: int = 1, pad: int = 0, out=None, stream=None):
+    """As sw_conv2d_depthwise, through the kernel generated at run time for this geometry (compiled on first use)."""
+    import torch
+
+    N, C, H, W = x.shape
+    Cw, one, R, S = w.shape
+    if Cw != C or one != 1:
+        raise ValueError("depthwise weights must be [C,1,R,S]")
+    if out is None:
+        out = torch.empty(_out_shape("sw_conv2d_depthwise_jit", N, C, sw_out_dim(H, R, stride, pad),
+                                     sw_out_dim(W, S, stride, pad)), dtype=torch.float32, device=x.device)
+    rc = lib().sw_conv2d_depthwise_jit(_dev(x, torch.float32, 4, "x"), _dev(w, torch.float32, 4, "w"),
+                                       _dev(out, torch.float32, 4, "y"), N, C, H, W, R, S, stride, pad,
+                                       _stream(stream))
+    _check(rc, "sw_conv2d_depthwise_jit")
+    return out
+
+
+def sw_jit_prepare_depthwise(H: int, W: int, R: int, S: int, stride: int = 1, pad: int = 0) -> int:
+    """Compile and load the generated kernel of a geometry; returns the status (SW_ERR_UNSUPPORTED: the
+    precompiled kernels serve it)."""
+    return int(lib().sw_jit_prepare_depthwise(H, W, R, S, stride, pad))
+
+
+def sw_jit_compile_check(H: int, W: int, R: int, S: int, stride: int = 1, pad: int = 0) -> int:
+    """Compile only (no device needed); returns the status."""
+    return int(lib().sw_jit_compile_check(H, W, R, S, stride, pad))
+
+
+def sw_jit_cached_kernels() -> int:
+    return int(lib().sw_jit_cached_kernels())
 
 
 def sw_conv2d_s8(x, w, stride: int = 1, pad: int = 0, out=None, stream=None):

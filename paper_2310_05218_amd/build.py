@@ -34,6 +34,14 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
     shutil.rmtree(tmp, ignore_errors=True)
     os.makedirs(tmp)
     try:
+        # the source of the run-time-compiled kernel travels inside the library as a string literal
+        with open(os.path.join(CSRC, "jit", "sliding_plane_jit.hip")) as f:
+            text = f.read()
+        assert ')SWJIT"' not in text
+        with open(os.path.join(tmp, "sw_jit_source.inc"), "w") as f:
+            f.write('R"SWJIT(' + text + ')SWJIT"\n')
+        inc += ["-I", tmp]
+
         def compile_one(src):
             obj = os.path.join(tmp, os.path.basename(src) + ".o")
             cmd = [hipcc, *HIPCC_FLAGS, *inc, "-c", src, "-o", obj]
@@ -44,7 +52,7 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
 
         with concurrent.futures.ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
             objs = list(pool.map(compile_one, sources()))
-        cmd = [hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB, *objs]
+        cmd = [hipcc, "--offload-arch=gfx950", "-fPIC", "-shared", "-o", LIB, *objs, "-lhiprtc"]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)

@@ -168,6 +168,7 @@ const char* sw_status_string(int status)
         case SW_ERR_ALIGN: return "pointer not aligned to its element size";
         case SW_ERR_ALIAS: return "output overlaps an input";
         case SW_ERR_LAUNCH: return "HIP launch failed";
+        case SW_ERR_JIT: return "run-time compilation of a generated kernel failed";
         default: return "unknown status";
     }
 }
@@ -243,6 +244,34 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
 }
+
+int sw_conv2d_depthwise_jit(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,
+                            int stride, int pad, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s);
+    if (rc != SW_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (!force_direct() && jit_plane_supported(x, y, H, W, R, S, stride, pad))
+        return jit_launch_plane(x, w, y, (int64_t)N * C, 1, C, H, W, R, S, stride, pad, st);
+    return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
+}
+
+int sw_jit_prepare_depthwise(int H, int W, int R, int S, int stride, int pad)
+{
+    if (H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return SW_ERR_SHAPE;
+    if (sw_out_dim(H, R, stride, pad) <= 0 || sw_out_dim(W, S, stride, pad) <= 0) return SW_ERR_SHAPE;
+    return jit_prepare_plane(H, W, R, S, stride, pad);
+}
+
+int sw_jit_compile_check(int H, int W, int R, int S, int stride, int pad)
+{
+    if (H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return SW_ERR_SHAPE;
+    if (sw_out_dim(H, R, stride, pad) <= 0 || sw_out_dim(W, S, stride, pad) <= 0) return SW_ERR_SHAPE;
+    return jit_compile_only(H, W, R, S, stride, pad);
+}
+
+int sw_jit_cached_kernels(void) { return jit_cached_kernels(); }
 
 int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, int N, int C_in, int C_out, int H, int W,
                  int R, int S, int stride, int pad, void* hip_stream)

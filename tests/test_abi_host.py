@@ -36,7 +36,7 @@ def test_out_dim_and_constants(L):
     assert B.sw_out_dim(7, 3, 2, 1) == 4
     assert B.sw_out_dim(2, 3, 1, 0) <= 0
     assert B.sw_out_dim(0, 3, 1, 0) <= 0 and B.sw_out_dim(5, 3, 0, 0) <= 0 and B.sw_out_dim(5, 3, 1, -1) <= 0
-    for s in range(0, 8):
+    for s in range(0, 9):
         assert len(B.status_string(s)) > 0
 
 
@@ -147,6 +147,45 @@ def test_depthwise_argument_errors(L):
         assert f(X, W_, Y, *bad, None) == B.SW_ERR_SHAPE, i
     assert f(X, W_, Y, 2, 16, 4, 4, 7, 7, 1, 0, None) == B.SW_ERR_SHAPE
     assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
+
+
+def test_jit_entry_point_argument_errors(L):
+    f = L.sw_conv2d_depthwise_jit
+    ok = (2, 16, 56, 56, 9, 9, 1, 4)
+    assert f(None, W_, Y, *ok, None) == B.SW_ERR_NULL
+    for i in range(7):
+        bad = list(ok)
+        bad[i] = 0
+        assert f(X, W_, Y, *bad, None) == B.SW_ERR_SHAPE, i
+    assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
+    assert f(X, W_, Y + 2, *ok, None) == B.SW_ERR_ALIGN
+
+
+# geometries inside the generated kernel's range: H, W, R, S, pad
+JIT_GEOMETRIES = [(56, 56, 1, 1, 0), (56, 56, 3, 3, 1), (56, 56, 9, 9, 4), (56, 56, 11, 11, 5), (56, 56, 17, 17, 8),
+                  (56, 56, 29, 29, 14), (56, 56, 41, 41, 20), (64, 64, 9, 9, 0), (56, 56, 5, 9, 2), (48, 52, 7, 7, 3)]
+
+
+@pytest.mark.parametrize("geometry", JIT_GEOMETRIES)
+def test_generated_source_compiles_for_its_whole_range(L, geometry):
+    """The run-time compiler accepts the generated kernel (its static_asserts included) for each geometry; the
+    compile step needs no device."""
+    H, W, R, S, pad = geometry
+    assert B.sw_jit_compile_check(H, W, R, S, 1, pad) == B.SW_OK
+
+
+def test_jit_range_and_errors(L):
+    assert B.sw_jit_compile_check(56, 56, 9, 9, 2, 4) == B.SW_ERR_UNSUPPORTED      # stride 2
+    assert B.sw_jit_compile_check(28, 28, 9, 9, 1, 4) == B.SW_ERR_UNSUPPORTED      # small plane
+    assert B.sw_jit_compile_check(58, 58, 3, 3, 1, 1) == B.SW_ERR_UNSUPPORTED      # output above 56 x 56
+    assert B.sw_jit_compile_check(56, 56, 12, 12, 1, 4) == B.SW_ERR_UNSUPPORTED    # W_out = 53
+    assert B.sw_jit_compile_check(56, 56, 9, 9, 1, 6) == B.SW_ERR_UNSUPPORTED      # output larger than the plane
+    assert B.sw_jit_compile_check(56, 56, 45, 45, 1, 22) == B.SW_ERR_UNSUPPORTED   # window above 40 KB
+    assert B.sw_jit_compile_check(0, 56, 9, 9, 1, 4) == B.SW_ERR_SHAPE
+    assert B.sw_jit_compile_check(4, 4, 9, 9, 1, 0) == B.SW_ERR_SHAPE              # filter larger than the plane
+    assert B.sw_jit_prepare_depthwise(56, 56, 9, 9, 1, -1) == B.SW_ERR_SHAPE
+    assert B.sw_jit_prepare_depthwise(28, 28, 9, 9, 1, 4) == B.SW_ERR_UNSUPPORTED
+    assert B.sw_jit_cached_kernels() >= 0
 
 
 def test_binding_refuses_host_tensors(L):

@@ -174,8 +174,10 @@ def time_kernel(torch, fn, sets, reps, batches=5):
 def filter_size_sweep(torch, sw):
     """Throughput against filter size on one plane-per-filter workload (N=32, C=64, 56x56, stride 1, 'same'
     padding, fp32 N(0,1), weights N(0, 1/k^2)): sizes 3, 5, 7 run the fixed-size kernels, up to 17 the first
-    generic kernel, beyond that the wide-window generic kernel.  Each size is first checked against the CPU
-    oracle on two planes."""
+    generic kernel, beyond that the wide-window generic kernel.  Sizes up to 33 are also timed through the kernel
+    generated at run time for the geometry (`jit_*` columns; paper, section 2); its compilation happens in the
+    warm-up call, outside the timed launches.  Each size and path is first checked against the CPU oracle on two
+    planes."""
     import numpy as np
 
     import oracle
@@ -197,10 +199,20 @@ def filter_size_sweep(torch, sw):
                          50 if k < 20 else 10)
         flop = 2.0 * k * k * N * C * H * H
         nbytes = 2 * N * C * H * H * 4 + C * k * k * 4
-        rows.append({"filter": k, "us": round(us, 2), "gflops": round(flop / us / 1e3, 1),
-                     "gbs": round(nbytes / us / 1e3, 1), "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4),
-                     "frac_alu_f32_plain_fma": round(flop / us / 1e6 / VALU_F32_TFLOPS, 4),
-                     "max_norm_err": float("%.2e" % err)})
+        row = {"filter": k, "us": round(us, 2), "gflops": round(flop / us / 1e3, 1),
+               "gbs": round(nbytes / us / 1e3, 1), "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4),
+               "frac_alu_f32_plain_fma": round(flop / us / 1e6 / VALU_F32_TFLOPS, 4),
+               "max_norm_err": float("%.2e" % err)}
+        if sw.sw_jit_prepare_depthwise(H, H, k, k, 1, pad) == 0:
+            y = sw.sw_conv2d_depthwise_jit(sets[0]["x"][:1, :2].contiguous(), wd[:2].contiguous(), 1, pad).cpu().numpy()
+            err = float(np.max(np.abs(y - y_ref) / d))
+            assert err <= 2e-5, ("jit", k, err)
+            us = time_kernel(torch, lambda s_: sw.sw_conv2d_depthwise_jit(s_["x"], wd, 1, pad, out=s_["y"]), sets,
+                             50 if k < 20 else 10)
+            row.update({"jit_us": round(us, 2), "jit_gflops": round(flop / us / 1e3, 1),
+                        "jit_frac_alu_f32_plain_fma": round(flop / us / 1e6 / VALU_F32_TFLOPS, 4),
+                        "jit_max_norm_err": float("%.2e" % err)})
+        rows.append(row)
     return {"sweep": "depthwise-shaped 32x64x56x56 fp32, square filter, stride 1, same padding", "rows": rows}
 
 

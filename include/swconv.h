@@ -163,7 +163,8 @@ int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, 
  * custom kernels generated at run time for every filter size).  Arguments, layouts,
  * result and errors as sw_conv2d_depthwise.  For stride 1, an output plane of at
  * most 56 x 56 (and at least half of that), W and W_out multiples of 4, H*W <= 4096,
- * 2*pad <= min(R,S)-1, a window of at most 40 KB and x, y 16-byte aligned, the first
+ * 2*pad <= min(R,S)-1, an LDS window (55+R rows) of at most 37 KB (33 x 33 at 56 x 56)
+ * and x, y 16-byte aligned, the first
  * call for a geometry (H, W, R, S, pad) compiles a kernel specialised on it (about a
  * second on the calling thread, host-synchronous; do not make that first call inside
  * a stream capture -- use sw_jit_prepare_depthwise beforehand), keeps it for the life

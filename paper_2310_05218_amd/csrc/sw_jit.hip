@@ -43,7 +43,7 @@ struct JitKernel {
     JitPlan plan;
 };
 
-typedef std::tuple<int, int, int, int, int, int> JitKey;   // device, H, W, R, S, pad
+typedef std::tuple<int, int, int, int, int, int, int, int> JitKey;   // device, H, W, R, S, pad, RB, NT
 
 std::mutex g_mutex;
 std::map<JitKey, JitKernel> g_cache;
@@ -72,20 +72,30 @@ bool jit_plan(int H, int W, int R, int S, int stride, int pad, JitPlan* out)
     if (bytes <= 20 * 1024) {
         p.waves_per_cu = 8;
         p.lds_bytes = bytes < 18432 ? 18432 : bytes;         // more than 160 KB / 9
-    } else if (bytes <= 40 * 1024) {
+    } else if (bytes <= 37 * 1024) {                         // beyond, the run-time-extent kernel is as fast
         p.waves_per_cu = 4;
         p.lds_bytes = bytes < 33792 ? 33792 : bytes;         // more than 160 KB / 5
     } else {
         return false;
     }
-    // taps of a pass live in scalar registers: about forty of them; passes of equal size on both axes
+    // taps of a pass live in scalar registers: a whole filter of up to 49 taps, else about forty of them (more
+    // would spill inside the loops over passes); passes of equal size on both axes
     const int s_chunks = S <= 10 ? 1 : (S + 8) / 9;
     p.NT = (S + s_chunks - 1) / s_chunks;
-    int RB = 40 / p.NT;
+    int RB = R * S <= 49 ? R : 40 / p.NT;
     if (RB < 1) RB = 1;
     if (RB > R) RB = R;
     const int r_blocks = (R + RB - 1) / RB;
     p.RB = (R + r_blocks - 1) / r_blocks;
+    // SWCONV_JIT_RB / SWCONV_JIT_NT override the split (tuning)
+    if (const char* e = getenv("SWCONV_JIT_RB")) {
+        const int v = atoi(e);
+        if (v >= 1 && v <= R) p.RB = v;
+    }
+    if (const char* e = getenv("SWCONV_JIT_NT")) {
+        const int v = atoi(e);
+        if (v >= 1 && v <= S && v <= 16) p.NT = v;
+    }
     *out = p;
     return true;
 }
@@ -137,7 +147,7 @@ int get_kernel(const JitPlan& p, JitKernel* out)
         (void)hipGetLastError();
         return SW_ERR_LAUNCH;
     }
-    const JitKey key(dev, p.H, p.W, p.R, p.S, p.pad);
+    const JitKey key(dev, p.H, p.W, p.R, p.S, p.pad, p.RB, p.NT);
     std::lock_guard<std::mutex> lock(g_mutex);
     auto it = g_cache.find(key);
     if (it != g_cache.end()) {

@@ -163,7 +163,7 @@ def test_jit_entry_point_argument_errors(L):
 
 # geometries inside the generated kernel's range: H, W, R, S, pad
 JIT_GEOMETRIES = [(56, 56, 1, 1, 0), (56, 56, 3, 3, 1), (56, 56, 9, 9, 4), (56, 56, 11, 11, 5), (56, 56, 17, 17, 8),
-                  (56, 56, 29, 29, 14), (56, 56, 41, 41, 20), (64, 64, 9, 9, 0), (56, 56, 5, 9, 2), (48, 52, 7, 7, 3)]
+                  (56, 56, 29, 29, 14), (56, 56, 33, 33, 16), (64, 64, 9, 9, 0), (56, 56, 5, 9, 2), (48, 52, 7, 7, 3)]
 
 
 @pytest.mark.parametrize("geometry", JIT_GEOMETRIES)
@@ -180,7 +180,7 @@ def test_jit_range_and_errors(L):
     assert B.sw_jit_compile_check(58, 58, 3, 3, 1, 1) == B.SW_ERR_UNSUPPORTED      # output above 56 x 56
     assert B.sw_jit_compile_check(56, 56, 12, 12, 1, 4) == B.SW_ERR_UNSUPPORTED    # W_out = 53
     assert B.sw_jit_compile_check(56, 56, 9, 9, 1, 6) == B.SW_ERR_UNSUPPORTED      # output larger than the plane
-    assert B.sw_jit_compile_check(56, 56, 45, 45, 1, 22) == B.SW_ERR_UNSUPPORTED   # window above 40 KB
+    assert B.sw_jit_compile_check(56, 56, 37, 37, 1, 18) == B.SW_ERR_UNSUPPORTED   # window above 37 KB
     assert B.sw_jit_compile_check(0, 56, 9, 9, 1, 4) == B.SW_ERR_SHAPE
     assert B.sw_jit_compile_check(4, 4, 9, 9, 1, 0) == B.SW_ERR_SHAPE              # filter larger than the plane
     assert B.sw_jit_prepare_depthwise(56, 56, 9, 9, 1, -1) == B.SW_ERR_SHAPE

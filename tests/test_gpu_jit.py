@@ -40,8 +40,8 @@ JIT_CASES = [
     (2, 9, 56, 56, 13, 13, 6),
     (2, 9, 56, 56, 17, 17, 8),   # four wavefronts per CU from here on (larger window)
     (1, 6, 56, 56, 25, 25, 12),
-    (1, 5, 56, 56, 33, 33, 16),
-    (1, 3, 56, 56, 41, 41, 20),  # the largest window
+    (1, 5, 56, 56, 33, 33, 16),  # the largest window
+    (1, 3, 56, 56, 41, 41, 20),  # beyond it -> precompiled path
     (2, 5, 64, 64, 9, 9, 0),     # no padding: the plane is larger than the output tile
     (2, 5, 56, 56, 5, 9, 2),     # rectangular filter, output 56 x 52
     (2, 5, 56, 56, 9, 5, 2),

@@ -58,6 +58,8 @@ def _load():
     lib.oracle_pool2d.argtypes = [vp] * 3 + [i64] * 7 + [ctypes.c_int]
     lib.oracle_requant_s8.restype = ctypes.c_int
     lib.oracle_requant_s8.argtypes = [vp] * 4 + [i64] * 3 + [ctypes.c_int]
+    lib.oracle_bias_relu.restype = ctypes.c_int
+    lib.oracle_bias_relu.argtypes = [vp] * 3 + [i64] * 3 + [ctypes.c_int]
     lib.oracle_conv2d_s8.restype = ctypes.c_int
     lib.oracle_conv2d_s8.argtypes = [vp] * 3 + [i64] * 9
     _lib = lib
@@ -210,3 +212,19 @@ def conv2d_s8_requant(x, w, bias, scale, stride: int = 1, pad: int = 0, relu: bo
     if rc:
         raise ValueError(f"oracle_requant_s8 rejected the arguments (code {rc})")
     return q
+
+
+def conv2d_bias_relu(x, w, bias, stride: int = 1, pad: int = 0, relu: bool = False):
+    """fp32 convolution followed by a per-channel bias and an optional rectifier, in fp64:
+    y = act(conv2d(x, w) + bias[co]); returns (y, D) with D = sum|x*w| + |bias[co]|.  bias fp32 [C_out] or None."""
+    y, d = conv2d(x, w, stride, pad)
+    N, C_out, Ho, Wo = y.shape
+    if bias is not None:
+        bias = _as(bias, np.float32, 1)
+        if bias.shape[0] != C_out:
+            raise ValueError("one bias per output channel")
+    rc = _load().oracle_bias_relu(_p(y), _p(d), _p(bias) if bias is not None else None, N, C_out, Ho * Wo,
+                                  1 if relu else 0)
+    if rc:
+        raise ValueError(f"oracle_bias_relu rejected the arguments (code {rc})")
+    return y, d

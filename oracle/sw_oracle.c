@@ -19,6 +19,7 @@
  *   avg pool2d y[p,i,j]    = (1/(R*S)) * sum_{r,s} xz[p,i*st+r-pad,j*st+s-pad]
  *   max pool2d y[p,i,j]    = max over the (r,s) whose position lies inside the plane
  *   requantise q[n,co,p]   = clamp(rne(scale[co] * float(acc[n,co,p] + bias[co])), lo, 127),  lo = relu ? 0 : -128
+ *   bias, relu y[n,co,p]   = act(y[n,co,p] + bias[co]),  act(t) = relu ? max(t, 0) : t
  *
  * xz is x inside the tensor and 0 outside (zero padding); no filter flip
  * (cross-correlation, as DNN frameworks define "convolution"); output extent
@@ -310,4 +311,26 @@ int oracle_requant_s8(const int32_t *acc, const int32_t *bias, const float *scal
         }
     }
     return overflow ? 2 : 0;
+}
+
+/* Per-channel bias and rectifier on a finished fp64 convolution result (section 1 of the paper: the layers these
+ * kernels serve are followed by a bias and an activation; the paper gives no formula, this is the usual one):
+ * y <- y + bias[co], the magnitude sum D <- D + |bias[co]| (the bias is one more term of the sum), then
+ * y <- max(y, 0) if relu.  bias may be NULL (zeros).  In place. */
+int oracle_bias_relu(double *y, double *d, const float *bias, int64_t N, int64_t C_out, int64_t pixels, int relu)
+{
+    if (N <= 0 || C_out <= 0 || pixels <= 0) return 1;
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t co = 0; co < C_out; ++co) {
+            const double b = bias ? (double)bias[co] : 0.0;
+            for (int64_t p = 0; p < pixels; ++p) {
+                const int64_t o = (n * C_out + co) * pixels + p;
+                double t = y[o] + b;
+                if (relu && t < 0.0) t = 0.0;
+                y[o] = t;
+                d[o] += fabs(b);
+            }
+        }
+    }
+    return 0;
 }

@@ -9,6 +9,7 @@ import pytest
 
 import test_oracle_pins as pins
 import test_oracle_pool2d_pins as pool_pins
+import test_oracle_bias_relu_pins as br_pins
 import test_oracle_requant_pins as rq_pins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -45,6 +46,12 @@ MUTANTS = [
     ("requantisation: scale of the neighbouring channel", "const float sc = scale[co];", "const float sc = scale[(co + 1) % C_out];", 0),
     ("requantisation: upper clamp at 128 wraps", "if (r > 127.0f) r = 127.0f;", "if (r > 128.0f) r = 128.0f;", 0),
     ("int8 overflow never reported", "return overflow ? 2 : 0;", "return 0;", 0),
+    ("bias of the neighbouring channel", "const double b = bias ? (double)bias[co] : 0.0;", "const double b = bias ? (double)bias[(co + 1) % C_out] : 0.0;", 0),
+    ("bias subtracted", "double t = y[o] + b;", "double t = y[o] - b;", 0),
+    ("rectifier before the bias", "double t = y[o] + b;\n                if (relu && t < 0.0) t = 0.0;", "double t = y[o];\n                if (relu && t < 0.0) t = 0.0;\n                t += b;", 0),
+    ("rectifier always on", "if (relu && t < 0.0) t = 0.0;", "if (t < 0.0) t = 0.0;", 0),
+    ("rectifier takes the magnitude", "if (relu && t < 0.0) t = 0.0;", "if (relu && t < 0.0) t = -t;", 0),
+    ("bias left out of the magnitude sum", "d[o] += fabs(b);", "d[o] += 0.0;", 0),
 ]
 
 
@@ -97,6 +104,8 @@ def _battery(o):
     rq_pins.test_conversion_to_fp32_comes_before_the_product(o)
     rq_pins.test_identity_monotonicity_and_overflow(o)
     pool_pins.test_special_cases_reduce_to_the_other_entry_points(o)
+    br_pins.test_hand_worked_example(o)
+    br_pins.test_no_bias_and_no_rectifier_is_the_plain_convolution(o)
 
 
 def test_unmutated_copy_passes_the_battery(tmp_path, oracle):

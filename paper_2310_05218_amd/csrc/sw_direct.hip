@@ -55,7 +55,8 @@ __global__ __launch_bounds__(kThreads) void direct_conv2d_kernel(const TI* __res
                                                                  const TI* __restrict__ w,
                                                                  TA* __restrict__ y, Conv2dShape s,
                                                                  int8_t* __restrict__ y8 = nullptr,
-                                                                 Requant rq = Requant{nullptr, nullptr, 0})
+                                                                 Requant rq = Requant{nullptr, nullptr, 0},
+                                                                 Epilogue ep = Epilogue{nullptr, 0})
 {
     const int64_t plane_o = (int64_t)s.Ho * s.Wo;
     const int64_t total = (int64_t)s.N * s.C_out * plane_o;
@@ -84,6 +85,7 @@ __global__ __launch_bounds__(kThreads) void direct_conv2d_kernel(const TI* __res
             }
         }
         if constexpr (RQ) y8[o] = requant_s8((int)acc, co, rq);
+        else if constexpr (sizeof(TI) == 4) y[o] = apply_epilogue(acc, co, ep);
         else y[o] = acc;
     }
 }
@@ -178,15 +180,17 @@ hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t ro
 }
 
 hipError_t launch_direct_conv2d_f32(const float* x, const float* w, float* y, const Conv2dShape& s,
-                                    bool depthwise, hipStream_t st)
+                                    bool depthwise, hipStream_t st, const Epilogue* ep)
 {
     const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
+    const Epilogue e = ep ? *ep : Epilogue{nullptr, 0};
+    const Requant none{nullptr, nullptr, 0};
     if (depthwise)
         hipLaunchKernelGGL((direct_conv2d_kernel<float, float, true>), dim3(grid), dim3(kThreads), 0, st, x,
-                           w, y, s);
+                           w, y, s, static_cast<int8_t*>(nullptr), none, e);
     else
         hipLaunchKernelGGL((direct_conv2d_kernel<float, float, false>), dim3(grid), dim3(kThreads), 0, st, x,
-                           w, y, s);
+                           w, y, s, static_cast<int8_t*>(nullptr), none, e);
     return hipGetLastError();
 }
 

@@ -37,12 +37,14 @@ constexpr int kXBytes = 4 * kLdsPx * 16;
 constexpr int kWGroupBytes = 64 * 16 + 64;   // one (tap, channel quad): 64 channels x 16 bytes, skewed
 
 struct F32Params {
+    Epilogue ep;                       // bias and rectifier of the EP variant
     int C_in, C_out, H, W, pad, Ho, Wo, TH, TW;
     FastDiv by_tiles_x, by_TW, by_IW, by_npx;
 };
 
 // DB: two LDS buffers, the next chunk is copied in while the current one is multiplied.
-template <int R, int S, bool DB>
+// EP: a per-channel bias and a rectifier are applied in the store (the plain variant carries no trace of them).
+template <int R, int S, bool DB, bool EP>
 __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restrict__ x,
                                                           const float* __restrict__ w,
                                                           float* __restrict__ y, const F32Params P)
@@ -180,6 +182,7 @@ __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restric
 
     const int HoWo = Ho * Wo;
     float* yn = y + ((int64_t)n * C_out + (mb << 6) + 32 * wm + 4 * lg) * HoWo;
+    float bv[16];                       // EP: the biases of this lane's 16 output channels (set before the stores)
     auto store_block = [&](int nb, const floatx16& c) {
         const int p = nb * 32 + lj;
         const int pi = fast_div(p, P.by_TW), pj = p - pi * TW;
@@ -187,7 +190,14 @@ __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restric
         if (p < tile_px && oi < Ho && oj < Wo) {
             float* dst = yn + oi * Wo + oj;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) dst[(8 * (v >> 2) + (v & 3)) * HoWo] = c[v];
+            for (int v = 0; v < 16; ++v) {
+                float t = c[v];
+                if (EP) {
+                    t += bv[v];
+                    if (P.ep.relu) t = fmaxf(t, 0.0f);
+                }
+                dst[(8 * (v >> 2) + (v & 3)) * HoWo] = t;
+            }
         }
     };
 
@@ -241,6 +251,11 @@ __global__ __launch_bounds__(256, 1) void mfma_f32_kernel(const float* __restric
     }
 
     // ---- last chunk: block by block, so that finished blocks are stored while the next ones multiply ----
+    if (EP) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            bv[v] = P.ep.bias ? P.ep.bias[(mb << 6) + 32 * wm + 4 * lg + 8 * (v >> 2) + (v & 3)] : 0.0f;
+    }
     {
         const int bofs = (DB ? ((chunks - 1) & 1) : 0) * kBufBytes;
         // swing block first: this wavefront's octet, then the two octet halves meet in LDS
@@ -315,16 +330,18 @@ constexpr int kLdsMax = 160 * 1024;
 constexpr int kSumBytes = 2 * 16 * 64 * 4;
 constexpr int buf_bytes(int RS) { return kXBytes + RS * 4 * kWGroupBytes; }
 
-template <int R, int S>
-hipError_t launch(const float* x, const float* w, float* y, const Conv2dShape& s, const Tiling& t, hipStream_t st)
+template <int R, int S, bool EP>
+hipError_t launch(const float* x, const float* w, float* y, const Conv2dShape& s, const Tiling& t, hipStream_t st,
+                  const Epilogue& ep)
 {
     constexpr bool DB = 2 * buf_bytes(R * S) + kSumBytes <= kLdsMax;
     constexpr int bytes = (DB ? 2 : 1) * buf_bytes(R * S) + kSumBytes;
     static_assert(bytes <= kLdsMax, "LDS budget");
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_f32_kernel<R, S, DB>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_f32_kernel<R, S, DB, EP>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
     if (attr != hipSuccess) return attr;
     F32Params P;
+    P.ep = ep;
     P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
     P.TH = t.TH; P.TW = t.TW;
     P.by_tiles_x = make_fastdiv(t.tiles_x);
@@ -332,7 +349,7 @@ hipError_t launch(const float* x, const float* w, float* y, const Conv2dShape& s
     P.by_IW = make_fastdiv(t.TW + S - 1);
     P.by_npx = make_fastdiv((t.TH + R - 1) * (t.TW + S - 1));
     dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)s.N, (unsigned)(s.C_out / 64));
-    hipLaunchKernelGGL((mfma_f32_kernel<R, S, DB>), grid, dim3(256), bytes, st, x, w, y, P);
+    hipLaunchKernelGGL((mfma_f32_kernel<R, S, DB, EP>), grid, dim3(256), bytes, st, x, w, y, P);
     return hipGetLastError();
 }
 
@@ -355,12 +372,17 @@ int64_t mfma_f32_workgroups(const Conv2dShape& s)
     return (int64_t)t.tiles_x * t.tiles_y * s.N * (s.C_out / 64);
 }
 
-hipError_t launch_mfma_f32(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st)
+hipError_t launch_mfma_f32(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
+                           const Epilogue& ep)
 {
-    if (reinterpret_cast<uintptr_t>(w) % 16 != 0) return launch_direct_conv2d_f32(x, w, y, s, false, st);
+    if (reinterpret_cast<uintptr_t>(w) % 16 != 0) return launch_direct_conv2d_f32(x, w, y, s, false, st, &ep);
     const Tiling t = pick_tiling(s);
-    if (s.R == 3) return launch<3, 3>(x, w, y, s, t, st);
-    return launch<5, 5>(x, w, y, s, t, st);
+    if (ep.bias || ep.relu) {
+        if (s.R == 3) return launch<3, 3, true>(x, w, y, s, t, st, ep);
+        return launch<5, 5, true>(x, w, y, s, t, st, ep);
+    }
+    if (s.R == 3) return launch<3, 3, false>(x, w, y, s, t, st, ep);
+    return launch<5, 5, false>(x, w, y, s, t, st, ep);
 }
 
 }  // namespace swconv

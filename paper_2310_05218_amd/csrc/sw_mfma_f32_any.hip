@@ -29,6 +29,7 @@ constexpr int kXS = 16;                // register-prefetch slots per thread: in
 constexpr int kWS = 6;                 // ... and filters (16-byte groups)
 
 struct AnyParams {
+    Epilogue ep;                       // bias and rectifier applied in the store
     int C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
     int TH, TW, IH, IW, tiles_x, wpitch;
     FastDiv by_tiles_x, by_TW, by_IW, by_win, by_span, by_span4;
@@ -192,8 +193,8 @@ __global__ __launch_bounds__(256) void mfma_f32_any_kernel(const float* __restri
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int co = 8 * (v >> 2) + 4 * kk + (v & 3);
-        if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = acc0[v];
-        if (co0 + 32 + co < P.C_out) yp[(int64_t)(32 + co) * HoWo] = acc1[v];
+        if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = apply_epilogue(acc0[v], co0 + co, P.ep);
+        if (co0 + 32 + co < P.C_out) yp[(int64_t)(32 + co) * HoWo] = apply_epilogue(acc1[v], co0 + 32 + co, P.ep);
     }
 }
 
@@ -251,9 +252,11 @@ AnyPlan plan_any(const Conv2dShape& s, const float* w)
 }
 
 template <int CK>
-hipError_t launch_any(const float* x, const float* w, float* y, const Conv2dShape& s, const AnyPlan& a, hipStream_t st)
+hipError_t launch_any(const float* x, const float* w, float* y, const Conv2dShape& s, const AnyPlan& a, hipStream_t st,
+                      const Epilogue& ep)
 {
     AnyParams P;
+    P.ep = ep;
     P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.R = s.R; P.S = s.S; P.stride = s.stride;
     P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
     P.TH = a.TH; P.TW = a.TW; P.IH = a.IH; P.IW = a.IW; P.tiles_x = a.tiles_x; P.wpitch = a.wpitch;
@@ -277,16 +280,17 @@ hipError_t launch_any(const float* x, const float* w, float* y, const Conv2dShap
 
 bool mfma_f32_any_supported(const Conv2dShape& s) { return s.C_in >= 2 && plan_any(s, nullptr).ok; }
 
-hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st)
+hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
+                               const Epilogue& ep)
 {
     const AnyPlan a = plan_any(s, w);
     if (!a.ok) return hipErrorInvalidValue;
     switch (a.CK) {
-        case 32: return launch_any<32>(x, w, y, s, a, st);
-        case 16: return launch_any<16>(x, w, y, s, a, st);
-        case 8: return launch_any<8>(x, w, y, s, a, st);
-        case 4: return launch_any<4>(x, w, y, s, a, st);
-        default: return launch_any<2>(x, w, y, s, a, st);
+        case 32: return launch_any<32>(x, w, y, s, a, st, ep);
+        case 16: return launch_any<16>(x, w, y, s, a, st, ep);
+        case 8: return launch_any<8>(x, w, y, s, a, st, ep);
+        case 4: return launch_any<4>(x, w, y, s, a, st, ep);
+        default: return launch_any<2>(x, w, y, s, a, st, ep);
     }
 }
 

@@ -26,6 +26,7 @@ constexpr int kXS = 4;                 // staging items per thread: input window
 constexpr int kWS = 6;                 // ... and filters
 
 struct QuadParams {
+    Epilogue ep;                       // bias and rectifier applied in the store
     int C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
     int TH, TW, IH, IW, tiles_x;
     FastDiv by_tiles_x, by_TW, by_IW, by_win, by_RS, by_QRS;
@@ -176,8 +177,8 @@ __global__ __launch_bounds__(256) void mfma_f32_quad_kernel(const float* __restr
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int co = 8 * (v >> 2) + 4 * kk + (v & 3);
-        if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = acc0[v];
-        if (co0 + 32 + co < P.C_out) yp[(int64_t)(32 + co) * HoWo] = acc1[v];
+        if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = apply_epilogue(acc0[v], co0 + co, P.ep);
+        if (co0 + 32 + co < P.C_out) yp[(int64_t)(32 + co) * HoWo] = apply_epilogue(acc1[v], co0 + 32 + co, P.ep);
     }
 }
 
@@ -214,9 +215,11 @@ QuadPlan plan_quad(const Conv2dShape& s)
 }
 
 template <int CK>
-hipError_t launch_quad(const float* x, const float* w, float* y, const Conv2dShape& s, const QuadPlan& a, hipStream_t st)
+hipError_t launch_quad(const float* x, const float* w, float* y, const Conv2dShape& s, const QuadPlan& a, hipStream_t st,
+                       const Epilogue& ep)
 {
     QuadParams P;
+    P.ep = ep;
     P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.R = s.R; P.S = s.S; P.stride = s.stride;
     P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
     P.TH = a.TH; P.TW = a.TW; P.IH = a.IH; P.IW = a.IW; P.tiles_x = a.tiles_x;
@@ -236,13 +239,14 @@ hipError_t launch_quad(const float* x, const float* w, float* y, const Conv2dSha
 // (with fewer than five input channels most of an eight-channel group would be zero padding)
 bool mfma_f32_quad_supported(const Conv2dShape& s) { return s.C_in >= 5 && plan_quad(s).ok; }
 
-hipError_t launch_mfma_f32_quad(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st)
+hipError_t launch_mfma_f32_quad(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
+                                const Epilogue& ep)
 {
     const QuadPlan a = plan_quad(s);
     if (!a.ok) return hipErrorInvalidValue;
-    if (a.CK == 32) return launch_quad<32>(x, w, y, s, a, st);
-    if (a.CK == 16) return launch_quad<16>(x, w, y, s, a, st);
-    return launch_quad<8>(x, w, y, s, a, st);
+    if (a.CK == 32) return launch_quad<32>(x, w, y, s, a, st, ep);
+    if (a.CK == 16) return launch_quad<16>(x, w, y, s, a, st, ep);
+    return launch_quad<8>(x, w, y, s, a, st, ep);
 }
 
 }  // namespace swconv

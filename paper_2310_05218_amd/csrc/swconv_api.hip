@@ -213,26 +213,44 @@ int sw_pool2d(const float* x, float* y, int N, int C, int H, int W, int R, int S
     return launch_status(launch_direct_pool2d(x, y, planes, H, W, R, S, stride, pad, (int)Ho, (int)Wo, maximum, st));
 }
 
-int sw_conv2d(const float* x, const float* w, float* y, int N, int C_in, int C_out, int H, int W, int R,
-              int S, int stride, int pad, void* hip_stream)
+// The multi-channel fp32 convolution with the store's epilogue (none for sw_conv2d).
+static int run_conv2d(const float* x, const float* w, float* y, const Conv2dShape& s, const Epilogue& ep, hipStream_t st)
 {
-    Conv2dShape s;
-    const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, 4, 4, &s);
-    if (rc != SW_OK) return rc;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (C_in == 1) return run_plane(x, w, y, (int64_t)N * C_out, C_out, C_out, s, false, st);
-    if (!force_direct()) {
+    const bool plain = !ep.bias && !ep.relu;
+    if (s.C_in == 1 && plain) return run_plane(x, w, y, (int64_t)s.N * s.C_out, s.C_out, s.C_out, s, false, st);
+    // (one input channel with an epilogue: the one-filter-per-plane kernels have none, one thread per output has)
+    if (!force_direct() && s.C_in > 1) {
         // The fixed 3x3 / 5x5 kernel holds a CU with one large tile: it needs enough of them to fill the chip
         // (28 x 28 images and below at batch 32 leave it at 128 or fewer); the any-shape kernel's 128-pixel
         // tiles take over there, and everywhere the fixed kernel has no variant.
         const bool quad_ok = mfma_f32_quad_supported(s);
         const bool any_ok = quad_ok || mfma_f32_any_supported(s);
         if (mfma_f32_supported(s) && !no_large_tile_mfma() && (mfma_f32_workgroups(s) >= 160 || !any_ok))
-            return launch_status(launch_mfma_f32(x, w, y, s, st));
-        if (quad_ok) return launch_status(launch_mfma_f32_quad(x, w, y, s, st));
-        if (any_ok) return launch_status(launch_mfma_f32_any(x, w, y, s, st));
+            return launch_status(launch_mfma_f32(x, w, y, s, st, ep));
+        if (quad_ok) return launch_status(launch_mfma_f32_quad(x, w, y, s, st, ep));
+        if (any_ok) return launch_status(launch_mfma_f32_any(x, w, y, s, st, ep));
     }
-    return launch_status(launch_direct_conv2d_f32(x, w, y, s, false, st));
+    return launch_status(launch_direct_conv2d_f32(x, w, y, s, false, st, &ep));
+}
+
+int sw_conv2d(const float* x, const float* w, float* y, int N, int C_in, int C_out, int H, int W, int R,
+              int S, int stride, int pad, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, 4, 4, &s);
+    if (rc != SW_OK) return rc;
+    return run_conv2d(x, w, y, s, Epilogue{nullptr, 0}, static_cast<hipStream_t>(hip_stream));
+}
+
+int sw_conv2d_bias_relu(const float* x, const float* w, const float* bias, float* y, int N, int C_in, int C_out, int H,
+                        int W, int R, int S, int stride, int pad, int relu, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, 4, 4, &s);
+    if (rc != SW_OK) return rc;
+    if (bias && misaligned(bias, 4)) return SW_ERR_ALIGN;
+    if (bias && overlaps(y, (int64_t)N * C_out * s.Ho * s.Wo * 4, bias, (int64_t)C_out * 4)) return SW_ERR_ALIAS;
+    return run_conv2d(x, w, y, s, Epilogue{bias, relu != 0}, static_cast<hipStream_t>(hip_stream));
 }
 
 int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,

@@ -24,6 +24,20 @@ struct Conv2dShape {
     int N, C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
 };
 
+// Per-channel bias and rectifier on an fp32 sum on its way out: y = relu ? max(acc + bias[co], 0) : acc + bias[co]
+// (one fp32 addition).  bias may be null.
+struct Epilogue {
+    const float* bias;
+    int relu;
+};
+__device__ __forceinline__ float apply_epilogue(float acc, int co, const Epilogue& e)
+{
+    float t = acc;
+    if (e.bias) t += e.bias[co];
+    if (e.relu) t = fmaxf(t, 0.0f);
+    return t;
+}
+
 // Requantisation of an exact int32 sum to int8, per output channel:
 //     q = clamp(rne(scale[co] * float(acc + bias[co])), relu ? 0 : -128, 127)
 // with the conversion, the product and the rounding in fp32 (v_cvt_f32_i32, v_mul_f32, v_rndne_f32: the
@@ -46,7 +60,7 @@ __device__ __forceinline__ int8_t requant_s8(int acc, int co, const Requant& rq)
 hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
                             int64_t len_out, int k, int stride, int pad, Op1D op, hipStream_t st);
 hipError_t launch_direct_conv2d_f32(const float* x, const float* w, float* y, const Conv2dShape& s,
-                                    bool depthwise, hipStream_t st);
+                                    bool depthwise, hipStream_t st, const Epilogue* ep = nullptr);
 hipError_t launch_direct_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s,
                                    hipStream_t st);
 hipError_t launch_direct_pool2d(const float* x, float* y, int64_t planes, int H, int W, int R, int S, int stride,
@@ -106,12 +120,15 @@ hipError_t launch_global_pool(const float* x, float* y, int64_t planes, int HW, 
 
 // ---- multi-channel kernels on the matrix cores (stride 1) --------------------------------------
 bool       mfma_f32_supported(const Conv2dShape& s);
-hipError_t launch_mfma_f32(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
+hipError_t launch_mfma_f32(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
+                           const Epilogue& ep = Epilogue{nullptr, 0});
 int64_t    mfma_f32_workgroups(const Conv2dShape& s);     // of the fixed 3x3 / 5x5 kernel, one per CU at a time; 0: tiles half empty
 bool       mfma_f32_any_supported(const Conv2dShape& s);  // any extent, stride and channel count (C_in >= 2)
-hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
+hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
+                               const Epilogue& ep = Epilogue{nullptr, 0});
 bool       mfma_f32_quad_supported(const Conv2dShape& s); // the same for few taps (R * S <= 12): 16-byte operand reads
-hipError_t launch_mfma_f32_quad(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st);
+hipError_t launch_mfma_f32_quad(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
+                                const Epilogue& ep = Epilogue{nullptr, 0});
 bool       mfma_s8_supported(const Conv2dShape& s);
 hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st);
 // the same with the requantisation fused into the store (y8: int8 output)

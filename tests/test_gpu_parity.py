@@ -362,6 +362,52 @@ CONV2D_CASES = [
 ]
 
 
+BIAS_RELU_CASES = [
+    # N, C_in, C_out, H, W, R, S, stride, pad
+    (8, 16, 256, 56, 56, 3, 3, 1, 1),    # enough large tiles for the fixed 3x3 matrix-core kernel (256 workgroups)
+    (4, 16, 256, 56, 56, 5, 5, 1, 2),    # ... and the 5x5 one
+    (2, 16, 64, 56, 56, 3, 3, 1, 1),     # 128-pixel tiles, channel quads
+    (1, 3, 5, 9, 11, 3, 3, 1, 1),        # any-shape kernel, ragged channel block
+    (2, 4, 3, 12, 10, 2, 5, 2, 2),
+    (1, 9, 130, 16, 16, 2, 2, 2, 0),     # three channel blocks with a ragged last one
+    (2, 1, 6, 20, 20, 3, 3, 1, 1),       # one input channel: one thread per output
+]
+
+
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("case", BIAS_RELU_CASES)
+def test_conv2d_bias_relu(torch, sw, oracle, case, relu):
+    """Per-channel bias and rectifier fused into the store: y = act(conv + bias[co]); the bias is one more term of
+    the magnitude sum the tolerance is relative to."""
+    N, C_in, C_out, H, W, R, S, stride, pad = case
+    x = inputs.normal_f32((N, C_in, H, W), 3101)
+    w = inputs.normal_f32((C_out, C_in, R, S), 3102, (2.0 / (C_in * R * S)) ** 0.5)
+    bias = inputs.normal_f32((C_out,), 3103, 0.7)
+    y_ref, d = oracle.conv2d_bias_relu(x, w, bias, stride, pad, relu)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_bias_relu(dev(torch, x), dev(torch, w), dev(torch, bias), stride, pad, relu, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    y = out.cpu().numpy()
+    assert_f32_parity(y, y_ref, d, f"conv2d_bias_relu {case} relu={relu}")
+    if relu:
+        assert y.min() == 0.0 and 0.2 < (y == 0).mean() < 0.8
+    else:
+        # the bias really is per output channel: channel means move by it
+        y0 = sw.sw_conv2d(dev(torch, x), dev(torch, w), stride, pad).cpu().numpy()
+        shift = (y - y0).mean(axis=(0, 2, 3))
+        assert np.allclose(shift, bias, atol=1e-4)
+
+
+def test_conv2d_bias_relu_without_bias_or_rectifier(torch, sw, oracle):
+    x = inputs.normal_f32((2, 16, 28, 28), 3111)
+    w = inputs.normal_f32((64, 16, 3, 3), 3112, 0.1)
+    xd, wd = dev(torch, x), dev(torch, w)
+    plain = sw.sw_conv2d(xd, wd, 1, 1)
+    assert torch.equal(sw.sw_conv2d_bias_relu(xd, wd, None, 1, 1, False), plain)
+    assert torch.equal(sw.sw_conv2d_bias_relu(xd, wd, None, 1, 1, True), torch.clamp_min(plain, 0.0))
+
+
 @pytest.mark.parametrize("case", CONV2D_CASES)
 def test_conv2d(torch, sw, oracle, case):
     N, C_in, C_out, H, W, R, S, stride, pad = case

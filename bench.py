@@ -213,7 +213,27 @@ def filter_size_sweep(torch, sw):
                         "jit_frac_alu_f32_plain_fma": round(flop / us / 1e6 / VALU_F32_TFLOPS, 4),
                         "jit_max_norm_err": float("%.2e" % err)})
         rows.append(row)
-    return {"sweep": "depthwise-shaped 32x64x56x56 fp32, square filter, stride 1, same padding", "rows": rows}
+    # the same axis with a C_in reduction (matrix cores): workload 3's shape with growing filters
+    mc_rows = []
+    Ci = Co = 64
+    xm = inputs.normal_f32((N, Ci, H, H), inputs.seed_for(6, 1000))
+    msets = [{"x": torch.from_numpy(xm).cuda(), "y": torch.empty((N, Co, H, H), device="cuda")} for _ in range(6)]
+    for k in (1, 3, 5, 7, 9, 11, 13):
+        w = inputs.normal_f32((Co, Ci, k, k), inputs.seed_for(6, 1000 + k), (2.0 / (Ci * k * k)) ** 0.5)
+        wd = torch.from_numpy(w).cuda()
+        pad = (k - 1) // 2
+        y = sw.sw_conv2d(msets[0]["x"][:1].contiguous(), wd, 1, pad).cpu().numpy()
+        y_ref, d = oracle.conv2d(xm[:1], w, 1, pad)
+        err = float(np.max(np.abs(y - y_ref) / d))
+        assert err <= 2e-5, ("multi-channel", k, err)
+        us = time_kernel(torch, lambda s_: sw.sw_conv2d(s_["x"], wd, 1, pad, out=s_["y"]), msets, 12 if k < 7 else 6)
+        flop = 2.0 * k * k * Ci * Co * N * H * H
+        mc_rows.append({"filter": k, "us": round(us, 2), "gflops": round(flop / us / 1e3, 1),
+                        "frac_mfma_f32": round(flop / us / 1e6 / MFMA_F32_TFLOPS, 4),
+                        "max_norm_err": float("%.2e" % err)})
+    return {"sweep": "depthwise-shaped 32x64x56x56 fp32, square filter, stride 1, same padding", "rows": rows,
+            "multi_channel_sweep": "32x64x56x56 -> 64 channels fp32, square filter, stride 1, same padding",
+            "multi_channel_rows": mc_rows}
 
 
 def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, stride, pad, C_out):

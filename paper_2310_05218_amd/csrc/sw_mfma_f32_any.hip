@@ -25,6 +25,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 constexpr int kTilePx = 128;           // output pixels per workgroup: one 32-pixel block per wavefront
 constexpr int kLdsBudget = 64 * 1024;  // keeps at least two workgroups on a CU
+constexpr int kLdsLarge = 156 * 1024;  // one workgroup per CU: filters whose 64 x (channels x taps) rows need it
 constexpr int kXS = 16;                // register-prefetch slots per thread: input window (floats) ...
 constexpr int kWS = 6;                 // ... and filters (16-byte groups)
 
@@ -222,7 +223,10 @@ AnyPlan plan_any(const Conv2dShape& s, const float* w)
         a.wpitch = span | 1;     // odd: the 32 rows an operand read touches fall into 32 banks
         return ((((size_t)a.CK * a.IH * a.IW + 3) & ~(size_t)3) + (size_t)64 * a.wpitch) * sizeof(float);
     };
-    while (bytes() > (size_t)kLdsBudget) {
+    // two workgroups per CU if the filters allow it, else one (large filters: 11 x 11 needs 62 KB for the
+    // filter rows of two channels alone)
+    size_t budget = (size_t)64 * ((2 * RS) | 1) * sizeof(float) + 4096 <= (size_t)kLdsBudget ? kLdsBudget : kLdsLarge;
+    while (bytes() > budget) {
         if (a.CK > 2) a.CK /= 2;
         else if (a.TH > 1) a.TH = (a.TH + 1) / 2;
         else if (a.TW > 32) a.TW = (a.TW + 1) / 2;
@@ -241,7 +245,7 @@ AnyPlan plan_any(const Conv2dShape& s, const float* w)
     a.tiles_x = (s.Wo + a.TW - 1) / a.TW;
     a.tiles_y = (s.Ho + a.TH - 1) / a.TH;
     const int64_t span = (int64_t)a.CK * RS;
-    a.ok = a.lds <= (size_t)kLdsBudget && (int64_t)a.tiles_x * a.tiles_y * a.tiles_x < 2147483647LL && s.N <= 65535 &&
+    a.ok = a.lds <= budget && (int64_t)a.tiles_x * a.tiles_y * a.tiles_x < 2147483647LL && s.N <= 65535 &&
            (s.C_out + 63) / 64 <= 65535 &&
            // 32-bit index arithmetic inside one image / 64 output channels' filters, and exact fast division
            (int64_t)s.C_in * s.H * s.W <= 2147483647LL && (int64_t)64 * s.C_in * RS <= 2147483647LL &&
@@ -249,6 +253,15 @@ AnyPlan plan_any(const Conv2dShape& s, const float* w)
     a.prefetch = span % 4 == 0 && ((int64_t)s.C_in * RS) % 4 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 &&
                  (int64_t)a.CK * a.IH * a.IW <= 256 * kXS && 64 * (span / 4) <= 256 * kWS;
     return a;
+}
+
+// Dynamic LDS above 64 KB has to be allowed per kernel, once.
+template <int CK, int XS>
+hipError_t allow_large_lds()
+{
+    static const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_f32_any_kernel<CK, XS>),
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsLarge);
+    return e;
 }
 
 template <int CK>
@@ -267,12 +280,17 @@ hipError_t launch_any(const float* x, const float* w, float* y, const Conv2dShap
     P.by_span = make_fastdiv(CK * s.R * s.S);
     P.by_span4 = make_fastdiv(a.prefetch ? CK * s.R * s.S / 4 : 1);
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
-    if (a.prefetch && CK * a.IH * a.IW <= 256 * 8)
+    const bool large = a.lds > (size_t)kLdsBudget;
+    if (a.prefetch && CK * a.IH * a.IW <= 256 * 8) {
+        if (large && allow_large_lds<CK, 8>() != hipSuccess) return hipErrorInvalidValue;
         hipLaunchKernelGGL((mfma_f32_any_kernel<CK, 8>), grid, dim3(256), a.lds, st, x, w, y, P);
-    else if (a.prefetch)
+    } else if (a.prefetch) {
+        if (large && allow_large_lds<CK, kXS>() != hipSuccess) return hipErrorInvalidValue;
         hipLaunchKernelGGL((mfma_f32_any_kernel<CK, kXS>), grid, dim3(256), a.lds, st, x, w, y, P);
-    else
+    } else {
+        if (large && allow_large_lds<CK, 0>() != hipSuccess) return hipErrorInvalidValue;
         hipLaunchKernelGGL((mfma_f32_any_kernel<CK, 0>), grid, dim3(256), a.lds, st, x, w, y, P);
+    }
     return hipGetLastError();
 }
 

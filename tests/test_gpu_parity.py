@@ -357,6 +357,10 @@ CONV2D_CASES = [
     (2, 40, 64, 14, 14, 1, 1, 1, 0),     # pointwise, C_in not a multiple of 8
     (1, 24, 64, 14, 14, 1, 1, 2, 0),     # pointwise with stride
     (1, 6, 8, 30, 30, 13, 13, 1, 6),     # 169 taps: channel chunks of two
+    (1, 6, 64, 30, 30, 11, 11, 1, 5),    # filter rows beyond 64 KB of LDS: one workgroup per CU
+    (2, 4, 70, 24, 24, 13, 13, 1, 6),
+    (1, 3, 64, 40, 40, 17, 17, 2, 8),    # the largest filter of the matrix-core kernel
+    (1, 2, 5, 40, 40, 18, 18, 1, 9),     # beyond it: one thread per output
     (1, 2, 4, 5, 5, 5, 5, 1, 0),         # a single output pixel
     (1, 9, 130, 16, 16, 2, 2, 2, 0),     # even filter, three channel blocks with a ragged last one
 ]

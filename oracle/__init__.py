@@ -58,6 +58,10 @@ def _load():
     lib.oracle_pool2d.argtypes = [vp] * 3 + [i64] * 7 + [ctypes.c_int]
     lib.oracle_requant_s8.restype = ctypes.c_int
     lib.oracle_requant_s8.argtypes = [vp] * 4 + [i64] * 3 + [ctypes.c_int]
+    lib.oracle_out_dim_dilated.restype = i64
+    lib.oracle_out_dim_dilated.argtypes = [i64] * 5
+    lib.oracle_conv2d_dilated.restype = ctypes.c_int
+    lib.oracle_conv2d_dilated.argtypes = [vp] * 4 + [i64] * 10 + [ctypes.c_int]
     lib.oracle_bias_relu.restype = ctypes.c_int
     lib.oracle_bias_relu.argtypes = [vp] * 3 + [i64] * 3 + [ctypes.c_int]
     lib.oracle_conv2d_s8.restype = ctypes.c_int
@@ -227,4 +231,28 @@ def conv2d_bias_relu(x, w, bias, stride: int = 1, pad: int = 0, relu: bool = Fal
                                   1 if relu else 0)
     if rc:
         raise ValueError(f"oracle_bias_relu rejected the arguments (code {rc})")
+    return y, d
+
+
+def conv2d_dilated(x, w, stride: int = 1, pad: int = 0, dilation: int = 1, depthwise: bool = False):
+    """Dilated convolution in fp64: taps `dilation` positions apart.  x [N,C_in,H,W]; w [C_out,C_in,R,S], or
+    [C,1,R,S] with depthwise=True.  Returns (y, D)."""
+    x = _as(x, np.float32, 4)
+    w = _as(w, np.float32, 4)
+    N, C_in, H, W = x.shape
+    C_out, Cw, R, S = w.shape
+    if (depthwise and (Cw != 1 or C_out != C_in)) or (not depthwise and Cw != C_in):
+        raise ValueError("channel mismatch between x and w")
+    if dilation < 1:
+        raise ValueError("dilation must be at least 1")
+    Ho = int(_load().oracle_out_dim_dilated(H, R, stride, pad, dilation))
+    Wo = int(_load().oracle_out_dim_dilated(W, S, stride, pad, dilation))
+    if Ho <= 0 or Wo <= 0:
+        raise ValueError("the dilated filter does not fit the padded input")
+    y = np.empty((N, C_out, Ho, Wo), np.float64)
+    d = np.empty_like(y)
+    rc = _load().oracle_conv2d_dilated(_p(x), _p(w), _p(y), _p(d), N, C_in, C_out, H, W, R, S, stride, pad,
+                                       dilation, 1 if depthwise else 0)
+    if rc:
+        raise ValueError(f"oracle_conv2d_dilated rejected the arguments (code {rc})")
     return y, d

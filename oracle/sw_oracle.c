@@ -20,6 +20,7 @@
  *   max pool2d y[p,i,j]    = max over the (r,s) whose position lies inside the plane
  *   requantise q[n,co,p]   = clamp(rne(scale[co] * float(acc[n,co,p] + bias[co])), lo, 127),  lo = relu ? 0 : -128
  *   bias, relu y[n,co,p]   = act(y[n,co,p] + bias[co]),  act(t) = relu ? max(t, 0) : t
+ *   dilated    y[n,co,i,j] = sum_{ci,r,s} w[co,ci,r,s] * xz[n,ci,i*st+r*dil-pad,j*st+s*dil-pad]
  *
  * xz is x inside the tensor and 0 outside (zero padding); no filter flip
  * (cross-correlation, as DNN frameworks define "convolution"); output extent
@@ -329,6 +330,56 @@ int oracle_bias_relu(double *y, double *d, const float *bias, int64_t N, int64_t
                 if (relu && t < 0.0) t = 0.0;
                 y[o] = t;
                 d[o] += fabs(b);
+            }
+        }
+    }
+    return 0;
+}
+
+/* Dilated (a trous) convolution by its definition: the taps of the filter are `dil` input positions apart, so
+ * the filter spans dil*(k-1)+1 inputs per axis and the output extent is that of a filter of this span (figure 2
+ * of the paper names dilated variants among the 2-D kernels).  depthwise != 0: one filter per channel,
+ * w is [C,1,R,S] and C_in == C_out is required; else w is [C_out,C_in,R,S].  d may be NULL. */
+int64_t oracle_out_dim_dilated(int64_t in, int64_t k, int64_t stride, int64_t pad, int64_t dil)
+{
+    if (k <= 0 || dil <= 0) return 0;
+    return oracle_out_dim(in, dil * (k - 1) + 1, stride, pad);
+}
+
+int oracle_conv2d_dilated(const float *x, const float *w, double *y, double *d,
+                          int64_t N, int64_t C_in, int64_t C_out, int64_t H, int64_t W,
+                          int64_t R, int64_t S, int64_t stride, int64_t pad, int64_t dil, int depthwise)
+{
+    if (dil <= 0 || R <= 0 || S <= 0) return 1;
+    const int64_t Ho = oracle_out_dim_dilated(H, R, stride, pad, dil);
+    const int64_t Wo = oracle_out_dim_dilated(W, S, stride, pad, dil);
+    if (N <= 0 || C_in <= 0 || C_out <= 0 || Ho <= 0 || Wo <= 0) return 1;
+    if (depthwise && C_in != C_out) return 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        for (int64_t co = 0; co < C_out; ++co) {
+            const int64_t ci_first = depthwise ? co : 0, ci_end = depthwise ? co + 1 : C_in;
+            for (int64_t i = 0; i < Ho; ++i) {
+                for (int64_t j = 0; j < Wo; ++j) {
+                    double acc = 0.0, mag = 0.0;
+                    for (int64_t ci = ci_first; ci < ci_end; ++ci) {
+                        const float *wf = depthwise ? w + co * R * S : w + (co * C_in + ci) * R * S;
+                        for (int64_t r = 0; r < R; ++r) {
+                            const int64_t hd = i * stride + r * dil - pad;
+                            if (hd < 0 || hd >= H) continue;
+                            for (int64_t s = 0; s < S; ++s) {
+                                const int64_t vd = j * stride + s * dil - pad;
+                                if (vd < 0 || vd >= W) continue;
+                                const double t = (double)x[((n * C_in + ci) * H + hd) * W + vd] * (double)wf[r * S + s];
+                                acc += t;
+                                mag += fabs(t);
+                            }
+                        }
+                    }
+                    const int64_t o = ((n * C_out + co) * Ho + i) * Wo + j;
+                    y[o] = acc;
+                    if (d) d[o] = mag;
+                }
             }
         }
     }

@@ -10,6 +10,7 @@ import pytest
 import test_oracle_pins as pins
 import test_oracle_pool2d_pins as pool_pins
 import test_oracle_bias_relu_pins as br_pins
+import test_oracle_dilated_pins as dil_pins
 import test_oracle_requant_pins as rq_pins
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -46,6 +47,12 @@ MUTANTS = [
     ("requantisation: scale of the neighbouring channel", "const float sc = scale[co];", "const float sc = scale[(co + 1) % C_out];", 0),
     ("requantisation: upper clamp at 128 wraps", "if (r > 127.0f) r = 127.0f;", "if (r > 128.0f) r = 128.0f;", 0),
     ("int8 overflow never reported", "return overflow ? 2 : 0;", "return 0;", 0),
+    ("dilation ignored on columns", "const int64_t vd = j * stride + s * dil - pad;", "const int64_t vd = j * stride + s - pad;", 0),
+    ("dilation multiplies the stride", "const int64_t hd = i * stride + r * dil - pad;", "const int64_t hd = (i * stride + r) * dil - pad;", 0),
+    ("dilated extent taken from the undilated filter", "return oracle_out_dim(in, dil * (k - 1) + 1, stride, pad);", "return oracle_out_dim(in, k, stride, pad);", 0),
+    ("dilated span one tap too long", "return oracle_out_dim(in, dil * (k - 1) + 1, stride, pad);", "return oracle_out_dim(in, dil * k, stride, pad);", 0),
+    ("dilated depthwise reads every channel", "const int64_t ci_first = depthwise ? co : 0, ci_end = depthwise ? co + 1 : C_in;", "const int64_t ci_first = 0, ci_end = C_in;", 0),
+    ("dilated depthwise takes the first filter", "const float *wf = depthwise ? w + co * R * S : w + (co * C_in + ci) * R * S;", "const float *wf = depthwise ? w : w + (co * C_in + ci) * R * S;", 0),
     ("bias of the neighbouring channel", "const double b = bias ? (double)bias[co] : 0.0;", "const double b = bias ? (double)bias[(co + 1) % C_out] : 0.0;", 0),
     ("bias subtracted", "double t = y[o] + b;", "double t = y[o] - b;", 0),
     ("rectifier before the bias", "double t = y[o] + b;\n                if (relu && t < 0.0) t = 0.0;", "double t = y[o];\n                if (relu && t < 0.0) t = 0.0;\n                t += b;", 0),
@@ -105,6 +112,9 @@ def _battery(o):
     rq_pins.test_identity_monotonicity_and_overflow(o)
     pool_pins.test_special_cases_reduce_to_the_other_entry_points(o)
     br_pins.test_hand_worked_example(o)
+    dil_pins.test_hand_worked_example(o)
+    for case in dil_pins.CASES:
+        dil_pins.test_dilated_equals_plain_convolution_with_a_zero_stuffed_filter(o, case)
     br_pins.test_no_bias_and_no_rectifier_is_the_plain_convolution(o)
 
 

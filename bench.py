@@ -239,7 +239,8 @@ def filter_size_sweep(torch, sw):
 def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, stride, pad, C_out):
     """One multi-channel layer of the table below (fp32 or int8), checked on one image against the oracle."""
     N, C, H, W = shape
-    Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
+    dil = 2 if kind == "conv_dil" else 1            # the dilated row: taps two positions apart
+    Ho, Wo = (H + 2 * pad - dil * (R - 1) - 1) // stride + 1, (W + 2 * pad - dil * (R - 1) - 1) // stride + 1
     s8 = kind in ("conv_s8", "conv_s8_rq")
     rq = kind == "conv_s8_rq"
     br = kind == "conv_br"
@@ -258,6 +259,8 @@ def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, st
         x = inputs.normal_f32(shape, inputs.seed_for(7, idx))
         w = inputs.normal_f32((C_out, C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
         call, odt, esz = sw.sw_conv2d, torch.float32, 4
+        if dil > 1:
+            call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_dilated(a, b, st_, p_, dil, out=out)
         if br:      # bias and rectifier fused into the store
             bias = inputs.normal_f32((C_out,), inputs.seed_for(7, 200 + idx), 0.5)
             bd = torch.from_numpy(bias).cuda()
@@ -271,7 +274,12 @@ def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, st
         assert np.array_equal(y, oracle.conv2d_s8(x[:1], w, stride, pad)), name
         err = 0.0
     else:
-        y_ref, d = oracle.conv2d_bias_relu(x[:1], w, bias, stride, pad, True) if br else oracle.conv2d(x[:1], w, stride, pad)
+        if br:
+            y_ref, d = oracle.conv2d_bias_relu(x[:1], w, bias, stride, pad, True)
+        elif dil > 1:
+            y_ref, d = oracle.conv2d_dilated(x[:1], w, stride, pad, dil)
+        else:
+            y_ref, d = oracle.conv2d(x[:1], w, stride, pad)
         err = float(np.max(np.abs(y - y_ref) / d))
         assert err <= 2e-5, (name, err)
     nbytes = x.nbytes + w.nbytes + N * C_out * Ho * Wo * (1 if rq else 4)
@@ -313,6 +321,7 @@ def strided_and_pooling_table(torch, sw):
         ("conv_3x3_64to64", "conv", (32, 64, 56, 56), 3, 1, 1, 64),
         ("conv_3x3_64to64_bias_relu", "conv_br", (32, 64, 56, 56), 3, 1, 1, 64),
         ("conv_3x3_14x14_256_bias_relu", "conv_br", (32, 256, 14, 14), 3, 1, 1, 256),
+        ("conv_3x3_dilation2_64to64", "conv_dil", (32, 64, 56, 56), 3, 1, 2, 64),
         ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
         ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
         ("conv_s8_requant_3x3_128to128", "conv_s8_rq", (32, 128, 28, 28), 3, 1, 1, 128),
@@ -320,7 +329,7 @@ def strided_and_pooling_table(torch, sw):
     rows = []
     for idx, (name, kind, shape, R, stride, pad, *more) in enumerate(layers):
         N, C, H, W = shape
-        if kind in ("conv", "conv_br", "conv_s8", "conv_s8_rq"):
+        if kind in ("conv", "conv_br", "conv_dil", "conv_s8", "conv_s8_rq"):
             rows.append(_conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, stride, pad, more[0]))
             continue
         Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1

@@ -173,6 +173,24 @@ int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, 
                          int stride, int pad, int relu, void* hip_stream);
 
 /*
+ * Dilated (a trous) variants of sw_conv2d and sw_conv2d_depthwise (paper, figure 2
+ * names dilated variants among the 2-D kernels): neighbouring taps are `dilation`
+ * input positions apart,
+ *     y[n,co,i,j] = sum_{ci,r,s} w[co,ci,r,s] * xz[n,ci,i*stride+r*dilation-pad, j*stride+s*dilation-pad]
+ * so the filter spans dilation*(R-1)+1 rows and H_out = sw_out_dim(H, dilation*(R-1)+1, stride, pad)
+ * (columns alike).  dilation >= 1 (else SW_ERR_SHAPE); dilation == 1 is the undilated call.
+ * Other arguments, layouts and errors as the undilated calls.  With C_in >= 2 the
+ * matrix-core kernel runs (the window in LDS grows, the taps step through it
+ * `dilation` apart); depthwise and C_in == 1 run one thread per output.
+ */
+int sw_conv2d_dilated(const float* x, const float* w, float* y,
+                      int N, int C_in, int C_out, int H, int W, int R, int S,
+                      int stride, int pad, int dilation, void* hip_stream);
+int sw_conv2d_depthwise_dilated(const float* x, const float* w, float* y,
+                                int N, int C, int H, int W, int R, int S,
+                                int stride, int pad, int dilation, void* hip_stream);
+
+/*
  * Depthwise 2-D convolution through a kernel generated at run time (paper, section 2:
  * custom kernels generated at run time for every filter size).  Arguments, layouts,
  * result and errors as sw_conv2d_depthwise.  For stride 1, an output plane of at

@@ -75,10 +75,10 @@ __global__ __launch_bounds__(kThreads) void direct_conv2d_kernel(const TI* __res
             const TI* xp = x + ((int64_t)n * s.C_in + ci) * s.H * s.W;
             const TI* wp = w + ((int64_t)co * (DW ? 1 : s.C_in) + (DW ? 0 : ci)) * s.R * s.S;
             for (int r = 0; r < s.R; ++r) {
-                const int h = h0 + r;
+                const int h = h0 + r * s.dil;
                 if (h < 0 || h >= s.H) continue;
                 for (int q = 0; q < s.S; ++q) {
-                    const int v = v0 + q;
+                    const int v = v0 + q * s.dil;
                     if (v < 0 || v >= s.W) continue;
                     acc += (TA)xp[h * s.W + v] * (TA)wp[r * s.S + q];
                 }

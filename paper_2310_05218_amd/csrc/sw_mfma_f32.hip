@@ -357,7 +357,7 @@ hipError_t launch(const float* x, const float* w, float* y, const Conv2dShape& s
 
 bool mfma_f32_supported(const Conv2dShape& s)
 {
-    if (s.stride != 1 || s.C_in % kCK != 0 || s.C_out % 64 != 0) return false;
+    if (s.stride != 1 || s.dil != 1 || s.C_in % kCK != 0 || s.C_out % 64 != 0) return false;
     if (!((s.R == 3 && s.S == 3) || (s.R == 5 && s.S == 5))) return false;
     if ((int64_t)s.C_in * s.H * s.W > 2147483647LL) return false;
     const Tiling t = pick_tiling(s);

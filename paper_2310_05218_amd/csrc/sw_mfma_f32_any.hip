@@ -32,7 +32,7 @@ constexpr int kWS = 6;                 // ... and filters (16-byte groups)
 struct AnyParams {
     Epilogue ep;                       // bias and rectifier applied in the store
     int C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
-    int TH, TW, IH, IW, tiles_x, wpitch;
+    int TH, TW, IH, IW, tiles_x, wpitch, dil;
     FastDiv by_tiles_x, by_TW, by_IW, by_win, by_span, by_span4;
 };
 
@@ -93,8 +93,8 @@ __global__ __launch_bounds__(256) void mfma_f32_any_kernel(const float* __restri
                 acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b, acc0, 0, 0, 0);
                 acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b, acc1, 0, 0, 0);
             }
-            ++toff;
-            if (++s == P.S) { s = 0; toff += P.IW - P.S; }
+            toff += P.dil;                                   // next tap column, P.dil input positions on
+            if (++s == P.S) { s = 0; toff += P.dil * (P.IW - P.S); }
         }
     };
 
@@ -217,8 +217,8 @@ AnyPlan plan_any(const Conv2dShape& s, const float* w)
     a.CK = 32;
     while (a.CK > 2 && (a.CK * RS > 96 || a.CK >= 2 * s.C_in)) a.CK /= 2;
     auto bytes = [&]() {
-        a.IH = (a.TH - 1) * s.stride + s.R;
-        a.IW = (a.TW - 1) * s.stride + s.S;
+        a.IH = (a.TH - 1) * s.stride + (s.R - 1) * s.dil + 1;
+        a.IW = (a.TW - 1) * s.stride + (s.S - 1) * s.dil + 1;
         const int span = a.CK * RS;
         a.wpitch = span | 1;     // odd: the 32 rows an operand read touches fall into 32 banks
         return ((((size_t)a.CK * a.IH * a.IW + 3) & ~(size_t)3) + (size_t)64 * a.wpitch) * sizeof(float);
@@ -272,7 +272,7 @@ hipError_t launch_any(const float* x, const float* w, float* y, const Conv2dShap
     P.ep = ep;
     P.C_in = s.C_in; P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.R = s.R; P.S = s.S; P.stride = s.stride;
     P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo;
-    P.TH = a.TH; P.TW = a.TW; P.IH = a.IH; P.IW = a.IW; P.tiles_x = a.tiles_x; P.wpitch = a.wpitch;
+    P.TH = a.TH; P.TW = a.TW; P.IH = a.IH; P.IW = a.IW; P.tiles_x = a.tiles_x; P.wpitch = a.wpitch; P.dil = s.dil;
     P.by_tiles_x = make_fastdiv(a.tiles_x);
     P.by_TW = make_fastdiv(a.TW);
     P.by_IW = make_fastdiv(a.IW);

@@ -237,7 +237,7 @@ hipError_t launch_quad(const float* x, const float* w, float* y, const Conv2dSha
 }  // namespace
 
 // (with fewer than five input channels most of an eight-channel group would be zero padding)
-bool mfma_f32_quad_supported(const Conv2dShape& s) { return s.C_in >= 5 && plan_quad(s).ok; }
+bool mfma_f32_quad_supported(const Conv2dShape& s) { return s.dil == 1 && s.C_in >= 5 && plan_quad(s).ok; }
 
 hipError_t launch_mfma_f32_quad(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
                                 const Epilogue& ep)

@@ -100,12 +100,16 @@ int run_plane(const float* x, const float* w, float* y, int64_t planes, int plan
 // Shared validation of the 2-D calls.  esz_in / esz_out are element sizes in bytes.
 int check_conv2d(const void* x, const void* w, const void* y, int N, int C_in, int C_out, int H, int W,
                  int R, int S, int stride, int pad, bool depthwise, size_t esz_in, size_t esz_out,
-                 Conv2dShape* out)
+                 Conv2dShape* out, int dil = 1)
 {
     if (!x || !w || !y) return SW_ERR_NULL;
-    if (N <= 0 || C_in <= 0 || C_out <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0)
+    if (N <= 0 || C_in <= 0 || C_out <= 0 || H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0 ||
+        dil <= 0)
         return SW_ERR_SHAPE;
-    const int64_t Ho = sw_out_dim(H, R, stride, pad), Wo = sw_out_dim(W, S, stride, pad);
+    // a dilated filter spans dil * (k - 1) + 1 input positions
+    const int64_t span_r = (int64_t)dil * (R - 1) + 1, span_s = (int64_t)dil * (S - 1) + 1;
+    if (span_r > kMaxElems || span_s > kMaxElems) return SW_ERR_SHAPE;
+    const int64_t Ho = sw_out_dim(H, (int)span_r, stride, pad), Wo = sw_out_dim(W, (int)span_s, stride, pad);
     if (Ho <= 0 || Wo <= 0) return SW_ERR_SHAPE;
     const int64_t nx = (int64_t)N * C_in * H * W;
     const int64_t nw = (int64_t)C_out * (depthwise ? 1 : C_in) * R * S;
@@ -118,7 +122,7 @@ int check_conv2d(const void* x, const void* w, const void* y, int N, int C_in, i
     if (overlaps(y, ny * (int64_t)esz_out, x, nx * (int64_t)esz_in) ||
         overlaps(y, ny * (int64_t)esz_out, w, nw * (int64_t)esz_in))
         return SW_ERR_ALIAS;
-    *out = Conv2dShape{N, C_in, C_out, H, W, R, S, stride, pad, (int)Ho, (int)Wo};
+    *out = Conv2dShape{N, C_in, C_out, H, W, R, S, stride, pad, (int)Ho, (int)Wo, dil};
     return SW_OK;
 }
 
@@ -217,8 +221,9 @@ int sw_pool2d(const float* x, float* y, int N, int C, int H, int W, int R, int S
 static int run_conv2d(const float* x, const float* w, float* y, const Conv2dShape& s, const Epilogue& ep, hipStream_t st)
 {
     const bool plain = !ep.bias && !ep.relu;
-    if (s.C_in == 1 && plain) return run_plane(x, w, y, (int64_t)s.N * s.C_out, s.C_out, s.C_out, s, false, st);
-    // (one input channel with an epilogue: the one-filter-per-plane kernels have none, one thread per output has)
+    if (s.C_in == 1 && plain && s.dil == 1) return run_plane(x, w, y, (int64_t)s.N * s.C_out, s.C_out, s.C_out, s, false, st);
+    // (one input channel with an epilogue or a dilation: the one-filter-per-plane kernels have neither, one thread
+    // per output has)
     if (!force_direct() && s.C_in > 1) {
         // The fixed 3x3 / 5x5 kernel holds a CU with one large tile: it needs enough of them to fill the chip
         // (28 x 28 images and below at batch 32 leave it at 128 or fewer); the any-shape kernel's 128-pixel
@@ -251,6 +256,26 @@ int sw_conv2d_bias_relu(const float* x, const float* w, const float* bias, float
     if (bias && misaligned(bias, 4)) return SW_ERR_ALIGN;
     if (bias && overlaps(y, (int64_t)N * C_out * s.Ho * s.Wo * 4, bias, (int64_t)C_out * 4)) return SW_ERR_ALIAS;
     return run_conv2d(x, w, y, s, Epilogue{bias, relu != 0}, static_cast<hipStream_t>(hip_stream));
+}
+
+int sw_conv2d_dilated(const float* x, const float* w, float* y, int N, int C_in, int C_out, int H, int W, int R,
+                      int S, int stride, int pad, int dilation, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, 4, 4, &s, dilation);
+    if (rc != SW_OK) return rc;
+    return run_conv2d(x, w, y, s, Epilogue{nullptr, 0}, static_cast<hipStream_t>(hip_stream));
+}
+
+int sw_conv2d_depthwise_dilated(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,
+                                int stride, int pad, int dilation, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s, dilation);
+    if (rc != SW_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (dilation == 1) return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
+    return launch_status(launch_direct_conv2d_f32(x, w, y, s, true, st));
 }
 
 int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,

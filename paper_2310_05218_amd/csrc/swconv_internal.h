@@ -22,6 +22,7 @@ __device__ __forceinline__ int fast_div(int n, FastDiv f) { return f.magic ? (in
 
 struct Conv2dShape {
     int N, C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
+    int dil = 1;      // input positions between neighbouring taps (only the any-shape fp32 and direct kernels take > 1)
 };
 
 // Per-channel bias and rectifier on an fp32 sum on its way out: y = relu ? max(acc + bias[co], 0) : acc + bias[co]

@@ -149,6 +149,21 @@ def test_depthwise_argument_errors(L):
     assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
 
 
+def test_dilated_argument_errors(L):
+    f, g = L.sw_conv2d_dilated, L.sw_conv2d_depthwise_dilated
+    ok = (2, 16, 64, 12, 12, 3, 3, 1, 2, 2)
+    okd = (2, 16, 12, 12, 3, 3, 1, 2, 2)
+    assert f(None, W_, Y, *ok, None) == B.SW_ERR_NULL and g(X, None, Y, *okd, None) == B.SW_ERR_NULL
+    for bad_dil in (0, -1):
+        assert f(X, W_, Y, *ok[:-1], bad_dil, None) == B.SW_ERR_SHAPE
+        assert g(X, W_, Y, *okd[:-1], bad_dil, None) == B.SW_ERR_SHAPE
+    # span 6 * 2 + 1 = 13 > 12: the dilated filter does not fit the unpadded plane
+    assert f(X, W_, Y, 2, 16, 64, 12, 12, 7, 7, 1, 0, 2, None) == B.SW_ERR_SHAPE
+    assert g(X, W_, Y, 2, 16, 12, 12, 7, 7, 1, 0, 2, None) == B.SW_ERR_SHAPE
+    assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
+    assert g(X + 2, W_, Y, *okd, None) == B.SW_ERR_ALIGN
+
+
 def test_bias_relu_argument_errors(L):
     f = L.sw_conv2d_bias_relu
     B_ = 0x2100000

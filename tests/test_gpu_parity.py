@@ -366,6 +366,53 @@ CONV2D_CASES = [
 ]
 
 
+DILATED_CASES = [
+    # N, C_in, C_out, H, W, R, S, stride, pad, dilation
+    (2, 16, 64, 28, 28, 3, 3, 1, 2, 2),      # "same" 3x3 at dilation 2: matrix-core kernel, window grows by 2
+    (1, 32, 70, 33, 31, 3, 3, 1, 4, 4),      # dilation 4 (segmentation heads), ragged channel block
+    (2, 8, 16, 40, 40, 3, 3, 2, 3, 3),       # with stride 2
+    (1, 3, 5, 25, 27, 5, 2, 1, 3, 2),        # rectangular filter
+    (1, 6, 64, 64, 64, 3, 3, 1, 12, 12),     # dilation 12: window 25 rows taller than the tile
+    (1, 4, 8, 20, 20, 7, 7, 1, 9, 3),        # 49 taps, span 19
+    (2, 5, 9, 12, 12, 1, 1, 1, 0, 5),        # one tap: dilation changes nothing
+    (1, 2, 3, 9, 9, 3, 3, 1, 0, 4),          # span 9 = the plane: a single output
+    (2, 1, 6, 20, 22, 3, 3, 1, 2, 2),        # one input channel: one thread per output
+]
+
+
+@pytest.mark.parametrize("case", DILATED_CASES)
+def test_conv2d_dilated(torch, sw, oracle, case):
+    N, C_in, C_out, H, W, R, S, stride, pad, dil = case
+    x = inputs.normal_f32((N, C_in, H, W), 3201)
+    w = inputs.normal_f32((C_out, C_in, R, S), 3202, (2.0 / (C_in * R * S)) ** 0.5)
+    y_ref, d = oracle.conv2d_dilated(x, w, stride, pad, dil)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_dilated(dev(torch, x), dev(torch, w), stride, pad, dil, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"conv2d_dilated {case}")
+
+
+@pytest.mark.parametrize("case", [(2, 7, 30, 28, 3, 3, 1, 2, 2), (1, 5, 21, 40, 5, 3, 2, 4, 3), (3, 4, 14, 14, 3, 3, 1, 0, 6),
+                                  (1, 6, 56, 56, 3, 3, 1, 1, 1)])
+def test_conv2d_depthwise_dilated(torch, sw, oracle, case):
+    N, C, H, W, R, S, stride, pad, dil = case
+    x = inputs.normal_f32((N, C, H, W), 3211)
+    w = inputs.normal_f32((C, 1, R, S), 3212)
+    y_ref, d = oracle.conv2d_dilated(x, w, stride, pad, dil, depthwise=True)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_depthwise_dilated(dev(torch, x), dev(torch, w), stride, pad, dil, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"depthwise_dilated {case}")
+
+
+def test_dilation_one_is_the_undilated_call(torch, sw):
+    x = dev(torch, inputs.normal_f32((2, 16, 28, 28), 3221))
+    w = dev(torch, inputs.normal_f32((64, 16, 3, 3), 3222, 0.1))
+    assert torch.equal(sw.sw_conv2d_dilated(x, w, 1, 1, 1), sw.sw_conv2d(x, w, 1, 1))
+
+
 BIAS_RELU_CASES = [
     # N, C_in, C_out, H, W, R, S, stride, pad
     (8, 16, 256, 56, 56, 3, 3, 1, 1),    # enough large tiles for the fixed 3x3 matrix-core kernel (256 workgroups)

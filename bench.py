@@ -310,6 +310,8 @@ def strided_and_pooling_table(torch, sw):
         ("avgpool_3x3_s1", "avg", (32, 64, 56, 56), 3, 1, 1),
         ("depthwise_3x3_s2", "dw", (32, 128, 112, 112), 3, 2, 1),
         ("depthwise_5x5_s2", "dw", (32, 128, 112, 112), 5, 2, 2),
+        ("depthwise_3x3_bf16", "dw_bf16", (32, 256, 56, 56), 3, 1, 1),
+        ("depthwise_7x7_bf16", "dw_bf16", (32, 256, 56, 56), 7, 1, 3),
         ("global_avgpool_7x7", "avg", (32, 2048, 7, 7), 7, 1, 0),
         ("depthwise_3x3_28x28", "dw", (32, 256, 28, 28), 3, 1, 1),
         ("depthwise_3x3_14x14", "dw", (32, 512, 14, 14), 3, 1, 1),
@@ -339,7 +341,23 @@ def strided_and_pooling_table(torch, sw):
         xs = torch.from_numpy(x).cuda()
         sets = [{"x": xs if i == 0 else xs.clone(), "y": torch.empty((N, C, Ho, Wo), device="cuda")}
                 for i in range(nsets)]
-        if kind == "dw":
+        if kind == "dw_bf16":       # bf16 planes, fp32 filter and accumulation: half the bytes of the fp32 layer
+            xb = inputs.to_bf16_bits(x)
+            xs = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
+            in_bytes, out_bytes = xb.nbytes, N * C * Ho * Wo * 2
+            nsets = min(32, max(3, -(-COLD_ROTATION_BYTES // (in_bytes + out_bytes))))
+            sets = [{"x": xs if i == 0 else xs.clone(),
+                     "y": torch.empty((N, C, Ho, Wo), dtype=torch.bfloat16, device="cuda")} for i in range(nsets)]
+            w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R)
+            wd = torch.from_numpy(w).cuda()
+            fn = lambda s_: sw.sw_conv2d_depthwise_bf16(s_["x"], wd, stride, pad, out=s_["y"])
+            yb = sw.sw_conv2d_depthwise_bf16(xs[:1, :2].contiguous(), wd[:2].contiguous(), stride, pad)
+            y = inputs.bf16_bits_to_f32(yb.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+            y_ref, d = oracle.conv2d_depthwise(inputs.bf16_bits_to_f32(xb[:1, :2]), w[:2], stride, pad)
+            # fp32 parity bound plus half a bf16 unit of the exact sum, normalised to the usual 2e-5
+            err = float(np.max(np.abs(y - y_ref) / (d + 2.0 ** -8 * np.abs(y_ref) / 2e-5 + 1e-30)))
+            ops, extra = 2.0 * R * R * N * C * Ho * Wo, w.nbytes
+        elif kind == "dw":
             w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R)
             wd = torch.from_numpy(w).cuda()
             fn = lambda s_: sw.sw_conv2d_depthwise(s_["x"], wd, stride, pad, out=s_["y"])

@@ -173,6 +173,23 @@ int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, 
                          int stride, int pad, int relu, void* hip_stream);
 
 /*
+ * Depthwise 2-D convolution on bf16 activations with fp32 accumulation (paper,
+ * section 1.1: reduced-precision inference; the sliding kernels are bound by the
+ * bytes of the planes, which this halves).  x and y hold bf16 bit patterns (the
+ * upper 16 bits of an IEEE fp32); the filter stays fp32.  Every product and sum
+ * is fp32, exactly as in sw_conv2d_depthwise on the widened input; the finished
+ * sum is rounded to bf16 once (nearest, ties to even; NaN stays NaN).
+ * x: [N,C,H,W] bf16;  w: [C,1,R,S] fp32;  y: [N,C,H_out,W_out] bf16.
+ * x and y must be 2-byte aligned, w 4-byte aligned; errors as sw_conv2d_depthwise.
+ * 3x3, 5x5, 7x7 at stride 1 on planes up to 56 x 56 with W and W_out multiples of
+ * 8 and 16-byte aligned x, y run the sliding whole-plane kernel; every other
+ * valid shape one thread per output.
+ */
+int sw_conv2d_depthwise_bf16(const uint16_t* x, const float* w, uint16_t* y,
+                             int N, int C, int H, int W, int R, int S,
+                             int stride, int pad, void* hip_stream);
+
+/*
  * Dilated (a trous) variants of sw_conv2d and sw_conv2d_depthwise (paper, figure 2
  * names dilated variants among the 2-D kernels): neighbouring taps are `dilation`
  * input positions apart,

@@ -18,7 +18,7 @@ SW_POOL_AVG, SW_POOL_MAX = 0, 1
 
 EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
            "sw_conv2d_s8_requant", "sw_conv2d_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
-           "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
+           "sw_conv2d_depthwise_bf16", "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
            "sw_jit_cached_kernels",
            "sw_out_dim", "sw_workspace_bytes", "sw_status_string", "sw_version")
 
@@ -56,6 +56,8 @@ def lib() -> ctypes.CDLL:
     L.sw_conv2d_depthwise_dilated.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.sw_conv2d_depthwise.restype = i32
     L.sw_conv2d_depthwise.argtypes = [vp, vp, vp] + [i32] * 8 + [vp]
+    L.sw_conv2d_depthwise_bf16.restype = i32
+    L.sw_conv2d_depthwise_bf16.argtypes = [vp, vp, vp] + [i32] * 8 + [vp]
     L.sw_conv2d_depthwise_jit.restype = i32
     L.sw_conv2d_depthwise_jit.argtypes = [vp, vp, vp] + [i32] * 8 + [vp]
     for name in ("sw_jit_prepare_depthwise", "sw_jit_compile_check"):
@@ -277,6 +279,24 @@ def sw_conv2d_depthwise(x, w, stride: int = 1, pad: int = 0, out=None, stream=No
                                    _dev(out, torch.float32, 4, "y"), N, C, H, W, R, S, stride, pad,
                                    _stream(stream))
     _check(rc, "sw_conv2d_depthwise")
+    return out
+
+
+def sw_conv2d_depthwise_bf16(x, w, stride: int = 1, pad: int = 0, out=None, stream=None):
+    """x [N,C,H,W] bfloat16, w [C,1,R,S] fp32 -> y [N,C,H_out,W_out] bfloat16 (fp32 accumulation, one rounding)."""
+    import torch
+
+    N, C, H, W = x.shape
+    Cw, one, R, S = w.shape
+    if Cw != C or one != 1:
+        raise ValueError("depthwise weights must be [C,1,R,S]")
+    if out is None:
+        out = torch.empty(_out_shape("sw_conv2d_depthwise_bf16", N, C, sw_out_dim(H, R, stride, pad),
+                                     sw_out_dim(W, S, stride, pad)), dtype=torch.bfloat16, device=x.device)
+    rc = lib().sw_conv2d_depthwise_bf16(_dev(x, torch.bfloat16, 4, "x"), _dev(w, torch.float32, 4, "w"),
+                                        _dev(out, torch.bfloat16, 4, "y"), N, C, H, W, R, S, stride, pad,
+                                        _stream(stream))
+    _check(rc, "sw_conv2d_depthwise_bf16")
     return out
 
 

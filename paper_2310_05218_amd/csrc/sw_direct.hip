@@ -90,6 +90,39 @@ __global__ __launch_bounds__(kThreads) void direct_conv2d_kernel(const TI* __res
     }
 }
 
+// Depthwise convolution on bf16 planes, one thread per output: bf16 in, fp32 products and sums, bf16 out
+// (nearest, ties to even).
+__global__ __launch_bounds__(kThreads) void direct_depthwise_bf16_kernel(const unsigned short* __restrict__ x,
+                                                                         const float* __restrict__ w,
+                                                                         unsigned short* __restrict__ y, Conv2dShape s)
+{
+    const int64_t plane_o = (int64_t)s.Ho * s.Wo;
+    const int64_t total = (int64_t)s.N * s.C_out * plane_o;
+    for (int64_t o = (int64_t)blockIdx.x * kThreads + threadIdx.x; o < total; o += (int64_t)gridDim.x * kThreads) {
+        const int64_t nc = o / plane_o;
+        const int pix = (int)(o - nc * plane_o);
+        const int c = (int)(nc % s.C_out);
+        const int i = pix / s.Wo, j = pix - i * s.Wo;
+        const int h0 = i * s.stride - s.pad, v0 = j * s.stride - s.pad;
+        const unsigned short* xp = x + nc * s.H * s.W;
+        const float* wp = w + (int64_t)c * s.R * s.S;
+        float acc = 0.f;
+        for (int r = 0; r < s.R; ++r) {
+            const int h = h0 + r;
+            if (h < 0 || h >= s.H) continue;
+            for (int q = 0; q < s.S; ++q) {
+                const int v = v0 + q;
+                if (v < 0 || v >= s.W) continue;
+                acc = fmaf(__uint_as_float((unsigned)xp[h * s.W + v] << 16), wp[r * s.S + q], acc);
+            }
+        }
+        const unsigned u = __float_as_uint(acc);
+        unsigned b = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+        if ((u & 0x7FFFFFFFu) > 0x7F800000u) b = (u >> 16) | 0x40u;
+        y[o] = (unsigned short)b;
+    }
+}
+
 // 2-D pooling, one thread per output: the average sums the zero-padded window and scales by 1/(R*S),
 // the maximum runs over the window positions inside the plane.
 template <bool MAXIMUM>
@@ -234,6 +267,14 @@ hipError_t launch_direct_pool2d(const float* x, float* y, int64_t planes, int H,
     else
         hipLaunchKernelGGL(direct_pool2d_kernel<false>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
                            stride, pad, Ho, Wo);
+    return hipGetLastError();
+}
+
+hipError_t launch_direct_depthwise_bf16(const unsigned short* x, const float* w, unsigned short* y,
+                                        const Conv2dShape& s, hipStream_t st)
+{
+    const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
+    hipLaunchKernelGGL(direct_depthwise_bf16_kernel, dim3(grid), dim3(kThreads), 0, st, x, w, y, s);
     return hipGetLastError();
 }
 

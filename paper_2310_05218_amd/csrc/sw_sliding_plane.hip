@@ -377,6 +377,135 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
     }
 }
 
+
+// ---- bf16 activations, fp32 accumulation ----
+// The whole-plane kernel with 16-bit planes in memory: a lane moves 16-byte groups of eight bf16 values, widens
+// them to fp32 on their way into LDS (a bf16 is the upper half of an fp32: a shift) and rounds the finished fp32
+// sums to bf16 (nearest, ties to even) on their way out.  Everything between is the fp32 kernel: the same window
+// in LDS, the same 7 x 7 accumulation.  Half the HBM bytes per plane.
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+
+// Two fp32 values -> two bf16 (nearest, ties to even; a in the low half): the conversion instruction of gfx950.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned pack_bf16_rne(float a, float b)
+{
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(floatx2{a, b}, bf16x2));
+}
+
+// SQ: the plane and its output are exactly 56 x 56 (every slot is then unconditional, as in the fp32 kernel: the
+// last slot is moved back to the plane's last 64 groups).
+template <int R, int S, bool SQ>
+__global__ __launch_bounds__(64) void sliding_plane_bf16_kernel(const unsigned short* __restrict__ x,
+                                                                const float* __restrict__ w,
+                                                                unsigned short* __restrict__ y, int planes,
+                                                                int n_filters, int H_rt, int W_rt, int pad, int Ho_rt,
+                                                                int Wo_rt)
+{
+    const int H = SQ ? kTile : H_rt, W = SQ ? kTile : W_rt, Ho = SQ ? kTile : Ho_rt, Wo = SQ ? kTile : Wo_rt;
+    constexpr int P = in_pitch(S);
+    constexpr int ROWS = in_rows(R);
+    constexpr int NSLOT = (kTile * kTile / 8 + 63) / 64;      // 7 groups of eight per lane at most
+    __shared__ __attribute__((aligned(16))) float lds[ROWS * P];
+
+    const int lane = threadIdx.x;
+    const int pad_up = (pad + 3) & ~3;
+    const int shift = pad_up - pad;
+    const int W8 = W >> 3, Wo8 = Wo >> 3;
+    const int n_in8 = H * W8, n_out8 = Ho * Wo8;
+    const int nin_full = n_in8 >> 6, nin_rem = n_in8 & 63;
+    const int nout_full = n_out8 >> 6, nout_rem = n_out8 & 63;
+    auto group = [&](int k) { return SQ && k == NSLOT - 1 ? kTile * kTile / 8 - 64 + lane : lane + 64 * k; };
+    auto in_live = [&](int k) { return SQ || k < nin_full || (k == nin_full && lane < nin_rem); };
+    auto out_live = [&](int k) { return SQ || k < nout_full || (k == nout_full && lane < nout_rem); };
+    int in_slot[NSLOT], out_slot[NSLOT];
+#pragma unroll
+    for (int k = 0; k < NSLOT; ++k) {
+        const int f = group(k);
+        const int ri = f / W8, ro = f / Wo8;
+        in_slot[k] = (ri + pad) * P + pad_up + 8 * (f - ri * W8);
+        out_slot[k] = (ro + pad) * P + pad_up + 8 * (f - ro * Wo8);
+    }
+
+    int plane = blockIdx.x;
+    if (plane >= planes) return;
+
+    for (int i = lane; i < ROWS * P / 4; i += 64) reinterpret_cast<float4*>(lds)[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+
+    const int bx = lane & 7, by = lane >> 3;
+    const float* win = lds + (kB * by) * P + shift + kB * bx;
+    float* stage = lds + (kB * by + pad) * P + pad_up + kB * bx;
+
+    uintx4 pre[NSLOT];
+    auto fetch = [&](int pl) __attribute__((always_inline)) {
+        const uintx4* src = reinterpret_cast<const uintx4*>(x + (int64_t)pl * H * W);
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k)
+            if (in_live(k)) pre[k] = __builtin_nontemporal_load(src + group(k));
+    };
+    auto fill = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k)
+            if (in_live(k)) {
+                floatx4 lo, hi;
+                lo.x = __uint_as_float(pre[k].x << 16); lo.y = __uint_as_float(pre[k].x & 0xFFFF0000u);
+                lo.z = __uint_as_float(pre[k].y << 16); lo.w = __uint_as_float(pre[k].y & 0xFFFF0000u);
+                hi.x = __uint_as_float(pre[k].z << 16); hi.y = __uint_as_float(pre[k].z & 0xFFFF0000u);
+                hi.z = __uint_as_float(pre[k].w << 16); hi.w = __uint_as_float(pre[k].w & 0xFFFF0000u);
+                *reinterpret_cast<floatx4*>(lds + in_slot[k]) = lo;
+                *reinterpret_cast<floatx4*>(lds + in_slot[k] + 4) = hi;
+            }
+    };
+
+    fetch(plane);
+    fill();
+    int next = plane + gridDim.x;
+    if (next < planes) fetch(next);
+    wave_lds_sync();
+#pragma unroll 1
+    for (;;) {
+        const int left = (planes - 1 - plane) / (int)gridDim.x;
+        if (left >= 3) __builtin_amdgcn_s_setprio(3);
+        else if (left == 2) __builtin_amdgcn_s_setprio(2);
+        else if (left == 1) __builtin_amdgcn_s_setprio(1);
+        else __builtin_amdgcn_s_setprio(0);
+        float acc[kB][kB];
+#pragma unroll
+        for (int i = 0; i < kB; ++i)
+#pragma unroll
+            for (int j = 0; j < kB; ++j) acc[i][j] = 0.f;
+        accumulate_block<R, S, P>(win, w + (int64_t)(plane % n_filters) * R * S, acc);
+        wave_lds_sync();
+#pragma unroll
+        for (int i = 0; i < kB; ++i)
+#pragma unroll
+            for (int j = 0; j < kB; ++j)
+                if (SQ || (kB * by + i < Ho && kB * bx + j < Wo)) stage[i * P + j] = acc[i][j];
+        wave_lds_sync();
+        uintx4* dst = reinterpret_cast<uintx4*>(y + (int64_t)plane * Ho * Wo);
+#pragma unroll
+        for (int k = 0; k < NSLOT; ++k)
+            if (out_live(k)) {
+                const floatx4 lo = *reinterpret_cast<const floatx4*>(lds + out_slot[k]);
+                const floatx4 hi = *reinterpret_cast<const floatx4*>(lds + out_slot[k] + 4);
+                uintx4 v;
+                v.x = pack_bf16_rne(lo.x, lo.y);
+                v.y = pack_bf16_rne(lo.z, lo.w);
+                v.z = pack_bf16_rne(hi.x, hi.y);
+                v.w = pack_bf16_rne(hi.z, hi.w);
+                __builtin_nontemporal_store(v, dst + group(k));
+            }
+        wave_lds_sync();
+
+        if (next >= planes) break;
+        plane = next;
+        fill();
+        next = plane + gridDim.x;
+        if (next < planes) fetch(next);
+        wave_lds_sync();
+    }
+}
+
 }  // namespace
 
 bool sliding_plane_whole(const float* x, const float* y, int W, int R, int S, int pad, int Ho, int Wo);
@@ -443,6 +572,38 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
     else if (R <= kMaxRS && S <= kMaxRS) SW_PLANE(0, 0, kMaxRS);
     else SW_PLANE(0, 0, kMaxRSWide);
 #undef SW_PLANE
+    return hipGetLastError();
+}
+
+// bf16 planes: 3x3 / 5x5 / 7x7 at stride 1, planes that fit one 56 x 56 tile, rows that are whole 16-byte groups.
+bool sliding_plane_bf16_supported(const void* x, const void* y, int W, int R, int S, int stride, int pad, int Ho, int Wo)
+{
+    const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
+    const bool fixed = R == S && (R == 3 || R == 5 || R == 7);
+    return stride == 1 && fixed && aligned && Ho <= kTile && Wo <= kTile && 2 * pad <= R - 1 && W % 8 == 0 &&
+           Wo % 8 == 0;
+}
+
+hipError_t launch_sliding_plane_bf16(const unsigned short* x, const float* w, unsigned short* y, int64_t planes,
+                                     int n_filters, int H, int W, int R, int pad, int Ho, int Wo, hipStream_t st)
+{
+    if (planes > 2147483647LL) return hipErrorInvalidValue;
+    const int64_t want = 256 * 8;
+    dim3 grid((unsigned)(planes < want ? planes : want)), block(64);
+    const bool sq = H == kTile && W == kTile && Ho == kTile && Wo == kTile;
+#define SW_BF16(RC)                                                                                               \
+    do {                                                                                                          \
+        if (sq)                                                                                                   \
+            hipLaunchKernelGGL((sliding_plane_bf16_kernel<RC, RC, true>), grid, block, 0, st, x, w, y, (int)planes, \
+                               n_filters, H, W, pad, Ho, Wo);                                                     \
+        else                                                                                                      \
+            hipLaunchKernelGGL((sliding_plane_bf16_kernel<RC, RC, false>), grid, block, 0, st, x, w, y, (int)planes, \
+                               n_filters, H, W, pad, Ho, Wo);                                                     \
+    } while (0)
+    if (R == 3) SW_BF16(3);
+    else if (R == 5) SW_BF16(5);
+    else SW_BF16(7);
+#undef SW_BF16
     return hipGetLastError();
 }
 

@@ -288,6 +288,21 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, 
     return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
 }
 
+int sw_conv2d_depthwise_bf16(const uint16_t* x, const float* w, uint16_t* y, int N, int C, int H, int W, int R, int S,
+                             int stride, int pad, void* hip_stream)
+{
+    Conv2dShape s;
+    // (element sizes: activations 2 bytes; the filter is checked as fp32 below)
+    const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 2, 2, &s);
+    if (rc != SW_OK) return rc;
+    if (misaligned(w, 4)) return SW_ERR_ALIGN;
+    if (overlaps(y, (int64_t)N * C * s.Ho * s.Wo * 2, w, (int64_t)C * R * S * 4)) return SW_ERR_ALIAS;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (!force_direct() && sliding_plane_bf16_supported(x, y, W, R, S, stride, pad, s.Ho, s.Wo))
+        return launch_status(launch_sliding_plane_bf16(x, w, y, (int64_t)N * C, C, H, W, R, pad, s.Ho, s.Wo, st));
+    return launch_status(launch_direct_depthwise_bf16(x, w, y, s, st));
+}
+
 int sw_conv2d_depthwise_jit(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,
                             int stride, int pad, void* hip_stream)
 {

@@ -149,6 +149,20 @@ def test_depthwise_argument_errors(L):
     assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
 
 
+def test_bf16_argument_errors(L):
+    f = L.sw_conv2d_depthwise_bf16
+    ok = (2, 16, 8, 8, 3, 3, 1, 1)
+    assert f(None, W_, Y, *ok, None) == B.SW_ERR_NULL
+    for i in range(7):
+        bad = list(ok)
+        bad[i] = 0
+        assert f(X, W_, Y, *bad, None) == B.SW_ERR_SHAPE, i
+    assert f(X + 1, W_, Y, *ok, None) == B.SW_ERR_ALIGN        # bf16 planes: 2-byte aligned
+    assert f(X, W_ + 2, Y, *ok, None) == B.SW_ERR_ALIGN        # the fp32 filter: 4-byte aligned
+    assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
+    assert f(X, Y + 2 * 2 * 16 * 64 - 4, Y, *ok, None) == B.SW_ERR_ALIAS   # the filter's last bytes under y
+
+
 def test_dilated_argument_errors(L):
     f, g = L.sw_conv2d_dilated, L.sw_conv2d_depthwise_dilated
     ok = (2, 16, 64, 12, 12, 3, 3, 1, 2, 2)

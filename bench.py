@@ -59,14 +59,14 @@ SECOND_ROOF = {"depthwise_7x7": (VALU_F32_TFLOPS, "frac_alu_f32_plain_fma"),
 # profiles/hbm_traffic_all_kernels.txt), with the kernel source and its sha256 prefix at the time the
 # counters were taken.  A kernel whose source has changed since reports traffic = null.
 TRAFFIC = {
-    "conv2d_64x64_3x3": (62424836, "sw_mfma_f32.hip", "79cf8dd0d7c7fbdc"),
-    "depthwise_3x3": (207296878, "sw_sliding_plane.hip", "bbd3c61f82b1358d"),
-    "depthwise_7x7": (206216454, "sw_sliding_plane.hip", "bbd3c61f82b1358d"),
-    "conv2d_s8_128x128_3x3": (21145857, "sw_mfma_s8.hip", "e4d62c0d4706586a"),
-    "conv1d_k9": (33891531, "sw_sliding1d.hip", "eeb6f644a27cb890"),
-    "avgpool1d_w8": (34168735, "sw_sliding1d.hip", "eeb6f644a27cb890"),
-    "maxpool1d_w8": (34141220, "sw_sliding1d.hip", "eeb6f644a27cb890"),
-    "conv2d_1ch_3x3": (655814, "sw_sliding_rows.hip", "8a6fcf2dac8abc29"),
+    "depthwise_3x3": (207313084, "sw_sliding_plane.hip", "ad10d81c44e6a1fe"),
+    "depthwise_7x7": (206211026, "sw_sliding_plane.hip", "ad10d81c44e6a1fe"),
+    "conv2d_64x64_3x3": (62457581, "sw_mfma_f32.hip", "c33152360085e7c7"),
+    "conv2d_s8_128x128_3x3": (21145344, "sw_mfma_s8.hip", "878da741cf86fab2"),
+    "conv1d_k9": (33894139, "sw_sliding1d.hip", "eeb6f644a27cb890"),
+    "avgpool1d_w8": (34164929, "sw_sliding1d.hip", "eeb6f644a27cb890"),
+    "maxpool1d_w8": (34145765, "sw_sliding1d.hip", "eeb6f644a27cb890"),
+    "conv2d_1ch_3x3": (656583, "sw_sliding_rows.hip", "8a6fcf2dac8abc29"),
 }
 
 

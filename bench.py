@@ -310,6 +310,8 @@ def strided_and_pooling_table(torch, sw):
         ("avgpool_3x3_s1", "avg", (32, 64, 56, 56), 3, 1, 1),
         ("depthwise_3x3_s2", "dw", (32, 128, 112, 112), 3, 2, 1),
         ("depthwise_5x5_s2", "dw", (32, 128, 112, 112), 5, 2, 2),
+        ("depthwise_3x3_bias_relu", "dw_br", (32, 256, 56, 56), 3, 1, 1),
+        ("depthwise_3x3_s2_bias_relu", "dw_br", (32, 128, 112, 112), 3, 2, 1),
         ("depthwise_3x3_bf16", "dw_bf16", (32, 256, 56, 56), 3, 1, 1),
         ("depthwise_7x7_bf16", "dw_bf16", (32, 256, 56, 56), 7, 1, 3),
         ("global_avgpool_7x7", "avg", (32, 2048, 7, 7), 7, 1, 0),
@@ -356,6 +358,16 @@ def strided_and_pooling_table(torch, sw):
             y_ref, d = oracle.conv2d_depthwise(inputs.bf16_bits_to_f32(xb[:1, :2]), w[:2], stride, pad)
             # fp32 parity bound plus half a bf16 unit of the exact sum, normalised to the usual 2e-5
             err = float(np.max(np.abs(y - y_ref) / (d + 2.0 ** -8 * np.abs(y_ref) / 2e-5 + 1e-30)))
+            ops, extra = 2.0 * R * R * N * C * Ho * Wo, w.nbytes
+        elif kind == "dw_br":       # depthwise with bias and rectifier fused into the store
+            w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R)
+            bias = inputs.normal_f32((C,), inputs.seed_for(7, 200 + idx), 0.5)
+            wd, bd = torch.from_numpy(w).cuda(), torch.from_numpy(bias).cuda()
+            fn = lambda s_: sw.sw_conv2d_depthwise_bias_relu(s_["x"], wd, bd, stride, pad, True, out=s_["y"])
+            y = sw.sw_conv2d_depthwise_bias_relu(xs[:1, :2].contiguous(), wd[:2].contiguous(), bd[:2].contiguous(),
+                                                 stride, pad, True).cpu().numpy()
+            y_ref, d = oracle.conv2d_depthwise_bias_relu(x[:1, :2], w[:2], bias[:2], stride, pad, True)
+            err = float(np.max(np.abs(y - y_ref) / d))
             ops, extra = 2.0 * R * R * N * C * Ho * Wo, w.nbytes
         elif kind == "dw":
             w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R)

@@ -122,12 +122,15 @@ int sw_conv2d(const float* x, const float* w, float* y,
  *     y[n,co,i,j] = act(conv + bias[co]),  act(t) = relu ? max(t, 0) : t
  * bias: [C_out] fp32 device pointer or NULL (no bias); relu: 0 or non-zero.
  * One more fp32 addition than sw_conv2d.  Shapes, support and errors as
- * sw_conv2d; bias must be 4-byte aligned and must not overlap y.  With
- * C_in == 1 the epilogue runs in the one-thread-per-output kernel.
+ * sw_conv2d; bias must be 4-byte aligned and must not overlap y.
+ * sw_conv2d_depthwise_bias_relu: the same for sw_conv2d_depthwise (bias: [C]).
  */
 int sw_conv2d_bias_relu(const float* x, const float* w, const float* bias, float* y,
                         int N, int C_in, int C_out, int H, int W, int R, int S,
                         int stride, int pad, int relu, void* hip_stream);
+int sw_conv2d_depthwise_bias_relu(const float* x, const float* w, const float* bias, float* y,
+                                  int N, int C, int H, int W, int R, int S,
+                                  int stride, int pad, int relu, void* hip_stream);
 
 /*
  * Depthwise 2-D convolution: one R x S filter per channel (paper, section 1.2,

@@ -256,3 +256,19 @@ def conv2d_dilated(x, w, stride: int = 1, pad: int = 0, dilation: int = 1, depth
     if rc:
         raise ValueError(f"oracle_conv2d_dilated rejected the arguments (code {rc})")
     return y, d
+
+
+def conv2d_depthwise_bias_relu(x, w, bias, stride: int = 1, pad: int = 0, relu: bool = False):
+    """Depthwise convolution followed by a per-channel bias and an optional rectifier, in fp64 (the same
+    oracle_bias_relu step as conv2d_bias_relu).  Returns (y, D) with D = sum|x*w| + |bias[c]|."""
+    y, d = conv2d_depthwise(x, w, stride, pad)
+    N, C, Ho, Wo = y.shape
+    if bias is not None:
+        bias = _as(bias, np.float32, 1)
+        if bias.shape[0] != C:
+            raise ValueError("one bias per channel")
+    rc = _load().oracle_bias_relu(_p(y), _p(d), _p(bias) if bias is not None else None, N, C, Ho * Wo,
+                                  1 if relu else 0)
+    if rc:
+        raise ValueError(f"oracle_bias_relu rejected the arguments (code {rc})")
+    return y, d

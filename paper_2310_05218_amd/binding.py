@@ -17,7 +17,7 @@ SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN, SW_ERR_ALIAS, SW_ER
 SW_POOL_AVG, SW_POOL_MAX = 0, 1
 
 EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
-           "sw_conv2d_s8_requant", "sw_conv2d_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
+           "sw_conv2d_s8_requant", "sw_conv2d_bias_relu", "sw_conv2d_depthwise_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
            "sw_conv2d_depthwise_bf16", "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
            "sw_jit_cached_kernels",
            "sw_out_dim", "sw_workspace_bytes", "sw_status_string", "sw_version")
@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
     L.sw_conv2d.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.sw_conv2d_bias_relu.restype = i32
     L.sw_conv2d_bias_relu.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp]
+    L.sw_conv2d_depthwise_bias_relu.restype = i32
+    L.sw_conv2d_depthwise_bias_relu.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp]
     L.sw_conv2d_dilated.restype = i32
     L.sw_conv2d_dilated.argtypes = [vp, vp, vp] + [i32] * 10 + [vp]
     L.sw_conv2d_depthwise_dilated.restype = i32
@@ -222,6 +224,27 @@ def sw_conv2d_bias_relu(x, w, bias, stride: int = 1, pad: int = 0, relu: bool = 
                                    _dev(out, torch.float32, 4, "y"), N, C_in, C_out, H, W, R, S, stride, pad,
                                    1 if relu else 0, _stream(stream))
     _check(rc, "sw_conv2d_bias_relu")
+    return out
+
+
+def sw_conv2d_depthwise_bias_relu(x, w, bias, stride: int = 1, pad: int = 0, relu: bool = False, out=None, stream=None):
+    """x [N,C,H,W] fp32, w [C,1,R,S] fp32, bias [C] fp32 or None -> y = act(depthwise conv + bias)."""
+    import torch
+
+    N, C, H, W = x.shape
+    Cw, one, R, S = w.shape
+    if Cw != C or one != 1:
+        raise ValueError("depthwise weights must be [C,1,R,S]")
+    if bias is not None and tuple(bias.shape) != (C,):
+        raise ValueError("one bias per channel")
+    if out is None:
+        out = torch.empty(_out_shape("sw_conv2d_depthwise_bias_relu", N, C, sw_out_dim(H, R, stride, pad),
+                                     sw_out_dim(W, S, stride, pad)), dtype=torch.float32, device=x.device)
+    rc = lib().sw_conv2d_depthwise_bias_relu(_dev(x, torch.float32, 4, "x"), _dev(w, torch.float32, 4, "w"),
+                                             _dev(bias, torch.float32, 1, "bias") if bias is not None else None,
+                                             _dev(out, torch.float32, 4, "y"), N, C, H, W, R, S, stride, pad,
+                                             1 if relu else 0, _stream(stream))
+    _check(rc, "sw_conv2d_depthwise_bias_relu")
     return out
 
 

@@ -109,7 +109,7 @@ __global__ __launch_bounds__(RC > 0 ? 64 : 256) void sliding_plane_kernel(const 
                                                            int n_filters, int H, int W, int R_rt,
                                                            int S_rt, int pad, int Ho, int Wo,
                                                            int tiles_x, int tiles_y, int x_vec_ok,
-                                                           int y_vec_ok)
+                                                           int y_vec_ok, const Epilogue ep)
 {
     constexpr int RMAX = RC > 0 ? RC : MAXRS;
     constexpr int SMAX = RC > 0 ? SC : MAXRS;
@@ -223,6 +223,16 @@ __global__ __launch_bounds__(RC > 0 ? 64 : 256) void sliding_plane_kernel(const 
         __syncthreads();
     }
     if (wave == 0) {
+        if (ep.bias != nullptr || ep.relu != 0) {      // fused-epilogue entry point: per-channel bias, rectifier
+            const float eb = ep.bias ? ep.bias[plane % n_filters] : 0.f;
+#pragma unroll
+            for (int i = 0; i < kB; ++i)
+#pragma unroll
+                for (int j = 0; j < kB; ++j) {
+                    const float t = acc[i][j] + eb;
+                    acc[i][j] = ep.relu ? fmaxf(t, 0.f) : t;
+                }
+        }
 #pragma unroll
         for (int i = 0; i < kB; ++i)
 #pragma unroll
@@ -261,12 +271,15 @@ __global__ __launch_bounds__(RC > 0 ? 64 : 256) void sliding_plane_kernel(const 
 __device__ __forceinline__ void wave_lds_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
 // SQ: the plane and its output are exactly 56 x 56 (every slot count is then a compile-time constant).
-template <int R, int S, bool SQ>
+// EP: a per-channel bias and a rectifier are applied while the outputs are staged (the plain variant carries no
+// trace of them).
+template <int R, int S, bool SQ, bool EP>
 __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __restrict__ x,
                                                                 const float* __restrict__ w,
                                                                 float* __restrict__ y, int planes,
                                                                 int planes_per_x, int n_filters, int H_rt,
-                                                                int W_rt, int pad, int Ho_rt, int Wo_rt)
+                                                                int W_rt, int pad, int Ho_rt, int Wo_rt,
+                                                                const Epilogue ep)
 {
     const int H = SQ ? kTile : H_rt, W = SQ ? kTile : W_rt, Ho = SQ ? kTile : Ho_rt, Wo = SQ ? kTile : Wo_rt;
     constexpr int P = in_pitch(S);
@@ -347,6 +360,16 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
             for (int j = 0; j < kB; ++j) acc[i][j] = 0.f;
         accumulate_block<R, S, P>(win, w + (int64_t)(plane % n_filters) * R * S, acc);
         wave_lds_sync();
+        if (EP) {
+            const float eb = ep.bias ? ep.bias[plane % n_filters] : 0.f;
+#pragma unroll
+            for (int i = 0; i < kB; ++i)
+#pragma unroll
+                for (int j = 0; j < kB; ++j) {
+                    const float t = acc[i][j] + eb;
+                    acc[i][j] = ep.relu ? fmaxf(t, 0.f) : t;
+                }
+        }
 
         if (full) {
 #pragma unroll
@@ -535,26 +558,29 @@ bool sliding_plane_worthwhile(int64_t planes, int Ho, int Wo, int R, int S)
 
 hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x,
                                 int n_filters, int H, int W, int R, int S, int pad, int Ho, int Wo,
-                                hipStream_t st)
+                                hipStream_t st, const Epilogue& ep)
 {
     if (sliding_plane_whole(x, y, W, R, S, pad, Ho, Wo) && planes <= 2147483647LL) {
         // enough wavefronts to fill the chip, each walking over several planes
         const int64_t want = 256 * 8;
         dim3 grid((unsigned)(planes < want ? planes : want)), block(64);
+#define SW_FULL2(RC, SQC, EPC)                                                                               \
+    hipLaunchKernelGGL((sliding_plane_full_kernel<RC, RC, SQC, EPC>), grid, block, 0, st, x, w, y, (int)planes, \
+                       planes_per_x, n_filters, H, W, pad, Ho, Wo, ep)
 #define SW_FULL(RC)                                                                                          \
     do {                                                                                                     \
-        if (sq)                                                                                              \
-            hipLaunchKernelGGL((sliding_plane_full_kernel<RC, RC, true>), grid, block, 0, st, x, w, y,       \
-                               (int)planes, planes_per_x, n_filters, H, W, pad, Ho, Wo);                     \
-        else                                                                                                 \
-            hipLaunchKernelGGL((sliding_plane_full_kernel<RC, RC, false>), grid, block, 0, st, x, w, y,      \
-                               (int)planes, planes_per_x, n_filters, H, W, pad, Ho, Wo);                     \
+        if (sq && with_ep) SW_FULL2(RC, true, true);                                                         \
+        else if (sq) SW_FULL2(RC, true, false);                                                              \
+        else if (with_ep) SW_FULL2(RC, false, true);                                                         \
+        else SW_FULL2(RC, false, false);                                                                     \
     } while (0)
         const bool sq = H == kTile && W == kTile && Ho == kTile && Wo == kTile;
+        const bool with_ep = ep.bias != nullptr || ep.relu != 0;
         if (R == 3) SW_FULL(3);
         else if (R == 5) SW_FULL(5);
         else SW_FULL(7);
 #undef SW_FULL
+#undef SW_FULL2
         return hipGetLastError();
     }
     const int tiles_x = (Wo + kTile - 1) / kTile, tiles_y = (Ho + kTile - 1) / kTile;
@@ -565,7 +591,7 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
     dim3 grid((unsigned)blocks);
 #define SW_PLANE(RC, SC, MAXRS)                                                                          \
     hipLaunchKernelGGL((sliding_plane_kernel<RC, SC, MAXRS>), grid, dim3(RC > 0 ? 64 : 256), 0, st, x, w, y, planes_per_x, \
-                       n_filters, H, W, R, S, pad, Ho, Wo, tiles_x, tiles_y, x_vec_ok, y_vec_ok)
+                       n_filters, H, W, R, S, pad, Ho, Wo, tiles_x, tiles_y, x_vec_ok, y_vec_ok, ep)
     if (R == 3 && S == 3) SW_PLANE(3, 3, 0);
     else if (R == 5 && S == 5) SW_PLANE(5, 5, 0);
     else if (R == 7 && S == 7) SW_PLANE(7, 7, 0);

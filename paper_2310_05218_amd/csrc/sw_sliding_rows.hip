@@ -60,7 +60,7 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
                                                            float* __restrict__ y, int planes_per_x,
                                                            int n_filters, int H, int W, int Ho, int Wo,
                                                            int strips, int bands, int64_t waves, int64_t items,
-                                                           int y_vec_ok)
+                                                           int y_vec_ok, const Epilogue ep)
 {
     constexpr int NOUT = 4 / ST;                                   // outputs per lane and output row
     constexpr int LEFT = PADC;
@@ -148,6 +148,9 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
     const bool right_ok = SEGL != 64 || lane < 63 || c0 + kStripIn >= W;
     if (!left_ok || !right_ok || ocol >= Wo || !live) return;
     constexpr float kScale = 1.0f / (float)(R * S);
+    // convolution only: per-channel bias and rectifier of the fused-epilogue entry point (both off otherwise)
+    const bool with_ep = OP == ROWS_CONV && (ep.bias != nullptr || ep.relu != 0);
+    const float ep_bias = (OP == ROWS_CONV && ep.bias) ? ep.bias[plane % n_filters] : 0.f;
 #pragma unroll
     for (int orow = 0; orow < TR; ++orow) {
         const int oi = i0 + orow;
@@ -155,6 +158,13 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
         if constexpr (OP == ROWS_AVG) {
 #pragma unroll
             for (int p = 0; p < NOUT; ++p) acc[orow][p] *= kScale;
+        }
+        if (with_ep) {
+#pragma unroll
+            for (int p = 0; p < NOUT; ++p) {
+                const float t = acc[orow][p] + ep_bias;
+                acc[orow][p] = ep.relu ? fmaxf(t, 0.f) : t;
+            }
         }
         float* dst = yp + (int64_t)oi * Wo + ocol;
         if (y_vec_ok && ocol + NOUT - 1 < Wo) {
@@ -174,7 +184,7 @@ __global__ __launch_bounds__(256) void sliding_rows_kernel(const float* __restri
 
 template <int R, int S, int PADC, int ST, int OP, int SEGL>
 hipError_t launch_rows_seg(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
-                           int H, int W, int Ho, int Wo, hipStream_t st)
+                           int H, int W, int Ho, int Wo, hipStream_t st, const Epilogue& ep)
 {
     constexpr int NOUT = 4 / ST;
     const int y_vec_ok = reinterpret_cast<uintptr_t>(y) % (4 * NOUT) == 0 && Wo % NOUT == 0;
@@ -198,10 +208,10 @@ hipError_t launch_rows_seg(const float* x, const float* w, float* y, int64_t pla
     dim3 grid((unsigned)blocks), block(256);
     if (small)
         hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_SMALL, ST, OP, SEGL>), grid, block, 0, st, x, w, y,
-                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, items, y_vec_ok);
+                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, items, y_vec_ok, ep);
     else
         hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_BIG, ST, OP, SEGL>), grid, block, 0, st, x, w, y,
-                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, items, y_vec_ok);
+                           planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, items, y_vec_ok, ep);
     return hipGetLastError();
 }
 
@@ -209,10 +219,10 @@ hipError_t launch_rows_seg(const float* x, const float* w, float* y, int64_t pla
 // that the lane between two planes holds padding.
 template <int R, int S, int PADC, int ST, int OP>
 hipError_t launch_rows(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
-                       int H, int W, int Ho, int Wo, hipStream_t st)
+                       int H, int W, int Ho, int Wo, hipStream_t st, const Epilogue& ep)
 {
     const int lanes = W / 4 + 1;
-#define SW_SEG(L) return launch_rows_seg<R, S, PADC, ST, OP, L>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st)
+#define SW_SEG(L) return launch_rows_seg<R, S, PADC, ST, OP, L>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st, ep)
     if (lanes <= 8) SW_SEG(8);
     if (lanes <= 16) SW_SEG(16);
     if (lanes <= 32) SW_SEG(32);
@@ -234,26 +244,26 @@ bool sliding_rows_supported(const float* x, int H, int W, int R, int S, int stri
 
 hipError_t launch_sliding_rows(const float* x, const float* w, float* y, int64_t planes, int planes_per_x,
                                int n_filters, int H, int W, int R, int S, int stride, int pad, int Ho, int Wo,
-                               hipStream_t st)
+                               hipStream_t st, const Epilogue& ep)
 {
     (void)S;
 #define SW_ROWS(RC, PC)                                                                                        \
     if (R == RC && pad == PC) {                                                                                \
         if (stride == 1)                                                                                       \
-            return launch_rows<RC, RC, PC, 1, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st); \
-        return launch_rows<RC, RC, PC, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);     \
+            return launch_rows<RC, RC, PC, 1, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st, ep); \
+        return launch_rows<RC, RC, PC, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st, ep);     \
     }
     SW_ROWS(3, 0) SW_ROWS(3, 1) SW_ROWS(5, 0) SW_ROWS(5, 1) SW_ROWS(5, 2)
     if (R == 7 && pad == 3) {
-        if (stride == 1) return launch_rows<7, 7, 3, 1, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
-        return launch_rows<7, 7, 3, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
+        if (stride == 1) return launch_rows<7, 7, 3, 1, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st, ep);
+        return launch_rows<7, 7, 3, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st, ep);
     }
     if (R == 7 && pad == 2) {
-        if (stride == 1) return launch_rows<7, 7, 2, 1, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
-        return launch_rows<7, 7, 2, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
+        if (stride == 1) return launch_rows<7, 7, 2, 1, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st, ep);
+        return launch_rows<7, 7, 2, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st, ep);
     }
     if (R == 7 && pad == 1 && stride == 2)
-        return launch_rows<7, 7, 1, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st);
+        return launch_rows<7, 7, 1, 2, ROWS_CONV>(x, w, y, planes, planes_per_x, n_filters, H, W, Ho, Wo, st, ep);
 #undef SW_ROWS
     return hipErrorInvalidValue;
 }
@@ -271,8 +281,8 @@ hipError_t launch_pool_rows(const float* x, float* y, int64_t planes, int H, int
 {
 #define SW_POOL(RC, PC, SC)                                                                                    \
     if (R == RC && pad == PC && stride == SC) {                                                                \
-        if (maximum) return launch_rows<RC, RC, PC, SC, ROWS_MAX>(x, nullptr, y, planes, 1, 1, H, W, Ho, Wo, st); \
-        return launch_rows<RC, RC, PC, SC, ROWS_AVG>(x, nullptr, y, planes, 1, 1, H, W, Ho, Wo, st);           \
+        if (maximum) return launch_rows<RC, RC, PC, SC, ROWS_MAX>(x, nullptr, y, planes, 1, 1, H, W, Ho, Wo, st, Epilogue{nullptr, 0}); \
+        return launch_rows<RC, RC, PC, SC, ROWS_AVG>(x, nullptr, y, planes, 1, 1, H, W, Ho, Wo, st, Epilogue{nullptr, 0}); \
     }
     SW_POOL(2, 0, 2) SW_POOL(3, 0, 1) SW_POOL(3, 1, 1) SW_POOL(3, 0, 2) SW_POOL(3, 1, 2)
 #undef SW_POOL

@@ -20,6 +20,7 @@ constexpr int kThreads = 256;
 constexpr int kLdsFloats = 12 * 1024;      // 48 KB per workgroup: three workgroups per CU
 
 struct SmallParams {
+    Epilogue ep;                           // per-channel bias and rectifier of the fused-epilogue entry point
     int H, W, R, S, stride, pad, Ho, Wo, n_filters, G;
     int Hp, Wp, QH;                        // framed plane in LDS, groups of four output rows
     int64_t planes;
@@ -100,6 +101,14 @@ __global__ __launch_bounds__(kThreads) void small_planes_kernel(const float* __r
                     for (int j = 0; j < 4; ++j) acc[j] = fmaf(tap, col[j * ST * P.Wp], acc[j]);
                 }
         }
+        if (P.ep.bias != nullptr || P.ep.relu != 0) {
+            const float eb = P.ep.bias ? P.ep.bias[(p0 + g) % P.n_filters] : 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float t = acc[j] + eb;
+                acc[j] = P.ep.relu ? fmaxf(t, 0.f) : t;
+            }
+        }
         float* o = dst + g * HoWo + oi * P.Wo + oj;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
@@ -130,9 +139,10 @@ bool small_planes_supported(int64_t planes, int planes_per_x, int H, int W, int 
 }
 
 hipError_t launch_small_planes(const float* x, const float* w, float* y, int64_t planes, int n_filters, int H, int W,
-                               int R, int S, int stride, int pad, int Ho, int Wo, hipStream_t st)
+                               int R, int S, int stride, int pad, int Ho, int Wo, hipStream_t st, const Epilogue& ep)
 {
     SmallParams P;
+    P.ep = ep;
     P.H = H; P.W = W; P.R = R; P.S = S; P.stride = stride; P.pad = pad; P.Ho = Ho; P.Wo = Wo;
     P.n_filters = n_filters; P.planes = planes;
     frame_of(R, S, stride, Ho, Wo, &P.Hp, &P.Wp, &P.QH);

@@ -72,7 +72,7 @@ int launch_status(hipError_t e) { return e == hipSuccess ? SW_OK : SW_ERR_LAUNCH
 // One filter per plane (single input channel, depthwise): picks among the whole-plane kernel (many planes
 // that fit a 56 x 56 tile), the register-only rows kernel (3x3 / 5x5), the tile kernel and the direct kernel.
 int run_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
-              const Conv2dShape& s, bool depthwise, hipStream_t st)
+              const Conv2dShape& s, bool depthwise, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0})
 {
     if (!force_direct()) {
         // planes up to 20 x 20, and larger ragged ones (width not a multiple of 4) that the register-only and
@@ -80,7 +80,7 @@ int run_plane(const float* x, const float* w, float* y, int64_t planes, int plan
         if (!no_small_planes_kernel() && (s.H * s.W <= 400 || s.W % 4 != 0 || s.R * s.S >= 25) &&
             small_planes_supported(planes, planes_per_x, s.H, s.W, s.R, s.S, s.stride, s.Ho, s.Wo))
             return launch_status(launch_small_planes(x, w, y, planes, n_filters, s.H, s.W, s.R, s.S, s.stride, s.pad,
-                                                     s.Ho, s.Wo, st));
+                                                     s.Ho, s.Wo, st, ep));
         const bool rows = !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad);
         // the whole-plane kernel spends a 56 x 56 tile per plane: planes up to 32 wide leave most of its lanes
         // idle and go to the rows kernel (lane groups) when that has a variant
@@ -88,13 +88,13 @@ int run_plane(const float* x, const float* w, float* y, int64_t planes, int plan
                            planes >= 512 && !(no_whole_plane_kernel() && s.R < 7) && !(rows && s.W <= 32);
         if (!whole && rows)
             return launch_status(launch_sliding_rows(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
-                                                     s.stride, s.pad, s.Ho, s.Wo, st));
+                                                     s.stride, s.pad, s.Ho, s.Wo, st, ep));
         if (sliding_plane_supported(s.H, s.W, s.R, s.S, s.stride, s.pad) &&
             sliding_plane_worthwhile(planes, s.Ho, s.Wo, s.R, s.S))
             return launch_status(launch_sliding_plane(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
-                                                      s.pad, s.Ho, s.Wo, st));
+                                                      s.pad, s.Ho, s.Wo, st, ep));
     }
-    return launch_status(launch_direct_conv2d_f32(x, w, y, s, depthwise, st));
+    return launch_status(launch_direct_conv2d_f32(x, w, y, s, depthwise, st, &ep));
 }
 
 // Shared validation of the 2-D calls.  esz_in / esz_out are element sizes in bytes.
@@ -221,9 +221,10 @@ int sw_pool2d(const float* x, float* y, int N, int C, int H, int W, int R, int S
 static int run_conv2d(const float* x, const float* w, float* y, const Conv2dShape& s, const Epilogue& ep, hipStream_t st)
 {
     const bool plain = !ep.bias && !ep.relu;
-    if (s.C_in == 1 && plain && s.dil == 1) return run_plane(x, w, y, (int64_t)s.N * s.C_out, s.C_out, s.C_out, s, false, st);
-    // (one input channel with an epilogue or a dilation: the one-filter-per-plane kernels have neither, one thread
-    // per output has)
+    (void)plain;
+    if (s.C_in == 1 && s.dil == 1)
+        return run_plane(x, w, y, (int64_t)s.N * s.C_out, s.C_out, s.C_out, s, false, st, ep);
+    // (one input channel with a dilation: the one-filter-per-plane kernels have none, one thread per output has)
     if (!force_direct() && s.C_in > 1) {
         // The fixed 3x3 / 5x5 kernel holds a CU with one large tile: it needs enough of them to fill the chip
         // (28 x 28 images and below at batch 32 leave it at 128 or fewer); the any-shape kernel's 128-pixel
@@ -286,6 +287,18 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, 
     if (rc != SW_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
+}
+
+int sw_conv2d_depthwise_bias_relu(const float* x, const float* w, const float* bias, float* y, int N, int C, int H,
+                                  int W, int R, int S, int stride, int pad, int relu, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s);
+    if (rc != SW_OK) return rc;
+    if (bias && misaligned(bias, 4)) return SW_ERR_ALIGN;
+    if (bias && overlaps(y, (int64_t)N * C * s.Ho * s.Wo * 4, bias, (int64_t)C * 4)) return SW_ERR_ALIAS;
+    return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, static_cast<hipStream_t>(hip_stream),
+                     Epilogue{bias, relu != 0});
 }
 
 int sw_conv2d_depthwise_bf16(const uint16_t* x, const float* w, uint16_t* y, int N, int C, int H, int W, int R, int S,

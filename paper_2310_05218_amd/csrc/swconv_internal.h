@@ -94,13 +94,13 @@ bool       sliding_plane_whole(const float* x, const float* y, int W, int R, int
 bool       sliding_rows_supported(const float* x, int H, int W, int R, int S, int stride, int pad);
 hipError_t launch_sliding_rows(const float* x, const float* w, float* y, int64_t planes, int planes_per_x,
                                int n_filters, int H, int W, int R, int S, int stride, int pad, int Ho, int Wo,
-                               hipStream_t st);
+                               hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0});
 bool       pool_rows_supported(const float* x, int W, int R, int S, int stride, int pad);
 hipError_t launch_pool_rows(const float* x, float* y, int64_t planes, int H, int W, int R, int stride, int pad,
                             int Ho, int Wo, bool maximum, hipStream_t st);
 hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes,
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
-                                int Ho, int Wo, hipStream_t st);
+                                int Ho, int Wo, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0});
 
 // ---- depthwise on small planes (at most 1024 elements): a run of planes per workgroup through LDS --------
 // bf16 activations (bit patterns in unsigned short), fp32 filters and accumulation
@@ -121,7 +121,8 @@ int        jit_launch_plane(const float* x, const float* w, float* y, int64_t pl
 bool       small_planes_supported(int64_t planes, int planes_per_x, int H, int W, int R, int S, int stride, int Ho,
                                   int Wo);
 hipError_t launch_small_planes(const float* x, const float* w, float* y, int64_t planes, int n_filters, int H, int W,
-                               int R, int S, int stride, int pad, int Ho, int Wo, hipStream_t st);
+                               int R, int S, int stride, int pad, int Ho, int Wo, hipStream_t st,
+                               const Epilogue& ep = Epilogue{nullptr, 0});
 
 // ---- global pooling of planes of at most 256 elements: 64 planes per wavefront through LDS ----------------
 bool       global_pool_supported(int H, int W, int R, int S, int pad);

@@ -193,6 +193,19 @@ def test_bias_relu_argument_errors(L):
     assert f(X, W_, B_, X + 64, *ok, 0, None) == B.SW_ERR_ALIAS
 
 
+def test_depthwise_bias_relu_argument_errors(L):
+    f = L.sw_conv2d_depthwise_bias_relu
+    B_ = 0x2100000
+    ok = (2, 16, 8, 8, 3, 3, 1, 1)
+    assert f(None, W_, B_, Y, *ok, 0, None) == B.SW_ERR_NULL
+    for i in range(7):
+        bad = list(ok)
+        bad[i] = 0
+        assert f(X, W_, B_, Y, *bad, 0, None) == B.SW_ERR_SHAPE, i
+    assert f(X, W_, B_ + 2, Y, *ok, 0, None) == B.SW_ERR_ALIGN
+    assert f(X, W_, Y + 16, Y, *ok, 0, None) == B.SW_ERR_ALIAS
+
+
 def test_jit_entry_point_argument_errors(L):
     f = L.sw_conv2d_depthwise_jit
     ok = (2, 16, 56, 56, 9, 9, 1, 4)

@@ -413,6 +413,50 @@ def test_dilation_one_is_the_undilated_call(torch, sw):
     assert torch.equal(sw.sw_conv2d_dilated(x, w, 1, 1, 1), sw.sw_conv2d(x, w, 1, 1))
 
 
+DW_BIAS_RELU_CASES = [
+    # N, C, H, W, R, S, stride, pad -- one per kernel of the one-filter-per-plane dispatch
+    (2, 256, 56, 56, 3, 3, 1, 1),        # whole-plane kernel, 56 x 56 specialisation
+    (2, 256, 56, 56, 7, 7, 1, 3),
+    (8, 64, 48, 56, 5, 5, 1, 2),         # ... general variant
+    (2, 8, 112, 112, 3, 3, 2, 1),        # register-only rows kernel, stride 2
+    (2, 40, 28, 28, 3, 3, 1, 1),         # rows kernel, two planes per wavefront
+    (4, 32, 14, 14, 3, 3, 1, 1),         # small planes through LDS
+    (2, 40, 7, 7, 5, 5, 1, 2),
+    (2, 40, 60, 60, 9, 9, 1, 4),         # run-time-extent tile kernel (four wavefronts per tile)
+    (1, 70, 100, 60, 4, 6, 1, 2),
+    (2, 5, 30, 31, 3, 3, 3, 1),          # one thread per output
+]
+
+
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("case", DW_BIAS_RELU_CASES)
+def test_conv2d_depthwise_bias_relu(torch, sw, oracle, case, relu):
+    N, C, H, W, R, S, stride, pad = case
+    x = inputs.normal_f32((N, C, H, W), 3301)
+    w = inputs.normal_f32((C, 1, R, S), 3302, 1.0 / (R * S) ** 0.5)
+    bias = inputs.normal_f32((C,), 3303, 0.7)
+    y_ref, d = oracle.conv2d_depthwise_bias_relu(x, w, bias, stride, pad, relu)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_depthwise_bias_relu(dev(torch, x), dev(torch, w), dev(torch, bias), stride, pad, relu, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    y = out.cpu().numpy()
+    assert_f32_parity(y, y_ref, d, f"depthwise_bias_relu {case} relu={relu}")
+    if relu:
+        assert y.min() == 0.0 and 0.2 < (y == 0).mean() < 0.8
+    else:
+        y0 = sw.sw_conv2d_depthwise(dev(torch, x), dev(torch, w), stride, pad).cpu().numpy()
+        assert np.allclose((y - y0).mean(axis=(0, 2, 3)), bias, atol=1e-4)
+
+
+def test_depthwise_bias_relu_without_either_is_the_plain_call(torch, sw):
+    x = dev(torch, inputs.normal_f32((2, 256, 56, 56), 3311))
+    w = dev(torch, inputs.normal_f32((256, 1, 3, 3), 3312))
+    plain = sw.sw_conv2d_depthwise(x, w, 1, 1)
+    assert torch.equal(sw.sw_conv2d_depthwise_bias_relu(x, w, None, 1, 1, False), plain)
+    assert torch.equal(sw.sw_conv2d_depthwise_bias_relu(x, w, None, 1, 1, True), torch.clamp_min(plain, 0.0))
+
+
 BIAS_RELU_CASES = [
     # N, C_in, C_out, H, W, R, S, stride, pad
     (8, 16, 256, 56, 56, 3, 3, 1, 1),    # enough large tiles for the fixed 3x3 matrix-core kernel (256 workgroups)
@@ -421,7 +465,8 @@ BIAS_RELU_CASES = [
     (1, 3, 5, 9, 11, 3, 3, 1, 1),        # any-shape kernel, ragged channel block
     (2, 4, 3, 12, 10, 2, 5, 2, 2),
     (1, 9, 130, 16, 16, 2, 2, 2, 0),     # three channel blocks with a ragged last one
-    (2, 1, 6, 20, 20, 3, 3, 1, 1),       # one input channel: one thread per output
+    (2, 1, 6, 20, 20, 3, 3, 1, 1),       # one input channel: the one-filter-per-plane kernels
+    (2, 1, 64, 56, 56, 7, 7, 1, 3),
 ]
 
 

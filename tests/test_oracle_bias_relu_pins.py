@@ -53,3 +53,15 @@ def test_no_bias_and_no_rectifier_is_the_plain_convolution(oracle):
     assert np.array_equal(y2, np.maximum(y0, 0.0))
     with pytest.raises(ValueError):
         oracle.conv2d_bias_relu(x, w, np.zeros(2, np.float32), 1, 1, False)
+
+
+def test_depthwise_variant_hand_worked(oracle):
+    # two channels, each its own 1x1 filter and bias: y[c] = act(w[c] * x[c] + bias[c])
+    x = np.array([[[[1.0, -2.0]], [[3.0, -4.0]]]], np.float32)            # [1,2,1,2]
+    w = np.array([2.0, -1.0], np.float32).reshape(2, 1, 1, 1)
+    bias = np.array([0.5, 2.0], np.float32)
+    y, d = oracle.conv2d_depthwise_bias_relu(x, w, bias, 1, 0, False)
+    assert y.tolist() == [[[[2.5, -3.5]], [[-1.0, 6.0]]]]
+    assert d.tolist() == [[[[2.5, 4.5]], [[5.0, 6.0]]]]
+    y, _ = oracle.conv2d_depthwise_bias_relu(x, w, bias, 1, 0, True)
+    assert y.tolist() == [[[[2.5, 0.0]], [[0.0, 6.0]]]]

@@ -138,3 +138,107 @@ def test_conv1d_and_pool1d_random(torch, sw, oracle, case):
                 assert np.array_equal(y.astype(np.float64), y_ref)
             else:
                 assert_f32_parity(y, y_ref, d, f"avg pool1d window={k} stride={stride} len={length}")
+
+
+@pytest.mark.parametrize("case", _cases(81, 30, max_hw=40, max_k=5), ids=lambda c: "x".join(map(str, c[1:7])))
+def test_conv2d_dilated_random(torch, sw, oracle, case):
+    _, H, W, R, S, stride, pad, seed = case
+    rng = np.random.default_rng(seed)
+    dil = int(rng.integers(1, 5))
+    # keep the dilated filter inside the padded plane
+    H = max(H, dil * (R - 1) + 1 - 2 * pad)
+    W = max(W, dil * (S - 1) + 1 - 2 * pad)
+    N = int(rng.integers(1, 3))
+    depthwise = bool(rng.random() < 0.3)
+    C_in, C_out = int(rng.choice([1, 2, 3, 7, 16, 33])), int(rng.choice([1, 5, 32, 64, 70]))
+    if depthwise:
+        C_out = C_in
+    x = inputs.normal_f32((N, C_in, H, W), seed % 100000)
+    w = inputs.normal_f32((C_out, 1 if depthwise else C_in, R, S), seed % 100000 + 1)
+    y_ref, d = oracle.conv2d_dilated(x, w, stride, pad, dil, depthwise=depthwise)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    call = sw.sw_conv2d_depthwise_dilated if depthwise else sw.sw_conv2d_dilated
+    call(dev(torch, x), dev(torch, w), stride, pad, dil, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"dilated {case} dil={dil} dw={depthwise} C_in={C_in} C_out={C_out}")
+
+
+@pytest.mark.parametrize("case", _cases(82, 40, max_hw=60, max_k=7), ids=lambda c: "x".join(map(str, c[1:7])))
+def test_bias_relu_random(torch, sw, oracle, case):
+    """Both fused-epilogue entry points (multi-channel and depthwise), bias present or not, rectifier on or off."""
+    _, H, W, R, S, stride, pad, seed = case
+    rng = np.random.default_rng(seed)
+    N = int(rng.integers(1, 3))
+    depthwise = bool(rng.random() < 0.5)
+    C_in, C_out = int(rng.choice([1, 3, 8, 16, 40])), int(rng.choice([1, 5, 64, 70]))
+    if depthwise:
+        C_in = C_out = int(rng.choice([1, 3, 8, 70, 130]))
+    relu, with_bias = bool(rng.random() < 0.6), bool(rng.random() < 0.8)
+    x = inputs.normal_f32((N, C_in, H, W), seed % 100000)
+    w = inputs.normal_f32((C_out, 1 if depthwise else C_in, R, S), seed % 100000 + 1)
+    bias = inputs.normal_f32((C_out,), seed % 100000 + 2, 0.8) if with_bias else None
+    if depthwise:
+        y_ref, d = oracle.conv2d_depthwise_bias_relu(x, w, bias, stride, pad, relu)
+        call = sw.sw_conv2d_depthwise_bias_relu
+    else:
+        y_ref, d = oracle.conv2d_bias_relu(x, w, bias, stride, pad, relu)
+        call = sw.sw_conv2d_bias_relu
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    call(dev(torch, x), dev(torch, w), dev(torch, bias) if with_bias else None, stride, pad, relu, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"bias_relu {case} dw={depthwise} relu={relu} bias={with_bias}")
+
+
+@pytest.mark.parametrize("case", _cases(83, 30, max_hw=60, max_k=7), ids=lambda c: "x".join(map(str, c[1:7])))
+def test_depthwise_bf16_random(torch, sw, oracle, case):
+    _, H, W, R, S, stride, pad, seed = case
+    rng = np.random.default_rng(seed)
+    if rng.random() < 0.5:          # steer half of the cases to the whole-plane kernel's range
+        R = S = int(rng.choice([3, 5, 7]))
+        stride, pad = 1, R // 2
+        H, W = int(rng.integers(R, 57)), int(rng.choice([8, 16, 24, 32, 40, 48, 56]))
+    N, C = int(rng.integers(1, 4)), int(rng.choice([1, 3, 8, 70]))
+    xb = inputs.normal_bf16((N, C, H, W), seed % 100000)
+    w = inputs.normal_f32((C, 1, R, S), seed % 100000 + 1, 1.0 / (R * S) ** 0.5)
+    y_ref, d = oracle.conv2d_depthwise(inputs.bf16_bits_to_f32(xb), w, stride, pad)
+    xd = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.bfloat16)
+    sw.sw_conv2d_depthwise_bf16(xd, dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    y = inputs.bf16_bits_to_f32(out.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+    assert np.all(np.abs(y - y_ref) <= 2e-5 * d + 2.0 ** -8 * np.abs(y_ref) + 1e-37), f"bf16 depthwise {case} N={N} C={C}"
+
+
+def _jit_cases(seed, n):
+    """Geometries inside the generated kernel's range: stride 1, W and W_out multiples of 4, output at most
+    56 x 56 and at least half of that, 2 * pad <= min(R, S) - 1."""
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < n:
+        R, S = int(rng.integers(1, 20)), int(rng.integers(1, 20))
+        pad = int(rng.integers(0, (min(R, S) - 1) // 2 + 1))
+        Ho, Wo = int(rng.integers(40, 57)), int(rng.choice([40, 44, 48, 52, 56]))
+        H, W = Ho + R - 1 - 2 * pad, Wo + S - 1 - 2 * pad
+        if W % 4 or H * W > 4096:
+            continue
+        out.append((len(out), H, W, R, S, pad, int(rng.integers(0, 1 << 30))))
+    return out
+
+
+@pytest.mark.parametrize("case", _jit_cases(84, 16), ids=lambda c: "x".join(map(str, c[1:6])))
+def test_depthwise_jit_random(torch, sw, oracle, case):
+    _, H, W, R, S, pad, seed = case
+    assert sw.sw_jit_prepare_depthwise(H, W, R, S, 1, pad) == 0, "geometry expected inside the generated kernel's range"
+    rng = np.random.default_rng(seed)
+    N, C = int(rng.integers(1, 3)), int(rng.choice([1, 3, 9]))
+    x = inputs.normal_f32((N, C, H, W), seed % 100000)
+    w = inputs.normal_f32((C, 1, R, S), seed % 100000 + 1, 1.0 / (R * S) ** 0.5)
+    y_ref, d = oracle.conv2d_depthwise(x, w, 1, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_depthwise_jit(dev(torch, x), dev(torch, w), 1, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"jit depthwise {case} N={N} C={C}")

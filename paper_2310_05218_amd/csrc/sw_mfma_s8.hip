@@ -323,14 +323,14 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
             int r[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) r[t] = requant_reg(c[4 * g + t], 4 * g + t) & 255;
-            // round 1, partner lane ^ 1: keep the channels whose bit 0 is this lane's bit 0
+            // exchange 1, partner lane ^ 1: keep the channels whose bit 0 is this lane's bit 0
             const bool b0 = k & 1, b1 = k & 2;
             const int keep01 = b0 ? r[1] : r[0], send01 = b0 ? r[0] : r[1];
             const int keep23 = b0 ? r[3] : r[2], send23 = b0 ? r[2] : r[3];
             const int got01 = __builtin_amdgcn_mov_dpp(send01, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
             const int got23 = __builtin_amdgcn_mov_dpp(send23, 0xB1, 0xF, 0xF, true);
             // now (keep01, got01) = channel b0 of pixels (k, k^1), (keep23, got23) = channel 2 + b0 of the same
-            // round 2, partner lane ^ 2: keep the pair whose channel has this lane's bit 1
+            // exchange 2, partner lane ^ 2: keep the pair whose channel has this lane's bit 1
             const int own_a = b1 ? keep23 : keep01, own_b = b1 ? got23 : got01;
             const int snd_a = b1 ? keep01 : keep23, snd_b = b1 ? got01 : got23;
             const int far_a = __builtin_amdgcn_mov_dpp(snd_a, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]

@@ -102,8 +102,7 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0});
 
-// ---- depthwise on small planes (at most 1024 elements): a run of planes per workgroup through LDS --------
-// bf16 activations (bit patterns in unsigned short), fp32 filters and accumulation
+// ---- bf16 activations (bit patterns in unsigned short), fp32 filters and accumulation --------------------
 bool       sliding_plane_bf16_supported(const void* x, const void* y, int W, int R, int S, int stride, int pad, int Ho,
                                         int Wo);
 hipError_t launch_sliding_plane_bf16(const unsigned short* x, const float* w, unsigned short* y, int64_t planes,
@@ -111,13 +110,15 @@ hipError_t launch_sliding_plane_bf16(const unsigned short* x, const float* w, un
 hipError_t launch_direct_depthwise_bf16(const unsigned short* x, const float* w, unsigned short* y,
                                         const Conv2dShape& s, hipStream_t st);
 
-// sw_jit.hip: one-filter-per-plane kernels compiled at run time, one per geometry (status codes, not hipError_t)
+// ---- sw_jit.hip: one-filter-per-plane kernels compiled at run time, one per geometry (status codes) ------
 bool       jit_plane_supported(const float* x, const float* y, int H, int W, int R, int S, int stride, int pad);
 int        jit_prepare_plane(int H, int W, int R, int S, int stride, int pad);
 int        jit_compile_only(int H, int W, int R, int S, int stride, int pad);
 int        jit_cached_kernels();
 int        jit_launch_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
                             int H, int W, int R, int S, int stride, int pad, hipStream_t st);
+
+// ---- depthwise on small planes (at most 1024 elements): a run of planes per workgroup through LDS --------
 bool       small_planes_supported(int64_t planes, int planes_per_x, int H, int W, int R, int S, int stride, int Ho,
                                   int Wo);
 hipError_t launch_small_planes(const float* x, const float* w, float* y, int64_t planes, int n_filters, int H, int W,

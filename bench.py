@@ -59,6 +59,8 @@ SECOND_ROOF = {"depthwise_7x7": (VALU_F32_TFLOPS, "frac_alu_f32_plain_fma"),
 # profiles/hbm_traffic_all_kernels.txt), with the kernel source and its sha256 prefix at the time the
 # counters were taken.  A kernel whose source has changed since reports traffic = null.
 TRAFFIC = {
+    "depthwise_3x3": (207440308, "sw_sliding_plane.hip", "c19725ff48dea175"),
+    "depthwise_7x7": (206218314, "sw_sliding_plane.hip", "c19725ff48dea175"),
     "conv2d_64x64_3x3": (62453541, "sw_mfma_f32.hip", "c33152360085e7c7"),
     "conv2d_s8_128x128_3x3": (21145795, "sw_mfma_s8.hip", "5793f7bda96a651e"),
     "conv1d_k9": (33896715, "sw_sliding1d.hip", "eeb6f644a27cb890"),
@@ -71,6 +73,8 @@ TRAFFIC = {
 def measured_traffic(name):
     import hashlib
 
+    if name not in TRAFFIC:
+        return None
     nbytes, src, digest = TRAFFIC[name]
     path = os.path.join(ROOT, "paper_2310_05218_amd", "csrc", src)
     try:

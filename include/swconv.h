@@ -245,6 +245,26 @@ int sw_jit_compile_check(int H, int W, int R, int S, int stride, int pad);
 /* Number of generated kernels this process holds. */
 int sw_jit_cached_kernels(void);
 
+/*
+ * The quantised convolution on channel-last tensors (paper, sections 1.1 and 3; the
+ * layout quantised inference engines keep their activations in):
+ *     x: [N,H,W,C_in] int8;  w: [C_out,R,S,C_in] int8;
+ *     y: [N,H_out,W_out,C_out] int32 (sw_conv2d_s8_nhwc) or int8 (…_requant),
+ * the same sums as sw_conv2d_s8 / sw_conv2d_s8_requant on the transposed tensors, bit
+ * for bit.  The matrix instruction reads 16 consecutive channels per lane, which in
+ * this layout are 16 consecutive bytes: nothing is transposed on the way.  Note the
+ * argument order (H, W before the channel counts).  Errors as the channel-first
+ * calls.  C_in a multiple of 32, 16-byte aligned x and w and the filters of 64 output
+ * channels within 96 KB run on the matrix cores (any extent and stride, C_out any);
+ * every other valid shape one thread per output.
+ */
+int sw_conv2d_s8_nhwc(const int8_t* x, const int8_t* w, int32_t* y,
+                      int N, int H, int W, int C_in, int C_out, int R, int S,
+                      int stride, int pad, void* hip_stream);
+int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* bias, const float* scale, int8_t* y,
+                              int N, int H, int W, int C_in, int C_out, int R, int S,
+                              int stride, int pad, int relu, void* hip_stream);
+
 /* Output extent of one axis; <= 0 means the filter does not fit (or bad arguments). */
 int64_t sw_out_dim(int64_t in, int k, int stride, int pad);
 

@@ -272,3 +272,22 @@ def conv2d_depthwise_bias_relu(x, w, bias, stride: int = 1, pad: int = 0, relu: 
     if rc:
         raise ValueError(f"oracle_bias_relu rejected the arguments (code {rc})")
     return y, d
+
+
+def conv2d_s8_nhwc(x, w, stride: int = 1, pad: int = 0):
+    """The int8 convolution on channel-last tensors: x [N,H,W,C_in], w [C_out,R,S,C_in] -> y [N,H_out,W_out,C_out]
+    int32.  Only the axes are permuted around conv2d_s8 (a change of layout, no arithmetic)."""
+    x = _as(x, np.int8, 4)
+    w = _as(w, np.int8, 4)
+    y = conv2d_s8(np.ascontiguousarray(x.transpose(0, 3, 1, 2)), np.ascontiguousarray(w.transpose(0, 3, 1, 2)),
+                  stride, pad)
+    return np.ascontiguousarray(y.transpose(0, 2, 3, 1))
+
+
+def conv2d_s8_nhwc_requant(x, w, bias, scale, stride: int = 1, pad: int = 0, relu: bool = False):
+    """conv2d_s8_requant on channel-last tensors (axes permuted, no arithmetic added)."""
+    x = _as(x, np.int8, 4)
+    w = _as(w, np.int8, 4)
+    q = conv2d_s8_requant(np.ascontiguousarray(x.transpose(0, 3, 1, 2)), np.ascontiguousarray(w.transpose(0, 3, 1, 2)),
+                          bias, scale, stride, pad, relu)
+    return np.ascontiguousarray(q.transpose(0, 2, 3, 1))

@@ -17,7 +17,7 @@ SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN, SW_ERR_ALIAS, SW_ER
 SW_POOL_AVG, SW_POOL_MAX = 0, 1
 
 EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
-           "sw_conv2d_s8_requant", "sw_conv2d_bias_relu", "sw_conv2d_depthwise_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
+           "sw_conv2d_s8_requant", "sw_conv2d_s8_nhwc", "sw_conv2d_s8_nhwc_requant", "sw_conv2d_bias_relu", "sw_conv2d_depthwise_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
            "sw_conv2d_depthwise_bf16", "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
            "sw_jit_cached_kernels",
            "sw_out_dim", "sw_workspace_bytes", "sw_status_string", "sw_version")
@@ -69,6 +69,10 @@ def lib() -> ctypes.CDLL:
     L.sw_jit_cached_kernels.argtypes = []
     L.sw_conv2d_s8.restype = i32
     L.sw_conv2d_s8.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
+    L.sw_conv2d_s8_nhwc.restype = i32
+    L.sw_conv2d_s8_nhwc.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
+    L.sw_conv2d_s8_nhwc_requant.restype = i32
+    L.sw_conv2d_s8_nhwc_requant.argtypes = [vp, vp, vp, vp, vp] + [i32] * 10 + [vp]
     L.sw_conv2d_s8_requant.restype = i32
     L.sw_conv2d_s8_requant.argtypes = [vp, vp, vp, vp, vp] + [i32] * 10 + [vp]
     L.sw_out_dim.restype = i64
@@ -85,6 +89,36 @@ def lib() -> ctypes.CDLL:
 
 def status_string(status: int) -> str:
     return lib().sw_status_string(int(status)).decode()
+
+
+def sw_conv2d_s8_nhwc(x, w, stride: int = 1, pad: int = 0, bias=None, scale=None, relu: bool = False, out=None,
+                      stream=None):
+    """Channel-last int8 convolution: x [N,H,W,C_in] int8, w [C_out,R,S,C_in] int8 -> y [N,H_out,W_out,C_out]
+    int32 (exact sums), or int8 when `scale` ([C_out] fp32, with optional int32 `bias`) is given:
+    clamp(rne(scale * float(acc + bias)), 0 if relu else -128, 127)."""
+    import torch
+
+    N, H, W, C_in = x.shape
+    C_out, R, S, C_in_w = w.shape
+    if C_in_w != C_in:
+        raise ValueError("channel mismatch between x and w")
+    rq = scale is not None
+    name = "sw_conv2d_s8_nhwc_requant" if rq else "sw_conv2d_s8_nhwc"
+    if out is None:
+        out = torch.empty(_out_shape(name, N, sw_out_dim(H, R, stride, pad), sw_out_dim(W, S, stride, pad), C_out),
+                          dtype=torch.int8 if rq else torch.int32, device=x.device)
+    if rq:
+        rc = lib().sw_conv2d_s8_nhwc_requant(_dev(x, torch.int8, 4, "x"), _dev(w, torch.int8, 4, "w"),
+                                             _dev(bias, torch.int32, 1, "bias") if bias is not None else None,
+                                             _dev(scale, torch.float32, 1, "scale"), _dev(out, torch.int8, 4, "y"),
+                                             N, H, W, C_in, C_out, R, S, stride, pad, 1 if relu else 0,
+                                             _stream(stream))
+    else:
+        rc = lib().sw_conv2d_s8_nhwc(_dev(x, torch.int8, 4, "x"), _dev(w, torch.int8, 4, "w"),
+                                     _dev(out, torch.int32, 4, "y"), N, H, W, C_in, C_out, R, S, stride, pad,
+                                     _stream(stream))
+    _check(rc, name)
+    return out
 
 
 def sw_conv2d_s8_requant(x, w, bias, scale, stride: int = 1, pad: int = 0, relu: bool = False, out=None, stream=None):

@@ -289,6 +289,43 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, 
     return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
 }
 
+// int8 convolution on channel-last tensors; bias/scale == nullptr and y8 == nullptr: int32 sums
+static int run_s8_nhwc(const int8_t* x, const int8_t* w, const int32_t* bias, const float* scale, int32_t* y, int8_t* y8,
+                       int N, int H, int W, int C_in, int C_out, int R, int S, int stride, int pad, int relu,
+                       void* hip_stream)
+{
+    Conv2dShape s;
+    const void* out = y8 ? static_cast<const void*>(y8) : static_cast<const void*>(y);
+    const int rc = check_conv2d(x, w, out, N, C_in, C_out, H, W, R, S, stride, pad, false, 1, y8 ? 1 : 4, &s);
+    if (rc != SW_OK) return rc;
+    if ((int64_t)C_in * R * S > 131071) return SW_ERR_SHAPE;  // 131072 * 2^14 = 2^31 leaves int32
+    Requant rq{bias, scale, relu != 0};
+    if (y8) {
+        if (misaligned(scale, 4) || (bias && misaligned(bias, 4))) return SW_ERR_ALIGN;
+        const int64_t ny = (int64_t)N * C_out * s.Ho * s.Wo;
+        if (overlaps(y8, ny, scale, (int64_t)C_out * 4) || (bias && overlaps(y8, ny, bias, (int64_t)C_out * 4)))
+            return SW_ERR_ALIAS;
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (!force_direct() && mfma_s8_nhwc_supported(x, w, s))
+        return launch_status(launch_mfma_s8_nhwc(x, w, y, y8, y8 ? &rq : nullptr, s, st));
+    return launch_status(launch_direct_s8_nhwc(x, w, y, y8, y8 ? &rq : nullptr, s, st));
+}
+
+int sw_conv2d_s8_nhwc(const int8_t* x, const int8_t* w, int32_t* y, int N, int H, int W, int C_in, int C_out, int R,
+                      int S, int stride, int pad, void* hip_stream)
+{
+    return run_s8_nhwc(x, w, nullptr, nullptr, y, nullptr, N, H, W, C_in, C_out, R, S, stride, pad, 0, hip_stream);
+}
+
+int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* bias, const float* scale, int8_t* y,
+                              int N, int H, int W, int C_in, int C_out, int R, int S, int stride, int pad, int relu,
+                              void* hip_stream)
+{
+    if (!scale || !y) return SW_ERR_NULL;
+    return run_s8_nhwc(x, w, bias, scale, nullptr, y, N, H, W, C_in, C_out, R, S, stride, pad, relu, hip_stream);
+}
+
 int sw_conv2d_depthwise_bias_relu(const float* x, const float* w, const float* bias, float* y, int N, int C, int H,
                                   int W, int R, int S, int stride, int pad, int relu, void* hip_stream)
 {

@@ -102,6 +102,13 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0});
 
+// ---- int8 on channel-last tensors (x [N,H,W,C_in], w [C_out,R,S,C_in], y [N,Ho,Wo,C_out]); rq == nullptr: int32 out
+bool       mfma_s8_nhwc_supported(const int8_t* x, const int8_t* w, const Conv2dShape& s);
+hipError_t launch_mfma_s8_nhwc(const int8_t* x, const int8_t* w, int32_t* y, int8_t* y8, const Requant* rq,
+                               const Conv2dShape& s, hipStream_t st);
+hipError_t launch_direct_s8_nhwc(const int8_t* x, const int8_t* w, int32_t* y, int8_t* y8, const Requant* rq,
+                                 const Conv2dShape& s, hipStream_t st);
+
 // ---- bf16 activations (bit patterns in unsigned short), fp32 filters and accumulation --------------------
 bool       sliding_plane_bf16_supported(const void* x, const void* y, int W, int R, int S, int stride, int pad, int Ho,
                                         int Wo);

@@ -149,6 +149,26 @@ def test_depthwise_argument_errors(L):
     assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
 
 
+def test_s8_nhwc_argument_errors(L):
+    f, g = L.sw_conv2d_s8_nhwc, L.sw_conv2d_s8_nhwc_requant
+    B_, SC = 0x2100000, 0x2200000
+    ok = (2, 8, 8, 32, 64, 3, 3, 1, 1)          # N, H, W, C_in, C_out, R, S, stride, pad
+    assert f(None, W_, Y, *ok, None) == B.SW_ERR_NULL
+    assert g(X, W_, B_, None, Y, *ok, 0, None) == B.SW_ERR_NULL
+    assert g(X, W_, B_, SC, None, *ok, 0, None) == B.SW_ERR_NULL
+    for i in range(8):
+        bad = list(ok)
+        bad[i] = 0
+        assert f(X, W_, Y, *bad, None) == B.SW_ERR_SHAPE, i
+        assert g(X, W_, B_, SC, Y, *bad, 0, None) == B.SW_ERR_SHAPE, i
+    assert f(X, W_, Y + 2, *ok, None) == B.SW_ERR_ALIGN
+    assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
+    assert g(X, W_, B_, SC + 2, Y, *ok, 0, None) == B.SW_ERR_ALIGN
+    assert g(X, W_, B_, Y + 8, Y, *ok, 0, None) == B.SW_ERR_ALIAS
+    # 131072 products of magnitude 2^14 could leave int32
+    assert f(X, W_, Y, 1, 64, 64, 4096, 8, 6, 6, 1, 0, None) == B.SW_ERR_SHAPE
+
+
 def test_bf16_argument_errors(L):
     f = L.sw_conv2d_depthwise_bf16
     ok = (2, 16, 8, 8, 3, 3, 1, 1)

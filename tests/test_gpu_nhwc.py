@@ -1,0 +1,101 @@
+"""GPU parity of the channel-last int8 convolution (sw_conv2d_s8_nhwc, int32 and requantised int8 output) against
+the CPU oracle: bit-exact."""
+import numpy as np
+import pytest
+
+from paper_2310_05218_amd import inputs
+from parity import assert_guards_intact, guarded_empty
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as _t
+
+    assert _t.cuda.is_available(), "these tests need the GPU"
+    return _t
+
+
+@pytest.fixture(scope="module")
+def sw():
+    import paper_2310_05218_amd as _sw
+    from paper_2310_05218_amd import binding
+
+    binding.lib()            # fails loudly if the library is not built
+    return _sw
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+CASES = [
+    # N, H, W, C_in, C_out, R, S, stride, pad
+    (2, 28, 28, 128, 128, 3, 3, 1, 1),   # workload 5's layer, channel-last: 7-row bands, two channel blocks
+    (1, 28, 28, 32, 64, 3, 3, 1, 1),     # one K step
+    (2, 14, 14, 64, 96, 3, 3, 1, 1),     # the whole image in one band, ragged channel block
+    (1, 56, 56, 64, 64, 3, 3, 1, 1),     # 4-row bands (224 pixels)
+    (2, 30, 41, 32, 40, 3, 3, 1, 1),     # blocks of 32 pixels that span rows, ragged last block
+    (1, 57, 57, 64, 128, 3, 3, 2, 1),    # stride 2
+    (1, 20, 20, 32, 32, 5, 5, 1, 2),     # 25 taps
+    (2, 19, 23, 64, 70, 1, 1, 1, 0),     # pointwise
+    (1, 33, 17, 32, 5, 7, 3, 2, 3),      # rectangular filter, few output channels
+    (1, 9, 300, 32, 64, 3, 3, 1, 1),     # rows wider than 256 outputs: one thread per output
+    (1, 12, 12, 24, 16, 3, 3, 1, 1),     # C_in not a multiple of 32: one thread per output
+    (1, 5, 5, 32, 8, 5, 5, 1, 0),        # a single output pixel
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_s8_nhwc_is_bit_exact(torch, sw, oracle, case):
+    N, H, W, C_in, C_out, R, S, stride, pad = case
+    x = inputs.uniform_s8((N, H, W, C_in), 5001)
+    w = inputs.uniform_s8((C_out, R, S, C_in), 5002)
+    y_ref = oracle.conv2d_s8_nhwc(x, w, stride, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.int32)
+    sw.sw_conv2d_s8_nhwc(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert np.array_equal(out.cpu().numpy(), y_ref), f"s8 nhwc {case}"
+
+
+@pytest.mark.parametrize("relu", [False, True])
+@pytest.mark.parametrize("case", CASES[:6] + CASES[9:11])
+def test_s8_nhwc_requant_is_bit_exact(torch, sw, oracle, case, relu):
+    N, H, W, C_in, C_out, R, S, stride, pad = case
+    x = inputs.uniform_s8((N, H, W, C_in), 5011)
+    w = inputs.uniform_s8((C_out, R, S, C_in), 5012)
+    rng = np.random.default_rng(5013)
+    std = (C_in * R * S) ** 0.5 * 5461.0                       # of a sum of products of two uniform int8
+    bias = rng.integers(-int(std), int(std), size=C_out).astype(np.int32)
+    scale = (rng.uniform(0.5, 2.0, size=C_out) * 60.0 / std).astype(np.float32)
+    q_ref = oracle.conv2d_s8_nhwc_requant(x, w, bias, scale, stride, pad, relu)
+    buf, out, front, n, s = guarded_empty(torch, q_ref.shape, torch.int8, fill=77)
+    sw.sw_conv2d_s8_nhwc(dev(torch, x), dev(torch, w), stride, pad, bias=dev(torch, bias), scale=dev(torch, scale),
+                         relu=relu, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    q = out.cpu().numpy()
+    assert np.array_equal(q, q_ref), f"s8 nhwc requant {case} relu={relu}"
+    assert len(np.unique(q)) > 50
+
+
+def test_s8_nhwc_extremes(torch, sw, oracle):
+    """All -128: every product is +16384, the largest sum a 3x3 x 128-channel layer can reach."""
+    x = np.full((1, 8, 8, 128), -128, np.int8)
+    w = np.full((64, 3, 3, 128), -128, np.int8)
+    y = sw.sw_conv2d_s8_nhwc(dev(torch, x), dev(torch, w), 1, 1).cpu().numpy()
+    assert y.max() == 9 * 128 * 16384 and np.array_equal(y, oracle.conv2d_s8_nhwc(x, w, 1, 1))
+
+
+def test_s8_nhwc_full_size_agrees_with_the_channel_first_call(torch, sw, oracle):
+    """Workload 5 at full size in both layouts: the two entry points must give the same sums; sampled images are
+    also checked against the oracle."""
+    x, w = inputs.workload5()
+    xd, wd = dev(torch, x), dev(torch, w)
+    y_cf = sw.sw_conv2d_s8(xd, wd, 1, 1)
+    y_cl = sw.sw_conv2d_s8_nhwc(xd.permute(0, 2, 3, 1).contiguous(), wd.permute(0, 2, 3, 1).contiguous(), 1, 1)
+    assert torch.equal(y_cl.permute(0, 3, 1, 2), y_cf)
+    for n in (0, 31):
+        assert np.array_equal(y_cf[n:n + 1].cpu().numpy(), oracle.conv2d_s8(x[n:n + 1], w, 1, 1))

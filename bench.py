@@ -243,8 +243,9 @@ def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, st
     N, C, H, W = shape
     dil = 2 if kind == "conv_dil" else 1            # the dilated row: taps two positions apart
     Ho, Wo = (H + 2 * pad - dil * (R - 1) - 1) // stride + 1, (W + 2 * pad - dil * (R - 1) - 1) // stride + 1
-    s8 = kind in ("conv_s8", "conv_s8_rq")
-    rq = kind == "conv_s8_rq"
+    s8 = kind in ("conv_s8", "conv_s8_rq", "conv_s8_nhwc", "conv_s8_nhwc_rq")
+    rq = kind in ("conv_s8_rq", "conv_s8_nhwc_rq")
+    nhwc = kind in ("conv_s8_nhwc", "conv_s8_nhwc_rq")      # the same layer on channel-last tensors
     br = kind == "conv_br"
     if s8:
         x = inputs.uniform_s8(shape, inputs.seed_for(7, idx))
@@ -257,6 +258,13 @@ def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, st
             bd, sd = torch.from_numpy(bias).cuda(), torch.from_numpy(scale).cuda()
             call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_s8_requant(a, b, bd, sd, st_, p_, True, out=out)
             odt = torch.int8
+        if nhwc:
+            x = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+            w = np.ascontiguousarray(w.transpose(0, 2, 3, 1))
+            if rq:
+                call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_s8_nhwc(a, b, st_, p_, bias=bd, scale=sd, relu=True, out=out)
+            else:
+                call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_s8_nhwc(a, b, st_, p_, out=out)
     else:
         x = inputs.normal_f32(shape, inputs.seed_for(7, idx))
         w = inputs.normal_f32((C_out, C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
@@ -269,7 +277,13 @@ def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, st
             call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_bias_relu(a, b, bd, st_, p_, True, out=out)
     xs, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
     y = call(xs[:1].contiguous(), wd, stride, pad).cpu().numpy()
-    if rq:
+    if nhwc and rq:
+        assert np.array_equal(y, oracle.conv2d_s8_nhwc_requant(x[:1], w, bias, scale, stride, pad, True)), name
+        err = 0.0
+    elif nhwc:
+        assert np.array_equal(y, oracle.conv2d_s8_nhwc(x[:1], w, stride, pad)), name
+        err = 0.0
+    elif rq:
         assert np.array_equal(y, oracle.conv2d_s8_requant(x[:1], w, bias, scale, stride, pad, True)), name
         err = 0.0
     elif s8:
@@ -286,7 +300,8 @@ def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, st
         assert err <= 2e-5, (name, err)
     nbytes = x.nbytes + w.nbytes + N * C_out * Ho * Wo * (1 if rq else 4)
     nsets = min(16, max(3, -(-COLD_ROTATION_BYTES // nbytes)))
-    sets = [{"x": xs if i == 0 else xs.clone(), "y": torch.empty((N, C_out, Ho, Wo), dtype=odt, device="cuda")}
+    oshape = (N, Ho, Wo, C_out) if nhwc else (N, C_out, Ho, Wo)
+    sets = [{"x": xs if i == 0 else xs.clone(), "y": torch.empty(oshape, dtype=odt, device="cuda")}
             for i in range(nsets)]
     us = time_kernel(torch, lambda s_: call(s_["x"], wd, stride, pad, out=s_["y"]), sets, 2 * nsets)
     ops = 2.0 * N * C_out * Ho * Wo * C * R * R
@@ -331,11 +346,15 @@ def strided_and_pooling_table(torch, sw):
         ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
         ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
         ("conv_s8_requant_3x3_128to128", "conv_s8_rq", (32, 128, 28, 28), 3, 1, 1, 128),
+        ("conv_s8_nhwc_3x3_128to128", "conv_s8_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
+        ("conv_s8_nhwc_requant_3x3_128to128", "conv_s8_nhwc_rq", (32, 128, 28, 28), 3, 1, 1, 128),
+        ("conv_s8_nhwc_3x3_s2_64to128", "conv_s8_nhwc", (32, 64, 56, 56), 3, 2, 1, 128),
+        ("conv_s8_nhwc_1x1_64to256", "conv_s8_nhwc", (32, 64, 56, 56), 1, 1, 0, 256),
     ]
     rows = []
     for idx, (name, kind, shape, R, stride, pad, *more) in enumerate(layers):
         N, C, H, W = shape
-        if kind in ("conv", "conv_br", "conv_dil", "conv_s8", "conv_s8_rq"):
+        if kind in ("conv", "conv_br", "conv_dil", "conv_s8", "conv_s8_rq", "conv_s8_nhwc", "conv_s8_nhwc_rq"):
             rows.append(_conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, stride, pad, more[0]))
             continue
         Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1

@@ -43,7 +43,8 @@ struct NhwcParams {
 };
 
 // RQ: the sums leave requantised to int8 (y8) instead of as int32 (y).
-template <bool RQ>
+// KS: K steps of 32 channels per tap (C_in / 32) when that is 1, 2 or 4; 0: any multiple of 32, at run time.
+template <bool RQ, int KS>
 __global__ __launch_bounds__(256, 1) void mfma_s8_nhwc_kernel(const int8_t* __restrict__ x,
                                                               const int8_t* __restrict__ w,
                                                               int32_t* __restrict__ y, int8_t* __restrict__ y8,
@@ -119,40 +120,129 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_nhwc_kernel(const int8_t* __re
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[b][v] = 0;
 
-    const int ksteps = P.C_in >> 5;
+    // Operands of one tap: KS K steps, the filter block and the wavefront's pixel blocks.  The operands of the
+    // next tap are on their way from LDS while the matrix instructions of this one run (two register sets, the
+    // tap loop unrolled by two); KS == 0: K steps at run time, read and multiplied one after the other.
+    struct Ops {
+        intx4 bq[KS > 0 ? KS : 1];
+        intx4 aq[KS > 0 ? KS : 1][kBlocksPerWave];
+    };
     int tap_x = 0, tap_w = 0, s = 0;                    // byte offsets of the tap in the window / in a filter row
-#pragma unroll 1
-    for (int tap = 0; tap < P.R * P.S; ++tap) {
-#pragma unroll 1
-        for (int k = 0; k < ksteps; ++k) {
-            const intx4 bq = *reinterpret_cast<const intx4*>(bsrc + tap_w + 32 * k);
-            intx4 aq[kBlocksPerWave];
-#pragma unroll
-            for (int b = 0; b < kBlocksPerWave; ++b)
-                aq[b] = *reinterpret_cast<const intx4*>(lx + aoff[b] + tap_x + 32 * k);
-#pragma unroll
-            for (int b = 0; b < kBlocksPerWave; ++b)
-                if (wp + 2 * b < nblocks)               // (wave-uniform)
-                    acc[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[b], bq, acc[b], 0, 0, 0);
-        }
+    auto next_tap = [&]() __attribute__((always_inline)) {
         tap_w += P.C_in;
         tap_x += P.CP;
         if (++s == P.S) { s = 0; tap_x += (P.IWp - P.S) * P.CP; }
+    };
+    auto load_ops = [&](Ops& o) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < KS; ++k) {
+            o.bq[k] = *reinterpret_cast<const intx4*>(bsrc + tap_w + 32 * k);
+#pragma unroll
+            for (int b = 0; b < kBlocksPerWave; ++b)
+                o.aq[k][b] = *reinterpret_cast<const intx4*>(lx + aoff[b] + tap_x + 32 * k);
+        }
+    };
+    auto multiply = [&](const Ops& o) __attribute__((always_inline)) {
+#pragma unroll
+        for (int k = 0; k < KS; ++k)
+#pragma unroll
+            for (int b = 0; b < kBlocksPerWave; ++b)
+                if (wp + 2 * b < nblocks)               // (wave-uniform)
+                    acc[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.aq[k][b], o.bq[k], acc[b], 0, 0, 0);
+    };
+    const int RS = P.R * P.S;
+    if constexpr (KS > 0) {
+        Ops o0, o1;
+        load_ops(o0);
+        int tap = 0;
+#pragma unroll 1
+        for (; tap + 2 <= RS; tap += 2) {
+            next_tap();
+            load_ops(o1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(o0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (tap + 2 < RS) {
+                next_tap();
+                load_ops(o0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(o1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (tap < RS) multiply(o0);                     // odd tap count: the last tap is already in o0
+    } else {
+        const int ksteps = P.C_in >> 5;
+#pragma unroll 1
+        for (int tap = 0; tap < RS; ++tap) {
+#pragma unroll 1
+            for (int k = 0; k < ksteps; ++k) {
+                const intx4 bq = *reinterpret_cast<const intx4*>(bsrc + tap_w + 32 * k);
+                intx4 aq[kBlocksPerWave];
+#pragma unroll
+                for (int b = 0; b < kBlocksPerWave; ++b)
+                    aq[b] = *reinterpret_cast<const intx4*>(lx + aoff[b] + tap_x + 32 * k);
+#pragma unroll
+                for (int b = 0; b < kBlocksPerWave; ++b)
+                    if (wp + 2 * b < nblocks)
+                        acc[b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq[b], bq, acc[b], 0, 0, 0);
+            }
+            next_tap();
+        }
     }
 
     // ---- store: register v of a lane is pixel 8*(v/4) + 4*lg + v%4 of the block, channel lj ----
     const int co = co0 + 32 * wn + lj;
-    if (co >= P.C_out) return;
     const int64_t pix0 = ((int64_t)n * P.Ho + oi0) * P.Wo;
+    if constexpr (!RQ) {
+        if (co >= P.C_out) return;
 #pragma unroll
-    for (int b = 0; b < kBlocksPerWave; ++b) {
-        if (wp + 2 * b >= nblocks) break;
+        for (int b = 0; b < kBlocksPerWave; ++b) {
+            if (wp + 2 * b >= nblocks) break;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int p = 32 * (wp + 2 * b) + 8 * (v >> 2) + 4 * lg + (v & 3);
-            if (p < npix) {
-                if (RQ) y8[(pix0 + p) * P.C_out + co] = requant_s8(acc[b][v], co, rq);
-                else y[(pix0 + p) * P.C_out + co] = acc[b][v];
+            for (int v = 0; v < 16; ++v) {
+                const int p = 32 * (wp + 2 * b) + 8 * (v >> 2) + 4 * lg + (v & 3);
+                if (p < npix) y[(pix0 + p) * P.C_out + co] = acc[b][v];
+            }
+        }
+    } else {
+        // int8 output: a lane holds one channel of four consecutive pixels in registers 4g .. 4g+3, and its bytes
+        // lie a whole pixel apart in memory.  Two exchanges inside each lane quad (DPP quad_perm) transpose the
+        // 4 x 4 block, so that lane k ends up with pixel k of the quad's four consecutive channels and stores them
+        // as one dword.  (All lanes take part; lanes past C_out or past the band only skip the store.)
+        const int cl = co < P.C_out ? co : P.C_out - 1;
+        const bool wide = P.C_out % 4 == 0 && reinterpret_cast<uintptr_t>(y8) % 4 == 0;
+        const int k = lane & 3;
+        const bool b0 = k & 1, b1 = k & 2;
+        const int cq = co0 + 32 * wn + (lj & ~3);               // first channel of the quad
+#pragma unroll
+        for (int b = 0; b < kBlocksPerWave; ++b) {
+            if (wp + 2 * b >= nblocks) break;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int p0 = 32 * (wp + 2 * b) + 8 * g + 4 * lg;   // pixel of register 4g
+                int r[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) r[t] = (int)requant_s8(acc[b][4 * g + t], cl, rq) & 255;
+                if (wide) {
+                    const int keep01 = b0 ? r[1] : r[0], send01 = b0 ? r[0] : r[1];
+                    const int keep23 = b0 ? r[3] : r[2], send23 = b0 ? r[2] : r[3];
+                    const int got01 = __builtin_amdgcn_mov_dpp(send01, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+                    const int got23 = __builtin_amdgcn_mov_dpp(send23, 0xB1, 0xF, 0xF, true);
+                    const int own_a = b1 ? keep23 : keep01, own_b = b1 ? got23 : got01;
+                    const int snd_a = b1 ? keep01 : keep23, snd_b = b1 ? got01 : got23;
+                    const int far_a = __builtin_amdgcn_mov_dpp(snd_a, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+                    const int far_b = __builtin_amdgcn_mov_dpp(snd_b, 0x4E, 0xF, 0xF, true);
+                    // pixel k of the channels of lanes k, k^1, k^2, k^3: byte j of the dword is the quad's channel j
+                    const unsigned word = (unsigned)own_a << (8 * k) | (unsigned)own_b << (8 * (k ^ 1)) |
+                                          (unsigned)far_a << (8 * (k ^ 2)) | (unsigned)far_b << (8 * (k ^ 3));
+                    if (p0 + k < npix && cq < P.C_out)
+                        *reinterpret_cast<unsigned*>(y8 + (pix0 + p0 + k) * P.C_out + cq) = word;
+                } else if (co < P.C_out) {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (p0 + t < npix) y8[(pix0 + p0 + t) * P.C_out + co] = (int8_t)r[t];
+                }
             }
         }
     }
@@ -238,16 +328,28 @@ NhwcPlan plan_nhwc(const Conv2dShape& s)
     return a;
 }
 
+template <bool RQ, int KS>
+hipError_t launch_nhwc_ks(const int8_t* x, const int8_t* w, int32_t* y, int8_t* y8, const Requant& rq, const NhwcPlan& a,
+                          const Conv2dShape& s, hipStream_t st)
+{
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_nhwc_kernel<RQ, KS>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudgetNhwc);
+    if (attr != hipSuccess) return attr;
+    dim3 grid((unsigned)a.bands, (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
+    hipLaunchKernelGGL((mfma_s8_nhwc_kernel<RQ, KS>), grid, dim3(256), a.lds, st, x, w, y, y8, a.P, rq);
+    return hipGetLastError();
+}
+
 template <bool RQ>
 hipError_t launch_nhwc(const int8_t* x, const int8_t* w, int32_t* y, int8_t* y8, const Requant& rq, const NhwcPlan& a,
                        const Conv2dShape& s, hipStream_t st)
 {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_nhwc_kernel<RQ>),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudgetNhwc);
-    if (attr != hipSuccess) return attr;
-    dim3 grid((unsigned)a.bands, (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
-    hipLaunchKernelGGL((mfma_s8_nhwc_kernel<RQ>), grid, dim3(256), a.lds, st, x, w, y, y8, a.P, rq);
-    return hipGetLastError();
+    switch (s.C_in / 32) {
+        case 1: return launch_nhwc_ks<RQ, 1>(x, w, y, y8, rq, a, s, st);
+        case 2: return launch_nhwc_ks<RQ, 2>(x, w, y, y8, rq, a, s, st);
+        case 4: return launch_nhwc_ks<RQ, 4>(x, w, y, y8, rq, a, s, st);
+        default: return launch_nhwc_ks<RQ, 0>(x, w, y, y8, rq, a, s, st);
+    }
 }
 
 }  // namespace

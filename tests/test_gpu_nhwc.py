@@ -61,7 +61,7 @@ def test_s8_nhwc_is_bit_exact(torch, sw, oracle, case):
 
 
 @pytest.mark.parametrize("relu", [False, True])
-@pytest.mark.parametrize("case", CASES[:6] + CASES[9:11])
+@pytest.mark.parametrize("case", CASES)
 def test_s8_nhwc_requant_is_bit_exact(torch, sw, oracle, case, relu):
     N, H, W, C_in, C_out, R, S, stride, pad = case
     x = inputs.uniform_s8((N, H, W, C_in), 5011)
@@ -78,7 +78,7 @@ def test_s8_nhwc_requant_is_bit_exact(torch, sw, oracle, case, relu):
     assert_guards_intact(buf, front, n, s)
     q = out.cpu().numpy()
     assert np.array_equal(q, q_ref), f"s8 nhwc requant {case} relu={relu}"
-    assert len(np.unique(q)) > 50
+    assert len(np.unique(q)) > (50 if q.size > 2000 else 5)
 
 
 def test_s8_nhwc_extremes(torch, sw, oracle):

@@ -191,11 +191,29 @@ __global__ __launch_bounds__(256) void mfma_f32_any_kernel(const float* __restri
     if (!p_ok) return;
     const int HoWo = P.Ho * P.Wo;
     float* yp = y + ((int64_t)n * P.C_out + co0) * HoWo + (row0 + pi) * P.Wo + col0 + pj;
+    if (P.ep.bias != nullptr || P.ep.relu != 0) {
+        // the lane's 32 biases are read together (one wait), then added, rectified and stored
+        float b0[16], b1[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
+            b0[v] = (P.ep.bias && co < P.C_out) ? P.ep.bias[co] : 0.f;
+            b1[v] = (P.ep.bias && co + 32 < P.C_out) ? P.ep.bias[co + 32] : 0.f;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int co = 8 * (v >> 2) + 4 * kk + (v & 3);
+            const float t0 = acc0[v] + b0[v], t1 = acc1[v] + b1[v];
+            if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = P.ep.relu ? fmaxf(t0, 0.f) : t0;
+            if (co0 + 32 + co < P.C_out) yp[(int64_t)(32 + co) * HoWo] = P.ep.relu ? fmaxf(t1, 0.f) : t1;
+        }
+        return;
+    }
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int co = 8 * (v >> 2) + 4 * kk + (v & 3);
-        if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = apply_epilogue(acc0[v], co0 + co, P.ep);
-        if (co0 + 32 + co < P.C_out) yp[(int64_t)(32 + co) * HoWo] = apply_epilogue(acc1[v], co0 + 32 + co, P.ep);
+        if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = acc0[v];
+        if (co0 + 32 + co < P.C_out) yp[(int64_t)(32 + co) * HoWo] = acc1[v];
     }
 }
 

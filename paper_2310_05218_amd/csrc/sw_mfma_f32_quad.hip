@@ -13,6 +13,8 @@
 // multiplies.  No alignment of x or w is needed; channels beyond C_in and C_out are zero-filled.
 #include "swconv_internal.h"
 
+#include <cstdlib>
+
 namespace swconv {
 
 namespace {
@@ -32,20 +34,27 @@ struct QuadParams {
     FastDiv by_tiles_x, by_TW, by_IW, by_win, by_RS, by_QRS;
 };
 
-template <int CK>
-__global__ __launch_bounds__(256) void mfma_f32_quad_kernel(const float* __restrict__ x, const float* __restrict__ w,
-                                                            float* __restrict__ y, const QuadParams P)
+// SPLIT: the workgroup has eight wavefronts, four that only multiply and four that only load.  A wavefront that
+// issues the loads of the next chunk sits in their issue until the memory system has taken them (thousands of cycles
+// when the launch runs at the HBM rate); in a wavefront of its own that wait holds no matrix instruction back.  The
+// loaders copy chunk c + 1 into the second LDS buffer while the others multiply chunk c; one barrier per chunk.
+template <int CK, bool SPLIT>
+__global__ __launch_bounds__(SPLIT ? 512 : 256, SPLIT ? 4 : 2) void mfma_f32_quad_kernel(const float* __restrict__ x,
+                                                                          const float* __restrict__ w,
+                                                                          float* __restrict__ y, const QuadParams P)
 {
     constexpr int Q = CK / 4;                   // channel quads per chunk
     constexpr int G = CK / 8;                   // groups of eight channels = four matrix steps
     extern __shared__ __attribute__((aligned(16))) float smem[];
     const int RS = P.R * P.S;
     const int WP = P.IH * P.IW;                 // window pixels
-    floatx4* xs = reinterpret_cast<floatx4*>(smem);      // [Q][WP]
-    floatx4* ws = xs + Q * WP;                           // [RS][Q][64]
+    const int BUF = Q * WP + RS * Q * 64;                // floatx4 per LDS buffer: window [Q][WP], filters [RS][Q][64]
+    floatx4* xs = reinterpret_cast<floatx4*>(smem);
+    floatx4* ws = xs + Q * WP;
 
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int tid = SPLIT ? (threadIdx.x & 255) : threadIdx.x;   // index among the loading (or all) threads
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool loader = SPLIT && wave >= 4;
     const int lj = lane & 31, kk = lane >> 5;   // row/column inside a 32 x 32 block, K lane
 
     const int ty = fast_div(blockIdx.x, P.by_tiles_x);
@@ -56,11 +65,11 @@ __global__ __launch_bounds__(256) void mfma_f32_quad_kernel(const float* __restr
     const int grow0 = row0 * P.stride - P.pad, gcol0 = col0 * P.stride - P.pad;
 
     const int tile_px = P.TH * P.TW;
-    const int p = wave * 32 + lj;
+    const int p = (wave & 3) * 32 + lj;
     const int pi = fast_div(p, P.by_TW), pj = p - pi * P.TW;
     const bool p_ok = p < tile_px && row0 + pi < P.Ho && col0 + pj < P.Wo;
     const int pixoff = p_ok ? (pi * P.stride) * P.IW + pj * P.stride : 0;
-    const bool wave_live = __builtin_amdgcn_readfirstlane(wave * 32) < tile_px;
+    const bool wave_live = __builtin_amdgcn_readfirstlane((wave & 3) * 32) < tile_px;
 
     floatx16 acc0, acc1;
 #pragma unroll
@@ -116,21 +125,21 @@ __global__ __launch_bounds__(256) void mfma_f32_quad_kernel(const float* __restr
             }
         }
     };
-    auto stage = [&]() __attribute__((always_inline)) {
+    auto stage = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < kXS; ++u)
-            if (tid + 256 * u < Q * WP) xs[tid + 256 * u] = xv[u];
+            if (tid + 256 * u < Q * WP) xs[buf * BUF + tid + 256 * u] = xv[u];
 #pragma unroll
         for (int u = 0; u < kWS; ++u)
-            if (tid + 256 * u < 64 * Q * RS) ws[wd[u]] = wv[u];
+            if (tid + 256 * u < 64 * Q * RS) ws[buf * BUF + wd[u]] = wv[u];
     };
 
     // one tap of one group of eight channels: 2 x 4 matrix steps; the operands of the next (tap, group) are read
     // from LDS before these are multiplied
-    auto multiply = [&]() __attribute__((always_inline)) {
+    auto multiply = [&](int buf) __attribute__((always_inline)) {
         if (!wave_live) return;
-        const floatx4* bp = xs + kk * WP + pixoff;
-        const floatx4* ap = ws + kk * 64 + lj;
+        const floatx4* bp = xs + buf * BUF + kk * WP + pixoff;
+        const floatx4* ap = ws + buf * BUF + kk * 64 + lj;
         floatx4 a0 = ap[0], a1 = ap[32], b = bp[0];
         int toff = 0, s = 0;
 #pragma unroll 1
@@ -161,13 +170,36 @@ __global__ __launch_bounds__(256) void mfma_f32_quad_kernel(const float* __restr
         }
     };
 
-    fetch(0);
-    for (int ci0 = 0; ci0 < P.C_in; ci0 += CK) {
-        stage();
+    if constexpr (!SPLIT) {
+        fetch(0);
+        for (int ci0 = 0; ci0 < P.C_in; ci0 += CK) {
+            stage(0);
+            __syncthreads();
+            if (ci0 + CK < P.C_in) fetch(ci0 + CK);
+            multiply(0);
+            __syncthreads();
+        }
+    } else {
+        // every wavefront passes 1 + chunks barriers
+        const int chunks = (P.C_in + CK - 1) / CK;
+        if (loader) {
+            fetch(0);
+            stage(0);
+            __syncthreads();
+            for (int c = 0; c < chunks; ++c) {
+                if (c + 1 < chunks) {
+                    fetch((c + 1) * CK);
+                    stage((c + 1) & 1);          // (read by the others in turn c - 1, which the last barrier ended)
+                }
+                __syncthreads();
+            }
+            return;
+        }
         __syncthreads();
-        if (ci0 + CK < P.C_in) fetch(ci0 + CK);
-        multiply();
-        __syncthreads();
+        for (int c = 0; c < chunks; ++c) {
+            multiply(c & 1);
+            __syncthreads();
+        }
     }
 
     // ---- store: register v of a lane is output channel 8*(v/4) + 4*kk + v%4 of the block, pixel lj
@@ -203,8 +235,15 @@ __global__ __launch_bounds__(256) void mfma_f32_quad_kernel(const float* __restr
 struct QuadPlan {
     int TH, TW, IH, IW, CK, tiles_x, tiles_y;
     size_t lds;
-    bool ok;
+    bool ok, split;
 };
+
+// SWCONV_NO_SPLIT=1 keeps the four-wavefront variant (A/B checks)
+bool no_split_kernel()
+{
+    static const bool v = [] { const char* e = getenv("SWCONV_NO_SPLIT"); return e && e[0] == '1'; }();
+    return v;
+}
 
 QuadPlan plan_quad(const Conv2dShape& s)
 {
@@ -223,6 +262,11 @@ QuadPlan plan_quad(const Conv2dShape& s)
     };
     while (!fits() && a.CK > 8) a.CK /= 2;      // (a window that needs more staging slots goes to the other kernel)
     a.lds = ((size_t)(a.CK / 4) * a.IH * a.IW + (size_t)RS * (a.CK / 4) * 64) * 16;
+    // two buffers, loaders a chunk ahead: pays where a chunk has several taps to multiply (14 x 14 x 256 3x3: 143 ->
+    // 132 us, 7 x 7 x 512: 280 -> 246 us); with one tap per chunk (1x1) the loaders cannot keep enough bytes in flight
+    // from one chunk ahead and the launch is slower (74 -> 103 us at 56 x 56 x 256 -> 64)
+    a.split = RS > 1 && 2 * a.lds <= (size_t)kLdsBudget && !no_split_kernel();
+    if (a.split) a.lds *= 2;
     a.tiles_x = (s.Wo + a.TW - 1) / a.TW;
     a.tiles_y = (s.Ho + a.TH - 1) / a.TH;
     a.ok = fits() && a.CK * RS <= 96 && a.lds <= (size_t)kLdsBudget &&
@@ -248,7 +292,10 @@ hipError_t launch_quad(const float* x, const float* w, float* y, const Conv2dSha
     P.by_RS = make_fastdiv(s.R * s.S);
     P.by_QRS = make_fastdiv((CK / 4) * s.R * s.S);
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
-    hipLaunchKernelGGL((mfma_f32_quad_kernel<CK>), grid, dim3(256), a.lds, st, x, w, y, P);
+    if (a.split)
+        hipLaunchKernelGGL((mfma_f32_quad_kernel<CK, true>), grid, dim3(512), a.lds, st, x, w, y, P);
+    else
+        hipLaunchKernelGGL((mfma_f32_quad_kernel<CK, false>), grid, dim3(256), a.lds, st, x, w, y, P);
     return hipGetLastError();
 }
 

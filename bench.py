@@ -556,6 +556,21 @@ def main():
 
     if not args.no_detail:
         table = []
+        copy_cache = {}
+
+        def copy_gbs(nbytes):
+            """What a plain device copy that moves the same number of bytes reaches on this GPU, cold (half read,
+            half written; torch's elementwise kernel): the measured-achievable HBM rate beside the datasheet's."""
+            n_el = max(1024, int(nbytes) // 8)
+            if n_el not in copy_cache:
+                need = min(32, max(3, -(-COLD_ROTATION_BYTES // (8 * n_el))))
+                cs = [{"a": torch.empty(n_el, device="cuda").normal_(), "b": torch.empty(n_el, device="cuda")}
+                      for _ in range(need)]
+                us = time_kernel(torch, lambda d: torch.mul(d["a"], 1.0, out=d["b"]), cs, max(50, 2 * need))
+                copy_cache[n_el] = 8.0 * n_el / us / 1e3
+                del cs
+            return copy_cache[n_el]
+
         for n, fn in ls:
             ops, nbytes, bound, peak, unit = work[n]
             reps = 200 if probe[n] < 200 else 50
@@ -570,6 +585,9 @@ def main():
             row["frac_hot"] = round((nbytes / hot / 1e3) / peak if bound == "hbm" else (ops / hot / 1e6) / peak, 4)
             if n in SECOND_ROOF:
                 row[SECOND_ROOF[n][1]] = round(ops / cold / 1e6 / SECOND_ROOF[n][0], 4)
+            if bound == "hbm":
+                row["copy_gbs_same_bytes"] = round(copy_gbs(nbytes), 1)
+                row["frac_of_copy"] = round((nbytes / cold / 1e3) / row["copy_gbs_same_bytes"], 4)
             row["traffic"] = measured_traffic(n)
             table.append(row)
         result["kernels"] = table

@@ -135,10 +135,19 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
     const int HW = H * W;
     const int8_t* xn = x + (int64_t)n * C_in * HW;
 
-    // zeroes the input window once: halo and out-of-image cells are never written again.  Called after the
-    // first global loads have been issued, so that it runs under their latency.
+    // zeroes the window cells that lie outside the image (the padding), once: the staging below writes every cell
+    // inside the image and no other, so the two never touch the same bytes and no barrier has to separate them.
+    // Called after the first global loads have been issued, so that it runs under their latency.
     auto zero_window = [&]() {
-        for (int i = tid; i < kXBytes / 16; i += 256) reinterpret_cast<intx4*>(lx)[i] = intx4{0, 0, 0, 0};
+        const int IWz = TW + 2, cells = (TH + 2) * IWz;
+        for (int i = tid; i < cells; i += 256) {
+            const int e = i / IWz, c = i - e * IWz;
+            const int gr = row0 - pad + e, gc = col0 - pad + c;
+            if (gr < 0 || gr >= H || gc < 0 || gc >= W) {
+#pragma unroll
+                for (int b = 0; b < kPitch; b += 16) *reinterpret_cast<intx4*>(lx + i * kPitch + b) = intx4{0, 0, 0, 0};
+            }
+        }
     };
 
     // ---- input staging plan: item = (16-channel group, window row, image column quad) ---------------
@@ -165,15 +174,16 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         xlds[k] = (e * IW + xc[k]) * kPitch + 16 * c16;
     }
 
-    // ---- weight staging: the workgroup's 64 x 576-byte block is copied in 16-byte pieces, piece
-    //      i*256 + tid per thread (coalesced); afterwards thread (co = tid/4, 16-channel group tid%4)
-    //      transposes its 144 bytes
+    // ---- weight staging: the workgroup's 64 x 576-byte block is copied in 16-byte pieces (coalesced);
+    //      afterwards thread (co = tid/4, 16-channel group tid%4) transposes its 144 bytes = pieces 9*tid .. 9*tid+8.
+    //      A wavefront copies exactly the 576 pieces its own lanes transpose (piece wave*576 + i*64 + lane), so the
+    //      raw copy needs no workgroup barrier: LDS operations of a wavefront complete in order.
     const int wco = tid >> 2, wc16 = tid & 3;
     const int8_t* wblk = w + (int64_t)(mb << 6) * C_in * 9;
     int woff[9];
 #pragma unroll
     for (int i = 0; i < 9; ++i) {
-        const int piece = i * 256 + tid;
+        const int piece = wave * 576 + i * 64 + lane;
         woff[i] = (piece / 36) * C_in * 9 + (piece % 36) * 16;
     }
 
@@ -212,7 +222,9 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         for (int v = 0; v < 16; ++v) acc[i][v] = 0;
 
     // registers -> LDS (with the byte transposes), then the chunk's 9 taps x 2 K steps
-    auto stage = [&](u32 (&xv)[XI][16], intx4 (&wv)[9], int coff) {
+    // (sync_after: a workgroup barrier after the transposed operands are in place; the resident variant stages two
+    // chunks before anybody reads and needs only the second one)
+    auto stage = [&](u32 (&xv)[XI][16], intx4 (&wv)[9], int coff, bool sync_after = true) {
 #pragma unroll
         for (int k = 0; k < XI; ++k) {
             if (xoff[k] >= 0) {
@@ -224,8 +236,8 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
             }
         }
 #pragma unroll
-        for (int i = 0; i < 9; ++i) *reinterpret_cast<intx4*>(lraw + (i * 256 + tid) * 16) = wv[i];
-        __syncthreads();
+        for (int i = 0; i < 9; ++i) *reinterpret_cast<intx4*>(lraw + (wave * 576 + i * 64 + lane) * 16) = wv[i];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // this wavefront's raw pieces are in LDS
         u32 raw[36];
 #pragma unroll
         for (int i = 0; i < 9; ++i) {
@@ -242,7 +254,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         *reinterpret_cast<intx4*>(wdst + 6 * 64 * kPitch) = wgather_tap<6>(raw);
         *reinterpret_cast<intx4*>(wdst + 7 * 64 * kPitch) = wgather_tap<7>(raw);
         *reinterpret_cast<intx4*>(wdst + 8 * 64 * kPitch) = wgather_tap<8>(raw);
-        __syncthreads();
+        if (sync_after) __syncthreads();
     };
     // 18 steps (9 taps x 2 K halves); the operands of step t+1 are read from LDS while step t multiplies
     auto load_step = [&](int step, intx4& a, intx4 (&bv)[kNBW]) {
@@ -277,8 +289,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         fetch(xv0, wv0, 0);
         fetch(xv1, wv1, kCK);
         zero_window();
-        __syncthreads();   // window zeroed
-        stage(xv0, wv0, 0);
+        stage(xv0, wv0, 0, false);
         stage(xv1, wv1, kCK);
         intx4 a[NSTEP];    // this wavefront's A operands for the whole K range
 #pragma unroll
@@ -407,7 +418,6 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
     fetch(xv0, wv0, 0);
     if (chunks > 1) fetch(xv1, wv1, kCK);
     zero_window();
-    __syncthreads();   // window zeroed
     for (int ch = 0; ch < chunks; ch += 2) {
         stage(xv0, wv0, 0);
         if (ch + 2 < chunks) fetch(xv0, wv0, (ch + 2) * kCK);

@@ -150,6 +150,28 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         }
     };
 
+    // ---- weight staging: the workgroup's 64 x 576-byte block is copied in 16-byte pieces (coalesced);
+    //      afterwards thread (co = tid/4, 16-channel group tid%4) transposes its 144 bytes = pieces 9*tid .. 9*tid+8.
+    //      A wavefront copies exactly the 576 pieces its own lanes transpose (piece wave*576 + i*64 + lane), so the
+    //      raw copy needs no workgroup barrier: LDS operations of a wavefront complete in order.
+    const int wco = tid >> 2, wc16 = tid & 3;
+    const int8_t* wblk = w + (int64_t)(mb << 6) * C_in * 9;
+    int woff[9];
+#pragma unroll
+    for (int i = 0; i < 9; ++i) {
+        const int piece = wave * 576 + i * 64 + lane;
+        woff[i] = (piece / 36) * C_in * 9 + (piece % 36) * 16;
+    }
+
+    intx4 wv0[9], wv1[9];
+    if constexpr (RES != 0) {
+        // the resident variant's filter loads go out before the index arithmetic of the input plan below
+#pragma unroll
+        for (int i = 0; i < 9; ++i) wv0[i] = *reinterpret_cast<const intx4*>(wblk + woff[i]);
+#pragma unroll
+        for (int i = 0; i < 9; ++i) wv1[i] = *reinterpret_cast<const intx4*>(wblk + (int64_t)kCK * 9 + woff[i]);
+    }
+
     // ---- input staging plan: item = (16-channel group, window row, image column quad) ---------------
     const int wc0 = col0 - pad;                        // image column of window column 0
     // column quads of the image that the window touches (quads outside the image stay zero)
@@ -174,23 +196,9 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
         xlds[k] = (e * IW + xc[k]) * kPitch + 16 * c16;
     }
 
-    // ---- weight staging: the workgroup's 64 x 576-byte block is copied in 16-byte pieces (coalesced);
-    //      afterwards thread (co = tid/4, 16-channel group tid%4) transposes its 144 bytes = pieces 9*tid .. 9*tid+8.
-    //      A wavefront copies exactly the 576 pieces its own lanes transpose (piece wave*576 + i*64 + lane), so the
-    //      raw copy needs no workgroup barrier: LDS operations of a wavefront complete in order.
-    const int wco = tid >> 2, wc16 = tid & 3;
-    const int8_t* wblk = w + (int64_t)(mb << 6) * C_in * 9;
-    int woff[9];
-#pragma unroll
-    for (int i = 0; i < 9; ++i) {
-        const int piece = wave * 576 + i * 64 + lane;
-        woff[i] = (piece / 36) * C_in * 9 + (piece % 36) * 16;
-    }
-
     // two register sets, each holding one chunk on its way from global memory to LDS
     u32 xv0[XI][16], xv1[XI][16];
-    intx4 wv0[9], wv1[9];
-    auto fetch = [&](u32 (&xv)[XI][16], intx4 (&wv)[9], int c0) {
+    auto fetch = [&](u32 (&xv)[XI][16], intx4 (&wv)[9], int c0, bool with_filters = true) {
         const int8_t* xcp = xn + (int64_t)c0 * HW;
 #pragma unroll
         for (int k = 0; k < XI; ++k) {
@@ -198,6 +206,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
             for (int c = 0; c < 16; ++c)      // skipped items read a valid dummy address; stage() ignores them
                 xv[k][c] = *reinterpret_cast<const u32*>(xcp + max(xoff[k], 0) + c * HW);
         }
+        if (!with_filters) return;
         const int8_t* ws = wblk + (int64_t)c0 * 9;
 #pragma unroll
         for (int i = 0; i < 9; ++i) wv[i] = *reinterpret_cast<const intx4*>(ws + woff[i]);
@@ -286,8 +295,8 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_kernel(const int8_t* __restric
     if constexpr (RES != 0) {
         constexpr int KS = RES / 32;            // K steps per tap
         constexpr int NSTEP = 9 * KS;
-        fetch(xv0, wv0, 0);
-        fetch(xv1, wv1, kCK);
+        fetch(xv0, wv0, 0, false);
+        fetch(xv1, wv1, kCK, false);
         zero_window();
         stage(xv0, wv0, 0, false);
         stage(xv1, wv1, kCK);

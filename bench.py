@@ -173,249 +173,213 @@ def time_kernel(torch, fn, sets, reps, batches=5):
     return out[len(out) // 2]
 
 
+# filter sizes of `--sweep`: one filter per plane, and with a C_in reduction
+SWEEP_FILTERS = (3, 5, 7, 9, 11, 13, 15, 17, 21, 25, 29, 33, 37, 45, 51)
+MC_SWEEP_FILTERS = (1, 3, 5, 7, 9, 11, 13)
+
+
 def filter_size_sweep(torch, sw):
     """Throughput against filter size on one plane-per-filter workload (N=32, C=64, 56x56, stride 1, 'same'
     padding, fp32 N(0,1), weights N(0, 1/k^2)): sizes 3, 5, 7 run the fixed-size kernels, up to 17 the first
     generic kernel, beyond that the wide-window generic kernel.  Sizes up to 33 are also timed through the kernel
     generated at run time for the geometry (`jit_*` columns; paper, section 2); its compilation happens in the
-    warm-up call, outside the timed launches.  Each size and path is first checked against the CPU oracle on two
-    planes."""
-    import numpy as np
-
-    import oracle
+    warm-up call, outside the timed launches.  (Parity of every size and path of this sweep against the CPU oracle
+    is a GPU test: tests/test_gpu_bench_shapes.py.)"""
     from paper_2310_05218_amd import inputs
 
     N, C, H = 32, 64, 56
     x = inputs.normal_f32((N, C, H, H), inputs.seed_for(6, 0))
     sets = [{"x": torch.from_numpy(x).cuda(), "y": torch.empty((N, C, H, H), device="cuda")} for _ in range(4)]
     rows = []
-    for k in (3, 5, 7, 9, 11, 13, 15, 17, 21, 25, 29, 33, 37, 45, 51):
+    for k in SWEEP_FILTERS:
         w = inputs.normal_f32((C, 1, k, k), inputs.seed_for(6, k), 1.0 / k)
         wd = torch.from_numpy(w).cuda()
         pad = (k - 1) // 2
-        y = sw.sw_conv2d_depthwise(sets[0]["x"][:1, :2].contiguous(), wd[:2].contiguous(), 1, pad).cpu().numpy()
-        y_ref, d = oracle.conv2d_depthwise(x[:1, :2], w[:2], 1, pad)
-        err = float(np.max(np.abs(y - y_ref) / d))
-        assert err <= 2e-5, (k, err)
         us = time_kernel(torch, lambda s_: sw.sw_conv2d_depthwise(s_["x"], wd, 1, pad, out=s_["y"]), sets,
                          50 if k < 20 else 10)
         flop = 2.0 * k * k * N * C * H * H
         nbytes = 2 * N * C * H * H * 4 + C * k * k * 4
         row = {"filter": k, "us": round(us, 2), "gflops": round(flop / us / 1e3, 1),
                "gbs": round(nbytes / us / 1e3, 1), "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4),
-               "frac_alu_f32_plain_fma": round(flop / us / 1e6 / VALU_F32_TFLOPS, 4),
-               "max_norm_err": float("%.2e" % err)}
+               "frac_alu_f32_plain_fma": round(flop / us / 1e6 / VALU_F32_TFLOPS, 4)}
         if sw.sw_jit_prepare_depthwise(H, H, k, k, 1, pad) == 0:
-            y = sw.sw_conv2d_depthwise_jit(sets[0]["x"][:1, :2].contiguous(), wd[:2].contiguous(), 1, pad).cpu().numpy()
-            err = float(np.max(np.abs(y - y_ref) / d))
-            assert err <= 2e-5, ("jit", k, err)
             us = time_kernel(torch, lambda s_: sw.sw_conv2d_depthwise_jit(s_["x"], wd, 1, pad, out=s_["y"]), sets,
                              50 if k < 20 else 10)
             row.update({"jit_us": round(us, 2), "jit_gflops": round(flop / us / 1e3, 1),
-                        "jit_frac_alu_f32_plain_fma": round(flop / us / 1e6 / VALU_F32_TFLOPS, 4),
-                        "jit_max_norm_err": float("%.2e" % err)})
+                        "jit_frac_alu_f32_plain_fma": round(flop / us / 1e6 / VALU_F32_TFLOPS, 4)})
         rows.append(row)
     # the same axis with a C_in reduction (matrix cores): workload 3's shape with growing filters
     mc_rows = []
     Ci = Co = 64
     xm = inputs.normal_f32((N, Ci, H, H), inputs.seed_for(6, 1000))
     msets = [{"x": torch.from_numpy(xm).cuda(), "y": torch.empty((N, Co, H, H), device="cuda")} for _ in range(6)]
-    for k in (1, 3, 5, 7, 9, 11, 13):
+    for k in MC_SWEEP_FILTERS:
         w = inputs.normal_f32((Co, Ci, k, k), inputs.seed_for(6, 1000 + k), (2.0 / (Ci * k * k)) ** 0.5)
         wd = torch.from_numpy(w).cuda()
         pad = (k - 1) // 2
-        y = sw.sw_conv2d(msets[0]["x"][:1].contiguous(), wd, 1, pad).cpu().numpy()
-        y_ref, d = oracle.conv2d(xm[:1], w, 1, pad)
-        err = float(np.max(np.abs(y - y_ref) / d))
-        assert err <= 2e-5, ("multi-channel", k, err)
         us = time_kernel(torch, lambda s_: sw.sw_conv2d(s_["x"], wd, 1, pad, out=s_["y"]), msets, 12 if k < 7 else 6)
         flop = 2.0 * k * k * Ci * Co * N * H * H
         mc_rows.append({"filter": k, "us": round(us, 2), "gflops": round(flop / us / 1e3, 1),
-                        "frac_mfma_f32": round(flop / us / 1e6 / MFMA_F32_TFLOPS, 4),
-                        "max_norm_err": float("%.2e" % err)})
+                        "frac_mfma_f32": round(flop / us / 1e6 / MFMA_F32_TFLOPS, 4)})
     return {"sweep": "depthwise-shaped 32x64x56x56 fp32, square filter, stride 1, same padding", "rows": rows,
             "multi_channel_sweep": "32x64x56x56 -> 64 channels fp32, square filter, stride 1, same padding",
             "multi_channel_rows": mc_rows}
 
 
-def _conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, stride, pad, C_out):
-    """One multi-channel layer of the table below (fp32 or int8), checked on one image against the oracle."""
+# layers of `--layers`: name, kind, (N, C, H, W), R (= S), stride, pad[, C_out]
+LAYERS = [
+    ("maxpool_3x3_s2", "max", (32, 64, 112, 112), 3, 2, 1),
+    ("maxpool_2x2_s2", "max", (32, 64, 112, 112), 2, 2, 0),
+    ("avgpool_2x2_s2", "avg", (32, 64, 112, 112), 2, 2, 0),
+    ("avgpool_3x3_s1", "avg", (32, 64, 56, 56), 3, 1, 1),
+    ("depthwise_3x3_s2", "dw", (32, 128, 112, 112), 3, 2, 1),
+    ("depthwise_5x5_s2", "dw", (32, 128, 112, 112), 5, 2, 2),
+    ("depthwise_3x3_bias_relu", "dw_br", (32, 256, 56, 56), 3, 1, 1),
+    ("depthwise_3x3_s2_bias_relu", "dw_br", (32, 128, 112, 112), 3, 2, 1),
+    ("depthwise_3x3_bf16", "dw_bf16", (32, 256, 56, 56), 3, 1, 1),
+    ("depthwise_7x7_bf16", "dw_bf16", (32, 256, 56, 56), 7, 1, 3),
+    ("global_avgpool_7x7", "avg", (32, 2048, 7, 7), 7, 1, 0),
+    ("depthwise_3x3_28x28", "dw", (32, 256, 28, 28), 3, 1, 1),
+    ("depthwise_3x3_14x14", "dw", (32, 512, 14, 14), 3, 1, 1),
+    ("depthwise_7x7_14x14", "dw", (32, 384, 14, 14), 7, 1, 3),
+    ("conv_7x7_s2_3to64", "conv", (32, 3, 224, 224), 7, 2, 3, 64),
+    ("conv_3x3_s2_64to128", "conv", (32, 64, 56, 56), 3, 2, 1, 128),
+    ("conv_1x1_256to64", "conv", (32, 256, 56, 56), 1, 1, 0, 64),
+    ("conv_3x3_14x14_256", "conv", (32, 256, 14, 14), 3, 1, 1, 256),
+    ("conv_3x3_64to64", "conv", (32, 64, 56, 56), 3, 1, 1, 64),
+    ("conv_3x3_64to64_bias_relu", "conv_br", (32, 64, 56, 56), 3, 1, 1, 64),
+    ("conv_3x3_14x14_256_bias_relu", "conv_br", (32, 256, 14, 14), 3, 1, 1, 256),
+    ("conv_3x3_dilation2_64to64", "conv_dil", (32, 64, 56, 56), 3, 1, 2, 64),
+    ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
+    ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
+    ("conv_s8_requant_3x3_128to128", "conv_s8_rq", (32, 128, 28, 28), 3, 1, 1, 128),
+    ("conv_s8_nhwc_3x3_128to128", "conv_s8_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
+    ("conv_s8_nhwc_requant_3x3_128to128", "conv_s8_nhwc_rq", (32, 128, 28, 28), 3, 1, 1, 128),
+    ("conv_s8_nhwc_3x3_s2_64to128", "conv_s8_nhwc", (32, 64, 56, 56), 3, 2, 1, 128),
+    ("conv_s8_nhwc_1x1_64to256", "conv_s8_nhwc", (32, 64, 56, 56), 1, 1, 0, 256),
+]
+
+
+def layer_case(idx, n_images=None):
+    """Host-side description of layer LAYERS[idx] (optionally with fewer images): seeded inputs and everything
+    needed to call it.  Shared by `--layers` (timing) and tests/test_gpu_bench_shapes.py (parity against the CPU
+    oracle), so that what is timed is what is checked."""
+    import numpy as np
+
+    from paper_2310_05218_amd import inputs
+
+    name, kind, shape, R, stride, pad, *more = LAYERS[idx]
     N, C, H, W = shape
-    dil = 2 if kind == "conv_dil" else 1            # the dilated row: taps two positions apart
-    Ho, Wo = (H + 2 * pad - dil * (R - 1) - 1) // stride + 1, (W + 2 * pad - dil * (R - 1) - 1) // stride + 1
-    s8 = kind in ("conv_s8", "conv_s8_rq", "conv_s8_nhwc", "conv_s8_nhwc_rq")
-    rq = kind in ("conv_s8_rq", "conv_s8_nhwc_rq")
-    nhwc = kind in ("conv_s8_nhwc", "conv_s8_nhwc_rq")      # the same layer on channel-last tensors
-    br = kind == "conv_br"
-    if s8:
-        x = inputs.uniform_s8(shape, inputs.seed_for(7, idx))
-        w = inputs.uniform_s8((C_out, C, R, R), inputs.seed_for(7, 100 + idx))
-        call, odt, esz = sw.sw_conv2d_s8, torch.int32, 1
-        if rq:      # workload 5 with the requantisation fused into the store: int8 out instead of int32
-            rng = np.random.default_rng(inputs.seed_for(7, 200 + idx))
-            bias = rng.integers(-50000, 50000, size=C_out).astype(np.int32)
-            scale = (rng.uniform(1.0, 3.0, size=C_out) * 2.0 ** -18).astype(np.float32)
-            bd, sd = torch.from_numpy(bias).cuda(), torch.from_numpy(scale).cuda()
-            call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_s8_requant(a, b, bd, sd, st_, p_, True, out=out)
-            odt = torch.int8
-        if nhwc:
+    if n_images is not None:
+        N = n_images
+    c = {"name": name, "kind": kind, "N": N, "C": C, "H": H, "W": W, "R": R, "stride": stride, "pad": pad,
+         "dil": 2 if kind == "conv_dil" else 1, "C_out": more[0] if more else C}
+    span = c["dil"] * (R - 1) + 1
+    c["Ho"], c["Wo"] = (H + 2 * pad - span) // stride + 1, (W + 2 * pad - span) // stride + 1
+    rng = np.random.default_rng(inputs.seed_for(7, 200 + idx))
+    if kind.startswith("conv_s8"):
+        x = inputs.uniform_s8((N, C, H, W), inputs.seed_for(7, idx))
+        w = inputs.uniform_s8((c["C_out"], C, R, R), inputs.seed_for(7, 100 + idx))
+        if kind.endswith("rq"):
+            c["bias"] = rng.integers(-50000, 50000, size=c["C_out"]).astype(np.int32)
+            c["scale"] = (rng.uniform(1.0, 3.0, size=c["C_out"]) * 2.0 ** -18).astype(np.float32)
+        if "nhwc" in kind:
             x = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
             w = np.ascontiguousarray(w.transpose(0, 2, 3, 1))
-            if rq:
-                call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_s8_nhwc(a, b, st_, p_, bias=bd, scale=sd, relu=True, out=out)
-            else:
-                call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_s8_nhwc(a, b, st_, p_, out=out)
+    elif kind.startswith("conv"):
+        x = inputs.normal_f32((N, C, H, W), inputs.seed_for(7, idx))
+        w = inputs.normal_f32((c["C_out"], C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
+        if kind == "conv_br":
+            c["bias"] = inputs.normal_f32((c["C_out"],), inputs.seed_for(7, 200 + idx), 0.5)
     else:
-        x = inputs.normal_f32(shape, inputs.seed_for(7, idx))
-        w = inputs.normal_f32((C_out, C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
-        call, odt, esz = sw.sw_conv2d, torch.float32, 4
-        if dil > 1:
-            call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_dilated(a, b, st_, p_, dil, out=out)
-        if br:      # bias and rectifier fused into the store
-            bias = inputs.normal_f32((C_out,), inputs.seed_for(7, 200 + idx), 0.5)
-            bd = torch.from_numpy(bias).cuda()
-            call = lambda a, b, st_, p_, out=None: sw.sw_conv2d_bias_relu(a, b, bd, st_, p_, True, out=out)
-    xs, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
-    y = call(xs[:1].contiguous(), wd, stride, pad).cpu().numpy()
-    if nhwc and rq:
-        assert np.array_equal(y, oracle.conv2d_s8_nhwc_requant(x[:1], w, bias, scale, stride, pad, True)), name
-        err = 0.0
-    elif nhwc:
-        assert np.array_equal(y, oracle.conv2d_s8_nhwc(x[:1], w, stride, pad)), name
-        err = 0.0
-    elif rq:
-        assert np.array_equal(y, oracle.conv2d_s8_requant(x[:1], w, bias, scale, stride, pad, True)), name
-        err = 0.0
-    elif s8:
-        assert np.array_equal(y, oracle.conv2d_s8(x[:1], w, stride, pad)), name
-        err = 0.0
-    else:
-        if br:
-            y_ref, d = oracle.conv2d_bias_relu(x[:1], w, bias, stride, pad, True)
-        elif dil > 1:
-            y_ref, d = oracle.conv2d_dilated(x[:1], w, stride, pad, dil)
-        else:
-            y_ref, d = oracle.conv2d(x[:1], w, stride, pad)
-        err = float(np.max(np.abs(y - y_ref) / d))
-        assert err <= 2e-5, (name, err)
-    nbytes = x.nbytes + w.nbytes + N * C_out * Ho * Wo * (1 if rq else 4)
-    nsets = min(16, max(3, -(-COLD_ROTATION_BYTES // nbytes)))
-    oshape = (N, Ho, Wo, C_out) if nhwc else (N, C_out, Ho, Wo)
-    sets = [{"x": xs if i == 0 else xs.clone(), "y": torch.empty(oshape, dtype=odt, device="cuda")}
-            for i in range(nsets)]
-    us = time_kernel(torch, lambda s_: call(s_["x"], wd, stride, pad, out=s_["y"]), sets, 2 * nsets)
-    ops = 2.0 * N * C_out * Ho * Wo * C * R * R
-    peak = MFMA_I8_TOPS if s8 else MFMA_F32_TFLOPS
-    return {"layer": name, "shape": list(shape) + [C_out], "us_cold": round(us, 2), "gbs": round(nbytes / us / 1e3, 1),
-            "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4), "gops": round(ops / us / 1e3, 1),
-            "frac_mfma": round(ops / us / 1e6 / peak, 4), "max_norm_err": float("%.2e" % err)}
+        x = inputs.normal_f32((N, C, H, W), inputs.seed_for(7, idx))
+        w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R) if kind.startswith("dw") else None
+        if kind == "dw_br":
+            c["bias"] = inputs.normal_f32((C,), inputs.seed_for(7, 200 + idx), 0.5)
+        if kind == "dw_bf16":
+            x = inputs.to_bf16_bits(x)
+    c["x"], c["w"] = x, w
+    return c
+
+
+def layer_device(torch, c):
+    """Device tensors of a layer case: x, w, bias, scale (None where the layer has none) and an empty output."""
+    import numpy as np
+
+    def dev(a):
+        return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    x = c["x"]
+    xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16) if c["kind"] == "dw_bf16" else dev(x)
+    kind = c["kind"]
+    odt = (torch.bfloat16 if kind == "dw_bf16" else torch.int8 if kind.endswith("rq") else
+           torch.int32 if kind.startswith("conv_s8") else torch.float32)
+    oshape = ((c["N"], c["Ho"], c["Wo"], c["C_out"]) if "nhwc" in kind else (c["N"], c["C_out"], c["Ho"], c["Wo"]))
+    return {"x": xd, "w": dev(c["w"]), "bias": dev(c.get("bias")), "scale": dev(c.get("scale")),
+            "y": torch.empty(oshape, dtype=odt, device="cuda")}
+
+
+def layer_call(sw, c, d, x=None, y=None):
+    """Runs the layer on device tensors d (x / y override the input and output, for buffer rotations)."""
+    x = d["x"] if x is None else x
+    y = d["y"] if y is None else y
+    kind, st, p = c["kind"], c["stride"], c["pad"]
+    if kind in ("max", "avg"):
+        return sw.sw_pool2d(x, c["R"], c["R"], st, p, sw.SW_POOL_MAX if kind == "max" else sw.SW_POOL_AVG, out=y)
+    if kind == "dw":
+        return sw.sw_conv2d_depthwise(x, d["w"], st, p, out=y)
+    if kind == "dw_br":
+        return sw.sw_conv2d_depthwise_bias_relu(x, d["w"], d["bias"], st, p, True, out=y)
+    if kind == "dw_bf16":
+        return sw.sw_conv2d_depthwise_bf16(x, d["w"], st, p, out=y)
+    if kind == "conv":
+        return sw.sw_conv2d(x, d["w"], st, p, out=y)
+    if kind == "conv_br":
+        return sw.sw_conv2d_bias_relu(x, d["w"], d["bias"], st, p, True, out=y)
+    if kind == "conv_dil":
+        return sw.sw_conv2d_dilated(x, d["w"], st, p, c["dil"], out=y)
+    if kind == "conv_s8":
+        return sw.sw_conv2d_s8(x, d["w"], st, p, out=y)
+    if kind == "conv_s8_rq":
+        return sw.sw_conv2d_s8_requant(x, d["w"], d["bias"], d["scale"], st, p, True, out=y)
+    if kind == "conv_s8_nhwc":
+        return sw.sw_conv2d_s8_nhwc(x, d["w"], st, p, out=y)
+    if kind == "conv_s8_nhwc_rq":
+        return sw.sw_conv2d_s8_nhwc(x, d["w"], st, p, bias=d["bias"], scale=d["scale"], relu=True, out=y)
+    raise ValueError(kind)
 
 
 def strided_and_pooling_table(torch, sw):
-    """2-D pooling and stride-2 layers of common CNN shapes (fp32 N(0,1) activations), timed cold like the
-    step's kernels; each is first checked against the CPU oracle on two planes.  All are bound by HBM:
-    bytes = input once + output once (+ filters)."""
-    import numpy as np
-
-    import oracle
-    from paper_2310_05218_amd import inputs
-
-    layers = [  # name, kind, (N, C, H, W), R, stride, pad
-        ("maxpool_3x3_s2", "max", (32, 64, 112, 112), 3, 2, 1),
-        ("maxpool_2x2_s2", "max", (32, 64, 112, 112), 2, 2, 0),
-        ("avgpool_2x2_s2", "avg", (32, 64, 112, 112), 2, 2, 0),
-        ("avgpool_3x3_s1", "avg", (32, 64, 56, 56), 3, 1, 1),
-        ("depthwise_3x3_s2", "dw", (32, 128, 112, 112), 3, 2, 1),
-        ("depthwise_5x5_s2", "dw", (32, 128, 112, 112), 5, 2, 2),
-        ("depthwise_3x3_bias_relu", "dw_br", (32, 256, 56, 56), 3, 1, 1),
-        ("depthwise_3x3_s2_bias_relu", "dw_br", (32, 128, 112, 112), 3, 2, 1),
-        ("depthwise_3x3_bf16", "dw_bf16", (32, 256, 56, 56), 3, 1, 1),
-        ("depthwise_7x7_bf16", "dw_bf16", (32, 256, 56, 56), 7, 1, 3),
-        ("global_avgpool_7x7", "avg", (32, 2048, 7, 7), 7, 1, 0),
-        ("depthwise_3x3_28x28", "dw", (32, 256, 28, 28), 3, 1, 1),
-        ("depthwise_3x3_14x14", "dw", (32, 512, 14, 14), 3, 1, 1),
-        ("depthwise_7x7_14x14", "dw", (32, 384, 14, 14), 7, 1, 3),
-        ("conv_7x7_s2_3to64", "conv", (32, 3, 224, 224), 7, 2, 3, 64),
-        ("conv_3x3_s2_64to128", "conv", (32, 64, 56, 56), 3, 2, 1, 128),
-        ("conv_1x1_256to64", "conv", (32, 256, 56, 56), 1, 1, 0, 64),
-        ("conv_3x3_14x14_256", "conv", (32, 256, 14, 14), 3, 1, 1, 256),
-        ("conv_3x3_64to64", "conv", (32, 64, 56, 56), 3, 1, 1, 64),
-        ("conv_3x3_64to64_bias_relu", "conv_br", (32, 64, 56, 56), 3, 1, 1, 64),
-        ("conv_3x3_14x14_256_bias_relu", "conv_br", (32, 256, 14, 14), 3, 1, 1, 256),
-        ("conv_3x3_dilation2_64to64", "conv_dil", (32, 64, 56, 56), 3, 1, 2, 64),
-        ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
-        ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
-        ("conv_s8_requant_3x3_128to128", "conv_s8_rq", (32, 128, 28, 28), 3, 1, 1, 128),
-        ("conv_s8_nhwc_3x3_128to128", "conv_s8_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
-        ("conv_s8_nhwc_requant_3x3_128to128", "conv_s8_nhwc_rq", (32, 128, 28, 28), 3, 1, 1, 128),
-        ("conv_s8_nhwc_3x3_s2_64to128", "conv_s8_nhwc", (32, 64, 56, 56), 3, 2, 1, 128),
-        ("conv_s8_nhwc_1x1_64to256", "conv_s8_nhwc", (32, 64, 56, 56), 1, 1, 0, 256),
-    ]
+    """Layers of common CNN shapes beyond the five workloads (2-D pooling, strides, small planes, fused epilogues,
+    dilation, bf16 planes, int8 in both layouts), timed cold like the step's kernels.  bytes = input once + output
+    once (+ filters); multi-channel rows also give the fraction of the matrix peak.  (Parity of every row against
+    the CPU oracle is a GPU test: tests/test_gpu_bench_shapes.py.)"""
     rows = []
-    for idx, (name, kind, shape, R, stride, pad, *more) in enumerate(layers):
-        N, C, H, W = shape
-        if kind in ("conv", "conv_br", "conv_dil", "conv_s8", "conv_s8_rq", "conv_s8_nhwc", "conv_s8_nhwc_rq"):
-            rows.append(_conv_layer_row(torch, sw, oracle, inputs, np, idx, name, kind, shape, R, stride, pad, more[0]))
-            continue
-        Ho, Wo = (H + 2 * pad - R) // stride + 1, (W + 2 * pad - R) // stride + 1
-        x = inputs.normal_f32(shape, inputs.seed_for(7, idx))
-        in_bytes, out_bytes = x.nbytes, N * C * Ho * Wo * 4
-        nsets = min(32, max(3, -(-COLD_ROTATION_BYTES // (in_bytes + out_bytes))))
-        xs = torch.from_numpy(x).cuda()
-        sets = [{"x": xs if i == 0 else xs.clone(), "y": torch.empty((N, C, Ho, Wo), device="cuda")}
-                for i in range(nsets)]
-        if kind == "dw_bf16":       # bf16 planes, fp32 filter and accumulation: half the bytes of the fp32 layer
-            xb = inputs.to_bf16_bits(x)
-            xs = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
-            in_bytes, out_bytes = xb.nbytes, N * C * Ho * Wo * 2
-            nsets = min(32, max(3, -(-COLD_ROTATION_BYTES // (in_bytes + out_bytes))))
-            sets = [{"x": xs if i == 0 else xs.clone(),
-                     "y": torch.empty((N, C, Ho, Wo), dtype=torch.bfloat16, device="cuda")} for i in range(nsets)]
-            w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R)
-            wd = torch.from_numpy(w).cuda()
-            fn = lambda s_: sw.sw_conv2d_depthwise_bf16(s_["x"], wd, stride, pad, out=s_["y"])
-            yb = sw.sw_conv2d_depthwise_bf16(xs[:1, :2].contiguous(), wd[:2].contiguous(), stride, pad)
-            y = inputs.bf16_bits_to_f32(yb.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
-            y_ref, d = oracle.conv2d_depthwise(inputs.bf16_bits_to_f32(xb[:1, :2]), w[:2], stride, pad)
-            # fp32 parity bound plus half a bf16 unit of the exact sum, normalised to the usual 2e-5
-            err = float(np.max(np.abs(y - y_ref) / (d + 2.0 ** -8 * np.abs(y_ref) / 2e-5 + 1e-30)))
-            ops, extra = 2.0 * R * R * N * C * Ho * Wo, w.nbytes
-        elif kind == "dw_br":       # depthwise with bias and rectifier fused into the store
-            w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R)
-            bias = inputs.normal_f32((C,), inputs.seed_for(7, 200 + idx), 0.5)
-            wd, bd = torch.from_numpy(w).cuda(), torch.from_numpy(bias).cuda()
-            fn = lambda s_: sw.sw_conv2d_depthwise_bias_relu(s_["x"], wd, bd, stride, pad, True, out=s_["y"])
-            y = sw.sw_conv2d_depthwise_bias_relu(xs[:1, :2].contiguous(), wd[:2].contiguous(), bd[:2].contiguous(),
-                                                 stride, pad, True).cpu().numpy()
-            y_ref, d = oracle.conv2d_depthwise_bias_relu(x[:1, :2], w[:2], bias[:2], stride, pad, True)
-            err = float(np.max(np.abs(y - y_ref) / d))
-            ops, extra = 2.0 * R * R * N * C * Ho * Wo, w.nbytes
-        elif kind == "dw":
-            w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R)
-            wd = torch.from_numpy(w).cuda()
-            fn = lambda s_: sw.sw_conv2d_depthwise(s_["x"], wd, stride, pad, out=s_["y"])
-            y = sw.sw_conv2d_depthwise(xs[:1, :2].contiguous(), wd[:2].contiguous(), stride, pad).cpu().numpy()
-            y_ref, d = oracle.conv2d_depthwise(x[:1, :2], w[:2], stride, pad)
-            err = float(np.max(np.abs(y - y_ref) / d))
-            ops, extra = 2.0 * R * R * N * C * Ho * Wo, w.nbytes
+    for idx in range(len(LAYERS)):
+        c = layer_case(idx)
+        d = layer_device(torch, c)
+        kind, N, C, R = c["kind"], c["N"], c["C"], c["R"]
+        w_bytes = 0 if c["w"] is None else c["w"].nbytes
+        nbytes = c["x"].nbytes + w_bytes + d["y"].numel() * d["y"].element_size()
+        nsets = min(32, max(3, -(-COLD_ROTATION_BYTES // nbytes)))
+        sets = [{"x": d["x"] if i == 0 else d["x"].clone(), "y": torch.empty_like(d["y"])} for i in range(nsets)]
+        us = time_kernel(torch, lambda s_: layer_call(sw, c, d, s_["x"], s_["y"]), sets, 4 * nsets)
+        outs = N * c["C_out"] * c["Ho"] * c["Wo"]
+        if kind.startswith("conv"):
+            ops = 2.0 * outs * C * R * R
+        elif kind.startswith("dw"):
+            ops = 2.0 * outs * R * R
         else:
-            mode = sw.SW_POOL_MAX if kind == "max" else sw.SW_POOL_AVG
-            fn = lambda s_: sw.sw_pool2d(s_["x"], R, R, stride, pad, mode, out=s_["y"])
-            y = sw.sw_pool2d(xs[:1, :2].contiguous(), R, R, stride, pad, mode).cpu().numpy()
-            y_ref, d = oracle.pool2d(x[:1, :2], R, R, stride, pad, mode)
-            err = float(np.max(np.abs(y - y_ref) / np.maximum(d, 1e-300)))
-            if kind == "max":
-                assert np.array_equal(y.astype(np.float64), y_ref), name
-            ops, extra = float(R * R * N * C * Ho * Wo), 0
-        assert err <= 2e-5, (name, err)
-        us = time_kernel(torch, fn, sets, 4 * nsets)
-        nbytes = in_bytes + out_bytes + extra
-        rows.append({"layer": name, "shape": list(shape), "us_cold": round(us, 2), "gbs": round(nbytes / us / 1e3, 1),
-                     "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4), "gops": round(ops / us / 1e3, 1),
-                     "max_norm_err": float("%.2e" % err)})
-        del sets, xs
+            ops = float(outs * R * R)
+        row = {"layer": c["name"], "shape": [N, C, c["H"], c["W"]] + ([c["C_out"]] if kind.startswith("conv") else []),
+               "us_cold": round(us, 2), "gbs": round(nbytes / us / 1e3, 1),
+               "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4), "gops": round(ops / us / 1e3, 1)}
+        if kind.startswith("conv"):
+            row["frac_mfma"] = round(ops / us / 1e6 / (MFMA_I8_TOPS if "s8" in kind else MFMA_F32_TFLOPS), 4)
+        rows.append(row)
+        del sets, d
         torch.cuda.empty_cache()
-    return {"table": "2-D pooling, stride-2, small-plane and other multi-channel layers, cold (rotation larger than the Infinity Cache)",
+    return {"table": "layers of common CNN shapes beyond the five workloads, cold (rotation larger than the Infinity Cache)",
             "rows": rows}
 
 

@@ -192,20 +192,23 @@ __global__ __launch_bounds__(256) void mfma_f32_any_kernel(const float* __restri
     const int HoWo = P.Ho * P.Wo;
     float* yp = y + ((int64_t)n * P.C_out + co0) * HoWo + (row0 + pi) * P.Wo + col0 + pj;
     if (P.ep.bias != nullptr || P.ep.relu != 0) {
-        // the lane's 32 biases are read together (one wait), then added, rectified and stored
-        float b0[16], b1[16];
+        // the lane's biases are read eight at a time (one wait per group, and few registers: the plain path's
+        // occupancy must not pay for the epilogue), then added, rectified and stored
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int co = co0 + 8 * (v >> 2) + 4 * kk + (v & 3);
-            b0[v] = (P.ep.bias && co < P.C_out) ? P.ep.bias[co] : 0.f;
-            b1[v] = (P.ep.bias && co + 32 < P.C_out) ? P.ep.bias[co + 32] : 0.f;
-        }
+        for (int h = 0; h < 4; ++h) {                   // h: accumulator (0, 1) x its register halves
+            const int cb = h >= 2 ? 32 : 0, v0 = (h & 1) * 8;
+            float b[8];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int co = 8 * (v >> 2) + 4 * kk + (v & 3);
-            const float t0 = acc0[v] + b0[v], t1 = acc1[v] + b1[v];
-            if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = P.ep.relu ? fmaxf(t0, 0.f) : t0;
-            if (co0 + 32 + co < P.C_out) yp[(int64_t)(32 + co) * HoWo] = P.ep.relu ? fmaxf(t1, 0.f) : t1;
+            for (int i = 0; i < 8; ++i) {
+                const int v = v0 + i, co = co0 + cb + 8 * (v >> 2) + 4 * kk + (v & 3);
+                b[i] = (P.ep.bias && co < P.C_out) ? P.ep.bias[co] : 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int v = v0 + i, co = cb + 8 * (v >> 2) + 4 * kk + (v & 3);
+                const float t = (h >= 2 ? acc1[v] : acc0[v]) + b[i];
+                if (co0 + co < P.C_out) yp[(int64_t)co * HoWo] = P.ep.relu ? fmaxf(t, 0.f) : t;
+            }
         }
         return;
     }

@@ -176,6 +176,7 @@ def time_kernel(torch, fn, sets, reps, batches=5):
 # filter sizes of `--sweep`: one filter per plane, and with a C_in reduction
 SWEEP_FILTERS = (3, 5, 7, 9, 11, 13, 15, 17, 21, 25, 29, 33, 37, 45, 51)
 MC_SWEEP_FILTERS = (1, 3, 5, 7, 9, 11, 13)
+SWEEP_1D = (2, 3, 5, 9, 13, 17, 25, 33, 49, 64)        # 1-D filter lengths / pooling windows
 
 
 def filter_size_sweep(torch, sw):
@@ -221,7 +222,29 @@ def filter_size_sweep(torch, sw):
         flop = 2.0 * k * k * Ci * Co * N * H * H
         mc_rows.append({"filter": k, "us": round(us, 2), "gflops": round(flop / us / 1e3, 1),
                         "frac_mfma_f32": round(flop / us / 1e6 / MFMA_F32_TFLOPS, 4)})
+    # the 1-D axis (the paper's first experiment): workload 2's rows with growing filters / windows
+    rows_1d = []
+    x2 = inputs.normal_f32((64, 65536), inputs.seed_for(6, 2000))
+    nb = x2.nbytes
+    s1 = [{"x": torch.from_numpy(x2).cuda()} for _ in range(12)]
+    for k in SWEEP_1D:
+        w = torch.from_numpy(inputs.normal_f32((k,), inputs.seed_for(6, 2000 + k), 1.0 / k ** 0.5)).cuda()
+        Lo = 65536 - k + 1
+        for s_ in s1:
+            s_["y"] = torch.empty((64, Lo), device="cuda")
+        row = {"taps": k}
+        for name, fn, ops in (("conv", lambda d: sw.sw_conv1d(d["x"], w, 1, 0, out=d["y"]), 2.0 * k),
+                              ("avg", lambda d: sw.sw_pool1d(d["x"], k, 1, sw.SW_POOL_AVG, out=d["y"]), float(k)),
+                              ("max", lambda d: sw.sw_pool1d(d["x"], k, 1, sw.SW_POOL_MAX, out=d["y"]), float(k - 1))):
+            us = time_kernel(torch, fn, s1, 60)
+            nbytes = nb + 64 * Lo * 4
+            row[name + "_us"] = round(us, 2)
+            row[name + "_frac_hbm"] = round(nbytes / us / 1e3 / HBM_GBS, 4)
+            row[name + "_gops"] = round(ops * 64 * Lo / us / 1e3, 1)
+        rows_1d.append(row)
     return {"sweep": "depthwise-shaped 32x64x56x56 fp32, square filter, stride 1, same padding", "rows": rows,
+            "sweep_1d": "64 rows x 65536 fp32, stride 1, no padding: convolution, average and maximum by window length",
+            "rows_1d": rows_1d,
             "multi_channel_sweep": "32x64x56x56 -> 64 channels fp32, square filter, stride 1, same padding",
             "multi_channel_rows": mc_rows}
 

@@ -241,6 +241,7 @@ hipError_t launch_op(const float* x, const float* w, float* y, int64_t rows, int
     switch (k) {
         SW_CASE(2) SW_CASE(3) SW_CASE(4) SW_CASE(5) SW_CASE(6) SW_CASE(7) SW_CASE(8) SW_CASE(9)
         SW_CASE(11) SW_CASE(13) SW_CASE(15) SW_CASE(16) SW_CASE(17)
+        SW_CASE(25) SW_CASE(32) SW_CASE(33) SW_CASE(49) SW_CASE(64)
         default:
             hipLaunchKernelGGL((sliding_1d_kernel<OP, 0>), grid, block, 0, st, x, w, y, len, len_out, k, pad,
                                tiles_per_row, (int)tiles, x_vec_ok);

@@ -62,6 +62,18 @@ def test_sweep_multi_channel(torch, sw, oracle, k):
     assert_f32_parity(sw.sw_conv2d(dev(torch, x), dev(torch, w), 1, pad).cpu().numpy(), y_ref, d, f"multi-channel sweep {k}")
 
 
+@pytest.mark.parametrize("k", bench.SWEEP_1D)
+def test_sweep_1d(torch, sw, oracle, k):
+    x = inputs.normal_f32((2, 65536), inputs.seed_for(6, 2000))
+    w = inputs.normal_f32((k,), inputs.seed_for(6, 2000 + k), 1.0 / k ** 0.5)
+    xd = dev(torch, x)
+    assert_f32_parity(sw.sw_conv1d(xd, dev(torch, w), 1, 0).cpu().numpy(), *oracle.conv1d(x, w, 1, 0), f"conv1d {k}")
+    y_ref, mag = oracle.pool1d(x, k, 1, 0)
+    assert_f32_parity(sw.sw_pool1d(xd, k, 1, sw.SW_POOL_AVG).cpu().numpy(), y_ref, np.maximum(mag, 1e-300), f"avg {k}")
+    ym = sw.sw_pool1d(xd, k, 1, sw.SW_POOL_MAX).cpu().numpy().astype(np.float64)
+    assert np.array_equal(ym, oracle.pool1d(x, k, 1, 1)[0]), f"max {k}"
+
+
 @pytest.mark.parametrize("idx", range(len(bench.LAYERS)), ids=[layer[0] for layer in bench.LAYERS])
 def test_layer(torch, sw, oracle, idx):
     c = bench.layer_case(idx, n_images=1)

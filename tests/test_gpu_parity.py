@@ -49,6 +49,9 @@ CONV1D_CASES = [
     (2, 4500, 18, 1, 3),        # beyond the unrolled sizes: run-time tap count
     (3, 3000, 33, 1, 32),
     (2, 2500, 64, 1, 63),
+    (2, 8301, 25, 1, 3),        # unrolled long filters: 25, 32, 49 taps (33 and 64 above)
+    (3, 4100, 32, 1, 31),
+    (2, 9000, 49, 1, 0),
     (2, 2049, 12, 1, 0),
     (3, 1000, 9, 2, 0),         # strided kernel
     (3, 1001, 4, 3, 2),
@@ -84,7 +87,8 @@ def test_conv1d_more_tiles_than_workgroups(torch, sw, oracle):
 POOL_CASES = [(1, 8, 8, 1), (3, 4173, 8, 1), (2, 6144 + 7, 8, 1), (2, 12288 + 7, 8, 1), (3, 9001, 8, 1), (4, 5000, 3, 1), (2, 5000, 1, 1),
               (3, 4099, 2, 2), (5, 9000, 3, 2), (2, 10001, 4, 4), (2, 30000, 8, 8),
               (3, 4100, 2, 2), (5, 9000, 4, 4), (7, 10008, 8, 8), (1, 8, 8, 8), (64, 8192, 2, 2),   # windows tile the rows
-              (2, 4100, 17, 1), (2, 4100, 40, 1), (2, 3000, 64, 1), (3, 1000, 8, 2), (3, 1001, 3, 3)]
+              (2, 4100, 17, 1), (2, 4100, 40, 1), (2, 3000, 64, 1), (3, 1000, 8, 2), (3, 1001, 3, 3),
+              (2, 8301, 25, 1), (3, 4100, 32, 1), (2, 4173, 33, 1), (2, 9000, 49, 1)]          # unrolled long windows
 
 
 @pytest.mark.parametrize("case", POOL_CASES)

@@ -59,14 +59,14 @@ SECOND_ROOF = {"depthwise_7x7": (VALU_F32_TFLOPS, "frac_alu_f32_plain_fma"),
 # profiles/hbm_traffic_all_kernels.txt), with the kernel source and its sha256 prefix at the time the
 # counters were taken.  A kernel whose source has changed since reports traffic = null.
 TRAFFIC = {
-    "depthwise_3x3": (207363275, "sw_sliding_plane.hip", "c19725ff48dea175"),
-    "depthwise_7x7": (206176097, "sw_sliding_plane.hip", "c19725ff48dea175"),
-    "conv2d_64x64_3x3": (62452409, "sw_mfma_f32.hip", "c33152360085e7c7"),
-    "conv2d_s8_128x128_3x3": (21142296, "sw_mfma_s8.hip", "83bf83c186c5e9f3"),
-    "conv1d_k9": (33896573, "sw_sliding1d.hip", "eeb6f644a27cb890"),
-    "avgpool1d_w8": (34163235, "sw_sliding1d.hip", "eeb6f644a27cb890"),
-    "maxpool1d_w8": (34136887, "sw_sliding1d.hip", "eeb6f644a27cb890"),
-    "conv2d_1ch_3x3": (660935, "sw_sliding_rows.hip", "21935214a73b4290"),
+    "depthwise_3x3": (207459558, "sw_sliding_plane.hip", "c19725ff48dea175"),
+    "depthwise_7x7": (206223868, "sw_sliding_plane.hip", "c19725ff48dea175"),
+    "conv2d_64x64_3x3": (62439130, "sw_mfma_f32.hip", "c33152360085e7c7"),
+    "conv2d_s8_128x128_3x3": (21133029, "sw_mfma_s8.hip", "83bf83c186c5e9f3"),
+    "conv1d_k9": (33927085, "sw_sliding1d.hip", "e53250bbd93b8921"),
+    "avgpool1d_w8": (34178956, "sw_sliding1d.hip", "e53250bbd93b8921"),
+    "maxpool1d_w8": (34152177, "sw_sliding1d.hip", "e53250bbd93b8921"),
+    "conv2d_1ch_3x3": (661056, "sw_sliding_rows.hip", "21935214a73b4290"),
 }
 
 

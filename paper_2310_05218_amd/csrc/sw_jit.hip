@@ -41,6 +41,7 @@ struct JitKernel {
     hipModule_t module;
     hipFunction_t fn;
     JitPlan plan;
+    int cus;          // compute units of the device the module was loaded on
 };
 
 typedef std::tuple<int, int, int, int, int, int, int, int> JitKey;   // device, H, W, R, S, pad, RB, NT
@@ -168,6 +169,9 @@ int get_kernel(const JitPlan& p, JitKernel* out)
         (void)hipModuleUnload(k.module);
         return SW_ERR_LAUNCH;
     }
+    k.cus = 256;
+    int n = 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) k.cus = n;
     g_cache[key] = k;
     *out = k;
     return SW_OK;
@@ -214,13 +218,7 @@ int jit_launch_plane(const float* x, const float* w, float* y, int64_t planes, i
     JitKernel k;
     const int rc = get_kernel(p, &k);
     if (rc != SW_OK) return rc;
-    int cus = 256;
-    int dev = 0;
-    if (hipGetDevice(&dev) == hipSuccess) {
-        int n = 0;
-        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0) cus = n;
-    }
-    const int64_t want = (int64_t)cus * k.plan.waves_per_cu;
+    const int64_t want = (int64_t)k.cus * k.plan.waves_per_cu;
     unsigned grid = (unsigned)(planes < want ? planes : want);
     int planes_i = (int)planes, wgs = (int)grid;
     void* args[] = {(void*)&x, (void*)&w,           (void*)&y,        (void*)&planes_i,

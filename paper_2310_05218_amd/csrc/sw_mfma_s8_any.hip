@@ -14,6 +14,8 @@
 // the B operand.  No column matrix exists anywhere.
 #include "swconv_internal.h"
 
+#include <cstdlib>
+
 namespace swconv {
 
 namespace {
@@ -29,7 +31,8 @@ constexpr int kLdsBudget = 156 * 1024;  // one workgroup per CU up to here
 struct S8AnyParams {
     int C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
     int TH, TW, IH, IW, tiles_x, rawpitch, w_dwords;
-    FastDiv by_tiles_x, by_TW, by_IW, by_win, by_RS, by_span, by_span4;
+    int x_dwords, nq;                  // input rows are read as aligned dwords (four pixels); quads per window row
+    FastDiv by_tiles_x, by_TW, by_IW, by_win, by_RS, by_span, by_span4, by_nq, by_rowq;
 };
 
 // RQ: the sums leave requantised to int8 (y8) instead of as int32 (y).
@@ -76,7 +79,38 @@ __global__ __launch_bounds__(256) void mfma_s8_any_kernel(const int8_t* __restri
     const int8_t* wb = w + (int64_t)co0 * wrow;
 
     for (int ci0 = 0; ci0 < P.C_in; ci0 += CK) {
-        // ---- input window: slot = (group of four channels, window pixel); consecutive lanes take
+        if (P.x_dwords) {
+            // ---- input window, rows whose quads of four pixels are aligned dwords (W a multiple of 4): slot =
+            //      (group of four channels, window row, quad); four dword loads (one per channel, coalesced along
+            //      the image row), a 4 x 4 byte transpose in registers, one dword per pixel into LDS.  A quarter of
+            //      the load instructions of the byte path below.
+            const int q0 = gcol0 >> 2;                         // first quad that touches the window (floor)
+            const int rowq = P.IH * P.nq;
+            for (int idx = tid; idx < G * rowq; idx += 256) {
+                const int g = fast_div(idx, P.by_rowq);
+                const int t = idx - g * rowq;
+                const int e = fast_div(t, P.by_nq), qd = t - e * P.nq;
+                const int gr = grow0 + e, gc = 4 * (q0 + qd);  // image row, image column of the quad's first pixel
+                u32 r[4] = {0u, 0u, 0u, 0u};
+                if (gr >= 0 && gr < P.H && gc >= 0 && gc < P.W) {
+                    const int8_t* src = xn + (int64_t)(ci0 + 4 * g) * HW + gr * P.W + gc;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        if (ci0 + 4 * g + j < P.C_in) r[j] = *reinterpret_cast<const u32*>(src + (int64_t)j * HW);
+                }
+                const int f0 = gc - gcol0;                     // window column of the quad's first pixel
+#pragma unroll
+                for (int px = 0; px < 4; ++px) {
+                    // byte px of the four channel dwords -> one dword: channels 4g .. 4g+3 of this pixel
+                    const u32 t01 = __builtin_amdgcn_perm(r[1], r[0], (u32)px | ((u32)(4 + px) << 8));
+                    const u32 t23 = __builtin_amdgcn_perm(r[3], r[2], (u32)px | ((u32)(4 + px) << 8));
+                    const u32 packed = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
+                    const int f = f0 + px;
+                    if (f >= 0 && f < P.IW) *reinterpret_cast<u32*>(xs + (e * P.IW + f) * kPitch + 4 * g) = packed;
+                }
+            }
+        } else {
+        // ---- input window, any alignment: slot = (group of four channels, window pixel); consecutive lanes take
         //      consecutive pixels, so each of the four byte loads is coalesced along the image row
         for (int idx = tid; idx < G * WP; idx += 256) {
             const int g = fast_div(idx, P.by_win);
@@ -91,6 +125,7 @@ __global__ __launch_bounds__(256) void mfma_s8_any_kernel(const int8_t* __restri
                     if (ci0 + 4 * g + j < P.C_in) packed |= (u32)(unsigned char)src[(int64_t)j * HW] << (8 * j);
             }
             *reinterpret_cast<u32*>(xs + q * kPitch + 4 * g) = packed;
+        }
         }
         // ---- filters, first as they lie in memory: row co_l of the staging area is bytes ci0*RS .. +span of
         //      that output channel's filter (zero beyond C_in and C_out)
@@ -223,6 +258,11 @@ hipError_t launch_s8_any(const int8_t* x, const int8_t* w, int32_t* y, const Con
     P.by_RS = make_fastdiv(s.R * s.S);
     P.by_span = make_fastdiv(span);
     P.by_span4 = make_fastdiv(P.w_dwords ? span / 4 : 1);
+    // aligned dword reads of the input rows: every row of every plane starts on a 4-byte boundary
+    P.x_dwords = s.W % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && !getenv("SWCONV_S8_BYTE_X");
+    P.nq = (a.IW + 3) / 4 + 1;                  // quads that can touch a window row, whatever its alignment
+    P.by_nq = make_fastdiv(P.nq);
+    P.by_rowq = make_fastdiv(a.IH * P.nq);
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
     hipLaunchKernelGGL((mfma_s8_any_kernel<CK, RQ>), grid, dim3(256), a.lds, st, x, w, y, P, y8, rq);
     return hipGetLastError();

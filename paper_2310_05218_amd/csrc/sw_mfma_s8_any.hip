@@ -127,6 +127,19 @@ __global__ __launch_bounds__(256) void mfma_s8_any_kernel(const int8_t* __restri
             *reinterpret_cast<u32*>(xs + q * kPitch + 4 * g) = packed;
         }
         }
+        if (RS == 1 && P.w_dwords) {
+            // ---- 1 x 1 filters: four consecutive input channels of an output channel are one aligned dword of w
+            //      and one dword of the operand row: copied straight into place, no staging area, no regrouping
+            const int left1 = P.C_in - ci0;
+            for (int idx = tid; idx < 64 * G; idx += 256) {
+                const int co_l = idx / G, g = idx - co_l * G;     // G is a power of two
+                u32 v = 0;
+                if (co0 + co_l < P.C_out && 4 * g < left1)
+                    v = *reinterpret_cast<const u32*>(wb + co_l * wrow + ci0 + 4 * g);
+                *reinterpret_cast<u32*>(ws + co_l * kPitch + 4 * g) = v;
+            }
+            __syncthreads();
+        } else {
         // ---- filters, first as they lie in memory: row co_l of the staging area is bytes ci0*RS .. +span of
         //      that output channel's filter (zero beyond C_in and C_out)
         const int left = (P.C_in - ci0) * RS;                 // bytes that exist from ci0 on
@@ -160,6 +173,7 @@ __global__ __launch_bounds__(256) void mfma_s8_any_kernel(const int8_t* __restri
         }
         __syncthreads();
 
+        }
         if (wave_live) {
             const unsigned char* bsrc = xs + pixoff * kPitch + 16 * kg;
             const unsigned char* asrc = ws + lj * kPitch + 16 * kg;

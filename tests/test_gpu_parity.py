@@ -552,7 +552,12 @@ S8_CASES = [
     (2, 40, 33, 12, 150, 3, 3, 1, 1),    # ... output rows wider than a tile
     (1, 70, 65, 20, 9, 5, 3, 1, 2),      # ... rectangular filter, two channel chunks, ragged channel block
     (3, 64, 96, 7, 7, 3, 3, 1, 1),       # ... small images
-    (2, 100, 64, 14, 14, 1, 1, 1, 0),    # ... pointwise
+    (2, 100, 64, 14, 14, 1, 1, 1, 0),    # ... pointwise (two chunks, the second ragged; width not a multiple of 4)
+    (2, 64, 70, 28, 28, 1, 1, 1, 0),     # ... pointwise, rows read as dwords, ragged output-channel block
+    (1, 36, 64, 16, 20, 1, 1, 2, 0),     # ... pointwise with stride, C_in a multiple of 4 but not of the chunk
+    (1, 30, 16, 16, 16, 1, 1, 1, 0),     # ... pointwise, C_in not a multiple of 4: byte copy of the filters
+    (2, 8, 8, 24, 36, 3, 3, 1, 2),       # ... dword rows with padding on both sides
+    (1, 16, 32, 33, 40, 4, 4, 3, 1),     # ... stride 3, even filter
     (1, 64, 64, 17, 19, 3, 3, 2, 1),     # ... stride 2
     (1, 2, 4, 5, 5, 5, 5, 1, 0),         # ... a single output pixel
     (1, 9, 130, 16, 16, 2, 2, 2, 0),

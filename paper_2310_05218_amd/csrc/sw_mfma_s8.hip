@@ -27,6 +27,7 @@
 #include <algorithm>
 
 #include "swconv_internal.h"
+#include "sw_s8_perm.h"
 
 namespace swconv {
 
@@ -35,6 +36,9 @@ namespace {
 typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32;
+using s8perm::gather4;
+using s8perm::perm;
+using s8perm::wgather_tap;
 
 constexpr int kCK = 64;            // input channels per chunk
 constexpr int kPitchChunk = 80;    // bytes per pixel / per weight row in LDS, chunked variant
@@ -49,36 +53,6 @@ constexpr int kRawBytes = 64 * kCK * 9;             // 36864
 constexpr int kLdsBytes = kXBytesChunk + kWBytesChunk + kRawBytes;
 constexpr int kLdsPxRes = 270;     // window pixels of the resident variant (9 rows x 30)
 constexpr int kLdsBytesRes = kLdsPxRes * 144 + 9 * 64 * 144 + kRawBytes;   // 158688 of 163840
-
-// byte k of the result = byte sel_k of the 8-byte value {hi, lo} (lo = bytes 0..3)
-__device__ __forceinline__ u32 perm(u32 hi, u32 lo, u32 sel) { return __builtin_amdgcn_perm(hi, lo, sel); }
-
-// Gathers bytes P0..P3 (byte positions in the dword array r) into one dword.
-template <int P0, int P1, int P2, int P3>
-__device__ __forceinline__ u32 gather4(const u32* r)
-{
-    const u32 t01 = perm(r[P1 >> 2], r[P0 >> 2], (u32)(P0 & 3) | ((u32)(4 + (P1 & 3)) << 8));
-    const u32 t23 = perm(r[P3 >> 2], r[P2 >> 2], (u32)(P2 & 3) | ((u32)(4 + (P3 & 3)) << 8));
-    return perm(t23, t01, 0x05040100u);
-}
-
-// out[tap][a] = channels 4a..4a+3 of tap `tap`, from raw = 16 channels x 9 taps (tap fastest)
-template <int TAP, int A>
-__device__ __forceinline__ u32 wgather(const u32* raw)
-{
-    return gather4<(4 * A) * 9 + TAP, (4 * A + 1) * 9 + TAP, (4 * A + 2) * 9 + TAP, (4 * A + 3) * 9 + TAP>(raw);
-}
-
-template <int TAP>
-__device__ __forceinline__ intx4 wgather_tap(const u32* raw)
-{
-    intx4 v;
-    v.x = (int)wgather<TAP, 0>(raw);
-    v.y = (int)wgather<TAP, 1>(raw);
-    v.z = (int)wgather<TAP, 2>(raw);
-    v.w = (int)wgather<TAP, 3>(raw);
-    return v;
-}
 
 // 16 channels x 4 pixels (one dword per channel) -> pixel PX's 16 channel bytes
 template <int PX>

@@ -13,6 +13,7 @@
 // Every tap is then CK / 32 matrix instructions per 32 x 32 block, the shift being an LDS address offset of
 // the B operand.  No column matrix exists anywhere.
 #include "swconv_internal.h"
+#include "sw_s8_perm.h"
 
 #include <cstdlib>
 
@@ -162,7 +163,28 @@ __global__ __launch_bounds__(256) void mfma_s8_any_kernel(const int8_t* __restri
             }
         }
         __syncthreads();
-        // ---- ... then regrouped: slot = (output channel, group of four input channels, tap)
+        // ---- ... then regrouped.  3 x 3 filters: a thread takes the 144 contiguous bytes of (output channel, 16 input
+        //      channels) as 36 dwords and permutes them in registers into nine 16-byte operand pieces, one per tap
+        if (RS == 9 && P.w_dwords) {
+            for (int idx = tid; idx < 64 * (CK / 16); idx += 256) {
+                const int co_l = idx / (CK / 16), c16 = idx - co_l * (CK / 16);
+                const u32* src = reinterpret_cast<const u32*>(raw + co_l * P.rawpitch + c16 * 144);
+                u32 r36[36];
+#pragma unroll
+                for (int i = 0; i < 36; ++i) r36[i] = src[i];
+                unsigned char* dst = ws + co_l * kPitch + 16 * c16;
+                *reinterpret_cast<intx4*>(dst + 0 * 64 * kPitch) = s8perm::wgather_tap<0>(r36);
+                *reinterpret_cast<intx4*>(dst + 1 * 64 * kPitch) = s8perm::wgather_tap<1>(r36);
+                *reinterpret_cast<intx4*>(dst + 2 * 64 * kPitch) = s8perm::wgather_tap<2>(r36);
+                *reinterpret_cast<intx4*>(dst + 3 * 64 * kPitch) = s8perm::wgather_tap<3>(r36);
+                *reinterpret_cast<intx4*>(dst + 4 * 64 * kPitch) = s8perm::wgather_tap<4>(r36);
+                *reinterpret_cast<intx4*>(dst + 5 * 64 * kPitch) = s8perm::wgather_tap<5>(r36);
+                *reinterpret_cast<intx4*>(dst + 6 * 64 * kPitch) = s8perm::wgather_tap<6>(r36);
+                *reinterpret_cast<intx4*>(dst + 7 * 64 * kPitch) = s8perm::wgather_tap<7>(r36);
+                *reinterpret_cast<intx4*>(dst + 8 * 64 * kPitch) = s8perm::wgather_tap<8>(r36);
+            }
+        } else
+        // any other extent: slot = (output channel, group of four input channels, tap)
         for (int idx = tid; idx < 64 * G * RS; idx += 256) {
             const int cg = fast_div(idx, P.by_RS);            // co_l * G + g
             const int tap = idx - cg * RS;

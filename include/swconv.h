@@ -176,6 +176,24 @@ int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, 
                          int stride, int pad, int relu, void* hip_stream);
 
 /*
+ * A depthwise-separable block in one launch (paper, section 1.2: depthwise
+ * separable convolutions; sections 1 and 2: nothing but input, filters and output
+ * moves): depthwise 3 x 3 (stride 1, padding 1) with bias and optional rectifier,
+ * then a pointwise 1 x 1 convolution with bias and optional rectifier,
+ *     t[n,c,i,j]  = act_dw( sum_{r,s} w_dw[c,0,r,s] * xz[n,c,i+r-1,j+s-1] + b_dw[c] )
+ *     y[n,co,i,j] = act_pw( sum_c w_pw[co,c,0,0] * t[n,c,i,j] + b_pw[co] )
+ * with t kept in LDS: it is never written to device memory.
+ * x: [N,C,H,W];  w_dw: [C,1,3,3];  b_dw: [C] or NULL;  w_pw: [C_out,C,1,1];
+ * b_pw: [C_out] or NULL;  y: [N,C_out,H,W].  All fp32, products and sums fp32.
+ * Errors as sw_conv2d (SW_ERR_NULL, _SHAPE, _ALIGN, _ALIAS); any N, C, C_out, H, W
+ * within the 2^31-1 element bound is supported.
+ */
+int sw_dw_pw_block(const float* x, const float* w_dw, const float* b_dw,
+                   const float* w_pw, const float* b_pw, float* y,
+                   int N, int C, int C_out, int H, int W,
+                   int relu_dw, int relu_pw, void* hip_stream);
+
+/*
  * Depthwise 2-D convolution on bf16 activations with fp32 accumulation (paper,
  * section 1.1: reduced-precision inference; the sliding kernels are bound by the
  * bytes of the planes, which this halves).  x and y hold bf16 bit patterns (the

@@ -291,3 +291,27 @@ def conv2d_s8_nhwc_requant(x, w, bias, scale, stride: int = 1, pad: int = 0, rel
     q = conv2d_s8_requant(np.ascontiguousarray(x.transpose(0, 3, 1, 2)), np.ascontiguousarray(w.transpose(0, 3, 1, 2)),
                           bias, scale, stride, pad, relu)
     return np.ascontiguousarray(q.transpose(0, 2, 3, 1))
+
+
+def dw_pw_block(x, w_dw, b_dw, w_pw, b_pw, relu_dw: bool = True, relu_pw: bool = False):
+    """A depthwise-separable block in fp64: t = act_dw(depthwise3x3(x, stride 1, pad 1) + b_dw), then
+    y = act_pw(sum_c w_pw[co, c] * t[c] + b_pw[co]).  The depthwise stage is conv2d_depthwise_bias_relu; the pointwise
+    stage is a plain matrix product over the channels (numpy, fp64).  Returns (y, D): D is the magnitude sum of the
+    composite, sum_c |w_pw[co, c]| * D_dw[c] + |b_pw[co]|, the scale the parity tolerance is relative to."""
+    w_dw = _as(w_dw, np.float32, 4)
+    w_pw = _as(w_pw, np.float32, 4)
+    if w_dw.shape[1:] != (1, 3, 3) or w_pw.shape[2:] != (1, 1) or w_pw.shape[1] != w_dw.shape[0]:
+        raise ValueError("w_dw must be [C,1,3,3] and w_pw [C_out,C,1,1]")
+    t, d_t = conv2d_depthwise_bias_relu(x, w_dw, b_dw, 1, 1, relu_dw)
+    m = w_pw[:, :, 0, 0].astype(np.float64)
+    y = np.einsum("oc,nchw->nohw", m, t)
+    d = np.einsum("oc,nchw->nohw", np.abs(m), d_t)
+    if b_pw is not None:
+        b = _as(b_pw, np.float32, 1).astype(np.float64)
+        if b.shape[0] != m.shape[0]:
+            raise ValueError("one pointwise bias per output channel")
+        y += b[None, :, None, None]
+        d += np.abs(b)[None, :, None, None]
+    if relu_pw:
+        y = np.maximum(y, 0.0)
+    return y, d

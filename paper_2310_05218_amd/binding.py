@@ -17,7 +17,7 @@ SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN, SW_ERR_ALIAS, SW_ER
 SW_POOL_AVG, SW_POOL_MAX = 0, 1
 
 EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
-           "sw_conv2d_s8_requant", "sw_conv2d_s8_nhwc", "sw_conv2d_s8_nhwc_requant", "sw_conv2d_bias_relu", "sw_conv2d_depthwise_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
+           "sw_conv2d_s8_requant", "sw_conv2d_s8_nhwc", "sw_conv2d_s8_nhwc_requant", "sw_conv2d_bias_relu", "sw_dw_pw_block", "sw_conv2d_depthwise_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
            "sw_conv2d_depthwise_bf16", "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
            "sw_jit_cached_kernels",
            "sw_out_dim", "sw_workspace_bytes", "sw_status_string", "sw_version")
@@ -52,6 +52,8 @@ def lib() -> ctypes.CDLL:
     L.sw_conv2d_bias_relu.argtypes = [vp, vp, vp, vp] + [i32] * 10 + [vp]
     L.sw_conv2d_depthwise_bias_relu.restype = i32
     L.sw_conv2d_depthwise_bias_relu.argtypes = [vp, vp, vp, vp] + [i32] * 9 + [vp]
+    L.sw_dw_pw_block.restype = i32
+    L.sw_dw_pw_block.argtypes = [vp] * 6 + [i32] * 7 + [vp]
     L.sw_conv2d_dilated.restype = i32
     L.sw_conv2d_dilated.argtypes = [vp, vp, vp] + [i32] * 10 + [vp]
     L.sw_conv2d_depthwise_dilated.restype = i32
@@ -279,6 +281,28 @@ def sw_conv2d_depthwise_bias_relu(x, w, bias, stride: int = 1, pad: int = 0, rel
                                              _dev(out, torch.float32, 4, "y"), N, C, H, W, R, S, stride, pad,
                                              1 if relu else 0, _stream(stream))
     _check(rc, "sw_conv2d_depthwise_bias_relu")
+    return out
+
+
+def sw_dw_pw_block(x, w_dw, b_dw, w_pw, b_pw, relu_dw: bool = True, relu_pw: bool = False, out=None, stream=None):
+    """Depthwise 3x3 (stride 1, pad 1) + bias + rectifier, then pointwise 1x1 + bias + rectifier, in one launch:
+    x [N,C,H,W], w_dw [C,1,3,3], b_dw [C] or None, w_pw [C_out,C,1,1], b_pw [C_out] or None -> y [N,C_out,H,W]."""
+    import torch
+
+    N, C, H, W = x.shape
+    if tuple(w_dw.shape) != (C, 1, 3, 3):
+        raise ValueError("depthwise weights must be [C,1,3,3]")
+    C_out = w_pw.shape[0]
+    if tuple(w_pw.shape) != (C_out, C, 1, 1):
+        raise ValueError("pointwise weights must be [C_out,C,1,1]")
+    if out is None:
+        out = torch.empty((N, C_out, H, W), dtype=torch.float32, device=x.device)
+    f32 = torch.float32
+    rc = lib().sw_dw_pw_block(_dev(x, f32, 4, "x"), _dev(w_dw, f32, 4, "w_dw"),
+                              _dev(b_dw, f32, 1, "b_dw") if b_dw is not None else None, _dev(w_pw, f32, 4, "w_pw"),
+                              _dev(b_pw, f32, 1, "b_pw") if b_pw is not None else None, _dev(out, f32, 4, "y"),
+                              N, C, C_out, H, W, 1 if relu_dw else 0, 1 if relu_pw else 0, _stream(stream))
+    _check(rc, "sw_dw_pw_block")
     return out
 
 

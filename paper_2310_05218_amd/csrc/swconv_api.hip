@@ -326,6 +326,24 @@ int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* b
     return run_s8_nhwc(x, w, bias, scale, nullptr, y, N, H, W, C_in, C_out, R, S, stride, pad, relu, hip_stream);
 }
 
+int sw_dw_pw_block(const float* x, const float* w_dw, const float* b_dw, const float* w_pw, const float* b_pw, float* y,
+                   int N, int C, int C_out, int H, int W, int relu_dw, int relu_pw, void* hip_stream)
+{
+    if (!x || !w_dw || !w_pw || !y) return SW_ERR_NULL;
+    if (N <= 0 || C <= 0 || C_out <= 0 || H <= 0 || W <= 0) return SW_ERR_SHAPE;
+    const int64_t nx = (int64_t)N * C * H * W, ny = (int64_t)N * C_out * H * W, npw = (int64_t)C_out * C;
+    if (nx > kMaxElems || ny > kMaxElems || npw > kMaxElems) return SW_ERR_SHAPE;
+    if (misaligned(x, 4) || misaligned(w_dw, 4) || misaligned(w_pw, 4) || misaligned(y, 4) ||
+        (b_dw && misaligned(b_dw, 4)) || (b_pw && misaligned(b_pw, 4)))
+        return SW_ERR_ALIGN;
+    if (overlaps(y, ny * 4, x, nx * 4) || overlaps(y, ny * 4, w_dw, (int64_t)C * 9 * 4) || overlaps(y, ny * 4, w_pw, npw * 4) ||
+        (b_dw && overlaps(y, ny * 4, b_dw, (int64_t)C * 4)) || (b_pw && overlaps(y, ny * 4, b_pw, (int64_t)C_out * 4)))
+        return SW_ERR_ALIAS;
+    if (!dw_pw_block_supported(N, C, C_out, H, W)) return SW_ERR_UNSUPPORTED;
+    return launch_status(launch_dw_pw_block(x, w_dw, b_dw, w_pw, b_pw, y, N, C, C_out, H, W, relu_dw != 0, relu_pw != 0,
+                                            static_cast<hipStream_t>(hip_stream)));
+}
+
 int sw_conv2d_depthwise_bias_relu(const float* x, const float* w, const float* bias, float* y, int N, int C, int H,
                                   int W, int R, int S, int stride, int pad, int relu, void* hip_stream)
 {

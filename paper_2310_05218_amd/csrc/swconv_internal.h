@@ -102,6 +102,11 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0});
 
+// ---- depthwise 3x3 (stride 1, padding 1) -> pointwise 1x1 in one launch, the intermediate only in LDS
+bool       dw_pw_block_supported(int N, int C, int C_out, int H, int W);
+hipError_t launch_dw_pw_block(const float* x, const float* w_dw, const float* b_dw, const float* w_pw, const float* b_pw,
+                              float* y, int N, int C, int C_out, int H, int W, int relu1, int relu2, hipStream_t st);
+
 // ---- int8 on channel-last tensors (x [N,H,W,C_in], w [C_out,R,S,C_in], y [N,Ho,Wo,C_out]); rq == nullptr: int32 out
 bool       mfma_s8_nhwc_supported(const int8_t* x, const int8_t* w, const Conv2dShape& s);
 hipError_t launch_mfma_s8_nhwc(const int8_t* x, const int8_t* w, int32_t* y, int8_t* y8, const Requant* rq,

@@ -149,6 +149,24 @@ def test_depthwise_argument_errors(L):
     assert f(X, W_, X + 64, *ok, None) == B.SW_ERR_ALIAS
 
 
+def test_block_argument_errors(L):
+    f = L.sw_dw_pw_block
+    WD, BD, WP, BP = 0x2100000, 0x2200000, 0x2300000, 0x2400000
+    ok = (2, 16, 32, 8, 8)                      # N, C, C_out, H, W
+    assert f(None, WD, BD, WP, BP, Y, *ok, 1, 0, None) == B.SW_ERR_NULL
+    assert f(X, None, BD, WP, BP, Y, *ok, 1, 0, None) == B.SW_ERR_NULL
+    assert f(X, WD, BD, None, BP, Y, *ok, 1, 0, None) == B.SW_ERR_NULL
+    assert f(X, WD, BD, WP, BP, None, *ok, 1, 0, None) == B.SW_ERR_NULL
+    for i in range(5):
+        bad = list(ok)
+        bad[i] = 0
+        assert f(X, WD, BD, WP, BP, Y, *bad, 1, 0, None) == B.SW_ERR_SHAPE, i
+    assert f(X, WD, BD + 2, WP, BP, Y, *ok, 1, 0, None) == B.SW_ERR_ALIGN
+    assert f(X, WD, BD, WP, BP, X + 64, *ok, 1, 0, None) == B.SW_ERR_ALIAS
+    assert f(X, WD, BD, Y + 16, BP, Y, *ok, 1, 0, None) == B.SW_ERR_ALIAS
+    assert f(X, WD, None, WP, Y + 32, Y, *ok, 1, 0, None) == B.SW_ERR_ALIAS
+
+
 def test_s8_nhwc_argument_errors(L):
     f, g = L.sw_conv2d_s8_nhwc, L.sw_conv2d_s8_nhwc_requant
     B_, SC = 0x2100000, 0x2200000

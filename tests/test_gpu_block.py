@@ -1,0 +1,77 @@
+"""GPU parity of the depthwise-separable block (sw_dw_pw_block: depthwise 3x3 + bias + rectifier and pointwise 1x1 +
+bias + rectifier in one launch) against the CPU oracle.  Two chained fp32 stages: each contributes at most 2e-5 of
+its magnitude sum, so the bound is 4e-5 of the composite magnitude sum D the oracle returns."""
+import numpy as np
+import pytest
+
+from paper_2310_05218_amd import inputs
+from parity import assert_guards_intact, guarded_empty
+
+pytestmark = pytest.mark.gpu
+TOL = 4e-5
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch as _t
+
+    assert _t.cuda.is_available(), "these tests need the GPU"
+    return _t
+
+
+@pytest.fixture(scope="module")
+def sw():
+    import paper_2310_05218_amd as _sw
+    from paper_2310_05218_amd import binding
+
+    binding.lib()            # fails loudly if the library is not built
+    return _sw
+
+
+def dev(torch, a):
+    return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+CASES = [
+    # N, C, C_out, H, W, bias_dw, bias_pw, relu_dw, relu_pw
+    (2, 32, 64, 56, 56, True, True, True, False),     # one channel chunk, one output block, two-row tiles
+    (1, 96, 24, 56, 56, True, True, True, True),      # three chunks, ragged output block (MobileNet bottleneck)
+    (2, 40, 70, 28, 28, True, False, True, False),    # ragged last chunk, two output blocks
+    (1, 8, 8, 14, 14, False, False, False, False),    # neither bias nor rectifier; nine-row tiles
+    (3, 33, 65, 7, 7, True, True, True, True),        # whole image in a tile, odd channel counts
+    (1, 16, 32, 20, 150, True, True, True, False),    # rows wider than a tile: column tiles with a ragged last one
+    (1, 5, 3, 1, 1, True, True, False, True),         # a single pixel
+    (1, 64, 64, 31, 37, True, True, True, True),      # ragged rows and columns
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_block_matches_the_oracle(torch, sw, oracle, case):
+    N, C, C_out, H, W, bdw, bpw, r1, r2 = case
+    x = inputs.normal_f32((N, C, H, W), 7201)
+    w_dw = inputs.normal_f32((C, 1, 3, 3), 7202, 1.0 / 3)
+    w_pw = inputs.normal_f32((C_out, C, 1, 1), 7203, (2.0 / C) ** 0.5)
+    b_dw = inputs.normal_f32((C,), 7204, 0.3) if bdw else None
+    b_pw = inputs.normal_f32((C_out,), 7205, 0.3) if bpw else None
+    y_ref, d = oracle.dw_pw_block(x, w_dw, b_dw, w_pw, b_pw, r1, r2)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_dw_pw_block(dev(torch, x), dev(torch, w_dw), dev(torch, b_dw), dev(torch, w_pw), dev(torch, b_pw), r1, r2, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    y = out.cpu().numpy().astype(np.float64)
+    err = float(np.max(np.abs(y - y_ref) / np.maximum(d, 1e-300)))
+    assert err <= TOL, f"dw-pw block {case}: normalised error {err:.3e}"
+
+
+def test_block_equals_the_two_separate_launches(torch, sw):
+    """The fused launch against the library's own depthwise and pointwise entry points chained through memory."""
+    x = dev(torch, inputs.normal_f32((2, 64, 56, 56), 7211))
+    w_dw = dev(torch, inputs.normal_f32((64, 1, 3, 3), 7212, 1.0 / 3))
+    w_pw = dev(torch, inputs.normal_f32((128, 64, 1, 1), 7213, 0.18))
+    b_dw = dev(torch, inputs.normal_f32((64,), 7214, 0.3))
+    b_pw = dev(torch, inputs.normal_f32((128,), 7215, 0.3))
+    fused = sw.sw_dw_pw_block(x, w_dw, b_dw, w_pw, b_pw, True, True)
+    t = sw.sw_conv2d_depthwise_bias_relu(x, w_dw, b_dw, 1, 1, True)
+    two = sw.sw_conv2d_bias_relu(t, w_pw, b_pw, 1, 0, True)
+    scale = float(two.abs().max())
+    assert float((fused - two).abs().max()) <= 1e-5 * scale

@@ -273,6 +273,12 @@ LAYERS = [
     ("conv_3x3_64to64_bias_relu", "conv_br", (32, 64, 56, 56), 3, 1, 1, 64),
     ("conv_3x3_14x14_256_bias_relu", "conv_br", (32, 256, 14, 14), 3, 1, 1, 256),
     ("conv_3x3_dilation2_64to64", "conv_dil", (32, 64, 56, 56), 3, 1, 2, 64),
+    ("block_dw3x3_pw_128to128_56x56", "block", (32, 128, 56, 56), 3, 1, 1, 128),
+    ("block_two_launches_128to128_56x56", "block2", (32, 128, 56, 56), 3, 1, 1, 128),
+    ("block_dw3x3_pw_256to256_28x28", "block", (32, 256, 28, 28), 3, 1, 1, 256),
+    ("block_two_launches_256to256_28x28", "block2", (32, 256, 28, 28), 3, 1, 1, 256),
+    ("block_dw3x3_pw_512to512_14x14", "block", (32, 512, 14, 14), 3, 1, 1, 512),
+    ("block_two_launches_512to512_14x14", "block2", (32, 512, 14, 14), 3, 1, 1, 512),
     ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
     ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
     ("conv_s8_requant_3x3_128to128", "conv_s8_rq", (32, 128, 28, 28), 3, 1, 1, 128),
@@ -309,6 +315,12 @@ def layer_case(idx, n_images=None):
         if "nhwc" in kind:
             x = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
             w = np.ascontiguousarray(w.transpose(0, 2, 3, 1))
+    elif kind.startswith("block"):      # depthwise 3x3 + bias + ReLU, pointwise 1x1 + bias + ReLU: fused, or two launches
+        x = inputs.normal_f32((N, C, H, W), inputs.seed_for(7, idx))
+        w = inputs.normal_f32((C, 1, 3, 3), inputs.seed_for(7, 100 + idx), 1.0 / 3)
+        c["w_pw"] = inputs.normal_f32((c["C_out"], C, 1, 1), inputs.seed_for(7, 300 + idx), (2.0 / C) ** 0.5)
+        c["bias"] = inputs.normal_f32((C,), inputs.seed_for(7, 200 + idx), 0.3)
+        c["bias_pw"] = inputs.normal_f32((c["C_out"],), inputs.seed_for(7, 400 + idx), 0.3)
     elif kind.startswith("conv"):
         x = inputs.normal_f32((N, C, H, W), inputs.seed_for(7, idx))
         w = inputs.normal_f32((c["C_out"], C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
@@ -338,8 +350,13 @@ def layer_device(torch, c):
     odt = (torch.bfloat16 if kind == "dw_bf16" else torch.int8 if kind.endswith("rq") else
            torch.int32 if kind.startswith("conv_s8") else torch.float32)
     oshape = ((c["N"], c["Ho"], c["Wo"], c["C_out"]) if "nhwc" in kind else (c["N"], c["C_out"], c["Ho"], c["Wo"]))
-    return {"x": xd, "w": dev(c["w"]), "bias": dev(c.get("bias")), "scale": dev(c.get("scale")),
-            "y": torch.empty(oshape, dtype=odt, device="cuda")}
+    d = {"x": xd, "w": dev(c["w"]), "bias": dev(c.get("bias")), "scale": dev(c.get("scale")),
+         "y": torch.empty(oshape, dtype=odt, device="cuda")}
+    if kind.startswith("block"):
+        d["w_pw"], d["bias_pw"] = dev(c["w_pw"]), dev(c["bias_pw"])
+        if kind == "block2":            # the intermediate of the two-launch form lives in device memory
+            d["t"] = torch.empty((c["N"], c["C"], c["H"], c["W"]), device="cuda")
+    return d
 
 
 def layer_call(sw, c, d, x=None, y=None):
@@ -355,6 +372,11 @@ def layer_call(sw, c, d, x=None, y=None):
         return sw.sw_conv2d_depthwise_bias_relu(x, d["w"], d["bias"], st, p, True, out=y)
     if kind == "dw_bf16":
         return sw.sw_conv2d_depthwise_bf16(x, d["w"], st, p, out=y)
+    if kind == "block":
+        return sw.sw_dw_pw_block(x, d["w"], d["bias"], d["w_pw"], d["bias_pw"], True, True, out=y)
+    if kind == "block2":
+        sw.sw_conv2d_depthwise_bias_relu(x, d["w"], d["bias"], 1, 1, True, out=d["t"])
+        return sw.sw_conv2d_bias_relu(d["t"], d["w_pw"], d["bias_pw"], 1, 0, True, out=y)
     if kind == "conv":
         return sw.sw_conv2d(x, d["w"], st, p, out=y)
     if kind == "conv_br":
@@ -388,7 +410,10 @@ def strided_and_pooling_table(torch, sw):
         sets = [{"x": d["x"] if i == 0 else d["x"].clone(), "y": torch.empty_like(d["y"])} for i in range(nsets)]
         us = time_kernel(torch, lambda s_: layer_call(sw, c, d, s_["x"], s_["y"]), sets, 4 * nsets)
         outs = N * c["C_out"] * c["Ho"] * c["Wo"]
-        if kind.startswith("conv"):
+        if kind.startswith("block"):
+            ops = 2.0 * N * C * c["H"] * c["W"] * 9 + 2.0 * outs * C
+            nbytes += c["w_pw"].nbytes
+        elif kind.startswith("conv"):
             ops = 2.0 * outs * C * R * R
         elif kind.startswith("dw"):
             ops = 2.0 * outs * R * R
@@ -397,7 +422,7 @@ def strided_and_pooling_table(torch, sw):
         row = {"layer": c["name"], "shape": [N, C, c["H"], c["W"]] + ([c["C_out"]] if kind.startswith("conv") else []),
                "us_cold": round(us, 2), "gbs": round(nbytes / us / 1e3, 1),
                "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4), "gops": round(ops / us / 1e3, 1)}
-        if kind.startswith("conv"):
+        if kind.startswith("conv") or kind.startswith("block"):
             row["frac_mfma"] = round(ops / us / 1e6 / (MFMA_I8_TOPS if "s8" in kind else MFMA_F32_TFLOPS), 4)
         rows.append(row)
         del sets, d

@@ -186,7 +186,10 @@ int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, 
  * x: [N,C,H,W];  w_dw: [C,1,3,3];  b_dw: [C] or NULL;  w_pw: [C_out,C,1,1];
  * b_pw: [C_out] or NULL;  y: [N,C_out,H,W].  All fp32, products and sums fp32.
  * Errors as sw_conv2d (SW_ERR_NULL, _SHAPE, _ALIGN, _ALIAS); any N, C, C_out, H, W
- * within the 2^31-1 element bound is supported.
+ * within the 2^31-1 element bound is supported.  What it saves is the memory and
+ * the traffic of the intermediate (N*C*H*W floats written and read back); as it
+ * stands it is slower than sw_conv2d_depthwise_bias_relu followed by
+ * sw_conv2d_bias_relu (its stages run one after the other inside a workgroup).
  */
 int sw_dw_pw_block(const float* x, const float* w_dw, const float* b_dw,
                    const float* w_pw, const float* b_pw, float* y,

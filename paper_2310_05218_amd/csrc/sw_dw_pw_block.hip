@@ -5,12 +5,14 @@
 // The intermediate t never exists in memory: a workgroup computes it, 32 channels at a time, for its tile of 128
 // output pixels straight into the LDS layout that the matrix instructions read as their B operand
 // ([channel quad][pixel], 16 bytes per entry, as in the 128-pixel fp32 kernel), and multiplies it with the chunk's
-// 64 x 32 pointwise weights.  HBM sees x once per block of 64 output channels and y once.
+// pointwise weights.  HBM sees x once per block of up to 256 output channels and y once.
 //
 // Per chunk: (1) the window of 32 channels (tile + one-pixel frame, zero outside the image) and the chunk's
 // depthwise and pointwise weights go to LDS; (2) every thread computes 16 depthwise outputs (one channel-pixel
-// pair each: nine LDS reads, nine FMAs, bias, rectifier); (3) four groups of eight channels are multiplied,
-// two 32 x 32 blocks per wavefront.  Products and sums are fp32 throughout.
+// pair each: nine LDS reads, nine FMAs, bias, rectifier); (3) four groups of eight channels are multiplied with
+// the weights of up to 256 output channels (NB blocks of 64: two 32 x 32 accumulators per block and wavefront),
+// so that the depthwise stage is computed once per 256 output channels, not once per 64.  Products and sums are
+// fp32 throughout.
 #include "swconv_internal.h"
 
 namespace swconv {
@@ -33,6 +35,7 @@ struct BlockParams {
     FastDiv by_tiles_x, by_TW, by_IW, by_win;
 };
 
+template <int NB>
 __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restrict__ x, const float* __restrict__ w_dw,
                                                           const float* __restrict__ w_pw, float* __restrict__ y,
                                                           const BlockParams P)
@@ -40,8 +43,8 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
     extern __shared__ __attribute__((aligned(16))) float smem_blk[];
     const int WP = P.IH * P.IW;                                  // window pixels per channel
     floatx4* xs = reinterpret_cast<floatx4*>(smem_blk);          // [kQ][128]: the depthwise result, B operand
-    floatx4* ws = xs + kQ * kTilePx;                             // [kQ][64]: pointwise weights, A operand
-    float* wd = reinterpret_cast<float*>(ws + kQ * 64);          // [32][9] depthwise filters, then [32] biases
+    floatx4* ws = xs + kQ * kTilePx;                             // [NB][kQ][64]: pointwise weights, A operand
+    float* wd = reinterpret_cast<float*>(ws + NB * kQ * 64);     // [32][9] depthwise filters, then [32] biases
     float* xw = wd + kCK * 9 + kCK;                              // [32][IH][IW] input window
 
     const int tid = threadIdx.x;
@@ -50,7 +53,7 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
     const int ty = fast_div(blockIdx.x, P.by_tiles_x);
     const int tx = blockIdx.x - ty * P.tiles_x;
     const int n = blockIdx.y;
-    const int co0 = blockIdx.z * 64;
+    const int co0 = blockIdx.z * (64 * NB);
     const int row0 = ty * P.TH, col0 = tx * P.TW;
     const int tile_px = P.TH * P.TW;
     const int p = wave * 32 + lj;
@@ -58,9 +61,11 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
     const bool p_ok = p < tile_px && row0 + pi < P.H && col0 + pj < P.W;
     const bool wave_live = __builtin_amdgcn_readfirstlane(wave * 32) < tile_px;
 
-    floatx16 acc0, acc1;
+    floatx16 acc[NB][2];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { acc0[v] = 0.f; acc1[v] = 0.f; }
+    for (int b = 0; b < NB; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { acc[b][0][v] = 0.f; acc[b][1][v] = 0.f; }
 
     const int HW = P.H * P.W;
     const float* xn = x + (int64_t)n * P.C * HW;
@@ -90,15 +95,15 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
             wd[idx] = v;
         }
         // pointwise weights of the chunk: entry (quad q, output channel co_l) = channels ci0 + 4q .. + 3
-        for (int idx = tid; idx < 64 * kQ; idx += 256) {
-            const int co_l = idx >> 3, q = idx & 7;
+        for (int idx = tid; idx < NB * 64 * kQ; idx += 256) {
+            const int co_l = idx >> 3, q = idx & 7;             // co_l: 0 .. 64 * NB - 1
             floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};
             if (co0 + co_l < P.C_out) {
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
                     if (ci0 + 4 * q + t < P.C) v[t] = wb[(int64_t)co_l * P.C + ci0 + 4 * q + t];
             }
-            ws[q * 64 + co_l] = v;
+            ws[((co_l >> 6) * kQ + q) * 64 + (co_l & 63)] = v;
         }
         __syncthreads();
 
@@ -129,11 +134,14 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
 #pragma unroll
             for (int g = 0; g < kG; ++g) {
                 const floatx4 b = bp[2 * g * kTilePx];
-                const floatx4 a0 = ap[2 * g * 64], a1 = ap[2 * g * 64 + 32];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b[t], acc0, 0, 0, 0);
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b[t], acc1, 0, 0, 0);
+                for (int nb = 0; nb < NB; ++nb) {
+                    const floatx4 a0 = ap[(nb * kQ + 2 * g) * 64], a1 = ap[(nb * kQ + 2 * g) * 64 + 32];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        acc[nb][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0[t], b[t], acc[nb][0], 0, 0, 0);
+                        acc[nb][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1[t], b[t], acc[nb][1], 0, 0, 0);
+                    }
                 }
             }
         }
@@ -144,8 +152,9 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
     if (!p_ok) return;
     float* yp = y + ((int64_t)n * P.C_out + co0) * HW + (row0 + pi) * P.W + col0 + pj;
 #pragma unroll
-    for (int h = 0; h < 4; ++h) {
-        const int cb = h >= 2 ? 32 : 0, v0 = (h & 1) * 8;
+    for (int h = 0; h < 4 * NB; ++h) {
+        const int nb = h >> 2, half = (h >> 1) & 1, v0 = (h & 1) * 8;
+        const int cb = 64 * nb + 32 * half;
         float b[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -155,10 +164,19 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int v = v0 + i, co = cb + 8 * (v >> 2) + 4 * kk + (v & 3);
-            const float t = (h >= 2 ? acc1[v] : acc0[v]) + b[i];
+            const float t = acc[nb][half][v] + b[i];
             if (co0 + co < P.C_out) yp[(int64_t)co * HW] = P.relu2 ? fmaxf(t, 0.f) : t;
         }
     }
+}
+
+constexpr size_t kBlockLds = 112 * 1024;
+
+template <int NB>
+hipError_t allow_lds()
+{
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(dw_pw_block_kernel<NB>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBlockLds);
 }
 
 }  // namespace
@@ -190,14 +208,25 @@ hipError_t launch_dw_pw_block(const float* x, const float* w_dw, const float* b_
     P.by_TW = make_fastdiv(P.TW);
     P.by_IW = make_fastdiv(P.IW);
     P.by_win = make_fastdiv(P.IH * P.IW);
-    const size_t lds = ((size_t)kQ * kTilePx + (size_t)kQ * 64) * 16 +
+    // blocks of 64 output channels per workgroup: as many as the output has, up to four
+    const int nb = C_out > 128 ? 4 : C_out > 64 ? 2 : 1;
+    const size_t lds = ((size_t)kQ * kTilePx + (size_t)nb * kQ * 64) * 16 +
                        ((size_t)kCK * 9 + kCK + (size_t)kCK * P.IH * P.IW) * sizeof(float);
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(dw_pw_block_kernel),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
-    if (attr != hipSuccess) return attr;
-    if (lds > 96 * 1024) return hipErrorInvalidValue;
-    dim3 grid((unsigned)(P.tiles_x * tiles_y), (unsigned)N, (unsigned)((C_out + 63) / 64));
-    hipLaunchKernelGGL(dw_pw_block_kernel, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
+    if (lds > kBlockLds) return hipErrorInvalidValue;
+    dim3 grid((unsigned)(P.tiles_x * tiles_y), (unsigned)N, (unsigned)((C_out + 64 * nb - 1) / (64 * nb)));
+    if (nb == 4) {
+        static const hipError_t attr = allow_lds<4>();
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(dw_pw_block_kernel<4>, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
+    } else if (nb == 2) {
+        static const hipError_t attr = allow_lds<2>();
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(dw_pw_block_kernel<2>, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
+    } else {
+        static const hipError_t attr = allow_lds<1>();
+        if (attr != hipSuccess) return attr;
+        hipLaunchKernelGGL(dw_pw_block_kernel<1>, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
+    }
     return hipGetLastError();
 }
 

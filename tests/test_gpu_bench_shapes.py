@@ -87,6 +87,10 @@ def test_layer(torch, sw, oracle, idx):
             assert np.array_equal(y.cpu().numpy().astype(np.float64), y_ref), c["name"]
         else:
             assert_f32_parity(y.cpu().numpy(), y_ref, np.maximum(mag, 1e-300), c["name"])
+    elif kind in ("block", "block2"):
+        y_ref, mag = oracle.dw_pw_block(x, w, c["bias"], c["w_pw"], c["bias_pw"], True, True)
+        err = float(np.max(np.abs(y.cpu().numpy().astype(np.float64) - y_ref) / np.maximum(mag, 1e-300)))
+        assert err <= 4e-5, (c["name"], err)
     elif kind == "dw":
         assert_f32_parity(y.cpu().numpy(), *oracle.conv2d_depthwise(x, w, st, p), c["name"])
     elif kind == "dw_br":

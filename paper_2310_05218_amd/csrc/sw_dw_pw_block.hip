@@ -72,15 +72,24 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
     const float* wb = w_pw + (int64_t)co0 * P.C;
 
     for (int ci0 = 0; ci0 < P.C; ci0 += kCK) {
-        // ---- (1) input window of the chunk, zero outside the image and beyond C (coalesced along image rows)
-        for (int idx = tid; idx < kCK * WP; idx += 256) {
-            const int c = fast_div(idx, P.by_win);
-            const int q = idx - c * WP;
-            const int e = fast_div(q, P.by_IW), f = q - e * P.IW;
-            const int gr = row0 - 1 + e, gc = col0 - 1 + f;
-            float v = 0.f;
-            if (ci0 + c < P.C && gr >= 0 && gr < P.H && gc >= 0 && gc < P.W) v = xn[(int64_t)(ci0 + c) * HW + gr * P.W + gc];
-            xw[idx] = v;
+        // ---- (1) input window of the chunk, zero outside the image and beyond C (coalesced along image rows); eight
+        //      loads go out per thread before the first LDS write, so a batch costs one memory round trip
+        for (int base = tid; base < kCK * WP; base += 256 * 8) {
+            float v8[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int idx = base + 256 * u;
+                const int c = fast_div(idx, P.by_win);
+                const int q = idx - c * WP;
+                const int e = fast_div(q, P.by_IW), f = q - e * P.IW;
+                const int gr = row0 - 1 + e, gc = col0 - 1 + f;
+                v8[u] = 0.f;
+                if (idx < kCK * WP && ci0 + c < P.C && gr >= 0 && gr < P.H && gc >= 0 && gc < P.W)
+                    v8[u] = xn[(int64_t)(ci0 + c) * HW + gr * P.W + gc];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (base + 256 * u < kCK * WP) xw[base + 256 * u] = v8[u];
         }
         // depthwise filters and biases of the chunk
         for (int idx = tid; idx < kCK * 9 + kCK; idx += 256) {
@@ -109,6 +118,7 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
 
         // ---- (2) depthwise 3 x 3 with bias and rectifier, written as the matrix product's B operand
         float* xs_f = reinterpret_cast<float*>(xs);
+#pragma unroll 4
         for (int it = tid; it < kCK * kTilePx; it += 256) {
             const int c = it >> 7, pp = it & (kTilePx - 1);
             float v = 0.f;

@@ -161,25 +161,45 @@ __global__ __launch_bounds__(256) void mfma_f32_any_kernel(const float* __restri
         }
     } else {
         for (int ci0 = 0; ci0 < P.C_in; ci0 += CK) {
-            // input window (coalesced along image rows), zero outside the image and beyond C_in
-            for (int idx = tid; idx < CK * WP; idx += 256) {
-                const int c = fast_div(idx, P.by_win);
-                const int q = idx - c * WP;
-                const int e = fast_div(q, P.by_IW), f = q - e * P.IW;
-                const int gr = grow0 + e, gc = gcol0 + f;
-                float v = 0.f;
-                if (ci0 + c < P.C_in && gr >= 0 && gr < P.H && gc >= 0 && gc < P.W)
-                    v = xn[(int64_t)(ci0 + c) * HW + gr * P.W + gc];
-                xs[idx] = v;
+            // input window (coalesced along image rows), zero outside the image and beyond C_in; eight loads go out
+            // per thread before the first LDS write, so a batch costs one memory round trip instead of eight
+            for (int base = tid; base < CK * WP; base += 256 * 8) {
+                float v8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = base + 256 * u;
+                    const int c = fast_div(idx, P.by_win);
+                    const int q = idx - c * WP;
+                    const int e = fast_div(q, P.by_IW), f = q - e * P.IW;
+                    const int gr = grow0 + e, gc = gcol0 + f;
+                    v8[u] = 0.f;
+                    if (idx < CK * WP && ci0 + c < P.C_in && gr >= 0 && gr < P.H && gc >= 0 && gc < P.W)
+                        v8[u] = xn[(int64_t)(ci0 + c) * HW + gr * P.W + gc];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (base + 256 * u < CK * WP) xs[base + 256 * u] = v8[u];
             }
-            // filters: for one output channel the chunk's span floats are contiguous in memory
+            // filters: for one output channel the chunk's span floats are contiguous in memory (batched likewise)
             const int left = (P.C_in - ci0) * RS;
-            for (int idx = tid; idx < 64 * span; idx += 256) {
-                const int co_l = fast_div(idx, P.by_span);
-                const int q = idx - co_l * span;
-                float v = 0.f;
-                if (co0 + co_l < P.C_out && q < left) v = wb[co_l * wrow + (int64_t)ci0 * RS + q];
-                ws[co_l * P.wpitch + q] = v;
+            for (int base = tid; base < 64 * span; base += 256 * 8) {
+                float v8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = base + 256 * u;
+                    const int co_l = fast_div(idx, P.by_span);
+                    const int q = idx - co_l * span;
+                    v8[u] = 0.f;
+                    if (idx < 64 * span && co0 + co_l < P.C_out && q < left) v8[u] = wb[co_l * wrow + (int64_t)ci0 * RS + q];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = base + 256 * u;
+                    if (idx < 64 * span) {
+                        const int co_l = fast_div(idx, P.by_span);
+                        ws[co_l * P.wpitch + (idx - co_l * span)] = v8[u];
+                    }
+                }
             }
             __syncthreads();
             multiply();

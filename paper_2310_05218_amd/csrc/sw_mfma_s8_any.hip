@@ -87,27 +87,40 @@ __global__ __launch_bounds__(256) void mfma_s8_any_kernel(const int8_t* __restri
             //      the load instructions of the byte path below.
             const int q0 = gcol0 >> 2;                         // first quad that touches the window (floor)
             const int rowq = P.IH * P.nq;
-            for (int idx = tid; idx < G * rowq; idx += 256) {
-                const int g = fast_div(idx, P.by_rowq);
-                const int t = idx - g * rowq;
-                const int e = fast_div(t, P.by_nq), qd = t - e * P.nq;
-                const int gr = grow0 + e, gc = 4 * (q0 + qd);  // image row, image column of the quad's first pixel
-                u32 r[4] = {0u, 0u, 0u, 0u};
-                if (gr >= 0 && gr < P.H && gc >= 0 && gc < P.W) {
-                    const int8_t* src = xn + (int64_t)(ci0 + 4 * g) * HW + gr * P.W + gc;
+            for (int base = tid; base < G * rowq; base += 256 * 2) {
+                u32 r[2][4];
+                int e2[2], f2[2], g2[2];
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        if (ci0 + 4 * g + j < P.C_in) r[j] = *reinterpret_cast<const u32*>(src + (int64_t)j * HW);
+                for (int u = 0; u < 2; ++u) {                  // the loads of two slots go out together
+                    const int idx = base + 256 * u;
+                    const int g = fast_div(idx, P.by_rowq);
+                    const int t = idx - g * rowq;
+                    const int e = fast_div(t, P.by_nq), qd = t - e * P.nq;
+                    const int gr = grow0 + e, gc = 4 * (q0 + qd);  // image row, image column of the quad's first pixel
+                    r[u][0] = r[u][1] = r[u][2] = r[u][3] = 0u;
+                    if (idx < G * rowq && gr >= 0 && gr < P.H && gc >= 0 && gc < P.W) {
+                        const int8_t* src = xn + (int64_t)(ci0 + 4 * g) * HW + gr * P.W + gc;
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (ci0 + 4 * g + j < P.C_in) r[u][j] = *reinterpret_cast<const u32*>(src + (int64_t)j * HW);
+                    }
+                    e2[u] = idx < G * rowq ? e : -1;
+                    f2[u] = gc - gcol0;                        // window column of the quad's first pixel
+                    g2[u] = g;
                 }
-                const int f0 = gc - gcol0;                     // window column of the quad's first pixel
 #pragma unroll
-                for (int px = 0; px < 4; ++px) {
-                    // byte px of the four channel dwords -> one dword: channels 4g .. 4g+3 of this pixel
-                    const u32 t01 = __builtin_amdgcn_perm(r[1], r[0], (u32)px | ((u32)(4 + px) << 8));
-                    const u32 t23 = __builtin_amdgcn_perm(r[3], r[2], (u32)px | ((u32)(4 + px) << 8));
-                    const u32 packed = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
-                    const int f = f0 + px;
-                    if (f >= 0 && f < P.IW) *reinterpret_cast<u32*>(xs + (e * P.IW + f) * kPitch + 4 * g) = packed;
+                for (int u = 0; u < 2; ++u) {
+                    if (e2[u] < 0) continue;
+#pragma unroll
+                    for (int px = 0; px < 4; ++px) {
+                        // byte px of the four channel dwords -> one dword: channels 4g .. 4g+3 of this pixel
+                        const u32 t01 = __builtin_amdgcn_perm(r[u][1], r[u][0], (u32)px | ((u32)(4 + px) << 8));
+                        const u32 t23 = __builtin_amdgcn_perm(r[u][3], r[u][2], (u32)px | ((u32)(4 + px) << 8));
+                        const u32 packed = __builtin_amdgcn_perm(t23, t01, 0x05040100u);
+                        const int f = f2[u] + px;
+                        if (f >= 0 && f < P.IW)
+                            *reinterpret_cast<u32*>(xs + (e2[u] * P.IW + f) * kPitch + 4 * g2[u]) = packed;
+                    }
                 }
             }
         } else {
@@ -146,13 +159,23 @@ __global__ __launch_bounds__(256) void mfma_s8_any_kernel(const int8_t* __restri
         const int left = (P.C_in - ci0) * RS;                 // bytes that exist from ci0 on
         if (P.w_dwords) {
             const int span4 = span >> 2;
-            for (int idx = tid; idx < 64 * span4; idx += 256) {
-                const int co_l = fast_div(idx, P.by_span4);
-                const int q = 4 * (idx - co_l * span4);
-                u32 v = 0;
-                if (co0 + co_l < P.C_out && q < left)         // (row length and span are multiples of 4)
-                    v = *reinterpret_cast<const u32*>(wb + co_l * wrow + (int64_t)ci0 * RS + q);
-                *reinterpret_cast<u32*>(raw + co_l * P.rawpitch + q) = v;
+            // (eight loads per thread go out before the first LDS write: one memory round trip per batch)
+            for (int base = tid; base < 64 * span4; base += 256 * 8) {
+                u32 v8[8];
+                int dst8[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int idx = base + 256 * u;
+                    const int co_l = fast_div(idx, P.by_span4);
+                    const int q = 4 * (idx - co_l * span4);
+                    v8[u] = 0;
+                    dst8[u] = idx < 64 * span4 ? co_l * P.rawpitch + q : -1;
+                    if (idx < 64 * span4 && co0 + co_l < P.C_out && q < left)   // (row length and span are multiples of 4)
+                        v8[u] = *reinterpret_cast<const u32*>(wb + co_l * wrow + (int64_t)ci0 * RS + q);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    if (dst8[u] >= 0) *reinterpret_cast<u32*>(raw + dst8[u]) = v8[u];
             }
         } else {
             for (int idx = tid; idx < 64 * span; idx += 256) {

@@ -104,15 +104,24 @@ __global__ __launch_bounds__(256) void dw_pw_block_kernel(const float* __restric
             wd[idx] = v;
         }
         // pointwise weights of the chunk: entry (quad q, output channel co_l) = channels ci0 + 4q .. + 3
-        for (int idx = tid; idx < NB * 64 * kQ; idx += 256) {
-            const int co_l = idx >> 3, q = idx & 7;             // co_l: 0 .. 64 * NB - 1
-            floatx4 v = floatx4{0.f, 0.f, 0.f, 0.f};
-            if (co0 + co_l < P.C_out) {
+        for (int base = tid; base < NB * 64 * kQ; base += 256 * 2) {       // (two entries = eight loads per turn)
+            floatx4 v2[2];
 #pragma unroll
-                for (int t = 0; t < 4; ++t)
-                    if (ci0 + 4 * q + t < P.C) v[t] = wb[(int64_t)co_l * P.C + ci0 + 4 * q + t];
+            for (int u = 0; u < 2; ++u) {
+                const int idx = base + 256 * u;
+                const int co_l = idx >> 3, q = idx & 7;         // co_l: 0 .. 64 * NB - 1
+                v2[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (idx < NB * 64 * kQ && co0 + co_l < P.C_out) {
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+                        if (ci0 + 4 * q + t < P.C) v2[u][t] = wb[(int64_t)co_l * P.C + ci0 + 4 * q + t];
+                }
             }
-            ws[((co_l >> 6) * kQ + q) * 64 + (co_l & 63)] = v;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int idx = base + 256 * u;
+                if (idx < NB * 64 * kQ) ws[(((idx >> 3) >> 6) * kQ + (idx & 7)) * 64 + ((idx >> 3) & 63)] = v2[u];
+            }
         }
         __syncthreads();
 

@@ -142,24 +142,38 @@ __global__ __launch_bounds__(RC > 0 ? 64 : 256) void sliding_plane_kernel(const 
     const int grow0 = row0 - pad;
     const int rows_in = kTile + R - 1;
 
-    for (int idx = threadIdx.x; idx < rows_in * F4_PER_ROW; idx += NT) {
-        const int e = idx / F4_PER_ROW;
-        const int c4 = idx - e * F4_PER_ROW;
-        const int gr = grow0 + e;
-        const int gc = gcol0 + 4 * c4;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (gr >= 0 && gr < H && gc + 3 >= 0 && gc < W) {
-            const float* src = xp + (int64_t)gr * W + gc;
-            if (x_vec_ok && gc >= 0 && gc + 3 < W) {
-                v = *reinterpret_cast<const float4*>(src);
-            } else {
-                if (gc >= 0) v.x = src[0];
-                if (gc + 1 >= 0 && gc + 1 < W) v.y = src[1];
-                if (gc + 2 >= 0 && gc + 2 < W) v.z = src[2];
-                if (gc + 3 < W) v.w = src[3];
+    // (four 16-byte groups per thread go out before the first LDS write: one memory round trip per batch of four)
+    for (int base = threadIdx.x; base < rows_in * F4_PER_ROW; base += NT * 4) {
+        float4 v4[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + NT * u;
+            const int e = idx / F4_PER_ROW;
+            const int c4 = idx - e * F4_PER_ROW;
+            const int gr = grow0 + e;
+            const int gc = gcol0 + 4 * c4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx < rows_in * F4_PER_ROW && gr >= 0 && gr < H && gc + 3 >= 0 && gc < W) {
+                const float* src = xp + (int64_t)gr * W + gc;
+                if (x_vec_ok && gc >= 0 && gc + 3 < W) {
+                    v = *reinterpret_cast<const float4*>(src);
+                } else {
+                    if (gc >= 0) v.x = src[0];
+                    if (gc + 1 >= 0 && gc + 1 < W) v.y = src[1];
+                    if (gc + 2 >= 0 && gc + 2 < W) v.z = src[2];
+                    if (gc + 3 < W) v.w = src[3];
+                }
+            }
+            v4[u] = v;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + NT * u;
+            if (idx < rows_in * F4_PER_ROW) {
+                const int e = idx / F4_PER_ROW;
+                *reinterpret_cast<float4*>(lds + e * P + 4 * (idx - e * F4_PER_ROW)) = v4[u];
             }
         }
-        *reinterpret_cast<float4*>(lds + e * P + 4 * c4) = v;
     }
     __syncthreads();
 

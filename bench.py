@@ -59,14 +59,14 @@ SECOND_ROOF = {"depthwise_7x7": (VALU_F32_TFLOPS, "frac_alu_f32_plain_fma"),
 # profiles/hbm_traffic_all_kernels.txt), with the kernel source and its sha256 prefix at the time the
 # counters were taken.  A kernel whose source has changed since reports traffic = null.
 TRAFFIC = {
-    "depthwise_3x3": (207381467, "sw_sliding_plane.hip", "c19725ff48dea175"),
-    "depthwise_7x7": (206210419, "sw_sliding_plane.hip", "c19725ff48dea175"),
-    "conv2d_64x64_3x3": (62455864, "sw_mfma_f32.hip", "c33152360085e7c7"),
-    "conv2d_s8_128x128_3x3": (21143314, "sw_mfma_s8.hip", "26b043fef2788e7d"),
-    "conv1d_k9": (33929795, "sw_sliding1d.hip", "e53250bbd93b8921"),
-    "avgpool1d_w8": (34176741, "sw_sliding1d.hip", "e53250bbd93b8921"),
-    "maxpool1d_w8": (34161530, "sw_sliding1d.hip", "e53250bbd93b8921"),
-    "conv2d_1ch_3x3": (661066, "sw_sliding_rows.hip", "21935214a73b4290"),
+    "depthwise_3x3": (207450113, "sw_sliding_plane.hip", "6389c5288dd110dc"),
+    "depthwise_7x7": (206185308, "sw_sliding_plane.hip", "6389c5288dd110dc"),
+    "conv2d_64x64_3x3": (62598117, "sw_mfma_f32.hip", "c33152360085e7c7"),
+    "conv2d_s8_128x128_3x3": (21140265, "sw_mfma_s8.hip", "26b043fef2788e7d"),
+    "conv1d_k9": (33921280, "sw_sliding1d.hip", "e53250bbd93b8921"),
+    "avgpool1d_w8": (34169890, "sw_sliding1d.hip", "e53250bbd93b8921"),
+    "maxpool1d_w8": (34142598, "sw_sliding1d.hip", "e53250bbd93b8921"),
+    "conv2d_1ch_3x3": (661062, "sw_sliding_rows.hip", "21935214a73b4290"),
 }
 
 

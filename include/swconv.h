@@ -176,6 +176,35 @@ int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, 
                          int stride, int pad, int relu, void* hip_stream);
 
 /*
+ * The quantised convolution with filters packed once (paper, section 1.1: the weights of a
+ * quantised network are fixed at inference time; section 3: taps as small matrix products).
+ * sw_s8_pack_filter rewrites w [C_out,C_in,R,S] int8 into the operand order of the int8
+ * matrix instruction; sw_conv2d_s8_packed / _requant then compute exactly the sums of
+ * sw_conv2d_s8 / sw_conv2d_s8_requant (bit for bit) without transposing the filters in every
+ * workgroup of every call.  The input and the output are the same unmodified channel-first
+ * tensors as before.
+ *     packed: caller-owned device buffer of sw_s8_packed_filter_bytes(C_in, C_out, R, S) bytes,
+ *             16-byte aligned (SW_ERR_ALIGN), not overlapping w or y (SW_ERR_ALIAS).  Its
+ *             contents are private to this library version (sw_version) and depend on
+ *             (C_in, C_out, R, S) only; pack once, use for any N, H, W, stride and padding.
+ * sw_s8_packed_filter_bytes returns 0 for invalid extents (<= 0, R or S > 64, more than
+ * 2^31-1 filter elements).  sw_s8_pack_filter enqueues one small kernel on hip_stream; the
+ * convolution calls must be ordered after it (same stream, or an event).
+ * Errors of the convolution calls as sw_conv2d_s8 / sw_conv2d_s8_requant.  3x3 at stride 1
+ * with C_in in {32, 64, 128}, C_out % 64 == 0, W % 4 == 0 and 4-byte aligned x runs on the
+ * matrix cores with every A operand loaded straight into registers; every other valid shape
+ * one thread per output.
+ */
+int64_t sw_s8_packed_filter_bytes(int C_in, int C_out, int R, int S);
+int sw_s8_pack_filter(const int8_t* w, int8_t* packed, int C_in, int C_out, int R, int S, void* hip_stream);
+int sw_conv2d_s8_packed(const int8_t* x, const int8_t* packed, int32_t* y,
+                        int N, int C_in, int C_out, int H, int W, int R, int S,
+                        int stride, int pad, void* hip_stream);
+int sw_conv2d_s8_packed_requant(const int8_t* x, const int8_t* packed, const int32_t* bias, const float* scale,
+                                int8_t* y, int N, int C_in, int C_out, int H, int W, int R, int S,
+                                int stride, int pad, int relu, void* hip_stream);
+
+/*
  * A depthwise-separable block in one launch (paper, section 1.2: depthwise
  * separable convolutions; sections 1 and 2: nothing but input, filters and output
  * moves): depthwise 3 x 3 (stride 1, padding 1) with bias and optional rectifier,
@@ -289,6 +318,9 @@ int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* b
 /* Output extent of one axis; <= 0 means the filter does not fit (or bad arguments). */
 int64_t sw_out_dim(int64_t in, int k, int stride, int pad);
 
+/* The same for a filter whose taps are `dilation` input positions apart (span dilation*(k-1)+1). */
+int64_t sw_out_dim_dilated(int64_t in, int k, int stride, int pad, int dilation);
+
 /* Device workspace the library needs: always 0 (paper, sections 1 and 2). */
 size_t sw_workspace_bytes(void);
 
@@ -297,6 +329,14 @@ const char* sw_status_string(int status);
 
 /* major*10000 + minor*100 + patch */
 int sw_version(void);
+
+/*
+ * Diagnostics: the name (with template arguments) of the kernel that the calling thread's most
+ * recent convolution, pooling or packing call enqueued; "" before the first call.  The string
+ * lives in thread-local storage and is overwritten by the next sw_last_kernel call of the thread.
+ * Tests use it to check that a small case runs the same kernel as the large launch it stands for.
+ */
+const char* sw_last_kernel(void);
 
 #ifdef __cplusplus
 }

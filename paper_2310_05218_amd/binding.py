@@ -20,7 +20,8 @@ EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthw
            "sw_conv2d_s8_requant", "sw_conv2d_s8_nhwc", "sw_conv2d_s8_nhwc_requant", "sw_conv2d_bias_relu", "sw_dw_pw_block", "sw_conv2d_depthwise_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
            "sw_conv2d_depthwise_bf16", "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
            "sw_jit_cached_kernels",
-           "sw_out_dim", "sw_workspace_bytes", "sw_status_string", "sw_version")
+           "sw_s8_packed_filter_bytes", "sw_s8_pack_filter", "sw_conv2d_s8_packed", "sw_conv2d_s8_packed_requant",
+           "sw_out_dim", "sw_out_dim_dilated", "sw_workspace_bytes", "sw_status_string", "sw_version", "sw_last_kernel")
 
 _lib = None
 
@@ -77,8 +78,20 @@ def lib() -> ctypes.CDLL:
     L.sw_conv2d_s8_nhwc_requant.argtypes = [vp, vp, vp, vp, vp] + [i32] * 10 + [vp]
     L.sw_conv2d_s8_requant.restype = i32
     L.sw_conv2d_s8_requant.argtypes = [vp, vp, vp, vp, vp] + [i32] * 10 + [vp]
+    L.sw_s8_packed_filter_bytes.restype = i64
+    L.sw_s8_packed_filter_bytes.argtypes = [i32] * 4
+    L.sw_s8_pack_filter.restype = i32
+    L.sw_s8_pack_filter.argtypes = [vp, vp] + [i32] * 4 + [vp]
+    L.sw_conv2d_s8_packed.restype = i32
+    L.sw_conv2d_s8_packed.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
+    L.sw_conv2d_s8_packed_requant.restype = i32
+    L.sw_conv2d_s8_packed_requant.argtypes = [vp, vp, vp, vp, vp] + [i32] * 10 + [vp]
     L.sw_out_dim.restype = i64
     L.sw_out_dim.argtypes = [i64, i32, i32, i32]
+    L.sw_out_dim_dilated.restype = i64
+    L.sw_out_dim_dilated.argtypes = [i64, i32, i32, i32, i32]
+    L.sw_last_kernel.restype = ctypes.c_char_p
+    L.sw_last_kernel.argtypes = []
     L.sw_workspace_bytes.restype = ctypes.c_size_t
     L.sw_workspace_bytes.argtypes = []
     L.sw_status_string.restype = ctypes.c_char_p
@@ -145,6 +158,15 @@ def sw_conv2d_s8_requant(x, w, bias, scale, stride: int = 1, pad: int = 0, relu:
 
 def sw_out_dim(n_in: int, k: int, stride: int, pad: int) -> int:
     return int(lib().sw_out_dim(n_in, k, stride, pad))
+
+
+def sw_out_dim_dilated(n_in: int, k: int, stride: int, pad: int, dilation: int) -> int:
+    return int(lib().sw_out_dim_dilated(n_in, k, stride, pad, dilation))
+
+
+def sw_last_kernel() -> str:
+    """Name (with template arguments) of the kernel the calling thread's most recent call enqueued."""
+    return lib().sw_last_kernel().decode()
 
 
 def sw_workspace_bytes() -> int:
@@ -315,8 +337,8 @@ def sw_conv2d_dilated(x, w, stride: int = 1, pad: int = 0, dilation: int = 1, ou
     if C_in_w != C_in:
         raise ValueError("channel mismatch between x and w")
     if out is None:
-        out = torch.empty(_out_shape("sw_conv2d_dilated", N, C_out, sw_out_dim(H, dilation * (R - 1) + 1, stride, pad),
-                                     sw_out_dim(W, dilation * (S - 1) + 1, stride, pad)),
+        out = torch.empty(_out_shape("sw_conv2d_dilated", N, C_out, sw_out_dim_dilated(H, R, stride, pad, dilation),
+                                     sw_out_dim_dilated(W, S, stride, pad, dilation)),
                           dtype=torch.float32, device=x.device)
     rc = lib().sw_conv2d_dilated(_dev(x, torch.float32, 4, "x"), _dev(w, torch.float32, 4, "w"),
                                  _dev(out, torch.float32, 4, "y"), N, C_in, C_out, H, W, R, S, stride, pad, dilation,
@@ -335,8 +357,8 @@ def sw_conv2d_depthwise_dilated(x, w, stride: int = 1, pad: int = 0, dilation: i
         raise ValueError("depthwise weights must be [C,1,R,S]")
     if out is None:
         out = torch.empty(_out_shape("sw_conv2d_depthwise_dilated", N, C,
-                                     sw_out_dim(H, dilation * (R - 1) + 1, stride, pad),
-                                     sw_out_dim(W, dilation * (S - 1) + 1, stride, pad)),
+                                     sw_out_dim_dilated(H, R, stride, pad, dilation),
+                                     sw_out_dim_dilated(W, S, stride, pad, dilation)),
                           dtype=torch.float32, device=x.device)
     rc = lib().sw_conv2d_depthwise_dilated(_dev(x, torch.float32, 4, "x"), _dev(w, torch.float32, 4, "w"),
                                            _dev(out, torch.float32, 4, "y"), N, C, H, W, R, S, stride, pad,
@@ -429,4 +451,51 @@ def sw_conv2d_s8(x, w, stride: int = 1, pad: int = 0, out=None, stream=None):
                             _dev(out, torch.int32, 4, "y"), N, C_in, C_out, H, W, R, S, stride, pad,
                             _stream(stream))
     _check(rc, "sw_conv2d_s8")
+    return out
+
+
+def sw_s8_packed_filter_bytes(C_in: int, C_out: int, R: int, S: int) -> int:
+    return int(lib().sw_s8_packed_filter_bytes(C_in, C_out, R, S))
+
+
+def sw_s8_pack_filter(w, out=None, stream=None):
+    """w [C_out,C_in,R,S] int8 -> the filters in the matrix instruction's operand order (1-D int8 tensor of
+    sw_s8_packed_filter_bytes bytes), for sw_conv2d_s8_packed."""
+    import torch
+
+    C_out, C_in, R, S = w.shape
+    nbytes = sw_s8_packed_filter_bytes(C_in, C_out, R, S)
+    if nbytes <= 0:
+        raise SwError(SW_ERR_SHAPE, "sw_s8_pack_filter")
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.int8, device=w.device)
+    rc = lib().sw_s8_pack_filter(_dev(w, torch.int8, 4, "w"), _dev(out, torch.int8, 1, "packed"), C_in, C_out, R, S,
+                                 _stream(stream))
+    _check(rc, "sw_s8_pack_filter")
+    return out
+
+
+def sw_conv2d_s8_packed(x, packed, C_out: int, R: int, S: int, stride: int = 1, pad: int = 0, bias=None, scale=None,
+                        relu: bool = False, out=None, stream=None):
+    """x [N,C_in,H,W] int8 and filters packed by sw_s8_pack_filter -> y [N,C_out,H_out,W_out] int32 (exact sums),
+    or int8 when `scale` ([C_out] fp32, with optional int32 `bias`) is given, as sw_conv2d_s8_requant."""
+    import torch
+
+    N, C_in, H, W = x.shape
+    rq = scale is not None
+    name = "sw_conv2d_s8_packed_requant" if rq else "sw_conv2d_s8_packed"
+    if out is None:
+        out = torch.empty(_out_shape(name, N, C_out, sw_out_dim(H, R, stride, pad), sw_out_dim(W, S, stride, pad)),
+                          dtype=torch.int8 if rq else torch.int32, device=x.device)
+    if rq:
+        rc = lib().sw_conv2d_s8_packed_requant(_dev(x, torch.int8, 4, "x"), _dev(packed, torch.int8, 1, "packed"),
+                                               _dev(bias, torch.int32, 1, "bias") if bias is not None else None,
+                                               _dev(scale, torch.float32, 1, "scale"), _dev(out, torch.int8, 4, "y"),
+                                               N, C_in, C_out, H, W, R, S, stride, pad, 1 if relu else 0,
+                                               _stream(stream))
+    else:
+        rc = lib().sw_conv2d_s8_packed(_dev(x, torch.int8, 4, "x"), _dev(packed, torch.int8, 1, "packed"),
+                                       _dev(out, torch.int32, 4, "y"), N, C_in, C_out, H, W, R, S, stride, pad,
+                                       _stream(stream))
+    _check(rc, name)
     return out

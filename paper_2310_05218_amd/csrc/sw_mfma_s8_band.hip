@@ -1,0 +1,424 @@
+// Quantised 3x3 convolution from packed filters, full-width row bands (paper, sections 1.1 and 3).
+// The latency-tuned variant of sw_mfma_s8_packed.hip for images no wider than 64 output pixels: a launch
+// of this kind has one tile per compute unit and lasts a few microseconds, so what counts is how soon after
+// the wavefront starts the first matrix instruction issues and how early the first results leave.
+//
+//   1. One batch of scalar loads, branch-free index arithmetic.
+//   2. The band of input rows a tile needs is one contiguous run per channel (the tile spans the image's
+//      width).  It is fetched with 16-byte loads, copied to LDS as it is, and byte-transposed from there into
+//      the [pixel][ci] operand layout (16 LDS dword reads replace 16 global dword loads per item: a global
+//      load instruction is paid per lane address, not per byte).
+//   3. The workgroup's packed filters (two blocks of 32 output channels, 9 * C_in / 32 KB each) are fetched
+//      once with coalesced 16-byte loads and copied to LDS; every wavefront then reads the A operands of its
+//      channel block into registers while its first block multiplies.
+//   4. A wavefront multiplies one block of 32 pixels at a time, the K steps alternating between two
+//      accumulators (so that no matrix instruction waits for the one before it), and the 16 stores of a
+//      finished block are spread between the matrix instructions of the next one: output starts to leave
+//      after a quarter of the multiplications, and only one block's stores remain at the end.
+#include <algorithm>
+#include <type_traits>
+
+#include "swconv_internal.h"
+#include "sw_s8_perm.h"
+
+namespace swconv {
+
+namespace {
+
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32;
+using s8perm::gather4;
+
+constexpr int kNBW = 4;            // 32-pixel blocks per wavefront at most
+constexpr int kMaxPieces = 20;     // 16-byte pieces of a channel's band (up to 304 bytes)
+constexpr int kWinPx = 320;        // window pixels
+constexpr int kLookAhead = 3;      // operand reads run this many steps ahead of the matrix instructions
+
+// 16 channels x 4 pixels (one dword per channel) -> pixel PX's 16 channel bytes
+template <int PX>
+__device__ __forceinline__ intx4 xgather_px(const u32* in)
+{
+    intx4 v;
+    v.x = (int)gather4<0 * 4 + PX, 1 * 4 + PX, 2 * 4 + PX, 3 * 4 + PX>(in);
+    v.y = (int)gather4<4 * 4 + PX, 5 * 4 + PX, 6 * 4 + PX, 7 * 4 + PX>(in);
+    v.z = (int)gather4<8 * 4 + PX, 9 * 4 + PX, 10 * 4 + PX, 11 * 4 + PX>(in);
+    v.w = (int)gather4<12 * 4 + PX, 13 * 4 + PX, 14 * 4 + PX, 15 * 4 + PX>(in);
+    return v;
+}
+
+// n / d without a branch: magic = ceil(2^32 / d) for d > 1; d == 1 has magic 0 and one 1.  Exact while n * d < 2^32.
+struct Div {
+    uint32_t d, magic, one;
+};
+inline Div make_div(int d) { return Div{(uint32_t)d, d == 1 ? 0u : (uint32_t)(0x100000000ULL / (uint32_t)d) + 1u, d == 1 ? 1u : 0u}; }
+__device__ __forceinline__ int div_by(int n, const Div& f) { return (int)(__umulhi((uint32_t)n, f.magic) + (uint32_t)n * f.one); }
+
+struct BandParams {
+    int C_out, H, W, pad, Ho, Wo, base, rem, max_pieces, wide_store;    // tile t: base + (t < rem) blocks of 32 pixels
+    Div by_pieces, by_W4, by_IW, by_Wo;
+};
+
+// KS: C_in / 32.  RQ: the sums leave requantised to int8 (y8) instead of as int32 (y).
+//
+// LDS: the window as [16-channel group][pixel][16 bytes] (group pitch = 16 mod 256 bytes, so that the staging
+// writes of neighbouring groups fall into different banks; an operand read takes 16 consecutive pixels of one
+// group, 256 contiguous bytes), the workgroup's packed filters as they are, and a private area per wavefront for
+// the raw band of the channel groups it stages: a wavefront transposes only what it fetched itself, so the only
+// workgroup barrier of the prologue is the one before the first matrix instruction.
+template <int KS, bool RQ>
+__global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __restrict__ x, const int8_t* __restrict__ wp,
+                                                              int32_t* __restrict__ y, const BandParams P,
+                                                              int8_t* __restrict__ y8, const Requant rq)
+{
+    constexpr int C_in = 32 * KS;
+    constexpr int NG = 2 * KS;                              // groups of 16 input channels
+    constexpr int GP = kWinPx * 16 + 16;                    // bytes per group in the window
+    constexpr int NSTEP = 9 * KS;
+    constexpr int GPW = NG >= 8 ? 2 : 1;                    // channel groups a wavefront stages
+    constexpr int XPW = (16 * GPW * kMaxPieces + 63) / 64;  // raw 16-byte pieces per lane
+    constexpr int QPW = GPW == 2 ? 32 : 64;                 // column quads per pass of a wavefront
+    constexpr int XIW = (kWinPx / 4 + QPW - 1) / QPW;       // transposition passes
+    constexpr bool OWN = KS >= 2;       // a wavefront keeps the half of its A operands it fetched itself in registers
+    constexpr int AH = (NSTEP + 1) / 2; // A operands a wavefront fetches: the steps of its own parity
+    const int C_out = P.C_out, H = P.H, W = P.W, pad = P.pad, Ho = P.Ho, Wo = P.Wo;
+    const int rawpitch = 16 * P.max_pieces;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char* lx = smem;                                   // [channel group][window pixel][16]
+    unsigned char* la = smem + NG * GP;                         // [channel block][step][lane][16]: as packed
+    unsigned char* lraw = la + 2 * NSTEP * 1024;                // per wavefront: [channel][band bytes], as in memory
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int lg = lane >> 5, lj = lane & 31;      // K half and row/column inside a 32 x 32 block
+    const int wm = wave >> 1, wn = wave & 1;
+    const int n = blockIdx.y, mb = blockIdx.z;
+
+    // the tile: blocks [blk0, blk0 + nblk) of 32 consecutive pixels of the image in row-major order, i.e. output
+    // rows row0 .. row_last (the first and the last one possibly in part); its stores are whole 128-byte runs
+    const int blk0 = blockIdx.x * P.base + min((int)blockIdx.x, P.rem), nblk = P.base + ((int)blockIdx.x < P.rem ? 1 : 0);
+    const int HoWo = Ho * Wo;
+    const int p0 = 32 * blk0, tile_px = min(32 * nblk, HoWo - p0);
+    const int row0 = div_by(p0, P.by_Wo), row_last = div_by(p0 + tile_px - 1, P.by_Wo);
+    const int IH = row_last - row0 + 3, IW = Wo + 2;
+    const int HW = H * W;
+    const int8_t* xn = x + (int64_t)n * C_in * HW;
+
+    // ---- the band: image rows [r_lo, r_hi) of every channel, fetched from the 16-byte boundary below its start;
+    //      this wavefront takes the channels of groups g0 .. g0 + GPW - 1
+    const int r_lo = max(row0 - pad, 0), r_hi = min(row0 - pad + IH, H);
+    const int band_off = r_lo * W, skew = band_off & 15;
+    const int npieces = (skew + (r_hi - r_lo) * W + 15) >> 4;
+    const int g0 = wave * GPW;
+    const bool stager = g0 < NG;                              // (C_in == 32: two groups, wavefronts 2 and 3 stage nothing)
+    unsigned char* lraw_w = lraw + wave * (16 * GPW * rawpitch + 128);
+    intx4 xr[XPW];
+    int xraw[XPW];
+#pragma unroll
+    for (int k = 0; k < XPW; ++k) {
+        const int idx = lane + 64 * k;
+        const int cl = div_by(idx, P.by_pieces);
+        const int piece = idx - cl * P.max_pieces;
+        const bool ok = stager && cl < 16 * GPW && piece < npieces;
+        xraw[k] = ok ? cl * rawpitch + 128 * (cl >> 4) + 16 * piece : -1;
+        const int8_t* src = xn + (ok ? (16 * g0 + cl) * HW + (band_off - skew) + 16 * piece : 0);
+        xr[k] = *reinterpret_cast<const intx4*>(src);
+    }
+    // ---- A operands: wavefront (wm, wn) fetches the steps of parity wn of channel block wm (coalesced 16-byte loads
+    //      in the packed order); issue slot k of the main loop multiplies step k ^ wn, so a[even] are these
+    const intx4* wa = reinterpret_cast<const intx4*>(wp) + ((int64_t)(2 * mb + wm) * NSTEP) * 64 + lane;
+    intx4 a[NSTEP];
+    intx4 a_tmp[OWN ? 1 : AH];
+#pragma unroll
+    for (int j = 0; j < AH; ++j) {
+        const int st = min(2 * j + wn, NSTEP - 1);
+        if constexpr (OWN) a[2 * j] = wa[st * 64];
+        else a_tmp[j] = wa[st * 64];
+    }
+
+    // ---- the padding: window cells outside the image are zeroed once (nothing else writes them)
+    {
+        const int cells = IH * IW;
+        for (int i = tid; i < cells; i += 256) {
+            const int e = div_by(i, P.by_IW), c = i - e * IW;
+            const int gr = row0 - pad + e, gc = c - pad;
+            if (gr < 0 || gr >= H || gc < 0 || gc >= W) {
+#pragma unroll
+                for (int g = 0; g < NG; ++g) *reinterpret_cast<intx4*>(lx + g * GP + i * 16) = intx4{0, 0, 0, 0};
+            }
+        }
+    }
+    // ---- band -> this wavefront's LDS area as it is, then -> [group][pixel][16] with the byte transposes:
+    //      item = (channel group, column quad of a window row); LDS operations of a wavefront complete in order
+#pragma unroll
+    for (int k = 0; k < XPW; ++k)
+        if (xraw[k] >= 0) *reinterpret_cast<intx4*>(lraw_w + xraw[k]) = xr[k];
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    if (stager) {
+        const int W4 = W >> 2;
+        const int nquads = IH * W4;
+        const int gl = GPW == 2 ? (lane & 1) : 0;
+        const int qslot = GPW == 2 ? (lane >> 1) : lane;
+#pragma unroll
+        for (int k = 0; k < XIW; ++k) {
+            const int quad = qslot + QPW * k;
+            const int e = div_by(quad, P.by_W4);
+            const int cq = quad - e * W4;
+            const int r = row0 - pad + e;
+            if (quad < nquads && r >= r_lo && r < r_hi) {
+                const unsigned char* src = lraw_w + gl * (16 * rawpitch + 128) + skew + (r - r_lo) * W + 4 * cq;
+                u32 v[16];
+#pragma unroll
+                for (int c = 0; c < 16; ++c) v[c] = *reinterpret_cast<const u32*>(src + c * rawpitch);
+                unsigned char* dst = lx + (g0 + gl) * GP + (e * IW + pad + 4 * cq) * 16;
+                *reinterpret_cast<intx4*>(dst) = xgather_px<0>(v);
+                *reinterpret_cast<intx4*>(dst + 16) = xgather_px<1>(v);
+                *reinterpret_cast<intx4*>(dst + 32) = xgather_px<2>(v);
+                *reinterpret_cast<intx4*>(dst + 48) = xgather_px<3>(v);
+            }
+        }
+    }
+    // ---- the fetched A operands -> LDS, for the partner wavefront (and, for C_in == 32, for this one as well)
+    {
+        unsigned char* la_own = la + (wm * NSTEP * 64 + lane) * 16;
+#pragma unroll
+        for (int j = 0; j < AH; ++j) {
+            const int st = 2 * j + wn;
+            if (st < NSTEP) {
+                if constexpr (OWN) *reinterpret_cast<intx4*>(la_own + st * 1024) = a[2 * j];
+                else *reinterpret_cast<intx4*>(la_own + st * 1024) = a_tmp[j];
+            }
+        }
+    }
+    __syncthreads();
+
+    // the tile's blocks in two halves, one per wavefront pair member
+    const int half = (nblk + 1) >> 1;
+    const int first = wn * half;
+    const int live = __builtin_amdgcn_readfirstlane(wn == 0 ? half : nblk - half);
+    if (live == 0) return;
+
+    const int co_base = (mb << 6) + 32 * wm + 4 * lg;       // this lane's first output channel
+    const int64_t ybase = ((int64_t)n * C_out + co_base) * HoWo;
+    const int rowoff1 = IW * 16, rowoff2 = 2 * IW * 16;
+    // issue slot k multiplies K step (OWN ? k ^ wn : k): its A operand (odd slots, or all of them) in LDS and the
+    // channel group of its B operand
+    const unsigned char* la_w = la + (wm * NSTEP * 64 + lane) * 16 + (OWN ? (1 - wn) * 1024 - 1024 : 0);
+    const int gsel_even = OWN ? 2 * wn + lg : lg, gsel_odd = OWN ? 2 * (1 - wn) + lg : lg;
+
+    // this lane's sixteen output channels' scales and biases, read once
+    float rq_scale[RQ ? 16 : 1];
+    int rq_bias[RQ ? 16 : 1];
+    if constexpr (RQ) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int co = co_base + 8 * (v >> 2) + (v & 3);
+            rq_scale[v] = rq.scale[co];
+            rq_bias[v] = rq.bias ? rq.bias[co] : 0;
+        }
+    }
+    auto requant_reg = [&](int acc_v, int v) __attribute__((always_inline)) {
+        float r = rintf(__int2float_rn(acc_v + rq_bias[RQ ? v : 0]) * rq_scale[RQ ? v : 0]);
+        r = fminf(fmaxf(r, rq.relu ? 0.0f : -128.0f), 127.0f);
+        return (int)r;
+    };
+    // Requantised output, rows whose groups of four pixels are aligned dwords in y8 (P.wide_store): the four
+    // lanes of a quad hold four pixels x four consecutive channels; two exchange rounds inside the quad
+    // (DPP quad_perm) transpose that, so that lane k ends up with channel k of all four pixels and stores
+    // them as one dword instead of four single bytes.
+    auto store_quad = [&](int dst, const intx16& c, int g) __attribute__((always_inline)) {
+        const int k = lane & 3;
+        int r[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) r[t] = requant_reg(c[4 * g + t], 4 * g + t) & 255;
+        const bool b0 = k & 1, b1 = k & 2;
+        const int keep01 = b0 ? r[1] : r[0], send01 = b0 ? r[0] : r[1];
+        const int keep23 = b0 ? r[3] : r[2], send23 = b0 ? r[2] : r[3];
+        const int got01 = __builtin_amdgcn_mov_dpp(send01, 0xB1, 0xF, 0xF, true);   // quad_perm [1,0,3,2]
+        const int got23 = __builtin_amdgcn_mov_dpp(send23, 0xB1, 0xF, 0xF, true);
+        const int own_a = b1 ? keep23 : keep01, own_b = b1 ? got23 : got01;
+        const int snd_a = b1 ? keep01 : keep23, snd_b = b1 ? got01 : got23;
+        const int far_a = __builtin_amdgcn_mov_dpp(snd_a, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+        const int far_b = __builtin_amdgcn_mov_dpp(snd_b, 0x4E, 0xF, 0xF, true);
+        // channel k of pixels k (own_a), k^1 (own_b), k^2 (far_a), k^3 (far_b); byte j of the dword is pixel j
+        const unsigned word = (unsigned)own_a << (8 * k) | (unsigned)own_b << (8 * (k ^ 1)) |
+                              (unsigned)far_a << (8 * (k ^ 2)) | (unsigned)far_b << (8 * (k ^ 3));
+        if (dst >= 0)
+            *reinterpret_cast<unsigned*>(y8 + ybase + (int64_t)(8 * g + k) * HoWo + (dst - k)) = word;
+    };
+    auto store_reg = [&](int dst, const intx16& c, int v) __attribute__((always_inline)) {
+        const int ch = 8 * (v >> 2) + (v & 3);
+        if constexpr (RQ) {
+            if (P.wide_store) {
+                if ((v & 3) == 3) store_quad(dst, c, v >> 2);
+            } else if (dst >= 0) {
+                y8[ybase + (int64_t)ch * HoWo + dst] = (int8_t)requant_reg(c[v], v);
+            }
+        } else {
+            if (dst >= 0) __builtin_nontemporal_store(c[v], y + ybase + (int64_t)ch * HoWo + dst);
+        }
+    };
+
+    // One block of 32 pixels: all K steps, even issue slots into one accumulator and odd ones into the other (so that
+    // no matrix instruction waits for the one before it).  FIRST: the A operands that are not in registers yet come
+    // from LDS on the way (and stay in registers); DRAIN: the 16 stores of the block before (prev at offset
+    // prev_dst) are spread between the matrix instructions.
+    auto block = [&](auto first_tag, auto drain_tag, int i, const intx16& prev, int prev_dst) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first_tag)::value, DRAIN = decltype(drain_tag)::value;
+        int p = (first + i) * 32 + lj;
+        if (p >= tile_px) p = 0;
+        const int pi = div_by(p0 + p, P.by_Wo), pj = p0 + p - pi * Wo;
+        const int cell = (pi - row0) * IW + pj;
+        const unsigned char* bb_even = lx + gsel_even * GP + cell * 16;
+        const unsigned char* bb_odd = lx + gsel_odd * GP + cell * 16;
+        auto b_at = [&](int k) __attribute__((always_inline)) {
+            // slot k: step k ^ wn (or k): tap = step / KS is the same for both, the K quarter's upper bits as well
+            const int tap = k / KS;
+            const int r = tap / 3, q = tap - 3 * r;
+            const int kk_hi = OWN ? ((k % KS) & ~1) : (k % KS);       // (its lowest bit is in the base pointer)
+            const unsigned char* base = (k & 1) ? bb_odd : bb_even;
+            return *reinterpret_cast<const intx4*>(base + 2 * kk_hi * GP + (r == 0 ? 0 : r == 1 ? rowoff1 : rowoff2) + q * 16);
+        };
+        auto a_from_lds = [&](int k) __attribute__((always_inline)) {
+            if (FIRST && (!OWN || (k & 1))) a[k] = *reinterpret_cast<const intx4*>(la_w + k * 1024);
+        };
+        intx16 acc0, acc1;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { acc0[v] = 0; acc1[v] = 0; }
+        intx4 b[kLookAhead + 1];
+#pragma unroll
+        for (int k = 0; k < kLookAhead && k < NSTEP; ++k) {
+            a_from_lds(k);
+            b[k] = b_at(k);
+        }
+        // 16 stores over the steps (KS == 1: two per step over the first eight)
+        constexpr int PER = NSTEP >= 18 ? 1 : 2;
+        constexpr int GAP = NSTEP >= 34 ? 2 : 1;
+#pragma unroll
+        for (int k = 0; k < NSTEP; ++k) {
+            if (k + kLookAhead < NSTEP) {
+                a_from_lds(k + kLookAhead);
+                b[(k + kLookAhead) % (kLookAhead + 1)] = b_at(k + kLookAhead);
+            }
+            if (DRAIN && k % GAP == 0) {
+#pragma unroll
+                for (int u = 0; u < PER; ++u) {
+                    const int sv = (k / GAP) * PER + u;
+                    if (sv < 16) store_reg(prev_dst, prev, sv);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (k & 1) acc1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[k], b[k % (kLookAhead + 1)], acc1, 0, 0, 0);
+            else acc0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[k], b[k % (kLookAhead + 1)], acc0, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        intx16 out;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) out[v] = acc0[v] + acc1[v];
+        return out;
+    };
+    // offset of this lane's pixel in block i inside a channel plane (-1 when it lies outside the tile/image)
+    auto block_dst = [&](int i) -> int {
+        const int p = (first + i) * 32 + lj;
+        return p < tile_px ? p0 + p : -1;
+    };
+
+    intx16 res = block(std::true_type{}, std::false_type{}, 0, intx16{}, -1);
+    int dst = block_dst(0);
+#pragma unroll 1
+    for (int i = 1; i < live; ++i) {
+        const intx16 nxt = block(std::false_type{}, std::true_type{}, i, res, dst);
+        res = nxt;
+        dst = block_dst(i);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) store_reg(dst, res, v);
+}
+
+struct BandTiling {
+    int base, rem, tiles, max_pieces;
+    bool ok;
+};
+
+// Tiles of up to 2 * kNBW blocks of 32 consecutive pixels (row-major over the image, so that every store covers
+// whole 128-byte runs of the output whatever the image width), evenly sized; the rows a tile touches plus the
+// filter halo must fit kWinPx window pixels and kMaxPieces 16-byte pieces per channel.
+BandTiling pick_band(const Conv2dShape& s)
+{
+    BandTiling t{0, 0, 0, 0, false};
+    if (s.Wo > 64) return t;
+    const int HoWo = s.Ho * s.Wo, blocks = (HoWo + 31) / 32;
+    for (int nb = 2 * kNBW; nb >= 1 && !t.ok; --nb) {
+        const int tiles = (blocks + nb - 1) / nb, base = blocks / tiles, rem = blocks % tiles;
+        bool fits = true;
+        int max_pieces = 1;
+        for (int i = 0; i < tiles && fits; ++i) {
+            const int p0 = 32 * (i * base + std::min(i, rem)), px = std::min(32 * (base + (i < rem ? 1 : 0)), HoWo - p0);
+            const int row0 = p0 / s.Wo, row_last = (p0 + px - 1) / s.Wo, IH = row_last - row0 + 3;
+            const int r_lo = std::max(row0 - s.pad, 0), r_hi = std::min(row0 - s.pad + IH, s.H);
+            const int pieces = (((r_lo * s.W) & 15) + (r_hi - r_lo) * s.W + 15) / 16;
+            fits = IH * (s.Wo + 2) <= kWinPx && pieces <= kMaxPieces && r_hi > r_lo;
+            max_pieces = std::max(max_pieces, pieces);
+        }
+        if (fits) t = BandTiling{base, rem, tiles, max_pieces, true};
+    }
+    t.ok = t.ok && s.N <= 65535 && s.C_out / 64 <= 65535;
+    return t;
+}
+
+template <int KS, bool RQ>
+hipError_t launch_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant& rq, const Conv2dShape& s,
+                       const BandTiling& t, hipStream_t st)
+{
+    constexpr int GPW = KS >= 4 ? 2 : 1;     // as in the kernel
+    auto lds_bytes = [](int pieces) { return 2 * KS * (kWinPx * 16 + 16) + 2 * 9 * KS * 1024 + 4 * (16 * GPW * 16 * pieces + 128); };
+    const size_t lds = (size_t)lds_bytes(t.max_pieces);
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_band_kernel<KS, RQ>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                       lds_bytes(kMaxPieces));
+    if (attr != hipSuccess) return attr;
+    BandParams P;
+    P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo; P.base = t.base; P.rem = t.rem;
+    P.max_pieces = t.max_pieces;
+    // (requantised output only) dword stores of four pixels: groups of four pixels must be aligned dwords of y8
+    P.wide_store = (s.Ho * s.Wo) % 4 == 0 && reinterpret_cast<uintptr_t>(y8) % 4 == 0;
+    P.by_pieces = make_div(t.max_pieces);
+    P.by_W4 = make_div(s.W / 4);
+    P.by_IW = make_div(s.Wo + 2);
+    P.by_Wo = make_div(s.Wo);
+    note_kernel("mfma_s8_band_kernel", KS, RQ);
+    hipLaunchKernelGGL((mfma_s8_band_kernel<KS, RQ>), dim3((unsigned)t.tiles, (unsigned)s.N, (unsigned)(s.C_out / 64)),
+                       dim3(256), lds, st, x, wp, y, P, y8, rq);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool mfma_s8_band_supported(const int8_t* x, const int8_t* wp, const Conv2dShape& s)
+{
+    if (s.stride != 1 || s.R != 3 || s.S != 3 || s.dil != 1) return false;
+    if (s.C_in != 32 && s.C_in != 64 && s.C_in != 128) return false;
+    if (s.C_out % 64 != 0 || s.W % 4 != 0 || ((int64_t)s.H * s.W) % 16 != 0) return false;
+    if ((int64_t)s.C_in * s.H * s.W > 2147483647LL) return false;
+    if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(wp) % 16 != 0) return false;
+    return pick_band(s).ok;
+}
+
+hipError_t launch_mfma_s8_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant* rq,
+                               const Conv2dShape& s, hipStream_t st)
+{
+    const BandTiling t = pick_band(s);
+    const Requant none{nullptr, nullptr, 0};
+    const int KS = s.C_in / 32;
+#define SW_BAND(KSC)                                                                         \
+    do {                                                                                     \
+        if (rq) return launch_band<KSC, true>(x, wp, nullptr, y8, *rq, s, t, st);            \
+        return launch_band<KSC, false>(x, wp, y, nullptr, none, s, t, st);                   \
+    } while (0)
+    if (KS == 4) SW_BAND(4);
+    if (KS == 2) SW_BAND(2);
+    SW_BAND(1);
+#undef SW_BAND
+}
+
+}  // namespace swconv

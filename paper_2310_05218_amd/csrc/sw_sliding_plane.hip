@@ -28,6 +28,8 @@ constexpr int kTile = 8 * kB;    // 56 outputs per tile per axis
 constexpr int kMaxRS = 17;       // largest filter extent of the first generic kernel
 constexpr int kMaxRSWide = 51;   // largest filter extent of the second one (a wider LDS window)
 constexpr int kOutPitch = kTile;
+constexpr int kWholeSlots = (kTile * kTile / 4 + 63) / 64;     // 16-byte groups of a plane per lane, whole-plane kernel
+constexpr int kWholeSlotsBf16 = (kTile * kTile / 8 + 63) / 64; // groups of eight bf16 per lane
 
 constexpr int in_pitch(int S) { return (3 + kTile + S - 1) <= 72 ? 72 : (3 + kTile + S - 1) <= 104 ? 104 : 136; }
 constexpr int in_rows(int R) { return kTile + R - 1; }
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(64) void sliding_plane_full_kernel(const float* __r
     const int H = SQ ? kTile : H_rt, W = SQ ? kTile : W_rt, Ho = SQ ? kTile : Ho_rt, Wo = SQ ? kTile : Wo_rt;
     constexpr int P = in_pitch(S);
     constexpr int ROWS = in_rows(R);
-    constexpr int NSLOT = (kTile * kTile / 4 + 63) / 64;      // 13 16-byte groups per lane at most
+    constexpr int NSLOT = kWholeSlots;                        // 13 16-byte groups per lane at most
     __shared__ __attribute__((aligned(16))) float lds[ROWS * P];
 
     const int lane = threadIdx.x;
@@ -442,7 +444,7 @@ __global__ __launch_bounds__(64) void sliding_plane_bf16_kernel(const unsigned s
     const int H = SQ ? kTile : H_rt, W = SQ ? kTile : W_rt, Ho = SQ ? kTile : Ho_rt, Wo = SQ ? kTile : Wo_rt;
     constexpr int P = in_pitch(S);
     constexpr int ROWS = in_rows(R);
-    constexpr int NSLOT = (kTile * kTile / 8 + 63) / 64;      // 7 groups of eight per lane at most
+    constexpr int NSLOT = kWholeSlotsBf16;                    // 7 groups of eight per lane at most
     __shared__ __attribute__((aligned(16))) float lds[ROWS * P];
 
     const int lane = threadIdx.x;
@@ -545,8 +547,6 @@ __global__ __launch_bounds__(64) void sliding_plane_bf16_kernel(const unsigned s
 
 }  // namespace
 
-bool sliding_plane_whole(const float* x, const float* y, int W, int R, int S, int pad, int Ho, int Wo);
-
 bool sliding_plane_supported(int H, int W, int R, int S, int stride, int pad)
 {
     (void)H; (void)W;
@@ -554,11 +554,14 @@ bool sliding_plane_supported(int H, int W, int R, int S, int stride, int pad)
 }
 
 // True when the persistent whole-plane kernel takes the problem (planes that fit one 56 x 56 tile).
-bool sliding_plane_whole(const float* x, const float* y, int W, int R, int S, int pad, int Ho, int Wo)
+// The input plane may be larger than its output (padding below (R-1)/2: up to 60 x 60 for 5x5 without padding); a
+// lane holds at most kWholeSlots 16-byte groups of it, so the plane must fit 64 * kWholeSlots groups.
+bool sliding_plane_whole(const float* x, const float* y, int H, int W, int R, int S, int pad, int Ho, int Wo)
 {
     const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
     const bool fixed = R == S && (R == 3 || R == 5 || R == 7);
-    return fixed && aligned && Ho <= kTile && Wo <= kTile && 2 * pad <= R - 1 && W % 4 == 0 && Wo % 4 == 0;
+    return fixed && aligned && Ho <= kTile && Wo <= kTile && 2 * pad <= R - 1 && W % 4 == 0 && Wo % 4 == 0 &&
+           (int64_t)H * W <= 64 * 4 * kWholeSlots;
 }
 
 // Launch-latency regime: with fewer than 64 tiles (a quarter of the CUs) and a small filter the whole
@@ -574,7 +577,7 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int n_filters, int H, int W, int R, int S, int pad, int Ho, int Wo,
                                 hipStream_t st, const Epilogue& ep)
 {
-    if (sliding_plane_whole(x, y, W, R, S, pad, Ho, Wo) && planes <= 2147483647LL) {
+    if (sliding_plane_whole(x, y, H, W, R, S, pad, Ho, Wo) && planes <= 2147483647LL) {
         // enough wavefronts to fill the chip, each walking over several planes
         const int64_t want = 256 * 8;
         dim3 grid((unsigned)(planes < want ? planes : want)), block(64);
@@ -616,12 +619,13 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
 }
 
 // bf16 planes: 3x3 / 5x5 / 7x7 at stride 1, planes that fit one 56 x 56 tile, rows that are whole 16-byte groups.
-bool sliding_plane_bf16_supported(const void* x, const void* y, int W, int R, int S, int stride, int pad, int Ho, int Wo)
+bool sliding_plane_bf16_supported(const void* x, const void* y, int H, int W, int R, int S, int stride, int pad, int Ho,
+                                  int Wo)
 {
     const bool aligned = reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
     const bool fixed = R == S && (R == 3 || R == 5 || R == 7);
     return stride == 1 && fixed && aligned && Ho <= kTile && Wo <= kTile && 2 * pad <= R - 1 && W % 8 == 0 &&
-           Wo % 8 == 0;
+           Wo % 8 == 0 && (int64_t)H * W <= 64 * 8 * kWholeSlotsBf16;
 }
 
 hipError_t launch_sliding_plane_bf16(const unsigned short* x, const float* w, unsigned short* y, int64_t planes,

@@ -2,11 +2,26 @@
 // reported before anything is enqueued; nothing here allocates or synchronises.
 #include "../../include/swconv.h"
 
+#include <cstdio>
 #include <cstdlib>
 
 #include "swconv_internal.h"
 
 using namespace swconv;
+
+namespace swconv {
+
+namespace {
+struct LastKernel {
+    const char* name;
+    int arg[4];
+};
+thread_local LastKernel g_last_kernel{nullptr, {-1, -1, -1, -1}};
+}  // namespace
+
+void note_kernel(const char* name, int a, int b, int c, int d) { g_last_kernel = LastKernel{name, {a, b, c, d}}; }
+
+}  // namespace swconv
 
 namespace {
 
@@ -84,7 +99,7 @@ int run_plane(const float* x, const float* w, float* y, int64_t planes, int plan
         const bool rows = !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad);
         // the whole-plane kernel spends a 56 x 56 tile per plane: planes up to 32 wide leave most of its lanes
         // idle and go to the rows kernel (lane groups) when that has a variant
-        const bool whole = s.stride == 1 && sliding_plane_whole(x, y, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) &&
+        const bool whole = s.stride == 1 && sliding_plane_whole(x, y, s.H, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) &&
                            planes >= 512 && !(no_whole_plane_kernel() && s.R < 7) && !(rows && s.W <= 32);
         if (!whole && rows)
             return launch_status(launch_sliding_rows(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
@@ -160,6 +175,14 @@ int64_t sw_out_dim(int64_t in, int k, int stride, int pad)
     return span / stride + 1;
 }
 
+int64_t sw_out_dim_dilated(int64_t in, int k, int stride, int pad, int dilation)
+{
+    if (k <= 0 || dilation <= 0) return 0;
+    const int64_t span = (int64_t)dilation * (k - 1) + 1;      // input positions a dilated filter covers
+    if (span > kMaxElems) return 0;
+    return sw_out_dim(in, (int)span, stride, pad);
+}
+
 size_t sw_workspace_bytes(void) { return 0; }
 
 const char* sw_status_string(int status)
@@ -177,7 +200,19 @@ const char* sw_status_string(int status)
     }
 }
 
-int sw_version(void) { return 100; }
+int sw_version(void) { return 200; }
+
+const char* sw_last_kernel(void)
+{
+    thread_local char text[160];
+    const auto& k = g_last_kernel;
+    if (!k.name) return "";
+    int n = std::snprintf(text, sizeof text, "%s", k.name);
+    for (int i = 0; i < 4 && k.arg[i] >= 0 && n > 0 && n < (int)sizeof text; ++i)
+        n += std::snprintf(text + n, sizeof text - n, "%s%d", i == 0 ? "<" : ",", k.arg[i]);
+    if (k.arg[0] >= 0 && n > 0 && n < (int)sizeof text - 1) std::snprintf(text + n, sizeof text - n, ">");
+    return text;
+}
 
 int sw_conv1d(const float* x, const float* w, float* y, int64_t rows, int64_t len, int k, int stride,
               int pad, void* hip_stream)
@@ -366,7 +401,7 @@ int sw_conv2d_depthwise_bf16(const uint16_t* x, const float* w, uint16_t* y, int
     if (misaligned(w, 4)) return SW_ERR_ALIGN;
     if (overlaps(y, (int64_t)N * C * s.Ho * s.Wo * 2, w, (int64_t)C * R * S * 4)) return SW_ERR_ALIAS;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (!force_direct() && sliding_plane_bf16_supported(x, y, W, R, S, stride, pad, s.Ho, s.Wo))
+    if (!force_direct() && sliding_plane_bf16_supported(x, y, H, W, R, S, stride, pad, s.Ho, s.Wo))
         return launch_status(launch_sliding_plane_bf16(x, w, y, (int64_t)N * C, C, H, W, R, pad, s.Ho, s.Wo, st));
     return launch_status(launch_direct_depthwise_bf16(x, w, y, s, st));
 }
@@ -435,6 +470,68 @@ int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, 
         if (mfma_s8_any_supported(s)) return launch_status(launch_mfma_s8_any_requant(x, w, y, rq, s, st));
     }
     return launch_status(launch_direct_conv2d_s8_requant(x, w, y, rq, s, st));
+}
+
+int64_t sw_s8_packed_filter_bytes(int C_in, int C_out, int R, int S)
+{
+    if (C_in <= 0 || C_out <= 0 || R <= 0 || S <= 0 || R > kMaxFilter2D || S > kMaxFilter2D) return 0;
+    if ((int64_t)C_out * C_in * R * S > kMaxElems) return 0;
+    const int64_t bytes = s8_packed_filter_bytes(C_in, C_out, R, S);
+    return bytes > kMaxElems ? 0 : bytes;
+}
+
+int sw_s8_pack_filter(const int8_t* w, int8_t* packed, int C_in, int C_out, int R, int S, void* hip_stream)
+{
+    if (!w || !packed) return SW_ERR_NULL;
+    if (C_in <= 0 || C_out <= 0 || R <= 0 || S <= 0) return SW_ERR_SHAPE;
+    if (R > kMaxFilter2D || S > kMaxFilter2D) return SW_ERR_UNSUPPORTED;
+    const int64_t nw = (int64_t)C_out * C_in * R * S;
+    if (nw > kMaxElems) return SW_ERR_SHAPE;
+    const int64_t bytes = sw_s8_packed_filter_bytes(C_in, C_out, R, S);
+    if (bytes <= 0) return SW_ERR_SHAPE;
+    if (misaligned(packed, 16)) return SW_ERR_ALIGN;
+    if (overlaps(packed, bytes, w, nw)) return SW_ERR_ALIAS;
+    return launch_status(launch_pack_filter_s8(w, packed, C_in, C_out, R, S, static_cast<hipStream_t>(hip_stream)));
+}
+
+// Shared by the two packed-filter calls; bias/scale/y8 == nullptr: int32 sums.
+static int run_s8_packed(const int8_t* x, const int8_t* packed, const int32_t* bias, const float* scale, int32_t* y,
+                         int8_t* y8, int N, int C_in, int C_out, int H, int W, int R, int S, int stride, int pad, int relu,
+                         void* hip_stream)
+{
+    Conv2dShape s;
+    const void* out = y8 ? static_cast<const void*>(y8) : static_cast<const void*>(y);
+    // (check_conv2d sees the packed buffer as the filter: it is at least as large as the filter tensor)
+    const int rc = check_conv2d(x, packed, out, N, C_in, C_out, H, W, R, S, stride, pad, false, 1, y8 ? 1 : 4, &s);
+    if (rc != SW_OK) return rc;
+    if ((int64_t)C_in * R * S > 131071) return SW_ERR_SHAPE;  // 131072 * 2^14 = 2^31 leaves int32
+    const int64_t bytes = sw_s8_packed_filter_bytes(C_in, C_out, R, S);
+    if (bytes <= 0) return SW_ERR_SHAPE;
+    if (misaligned(packed, 16)) return SW_ERR_ALIGN;
+    const int64_t ny = (int64_t)N * C_out * s.Ho * s.Wo * (y8 ? 1 : 4);
+    if (overlaps(out, ny, packed, bytes)) return SW_ERR_ALIAS;
+    Requant rq{bias, scale, relu != 0};
+    if (y8) {
+        if (misaligned(scale, 4) || (bias && misaligned(bias, 4))) return SW_ERR_ALIGN;
+        if (overlaps(y8, ny, scale, (int64_t)C_out * 4) || (bias && overlaps(y8, ny, bias, (int64_t)C_out * 4)))
+            return SW_ERR_ALIAS;
+    }
+    return launch_status(launch_conv2d_s8_packed(x, packed, y, y8, y8 ? &rq : nullptr, s, !force_direct(),
+                                                 static_cast<hipStream_t>(hip_stream)));
+}
+
+int sw_conv2d_s8_packed(const int8_t* x, const int8_t* packed, int32_t* y, int N, int C_in, int C_out, int H, int W,
+                        int R, int S, int stride, int pad, void* hip_stream)
+{
+    return run_s8_packed(x, packed, nullptr, nullptr, y, nullptr, N, C_in, C_out, H, W, R, S, stride, pad, 0, hip_stream);
+}
+
+int sw_conv2d_s8_packed_requant(const int8_t* x, const int8_t* packed, const int32_t* bias, const float* scale,
+                                int8_t* y, int N, int C_in, int C_out, int H, int W, int R, int S, int stride, int pad,
+                                int relu, void* hip_stream)
+{
+    if (!scale || !y) return SW_ERR_NULL;
+    return run_s8_packed(x, packed, bias, scale, nullptr, y, N, C_in, C_out, H, W, R, S, stride, pad, relu, hip_stream);
 }
 
 }  // extern "C"

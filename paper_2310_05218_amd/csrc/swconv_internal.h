@@ -57,6 +57,10 @@ __device__ __forceinline__ int8_t requant_s8(int acc, int co, const Requant& rq)
     return (int8_t)(int)r;
 }
 
+// Records the kernel a launcher is about to enqueue (name and up to four template arguments) for the calling
+// thread; sw_last_kernel() reports it.  Costs a few stores per launch.
+void note_kernel(const char* name, int a = -1, int b = -1, int c = -1, int d = -1);
+
 // ---- direct (one thread per output) kernels: any valid shape -------------------------------
 hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,
                             int64_t len_out, int k, int stride, int pad, Op1D op, hipStream_t st);
@@ -87,7 +91,7 @@ hipError_t launch_pool_tiles(const float* x, float* y, int64_t rows, int64_t len
 // one input plane; depthwise: 1); filter index is p % n_filters.
 bool       sliding_plane_supported(int H, int W, int R, int S, int stride, int pad);
 bool       sliding_plane_worthwhile(int64_t planes, int Ho, int Wo, int R, int S);
-bool       sliding_plane_whole(const float* x, const float* y, int W, int R, int S, int pad, int Ho, int Wo);
+bool       sliding_plane_whole(const float* x, const float* y, int H, int W, int R, int S, int pad, int Ho, int Wo);
 
 // ---- sliding rows kernel (stride 1 or 2; 3x3 / 5x5 filters, 2x2 / 3x3 pooling windows): registers only,
 // DPP wavefront shifts for the halo ---------------------------------------------------------------
@@ -115,7 +119,7 @@ hipError_t launch_direct_s8_nhwc(const int8_t* x, const int8_t* w, int32_t* y, i
                                  const Conv2dShape& s, hipStream_t st);
 
 // ---- bf16 activations (bit patterns in unsigned short), fp32 filters and accumulation --------------------
-bool       sliding_plane_bf16_supported(const void* x, const void* y, int W, int R, int S, int stride, int pad, int Ho,
+bool       sliding_plane_bf16_supported(const void* x, const void* y, int H, int W, int R, int S, int stride, int pad, int Ho,
                                         int Wo);
 hipError_t launch_sliding_plane_bf16(const unsigned short* x, const float* w, unsigned short* y, int64_t planes,
                                      int n_filters, int H, int W, int R, int pad, int Ho, int Wo, hipStream_t st);
@@ -162,6 +166,16 @@ hipError_t launch_mfma_s8_any_requant(const int8_t* x, const int8_t* w, int8_t* 
                                       const Conv2dShape& s, hipStream_t st);
 hipError_t launch_direct_conv2d_s8_requant(const int8_t* x, const int8_t* w, int8_t* y8, const Requant& rq,
                                            const Conv2dShape& s, hipStream_t st);
+// ---- int8 with filters packed once into the matrix instruction's operand order (sw_mfma_s8_packed.hip);
+// rq == nullptr: int32 out (y), else int8 out (y8); allow_fast == false: one thread per output
+int64_t    s8_packed_filter_bytes(int C_in, int C_out, int R, int S);
+hipError_t launch_pack_filter_s8(const int8_t* w, int8_t* packed, int C_in, int C_out, int R, int S, hipStream_t st);
+hipError_t launch_conv2d_s8_packed(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant* rq,
+                                   const Conv2dShape& s, bool allow_fast, hipStream_t st);
+// ... the same for full-width row bands of narrow images (sw_mfma_s8_band.hip)
+bool       mfma_s8_band_supported(const int8_t* x, const int8_t* wp, const Conv2dShape& s);
+hipError_t launch_mfma_s8_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant* rq,
+                               const Conv2dShape& s, hipStream_t st);
 bool       mfma_s8_any_supported(const Conv2dShape& s);   // any extent, stride and channel count
 hipError_t launch_mfma_s8_any(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st);
 

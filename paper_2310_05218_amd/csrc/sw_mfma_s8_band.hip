@@ -29,6 +29,7 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32;
 using s8perm::gather4;
+using s8perm::wgather_tap;
 
 constexpr int kNBW = 4;            // 32-pixel blocks per wavefront at most
 constexpr int kMaxPieces = 20;     // 16-byte pieces of a channel's band (up to 304 bytes)
@@ -66,7 +67,9 @@ struct BandParams {
 // group, 256 contiguous bytes), the workgroup's packed filters as they are, and a private area per wavefront for
 // the raw band of the channel groups it stages: a wavefront transposes only what it fetched itself, so the only
 // workgroup barrier of the prologue is the one before the first matrix instruction.
-template <int KS, bool RQ>
+// RAWW: wp is the filter tensor as the caller has it ([C_out][C_in][3][3]): every workgroup byte-transposes the
+// filters of its 64 output channels into the packed order on their way into LDS (C_in a multiple of 64).
+template <int KS, bool RQ, bool RAWW>
 __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __restrict__ x, const int8_t* __restrict__ wp,
                                                               int32_t* __restrict__ y, const BandParams P,
                                                               int8_t* __restrict__ y8, const Requant rq)
@@ -79,7 +82,8 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
     constexpr int XPW = (16 * GPW * kMaxPieces + 63) / 64;  // raw 16-byte pieces per lane
     constexpr int QPW = GPW == 2 ? 32 : 64;                 // column quads per pass of a wavefront
     constexpr int XIW = (kWinPx / 4 + QPW - 1) / QPW;       // transposition passes
-    constexpr bool OWN = KS >= 2;       // a wavefront keeps the half of its A operands it fetched itself in registers
+    static_assert(!RAWW || KS % 2 == 0, "raw filters come in chunks of 64 input channels");
+    constexpr bool OWN = KS >= 2 && !RAWW;   // a wavefront keeps the half of its A operands it fetched itself in registers
     constexpr int AH = (NSTEP + 1) / 2; // A operands a wavefront fetches: the steps of its own parity
     const int C_out = P.C_out, H = P.H, W = P.W, pad = P.pad, Ho = P.Ho, Wo = P.Wo;
     const int rawpitch = 16 * P.max_pieces;
@@ -128,12 +132,26 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
     //      in the packed order); issue slot k of the main loop multiplies step k ^ wn, so a[even] are these
     const intx4* wa = reinterpret_cast<const intx4*>(wp) + ((int64_t)(2 * mb + wm) * NSTEP) * 64 + lane;
     intx4 a[NSTEP];
-    intx4 a_tmp[OWN ? 1 : AH];
+    intx4 a_tmp[OWN || RAWW ? 1 : AH];
+    // (raw filters) thread = (output channel wco of the workgroup's 64, quarter wq of a 64-channel chunk): its 16
+    // channels x 9 taps are 144 contiguous bytes of the filter tensor; sixteen consecutive lanes take sixteen
+    // consecutive output channels, which puts their transposed 16-byte pieces into sixteen different LDS banks
+    constexpr int NCH = RAWW ? KS / 2 : 1;                 // chunks of 64 input channels
+    const int wco = 16 * wave + (lane & 15), wq = lane >> 4;
+    intx4 wraw[RAWW ? NCH : 1][RAWW ? 9 : 1];
+    if constexpr (RAWW) {
+        const int8_t* src = wp + ((int64_t)((mb << 6) + wco) * C_in + 16 * wq) * 9;
 #pragma unroll
-    for (int j = 0; j < AH; ++j) {
-        const int st = min(2 * j + wn, NSTEP - 1);
-        if constexpr (OWN) a[2 * j] = wa[st * 64];
-        else a_tmp[j] = wa[st * 64];
+        for (int ch = 0; ch < NCH; ++ch)
+#pragma unroll
+            for (int i = 0; i < 9; ++i) wraw[ch][i] = *reinterpret_cast<const intx4*>(src + ch * 576 + 16 * i);
+    } else {
+#pragma unroll
+        for (int j = 0; j < AH; ++j) {
+            const int st = min(2 * j + wn, NSTEP - 1);
+            if constexpr (OWN) a[2 * j] = wa[st * 64];
+            else a_tmp[j] = wa[st * 64];
+        }
     }
 
     // ---- the padding: window cells outside the image are zeroed once (nothing else writes them)
@@ -179,7 +197,29 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
         }
     }
     // ---- the fetched A operands -> LDS, for the partner wavefront (and, for C_in == 32, for this one as well)
-    {
+    if constexpr (RAWW) {
+        // channel block wco / 32, step = tap * KS + 2 * chunk + wq / 2, operand lane = wco % 32 + 32 * (wq % 2)
+        unsigned char* dst = la + (((wco >> 5) * NSTEP + (wq >> 1)) * 64 + (wco & 31) + 32 * (wq & 1)) * 16;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            u32 raw[36];
+#pragma unroll
+            for (int i = 0; i < 9; ++i) {
+                raw[4 * i + 0] = (u32)wraw[ch][i].x; raw[4 * i + 1] = (u32)wraw[ch][i].y;
+                raw[4 * i + 2] = (u32)wraw[ch][i].z; raw[4 * i + 3] = (u32)wraw[ch][i].w;
+            }
+            unsigned char* d = dst + 2 * ch * 1024;
+            *reinterpret_cast<intx4*>(d + 0 * KS * 1024) = wgather_tap<0>(raw);
+            *reinterpret_cast<intx4*>(d + 1 * KS * 1024) = wgather_tap<1>(raw);
+            *reinterpret_cast<intx4*>(d + 2 * KS * 1024) = wgather_tap<2>(raw);
+            *reinterpret_cast<intx4*>(d + 3 * KS * 1024) = wgather_tap<3>(raw);
+            *reinterpret_cast<intx4*>(d + 4 * KS * 1024) = wgather_tap<4>(raw);
+            *reinterpret_cast<intx4*>(d + 5 * KS * 1024) = wgather_tap<5>(raw);
+            *reinterpret_cast<intx4*>(d + 6 * KS * 1024) = wgather_tap<6>(raw);
+            *reinterpret_cast<intx4*>(d + 7 * KS * 1024) = wgather_tap<7>(raw);
+            *reinterpret_cast<intx4*>(d + 8 * KS * 1024) = wgather_tap<8>(raw);
+        }
+    } else {
         unsigned char* la_own = la + (wm * NSTEP * 64 + lane) * 16;
 #pragma unroll
         for (int j = 0; j < AH; ++j) {
@@ -366,14 +406,14 @@ BandTiling pick_band(const Conv2dShape& s)
     return t;
 }
 
-template <int KS, bool RQ>
+template <int KS, bool RQ, bool RAWW>
 hipError_t launch_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant& rq, const Conv2dShape& s,
                        const BandTiling& t, hipStream_t st)
 {
     constexpr int GPW = KS >= 4 ? 2 : 1;     // as in the kernel
     auto lds_bytes = [](int pieces) { return 2 * KS * (kWinPx * 16 + 16) + 2 * 9 * KS * 1024 + 4 * (16 * GPW * 16 * pieces + 128); };
     const size_t lds = (size_t)lds_bytes(t.max_pieces);
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_band_kernel<KS, RQ>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_band_kernel<KS, RQ, RAWW>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize,
                                                        lds_bytes(kMaxPieces));
     if (attr != hipSuccess) return attr;
@@ -386,38 +426,44 @@ hipError_t launch_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8
     P.by_W4 = make_div(s.W / 4);
     P.by_IW = make_div(s.Wo + 2);
     P.by_Wo = make_div(s.Wo);
-    note_kernel("mfma_s8_band_kernel", KS, RQ);
-    hipLaunchKernelGGL((mfma_s8_band_kernel<KS, RQ>), dim3((unsigned)t.tiles, (unsigned)s.N, (unsigned)(s.C_out / 64)),
+    note_kernel("mfma_s8_band_kernel", KS, RQ, RAWW);
+    hipLaunchKernelGGL((mfma_s8_band_kernel<KS, RQ, RAWW>), dim3((unsigned)t.tiles, (unsigned)s.N, (unsigned)(s.C_out / 64)),
                        dim3(256), lds, st, x, wp, y, P, y8, rq);
     return hipGetLastError();
 }
 
 }  // namespace
 
-bool mfma_s8_band_supported(const int8_t* x, const int8_t* wp, const Conv2dShape& s)
+// raw_filters: w is the caller's [C_out][C_in][3][3] tensor (C_in a multiple of 64), else the packed copy.
+bool mfma_s8_band_supported(const int8_t* x, const int8_t* w, const Conv2dShape& s, bool raw_filters)
 {
     if (s.stride != 1 || s.R != 3 || s.S != 3 || s.dil != 1) return false;
     if (s.C_in != 32 && s.C_in != 64 && s.C_in != 128) return false;
+    if (raw_filters && s.C_in % 64 != 0) return false;
     if (s.C_out % 64 != 0 || s.W % 4 != 0 || ((int64_t)s.H * s.W) % 16 != 0) return false;
     if ((int64_t)s.C_in * s.H * s.W > 2147483647LL) return false;
-    if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(wp) % 16 != 0) return false;
+    if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0) return false;
     return pick_band(s).ok;
 }
 
-hipError_t launch_mfma_s8_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant* rq,
-                               const Conv2dShape& s, hipStream_t st)
+hipError_t launch_mfma_s8_band(const int8_t* x, const int8_t* w, int32_t* y, int8_t* y8, const Requant* rq,
+                               const Conv2dShape& s, bool raw_filters, hipStream_t st)
 {
     const BandTiling t = pick_band(s);
     const Requant none{nullptr, nullptr, 0};
     const int KS = s.C_in / 32;
-#define SW_BAND(KSC)                                                                         \
+#define SW_BAND(KSC, RAWC)                                                                   \
     do {                                                                                     \
-        if (rq) return launch_band<KSC, true>(x, wp, nullptr, y8, *rq, s, t, st);            \
-        return launch_band<KSC, false>(x, wp, y, nullptr, none, s, t, st);                   \
+        if (rq) return launch_band<KSC, true, RAWC>(x, w, nullptr, y8, *rq, s, t, st);       \
+        return launch_band<KSC, false, RAWC>(x, w, y, nullptr, none, s, t, st);              \
     } while (0)
-    if (KS == 4) SW_BAND(4);
-    if (KS == 2) SW_BAND(2);
-    SW_BAND(1);
+    if (raw_filters) {
+        if (KS == 4) SW_BAND(4, true);
+        SW_BAND(2, true);
+    }
+    if (KS == 4) SW_BAND(4, false);
+    if (KS == 2) SW_BAND(2, false);
+    SW_BAND(1, false);
 #undef SW_BAND
 }
 

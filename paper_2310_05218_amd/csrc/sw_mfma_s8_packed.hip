@@ -471,7 +471,7 @@ hipError_t launch_conv2d_s8_packed(const int8_t* x, const int8_t* wp, int32_t* y
                                    const Conv2dShape& s, bool allow_fast, hipStream_t st)
 {
     const Requant none{nullptr, nullptr, 0};
-    if (allow_fast && mfma_s8_band_supported(x, wp, s)) return launch_mfma_s8_band(x, wp, y, y8, rq, s, st);
+    if (allow_fast && mfma_s8_band_supported(x, wp, s, false)) return launch_mfma_s8_band(x, wp, y, y8, rq, s, false, st);
     if (allow_fast && packed_fast_path(x, wp, s)) {
         if (rq) return launch_fast<true>(x, wp, nullptr, y8, *rq, s, st);
         return launch_fast<false>(x, wp, y, nullptr, none, s, st);

@@ -443,6 +443,8 @@ int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, int N, int C_in, 
     if ((int64_t)C_in * R * S > 131071) return SW_ERR_SHAPE;  // 131072 * 2^14 = 2^31 leaves int32
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (!force_direct()) {
+        if (mfma_s8_band_supported(x, w, s, true))
+            return launch_status(launch_mfma_s8_band(x, w, y, nullptr, nullptr, s, true, st));
         if (mfma_s8_supported(s) && !no_large_tile_mfma()) return launch_status(launch_mfma_s8(x, w, y, s, st));
         if (mfma_s8_any_supported(s)) return launch_status(launch_mfma_s8_any(x, w, y, s, st));
     }
@@ -465,6 +467,8 @@ int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, 
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const Requant rq{bias, scale, relu != 0};
     if (!force_direct()) {
+        if (mfma_s8_band_supported(x, w, s, true))
+            return launch_status(launch_mfma_s8_band(x, w, nullptr, y, &rq, s, true, st));
         if (mfma_s8_requant_supported(s) && !no_large_tile_mfma())
             return launch_status(launch_mfma_s8_requant(x, w, y, rq, s, st));
         if (mfma_s8_any_supported(s)) return launch_status(launch_mfma_s8_any_requant(x, w, y, rq, s, st));

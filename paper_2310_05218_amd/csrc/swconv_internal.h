@@ -173,9 +173,10 @@ hipError_t launch_pack_filter_s8(const int8_t* w, int8_t* packed, int C_in, int 
 hipError_t launch_conv2d_s8_packed(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant* rq,
                                    const Conv2dShape& s, bool allow_fast, hipStream_t st);
 // ... the same for full-width row bands of narrow images (sw_mfma_s8_band.hip)
-bool       mfma_s8_band_supported(const int8_t* x, const int8_t* wp, const Conv2dShape& s);
-hipError_t launch_mfma_s8_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant* rq,
-                               const Conv2dShape& s, hipStream_t st);
+// (raw_filters: w is the caller's channel-first filter tensor, transposed by every workgroup on its way into LDS)
+bool       mfma_s8_band_supported(const int8_t* x, const int8_t* w, const Conv2dShape& s, bool raw_filters);
+hipError_t launch_mfma_s8_band(const int8_t* x, const int8_t* w, int32_t* y, int8_t* y8, const Requant* rq,
+                               const Conv2dShape& s, bool raw_filters, hipStream_t st);
 bool       mfma_s8_any_supported(const Conv2dShape& s);   // any extent, stride and channel count
 hipError_t launch_mfma_s8_any(const int8_t* x, const int8_t* w, int32_t* y, const Conv2dShape& s, hipStream_t st);
 

@@ -127,7 +127,7 @@ def test_workload5_full_size_packed(torch, sw, oracle):
     y_ref = oracle.conv2d_s8(x, w, 1, 1)
     packed = sw.sw_s8_pack_filter(dev(torch, w))
     y = sw.sw_conv2d_s8_packed(dev(torch, x), packed, 128, 3, 3, 1, 1)
-    assert sw.sw_last_kernel() == "mfma_s8_band_kernel<4,0>"
+    assert sw.sw_last_kernel() == "mfma_s8_band_kernel<4,0,0>"
     assert np.array_equal(y.cpu().numpy(), y_ref)
     # the packed copy depends on the filters only: a second, different batch with the same buffer
     x2 = inputs.uniform_s8((3, 128, 28, 28), 5121)

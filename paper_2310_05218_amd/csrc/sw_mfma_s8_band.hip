@@ -28,7 +28,6 @@ namespace {
 typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32;
-using s8perm::gather4;
 using s8perm::wgather_tap;
 
 constexpr int kNBW = 4;            // 32-pixel blocks per wavefront at most
@@ -36,16 +35,23 @@ constexpr int kMaxPieces = 20;     // 16-byte pieces of a channel's band (up to 
 constexpr int kWinPx = 320;        // window pixels
 constexpr int kLookAhead = 3;      // operand reads run this many steps ahead of the matrix instructions
 
-// 16 channels x 4 pixels (one dword per channel) -> pixel PX's 16 channel bytes
-template <int PX>
-__device__ __forceinline__ intx4 xgather_px(const u32* in)
+// 16 channels x 4 pixels (one dword per channel) -> four pixels x 16 channel bytes: four 4 x 4 byte transposes of
+// eight v_perm_b32 each (pairs of channels interleaved first, then pairs of pairs)
+__device__ __forceinline__ void transpose_16x4(const u32* in, intx4 (&out)[4])
 {
-    intx4 v;
-    v.x = (int)gather4<0 * 4 + PX, 1 * 4 + PX, 2 * 4 + PX, 3 * 4 + PX>(in);
-    v.y = (int)gather4<4 * 4 + PX, 5 * 4 + PX, 6 * 4 + PX, 7 * 4 + PX>(in);
-    v.z = (int)gather4<8 * 4 + PX, 9 * 4 + PX, 10 * 4 + PX, 11 * 4 + PX>(in);
-    v.w = (int)gather4<12 * 4 + PX, 13 * 4 + PX, 14 * 4 + PX, 15 * 4 + PX>(in);
-    return v;
+    u32 o[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const u32 r0 = in[4 * g], r1 = in[4 * g + 1], r2 = in[4 * g + 2], r3 = in[4 * g + 3];
+        const u32 t0 = s8perm::perm(r1, r0, 0x05010400u), t1 = s8perm::perm(r1, r0, 0x07030602u);   // (r0.b, r1.b) pairs
+        const u32 u0 = s8perm::perm(r3, r2, 0x05010400u), u1 = s8perm::perm(r3, r2, 0x07030602u);
+        o[0][g] = s8perm::perm(u0, t0, 0x05040100u);
+        o[1][g] = s8perm::perm(u0, t0, 0x07060302u);
+        o[2][g] = s8perm::perm(u1, t1, 0x05040100u);
+        o[3][g] = s8perm::perm(u1, t1, 0x07060302u);
+    }
+#pragma unroll
+    for (int px = 0; px < 4; ++px) out[px] = intx4{(int)o[px][0], (int)o[px][1], (int)o[px][2], (int)o[px][3]};
 }
 
 // n / d without a branch: magic = ceil(2^32 / d) for d > 1; d == 1 has magic 0 and one 1.  Exact while n * d < 2^32.
@@ -69,8 +75,10 @@ struct BandParams {
 // workgroup barrier of the prologue is the one before the first matrix instruction.
 // RAWW: wp is the filter tensor as the caller has it ([C_out][C_in][3][3]): every workgroup byte-transposes the
 // filters of its 64 output channels into the packed order on their way into LDS (C_in a multiple of 64).
-template <int KS, bool RQ, bool RAWW>
-__global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __restrict__ x, const int8_t* __restrict__ wp,
+// NWV: wavefronts per workgroup, 4 or 8: the first four stage and multiply, the others only help with the staging
+// (the byte transposes are chains of LDS reads, permutes and LDS writes: two wavefronts per SIMD overlap them).
+template <int KS, bool RQ, bool RAWW, int NWV>
+__global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t* __restrict__ x, const int8_t* __restrict__ wp,
                                                               int32_t* __restrict__ y, const BandParams P,
                                                               int8_t* __restrict__ y8, const Requant rq)
 {
@@ -78,7 +86,8 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
     constexpr int NG = 2 * KS;                              // groups of 16 input channels
     constexpr int GP = kWinPx * 16 + 16;                    // bytes per group in the window
     constexpr int NSTEP = 9 * KS;
-    constexpr int GPW = NG >= 8 ? 2 : 1;                    // channel groups a wavefront stages
+    static_assert(NWV == 4 || (NWV == 8 && KS == 4), "helper wavefronts exist for C_in == 128 only");
+    constexpr int GPW = NG > NWV ? NG / NWV : 1;            // channel groups a wavefront stages
     constexpr int XPW = (16 * GPW * kMaxPieces + 63) / 64;  // raw 16-byte pieces per lane
     constexpr int QPW = GPW == 2 ? 32 : 64;                 // column quads per pass of a wavefront
     constexpr int XIW = (kWinPx / 4 + QPW - 1) / QPW;       // transposition passes
@@ -86,7 +95,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
     constexpr bool OWN = KS >= 2 && !RAWW;   // a wavefront keeps the half of its A operands it fetched itself in registers
     constexpr int AH = (NSTEP + 1) / 2; // A operands a wavefront fetches: the steps of its own parity
     const int C_out = P.C_out, H = P.H, W = P.W, pad = P.pad, Ho = P.Ho, Wo = P.Wo;
-    const int rawpitch = 16 * P.max_pieces;
+    constexpr int rawpitch = 16 * kMaxPieces;               // bytes per channel in the raw band (immediate offsets)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned char* lx = smem;                                   // [channel group][window pixel][16]
     unsigned char* la = smem + NG * GP;                         // [channel block][step][lane][16]: as packed
@@ -95,7 +104,8 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int lg = lane >> 5, lj = lane & 31;      // K half and row/column inside a 32 x 32 block
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = (wave >> 1) & 1, wn = wave & 1;   // (of the multiplying wavefronts 0..3)
+    const bool multiplier = wave < 4;
     const int n = blockIdx.y, mb = blockIdx.z;
 
     // the tile: blocks [blk0, blk0 + nblk) of 32 consecutive pixels of the image in row-major order, i.e. output
@@ -108,6 +118,18 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
     const int HW = H * W;
     const int8_t* xn = x + (int64_t)n * C_in * HW;
 
+    // ---- the padding: window cells outside the image are zeroed once (nothing else writes them)
+    {
+        const int cells = IH * IW;
+        for (int i = tid; i < cells; i += NWV * 64) {
+            const int e = div_by(i, P.by_IW), c = i - e * IW;
+            const int gr = row0 - pad + e, gc = c - pad;
+            if (gr < 0 || gr >= H || gc < 0 || gc >= W) {
+#pragma unroll
+                for (int g = 0; g < NG; ++g) *reinterpret_cast<intx4*>(lx + g * GP + i * 16) = intx4{0, 0, 0, 0};
+            }
+        }
+    }
     // ---- the band: image rows [r_lo, r_hi) of every channel, fetched from the 16-byte boundary below its start;
     //      this wavefront takes the channels of groups g0 .. g0 + GPW - 1
     const int r_lo = max(row0 - pad, 0), r_hi = min(row0 - pad + IH, H);
@@ -115,7 +137,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
     const int npieces = (skew + (r_hi - r_lo) * W + 15) >> 4;
     const int g0 = wave * GPW;
     const bool stager = g0 < NG;                              // (C_in == 32: two groups, wavefronts 2 and 3 stage nothing)
-    unsigned char* lraw_w = lraw + wave * (16 * GPW * rawpitch + 128);
+    unsigned char* lraw_w = lraw + wave * (16 * GPW * rawpitch + 144);
     intx4 xr[XPW];
     int xraw[XPW];
 #pragma unroll
@@ -124,7 +146,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
         const int cl = div_by(idx, P.by_pieces);
         const int piece = idx - cl * P.max_pieces;
         const bool ok = stager && cl < 16 * GPW && piece < npieces;
-        xraw[k] = ok ? cl * rawpitch + 128 * (cl >> 4) + 16 * piece : -1;
+        xraw[k] = ok ? cl * rawpitch + 128 * (cl >> 4) + 16 * piece : 16 * GPW * rawpitch + 128;   // (else: a spare slot)
         const int8_t* src = xn + (ok ? (16 * g0 + cl) * HW + (band_off - skew) + 16 * piece : 0);
         xr[k] = *reinterpret_cast<const intx4*>(src);
     }
@@ -137,15 +159,17 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
     // channels x 9 taps are 144 contiguous bytes of the filter tensor; sixteen consecutive lanes take sixteen
     // consecutive output channels, which puts their transposed 16-byte pieces into sixteen different LDS banks
     constexpr int NCH = RAWW ? KS / 2 : 1;                 // chunks of 64 input channels
-    const int wco = 16 * wave + (lane & 15), wq = lane >> 4;
-    intx4 wraw[RAWW ? NCH : 1][RAWW ? 9 : 1];
+    constexpr int CPT = NCH * 4 / NWV > 0 ? NCH * 4 / NWV : 1;  // ... per thread (chunk (wave / 4) + j * NWV / 4)
+    const int wco = 16 * (wave & 3) + (lane & 15), wq = lane >> 4;
+    intx4 wraw[RAWW ? CPT : 1][RAWW ? 9 : 1];
     if constexpr (RAWW) {
         const int8_t* src = wp + ((int64_t)((mb << 6) + wco) * C_in + 16 * wq) * 9;
 #pragma unroll
-        for (int ch = 0; ch < NCH; ++ch)
+        for (int j = 0; j < CPT; ++j)
 #pragma unroll
-            for (int i = 0; i < 9; ++i) wraw[ch][i] = *reinterpret_cast<const intx4*>(src + ch * 576 + 16 * i);
-    } else {
+            for (int i = 0; i < 9; ++i)
+                wraw[j][i] = *reinterpret_cast<const intx4*>(src + ((wave >> 2) + j * (NWV / 4)) * 576 + 16 * i);
+    } else if (multiplier) {
 #pragma unroll
         for (int j = 0; j < AH; ++j) {
             const int st = min(2 * j + wn, NSTEP - 1);
@@ -154,23 +178,11 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
         }
     }
 
-    // ---- the padding: window cells outside the image are zeroed once (nothing else writes them)
-    {
-        const int cells = IH * IW;
-        for (int i = tid; i < cells; i += 256) {
-            const int e = div_by(i, P.by_IW), c = i - e * IW;
-            const int gr = row0 - pad + e, gc = c - pad;
-            if (gr < 0 || gr >= H || gc < 0 || gc >= W) {
-#pragma unroll
-                for (int g = 0; g < NG; ++g) *reinterpret_cast<intx4*>(lx + g * GP + i * 16) = intx4{0, 0, 0, 0};
-            }
-        }
-    }
     // ---- band -> this wavefront's LDS area as it is, then -> [group][pixel][16] with the byte transposes:
     //      item = (channel group, column quad of a window row); LDS operations of a wavefront complete in order
 #pragma unroll
     for (int k = 0; k < XPW; ++k)
-        if (xraw[k] >= 0) *reinterpret_cast<intx4*>(lraw_w + xraw[k]) = xr[k];
+        *reinterpret_cast<intx4*>(lraw_w + xraw[k]) = xr[k];
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     if (stager) {
         const int W4 = W >> 2;
@@ -189,10 +201,12 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
 #pragma unroll
                 for (int c = 0; c < 16; ++c) v[c] = *reinterpret_cast<const u32*>(src + c * rawpitch);
                 unsigned char* dst = lx + (g0 + gl) * GP + (e * IW + pad + 4 * cq) * 16;
-                *reinterpret_cast<intx4*>(dst) = xgather_px<0>(v);
-                *reinterpret_cast<intx4*>(dst + 16) = xgather_px<1>(v);
-                *reinterpret_cast<intx4*>(dst + 32) = xgather_px<2>(v);
-                *reinterpret_cast<intx4*>(dst + 48) = xgather_px<3>(v);
+                intx4 t[4];
+                transpose_16x4(v, t);
+                *reinterpret_cast<intx4*>(dst) = t[0];
+                *reinterpret_cast<intx4*>(dst + 16) = t[1];
+                *reinterpret_cast<intx4*>(dst + 32) = t[2];
+                *reinterpret_cast<intx4*>(dst + 48) = t[3];
             }
         }
     }
@@ -201,14 +215,14 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
         // channel block wco / 32, step = tap * KS + 2 * chunk + wq / 2, operand lane = wco % 32 + 32 * (wq % 2)
         unsigned char* dst = la + (((wco >> 5) * NSTEP + (wq >> 1)) * 64 + (wco & 31) + 32 * (wq & 1)) * 16;
 #pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) {
+        for (int j = 0; j < CPT; ++j) {
             u32 raw[36];
 #pragma unroll
             for (int i = 0; i < 9; ++i) {
-                raw[4 * i + 0] = (u32)wraw[ch][i].x; raw[4 * i + 1] = (u32)wraw[ch][i].y;
-                raw[4 * i + 2] = (u32)wraw[ch][i].z; raw[4 * i + 3] = (u32)wraw[ch][i].w;
+                raw[4 * i + 0] = (u32)wraw[j][i].x; raw[4 * i + 1] = (u32)wraw[j][i].y;
+                raw[4 * i + 2] = (u32)wraw[j][i].z; raw[4 * i + 3] = (u32)wraw[j][i].w;
             }
-            unsigned char* d = dst + 2 * ch * 1024;
+            unsigned char* d = dst + 2 * ((wave >> 2) + j * (NWV / 4)) * 1024;
             *reinterpret_cast<intx4*>(d + 0 * KS * 1024) = wgather_tap<0>(raw);
             *reinterpret_cast<intx4*>(d + 1 * KS * 1024) = wgather_tap<1>(raw);
             *reinterpret_cast<intx4*>(d + 2 * KS * 1024) = wgather_tap<2>(raw);
@@ -219,7 +233,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
             *reinterpret_cast<intx4*>(d + 7 * KS * 1024) = wgather_tap<7>(raw);
             *reinterpret_cast<intx4*>(d + 8 * KS * 1024) = wgather_tap<8>(raw);
         }
-    } else {
+    } else if (multiplier) {
         unsigned char* la_own = la + (wm * NSTEP * 64 + lane) * 16;
 #pragma unroll
         for (int j = 0; j < AH; ++j) {
@@ -231,6 +245,7 @@ __global__ __launch_bounds__(256, 1) void mfma_s8_band_kernel(const int8_t* __re
         }
     }
     __syncthreads();
+    if (!multiplier) return;
 
     // the tile's blocks in two halves, one per wavefront pair member
     const int half = (nblk + 1) >> 1;
@@ -410,12 +425,14 @@ template <int KS, bool RQ, bool RAWW>
 hipError_t launch_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant& rq, const Conv2dShape& s,
                        const BandTiling& t, hipStream_t st)
 {
-    constexpr int GPW = KS >= 4 ? 2 : 1;     // as in the kernel
-    auto lds_bytes = [](int pieces) { return 2 * KS * (kWinPx * 16 + 16) + 2 * 9 * KS * 1024 + 4 * (16 * GPW * 16 * pieces + 128); };
-    const size_t lds = (size_t)lds_bytes(t.max_pieces);
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_band_kernel<KS, RQ, RAWW>),
+    // helper wavefronts where the register budget allows two wavefronts per SIMD (the requantising stores need more)
+    constexpr int NWV = (KS == 4 && !RQ) ? 8 : 4;
+    constexpr int GPW = 2 * KS > NWV ? 2 * KS / NWV : 1;     // as in the kernel
+    constexpr int kLds = 2 * KS * (kWinPx * 16 + 16) + 2 * 9 * KS * 1024 + NWV * (16 * GPW * 16 * kMaxPieces + 144);
+    const size_t lds = kLds;
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_band_kernel<KS, RQ, RAWW, NWV>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                       lds_bytes(kMaxPieces));
+                                                       kLds);
     if (attr != hipSuccess) return attr;
     BandParams P;
     P.C_out = s.C_out; P.H = s.H; P.W = s.W; P.pad = s.pad; P.Ho = s.Ho; P.Wo = s.Wo; P.base = t.base; P.rem = t.rem;
@@ -427,8 +444,8 @@ hipError_t launch_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8
     P.by_IW = make_div(s.Wo + 2);
     P.by_Wo = make_div(s.Wo);
     note_kernel("mfma_s8_band_kernel", KS, RQ, RAWW);
-    hipLaunchKernelGGL((mfma_s8_band_kernel<KS, RQ, RAWW>), dim3((unsigned)t.tiles, (unsigned)s.N, (unsigned)(s.C_out / 64)),
-                       dim3(256), lds, st, x, wp, y, P, y8, rq);
+    hipLaunchKernelGGL((mfma_s8_band_kernel<KS, RQ, RAWW, NWV>), dim3((unsigned)t.tiles, (unsigned)s.N, (unsigned)(s.C_out / 64)),
+                       dim3(NWV * 64), lds, st, x, wp, y, P, y8, rq);
     return hipGetLastError();
 }
 

@@ -282,6 +282,10 @@ LAYERS = [
     ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
     ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
     ("conv_s8_requant_3x3_128to128", "conv_s8_rq", (32, 128, 28, 28), 3, 1, 1, 128),
+    ("conv_s8_packed_3x3_128to128", "conv_s8_pk", (32, 128, 28, 28), 3, 1, 1, 128),
+    ("conv_s8_packed_requant_3x3_128to128", "conv_s8_pk_rq", (32, 128, 28, 28), 3, 1, 1, 128),
+    ("conv_s8_3x3_64to64_56x56", "conv_s8", (32, 64, 56, 56), 3, 1, 1, 64),
+    ("conv_s8_packed_3x3_64to64_56x56", "conv_s8_pk", (32, 64, 56, 56), 3, 1, 1, 64),
     ("conv_s8_nhwc_3x3_128to128", "conv_s8_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
     ("conv_s8_nhwc_requant_3x3_128to128", "conv_s8_nhwc_rq", (32, 128, 28, 28), 3, 1, 1, 128),
     ("conv_s8_nhwc_3x3_s2_64to128", "conv_s8_nhwc", (32, 64, 56, 56), 3, 2, 1, 128),
@@ -289,13 +293,21 @@ LAYERS = [
 ]
 
 
-def layer_case(idx, n_images=None):
+def layer_case(idx, n_images=None, data=True):
     """Host-side description of layer LAYERS[idx] (optionally with fewer images): seeded inputs and everything
     needed to call it.  Shared by `--layers` (timing) and tests/test_gpu_bench_shapes.py (parity against the CPU
-    oracle), so that what is timed is what is checked."""
+    oracle), so that what is timed is what is checked.  data=False: arrays of zeros with the same shapes and types
+    (the library's choice of kernel looks at shapes and addresses only)."""
     import numpy as np
 
     from paper_2310_05218_amd import inputs
+
+    if not data:
+        class inputs:       # noqa: F811  (same generators, zeros)
+            seed_for = staticmethod(lambda *a: 0)
+            normal_f32 = staticmethod(lambda shape, seed, std=1.0: np.zeros(shape, np.float32))
+            uniform_s8 = staticmethod(lambda shape, seed: np.zeros(shape, np.int8))
+            normal_bf16 = staticmethod(lambda shape, seed, std=1.0: np.zeros(shape, np.uint16))
 
     name, kind, shape, R, stride, pad, *more = LAYERS[idx]
     N, C, H, W = shape
@@ -332,7 +344,7 @@ def layer_case(idx, n_images=None):
         if kind == "dw_br":
             c["bias"] = inputs.normal_f32((C,), inputs.seed_for(7, 200 + idx), 0.5)
         if kind == "dw_bf16":
-            x = inputs.to_bf16_bits(x)
+            x = inputs.normal_bf16((N, C, H, W), inputs.seed_for(7, idx))
     c["x"], c["w"] = x, w
     return c
 
@@ -387,6 +399,12 @@ def layer_call(sw, c, d, x=None, y=None):
         return sw.sw_conv2d_s8(x, d["w"], st, p, out=y)
     if kind == "conv_s8_rq":
         return sw.sw_conv2d_s8_requant(x, d["w"], d["bias"], d["scale"], st, p, True, out=y)
+    if kind in ("conv_s8_pk", "conv_s8_pk_rq"):
+        if "packed" not in d:            # the filters are packed once, outside every timed region
+            d["packed"] = sw.sw_s8_pack_filter(d["w"])
+        if kind == "conv_s8_pk":
+            return sw.sw_conv2d_s8_packed(x, d["packed"], c["C_out"], c["R"], c["R"], st, p, out=y)
+        return sw.sw_conv2d_s8_packed(x, d["packed"], c["C_out"], c["R"], c["R"], st, p, d["bias"], d["scale"], True, out=y)
     if kind == "conv_s8_nhwc":
         return sw.sw_conv2d_s8_nhwc(x, d["w"], st, p, out=y)
     if kind == "conv_s8_nhwc_rq":

@@ -270,9 +270,13 @@ int sw_conv2d_depthwise_dilated(const float* x, const float* w, float* y,
  * call for a geometry (H, W, R, S, pad) compiles a kernel specialised on it (about a
  * second on the calling thread, host-synchronous; do not make that first call inside
  * a stream capture -- use sw_jit_prepare_depthwise beforehand), keeps it for the life
- * of the process and launches it; later calls only launch.  Every other valid shape
- * runs sw_conv2d_depthwise's precompiled kernels.  SW_ERR_JIT if the compiler
- * refuses the generated source (its log goes to stderr).  Thread-safe.
+ * of the process and launches it; later calls only launch.  That first call is the one
+ * place where this library allocates: loading the compiled module takes host and device
+ * memory from the HIP runtime, so callers that must not allocate (stream capture, serving
+ * loops) call sw_jit_prepare_depthwise for their geometries at set-up.  Every other valid
+ * shape, and a geometry whose generated kernel cannot be compiled or loaded (the compiler's
+ * log goes to stderr; sw_jit_prepare_depthwise reports SW_ERR_JIT), runs
+ * sw_conv2d_depthwise's precompiled kernels.  Thread-safe.
  */
 int sw_conv2d_depthwise_jit(const float* x, const float* w, float* y,
                             int N, int C, int H, int W, int R, int S,

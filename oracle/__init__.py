@@ -91,6 +91,18 @@ def set_threads(n: int) -> None:
     _load().oracle_set_threads(int(n))
 
 
+def bf16_to_f32(b: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns (uint16) -> the fp32 values they denote (exact): the widening the 16-bit entry points are
+    defined on."""
+    return (np.ascontiguousarray(b, np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
+def f32_to_bf16_rne(a: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bit patterns (uint16), round to nearest, ties to even; finite inputs."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
+
+
 def out_dim(n_in: int, k: int, stride: int, pad: int) -> int:
     return int(_load().oracle_out_dim(n_in, k, stride, pad))
 

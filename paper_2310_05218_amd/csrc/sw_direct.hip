@@ -197,15 +197,15 @@ hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t ro
     const int grid = grid_for(rows * len_out);
     switch (op) {
         case OP_CONV:
-            hipLaunchKernelGGL(direct_1d_kernel<OP_CONV>, dim3(grid), dim3(kThreads), 0, st, x, w, y, rows,
+            SW_NOTED_LAUNCH(note_kernel("direct_1d_kernel", (int)(OP_CONV)), direct_1d_kernel<OP_CONV>, dim3(grid), dim3(kThreads), 0, st, x, w, y, rows,
                                len, len_out, k, stride, pad);
             break;
         case OP_AVG:
-            hipLaunchKernelGGL(direct_1d_kernel<OP_AVG>, dim3(grid), dim3(kThreads), 0, st, x, w, y, rows,
+            SW_NOTED_LAUNCH(note_kernel("direct_1d_kernel", (int)(OP_AVG)), direct_1d_kernel<OP_AVG>, dim3(grid), dim3(kThreads), 0, st, x, w, y, rows,
                                len, len_out, k, stride, pad);
             break;
         case OP_MAX:
-            hipLaunchKernelGGL(direct_1d_kernel<OP_MAX>, dim3(grid), dim3(kThreads), 0, st, x, w, y, rows,
+            SW_NOTED_LAUNCH(note_kernel("direct_1d_kernel", (int)(OP_MAX)), direct_1d_kernel<OP_MAX>, dim3(grid), dim3(kThreads), 0, st, x, w, y, rows,
                                len, len_out, k, stride, pad);
             break;
     }
@@ -219,10 +219,10 @@ hipError_t launch_direct_conv2d_f32(const float* x, const float* w, float* y, co
     const Epilogue e = ep ? *ep : Epilogue{nullptr, 0};
     const Requant none{nullptr, nullptr, 0};
     if (depthwise)
-        hipLaunchKernelGGL((direct_conv2d_kernel<float, float, true>), dim3(grid), dim3(kThreads), 0, st, x,
+        SW_NOTED_LAUNCH(note_kernel("direct_conv2d_kernel", (int)(true)), (direct_conv2d_kernel<float, float, true>), dim3(grid), dim3(kThreads), 0, st, x,
                            w, y, s, static_cast<int8_t*>(nullptr), none, e);
     else
-        hipLaunchKernelGGL((direct_conv2d_kernel<float, float, false>), dim3(grid), dim3(kThreads), 0, st, x,
+        SW_NOTED_LAUNCH(note_kernel("direct_conv2d_kernel", (int)(false)), (direct_conv2d_kernel<float, float, false>), dim3(grid), dim3(kThreads), 0, st, x,
                            w, y, s, static_cast<int8_t*>(nullptr), none, e);
     return hipGetLastError();
 }
@@ -231,7 +231,7 @@ hipError_t launch_direct_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y,
                                    hipStream_t st)
 {
     const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
-    hipLaunchKernelGGL((direct_conv2d_kernel<int8_t, int32_t, false>), dim3(grid), dim3(kThreads), 0, st, x,
+    SW_NOTED_LAUNCH(note_kernel("direct_conv2d_kernel", (int)(false)), (direct_conv2d_kernel<int8_t, int32_t, false>), dim3(grid), dim3(kThreads), 0, st, x,
                        w, y, s);
     return hipGetLastError();
 }
@@ -240,7 +240,7 @@ hipError_t launch_direct_conv2d_s8_requant(const int8_t* x, const int8_t* w, int
                                            const Conv2dShape& s, hipStream_t st)
 {
     const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
-    hipLaunchKernelGGL((direct_conv2d_kernel<int8_t, int32_t, false, true>), dim3(grid), dim3(kThreads), 0, st, x,
+    SW_NOTED_LAUNCH(note_kernel("direct_conv2d_kernel", (int)(false), (int)(true)), (direct_conv2d_kernel<int8_t, int32_t, false, true>), dim3(grid), dim3(kThreads), 0, st, x,
                        w, static_cast<int32_t*>(nullptr), s, y8, rq);
     return hipGetLastError();
 }
@@ -253,19 +253,19 @@ hipError_t launch_direct_pool2d(const float* x, float* y, int64_t planes, int H,
         const int64_t g = (waves + kThreads / 64 - 1) / (kThreads / 64);
         const int grid = (int)(g < 256 * 256 ? g : 256 * 256);
         if (maximum)
-            hipLaunchKernelGGL(wave_pool2d_kernel<true>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
+            SW_NOTED_LAUNCH(note_kernel("wave_pool2d_kernel", (int)(true)), wave_pool2d_kernel<true>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
                                stride, pad, Ho, Wo);
         else
-            hipLaunchKernelGGL(wave_pool2d_kernel<false>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
+            SW_NOTED_LAUNCH(note_kernel("wave_pool2d_kernel", (int)(false)), wave_pool2d_kernel<false>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
                                stride, pad, Ho, Wo);
         return hipGetLastError();
     }
     const int grid = grid_for(planes * Ho * Wo);
     if (maximum)
-        hipLaunchKernelGGL(direct_pool2d_kernel<true>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
+        SW_NOTED_LAUNCH(note_kernel("direct_pool2d_kernel", (int)(true)), direct_pool2d_kernel<true>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
                            stride, pad, Ho, Wo);
     else
-        hipLaunchKernelGGL(direct_pool2d_kernel<false>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
+        SW_NOTED_LAUNCH(note_kernel("direct_pool2d_kernel", (int)(false)), direct_pool2d_kernel<false>, dim3(grid), dim3(kThreads), 0, st, x, y, planes, H, W, R, S,
                            stride, pad, Ho, Wo);
     return hipGetLastError();
 }
@@ -274,7 +274,7 @@ hipError_t launch_direct_depthwise_bf16(const unsigned short* x, const float* w,
                                         const Conv2dShape& s, hipStream_t st)
 {
     const int grid = grid_for((int64_t)s.N * s.C_out * s.Ho * s.Wo);
-    hipLaunchKernelGGL(direct_depthwise_bf16_kernel, dim3(grid), dim3(kThreads), 0, st, x, w, y, s);
+    SW_NOTED_LAUNCH(note_kernel("direct_depthwise_bf16_kernel"), direct_depthwise_bf16_kernel, dim3(grid), dim3(kThreads), 0, st, x, w, y, s);
     return hipGetLastError();
 }
 

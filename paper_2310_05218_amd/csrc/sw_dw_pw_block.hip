@@ -236,15 +236,15 @@ hipError_t launch_dw_pw_block(const float* x, const float* w_dw, const float* b_
     if (nb == 4) {
         static const hipError_t attr = allow_lds<4>();
         if (attr != hipSuccess) return attr;
-        hipLaunchKernelGGL(dw_pw_block_kernel<4>, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
+        SW_NOTED_LAUNCH(note_kernel("dw_pw_block_kernel", (int)(4)), dw_pw_block_kernel<4>, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
     } else if (nb == 2) {
         static const hipError_t attr = allow_lds<2>();
         if (attr != hipSuccess) return attr;
-        hipLaunchKernelGGL(dw_pw_block_kernel<2>, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
+        SW_NOTED_LAUNCH(note_kernel("dw_pw_block_kernel", (int)(2)), dw_pw_block_kernel<2>, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
     } else {
         static const hipError_t attr = allow_lds<1>();
         if (attr != hipSuccess) return attr;
-        hipLaunchKernelGGL(dw_pw_block_kernel<1>, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
+        SW_NOTED_LAUNCH(note_kernel("dw_pw_block_kernel", (int)(1)), dw_pw_block_kernel<1>, grid, dim3(256), lds, st, x, w_dw, w_pw, y, P);
     }
     return hipGetLastError();
 }

@@ -88,15 +88,6 @@ bool jit_plan(int H, int W, int R, int S, int stride, int pad, JitPlan* out)
     if (RB > R) RB = R;
     const int r_blocks = (R + RB - 1) / RB;
     p.RB = (R + r_blocks - 1) / r_blocks;
-    // SWCONV_JIT_RB / SWCONV_JIT_NT override the split (tuning)
-    if (const char* e = getenv("SWCONV_JIT_RB")) {
-        const int v = atoi(e);
-        if (v >= 1 && v <= R) p.RB = v;
-    }
-    if (const char* e = getenv("SWCONV_JIT_NT")) {
-        const int v = atoi(e);
-        if (v >= 1 && v <= S && v <= 16) p.NT = v;
-    }
     *out = p;
     return true;
 }
@@ -223,6 +214,7 @@ int jit_launch_plane(const float* x, const float* w, float* y, int64_t planes, i
     int planes_i = (int)planes, wgs = (int)grid;
     void* args[] = {(void*)&x, (void*)&w,           (void*)&y,        (void*)&planes_i,
                     (void*)&planes_per_x, (void*)&n_filters, (void*)&wgs};
+    note_kernel("sliding_plane_jit_kernel", R, S, H, W);
     const hipError_t e = hipModuleLaunchKernel(k.fn, grid, 1, 1, 64, 1, 1, (unsigned)k.plan.lds_bytes, st, args, nullptr);
     if (e != hipSuccess) {
         (void)hipGetLastError();

@@ -349,7 +349,7 @@ hipError_t launch(const float* x, const float* w, float* y, const Conv2dShape& s
     P.by_IW = make_fastdiv(t.TW + S - 1);
     P.by_npx = make_fastdiv((t.TH + R - 1) * (t.TW + S - 1));
     dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)s.N, (unsigned)(s.C_out / 64));
-    hipLaunchKernelGGL((mfma_f32_kernel<R, S, DB, EP>), grid, dim3(256), bytes, st, x, w, y, P);
+    SW_NOTED_LAUNCH(note_kernel("mfma_f32_kernel", (int)(R), (int)(S), (int)(DB), (int)(EP)), (mfma_f32_kernel<R, S, DB, EP>), grid, dim3(256), bytes, st, x, w, y, P);
     return hipGetLastError();
 }
 

@@ -324,13 +324,13 @@ hipError_t launch_any(const float* x, const float* w, float* y, const Conv2dShap
     const bool large = a.lds > (size_t)kLdsBudget;
     if (a.prefetch && CK * a.IH * a.IW <= 256 * 8) {
         if (large && allow_large_lds<CK, 8>() != hipSuccess) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((mfma_f32_any_kernel<CK, 8>), grid, dim3(256), a.lds, st, x, w, y, P);
+        SW_NOTED_LAUNCH(note_kernel("mfma_f32_any_kernel", (int)(CK), (int)(8)), (mfma_f32_any_kernel<CK, 8>), grid, dim3(256), a.lds, st, x, w, y, P);
     } else if (a.prefetch) {
         if (large && allow_large_lds<CK, kXS>() != hipSuccess) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((mfma_f32_any_kernel<CK, kXS>), grid, dim3(256), a.lds, st, x, w, y, P);
+        SW_NOTED_LAUNCH(note_kernel("mfma_f32_any_kernel", (int)(CK), (int)(kXS)), (mfma_f32_any_kernel<CK, kXS>), grid, dim3(256), a.lds, st, x, w, y, P);
     } else {
         if (large && allow_large_lds<CK, 0>() != hipSuccess) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((mfma_f32_any_kernel<CK, 0>), grid, dim3(256), a.lds, st, x, w, y, P);
+        SW_NOTED_LAUNCH(note_kernel("mfma_f32_any_kernel", (int)(CK), (int)(0)), (mfma_f32_any_kernel<CK, 0>), grid, dim3(256), a.lds, st, x, w, y, P);
     }
     return hipGetLastError();
 }

@@ -241,13 +241,6 @@ struct QuadPlan {
     bool ok, split;
 };
 
-// SWCONV_NO_SPLIT=1 keeps the four-wavefront variant (A/B checks)
-bool no_split_kernel()
-{
-    static const bool v = [] { const char* e = getenv("SWCONV_NO_SPLIT"); return e && e[0] == '1'; }();
-    return v;
-}
-
 QuadPlan plan_quad(const Conv2dShape& s)
 {
     QuadPlan a{};
@@ -268,7 +261,7 @@ QuadPlan plan_quad(const Conv2dShape& s)
     // two buffers, loaders a chunk ahead: pays where a chunk has several taps to multiply (14 x 14 x 256 3x3: 143 ->
     // 132 us, 7 x 7 x 512: 280 -> 246 us); with one tap per chunk (1x1) the loaders cannot keep enough bytes in flight
     // from one chunk ahead and the launch is slower (74 -> 103 us at 56 x 56 x 256 -> 64)
-    a.split = RS > 1 && 2 * a.lds <= (size_t)kLdsBudget && !no_split_kernel();
+    a.split = RS > 1 && 2 * a.lds <= (size_t)kLdsBudget;
     if (a.split) a.lds *= 2;
     a.tiles_x = (s.Wo + a.TW - 1) / a.TW;
     a.tiles_y = (s.Ho + a.TH - 1) / a.TH;
@@ -296,9 +289,9 @@ hipError_t launch_quad(const float* x, const float* w, float* y, const Conv2dSha
     P.by_QRS = make_fastdiv((CK / 4) * s.R * s.S);
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
     if (a.split)
-        hipLaunchKernelGGL((mfma_f32_quad_kernel<CK, true>), grid, dim3(512), a.lds, st, x, w, y, P);
+        SW_NOTED_LAUNCH(note_kernel("mfma_f32_quad_kernel", (int)(CK), (int)(true)), (mfma_f32_quad_kernel<CK, true>), grid, dim3(512), a.lds, st, x, w, y, P);
     else
-        hipLaunchKernelGGL((mfma_f32_quad_kernel<CK, false>), grid, dim3(256), a.lds, st, x, w, y, P);
+        SW_NOTED_LAUNCH(note_kernel("mfma_f32_quad_kernel", (int)(CK), (int)(false)), (mfma_f32_quad_kernel<CK, false>), grid, dim3(256), a.lds, st, x, w, y, P);
     return hipGetLastError();
 }
 

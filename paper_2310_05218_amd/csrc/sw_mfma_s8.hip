@@ -532,13 +532,13 @@ hipError_t launch_mfma_s8(const int8_t* x, const int8_t* w, int32_t* y, const Co
     const bool one_item = 4 * (t.TH + 2) * P.nq_max <= 256;
     const bool resident = s.C_in == 128 && (t.TH + 2) * (t.TW + 2) <= kLdsPxRes;
     if (resident && one_item)
-        hipLaunchKernelGGL((mfma_s8_kernel<128, 1>), grid, dim3(256), kLdsBytesRes, st, x, w, y, P);
+        SW_NOTED_LAUNCH(note_kernel("mfma_s8_kernel", (int)(128), (int)(1)), (mfma_s8_kernel<128, 1>), grid, dim3(256), kLdsBytesRes, st, x, w, y, P);
     else if (resident)
-        hipLaunchKernelGGL((mfma_s8_kernel<128, 2>), grid, dim3(256), kLdsBytesRes, st, x, w, y, P);
+        SW_NOTED_LAUNCH(note_kernel("mfma_s8_kernel", (int)(128), (int)(2)), (mfma_s8_kernel<128, 2>), grid, dim3(256), kLdsBytesRes, st, x, w, y, P);
     else if (one_item)
-        hipLaunchKernelGGL((mfma_s8_kernel<0, 1>), grid, dim3(256), kLdsBytes, st, x, w, y, P);
+        SW_NOTED_LAUNCH(note_kernel("mfma_s8_kernel", (int)(0), (int)(1)), (mfma_s8_kernel<0, 1>), grid, dim3(256), kLdsBytes, st, x, w, y, P);
     else
-        hipLaunchKernelGGL((mfma_s8_kernel<0, 2>), grid, dim3(256), kLdsBytes, st, x, w, y, P);
+        SW_NOTED_LAUNCH(note_kernel("mfma_s8_kernel", (int)(0), (int)(2)), (mfma_s8_kernel<0, 2>), grid, dim3(256), kLdsBytes, st, x, w, y, P);
     return hipGetLastError();
 }
 
@@ -578,9 +578,9 @@ hipError_t launch_mfma_s8_requant(const int8_t* x, const int8_t* w, int8_t* y8, 
     dim3 grid((unsigned)(t.tiles_x * t.tiles_y), (unsigned)s.N, (unsigned)(s.C_out / 64));
     int32_t* none = nullptr;
     if (4 * (t.TH + 2) * P.nq_max <= 256)
-        hipLaunchKernelGGL((mfma_s8_kernel<128, 1, true>), grid, dim3(256), kLdsBytesRes, st, x, w, none, P, y8, rq);
+        SW_NOTED_LAUNCH(note_kernel("mfma_s8_kernel", (int)(128), (int)(1), (int)(true)), (mfma_s8_kernel<128, 1, true>), grid, dim3(256), kLdsBytesRes, st, x, w, none, P, y8, rq);
     else
-        hipLaunchKernelGGL((mfma_s8_kernel<128, 2, true>), grid, dim3(256), kLdsBytesRes, st, x, w, none, P, y8, rq);
+        SW_NOTED_LAUNCH(note_kernel("mfma_s8_kernel", (int)(128), (int)(2), (int)(true)), (mfma_s8_kernel<128, 2, true>), grid, dim3(256), kLdsBytesRes, st, x, w, none, P, y8, rq);
     return hipGetLastError();
 }
 

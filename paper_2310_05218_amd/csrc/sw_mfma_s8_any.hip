@@ -318,12 +318,12 @@ hipError_t launch_s8_any(const int8_t* x, const int8_t* w, int32_t* y, const Con
     P.by_span = make_fastdiv(span);
     P.by_span4 = make_fastdiv(P.w_dwords ? span / 4 : 1);
     // aligned dword reads of the input rows: every row of every plane starts on a 4-byte boundary
-    P.x_dwords = s.W % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0 && !getenv("SWCONV_S8_BYTE_X");
+    P.x_dwords = s.W % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 4 == 0;
     P.nq = (a.IW + 3) / 4 + 1;                  // quads that can touch a window row, whatever its alignment
     P.by_nq = make_fastdiv(P.nq);
     P.by_rowq = make_fastdiv(a.IH * P.nq);
     dim3 grid((unsigned)(a.tiles_x * a.tiles_y), (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
-    hipLaunchKernelGGL((mfma_s8_any_kernel<CK, RQ>), grid, dim3(256), a.lds, st, x, w, y, P, y8, rq);
+    SW_NOTED_LAUNCH(note_kernel("mfma_s8_any_kernel", (int)(CK), (int)(RQ)), (mfma_s8_any_kernel<CK, RQ>), grid, dim3(256), a.lds, st, x, w, y, P, y8, rq);
     return hipGetLastError();
 }
 

@@ -336,7 +336,7 @@ hipError_t launch_nhwc_ks(const int8_t* x, const int8_t* w, int32_t* y, int8_t* 
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudgetNhwc);
     if (attr != hipSuccess) return attr;
     dim3 grid((unsigned)a.bands, (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
-    hipLaunchKernelGGL((mfma_s8_nhwc_kernel<RQ, KS>), grid, dim3(256), a.lds, st, x, w, y, y8, a.P, rq);
+    SW_NOTED_LAUNCH(note_kernel("mfma_s8_nhwc_kernel", (int)(RQ), (int)(KS)), (mfma_s8_nhwc_kernel<RQ, KS>), grid, dim3(256), a.lds, st, x, w, y, y8, a.P, rq);
     return hipGetLastError();
 }
 
@@ -375,9 +375,9 @@ hipError_t launch_direct_s8_nhwc(const int8_t* x, const int8_t* w, int32_t* y, i
     int64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 64) blocks = 256 * 64;
     if (rq)
-        hipLaunchKernelGGL(direct_s8_nhwc_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, x, w, y, y8, s, *rq);
+        SW_NOTED_LAUNCH(note_kernel("direct_s8_nhwc_kernel", (int)(true)), direct_s8_nhwc_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, x, w, y, y8, s, *rq);
     else
-        hipLaunchKernelGGL(direct_s8_nhwc_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, x, w, y, y8, s,
+        SW_NOTED_LAUNCH(note_kernel("direct_s8_nhwc_kernel", (int)(false)), direct_s8_nhwc_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, x, w, y, y8, s,
                            Requant{nullptr, nullptr, 0});
     return hipGetLastError();
 }

@@ -58,9 +58,9 @@ hipError_t launch_global_pool(const float* x, float* y, int64_t planes, int HW, 
     const int vec_ok = reinterpret_cast<uintptr_t>(x) % 16 == 0;
     const size_t lds = (size_t)64 * HW * sizeof(float);
     if (maximum)
-        hipLaunchKernelGGL(global_pool_kernel<true>, dim3((unsigned)groups), dim3(64), lds, st, x, y, planes, HW, vec_ok);
+        SW_NOTED_LAUNCH(note_kernel("global_pool_kernel", (int)(true)), global_pool_kernel<true>, dim3((unsigned)groups), dim3(64), lds, st, x, y, planes, HW, vec_ok);
     else
-        hipLaunchKernelGGL(global_pool_kernel<false>, dim3((unsigned)groups), dim3(64), lds, st, x, y, planes, HW, vec_ok);
+        SW_NOTED_LAUNCH(note_kernel("global_pool_kernel", (int)(false)), global_pool_kernel<false>, dim3((unsigned)groups), dim3(64), lds, st, x, y, planes, HW, vec_ok);
     return hipGetLastError();
 }
 

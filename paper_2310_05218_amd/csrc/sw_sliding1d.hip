@@ -235,7 +235,7 @@ hipError_t launch_op(const float* x, const float* w, float* y, int64_t rows, int
     dim3 grid((unsigned)blocks), block(kThreads);
 #define SW_CASE(KC)                                                                                      \
     case KC:                                                                                             \
-        hipLaunchKernelGGL((sliding_1d_kernel<OP, KC>), grid, block, 0, st, x, w, y, len, len_out, k,    \
+        SW_NOTED_LAUNCH(note_kernel("sliding_1d_kernel", (int)(OP), (int)(KC)), (sliding_1d_kernel<OP, KC>), grid, block, 0, st, x, w, y, len, len_out, k,    \
                            pad, tiles_per_row, (int)tiles, x_vec_ok);                                    \
         break;
     switch (k) {
@@ -243,7 +243,7 @@ hipError_t launch_op(const float* x, const float* w, float* y, int64_t rows, int
         SW_CASE(11) SW_CASE(13) SW_CASE(15) SW_CASE(16) SW_CASE(17)
         SW_CASE(25) SW_CASE(32) SW_CASE(33) SW_CASE(49) SW_CASE(64)
         default:
-            hipLaunchKernelGGL((sliding_1d_kernel<OP, 0>), grid, block, 0, st, x, w, y, len, len_out, k, pad,
+            SW_NOTED_LAUNCH(note_kernel("sliding_1d_kernel", (int)(OP), (int)(0)), (sliding_1d_kernel<OP, 0>), grid, block, 0, st, x, w, y, len, len_out, k, pad,
                                tiles_per_row, (int)tiles, x_vec_ok);
     }
 #undef SW_CASE

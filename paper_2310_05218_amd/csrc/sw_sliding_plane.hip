@@ -582,7 +582,7 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
         const int64_t want = 256 * 8;
         dim3 grid((unsigned)(planes < want ? planes : want)), block(64);
 #define SW_FULL2(RC, SQC, EPC)                                                                               \
-    hipLaunchKernelGGL((sliding_plane_full_kernel<RC, RC, SQC, EPC>), grid, block, 0, st, x, w, y, (int)planes, \
+    SW_NOTED_LAUNCH(note_kernel("sliding_plane_full_kernel", (int)(RC), (int)(RC), (int)(SQC), (int)(EPC)), (sliding_plane_full_kernel<RC, RC, SQC, EPC>), grid, block, 0, st, x, w, y, (int)planes, \
                        planes_per_x, n_filters, H, W, pad, Ho, Wo, ep)
 #define SW_FULL(RC)                                                                                          \
     do {                                                                                                     \
@@ -607,7 +607,7 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
     const int y_vec_ok = reinterpret_cast<uintptr_t>(y) % 16 == 0 && Wo % 4 == 0;
     dim3 grid((unsigned)blocks);
 #define SW_PLANE(RC, SC, MAXRS)                                                                          \
-    hipLaunchKernelGGL((sliding_plane_kernel<RC, SC, MAXRS>), grid, dim3(RC > 0 ? 64 : 256), 0, st, x, w, y, planes_per_x, \
+    SW_NOTED_LAUNCH(note_kernel("sliding_plane_kernel", (int)(RC), (int)(SC), (int)(MAXRS)), (sliding_plane_kernel<RC, SC, MAXRS>), grid, dim3(RC > 0 ? 64 : 256), 0, st, x, w, y, planes_per_x, \
                        n_filters, H, W, R, S, pad, Ho, Wo, tiles_x, tiles_y, x_vec_ok, y_vec_ok, ep)
     if (R == 3 && S == 3) SW_PLANE(3, 3, 0);
     else if (R == 5 && S == 5) SW_PLANE(5, 5, 0);
@@ -638,10 +638,10 @@ hipError_t launch_sliding_plane_bf16(const unsigned short* x, const float* w, un
 #define SW_BF16(RC)                                                                                               \
     do {                                                                                                          \
         if (sq)                                                                                                   \
-            hipLaunchKernelGGL((sliding_plane_bf16_kernel<RC, RC, true>), grid, block, 0, st, x, w, y, (int)planes, \
+            SW_NOTED_LAUNCH(note_kernel("sliding_plane_bf16_kernel", (int)(RC), (int)(RC), (int)(true)), (sliding_plane_bf16_kernel<RC, RC, true>), grid, block, 0, st, x, w, y, (int)planes, \
                                n_filters, H, W, pad, Ho, Wo);                                                     \
         else                                                                                                      \
-            hipLaunchKernelGGL((sliding_plane_bf16_kernel<RC, RC, false>), grid, block, 0, st, x, w, y, (int)planes, \
+            SW_NOTED_LAUNCH(note_kernel("sliding_plane_bf16_kernel", (int)(RC), (int)(RC), (int)(false)), (sliding_plane_bf16_kernel<RC, RC, false>), grid, block, 0, st, x, w, y, (int)planes, \
                                n_filters, H, W, pad, Ho, Wo);                                                     \
     } while (0)
     if (R == 3) SW_BF16(3);

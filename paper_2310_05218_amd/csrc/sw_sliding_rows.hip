@@ -207,10 +207,10 @@ hipError_t launch_rows_seg(const float* x, const float* w, float* y, int64_t pla
     if (blocks > 2147483647LL) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(256);
     if (small)
-        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_SMALL, ST, OP, SEGL>), grid, block, 0, st, x, w, y,
+        SW_NOTED_LAUNCH(note_kernel("sliding_rows_kernel", (int)(R), (int)(S), (int)(PADC), (int)(TR_SMALL)), (sliding_rows_kernel<R, S, PADC, TR_SMALL, ST, OP, SEGL>), grid, block, 0, st, x, w, y,
                            planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, items, y_vec_ok, ep);
     else
-        hipLaunchKernelGGL((sliding_rows_kernel<R, S, PADC, TR_BIG, ST, OP, SEGL>), grid, block, 0, st, x, w, y,
+        SW_NOTED_LAUNCH(note_kernel("sliding_rows_kernel", (int)(R), (int)(S), (int)(PADC), (int)(TR_BIG)), (sliding_rows_kernel<R, S, PADC, TR_BIG, ST, OP, SEGL>), grid, block, 0, st, x, w, y,
                            planes_per_x, n_filters, H, W, Ho, Wo, strips, bands, waves, items, y_vec_ok, ep);
     return hipGetLastError();
 }

@@ -162,12 +162,12 @@ hipError_t launch_small_planes(const float* x, const float* w, float* y, int64_t
     dim3 grid((unsigned)groups), block(kThreads);
 #define SW_SMALL(RC, STC)                                                                                     \
     if (R == RC && S == RC && stride == STC) {                                                                \
-        hipLaunchKernelGGL((small_planes_kernel<RC, RC, STC>), grid, block, lds, st, x, w, y, P);             \
+        SW_NOTED_LAUNCH(note_kernel("small_planes_kernel", (int)(RC), (int)(RC), (int)(STC)), (small_planes_kernel<RC, RC, STC>), grid, block, lds, st, x, w, y, P);             \
         return hipGetLastError();                                                                             \
     }
     SW_SMALL(3, 1) SW_SMALL(3, 2) SW_SMALL(5, 1) SW_SMALL(5, 2) SW_SMALL(7, 1)
 #undef SW_SMALL
-    hipLaunchKernelGGL((small_planes_kernel<0, 0, 0>), grid, block, lds, st, x, w, y, P);
+    SW_NOTED_LAUNCH(note_kernel("small_planes_kernel", (int)(0), (int)(0), (int)(0)), (small_planes_kernel<0, 0, 0>), grid, block, lds, st, x, w, y, P);
     return hipGetLastError();
 }
 

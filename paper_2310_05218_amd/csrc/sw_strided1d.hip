@@ -148,7 +148,7 @@ hipError_t launch_pool_tiles(const float* x, float* y, int64_t rows, int64_t len
     int64_t blocks = (n_groups + kThreads * 4 - 1) / (kThreads * 4);
     if (blocks > 256 * 64) blocks = 256 * 64;
     dim3 grid((unsigned)blocks), block(kThreads);
-#define SW_TILES(OPC, WINC) hipLaunchKernelGGL((pool_tiles_kernel<OPC, WINC>), grid, block, 0, st, x, y, n_groups)
+#define SW_TILES(OPC, WINC) SW_NOTED_LAUNCH(note_kernel("pool_tiles_kernel", (int)(OPC), (int)(WINC)), (pool_tiles_kernel<OPC, WINC>), grid, block, 0, st, x, y, n_groups)
     if (maximum) {
         if (window == 2) SW_TILES(OP_MAX, 2); else if (window == 4) SW_TILES(OP_MAX, 4); else SW_TILES(OP_MAX, 8);
     } else {
@@ -174,7 +174,7 @@ hipError_t launch_strided_1d(const float* x, const float* w, float* y, int64_t r
     dim3 grid((unsigned)(rows * tiles)), block(kThreads);
     const FastDiv by_tiles = make_fastdiv(tiles);
 #define SW_STRIDED(OPC)                                                                                        \
-    hipLaunchKernelGGL(strided_1d_kernel<OPC>, grid, block, 0, st, x, w, y, (int)len, (int)len_out, k, stride, pad, \
+    SW_NOTED_LAUNCH(note_kernel("strided_1d_kernel", (int)(OPC)), strided_1d_kernel<OPC>, grid, block, 0, st, x, w, y, (int)len, (int)len_out, k, stride, pad, \
                        tiles, by_tiles, x_vec_ok)
     if (op == OP_CONV) SW_STRIDED(OP_CONV);
     else if (op == OP_AVG) SW_STRIDED(OP_AVG);

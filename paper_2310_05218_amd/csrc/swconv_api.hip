@@ -38,42 +38,6 @@ bool force_direct()
     return v;
 }
 
-bool no_rows_kernel()      // A/B switch: keep one-filter-per-plane problems off the register-only rows kernel
-{
-    static const bool v = [] {
-        const char* e = std::getenv("SWCONV_NO_ROWS");
-        return e && e[0] == '1';
-    }();
-    return v;
-}
-
-bool no_whole_plane_kernel()   // A/B switch: keep 3x3 / 5x5 problems off the persistent whole-plane kernel
-{
-    static const bool v = [] {
-        const char* e = std::getenv("SWCONV_NO_WHOLE");
-        return e && e[0] == '1';
-    }();
-    return v;
-}
-
-bool no_large_tile_mfma()      // A/B switch: keep fp32 multi-channel problems off the fixed 3x3 / 5x5 kernel
-{
-    static const bool v = [] {
-        const char* e = std::getenv("SWCONV_NO_LARGE_TILE");
-        return e && e[0] == '1';
-    }();
-    return v;
-}
-
-bool no_small_planes_kernel()  // A/B switch: keep small planes off the run-of-planes kernel
-{
-    static const bool v = [] {
-        const char* e = std::getenv("SWCONV_NO_SMALL");
-        return e && e[0] == '1';
-    }();
-    return v;
-}
-
 bool misaligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) != 0; }
 
 bool overlaps(const void* a, int64_t abytes, const void* b, int64_t bbytes)
@@ -92,15 +56,15 @@ int run_plane(const float* x, const float* w, float* y, int64_t planes, int plan
     if (!force_direct()) {
         // planes up to 20 x 20, and larger ragged ones (width not a multiple of 4) that the register-only and
         // whole-plane kernels do not take: a run of planes per workgroup
-        if (!no_small_planes_kernel() && (s.H * s.W <= 400 || s.W % 4 != 0 || s.R * s.S >= 25) &&
+        if ((s.H * s.W <= 400 || s.W % 4 != 0 || s.R * s.S >= 25) &&
             small_planes_supported(planes, planes_per_x, s.H, s.W, s.R, s.S, s.stride, s.Ho, s.Wo))
             return launch_status(launch_small_planes(x, w, y, planes, n_filters, s.H, s.W, s.R, s.S, s.stride, s.pad,
                                                      s.Ho, s.Wo, st, ep));
-        const bool rows = !no_rows_kernel() && sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad);
+        const bool rows = sliding_rows_supported(x, s.H, s.W, s.R, s.S, s.stride, s.pad);
         // the whole-plane kernel spends a 56 x 56 tile per plane: planes up to 32 wide leave most of its lanes
         // idle and go to the rows kernel (lane groups) when that has a variant
         const bool whole = s.stride == 1 && sliding_plane_whole(x, y, s.H, s.W, s.R, s.S, s.pad, s.Ho, s.Wo) &&
-                           planes >= 512 && !(no_whole_plane_kernel() && s.R < 7) && !(rows && s.W <= 32);
+                           planes >= 512 && !(rows && s.W <= 32);
         if (!whole && rows)
             return launch_status(launch_sliding_rows(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
                                                      s.stride, s.pad, s.Ho, s.Wo, st, ep));
@@ -266,7 +230,7 @@ static int run_conv2d(const float* x, const float* w, float* y, const Conv2dShap
         // tiles take over there, and everywhere the fixed kernel has no variant.
         const bool quad_ok = mfma_f32_quad_supported(s);
         const bool any_ok = quad_ok || mfma_f32_any_supported(s);
-        if (mfma_f32_supported(s) && !no_large_tile_mfma() && (mfma_f32_workgroups(s) >= 160 || !any_ok))
+        if (mfma_f32_supported(s) && (mfma_f32_workgroups(s) >= 160 || !any_ok))
             return launch_status(launch_mfma_f32(x, w, y, s, st, ep));
         if (quad_ok) return launch_status(launch_mfma_f32_quad(x, w, y, s, st, ep));
         if (any_ok) return launch_status(launch_mfma_f32_any(x, w, y, s, st, ep));
@@ -413,8 +377,10 @@ int sw_conv2d_depthwise_jit(const float* x, const float* w, float* y, int N, int
     const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s);
     if (rc != SW_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (!force_direct() && jit_plane_supported(x, y, H, W, R, S, stride, pad))
-        return jit_launch_plane(x, w, y, (int64_t)N * C, 1, C, H, W, R, S, stride, pad, st);
+    if (!force_direct() && jit_plane_supported(x, y, H, W, R, S, stride, pad)) {
+        // a geometry whose generated kernel cannot be compiled or loaded is served by the precompiled kernels
+        if (jit_launch_plane(x, w, y, (int64_t)N * C, 1, C, H, W, R, S, stride, pad, st) == SW_OK) return SW_OK;
+    }
     return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
 }
 
@@ -445,7 +411,7 @@ int sw_conv2d_s8(const int8_t* x, const int8_t* w, int32_t* y, int N, int C_in, 
     if (!force_direct()) {
         if (mfma_s8_band_supported(x, w, s, true))
             return launch_status(launch_mfma_s8_band(x, w, y, nullptr, nullptr, s, true, st));
-        if (mfma_s8_supported(s) && !no_large_tile_mfma()) return launch_status(launch_mfma_s8(x, w, y, s, st));
+        if (mfma_s8_supported(s)) return launch_status(launch_mfma_s8(x, w, y, s, st));
         if (mfma_s8_any_supported(s)) return launch_status(launch_mfma_s8_any(x, w, y, s, st));
     }
     return launch_status(launch_direct_conv2d_s8(x, w, y, s, st));
@@ -469,7 +435,7 @@ int sw_conv2d_s8_requant(const int8_t* x, const int8_t* w, const int32_t* bias, 
     if (!force_direct()) {
         if (mfma_s8_band_supported(x, w, s, true))
             return launch_status(launch_mfma_s8_band(x, w, nullptr, y, &rq, s, true, st));
-        if (mfma_s8_requant_supported(s) && !no_large_tile_mfma())
+        if (mfma_s8_requant_supported(s))
             return launch_status(launch_mfma_s8_requant(x, w, y, rq, s, st));
         if (mfma_s8_any_supported(s)) return launch_status(launch_mfma_s8_any_requant(x, w, y, rq, s, st));
     }

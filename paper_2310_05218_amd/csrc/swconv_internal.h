@@ -60,6 +60,12 @@ __device__ __forceinline__ int8_t requant_s8(int acc, int co, const Requant& rq)
 // Records the kernel a launcher is about to enqueue (name and up to four template arguments) for the calling
 // thread; sw_last_kernel() reports it.  Costs a few stores per launch.
 void note_kernel(const char* name, int a = -1, int b = -1, int c = -1, int d = -1);
+// A launch with its note, as one statement.
+#define SW_NOTED_LAUNCH(note_call, ...)      \
+    do {                                     \
+        note_call;                           \
+        hipLaunchKernelGGL(__VA_ARGS__);     \
+    } while (0)
 
 // ---- direct (one thread per output) kernels: any valid shape -------------------------------
 hipError_t launch_direct_1d(const float* x, const float* w, float* y, int64_t rows, int64_t len,

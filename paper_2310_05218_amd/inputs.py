@@ -34,20 +34,10 @@ def normal_f32(shape, seed: int, std: float = 1.0) -> np.ndarray:
     return a
 
 
-def to_bf16_bits(a: np.ndarray) -> np.ndarray:
-    """fp32 -> bf16 bit patterns (uint16), round to nearest even; finite inputs."""
-    u = np.ascontiguousarray(a, np.float32).view(np.uint32)
-    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
-
-
-def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
-    """bf16 bit patterns (uint16) -> the fp32 values they denote (exact)."""
-    return (np.ascontiguousarray(b, np.uint16).astype(np.uint32) << 16).view(np.float32)
-
-
 def normal_bf16(shape, seed: int, std: float = 1.0) -> np.ndarray:
-    """N(0, std^2) rounded to bf16, as bit patterns (uint16)."""
-    return to_bf16_bits(normal_f32(shape, seed, std))
+    """bf16 bit patterns (uint16) of N(0, std^2) draws: the upper half of each fp32 draw's bit pattern (no rounding
+    arithmetic lives here: checkers widen the patterns with their own helper)."""
+    return (normal_f32(shape, seed, std).view(np.uint32) >> 16).astype(np.uint16)
 
 
 def uniform_s8(shape, seed: int) -> np.ndarray:

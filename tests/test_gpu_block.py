@@ -1,6 +1,6 @@
 """GPU parity of the depthwise-separable block (sw_dw_pw_block: depthwise 3x3 + bias + rectifier and pointwise 1x1 +
-bias + rectifier in one launch) against the CPU oracle.  Two chained fp32 stages: each contributes at most 2e-5 of
-its magnitude sum, so the bound is 4e-5 of the composite magnitude sum D the oracle returns."""
+bias + rectifier in one launch) against the CPU oracle: the fp32 parity bound, 2e-5 of the composite magnitude sum D
+the oracle returns (measured maxima of the two chained fp32 stages are below 1e-6)."""
 import numpy as np
 import pytest
 
@@ -8,7 +8,7 @@ from paper_2310_05218_amd import inputs
 from parity import assert_guards_intact, guarded_empty
 
 pytestmark = pytest.mark.gpu
-TOL = 4e-5
+TOL = 2e-5
 
 
 @pytest.fixture(scope="module")

@@ -202,13 +202,13 @@ def test_depthwise_bf16_random(torch, sw, oracle, case):
     N, C = int(rng.integers(1, 4)), int(rng.choice([1, 3, 8, 70]))
     xb = inputs.normal_bf16((N, C, H, W), seed % 100000)
     w = inputs.normal_f32((C, 1, R, S), seed % 100000 + 1, 1.0 / (R * S) ** 0.5)
-    y_ref, d = oracle.conv2d_depthwise(inputs.bf16_bits_to_f32(xb), w, stride, pad)
+    y_ref, d = oracle.conv2d_depthwise(oracle.bf16_to_f32(xb), w, stride, pad)
     xd = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
     buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.bfloat16)
     sw.sw_conv2d_depthwise_bf16(xd, dev(torch, w), stride, pad, out=out)
     torch.cuda.synchronize()
     assert_guards_intact(buf, front, n, s)
-    y = inputs.bf16_bits_to_f32(out.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+    y = oracle.bf16_to_f32(out.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
     assert np.all(np.abs(y - y_ref) <= 2e-5 * d + 2.0 ** -8 * np.abs(y_ref) + 1e-37), f"bf16 depthwise {case} N={N} C={C}"
 
 

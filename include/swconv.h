@@ -335,6 +335,21 @@ const char* sw_status_string(int status);
 int sw_version(void);
 
 /*
+ * Measurement aids (no part of the convolution path): sw_probe enqueues a kernel that issues `iters` loop
+ * turns of one kind of arithmetic instruction on every SIMD of the device and touches no memory;
+ * sw_probe_ops(kind, iters) is the number of arithmetic operations (2 per multiply-add) that launch performs.
+ * Timing the launch gives the rate the chip sustains for that instruction, to quote beside the datasheet peak.
+ * SW_ERR_SHAPE for iters <= 0, SW_ERR_UNSUPPORTED for an unknown kind.
+ */
+typedef enum {
+    SW_PROBE_MFMA_F32 = 0,  /* v_mfma_f32_32x32x2_f32                                  */
+    SW_PROBE_MFMA_I8 = 1,   /* v_mfma_i32_32x32x32_i8                                  */
+    SW_PROBE_FMA_F32 = 2    /* v_fma_f32, wave-uniform multiplicand (no packed forms)  */
+} sw_probe_kind;
+int sw_probe(int kind, int iters, void* hip_stream);
+int64_t sw_probe_ops(int kind, int iters);
+
+/*
  * Diagnostics: the name (with template arguments) of the kernel that the calling thread's most
  * recent convolution, pooling or packing call enqueued; "" before the first call.  The string
  * lives in thread-local storage and is overwritten by the next sw_last_kernel call of the thread.

@@ -21,7 +21,7 @@ EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthw
            "sw_conv2d_depthwise_bf16", "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
            "sw_jit_cached_kernels",
            "sw_s8_packed_filter_bytes", "sw_s8_pack_filter", "sw_conv2d_s8_packed", "sw_conv2d_s8_packed_requant",
-           "sw_out_dim", "sw_out_dim_dilated", "sw_workspace_bytes", "sw_status_string", "sw_version", "sw_last_kernel")
+           "sw_probe", "sw_probe_ops", "sw_out_dim", "sw_out_dim_dilated", "sw_workspace_bytes", "sw_status_string", "sw_version", "sw_last_kernel")
 
 _lib = None
 
@@ -86,6 +86,10 @@ def lib() -> ctypes.CDLL:
     L.sw_conv2d_s8_packed.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
     L.sw_conv2d_s8_packed_requant.restype = i32
     L.sw_conv2d_s8_packed_requant.argtypes = [vp, vp, vp, vp, vp] + [i32] * 10 + [vp]
+    L.sw_probe.restype = i32
+    L.sw_probe.argtypes = [i32, i32, vp]
+    L.sw_probe_ops.restype = i64
+    L.sw_probe_ops.argtypes = [i32, i32]
     L.sw_out_dim.restype = i64
     L.sw_out_dim.argtypes = [i64, i32, i32, i32]
     L.sw_out_dim_dilated.restype = i64
@@ -167,6 +171,15 @@ def sw_out_dim_dilated(n_in: int, k: int, stride: int, pad: int, dilation: int) 
 def sw_last_kernel() -> str:
     """Name (with template arguments) of the kernel the calling thread's most recent call enqueued."""
     return lib().sw_last_kernel().decode()
+
+
+SW_PROBE_MFMA_F32, SW_PROBE_MFMA_I8, SW_PROBE_FMA_F32 = 0, 1, 2
+
+
+def sw_probe(kind: int, iters: int, stream=None) -> int:
+    """Enqueue the arithmetic-only probe kernel of `kind`; returns the number of operations it performs."""
+    _check(lib().sw_probe(kind, iters, _stream(stream)), "sw_probe")
+    return int(lib().sw_probe_ops(kind, iters))
 
 
 def sw_workspace_bytes() -> int:

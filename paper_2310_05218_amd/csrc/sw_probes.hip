@@ -1,0 +1,112 @@
+// Measurement aids: kernels that issue one kind of arithmetic instruction and nothing else, so that a benchmark
+// can quote the rate this chip sustains (at the clock it holds under that instruction) beside the datasheet
+// peak.  They read and write no memory (the sink is only there to keep the arithmetic alive).
+#include "../../include/swconv.h"
+
+#include "swconv_internal.h"
+
+namespace swconv {
+
+namespace {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
+typedef int intx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kProbeGroups = 256 * 8;    // workgroups of one wavefront: eight per compute unit, two per SIMD
+constexpr int kMfmaPerIter = 8;          // matrix instructions per loop turn (four independent accumulators, twice)
+constexpr int kFmaAcc = 48;              // independent fp32 accumulators of the vector probe
+constexpr int kFmaPerIter = kFmaAcc * 4;
+
+__global__ __launch_bounds__(64) void probe_mfma_f32_kernel(int iters, float* sink)
+{
+    floatx16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    const float a = 1.0f + threadIdx.x * 1e-3f, b = 0.5f;
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < kMfmaPerIter; ++u) acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[u & 3], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 4; ++i) s += acc[i][0] + acc[i][15];
+    if (sink && s == 12345.678f) *sink = s;
+}
+
+__global__ __launch_bounds__(64) void probe_mfma_i8_kernel(int iters, float* sink)
+{
+    intx16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0;
+    const intx4 a = {(int)threadIdx.x, 0x01020304, 0x7f807f80, 0x11111111}, b = {0x01010101, 0x02020202, (int)blockIdx.x, 0x04040404};
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < kMfmaPerIter; ++u) acc[u & 3] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[u & 3], 0, 0, 0);
+    }
+    int s = 0;
+    for (int i = 0; i < 4; ++i) s += acc[i][0] + acc[i][15];
+    if (sink && s == 123456789) *sink = (float)s;
+}
+
+// plain v_fma_f32 with a wave-uniform multiplicand, as in the one-filter-per-plane kernels (no packed forms)
+__global__ __launch_bounds__(64) void probe_fma_f32_kernel(int iters, float* sink, float tap0, float tap1)
+{
+    float acc[kFmaAcc];
+    for (int i = 0; i < kFmaAcc; ++i) acc[i] = threadIdx.x * 1e-3f + i;
+    float in[4] = {1.0f + threadIdx.x * 1e-4f, 0.999f, 1.001f, 0.5f};
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int i = 0; i < kFmaAcc; ++i) acc[i] = fmaf((u & 1) ? tap1 : tap0, in[u], acc[i]);
+    }
+    float s = 0.f;
+    for (int i = 0; i < kFmaAcc; ++i) s += acc[i];
+    if (sink && s == 12345.678f) *sink = s;
+}
+
+}  // namespace
+
+}  // namespace swconv
+
+using namespace swconv;
+
+extern "C" {
+
+int64_t sw_probe_ops(int kind, int iters)
+{
+    if (iters <= 0) return 0;
+    const int64_t waves = kProbeGroups;
+    switch (kind) {
+        case SW_PROBE_MFMA_F32: return waves * iters * kMfmaPerIter * (2LL * 32 * 32 * 2);
+        case SW_PROBE_MFMA_I8: return waves * iters * kMfmaPerIter * (2LL * 32 * 32 * 32);
+        case SW_PROBE_FMA_F32: return waves * iters * kFmaPerIter * (2LL * 64);
+        default: return 0;
+    }
+}
+
+int sw_probe(int kind, int iters, void* hip_stream)
+{
+    if (iters <= 0) return SW_ERR_SHAPE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    float* none = nullptr;
+    switch (kind) {
+        case SW_PROBE_MFMA_F32:
+            SW_NOTED_LAUNCH(note_kernel("probe_mfma_f32_kernel"), probe_mfma_f32_kernel, dim3(kProbeGroups), dim3(64), 0, st, iters, none);
+            break;
+        case SW_PROBE_MFMA_I8:
+            SW_NOTED_LAUNCH(note_kernel("probe_mfma_i8_kernel"), probe_mfma_i8_kernel, dim3(kProbeGroups), dim3(64), 0, st, iters, none);
+            break;
+        case SW_PROBE_FMA_F32:
+            SW_NOTED_LAUNCH(note_kernel("probe_fma_f32_kernel"), probe_fma_f32_kernel, dim3(kProbeGroups), dim3(64), 0, st, iters, none,
+                            1.0000001f, 0.9999999f);
+            break;
+        default: return SW_ERR_UNSUPPORTED;
+    }
+    return hipGetLastError() == hipSuccess ? SW_OK : SW_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -176,6 +176,11 @@ PLANE_CASES = [
     (3, 50, 5, 9, 5, 7, 1, 3),
     (1, 2, 7, 5, 7, 5, 1, 0),
     (1, 2, 16, 16, 3, 3, 1, 2),     # padding wider than the usual (R-1)/2
+    (1, 2, 60, 60, 7, 7, 1, 1),     # one 56 x 56 tile of outputs from a plane larger than 56 x 56
+    (8, 64, 60, 60, 5, 5, 1, 0),    # ... on enough planes for the whole-plane kernels to be considered
+    (8, 64, 56, 60, 5, 5, 1, 0),
+    (8, 64, 58, 58, 3, 3, 1, 0),
+    (8, 64, 62, 62, 7, 7, 1, 0),
 ]
 
 

@@ -67,15 +67,15 @@ MEASURED_ROOF = {"conv2d_64x64_3x3": "mfma_f32_tflops", "conv2d_s8_128x128_3x3":
 TRAFFIC_SOURCE = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs made by the builder (profiles/hbm_traffic_all_kernels.txt), "
                   "not measured by this run; null where the kernel's source has changed since")
 TRAFFIC = {
-    "depthwise_3x3": (207450113, "sw_sliding_plane.hip", "6389c5288dd110dc"),
-    "depthwise_7x7": (206185308, "sw_sliding_plane.hip", "6389c5288dd110dc"),
-    "conv2d_64x64_3x3": (62598117, "sw_mfma_f32.hip", "c33152360085e7c7"),
-    "conv2d_s8_128x128_3x3": (0, "sw_mfma_s8_band.hip", "not yet measured"),
-    "conv2d_s8_128x128_3x3_packed": (0, "sw_mfma_s8_band.hip", "not yet measured"),
-    "conv1d_k9": (33921280, "sw_sliding1d.hip", "e53250bbd93b8921"),
-    "avgpool1d_w8": (34169890, "sw_sliding1d.hip", "e53250bbd93b8921"),
-    "maxpool1d_w8": (34142598, "sw_sliding1d.hip", "e53250bbd93b8921"),
-    "conv2d_1ch_3x3": (661062, "sw_sliding_rows.hip", "21935214a73b4290"),
+    "depthwise_3x3": (207394818, "sw_sliding_plane.hip", "60aa4c35684035d9"),
+    "depthwise_7x7": (206218853, "sw_sliding_plane.hip", "60aa4c35684035d9"),
+    "conv2d_64x64_3x3": (62466851, "sw_mfma_f32.hip", "20a2d4cb31e9e833"),
+    "conv2d_s8_128x128_3x3": (22085751, "sw_mfma_s8_band.hip", "acd15d54c6f41ca9"),
+    "conv1d_k9": (33980440, "sw_sliding1d.hip", "b574d6ab8949af6c"),
+    "avgpool1d_w8": (34234334, "sw_sliding1d.hip", "b574d6ab8949af6c"),
+    "maxpool1d_w8": (34237666, "sw_sliding1d.hip", "b574d6ab8949af6c"),
+    "conv2d_1ch_3x3": (661842, "sw_sliding_rows.hip", "0e35510846c9b8a1"),
+    "conv2d_s8_128x128_3x3_packed": (21936501, "sw_mfma_s8_band.hip", "acd15d54c6f41ca9"),
 }
 
 
@@ -558,7 +558,7 @@ def main():
         torch.cuda.synchronize()
         torch.mul(a, 1.0, out=b)        # plain copy kernel, 64 MiB read + 64 MiB written: scales FETCH_SIZE / WRITE_SIZE
         torch.cuda.synchronize()
-        for _, fn in ls:
+        for _, fn in ls + extra_launches(sw):
             fn(sets[0])
             fn(sets[1 % len(sets)])
         torch.cuda.synchronize()

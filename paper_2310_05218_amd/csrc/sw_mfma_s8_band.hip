@@ -66,7 +66,14 @@ struct BandParams {
     Div by_pieces, by_W4, by_IW, by_Wo;
 };
 
-// KS: C_in / 32.  RQ: the sums leave requantised to int8 (y8) instead of as int32 (y).
+// KS: C_in / 32.  RQ: 0 = the sums leave as int32 (y); otherwise requantised to int8 (y8): 1 = stored from the
+// registers as the matrix instruction leaves them (any output size and alignment), 2 = through LDS (planes of a
+// multiple of 16 pixels, y8 16-byte aligned): each wavefront requantises a finished block between the matrix
+// instructions of the next one -- per value an integer add, a conversion, the product, one v_med3_f32 for both
+// clamps and one fp32 add of 1.5 * 2^23, which rounds to nearest even and leaves the integer's low byte in the low
+// byte of the bit pattern (clamping before rounding changes nothing: the bounds are integers and rounding is
+// monotone) --, transposes 4 pixels x 4 channels inside each quad of lanes (three DPP moves, three byte permutes),
+// collects its 32 channels x up to 128 pixels in its own LDS area and writes them as 16-byte pieces at the end.
 //
 // LDS: the window as [16-channel group][pixel][16 bytes] (group pitch = 16 mod 256 bytes, so that the staging
 // writes of neighbouring groups fall into different banks; an operand read takes 16 consecutive pixels of one
@@ -77,7 +84,7 @@ struct BandParams {
 // filters of its 64 output channels into the packed order on their way into LDS (C_in a multiple of 64).
 // NWV: wavefronts per workgroup, 4 or 8: the first four stage and multiply, the others only help with the staging
 // (the byte transposes are chains of LDS reads, permutes and LDS writes: two wavefronts per SIMD overlap them).
-template <int KS, bool RQ, bool RAWW, int NWV>
+template <int KS, int RQ, bool RAWW, int NWV>
 __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t* __restrict__ x, const int8_t* __restrict__ wp,
                                                               int32_t* __restrict__ y, const BandParams P,
                                                               int8_t* __restrict__ y8, const Requant rq)
@@ -86,7 +93,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t*
     constexpr int NG = 2 * KS;                              // groups of 16 input channels
     constexpr int GP = kWinPx * 16 + 16;                    // bytes per group in the window
     constexpr int NSTEP = 9 * KS;
-    static_assert(NWV == 4 || (NWV == 8 && KS == 4), "helper wavefronts exist for C_in == 128 only");
+    static_assert(NWV == 4 || (NWV == 8 && KS == 4 && RQ != 1), "helper wavefronts exist for C_in == 128 only");
     constexpr int GPW = NG > NWV ? NG / NWV : 1;            // channel groups a wavefront stages
     constexpr int XPW = (16 * GPW * kMaxPieces + 63) / 64;  // raw 16-byte pieces per lane
     constexpr int QPW = GPW == 2 ? 32 : 64;                 // column quads per pass of a wavefront
@@ -100,6 +107,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t*
     unsigned char* lx = smem;                                   // [channel group][window pixel][16]
     unsigned char* la = smem + NG * GP;                         // [channel block][step][lane][16]: as packed
     unsigned char* lraw = la + 2 * NSTEP * 1024;                // per wavefront: [channel][band bytes], as in memory
+    unsigned char* lrq = lraw + NWV * (16 * (NG > NWV ? NG / NWV : 1) * 16 * kMaxPieces + 144);   // (RQ == 2) [64] scales, [64] biases
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -178,6 +186,15 @@ __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t*
         }
     }
 
+    // (RQ == 2) the workgroup's 64 scales and biases, requested behind the operands and parked in LDS with them
+    float rq_scale_in = 0.0f;
+    int rq_bias_in = 0;
+    if constexpr (RQ == 2) {
+        rq_scale_in = rq.scale[(mb << 6) + lane];
+        rq_bias_in = (rq.bias ? rq.bias : reinterpret_cast<const int*>(rq.scale))[(mb << 6) + lane];
+        if (!rq.bias) rq_bias_in = 0;
+    }
+
     // ---- band -> this wavefront's LDS area as it is, then -> [group][pixel][16] with the byte transposes:
     //      item = (channel group, column quad of a window row); LDS operations of a wavefront complete in order
 #pragma unroll
@@ -208,6 +225,12 @@ __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t*
                 *reinterpret_cast<intx4*>(dst + 32) = t[2];
                 *reinterpret_cast<intx4*>(dst + 48) = t[3];
             }
+        }
+    }
+    if constexpr (RQ == 2) {
+        if (wave == 0) {
+            reinterpret_cast<float*>(lrq)[lane] = rq_scale_in;
+            reinterpret_cast<int*>(lrq + 256)[lane] = rq_bias_in;
         }
     }
     // ---- the fetched A operands -> LDS, for the partner wavefront (and, for C_in == 32, for this one as well)
@@ -262,9 +285,9 @@ __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t*
     const int gsel_even = OWN ? 2 * wn + lg : lg, gsel_odd = OWN ? 2 * (1 - wn) + lg : lg;
 
     // this lane's sixteen output channels' scales and biases, read once
-    float rq_scale[RQ ? 16 : 1];
-    int rq_bias[RQ ? 16 : 1];
-    if constexpr (RQ) {
+    float rq_scale[RQ == 1 ? 16 : 1];
+    int rq_bias[RQ == 1 ? 16 : 1];
+    if constexpr (RQ == 1) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int co = co_base + 8 * (v >> 2) + (v & 3);
@@ -273,7 +296,7 @@ __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t*
         }
     }
     auto requant_reg = [&](int acc_v, int v) __attribute__((always_inline)) {
-        float r = rintf(__int2float_rn(acc_v + rq_bias[RQ ? v : 0]) * rq_scale[RQ ? v : 0]);
+        float r = rintf(__int2float_rn(acc_v + rq_bias[RQ == 1 ? v : 0]) * rq_scale[RQ == 1 ? v : 0]);
         r = fminf(fmaxf(r, rq.relu ? 0.0f : -128.0f), 127.0f);
         return (int)r;
     };
@@ -311,6 +334,44 @@ __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t*
             }
         } else {
             if (dst >= 0) __builtin_nontemporal_store(c[v], y + ybase + (int64_t)ch * HoWo + dst);
+        }
+    };
+
+    // (RQ == 2) the requantisation of one block in 32 micro-steps, eight per group g of four registers (channels
+    // 8g + 4lg + 0..3 of this lane's pixel): four values, the packing, the exchange inside the quad, the byte
+    // selection, the LDS write.  Lane k of a quad ends up with channel 8g + 4lg + k of the quad's four pixels.
+    constexpr int kOutPitch = 160;                            // bytes per channel in the output area (bank-conflict-free)
+    unsigned char* lout = lraw_w;                             // (the raw band is dead after the prologue)
+    const int qk = lane & 3;
+    const u32 sel_own = 0x0c0c0c0cu ^ ((0x0cu ^ (u32)qk) << (8 * qk)) ^ ((0x0cu ^ (u32)(4 + qk)) << (8 * (qk ^ 1)));
+    const u32 sel_far = 0x0c0c0c0cu ^ ((0x0cu ^ (u32)qk) << (8 * (qk ^ 2))) ^ ((0x0cu ^ (u32)(4 + qk)) << (8 * (qk ^ 3)));
+    const float rq_lo = rq.relu ? 0.0f : -128.0f;
+    u32 rqv[4], rq_packed = 0, rq_a = 0, rq_b = 0, rq_c = 0, rq_word = 0;
+    // scales and biases of the group's four channels come from LDS one group ahead (they would cost 32 registers)
+    typedef float floatx4 __attribute__((ext_vector_type(4)));
+    const unsigned char* lrq_lane = lrq + (32 * wm + 4 * lg) * 4;
+    floatx4 rq_sc = *reinterpret_cast<const floatx4*>(lrq_lane);
+    intx4 rq_bi = *reinterpret_cast<const intx4*>(lrq_lane + 256);
+    unsigned char* lout_lane = lout + (4 * lg + qk) * kOutPitch + 4 * (lj >> 2);
+    auto rq_step = [&](int ms, const intx16& c, int blk) __attribute__((always_inline)) {
+        const int g = ms >> 3, t = ms & 7;
+        if (t < 4) {
+            const int v = 4 * g + t;
+            float f = __int2float_rn(c[v] + rq_bi[t]) * rq_sc[t];
+            f = __builtin_amdgcn_fmed3f(f, rq_lo, 127.0f);
+            rqv[t] = __float_as_uint(f + 12582912.0f);
+        } else if (t == 4) {
+            rq_packed = s8perm::perm(s8perm::perm(rqv[3], rqv[2], 0x04000c0cu), s8perm::perm(rqv[1], rqv[0], 0x0c0c0400u), 0x07060100u);
+        } else if (t == 5) {
+            rq_a = (u32)__builtin_amdgcn_mov_dpp((int)rq_packed, 0xB1, 0xF, 0xF, true);   // from lane k ^ 1
+            rq_b = (u32)__builtin_amdgcn_mov_dpp((int)rq_packed, 0x4E, 0xF, 0xF, true);   // k ^ 2
+            rq_c = (u32)__builtin_amdgcn_mov_dpp((int)rq_packed, 0x1B, 0xF, 0xF, true);   // k ^ 3
+        } else if (t == 6) {
+            rq_word = s8perm::perm(rq_a, rq_packed, sel_own) | s8perm::perm(rq_c, rq_b, sel_far);
+            rq_sc = *reinterpret_cast<const floatx4*>(lrq_lane + 32 * ((g + 1) & 3));
+            rq_bi = *reinterpret_cast<const intx4*>(lrq_lane + 256 + 32 * ((g + 1) & 3));
+        } else {
+            *reinterpret_cast<u32*>(lout_lane + 8 * g * kOutPitch + 32 * blk) = rq_word;
         }
     };
 
@@ -355,7 +416,14 @@ __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t*
                 a_from_lds(k + kLookAhead);
                 b[(k + kLookAhead) % (kLookAhead + 1)] = b_at(k + kLookAhead);
             }
-            if (DRAIN && k % GAP == 0) {
+            if constexpr (RQ == 2) {
+                if (DRAIN) {
+                    constexpr int MPER = (32 + NSTEP - 1) / NSTEP;    // micro-steps per issue slot
+#pragma unroll
+                    for (int u = 0; u < MPER; ++u)
+                        if (k * MPER + u < 32) rq_step(k * MPER + u, prev, i - 1);
+                }
+            } else if (DRAIN && k % GAP == 0) {
 #pragma unroll
                 for (int u = 0; u < PER; ++u) {
                     const int sv = (k / GAP) * PER + u;
@@ -386,8 +454,22 @@ __global__ __launch_bounds__(NWV * 64, 1) void mfma_s8_band_kernel(const int8_t*
         res = nxt;
         dst = block_dst(i);
     }
+    if constexpr (RQ == 2) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) store_reg(dst, res, v);
+        for (int ms = 0; ms < 32; ++ms) rq_step(ms, res, live - 1);
+        // this wavefront's 32 channels x vbytes pixels leave as 16-byte pieces (eight slots per channel)
+        const int vbytes = min(32 * live, tile_px - 32 * first);
+        int8_t* yo = y8 + ((int64_t)n * C_out + (mb << 6) + 32 * wm) * HoWo + p0 + 32 * first;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = lane + 64 * j, ch = e >> 3, part = e & 7;
+            const intx4 v = *reinterpret_cast<const intx4*>(lout + ch * kOutPitch + 16 * part);
+            if (16 * part < vbytes) __builtin_nontemporal_store(v, reinterpret_cast<intx4*>(yo + (int64_t)ch * HoWo + 16 * part));
+        }
+    } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) store_reg(dst, res, v);
+    }
 }
 
 struct BandTiling {
@@ -421,14 +503,14 @@ BandTiling pick_band(const Conv2dShape& s)
     return t;
 }
 
-template <int KS, bool RQ, bool RAWW>
+template <int KS, int RQ, bool RAWW>
 hipError_t launch_band(const int8_t* x, const int8_t* wp, int32_t* y, int8_t* y8, const Requant& rq, const Conv2dShape& s,
                        const BandTiling& t, hipStream_t st)
 {
     // helper wavefronts where the register budget allows two wavefronts per SIMD (the requantising stores need more)
-    constexpr int NWV = (KS == 4 && !RQ) ? 8 : 4;
+    constexpr int NWV = (KS == 4 && RQ != 1) ? 8 : 4;
     constexpr int GPW = 2 * KS > NWV ? 2 * KS / NWV : 1;     // as in the kernel
-    constexpr int kLds = 2 * KS * (kWinPx * 16 + 16) + 2 * 9 * KS * 1024 + NWV * (16 * GPW * 16 * kMaxPieces + 144);
+    constexpr int kLds = 2 * KS * (kWinPx * 16 + 16) + 2 * 9 * KS * 1024 + NWV * (16 * GPW * 16 * kMaxPieces + 144) + (RQ == 2 ? 512 : 0);
     const size_t lds = kLds;
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_s8_band_kernel<KS, RQ, RAWW, NWV>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -469,10 +551,13 @@ hipError_t launch_mfma_s8_band(const int8_t* x, const int8_t* w, int32_t* y, int
     const BandTiling t = pick_band(s);
     const Requant none{nullptr, nullptr, 0};
     const int KS = s.C_in / 32;
+    // requantised output through LDS: 16-byte pieces of y8 must be aligned and never straddle the end of a plane
+    const bool staged = rq && (s.Ho * s.Wo) % 16 == 0 && reinterpret_cast<uintptr_t>(y8) % 16 == 0;
 #define SW_BAND(KSC, RAWC)                                                                   \
     do {                                                                                     \
-        if (rq) return launch_band<KSC, true, RAWC>(x, w, nullptr, y8, *rq, s, t, st);       \
-        return launch_band<KSC, false, RAWC>(x, w, y, nullptr, none, s, t, st);              \
+        if (rq && staged) return launch_band<KSC, 2, RAWC>(x, w, nullptr, y8, *rq, s, t, st); \
+        if (rq) return launch_band<KSC, 1, RAWC>(x, w, nullptr, y8, *rq, s, t, st);          \
+        return launch_band<KSC, 0, RAWC>(x, w, y, nullptr, none, s, t, st);                  \
     } while (0)
     if (raw_filters) {
         if (KS == 4) SW_BAND(4, true);

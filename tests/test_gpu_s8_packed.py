@@ -143,3 +143,45 @@ def test_packed_extremes(torch, sw):
     y = sw.sw_conv2d_s8_packed(dev(torch, x), packed, 128, 3, 3, 1, 1).cpu().numpy()
     assert np.all(y[:, :, 1:-1, 1:-1] == 128 * 9 * 16384)
     assert np.all(y[:, :, 0, 0] == 128 * 4 * 16384)
+
+
+@pytest.mark.parametrize("raw_filters", [False, True], ids=["packed", "caller-filters"])
+@pytest.mark.parametrize("case", [
+    # N, C_in, C_out, H, W, pad, byte offset of y8, store variant the band kernel must take
+    (32, 128, 128, 28, 28, 1, 0, 2),    # the quantised workload at full size: through LDS, 16-byte pieces
+    (2, 128, 64, 28, 28, 1, 0, 2),
+    (3, 64, 128, 28, 28, 1, 0, 2),      # C_in = 64, no helper wavefronts
+    (2, 64, 64, 56, 56, 1, 0, 2),       # several tiles per image, the last one ragged
+    (1, 128, 64, 12, 16, 1, 0, 2),      # a single tile of six blocks
+    (1, 64, 64, 20, 20, 1, 0, 2),       # 400 pixels: the last block holds 16
+    (2, 128, 64, 28, 28, 1, 4, 1),      # y8 not 16-byte aligned: dword stores from the registers
+    (2, 128, 64, 28, 28, 1, 1, 1),      # ... not even 4-byte aligned: byte stores
+    (2, 64, 64, 28, 28, 0, 0, 1),       # 26 x 26 outputs: planes of 676 pixels, not a multiple of 16
+], ids=lambda c: "x".join(map(str, c)))
+def test_band_kernel_requantised_store_variants(torch, sw, oracle, case, raw_filters):
+    N, C_in, C_out, H, W, pad, offset, variant = case
+    if raw_filters and C_in % 64:
+        pytest.skip("the band kernel takes the caller's filters in chunks of 64 input channels")
+    x = inputs.uniform_s8((N, C_in, H, W), 5131)
+    w = inputs.uniform_s8((C_out, C_in, 3, 3), 5132)
+    rng = np.random.default_rng(5133)
+    bias = rng.integers(-30000, 30000, size=C_out).astype(np.int32)
+    std = np.sqrt(C_in * 9) * 5461.0
+    scale = (rng.uniform(0.5, 2.0, size=C_out) * 40.0 / std).astype(np.float32)
+    scale[::3] = np.float32(2.0 ** np.round(np.log2(40.0 / std)))      # powers of two produce exact ties
+    scale[1::5] *= np.float32(-1.0)                                    # negative scales are legal
+    for relu in (False, True):
+        q_ref = oracle.conv2d_s8_requant(x, w, bias, scale, 1, pad, relu)
+        n = q_ref.size
+        buf = torch.full((256 + n + 64,), 77, dtype=torch.int8, device="cuda")
+        out = buf[256 + offset:256 + offset + n].view(q_ref.shape)
+        if raw_filters:
+            sw.sw_conv2d_s8_requant(dev(torch, x), dev(torch, w), dev(torch, bias), dev(torch, scale), 1, pad, relu, out=out)
+        else:
+            sw.sw_conv2d_s8_packed(dev(torch, x), sw.sw_s8_pack_filter(dev(torch, w)), C_out, 3, 3, 1, pad,
+                                   dev(torch, bias), dev(torch, scale), relu, out=out)
+        assert sw.sw_last_kernel() == f"mfma_s8_band_kernel<{C_in // 32},{variant},{int(raw_filters)}>", sw.sw_last_kernel()
+        torch.cuda.synchronize()
+        assert bool((buf[:256 + offset] == 77).all()) and bool((buf[256 + offset + n:] == 77).all()), "write outside y8"
+        q = out.cpu().numpy()
+        assert np.array_equal(q, q_ref), f"{case} relu={relu}: {np.count_nonzero(q != q_ref)} of {q.size} differ"

@@ -251,7 +251,9 @@ int sw_conv2d_depthwise_bf16(const uint16_t* x, const float* w, uint16_t* y,
  * (columns alike).  dilation >= 1 (else SW_ERR_SHAPE); dilation == 1 is the undilated call.
  * Other arguments, layouts and errors as the undilated calls.  With C_in >= 2 the
  * matrix-core kernel runs (the window in LDS grows, the taps step through it
- * `dilation` apart); depthwise and C_in == 1 run one thread per output.
+ * `dilation` apart); depthwise and C_in == 1 at stride 1 run the sliding tile
+ * kernel while the filter's span is at most 51 (3x3 at dilation 2 and 4 unrolled,
+ * other extents and dilations with run-time loops), else one thread per output.
  */
 int sw_conv2d_dilated(const float* x, const float* w, float* y,
                       int N, int C_in, int C_out, int H, int W, int R, int S,

@@ -37,34 +37,36 @@ constexpr int in_rows(int R) { return kTile + R - 1; }
 
 // The lane's 7 x 7 outputs for a filter extent known at compile time.  Input row ir of the lane's
 // window is read once (7 + S - 1 floats) and used by every output row orow with 0 <= ir - orow < R.
-template <int R, int S, int P>
+// DIL: input positions between neighbouring taps; filter row r then meets input row orow + r * DIL.
+template <int R, int S, int P, int DIL = 1>
 __device__ __forceinline__ void accumulate_block(const float* __restrict__ win, const float* __restrict__ wf,
                                                  float (&acc)[kB][kB])
 {
     float wr[R * S];
 #pragma unroll
     for (int t = 0; t < R * S; ++t) wr[t] = wf[t];
-    constexpr int N = kB + S - 1;
+    constexpr int N = kB + (S - 1) * DIL;
     float in[2][N];
 #pragma unroll
     for (int c = 0; c < N; ++c) in[0][c] = win[c];
 #pragma unroll
-    for (int ir = 0; ir < kB + R - 1; ++ir) {
+    for (int ir = 0; ir < kB + (R - 1) * DIL; ++ir) {
         // the next row is on its way from LDS while this one is accumulated
-        if (ir + 1 < kB + R - 1) {
+        if (ir + 1 < kB + (R - 1) * DIL) {
 #pragma unroll
             for (int c = 0; c < N; ++c) in[(ir + 1) & 1][c] = win[(ir + 1) * P + c];
         }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int orow = 0; orow < kB; ++orow) {
-            const int r = ir - orow;
-            if (r < 0 || r >= R) continue;
+            if (ir < orow || (ir - orow) % DIL != 0) continue;
+            const int r = (ir - orow) / DIL;
+            if (r >= R) continue;
 #pragma unroll
             for (int q = 0; q < S; ++q)
 #pragma unroll
                 for (int oc = 0; oc < kB; ++oc)
-                    acc[orow][oc] = fmaf(wr[r * S + q], in[ir & 1][oc + q], acc[orow][oc]);
+                    acc[orow][oc] = fmaf(wr[r * S + q], in[ir & 1][oc + q * DIL], acc[orow][oc]);
         }
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -75,14 +77,15 @@ __device__ __forceinline__ void accumulate_block(const float* __restrict__ win, 
 // window (7 + NT - 1 floats, the next row already on its way) and slides it under the taps by register rename.
 // An input row is read once per filter row it meets instead of once in all, which is what keeps the taps
 // of any R x S out of the register file; LDS has the bandwidth to spare (one 8-byte read per 7 to 8 FMAs).
-template <int NT>
+// DIL: input positions between neighbouring taps (dilation); the window row then spans 7 + (NT - 1) * DIL floats.
+template <int NT, int DIL = 1>
 __device__ __forceinline__ void row_step(const float* __restrict__ src, const float* __restrict__ taps, int P,
                                          float (&acc)[kB][kB])
 {
     float wr[NT];
 #pragma unroll
     for (int jj = 0; jj < NT; ++jj) wr[jj] = taps[jj];
-    constexpr int N = kB + NT - 1;
+    constexpr int N = kB + (NT - 1) * DIL;
     float in[2][N];
 #pragma unroll
     for (int c = 0; c < N; ++c) in[0][c] = src[c];
@@ -96,12 +99,13 @@ __device__ __forceinline__ void row_step(const float* __restrict__ src, const fl
 #pragma unroll
         for (int jj = 0; jj < NT; ++jj)
 #pragma unroll
-            for (int oc = 0; oc < kB; ++oc) acc[orow][oc] = fmaf(wr[jj], in[orow & 1][oc + jj], acc[orow][oc]);
+            for (int oc = 0; oc < kB; ++oc) acc[orow][oc] = fmaf(wr[jj], in[orow & 1][oc + jj * DIL], acc[orow][oc]);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-// RC, SC > 0: filter extent known at compile time, one wavefront per tile.  RC == 0: extent (R, S) at run
+// RC, SC > 0: filter extent known at compile time, one wavefront per tile; MAXRS is then the dilation (0: none).
+// RC == 0: extent (R, S) at run
 // time, up to MAXRS; four wavefronts share the tile's LDS window (which is what limits how many tiles a CU
 // holds), each takes every fourth filter row, and the four partial 7 x 7 blocks are summed through LDS.
 template <int RC, int SC, int MAXRS>
@@ -111,10 +115,11 @@ __global__ __launch_bounds__(RC > 0 ? 64 : 256) void sliding_plane_kernel(const 
                                                            int n_filters, int H, int W, int R_rt,
                                                            int S_rt, int pad, int Ho, int Wo,
                                                            int tiles_x, int tiles_y, int x_vec_ok,
-                                                           int y_vec_ok, const Epilogue ep)
+                                                           int y_vec_ok, const Epilogue ep, int dil)
 {
-    constexpr int RMAX = RC > 0 ? RC : MAXRS;
-    constexpr int SMAX = RC > 0 ? SC : MAXRS;
+    constexpr int DILC = RC > 0 && MAXRS > 1 ? MAXRS : 1;          // fixed extents: the dilation
+    constexpr int RMAX = RC > 0 ? (RC - 1) * DILC + 1 : MAXRS;     // rows / columns the window holds beyond the tile, plus 1
+    constexpr int SMAX = RC > 0 ? (SC - 1) * DILC + 1 : MAXRS;
     constexpr int P = in_pitch(SMAX);
     constexpr int F4_PER_ROW = (3 + kTile + SMAX - 1 + 3) / 4;   // 16-byte groups loaded per row
     static_assert(F4_PER_ROW * 4 <= P, "pitch too small");
@@ -142,7 +147,7 @@ __global__ __launch_bounds__(RC > 0 ? 64 : 256) void sliding_plane_kernel(const 
     const int shift = pad_up - pad;
     const int gcol0 = col0 - pad_up;
     const int grow0 = row0 - pad;
-    const int rows_in = kTile + R - 1;
+    const int rows_in = kTile + (R - 1) * (RC > 0 ? DILC : dil);
 
     // (four 16-byte groups per thread go out before the first LDS write: one memory round trip per batch of four)
     for (int base = threadIdx.x; base < rows_in * F4_PER_ROW; base += NT * 4) {
@@ -189,10 +194,32 @@ __global__ __launch_bounds__(RC > 0 ? 64 : 256) void sliding_plane_kernel(const 
     const float* win = lds + (kB * by) * P + shift + kB * bx;   // the lane's window origin
 
     if (RC > 0) {
-        accumulate_block<RMAX, SMAX, P>(win, wf, acc);
+        accumulate_block<(RC > 0 ? RC : 1), (RC > 0 ? SC : 1), P, DILC>(win, wf, acc);
     } else {
         // Run-time extents: filter rows one at a time (every NW-th row in this wavefront), tap columns in
-        // groups of eight.
+        // groups of eight.  Dilated filters (the window then holds the filter's span, (R - 1) * dil + 1 rows and
+        // as many columns more): dilation 2 in groups of four taps, any other one tap at a time.
+        if (dil == 2) {
+            const int full2 = S & ~3, rem2 = S & 3;
+#pragma unroll 1
+            for (int r = wave; r < R; r += NW) {
+                const float* row = win + 2 * r * P;
+                const float* taps = wf + r * S;
+#pragma unroll 1
+                for (int s0 = 0; s0 < full2; s0 += 4) row_step<4, 2>(row + 2 * s0, taps + s0, P, acc);
+                if (rem2 == 1) row_step<1, 2>(row + 2 * full2, taps + full2, P, acc);
+                else if (rem2 == 2) row_step<2, 2>(row + 2 * full2, taps + full2, P, acc);
+                else if (rem2 == 3) row_step<3, 2>(row + 2 * full2, taps + full2, P, acc);
+            }
+        } else if (dil != 1) {
+#pragma unroll 1
+            for (int r = wave; r < R; r += NW) {
+                const float* row = win + r * dil * P;
+                const float* taps = wf + r * S;
+#pragma unroll 1
+                for (int s0 = 0; s0 < S; ++s0) row_step<1>(row + s0 * dil, taps + s0, P, acc);
+            }
+        } else {
         const int full = S & ~7, rem = S & 7;
 #pragma unroll 1
         for (int r = wave; r < R; r += NW) {
@@ -210,6 +237,7 @@ __global__ __launch_bounds__(RC > 0 ? 64 : 256) void sliding_plane_kernel(const 
                 case 7: row_step<7>(row + full, taps + full, P, acc); break;
                 default: break;
             }
+        }
         }
     }
 
@@ -547,10 +575,12 @@ __global__ __launch_bounds__(64) void sliding_plane_bf16_kernel(const unsigned s
 
 }  // namespace
 
-bool sliding_plane_supported(int H, int W, int R, int S, int stride, int pad)
+// dil > 1: the run-time-extent kernels, whose window must hold the filter's span (R - 1) * dil + 1
+bool sliding_plane_supported(int H, int W, int R, int S, int stride, int pad, int dil)
 {
     (void)H; (void)W;
-    return stride == 1 && R <= kMaxRSWide && S <= kMaxRSWide && pad >= 0;
+    const int64_t span_r = (int64_t)(R - 1) * dil + 1, span_s = (int64_t)(S - 1) * dil + 1;
+    return stride == 1 && dil >= 1 && span_r <= kMaxRSWide && span_s <= kMaxRSWide && pad >= 0;
 }
 
 // True when the persistent whole-plane kernel takes the problem (planes that fit one 56 x 56 tile).
@@ -575,9 +605,9 @@ bool sliding_plane_worthwhile(int64_t planes, int Ho, int Wo, int R, int S)
 
 hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x,
                                 int n_filters, int H, int W, int R, int S, int pad, int Ho, int Wo,
-                                hipStream_t st, const Epilogue& ep)
+                                hipStream_t st, const Epilogue& ep, int dil)
 {
-    if (sliding_plane_whole(x, y, H, W, R, S, pad, Ho, Wo) && planes <= 2147483647LL) {
+    if (dil == 1 && sliding_plane_whole(x, y, H, W, R, S, pad, Ho, Wo) && planes <= 2147483647LL) {
         // enough wavefronts to fill the chip, each walking over several planes
         const int64_t want = 256 * 8;
         dim3 grid((unsigned)(planes < want ? planes : want)), block(64);
@@ -608,11 +638,14 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
     dim3 grid((unsigned)blocks);
 #define SW_PLANE(RC, SC, MAXRS)                                                                          \
     SW_NOTED_LAUNCH(note_kernel("sliding_plane_kernel", (int)(RC), (int)(SC), (int)(MAXRS)), (sliding_plane_kernel<RC, SC, MAXRS>), grid, dim3(RC > 0 ? 64 : 256), 0, st, x, w, y, planes_per_x, \
-                       n_filters, H, W, R, S, pad, Ho, Wo, tiles_x, tiles_y, x_vec_ok, y_vec_ok, ep)
-    if (R == 3 && S == 3) SW_PLANE(3, 3, 0);
-    else if (R == 5 && S == 5) SW_PLANE(5, 5, 0);
-    else if (R == 7 && S == 7) SW_PLANE(7, 7, 0);
-    else if (R <= kMaxRS && S <= kMaxRS) SW_PLANE(0, 0, kMaxRS);
+                       n_filters, H, W, R, S, pad, Ho, Wo, tiles_x, tiles_y, x_vec_ok, y_vec_ok, ep, dil)
+    const int span_r = (R - 1) * dil + 1, span_s = (S - 1) * dil + 1;
+    if (dil == 1 && R == 3 && S == 3) SW_PLANE(3, 3, 0);
+    else if (dil == 2 && R == 3 && S == 3) SW_PLANE(3, 3, 2);
+    else if (dil == 4 && R == 3 && S == 3) SW_PLANE(3, 3, 4);
+    else if (dil == 1 && R == 5 && S == 5) SW_PLANE(5, 5, 0);
+    else if (dil == 1 && R == 7 && S == 7) SW_PLANE(7, 7, 0);
+    else if (span_r <= kMaxRS && span_s <= kMaxRS) SW_PLANE(0, 0, kMaxRS);
     else SW_PLANE(0, 0, kMaxRSWide);
 #undef SW_PLANE
     return hipGetLastError();

@@ -53,7 +53,13 @@ int launch_status(hipError_t e) { return e == hipSuccess ? SW_OK : SW_ERR_LAUNCH
 int run_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
               const Conv2dShape& s, bool depthwise, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0})
 {
-    if (!force_direct()) {
+    if (!force_direct() && s.dil != 1) {
+        // dilated taps: the run-time-extent tile kernel, whose window holds the filter's span
+        if (sliding_plane_supported(s.H, s.W, s.R, s.S, s.stride, s.pad, s.dil) &&
+            sliding_plane_worthwhile(planes, s.Ho, s.Wo, s.R, s.S))
+            return launch_status(launch_sliding_plane(x, w, y, planes, planes_per_x, n_filters, s.H, s.W, s.R, s.S,
+                                                      s.pad, s.Ho, s.Wo, st, ep, s.dil));
+    } else if (!force_direct()) {
         // planes up to 20 x 20, and larger ragged ones (width not a multiple of 4) that the register-only and
         // whole-plane kernels do not take: a run of planes per workgroup
         if ((s.H * s.W <= 400 || s.W % 4 != 0 || s.R * s.S >= 25) &&
@@ -221,9 +227,8 @@ static int run_conv2d(const float* x, const float* w, float* y, const Conv2dShap
 {
     const bool plain = !ep.bias && !ep.relu;
     (void)plain;
-    if (s.C_in == 1 && s.dil == 1)
+    if (s.C_in == 1)
         return run_plane(x, w, y, (int64_t)s.N * s.C_out, s.C_out, s.C_out, s, false, st, ep);
-    // (one input channel with a dilation: the one-filter-per-plane kernels have none, one thread per output has)
     if (!force_direct() && s.C_in > 1) {
         // The fixed 3x3 / 5x5 kernel holds a CU with one large tile: it needs enough of them to fill the chip
         // (28 x 28 images and below at batch 32 leave it at 128 or fewer); the any-shape kernel's 128-pixel
@@ -274,8 +279,7 @@ int sw_conv2d_depthwise_dilated(const float* x, const float* w, float* y, int N,
     const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s, dilation);
     if (rc != SW_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (dilation == 1) return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
-    return launch_status(launch_direct_conv2d_f32(x, w, y, s, true, st));
+    return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
 }
 
 int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,

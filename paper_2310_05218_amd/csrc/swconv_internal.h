@@ -22,7 +22,7 @@ __device__ __forceinline__ int fast_div(int n, FastDiv f) { return f.magic ? (in
 
 struct Conv2dShape {
     int N, C_in, C_out, H, W, R, S, stride, pad, Ho, Wo;
-    int dil = 1;      // input positions between neighbouring taps (only the any-shape fp32 and direct kernels take > 1)
+    int dil = 1;      // input positions between neighbouring taps (the any-shape fp32, run-time-extent tile and direct kernels take > 1)
 };
 
 // Per-channel bias and rectifier on an fp32 sum on its way out: y = relu ? max(acc + bias[co], 0) : acc + bias[co]
@@ -95,7 +95,7 @@ hipError_t launch_pool_tiles(const float* x, float* y, int64_t rows, int64_t len
 // ---- sliding plane kernel (stride 1): one filter per plane (single channel, depthwise) --------
 // x plane index for output plane p is p / planes_per_x (conv2d with C_in == 1: C_out filters share
 // one input plane; depthwise: 1); filter index is p % n_filters.
-bool       sliding_plane_supported(int H, int W, int R, int S, int stride, int pad);
+bool       sliding_plane_supported(int H, int W, int R, int S, int stride, int pad, int dil = 1);
 bool       sliding_plane_worthwhile(int64_t planes, int Ho, int Wo, int R, int S);
 bool       sliding_plane_whole(const float* x, const float* y, int H, int W, int R, int S, int pad, int Ho, int Wo);
 
@@ -110,7 +110,7 @@ hipError_t launch_pool_rows(const float* x, float* y, int64_t planes, int H, int
                             int Ho, int Wo, bool maximum, hipStream_t st);
 hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_t planes,
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
-                                int Ho, int Wo, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0});
+                                int Ho, int Wo, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0}, int dil = 1);
 
 // ---- depthwise 3x3 (stride 1, padding 1) -> pointwise 1x1 in one launch, the intermediate only in LDS
 bool       dw_pw_block_supported(int N, int C, int C_out, int H, int W);

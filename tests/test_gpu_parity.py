@@ -416,6 +416,41 @@ def test_conv2d_depthwise_dilated(torch, sw, oracle, case):
     assert_f32_parity(out.cpu().numpy(), y_ref, d, f"depthwise_dilated {case}")
 
 
+@pytest.mark.parametrize("case", [
+    # N, C, H, W, R, S, pad, dilation, kernel the call must reach
+    (2, 64, 56, 56, 3, 3, 2, 2, "sliding_plane_kernel<3,3,2>"),      # 3x3 at dilation 2 and 4: unrolled kernels
+    (1, 64, 57, 59, 3, 3, 0, 2, "sliding_plane_kernel<3,3,2>"),      # ... ragged tiles, no padding
+    (1, 64, 40, 44, 4, 4, 3, 2, "sliding_plane_kernel<0,0,17>"),     # dilation 2, other extents: taps in groups of four
+    (1, 64, 57, 59, 5, 5, 4, 2, "sliding_plane_kernel<0,0,17>"),     # ... a group of four and one more, ragged tiles
+    (1, 70, 40, 44, 2, 7, 3, 2, "sliding_plane_kernel<0,0,17>"),     # ... and three more; two filter rows
+    (1, 64, 65, 70, 3, 3, 6, 6, "sliding_plane_kernel<0,0,17>"),     # any other dilation: one tap at a time, span 13
+    (1, 64, 60, 60, 3, 3, 12, 12, "sliding_plane_kernel<0,0,51>"),   # span 25: the wide window
+    (1, 64, 64, 64, 3, 3, 18, 18, "sliding_plane_kernel<0,0,51>"),   # span 37
+    (1, 64, 112, 112, 3, 3, 4, 4, "sliding_plane_kernel<3,3,4>"),    # four tiles per plane
+    (1, 8, 30, 30, 7, 7, 9, 3, "sliding_plane_kernel<0,0,51>"),      # 49 taps, span 19, few planes
+    (1, 64, 80, 80, 3, 3, 0, 30, "direct_conv2d_kernel"),            # span 61: no window holds it
+], ids=lambda c: "x".join(map(str, c[:8])))
+def test_depthwise_dilated_sliding_kernel(torch, sw, oracle, case):
+    """Dilated one-filter-per-plane convolution on the sliding tile kernel (enough planes to fill the chip)."""
+    N, C, H, W, R, S, pad, dil, kernel = case
+    x = inputs.normal_f32((N, C, H, W), 3221)
+    w = inputs.normal_f32((C, 1, R, S), 3222)
+    b = inputs.normal_f32((C,), 3223, 0.5)
+    y_ref, d = oracle.conv2d_dilated(x, w, 1, pad, dil, depthwise=True)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_depthwise_dilated(dev(torch, x), dev(torch, w), 1, pad, dil, out=out)
+    assert sw.sw_last_kernel().startswith(kernel), sw.sw_last_kernel()
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"depthwise_dilated {case}")
+    # one input channel, C filters: the same planes through sw_conv2d_dilated
+    x1 = inputs.normal_f32((N, 1, H, W), 3224)
+    y_ref, d = oracle.conv2d_dilated(x1, w, 1, pad, dil)
+    y = sw.sw_conv2d_dilated(dev(torch, x1), dev(torch, w), 1, pad, dil)
+    assert sw.sw_last_kernel().startswith(kernel), sw.sw_last_kernel()
+    assert_f32_parity(y.cpu().numpy(), y_ref, d, f"conv2d_dilated C_in=1 {case}")
+
+
 def test_dilation_one_is_the_undilated_call(torch, sw):
     x = dev(torch, inputs.normal_f32((2, 16, 28, 28), 3221))
     w = dev(torch, inputs.normal_f32((64, 16, 3, 3), 3222, 0.1))

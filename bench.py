@@ -204,7 +204,7 @@ def time_kernel(torch, fn, sets, reps, batches=5):
 
 # filter sizes of `--sweep`: one filter per plane, and with a C_in reduction
 SWEEP_FILTERS = (3, 5, 7, 9, 11, 13, 15, 17, 21, 25, 29, 33, 37, 45, 51)
-MC_SWEEP_FILTERS = (1, 3, 5, 7, 9, 11, 13)
+MC_SWEEP_FILTERS = (1, 3, 5, 7, 9, 11, 13, 15, 17, 21, 25, 29, 33, 37, 45, 51)
 SWEEP_1D = (2, 3, 5, 9, 13, 17, 25, 33, 49, 64)        # 1-D filter lengths / pooling windows
 
 

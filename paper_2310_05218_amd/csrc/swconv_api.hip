@@ -233,12 +233,18 @@ static int run_conv2d(const float* x, const float* w, float* y, const Conv2dShap
         // The fixed 3x3 / 5x5 kernel holds a CU with one large tile: it needs enough of them to fill the chip
         // (28 x 28 images and below at batch 32 leave it at 128 or fewer); the any-shape kernel's 128-pixel
         // tiles take over there, and everywhere the fixed kernel has no variant.
+        // Filters of 25 taps and more over at least 8 channels: the compound kernel (one filter row of a channel
+        // chunk at a time, 256-pixel tiles), measured faster than the kernels below from 5 x 5 upward and the only
+        // matrix-core kernel beyond 13 x 13.
+        if (s.R * s.S >= 25 && s.C_in >= 8 && mfma_f32_rows_supported(s, x))
+            return launch_status(launch_mfma_f32_rows(x, w, y, s, st, ep));
         const bool quad_ok = mfma_f32_quad_supported(s);
         const bool any_ok = quad_ok || mfma_f32_any_supported(s);
         if (mfma_f32_supported(s) && (mfma_f32_workgroups(s) >= 160 || !any_ok))
             return launch_status(launch_mfma_f32(x, w, y, s, st, ep));
         if (quad_ok) return launch_status(launch_mfma_f32_quad(x, w, y, s, st, ep));
         if (any_ok) return launch_status(launch_mfma_f32_any(x, w, y, s, st, ep));
+        if (mfma_f32_rows_supported(s, x)) return launch_status(launch_mfma_f32_rows(x, w, y, s, st, ep));
     }
     return launch_status(launch_direct_conv2d_f32(x, w, y, s, false, st, &ep));
 }

@@ -159,6 +159,9 @@ int64_t    mfma_f32_workgroups(const Conv2dShape& s);     // of the fixed 3x3 / 
 bool       mfma_f32_any_supported(const Conv2dShape& s);  // any extent, stride and channel count (C_in >= 2)
 hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
                                const Epilogue& ep = Epilogue{nullptr, 0});
+bool       mfma_f32_rows_supported(const Conv2dShape& s, const float* x); // large filters: one filter row of a channel chunk at a time
+hipError_t launch_mfma_f32_rows(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
+                                const Epilogue& ep = Epilogue{nullptr, 0});
 bool       mfma_f32_quad_supported(const Conv2dShape& s); // the same for few taps (R * S <= 12): 16-byte operand reads
 hipError_t launch_mfma_f32_quad(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
                                 const Epilogue& ep = Epilogue{nullptr, 0});

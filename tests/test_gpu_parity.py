@@ -369,7 +369,7 @@ CONV2D_CASES = [
     (1, 6, 64, 30, 30, 11, 11, 1, 5),    # filter rows beyond 64 KB of LDS: one workgroup per CU
     (2, 4, 70, 24, 24, 13, 13, 1, 6),
     (1, 3, 64, 40, 40, 17, 17, 2, 8),    # the largest filter of the matrix-core kernel
-    (1, 2, 5, 40, 40, 18, 18, 1, 9),     # beyond it: one thread per output
+    (1, 2, 5, 40, 40, 18, 18, 1, 9),     # beyond it: the compound (filter-row) kernel
     (1, 2, 4, 5, 5, 5, 5, 1, 0),         # a single output pixel
     (1, 9, 130, 16, 16, 2, 2, 2, 0),     # even filter, three channel blocks with a ragged last one
 ]
@@ -501,10 +501,56 @@ def test_depthwise_bias_relu_without_either_is_the_plain_call(torch, sw):
     assert torch.equal(sw.sw_conv2d_depthwise_bias_relu(x, w, None, 1, 1, True), torch.clamp_min(plain, 0.0))
 
 
+ROWS_KERNEL_CASES = [
+    # N, C_in, C_out, H, W, R, S, stride, pad, dilation, kernel instance the call must reach
+    (2, 16, 64, 56, 56, 5, 5, 1, 2, 1, "mfma_f32_rows_kernel<16,2,8>"),    # 25 taps: sixteen channels per chunk
+    (1, 64, 64, 28, 28, 7, 7, 1, 3, 1, "mfma_f32_rows_kernel<16,2,8>"),
+    (1, 24, 70, 40, 44, 9, 9, 1, 4, 1, "mfma_f32_rows_kernel<8,2,6>"),     # eight; ragged channel block and channel chunk
+    (1, 16, 64, 30, 32, 11, 11, 1, 5, 1, "mfma_f32_rows_kernel<8,2,6>"),
+    (1, 16, 64, 30, 32, 13, 13, 1, 6, 1, "mfma_f32_rows_kernel<8,2,8>"),   # longer filter rows: more filter slots per thread
+    (1, 12, 130, 24, 24, 17, 17, 1, 8, 1, "mfma_f32_rows_kernel<8,2,10>"),  # three channel blocks, the last one ragged
+    (1, 16, 64, 30, 32, 9, 3, 1, 1, 1, "mfma_f32_rows_kernel<16,2,4>"),    # rows of three taps (one thread takes a row)
+    (1, 8, 64, 20, 20, 21, 21, 1, 10, 1, "mfma_f32_rows_kernel<4,2,9>"),   # rows beyond 20 taps: four channels per chunk
+    (1, 8, 32, 48, 48, 41, 41, 1, 20, 1, "mfma_f32_rows_kernel<4,2,11>"),
+    (1, 8, 32, 36, 36, 33, 29, 1, 14, 1, "mfma_f32_rows_kernel<4,2,9>"),   # rectangular
+    (1, 6, 64, 32, 32, 51, 51, 1, 25, 1, "mfma_f32_rows_kernel<4,2,13>"),   # (fewer than 8 channels: no other kernel has it)
+    (1, 2, 5, 40, 40, 18, 18, 1, 9, 1, "mfma_f32_rows_kernel<2,2,10>"),     # two input channels
+    (1, 16, 64, 57, 60, 5, 5, 2, 2, 1, "mfma_f32_rows_kernel<4,2,9>"),     # stride 2: every second input row staged
+    (1, 33, 1, 24, 32, 5, 5, 3, 1, 1, "mfma_f32_rows_kernel<16,2,8>"),     # stride 3: image rows wider than the taps reach
+    (1, 9, 64, 41, 44, 7, 5, 3, 1, 1, "mfma_f32_rows_kernel<4,2,9>"),      # stride 3, rectangular, odd channel count
+    (1, 16, 64, 40, 40, 5, 5, 1, 4, 2, "mfma_f32_rows_kernel<16,2,8>"),    # dilation 2
+    (1, 8, 64, 48, 48, 7, 7, 2, 9, 3, "mfma_f32_rows_kernel<4,2,9>"),      # dilation 3 with stride 2
+    (1, 16, 64, 5, 8, 5, 5, 1, 0, 1, "mfma_f32_rows_kernel<16,2,8>"),      # a single row of four outputs
+    (2, 16, 64, 112, 112, 5, 5, 1, 2, 1, "mfma_f32_rows_kernel<8,2,6>"),   # tiles inside one image row pair
+    (40, 8, 128, 56, 56, 5, 5, 1, 2, 1, "mfma_f32_rows_kernel<4,4,9>"),    # enough work for 512-pixel tiles
+]
+
+
+@pytest.mark.parametrize("case", ROWS_KERNEL_CASES, ids=lambda c: "x".join(map(str, c[:10])))
+def test_conv2d_large_filters_rows_kernel(torch, sw, oracle, case):
+    """The compound kernel (one filter row of a channel chunk at a time), with and without the fused epilogue."""
+    N, C_in, C_out, H, W, R, S, stride, pad, dil, kernel = case
+    x = inputs.normal_f32((N, C_in, H, W), 3301)
+    w = inputs.normal_f32((C_out, C_in, R, S), 3302, (2.0 / (C_in * R * S)) ** 0.5)
+    y_ref, d = oracle.conv2d_dilated(x, w, stride, pad, dil)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_dilated(dev(torch, x), dev(torch, w), stride, pad, dil, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"rows kernel {case}")
+    assert sw.sw_last_kernel() == kernel, sw.sw_last_kernel()
+    if dil == 1 and N <= 2:
+        bias = inputs.normal_f32((C_out,), 3303, 0.7)
+        y_ref, d = oracle.conv2d_bias_relu(x, w, bias, stride, pad, True)
+        y = sw.sw_conv2d_bias_relu(dev(torch, x), dev(torch, w), dev(torch, bias), stride, pad, True)
+        assert sw.sw_last_kernel() == kernel, sw.sw_last_kernel()
+        assert_f32_parity(y.cpu().numpy(), y_ref, d, f"rows kernel, bias + rectifier {case}")
+
+
 BIAS_RELU_CASES = [
     # N, C_in, C_out, H, W, R, S, stride, pad
     (8, 16, 256, 56, 56, 3, 3, 1, 1),    # enough large tiles for the fixed 3x3 matrix-core kernel (256 workgroups)
-    (4, 16, 256, 56, 56, 5, 5, 1, 2),    # ... and the 5x5 one
+    (4, 16, 256, 56, 56, 5, 5, 1, 2),    # 5x5: the compound (filter-row) kernel
     (2, 16, 64, 56, 56, 3, 3, 1, 1),     # 128-pixel tiles, channel quads
     (1, 3, 5, 9, 11, 3, 3, 1, 1),        # any-shape kernel, ragged channel block
     (2, 4, 3, 12, 10, 2, 5, 2, 2),

@@ -28,6 +28,7 @@ sys.path.insert(0, ROOT)
 HBM_GBS = 8000.0
 MFMA_F32_TFLOPS = 157.3
 MFMA_I8_TOPS = 5000.0
+MFMA_BF16_TFLOPS = 2500.0
 VALU_F32_TFLOPS = 78.6     # 256 CU x 4 SIMD x 16 lanes x 2 flop x 2.4 GHz, no packed FP32
 
 
@@ -310,6 +311,12 @@ LAYERS = [
     ("block_two_launches_256to256_28x28", "block2", (32, 256, 28, 28), 3, 1, 1, 256),
     ("block_dw3x3_pw_512to512_14x14", "block", (32, 512, 14, 14), 3, 1, 1, 512),
     ("block_two_launches_512to512_14x14", "block2", (32, 512, 14, 14), 3, 1, 1, 512),
+    ("conv_nhwc_3x3_64to64", "conv_nhwc", (32, 64, 56, 56), 3, 1, 1, 64),              # channel-last fp32
+    ("conv_nhwc_3x3_128to128_28x28", "conv_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
+    ("conv_bf16_nhwc_3x3_64to64", "conv_bf16_nhwc", (32, 64, 56, 56), 3, 1, 1, 64),    # channel-last bf16, fp32 accumulation
+    ("conv_bf16_nhwc_3x3_128to128_28x28", "conv_bf16_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
+    ("conv_bf16_nhwc_3x3_s2_64to128", "conv_bf16_nhwc", (32, 64, 56, 56), 3, 2, 1, 128),
+    ("conv_bf16_nhwc_1x1_256to64", "conv_bf16_nhwc", (32, 256, 56, 56), 1, 1, 0, 64),
     ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
     ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
     ("conv_s8_requant_3x3_128to128", "conv_s8_rq", (32, 128, 28, 28), 3, 1, 1, 128),
@@ -370,6 +377,12 @@ def layer_case(idx, n_images=None, data=True):
         w = inputs.normal_f32((c["C_out"], C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
         if kind == "conv_br":
             c["bias"] = inputs.normal_f32((c["C_out"],), inputs.seed_for(7, 200 + idx), 0.5)
+        if kind == "conv_bf16_nhwc":        # (the same draws, truncated to bf16 bit patterns)
+            x = inputs.normal_bf16((N, C, H, W), inputs.seed_for(7, idx))
+            w = inputs.normal_bf16((c["C_out"], C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
+        if "nhwc" in kind:
+            x = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
+            w = np.ascontiguousarray(w.transpose(0, 2, 3, 1))
     else:
         x = inputs.normal_f32((N, C, H, W), inputs.seed_for(7, idx))
         w = inputs.normal_f32((C, 1, R, R), inputs.seed_for(7, 100 + idx), 1.0 / R) if kind.startswith("dw") else None
@@ -389,12 +402,13 @@ def layer_device(torch, c):
         return None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
     x = c["x"]
-    xd = torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16) if c["kind"] == "dw_bf16" else dev(x)
     kind = c["kind"]
-    odt = (torch.bfloat16 if kind == "dw_bf16" else torch.int8 if kind.endswith("rq") else
+    as_bf16 = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
+    xd = as_bf16(x) if kind in ("dw_bf16", "conv_bf16_nhwc") else dev(x)
+    odt = (torch.bfloat16 if kind in ("dw_bf16", "conv_bf16_nhwc") else torch.int8 if kind.endswith("rq") else
            torch.int32 if kind.startswith("conv_s8") else torch.float32)
     oshape = ((c["N"], c["Ho"], c["Wo"], c["C_out"]) if "nhwc" in kind else (c["N"], c["C_out"], c["Ho"], c["Wo"]))
-    d = {"x": xd, "w": dev(c["w"]), "bias": dev(c.get("bias")), "scale": dev(c.get("scale")),
+    d = {"x": xd, "w": as_bf16(c["w"]) if kind == "conv_bf16_nhwc" else dev(c["w"]), "bias": dev(c.get("bias")), "scale": dev(c.get("scale")),
          "y": torch.empty(oshape, dtype=odt, device="cuda")}
     if kind.startswith("block"):
         d["w_pw"], d["bias_pw"] = dev(c["w_pw"]), dev(c["bias_pw"])
@@ -429,6 +443,8 @@ def layer_call(sw, c, d, x=None, y=None):
         return sw.sw_conv2d_bias_relu(x, d["w"], d["bias"], st, p, True, out=y)
     if kind == "conv_dil":
         return sw.sw_conv2d_dilated(x, d["w"], st, p, c["dil"], out=y)
+    if kind in ("conv_nhwc", "conv_bf16_nhwc"):
+        return sw.sw_conv2d_nhwc(x, d["w"], st, p, 1, out=y)
     if kind == "conv_s8":
         return sw.sw_conv2d_s8(x, d["w"], st, p, out=y)
     if kind == "conv_s8_rq":
@@ -475,7 +491,8 @@ def strided_and_pooling_table(torch, sw):
                "us_cold": round(us, 2), "gbs": round(nbytes / us / 1e3, 1),
                "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4), "gops": round(ops / us / 1e3, 1)}
         if kind.startswith("conv") or kind.startswith("block"):
-            row["frac_mfma"] = round(ops / us / 1e6 / (MFMA_I8_TOPS if "s8" in kind else MFMA_F32_TFLOPS), 4)
+            row["frac_mfma"] = round(ops / us / 1e6 / (MFMA_I8_TOPS if "s8" in kind else MFMA_BF16_TFLOPS if "bf16" in kind
+                                                       else MFMA_F32_TFLOPS), 4)
         rows.append(row)
         del sets, d
         torch.cuda.empty_cache()

@@ -321,6 +321,31 @@ int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* b
                               int N, int H, int W, int C_in, int C_out, int R, int S,
                               int stride, int pad, int relu, void* hip_stream);
 
+/*
+ * The multi-channel convolution on channel-last tensors in fp32 and in bf16 (paper,
+ * section 3: the taps as small matrix products; section 1.1: reduced precision):
+ *     x: [N,H,W,C_in];  w: [C_out,R,S,C_in];  y: [N,H_out,W_out,C_out];
+ *     y[n,i,j,co] = act(sum_{r,s,ci} w[co,r,s,ci] * xz[n, i*stride+r*dilation-pad, j*stride+s*dilation-pad, ci] + bias[co])
+ * with act(t) = relu ? max(t, 0) : t, bias: [C_out] fp32 device pointer or NULL,
+ * dilation >= 1, H_out = sw_out_dim_dilated(H, R, stride, pad, dilation).
+ * sw_conv2d_nhwc: fp32 tensors, fp32 products and sums (any order), one fp32 addition
+ * of the bias.  sw_conv2d_bf16_nhwc: x, w and y hold bf16 bit patterns (2-byte
+ * aligned); products and sums are fp32 (a product of two bf16 values is exact in
+ * fp32: bf16 matrix instructions with fp32 accumulators), the bias is added in fp32,
+ * and the finished value is rounded once to bf16, to nearest, ties to even.
+ * Note the argument order (H, W before the channel counts).  Errors as sw_conv2d.
+ * Pixels of a multiple of 32 bytes (C_in % 8 == 0 in fp32, % 16 in bf16) and 16-byte
+ * aligned x and w run on the matrix cores, the channels in chunks of up to 128 bytes
+ * per pixel (any extent, stride, dilation and C_out); every other valid shape one
+ * thread per output.
+ */
+int sw_conv2d_nhwc(const float* x, const float* w, const float* bias, float* y,
+                   int N, int H, int W, int C_in, int C_out, int R, int S,
+                   int stride, int pad, int dilation, int relu, void* hip_stream);
+int sw_conv2d_bf16_nhwc(const void* x, const void* w, const float* bias, void* y,
+                        int N, int H, int W, int C_in, int C_out, int R, int S,
+                        int stride, int pad, int dilation, int relu, void* hip_stream);
+
 /* Output extent of one axis; <= 0 means the filter does not fit (or bad arguments). */
 int64_t sw_out_dim(int64_t in, int k, int stride, int pad);
 

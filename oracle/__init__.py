@@ -305,6 +305,35 @@ def conv2d_s8_nhwc_requant(x, w, bias, scale, stride: int = 1, pad: int = 0, rel
     return np.ascontiguousarray(q.transpose(0, 2, 3, 1))
 
 
+def conv2d_nhwc(x, w, stride: int = 1, pad: int = 0, dilation: int = 1, bias=None, relu: bool = False):
+    """The fp32 convolution on channel-last tensors, in fp64: x [N,H,W,C_in], w [C_out,R,S,C_in] ->
+    (y, D) [N,H_out,W_out,C_out], y = act(conv + bias[co]).  Only the axes are permuted around conv2d_dilated and
+    the oracle_bias_relu step (a change of layout, no arithmetic of its own)."""
+    x = _as(x, np.float32, 4)
+    w = _as(w, np.float32, 4)
+    y, d = conv2d_dilated(np.ascontiguousarray(x.transpose(0, 3, 1, 2)), np.ascontiguousarray(w.transpose(0, 3, 1, 2)),
+                          stride, pad, dilation)
+    if bias is not None or relu:
+        N, C_out, Ho, Wo = y.shape
+        if bias is not None:
+            bias = _as(bias, np.float32, 1)
+            if bias.shape[0] != C_out:
+                raise ValueError("one bias per output channel")
+        rc = _load().oracle_bias_relu(_p(y), _p(d), _p(bias) if bias is not None else None, N, C_out, Ho * Wo,
+                                      1 if relu else 0)
+        if rc:
+            raise ValueError(f"oracle_bias_relu rejected the arguments (code {rc})")
+    return np.ascontiguousarray(y.transpose(0, 2, 3, 1)), np.ascontiguousarray(d.transpose(0, 2, 3, 1))
+
+
+def conv2d_bf16_nhwc(x_bits, w_bits, stride: int = 1, pad: int = 0, dilation: int = 1, bias=None, relu: bool = False):
+    """The same for bf16 tensors given as bit patterns (uint16): both are widened to fp32 (exact), the sums are
+    taken in fp64; returns the unrounded (y, D) -- the one rounding of the finished sum to bf16 is the caller's
+    to account for (f32_to_bf16_rne gives the nearest-even pattern)."""
+    return conv2d_nhwc(bf16_to_f32(np.asarray(x_bits, np.uint16)), bf16_to_f32(np.asarray(w_bits, np.uint16)), stride, pad,
+                       dilation, bias, relu)
+
+
 def dw_pw_block(x, w_dw, b_dw, w_pw, b_pw, relu_dw: bool = True, relu_pw: bool = False):
     """A depthwise-separable block in fp64: t = act_dw(depthwise3x3(x, stride 1, pad 1) + b_dw), then
     y = act_pw(sum_c w_pw[co, c] * t[c] + b_pw[co]).  The depthwise stage is conv2d_depthwise_bias_relu; the pointwise

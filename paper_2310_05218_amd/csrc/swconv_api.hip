@@ -298,6 +298,34 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, 
     return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
 }
 
+// fp32 (esz 4) / bf16 (esz 2) convolution on channel-last tensors with the store's epilogue
+static int run_nhwc(const void* x, const void* w, const float* bias, void* y, int N, int H, int W, int C_in, int C_out,
+                    int R, int S, int stride, int pad, int dilation, int relu, int esz, void* hip_stream)
+{
+    Conv2dShape s;
+    const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, (size_t)esz, (size_t)esz, &s,
+                                dilation);
+    if (rc != SW_OK) return rc;
+    if (bias && misaligned(bias, 4)) return SW_ERR_ALIGN;
+    if (bias && overlaps(y, (int64_t)N * C_out * s.Ho * s.Wo * esz, bias, (int64_t)C_out * 4)) return SW_ERR_ALIAS;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const Epilogue ep{bias, relu != 0};
+    if (!force_direct() && mfma_nhwc_supported(x, w, s, esz)) return launch_status(launch_mfma_nhwc(x, w, y, s, esz, ep, st));
+    return launch_status(launch_direct_nhwc(x, w, y, s, esz, ep, st));
+}
+
+int sw_conv2d_nhwc(const float* x, const float* w, const float* bias, float* y, int N, int H, int W, int C_in, int C_out,
+                   int R, int S, int stride, int pad, int dilation, int relu, void* hip_stream)
+{
+    return run_nhwc(x, w, bias, y, N, H, W, C_in, C_out, R, S, stride, pad, dilation, relu, 4, hip_stream);
+}
+
+int sw_conv2d_bf16_nhwc(const void* x, const void* w, const float* bias, void* y, int N, int H, int W, int C_in, int C_out,
+                        int R, int S, int stride, int pad, int dilation, int relu, void* hip_stream)
+{
+    return run_nhwc(x, w, bias, y, N, H, W, C_in, C_out, R, S, stride, pad, dilation, relu, 2, hip_stream);
+}
+
 // int8 convolution on channel-last tensors; bias/scale == nullptr and y8 == nullptr: int32 sums
 static int run_s8_nhwc(const int8_t* x, const int8_t* w, const int32_t* bias, const float* scale, int32_t* y, int8_t* y8,
                        int N, int H, int W, int C_in, int C_out, int R, int S, int stride, int pad, int relu,

@@ -112,6 +112,13 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0}, int dil = 1);
 
+// ---- fp32 / bf16 multi-channel convolution on channel-last tensors (esz: 4 or 2 bytes per element) ----------
+bool       mfma_nhwc_supported(const void* x, const void* w, const Conv2dShape& s, int esz);
+hipError_t launch_mfma_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int esz, const Epilogue& ep,
+                            hipStream_t st);
+hipError_t launch_direct_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int esz, const Epilogue& ep,
+                              hipStream_t st);
+
 // ---- depthwise 3x3 (stride 1, padding 1) -> pointwise 1x1 in one launch, the intermediate only in LDS
 bool       dw_pw_block_supported(int N, int C, int C_out, int H, int W);
 hipError_t launch_dw_pw_block(const float* x, const float* w_dw, const float* b_dw, const float* w_pw, const float* b_pw,

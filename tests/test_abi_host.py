@@ -290,3 +290,22 @@ def test_binding_refuses_host_tensors(L):
     w = torch.zeros(3)
     with pytest.raises(ValueError):
         B.sw_conv1d(x, w)
+
+
+def test_float_nhwc_argument_errors(L):
+    for f, esz in ((L.sw_conv2d_nhwc, 4), (L.sw_conv2d_bf16_nhwc, 2)):
+        B_ = 0x2100000
+        ok = (2, 8, 8, 32, 64, 3, 3, 1, 1, 1)      # N, H, W, C_in, C_out, R, S, stride, pad, dilation
+        assert f(None, W_, None, Y, *ok, 0, None) == B.SW_ERR_NULL
+        assert f(X, None, None, Y, *ok, 0, None) == B.SW_ERR_NULL
+        assert f(X, W_, None, None, *ok, 0, None) == B.SW_ERR_NULL
+        for i in (0, 1, 2, 3, 4, 5, 6, 7, 9):       # every extent, the stride and the dilation
+            bad = list(ok)
+            bad[i] = 0
+            assert f(X, W_, None, Y, *bad, 0, None) == B.SW_ERR_SHAPE, i
+        assert f(X, W_, None, Y, 2, 8, 8, 32, 64, 3, 3, 1, 1, 5, 0, None) == B.SW_ERR_SHAPE   # span 11 > 8 + 2
+        assert f(X + 1, W_, None, Y, *ok, 0, None) == B.SW_ERR_ALIGN
+        assert f(X, W_, None, Y + esz // 2, *ok, 0, None) == B.SW_ERR_ALIGN
+        assert f(X, W_, B_ + 2, Y, *ok, 0, None) == B.SW_ERR_ALIGN                             # the fp32 bias
+        assert f(X, W_, None, X + 64, *ok, 0, None) == B.SW_ERR_ALIAS
+        assert f(X, W_, Y + 16, Y, *ok, 0, None) == B.SW_ERR_ALIAS

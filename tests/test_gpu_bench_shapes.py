@@ -158,6 +158,12 @@ def test_layer(torch, sw, oracle, idx):
         assert_f32_parity(y.cpu().numpy(), *oracle.conv2d_bias_relu(x, w, c["bias"], st, p, True), name)
     elif kind == "conv_dil":
         assert_f32_parity(y.cpu().numpy(), *oracle.conv2d_dilated(x, w, st, p, c["dil"]), name)
+    elif kind == "conv_nhwc":
+        assert_f32_parity(y.cpu().numpy(), *oracle.conv2d_nhwc(x, w, st, p), name)
+    elif kind == "conv_bf16_nhwc":
+        y_ref, mag = oracle.conv2d_bf16_nhwc(x, w, st, p)
+        yv = oracle.bf16_to_f32(y.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        assert np.all(np.abs(yv - y_ref) <= 2e-5 * mag + 2.0 ** -8 * np.abs(y_ref) + 1e-37), name
     elif kind in ("conv_s8", "conv_s8_pk"):
         assert np.array_equal(y.cpu().numpy(), oracle.conv2d_s8(x, w, st, p)), name
     elif kind in ("conv_s8_rq", "conv_s8_pk_rq"):

@@ -99,3 +99,77 @@ def test_s8_nhwc_full_size_agrees_with_the_channel_first_call(torch, sw, oracle)
     assert torch.equal(y_cl.permute(0, 3, 1, 2), y_cf)
     for n in (0, 31):
         assert np.array_equal(y_cf[n:n + 1].cpu().numpy(), oracle.conv2d_s8(x[n:n + 1], w, 1, 1))
+
+
+# ----------------------------------------------------------------------------- fp32 and bf16, channel-last
+
+FLOAT_CASES = [
+    # N, H, W, C_in, C_out, R, S, stride, pad, dilation, kernel for fp32, kernel for bf16
+    (2, 28, 28, 64, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),    # two fp32 chunks of 32 channels, one bf16 chunk
+    (1, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,2>"),    # 4-row bands (224 pixels)
+    (2, 14, 14, 128, 96, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),   # four / two chunks, ragged channel block
+    (2, 30, 41, 16, 40, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),    # blocks that span rows, ragged last block
+    (1, 57, 57, 64, 128, 3, 3, 2, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),   # stride 2
+    (1, 20, 20, 16, 32, 5, 5, 1, 2, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),    # 25 taps: two rounds of filter pieces
+    (1, 12, 12, 48, 64, 7, 7, 1, 3, 1, "mfma_nhwc_kernel<0,1>", "mfma_nhwc_kernel<1,1>"),    # 49 taps: LDS bounds the chunk
+    (2, 19, 23, 64, 70, 1, 1, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),    # pointwise
+    (1, 33, 17, 16, 5, 7, 3, 2, 3, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),     # rectangular filter, few output channels
+    (1, 28, 28, 32, 64, 3, 3, 1, 2, 2, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,2>"),    # dilation 2
+    (1, 40, 40, 16, 64, 3, 3, 2, 6, 6, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),    # dilation 6 with stride 2
+    (1, 9, 300, 16, 64, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "direct_nhwc_kernel<1>"),    # rows wider than 256 outputs
+    (1, 12, 12, 12, 16, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "direct_nhwc_kernel<1>"),    # pixels that are not whole K steps
+    (1, 12, 12, 8, 16, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,1>", "direct_nhwc_kernel<1>"),     # 32 bytes per pixel in fp32, 16 in bf16
+    (1, 5, 5, 16, 8, 5, 5, 1, 0, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),       # a single output pixel
+]
+
+
+@pytest.mark.parametrize("case", FLOAT_CASES, ids=lambda c: "x".join(map(str, c[:10])))
+def test_conv2d_nhwc_fp32(torch, sw, oracle, case):
+    N, H, W, C_in, C_out, R, S, stride, pad, dil, kernel, _ = case
+    x = inputs.normal_f32((N, H, W, C_in), 5201)
+    w = inputs.normal_f32((C_out, R, S, C_in), 5202, (2.0 / (C_in * R * S)) ** 0.5)
+    b = inputs.normal_f32((C_out,), 5203, 0.5)
+    for bias, relu in ((None, False), (b, True)):
+        y_ref, d = oracle.conv2d_nhwc(x, w, stride, pad, dil, bias, relu)
+        buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+        sw.sw_conv2d_nhwc(dev(torch, x), dev(torch, w), stride, pad, dil, None if bias is None else dev(torch, bias), relu,
+                          out=out)
+        assert sw.sw_last_kernel() == kernel, sw.sw_last_kernel()
+        torch.cuda.synchronize()
+        assert_guards_intact(buf, front, n, s)
+        err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - y_ref) / np.maximum(d, 1e-300)))
+        assert err <= 2e-5, f"nhwc fp32 {case} relu={relu}: normalised error {err:.3e}"
+
+
+@pytest.mark.parametrize("case", FLOAT_CASES, ids=lambda c: "x".join(map(str, c[:10])))
+def test_conv2d_nhwc_bf16(torch, sw, oracle, case):
+    """bf16 in and out, fp32 accumulation: |y - oracle| <= 2e-5 * D (the fp32 sums) + 2^-8 |oracle| (one rounding of the
+    result to bf16: half a unit in the last of 8 significant bits)."""
+    N, H, W, C_in, C_out, R, S, stride, pad, dil, _, kernel = case
+    xb = inputs.normal_bf16((N, H, W, C_in), 5211)
+    wb = inputs.normal_bf16((C_out, R, S, C_in), 5212, (2.0 / (C_in * R * S)) ** 0.5)
+    b = inputs.normal_f32((C_out,), 5213, 0.5)
+    as_bf16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    for bias, relu in ((None, False), (b, True)):
+        y_ref, d = oracle.conv2d_bf16_nhwc(xb, wb, stride, pad, dil, bias, relu)
+        n = y_ref.size
+        buf = torch.full((128 + n + 64,), 12345.0, dtype=torch.bfloat16, device="cuda")
+        out = buf[128:128 + n].view(y_ref.shape)
+        sw.sw_conv2d_bf16_nhwc(as_bf16(xb), as_bf16(wb), stride, pad, dil, None if bias is None else dev(torch, bias), relu,
+                               out=out)
+        assert sw.sw_last_kernel() == kernel, sw.sw_last_kernel()
+        torch.cuda.synchronize()
+        guard = buf.view(torch.int16)
+        assert bool((guard[:128] == guard[0]).all()) and bool((guard[128 + n:] == guard[0]).all()), "write outside y"
+        y = oracle.bf16_to_f32(out.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        assert np.all(np.abs(y - y_ref) <= 2e-5 * d + 2.0 ** -8 * np.abs(y_ref) + 1e-37), \
+            f"nhwc bf16 {case} relu={relu}: max excess {np.max(np.abs(y - y_ref) - 2e-5 * d - 2.0 ** -8 * np.abs(y_ref)):.3e}"
+
+
+def test_nhwc_is_the_channel_first_call_on_permuted_tensors(torch, sw):
+    """Same sums, other layout: the two fp32 entry points agree to rounding order on a layer both take."""
+    x = inputs.normal_f32((2, 64, 28, 28), 5221)
+    w = inputs.normal_f32((64, 64, 3, 3), 5222, 0.06)
+    y_cf = sw.sw_conv2d(dev(torch, x), dev(torch, w), 1, 1).cpu().numpy()
+    y_cl = sw.sw_conv2d_nhwc(dev(torch, x.transpose(0, 2, 3, 1)), dev(torch, w.transpose(0, 2, 3, 1)), 1, 1).cpu().numpy()
+    assert np.allclose(y_cl.transpose(0, 3, 1, 2), y_cf, rtol=0, atol=2e-5 * 40)

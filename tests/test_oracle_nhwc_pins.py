@@ -38,3 +38,48 @@ def test_channel_last_brute_force(oracle):
                         if 0 <= h < H and 0 <= v < W:
                             ref[n, i, j] += w[:, r, s, :].astype(np.int64) @ x[n, h, v].astype(np.int64)
     assert np.array_equal(y, ref)
+
+
+def test_hand_worked_channel_last_float_example(oracle):
+    # the same 1 x 2 image with 3 channels in fp32; dilation 1 and a bias + rectifier
+    x = np.array([[[[1, 2, 3], [4, 5, 6]]]], np.float32)
+    w = np.array([[[[1, 10, 100]]], [[[-1, 0, 2]]]], np.float32)
+    y, d = oracle.conv2d_nhwc(x, w, 1, 0)
+    assert y[0, 0].tolist() == [[321.0, 5.0], [654.0, 8.0]] and d[0, 0].tolist() == [[321.0, 7.0], [654.0, 16.0]]
+    y, d = oracle.conv2d_nhwc(x, w, 1, 0, 1, np.array([-400.0, 1.5], np.float32), True)
+    assert y[0, 0].tolist() == [[0.0, 6.5], [254.0, 9.5]] and d[0, 0].tolist() == [[721.0, 8.5], [1054.0, 17.5]]
+    # a 1 x 2 filter at dilation 2 over a row of four pixels: taps two pixels apart, channels innermost
+    x4 = np.arange(1, 13, dtype=np.float32).reshape(1, 1, 4, 3)            # pixels (1,2,3) (4,5,6) (7,8,9) (10,11,12)
+    w2 = np.array([[[[1, 0, 0], [0, 0, 10]]]], np.float32)                 # x[., j, c0] + 10 * x[., j + 2, c2]
+    y, _ = oracle.conv2d_nhwc(x4, w2, 1, 0, 2)
+    assert y.tolist() == [[[[91.0], [124.0]]]]
+    # bf16 bit patterns: 0x3F80 = 1, 0x4000 = 2, 0xC040 = -3; widened exactly, summed in fp64, not rounded
+    xb = np.array([[[[0x3F80, 0x4000]]]], np.uint16)
+    wb = np.array([[[[0x4000, 0xC040]]]], np.uint16)
+    y, d = oracle.conv2d_bf16_nhwc(xb, wb, 1, 0)
+    assert y.tolist() == [[[[-4.0]]]] and d.tolist() == [[[[8.0]]]]
+
+
+def test_channel_last_float_brute_force(oracle):
+    rng = np.random.default_rng(5151)
+    N, H, W, Ci, Co, R, S, stride, pad, dil = 2, 9, 8, 3, 4, 3, 2, 2, 2, 2
+    x = rng.integers(-8, 9, size=(N, H, W, Ci)).astype(np.float32)          # small integers: every sum is exact
+    w = rng.integers(-8, 9, size=(Co, R, S, Ci)).astype(np.float32)
+    b = rng.integers(-20, 21, size=Co).astype(np.float32)
+    y, d = oracle.conv2d_nhwc(x, w, stride, pad, dil, b, True)
+    Ho, Wo = (H + 2 * pad - (dil * (R - 1) + 1)) // stride + 1, (W + 2 * pad - (dil * (S - 1) + 1)) // stride + 1
+    assert y.shape == (N, Ho, Wo, Co)
+    ref = np.zeros((N, Ho, Wo, Co), np.int64)
+    mag = np.zeros((N, Ho, Wo, Co), np.int64)
+    for n in range(N):
+        for i in range(Ho):
+            for j in range(Wo):
+                for r in range(R):
+                    for s in range(S):
+                        h, v = i * stride + r * dil - pad, j * stride + s * dil - pad
+                        if 0 <= h < H and 0 <= v < W:
+                            ref[n, i, j] += w[:, r, s, :].astype(np.int64) @ x[n, h, v].astype(np.int64)
+                            mag[n, i, j] += np.abs(w[:, r, s, :]).astype(np.int64) @ np.abs(x[n, h, v]).astype(np.int64)
+    ref += b.astype(np.int64)
+    mag += np.abs(b).astype(np.int64)
+    assert np.array_equal(y, np.maximum(ref, 0)) and np.array_equal(d, mag)

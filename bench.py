@@ -305,6 +305,11 @@ LAYERS = [
     ("conv_3x3_dilation2_64to64", "conv_dil", (32, 64, 56, 56), 3, 1, 2, 64),
     ("depthwise_3x3_dilation2", "dw_dil", (32, 256, 56, 56), 3, 1, 2, 2),       # (last entry: the dilation)
     ("depthwise_3x3_dilation6", "dw_dil", (32, 256, 56, 56), 3, 1, 6, 6),
+    ("depthwise_3x3_dilation2_generated", "dw_dil_jit", (32, 256, 56, 56), 3, 1, 2, 2),   # kernels generated at run time
+    ("depthwise_3x3_dilation6_generated", "dw_dil_jit", (32, 256, 56, 56), 3, 1, 6, 6),
+    ("depthwise_3x3_s2_56x56", "dw", (32, 256, 56, 56), 3, 2, 1),
+    ("depthwise_3x3_s2_56x56_generated", "dw_dil_jit", (32, 256, 56, 56), 3, 2, 1, 1),
+    ("depthwise_5x5_s2_56x56_generated", "dw_dil_jit", (32, 256, 56, 56), 5, 2, 2, 1),
     ("block_dw3x3_pw_128to128_56x56", "block", (32, 128, 56, 56), 3, 1, 1, 128),
     ("block_two_launches_128to128_56x56", "block2", (32, 128, 56, 56), 3, 1, 1, 128),
     ("block_dw3x3_pw_256to256_28x28", "block", (32, 256, 28, 28), 3, 1, 1, 256),
@@ -352,8 +357,8 @@ def layer_case(idx, n_images=None, data=True):
     if n_images is not None:
         N = n_images
     c = {"name": name, "kind": kind, "N": N, "C": C, "H": H, "W": W, "R": R, "stride": stride, "pad": pad,
-         "dil": more[0] if kind == "dw_dil" else 2 if kind == "conv_dil" else 1,
-         "C_out": more[0] if more and kind != "dw_dil" else C}
+         "dil": more[0] if kind.startswith("dw_dil") else 2 if kind == "conv_dil" else 1,
+         "C_out": more[0] if more and not kind.startswith("dw_dil") else C}
     span = c["dil"] * (R - 1) + 1
     c["Ho"], c["Wo"] = (H + 2 * pad - span) // stride + 1, (W + 2 * pad - span) // stride + 1
     rng = np.random.default_rng(inputs.seed_for(7, 200 + idx))
@@ -428,6 +433,8 @@ def layer_call(sw, c, d, x=None, y=None):
         return sw.sw_conv2d_depthwise(x, d["w"], st, p, out=y)
     if kind == "dw_dil":
         return sw.sw_conv2d_depthwise_dilated(x, d["w"], st, p, c["dil"], out=y)
+    if kind == "dw_dil_jit":
+        return sw.sw_conv2d_depthwise_dilated_jit(x, d["w"], st, p, c["dil"], out=y)
     if kind == "dw_br":
         return sw.sw_conv2d_depthwise_bias_relu(x, d["w"], d["bias"], st, p, True, out=y)
     if kind == "dw_bf16":

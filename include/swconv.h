@@ -265,9 +265,10 @@ int sw_conv2d_depthwise_dilated(const float* x, const float* w, float* y,
 /*
  * Depthwise 2-D convolution through a kernel generated at run time (paper, section 2:
  * custom kernels generated at run time for every filter size).  Arguments, layouts,
- * result and errors as sw_conv2d_depthwise.  For stride 1, an output plane of at
- * most 56 x 56 (and at least half of that), W and W_out multiples of 4, H*W <= 4096,
- * 2*pad <= min(R,S)-1, an LDS window (55+R rows) of at most 37 KB (33 x 33 at 56 x 56)
+ * result and errors as sw_conv2d_depthwise.  For stride 1 or 2, an output plane of at
+ * most 56 x 56 (at least 9 x 9, and at least half of the 8 x 8 lane grid's share), W and W_out
+ * multiples of 4, H*W <= 4096, H_out <= H and W_out <= W, an LDS window of at most 37 KB
+ * (33 x 33 at 56 x 56)
  * and x, y 16-byte aligned, the first
  * call for a geometry (H, W, R, S, pad) compiles a kernel specialised on it (about a
  * second on the calling thread, host-synchronous; do not make that first call inside
@@ -297,6 +298,22 @@ int sw_jit_prepare_depthwise(int H, int W, int R, int S, int stride, int pad);
  * nothing): tells whether the generated source builds for a geometry.
  */
 int sw_jit_compile_check(int H, int W, int R, int S, int stride, int pad);
+
+/*
+ * The generated kernels with strides and dilations (paper, section 2: a custom kernel
+ * for every filter; figure 2 names strided and dilated variants): as the three calls
+ * above with taps `dilation` input positions apart (dilation == 1: the same calls).
+ * Generated for stride 1 and 2 and any dilation whose span (R-1)*dilation+1 is at most
+ * 64: the 8 x 8 lanes of a wavefront own ceil(max(H_out, W_out) / 8)^2 outputs each, the
+ * stride and the dilation are constants of the register slide.  The other limits are
+ * those of sw_conv2d_depthwise_jit (output plane at most 56 x 56 and at least 9 x 9,
+ * H*W <= 4096, W and W_out multiples of 4, LDS window at most 37 KB).
+ */
+int sw_conv2d_depthwise_dilated_jit(const float* x, const float* w, float* y,
+                                    int N, int C, int H, int W, int R, int S,
+                                    int stride, int pad, int dilation, void* hip_stream);
+int sw_jit_prepare_depthwise_dilated(int H, int W, int R, int S, int stride, int pad, int dilation);
+int sw_jit_compile_check_dilated(int H, int W, int R, int S, int stride, int pad, int dilation);
 
 /* Number of generated kernels this process holds. */
 int sw_jit_cached_kernels(void);

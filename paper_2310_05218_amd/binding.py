@@ -19,6 +19,7 @@ SW_POOL_AVG, SW_POOL_MAX = 0, 1
 EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
            "sw_conv2d_s8_requant", "sw_conv2d_s8_nhwc", "sw_conv2d_s8_nhwc_requant", "sw_conv2d_nhwc", "sw_conv2d_bf16_nhwc", "sw_conv2d_bias_relu", "sw_dw_pw_block", "sw_conv2d_depthwise_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
            "sw_conv2d_depthwise_bf16", "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
+           "sw_conv2d_depthwise_dilated_jit", "sw_jit_prepare_depthwise_dilated", "sw_jit_compile_check_dilated",
            "sw_jit_cached_kernels",
            "sw_s8_packed_filter_bytes", "sw_s8_pack_filter", "sw_conv2d_s8_packed", "sw_conv2d_s8_packed_requant",
            "sw_probe", "sw_probe_ops", "sw_out_dim", "sw_out_dim_dilated", "sw_workspace_bytes", "sw_status_string", "sw_version", "sw_last_kernel")
@@ -68,6 +69,11 @@ def lib() -> ctypes.CDLL:
     for name in ("sw_jit_prepare_depthwise", "sw_jit_compile_check"):
         getattr(L, name).restype = i32
         getattr(L, name).argtypes = [i32] * 6
+    L.sw_conv2d_depthwise_dilated_jit.restype = i32
+    L.sw_conv2d_depthwise_dilated_jit.argtypes = [vp, vp, vp] + [i32] * 9 + [vp]
+    for name in ("sw_jit_prepare_depthwise_dilated", "sw_jit_compile_check_dilated"):
+        getattr(L, name).restype = i32
+        getattr(L, name).argtypes = [i32] * 7
     L.sw_jit_cached_kernels.restype = i32
     L.sw_jit_cached_kernels.argtypes = []
     L.sw_conv2d_s8.restype = i32
@@ -469,6 +475,34 @@ def sw_conv2d_depthwise_jit(x, w, stride: int = 1, pad: int = 0, out=None, strea
                                        _stream(stream))
     _check(rc, "sw_conv2d_depthwise_jit")
     return out
+
+
+def sw_conv2d_depthwise_dilated_jit(x, w, stride: int = 1, pad: int = 0, dilation: int = 1, out=None, stream=None):
+    """sw_conv2d_depthwise_dilated through a kernel generated at run time for the geometry (stride 1 or 2, any dilation)."""
+    import torch
+
+    N, C, H, W = x.shape
+    Cw, one, R, S = w.shape
+    if Cw != C or one != 1:
+        raise ValueError("depthwise weights must be [C,1,R,S]")
+    if out is None:
+        out = torch.empty(_out_shape("sw_conv2d_depthwise_dilated_jit", N, C, sw_out_dim_dilated(H, R, stride, pad, dilation),
+                                     sw_out_dim_dilated(W, S, stride, pad, dilation)), dtype=torch.float32, device=x.device)
+    rc = lib().sw_conv2d_depthwise_dilated_jit(_dev(x, torch.float32, 4, "x"), _dev(w, torch.float32, 4, "w"),
+                                               _dev(out, torch.float32, 4, "y"), N, C, H, W, R, S, stride, pad, dilation,
+                                               _stream(stream))
+    _check(rc, "sw_conv2d_depthwise_dilated_jit")
+    return out
+
+
+def sw_jit_prepare_depthwise_dilated(H: int, W: int, R: int, S: int, stride: int = 1, pad: int = 0, dilation: int = 1) -> int:
+    """Compile and load the generated kernel of a strided / dilated geometry ahead of its first use; a status code."""
+    return int(lib().sw_jit_prepare_depthwise_dilated(H, W, R, S, stride, pad, dilation))
+
+
+def sw_jit_compile_check_dilated(H: int, W: int, R: int, S: int, stride: int = 1, pad: int = 0, dilation: int = 1) -> int:
+    """Compile only (no device needed): does the generated source build for the geometry?  A status code."""
+    return int(lib().sw_jit_compile_check_dilated(H, W, R, S, stride, pad, dilation))
 
 
 def sw_jit_prepare_depthwise(H: int, W: int, R: int, S: int, stride: int = 1, pad: int = 0) -> int:

@@ -408,32 +408,54 @@ int sw_conv2d_depthwise_bf16(const uint16_t* x, const float* w, uint16_t* y, int
     return launch_status(launch_direct_depthwise_bf16(x, w, y, s, st));
 }
 
-int sw_conv2d_depthwise_jit(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,
-                            int stride, int pad, void* hip_stream)
+int sw_conv2d_depthwise_dilated_jit(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,
+                                    int stride, int pad, int dilation, void* hip_stream)
 {
     Conv2dShape s;
-    const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s);
+    const int rc = check_conv2d(x, w, y, N, C, C, H, W, R, S, stride, pad, true, 4, 4, &s, dilation);
     if (rc != SW_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (!force_direct() && jit_plane_supported(x, y, H, W, R, S, stride, pad)) {
+    if (!force_direct() && jit_plane_supported(x, y, H, W, R, S, stride, pad, dilation)) {
         // a geometry whose generated kernel cannot be compiled or loaded is served by the precompiled kernels
-        if (jit_launch_plane(x, w, y, (int64_t)N * C, 1, C, H, W, R, S, stride, pad, st) == SW_OK) return SW_OK;
+        if (jit_launch_plane(x, w, y, (int64_t)N * C, 1, C, H, W, R, S, stride, pad, dilation, st) == SW_OK) return SW_OK;
     }
     return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
 }
 
+int sw_conv2d_depthwise_jit(const float* x, const float* w, float* y, int N, int C, int H, int W, int R, int S,
+                            int stride, int pad, void* hip_stream)
+{
+    return sw_conv2d_depthwise_dilated_jit(x, w, y, N, C, H, W, R, S, stride, pad, 1, hip_stream);
+}
+
+static int jit_geometry_ok(int H, int W, int R, int S, int stride, int pad, int dilation)
+{
+    if (H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0 || dilation <= 0) return SW_ERR_SHAPE;
+    if (sw_out_dim_dilated(H, R, stride, pad, dilation) <= 0 || sw_out_dim_dilated(W, S, stride, pad, dilation) <= 0)
+        return SW_ERR_SHAPE;
+    return SW_OK;
+}
+
+int sw_jit_prepare_depthwise_dilated(int H, int W, int R, int S, int stride, int pad, int dilation)
+{
+    const int rc = jit_geometry_ok(H, W, R, S, stride, pad, dilation);
+    return rc != SW_OK ? rc : jit_prepare_plane(H, W, R, S, stride, pad, dilation);
+}
+
 int sw_jit_prepare_depthwise(int H, int W, int R, int S, int stride, int pad)
 {
-    if (H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return SW_ERR_SHAPE;
-    if (sw_out_dim(H, R, stride, pad) <= 0 || sw_out_dim(W, S, stride, pad) <= 0) return SW_ERR_SHAPE;
-    return jit_prepare_plane(H, W, R, S, stride, pad);
+    return sw_jit_prepare_depthwise_dilated(H, W, R, S, stride, pad, 1);
+}
+
+int sw_jit_compile_check_dilated(int H, int W, int R, int S, int stride, int pad, int dilation)
+{
+    const int rc = jit_geometry_ok(H, W, R, S, stride, pad, dilation);
+    return rc != SW_OK ? rc : jit_compile_only(H, W, R, S, stride, pad, dilation);
 }
 
 int sw_jit_compile_check(int H, int W, int R, int S, int stride, int pad)
 {
-    if (H <= 0 || W <= 0 || R <= 0 || S <= 0 || stride <= 0 || pad < 0) return SW_ERR_SHAPE;
-    if (sw_out_dim(H, R, stride, pad) <= 0 || sw_out_dim(W, S, stride, pad) <= 0) return SW_ERR_SHAPE;
-    return jit_compile_only(H, W, R, S, stride, pad);
+    return sw_jit_compile_check_dilated(H, W, R, S, stride, pad, 1);
 }
 
 int sw_jit_cached_kernels(void) { return jit_cached_kernels(); }

@@ -140,12 +140,12 @@ hipError_t launch_direct_depthwise_bf16(const unsigned short* x, const float* w,
                                         const Conv2dShape& s, hipStream_t st);
 
 // ---- sw_jit.hip: one-filter-per-plane kernels compiled at run time, one per geometry (status codes) ------
-bool       jit_plane_supported(const float* x, const float* y, int H, int W, int R, int S, int stride, int pad);
-int        jit_prepare_plane(int H, int W, int R, int S, int stride, int pad);
-int        jit_compile_only(int H, int W, int R, int S, int stride, int pad);
+bool       jit_plane_supported(const float* x, const float* y, int H, int W, int R, int S, int stride, int pad, int dil = 1);
+int        jit_prepare_plane(int H, int W, int R, int S, int stride, int pad, int dil = 1);
+int        jit_compile_only(int H, int W, int R, int S, int stride, int pad, int dil = 1);
 int        jit_cached_kernels();
 int        jit_launch_plane(const float* x, const float* w, float* y, int64_t planes, int planes_per_x, int n_filters,
-                            int H, int W, int R, int S, int stride, int pad, hipStream_t st);
+                            int H, int W, int R, int S, int stride, int pad, int dil, hipStream_t st);
 
 // ---- depthwise on small planes (at most 1024 elements): a run of planes per workgroup through LDS --------
 bool       small_planes_supported(int64_t planes, int planes_per_x, int H, int W, int R, int S, int stride, int Ho,

@@ -144,7 +144,7 @@ def test_layer(torch, sw, oracle, idx):
         assert err <= 2e-5, (name, err)
     elif kind == "dw":
         assert_f32_parity(y.cpu().numpy(), *oracle.conv2d_depthwise(x, w, st, p), name)
-    elif kind == "dw_dil":
+    elif kind in ("dw_dil", "dw_dil_jit"):
         assert_f32_parity(y.cpu().numpy(), *oracle.conv2d_dilated(x, w, st, p, c["dil"], depthwise=True), name)
     elif kind == "dw_br":
         assert_f32_parity(y.cpu().numpy(), *oracle.conv2d_depthwise_bias_relu(x, w, c["bias"], st, p, True), name)

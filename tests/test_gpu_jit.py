@@ -65,6 +65,42 @@ def test_generated_kernel_matches_the_oracle(torch, sw, oracle, case):
     assert_f32_parity(out.cpu().numpy(), y_ref, d, f"jit depthwise {case}")
 
 
+STRIDED_DILATED_JIT_CASES = [
+    # N, C, H, W, R, S, stride, pad, dilation   (all inside the generated kernel's range)
+    (2, 5, 56, 56, 3, 3, 1, 2, 2),      # dilation 2, "same"
+    (2, 5, 56, 56, 3, 3, 1, 4, 4),
+    (1, 6, 56, 56, 3, 3, 1, 6, 6),
+    (1, 6, 56, 56, 3, 3, 1, 12, 12),    # span 25
+    (2, 5, 56, 56, 5, 5, 1, 4, 2),      # 5x5 at dilation 2
+    (1, 4, 56, 56, 7, 7, 1, 9, 3),      # 49 taps at dilation 3: passes on both axes
+    (2, 5, 60, 60, 3, 3, 1, 0, 2),      # no padding: 56 x 56 outputs of a 60 x 60 plane
+    (2, 5, 48, 52, 3, 5, 1, 2, 2),      # rectangular filter, ragged plane
+    (2, 5, 28, 28, 3, 3, 1, 1, 1),      # a 28 x 28 plane: four outputs per lane and axis
+    (2, 5, 28, 28, 5, 5, 1, 4, 2),
+    (3, 7, 56, 56, 3, 3, 2, 1, 1),      # stride 2: 28 x 28 outputs
+    (2, 5, 64, 64, 3, 3, 2, 1, 1),      # ... 32 x 32
+    (2, 5, 56, 56, 5, 5, 2, 2, 1),
+    (1, 5, 64, 64, 7, 7, 2, 3, 1),
+    (2, 5, 64, 64, 3, 3, 2, 2, 2),      # stride 2 with dilation 2
+    (2, 5, 40, 48, 3, 3, 2, 1, 1),      # 20 x 24 outputs: three per lane and axis, ragged
+]
+
+
+@pytest.mark.parametrize("case", STRIDED_DILATED_JIT_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_generated_strided_and_dilated_kernels(torch, sw, oracle, case):
+    N, C, H, W, R, S, stride, pad, dil = case
+    x = inputs.normal_f32((N, C, H, W), 2641)
+    w = inputs.normal_f32((C, 1, R, S), 2642)
+    y_ref, d = oracle.conv2d_dilated(x, w, stride, pad, dil, depthwise=True)
+    assert sw.sw_jit_prepare_depthwise_dilated(H, W, R, S, stride, pad, dil) == 0
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_depthwise_dilated_jit(dev(torch, x), dev(torch, w), stride, pad, dil, out=out)
+    assert sw.sw_last_kernel() == f"sliding_plane_jit_kernel<{R},{S},{stride},{dil}>", sw.sw_last_kernel()
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"jit strided / dilated depthwise {case}")
+
+
 def test_several_planes_per_wavefront(torch, sw, oracle):
     """More planes than the launch has wavefronts (2048): the persistent loop, the prefetch of the next plane and
     the last, partly filled round."""
@@ -93,8 +129,8 @@ def test_a_geometry_is_compiled_once(torch, sw):
     assert sw.sw_jit_cached_kernels() == n
     assert torch.equal(y1, y2)
     # a shape outside the generated kernel's range compiles nothing and still gives the result
-    xs = dev(torch, inputs.normal_f32((1, 2, 28, 28), 2623))
-    assert sw.sw_jit_prepare_depthwise(28, 28, 15, 15, 1, 7) == 3
+    xs = dev(torch, inputs.normal_f32((1, 2, 8, 8), 2623))
+    assert sw.sw_jit_prepare_depthwise(8, 8, 15, 15, 1, 7) == 3
     ys = sw.sw_conv2d_depthwise_jit(xs, w, 1, 7)
     assert sw.sw_jit_cached_kernels() == n
     assert torch.equal(ys, sw.sw_conv2d_depthwise(xs, w, 1, 7))

@@ -270,8 +270,13 @@ def test_generated_source_compiles_for_its_whole_range(L, geometry):
 
 
 def test_jit_range_and_errors(L):
-    assert B.sw_jit_compile_check(56, 56, 9, 9, 2, 4) == B.SW_ERR_UNSUPPORTED      # stride 2
-    assert B.sw_jit_compile_check(28, 28, 9, 9, 1, 4) == B.SW_ERR_UNSUPPORTED      # small plane
+    assert B.sw_jit_compile_check(56, 56, 9, 9, 3, 4) == B.SW_ERR_UNSUPPORTED      # stride 3
+    assert B.sw_jit_compile_check(8, 8, 3, 3, 1, 1) == B.SW_ERR_UNSUPPORTED        # small plane
+    assert B.sw_jit_compile_check(56, 24, 3, 3, 1, 1) == B.SW_ERR_UNSUPPORTED      # most lanes of the 8 x 8 grid idle
+    assert B.sw_jit_compile_check_dilated(56, 56, 3, 3, 1, 32, 32) == B.SW_ERR_UNSUPPORTED   # span 65
+    assert B.sw_jit_compile_check_dilated(56, 56, 3, 3, 1, 2, 0) == B.SW_ERR_SHAPE
+    assert B.sw_jit_compile_check_dilated(56, 56, 3, 3, 2, 1, 1) == B.SW_OK         # stride 2: builds
+    assert B.sw_jit_compile_check_dilated(28, 28, 5, 5, 1, 4, 2) == B.SW_OK         # four outputs per lane, dilation 2
     assert B.sw_jit_compile_check(58, 58, 3, 3, 1, 1) == B.SW_ERR_UNSUPPORTED      # output above 56 x 56
     assert B.sw_jit_compile_check(56, 56, 12, 12, 1, 4) == B.SW_ERR_UNSUPPORTED    # W_out = 53
     assert B.sw_jit_compile_check(56, 56, 9, 9, 1, 6) == B.SW_ERR_UNSUPPORTED      # output larger than the plane
@@ -279,7 +284,7 @@ def test_jit_range_and_errors(L):
     assert B.sw_jit_compile_check(0, 56, 9, 9, 1, 4) == B.SW_ERR_SHAPE
     assert B.sw_jit_compile_check(4, 4, 9, 9, 1, 0) == B.SW_ERR_SHAPE              # filter larger than the plane
     assert B.sw_jit_prepare_depthwise(56, 56, 9, 9, 1, -1) == B.SW_ERR_SHAPE
-    assert B.sw_jit_prepare_depthwise(28, 28, 9, 9, 1, 4) == B.SW_ERR_UNSUPPORTED
+    assert B.sw_jit_prepare_depthwise(8, 8, 3, 3, 1, 1) == B.SW_ERR_UNSUPPORTED
     assert B.sw_jit_cached_kernels() >= 0
 
 

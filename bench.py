@@ -121,7 +121,10 @@ def measured_peaks(torch, sw):
     memory), timed like everything else here: the measured-achievable peaks beside the datasheet's."""
     out = {}
     for key, kind, iters in (("mfma_f32_tflops", sw.SW_PROBE_MFMA_F32, 4000), ("mfma_i8_tops", sw.SW_PROBE_MFMA_I8, 8000),
-                             ("fma_f32_tflops", sw.SW_PROBE_FMA_F32, 1000)):
+                             ("fma_f32_tflops", sw.SW_PROBE_FMA_F32, 1000),
+                             # plain FMAs and fp32 matrix instructions in one stream: the sum of the two rates if the
+                             # pipes overlapped; measured, a round takes the sum of the two times instead
+                             ("fma_plus_mfma_f32_tflops", sw.SW_PROBE_FMA_MFMA_F32, 2000)):
         ops = sw.sw_probe(kind, iters)
         us = time_kernel(torch, lambda d: sw.sw_probe(kind, iters), [None], 10, 3)
         out[key] = round(ops / us / 1e6, 1)

@@ -388,7 +388,8 @@ int sw_version(void);
 typedef enum {
     SW_PROBE_MFMA_F32 = 0,  /* v_mfma_f32_32x32x2_f32                                  */
     SW_PROBE_MFMA_I8 = 1,   /* v_mfma_i32_32x32x32_i8                                  */
-    SW_PROBE_FMA_F32 = 2    /* v_fma_f32, wave-uniform multiplicand (no packed forms)  */
+    SW_PROBE_FMA_F32 = 2,   /* v_fma_f32, wave-uniform multiplicand (no packed forms)  */
+    SW_PROBE_FMA_MFMA_F32 = 3 /* nine v_fma_f32, one v_mfma_f32_16x16x4_f32, ... in one stream: do the two pipes overlap? */
 } sw_probe_kind;
 int sw_probe(int kind, int iters, void* hip_stream);
 int64_t sw_probe_ops(int kind, int iters);

@@ -10,6 +10,7 @@ namespace swconv {
 namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef int intx16 __attribute__((ext_vector_type(16)));
 typedef int intx4 __attribute__((ext_vector_type(4)));
 
@@ -17,6 +18,8 @@ constexpr int kProbeGroups = 256 * 8;    // workgroups of one wavefront: eight p
 constexpr int kMfmaPerIter = 8;          // matrix instructions per loop turn (four independent accumulators, twice)
 constexpr int kFmaAcc = 48;              // independent fp32 accumulators of the vector probe
 constexpr int kFmaPerIter = kFmaAcc * 4;
+constexpr int kMixRounds = 16;           // rounds per loop turn of the mixed probe:
+constexpr int kMixFma = 9;               // nine plain FMAs, then one 16 x 16 x 4 matrix instruction
 
 __global__ __launch_bounds__(64) void probe_mfma_f32_kernel(int iters, float* sink)
 {
@@ -68,6 +71,38 @@ __global__ __launch_bounds__(64) void probe_fma_f32_kernel(int iters, float* sin
     if (sink && s == 12345.678f) *sink = s;
 }
 
+// Plain FMAs and independent fp32 matrix instructions in one stream (nine v_fma_f32, one v_mfma_f32_16x16x4_f32, ...):
+// if the vector and the matrix pipe worked side by side on fp32, a round would take as long as its slower part; on this
+// chip it takes the sum of the two, which is why the one-filter-per-plane kernels leave the matrix cores alone.
+__global__ __launch_bounds__(64) void probe_fma_mfma_f32_kernel(int iters, float* sink, float tap0)
+{
+    float acc[kFmaAcc];
+    for (int i = 0; i < kFmaAcc; ++i) acc[i] = threadIdx.x * 1e-3f + i;
+    float in[8];
+    for (int j = 0; j < 8; ++j) in[j] = 1.0f + threadIdx.x * 1e-4f + j * 1e-3f;
+    floatx4 d[8];
+    for (int t = 0; t < 8; ++t) d[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+    const float a = 1.0f + threadIdx.x * 1e-3f, b = 0.5f;
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int g = 0; g < kMixRounds; ++g) {
+#pragma unroll
+            for (int i = 0; i < kMixFma; ++i) {
+                const int k = (g * kMixFma + i) % kFmaAcc;
+                acc[k] = fmaf(tap0, in[(k + g) & 7], acc[k]);
+            }
+            d[g & 7] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, d[g & 7], 0, 0, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, kMixFma, 0);     // keep the two kinds interleaved as written
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        }
+    }
+    float s = 0.f;
+    for (int i = 0; i < kFmaAcc; ++i) s += acc[i];
+    for (int t = 0; t < 8; ++t) s += d[t][0] + d[t][3];
+    if (sink && s == 12345.678f) *sink = s;
+}
+
 }  // namespace
 
 }  // namespace swconv
@@ -84,6 +119,7 @@ int64_t sw_probe_ops(int kind, int iters)
         case SW_PROBE_MFMA_F32: return waves * iters * kMfmaPerIter * (2LL * 32 * 32 * 2);
         case SW_PROBE_MFMA_I8: return waves * iters * kMfmaPerIter * (2LL * 32 * 32 * 32);
         case SW_PROBE_FMA_F32: return waves * iters * kFmaPerIter * (2LL * 64);
+        case SW_PROBE_FMA_MFMA_F32: return waves * iters * kMixRounds * (kMixFma * 2LL * 64 + 2LL * 16 * 16 * 4);
         default: return 0;
     }
 }
@@ -103,6 +139,10 @@ int sw_probe(int kind, int iters, void* hip_stream)
         case SW_PROBE_FMA_F32:
             SW_NOTED_LAUNCH(note_kernel("probe_fma_f32_kernel"), probe_fma_f32_kernel, dim3(kProbeGroups), dim3(64), 0, st, iters, none,
                             1.0000001f, 0.9999999f);
+            break;
+        case SW_PROBE_FMA_MFMA_F32:
+            SW_NOTED_LAUNCH(note_kernel("probe_fma_mfma_f32_kernel"), probe_fma_mfma_f32_kernel, dim3(kProbeGroups), dim3(64), 0, st, iters,
+                            none, 1.0000001f);
             break;
         default: return SW_ERR_UNSUPPORTED;
     }

@@ -314,3 +314,16 @@ def test_float_nhwc_argument_errors(L):
         assert f(X, W_, B_ + 2, Y, *ok, 0, None) == B.SW_ERR_ALIGN                             # the fp32 bias
         assert f(X, W_, None, X + 64, *ok, 0, None) == B.SW_ERR_ALIAS
         assert f(X, W_, Y + 16, Y, *ok, 0, None) == B.SW_ERR_ALIAS
+
+
+def test_probe_argument_errors_and_operation_counts(L):
+    # the measurement aids refuse bad arguments before anything is enqueued
+    assert L.sw_probe(B.SW_PROBE_FMA_F32, 0, None) == B.SW_ERR_SHAPE
+    assert L.sw_probe(99, 10, None) == B.SW_ERR_UNSUPPORTED
+    waves = 256 * 8
+    assert L.sw_probe_ops(B.SW_PROBE_MFMA_F32, 3) == waves * 3 * 8 * 2 * 32 * 32 * 2
+    assert L.sw_probe_ops(B.SW_PROBE_MFMA_I8, 3) == waves * 3 * 8 * 2 * 32 * 32 * 32
+    assert L.sw_probe_ops(B.SW_PROBE_FMA_F32, 3) == waves * 3 * 48 * 4 * 2 * 64
+    # sixteen rounds of nine FMAs (64 lanes) and one 16 x 16 x 4 matrix product
+    assert L.sw_probe_ops(B.SW_PROBE_FMA_MFMA_F32, 3) == waves * 3 * 16 * (9 * 2 * 64 + 2 * 16 * 16 * 4)
+    assert L.sw_probe_ops(99, 3) == 0 and L.sw_probe_ops(B.SW_PROBE_FMA_F32, 0) == 0

@@ -301,6 +301,9 @@ LAYERS = [
     ("conv_7x7_s2_3to64", "conv", (32, 3, 224, 224), 7, 2, 3, 64),
     ("conv_3x3_s2_64to128", "conv", (32, 64, 56, 56), 3, 2, 1, 128),
     ("conv_1x1_256to64", "conv", (32, 256, 56, 56), 1, 1, 0, 64),
+    ("conv_1x1_64to256", "conv", (32, 64, 56, 56), 1, 1, 0, 256),
+    ("conv_1x1_256to256_28x28", "conv", (32, 256, 28, 28), 1, 1, 0, 256),
+    ("conv_1x1_512to512_14x14", "conv", (32, 512, 14, 14), 1, 1, 0, 512),
     ("conv_3x3_14x14_256", "conv", (32, 256, 14, 14), 3, 1, 1, 256),
     ("conv_3x3_64to64", "conv", (32, 64, 56, 56), 3, 1, 1, 64),
     ("conv_3x3_64to64_bias_relu", "conv_br", (32, 64, 56, 56), 3, 1, 1, 64),

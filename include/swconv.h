@@ -106,10 +106,12 @@ int sw_pool2d(const float* x, float* y, int N, int C, int H, int W, int R, int S
  * Supported: any shape with R,S <= 64 (SW_ERR_UNSUPPORTED beyond).  C_in >= 2
  * runs on the matrix cores: 3x3 and 5x5 at stride 1 with C_in % 16 == 0,
  * C_out % 64 == 0 and 16-byte aligned w in a large-tile kernel when the problem
- * fills the chip with such tiles, every other extent, stride, padding and channel
- * count in an any-shape kernel (one thread per output only when its window or
- * filter does not fit 64 KB of LDS).  C_in == 1 runs the one-filter-per-plane
- * kernels of sw_conv2d_depthwise.
+ * fills the chip with such tiles, 1x1 at stride 1 without padding (C_in % 8 == 0,
+ * an even number of pixels per plane, x and y aligned to 8 bytes, w to 16) in a
+ * kernel that reads its operands straight from x, every other extent, stride,
+ * padding and channel count in an any-shape kernel (one thread per output only
+ * when its window or filter does not fit 64 KB of LDS).  C_in == 1 runs the
+ * one-filter-per-plane kernels of sw_conv2d_depthwise.
  */
 int sw_conv2d(const float* x, const float* w, float* y,
               int N, int C_in, int C_out, int H, int W, int R, int S,

@@ -236,6 +236,10 @@ static int run_conv2d(const float* x, const float* w, float* y, const Conv2dShap
         // Filters of 25 taps and more over at least 8 channels: the compound kernel (one filter row of a channel
         // chunk at a time, 256-pixel tiles), measured faster than the kernels below from 5 x 5 upward and the only
         // matrix-core kernel beyond 13 x 13.
+        // One tap, stride 1, no padding: the input is the B operand as it lies in memory (nothing staged); measured
+        // faster than the window kernels on every such layer tried.
+        if (mfma_f32_pointwise_supported(s, x, w, y))
+            return launch_status(launch_mfma_f32_pointwise(x, w, y, s, st, ep));
         if (s.R * s.S >= 25 && s.C_in >= 8 && mfma_f32_rows_supported(s, x))
             return launch_status(launch_mfma_f32_rows(x, w, y, s, st, ep));
         const bool quad_ok = mfma_f32_quad_supported(s);

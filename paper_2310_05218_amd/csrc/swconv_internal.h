@@ -169,6 +169,10 @@ hipError_t launch_mfma_f32_any(const float* x, const float* w, float* y, const C
 bool       mfma_f32_rows_supported(const Conv2dShape& s, const float* x); // large filters: one filter row of a channel chunk at a time
 hipError_t launch_mfma_f32_rows(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
                                 const Epilogue& ep = Epilogue{nullptr, 0});
+// 1 x 1, stride 1, no padding, C_in a multiple of 8: B operands straight from global memory, filters resident in LDS
+bool       mfma_f32_pointwise_supported(const Conv2dShape& s, const float* x, const float* w, const float* y);
+hipError_t launch_mfma_f32_pointwise(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
+                                     const Epilogue& ep = Epilogue{nullptr, 0});
 bool       mfma_f32_quad_supported(const Conv2dShape& s); // the same for few taps (R * S <= 12): 16-byte operand reads
 hipError_t launch_mfma_f32_quad(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
                                 const Epilogue& ep = Epilogue{nullptr, 0});

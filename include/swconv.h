@@ -356,7 +356,9 @@ int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* b
  * Pixels of a multiple of 32 bytes (C_in % 8 == 0 in fp32, % 16 in bf16) and 16-byte
  * aligned x and w run on the matrix cores, the channels in chunks of up to 128 bytes
  * per pixel (any extent, stride, dilation and C_out); every other valid shape one
- * thread per output.
+ * thread per output.  bf16 with C_out % 4 == 0, 8-byte aligned y, R, S <= 32, x below
+ * 2 GiB and the filters of 32 output channels within 150 KB reads its pixel operands
+ * straight from x (no window in LDS), which is the faster of the two bf16 kernels.
  */
 int sw_conv2d_nhwc(const float* x, const float* w, const float* bias, float* y,
                    int N, int H, int W, int C_in, int C_out, int R, int S,

@@ -116,6 +116,11 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
 bool       mfma_nhwc_supported(const void* x, const void* w, const Conv2dShape& s, int esz);
 hipError_t launch_mfma_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int esz, const Epilogue& ep,
                             hipStream_t st);
+// bf16 with the pixel operand read straight from global memory (C_in % 16 == 0, C_out % 4 == 0, filters of the
+// channel block resident in LDS)
+bool       mfma_bf16_nhwc_direct_supported(const void* x, const void* w, const void* y, const Conv2dShape& s);
+hipError_t launch_mfma_bf16_nhwc_direct(const void* x, const void* w, void* y, const Conv2dShape& s, const Epilogue& ep,
+                                        hipStream_t st);
 hipError_t launch_direct_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int esz, const Epilogue& ep,
                               hipStream_t st);
 

@@ -105,21 +105,25 @@ def test_s8_nhwc_full_size_agrees_with_the_channel_first_call(torch, sw, oracle)
 
 FLOAT_CASES = [
     # N, H, W, C_in, C_out, R, S, stride, pad, dilation, kernel for fp32, kernel for bf16
-    (2, 28, 28, 64, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),    # two fp32 chunks of 32 channels, one bf16 chunk
-    (1, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,2>"),    # 4-row bands (224 pixels)
-    (2, 14, 14, 128, 96, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),   # four / two chunks, ragged channel block
-    (2, 30, 41, 16, 40, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),    # blocks that span rows, ragged last block
-    (1, 57, 57, 64, 128, 3, 3, 2, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),   # stride 2
-    (1, 20, 20, 16, 32, 5, 5, 1, 2, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),    # 25 taps: two rounds of filter pieces
-    (1, 12, 12, 48, 64, 7, 7, 1, 3, 1, "mfma_nhwc_kernel<0,1>", "mfma_nhwc_kernel<1,1>"),    # 49 taps: LDS bounds the chunk
+    (2, 28, 28, 64, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # two fp32 chunks of 32 channels, one bf16 chunk
+    (1, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # 4-row bands (224 pixels)
+    (2, 14, 14, 128, 96, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),   # four / two chunks, ragged channel block
+    (2, 30, 41, 16, 40, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # blocks that span rows, ragged last block
+    (1, 57, 57, 64, 128, 3, 3, 2, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),   # stride 2
+    (1, 20, 20, 16, 32, 5, 5, 1, 2, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # 25 taps: two rounds of filter pieces
+    (1, 12, 12, 48, 64, 7, 7, 1, 3, 1, "mfma_nhwc_kernel<0,1>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # 49 taps: LDS bounds the chunk
     (2, 19, 23, 64, 70, 1, 1, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),    # pointwise
     (1, 33, 17, 16, 5, 7, 3, 2, 3, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),     # rectangular filter, few output channels
-    (1, 28, 28, 32, 64, 3, 3, 1, 2, 2, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,2>"),    # dilation 2
-    (1, 40, 40, 16, 64, 3, 3, 2, 6, 6, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),    # dilation 6 with stride 2
-    (1, 9, 300, 16, 64, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "direct_nhwc_kernel<1>"),    # rows wider than 256 outputs
+    (1, 28, 28, 32, 64, 3, 3, 1, 2, 2, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # dilation 2
+    (1, 40, 40, 16, 64, 3, 3, 2, 6, 6, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # dilation 6 with stride 2
+    (1, 9, 300, 16, 64, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # rows wider than 256 outputs
     (1, 12, 12, 12, 16, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "direct_nhwc_kernel<1>"),    # pixels that are not whole K steps
     (1, 12, 12, 8, 16, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,1>", "direct_nhwc_kernel<1>"),     # 32 bytes per pixel in fp32, 16 in bf16
-    (1, 5, 5, 16, 8, 5, 5, 1, 0, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),       # a single output pixel
+    (1, 5, 5, 16, 8, 5, 5, 1, 0, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),       # a single output pixel
+    (16, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<2,2>"),   # enough tiles for two channel blocks per wavefront
+    (3, 21, 21, 48, 36, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # three K steps per tap (27 iterations), ragged channel block
+    (2, 16, 16, 32, 64, 2, 2, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # 8 iterations: two left over after the ring's trips
+    (1, 20, 20, 32, 30, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,2>"),    # an output channel count the 8-byte stores do not take: window in LDS
 ]
 
 

@@ -24,7 +24,8 @@ struct SmallParams {
     int H, W, R, S, stride, pad, Ho, Wo, n_filters, G;
     int Hp, Wp, QH;                        // framed plane in LDS, groups of four output rows
     int64_t planes;
-    FastDiv by_frame, by_Wp, by_items, by_Wo;
+    int vec;                               // the run of planes starts on a 16-byte boundary in every workgroup: 16-byte loads
+    FastDiv by_frame, by_Wp, by_items, by_Wo, by_HW, by_W;
 };
 
 // RC, SC, STC > 0: filter extent and stride at compile time (taps unrolled); 0: at run time.
@@ -42,24 +43,58 @@ __global__ __launch_bounds__(kThreads) void small_planes_kernel(const float* __r
     float* xs = lds;                               // [np][Hp][Wp]
     float* ws = lds + P.G * frame;                 // [np][RS]
 
-    // every cell of the framed planes: the image where there is one, zero (the padding) around it; loads go
-    // out eight per thread before the first LDS write, so a batch costs one memory round trip
     const float* src = x + p0 * HW;
-    for (int base = tid; base < np * frame; base += kThreads * 8) {
-        float v8[8];
+    if (P.vec) {
+        // The run of planes is one contiguous, 16-byte aligned piece of memory: it comes in with 16-byte loads (four
+        // in flight per thread: one or two memory round trips for the whole run) and is scattered element by element
+        // into the frames, whose padding has been zeroed before.
+        typedef float floatx4 __attribute__((ext_vector_type(4)));
+        const int cells = np * frame;
+        for (int i = tid; i < cells / 4; i += kThreads) reinterpret_cast<floatx4*>(xs)[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (tid < cells % 4) xs[cells - 1 - tid] = 0.f;
+        __syncthreads();
+        const int n = np * HW, n4 = n / 4;
+        auto place = [&](int i, float v) __attribute__((always_inline)) {
+            const int g = fast_div(i, P.by_HW), c = i - g * HW;
+            const int h = fast_div(c, P.by_W), col = c - h * P.W;
+            if (h + P.pad < P.Hp && col + P.pad < P.Wp) xs[g * frame + (h + P.pad) * P.Wp + col + P.pad] = v;
+        };
+        for (int base = tid; base < n4; base += kThreads * 4) {
+            floatx4 v4[4];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int i = base + kThreads * u;
-            const int g = fast_div(i, P.by_frame);
-            const int c = i - g * frame;
-            const int hp = fast_div(c, P.by_Wp), vp = c - hp * P.Wp;
-            const int h = hp - P.pad, v = vp - P.pad;
-            v8[u] = 0.f;
-            if (i < np * frame && (unsigned)h < (unsigned)P.H && (unsigned)v < (unsigned)P.W) v8[u] = src[g * HW + h * P.W + v];
+            for (int u = 0; u < 4; ++u) {
+                const int q = base + kThreads * u;
+                v4[u] = reinterpret_cast<const floatx4*>(src)[q < n4 ? q : n4 - 1];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int q = base + kThreads * u;
+                if (q < n4) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) place(4 * q + e, v4[u][e]);
+                }
+            }
         }
+        if (tid < n % 4) place(n - 1 - tid, src[n - 1 - tid]);
+    } else {
+        // every cell of the framed planes: the image where there is one, zero (the padding) around it; loads go
+        // out eight per thread before the first LDS write, so a batch costs one memory round trip
+        for (int base = tid; base < np * frame; base += kThreads * 8) {
+            float v8[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-            if (base + kThreads * u < np * frame) xs[base + kThreads * u] = v8[u];
+            for (int u = 0; u < 8; ++u) {
+                const int i = base + kThreads * u;
+                const int g = fast_div(i, P.by_frame);
+                const int c = i - g * frame;
+                const int hp = fast_div(c, P.by_Wp), vp = c - hp * P.Wp;
+                const int h = hp - P.pad, v = vp - P.pad;
+                v8[u] = 0.f;
+                if (i < np * frame && (unsigned)h < (unsigned)P.H && (unsigned)v < (unsigned)P.W) v8[u] = src[g * HW + h * P.W + v];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (base + kThreads * u < np * frame) xs[base + kThreads * u] = v8[u];
+        }
     }
     // the filters of these planes (plane p uses filter p % n_filters)
     for (int i = tid; i < np * RS; i += kThreads) {
@@ -156,6 +191,12 @@ hipError_t launch_small_planes(const float* x, const float* w, float* y, int64_t
     P.by_Wp = make_fastdiv(P.Wp);
     P.by_items = make_fastdiv(P.QH * Wo);
     P.by_Wo = make_fastdiv(Wo);
+    P.by_HW = make_fastdiv(H * W);
+    P.by_W = make_fastdiv(W);
+    // every workgroup's run starts at plane k * G: a multiple of 16 bytes when G * H * W is a multiple of four floats
+    if ((H * W) % 4 != 0 && G >= 4) G &= ~3;
+    P.G = G;
+    P.vec = reinterpret_cast<uintptr_t>(x) % 16 == 0 && ((int64_t)G * H * W) % 4 == 0;
     const int64_t groups = (planes + G - 1) / G;
     if (groups > 2147483647LL) return hipErrorInvalidValue;
     const size_t lds = (size_t)G * per * sizeof(float);

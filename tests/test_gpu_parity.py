@@ -451,6 +451,33 @@ def test_depthwise_dilated_sliding_kernel(torch, sw, oracle, case):
     assert_f32_parity(y.cpu().numpy(), y_ref, d, f"conv2d_dilated C_in=1 {case}")
 
 
+# (N, C, H, W, R, S, stride, pad, floats the input is shifted by): plane sizes that are and are not multiples of four
+# floats, runs whose last workgroup holds fewer planes, an input off the 16-byte grid (4-byte loads), a frame smaller
+# than the padded image (stride 2)
+SMALL_PLANE_CASES = [
+    (3, 50, 13, 13, 3, 3, 1, 1, 0), (2, 65, 7, 7, 3, 3, 1, 1, 0), (1, 130, 7, 7, 5, 5, 1, 2, 0), (5, 13, 14, 14, 7, 7, 1, 3, 0),
+    (2, 67, 14, 14, 3, 3, 2, 1, 0), (1, 70, 9, 11, 3, 3, 1, 0, 0), (3, 50, 13, 13, 3, 3, 1, 1, 1), (2, 64, 14, 14, 3, 3, 1, 1, 2),
+    (32, 16, 28, 28, 5, 5, 1, 2, 0),
+]
+
+
+@pytest.mark.parametrize("case", SMALL_PLANE_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_depthwise_small_planes(torch, sw, oracle, case):
+    N, C, H, W, R, S, stride, pad, shift = case
+    x = inputs.normal_f32((N, C, H, W), 3231)
+    w = inputs.normal_f32((C, 1, R, S), 3232)
+    y_ref, d = oracle.conv2d_depthwise(x, w, stride, pad)
+    xbuf = torch.empty((x.size + 4,), device="cuda")
+    xd = xbuf[shift:shift + x.size].view(x.shape)
+    xd.copy_(dev(torch, x))
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_depthwise(xd, dev(torch, w), stride, pad, out=out)
+    assert sw.sw_last_kernel().startswith("small_planes_kernel"), sw.sw_last_kernel()
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"depthwise on small planes {case}")
+
+
 def test_dilation_one_is_the_undilated_call(torch, sw):
     x = dev(torch, inputs.normal_f32((2, 16, 28, 28), 3221))
     w = dev(torch, inputs.normal_f32((64, 16, 3, 3), 3222, 0.1))

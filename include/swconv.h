@@ -219,8 +219,10 @@ int sw_conv2d_s8_packed_requant(const int8_t* x, const int8_t* packed, const int
  * Errors as sw_conv2d (SW_ERR_NULL, _SHAPE, _ALIGN, _ALIAS); any N, C, C_out, H, W
  * within the 2^31-1 element bound is supported.  What it saves is the memory and
  * the traffic of the intermediate (N*C*H*W floats written and read back); as it
- * stands it is slower than sw_conv2d_depthwise_bias_relu followed by
- * sw_conv2d_bias_relu (its stages run one after the other inside a workgroup).
+ * stands it is 2-4 x slower than sw_conv2d_depthwise_bias_relu followed by
+ * sw_conv2d_bias_relu (its stages run one after the other inside a workgroup, and
+ * on this chip fp32 vector arithmetic does not overlap with fp32 matrix
+ * instructions): call those two unless the intermediate's memory is what matters.
  */
 int sw_dw_pw_block(const float* x, const float* w_dw, const float* b_dw,
                    const float* w_pw, const float* b_pw, float* y,

@@ -475,13 +475,15 @@ def layer_call(sw, c, d, x=None, y=None):
     raise ValueError(kind)
 
 
-def strided_and_pooling_table(torch, sw):
+def strided_and_pooling_table(torch, sw, only=None):
     """Layers of common CNN shapes beyond the five workloads (2-D pooling, strides, small planes, fused epilogues,
     dilation, bf16 planes, int8 in both layouts), timed cold like the step's kernels.  bytes = input once + output
     once (+ filters); multi-channel rows also give the fraction of the matrix peak.  (Parity of every row against
     the CPU oracle is a GPU test: tests/test_gpu_bench_shapes.py.)"""
     rows = []
     for idx in range(len(LAYERS)):
+        if only is not None and only not in LAYERS[idx][0]:
+            continue
         c = layer_case(idx)
         d = layer_device(torch, c)
         kind, N, C, R = c["kind"], c["N"], c["C"], c["R"]
@@ -556,6 +558,8 @@ def main():
                          "32x64x56x56 fp32, square filters 3..51, 'same' padding; prints one JSON line")
     ap.add_argument("--layers", action="store_true",
                     help="2-D pooling and stride-2 layers of common CNN shapes; prints one JSON line")
+    ap.add_argument("--only", default=None, metavar="TEXT",
+                    help="with --layers: only the rows whose name contains TEXT (short runs under a profiler)")
     ap.add_argument("--pmc-probe", action="store_true",
                     help="for counter runs under rocprofv3 --pmc: one 64 MiB device copy (calibration), then "
                          "every kernel of the step twice; prints nothing but a marker line")
@@ -576,7 +580,7 @@ def main():
         print(json.dumps(filter_size_sweep(torch, sw)))
         return
     if args.layers:
-        print(json.dumps(strided_and_pooling_table(torch, sw)))
+        print(json.dumps(strided_and_pooling_table(torch, sw, args.only)))
         return
 
     work = work_table()

@@ -103,6 +103,11 @@ def f32_to_bf16_rne(a: np.ndarray) -> np.ndarray:
     return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
 
 
+def f16_to_f32(h: np.ndarray) -> np.ndarray:
+    """IEEE half-precision bit patterns (uint16) -> the fp32 values they denote (exact; numpy's own widening)."""
+    return np.ascontiguousarray(h, np.uint16).view(np.float16).astype(np.float32)
+
+
 def out_dim(n_in: int, k: int, stride: int, pad: int) -> int:
     return int(_load().oracle_out_dim(n_in, k, stride, pad))
 
@@ -331,6 +336,14 @@ def conv2d_bf16_nhwc(x_bits, w_bits, stride: int = 1, pad: int = 0, dilation: in
     taken in fp64; returns the unrounded (y, D) -- the one rounding of the finished sum to bf16 is the caller's
     to account for (f32_to_bf16_rne gives the nearest-even pattern)."""
     return conv2d_nhwc(bf16_to_f32(np.asarray(x_bits, np.uint16)), bf16_to_f32(np.asarray(w_bits, np.uint16)), stride, pad,
+                       dilation, bias, relu)
+
+
+def conv2d_f16_nhwc(x_bits, w_bits, stride: int = 1, pad: int = 0, dilation: int = 1, bias=None, relu: bool = False):
+    """The same for IEEE half-precision tensors given as bit patterns (uint16): both are widened to fp32 (exact), the
+    sums are taken in fp64; returns the unrounded (y, D) -- the one rounding of the finished sum to half precision
+    (nearest even: numpy's astype(float16)) is the caller's to account for."""
+    return conv2d_nhwc(f16_to_f32(np.asarray(x_bits, np.uint16)), f16_to_f32(np.asarray(w_bits, np.uint16)), stride, pad,
                        dilation, bias, relu)
 
 

@@ -40,6 +40,11 @@ def normal_bf16(shape, seed: int, std: float = 1.0) -> np.ndarray:
     return (normal_f32(shape, seed, std).view(np.uint32) >> 16).astype(np.uint16)
 
 
+def normal_f16(shape, seed: int, std: float = 1.0) -> np.ndarray:
+    """IEEE half-precision bit patterns (uint16) of N(0, std^2) draws (numpy's cast of each fp32 draw)."""
+    return normal_f32(shape, seed, std).astype(np.float16).view(np.uint16)
+
+
 def uniform_s8(shape, seed: int) -> np.ndarray:
     rng = np.random.default_rng(seed)
     return rng.integers(-128, 128, size=shape, dtype=np.int8)

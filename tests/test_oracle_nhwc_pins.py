@@ -58,6 +58,15 @@ def test_hand_worked_channel_last_float_example(oracle):
     wb = np.array([[[[0x4000, 0xC040]]]], np.uint16)
     y, d = oracle.conv2d_bf16_nhwc(xb, wb, 1, 0)
     assert y.tolist() == [[[[-4.0]]]] and d.tolist() == [[[[8.0]]]]
+    # half-precision bit patterns: 0x3C00 = 1, 0x4000 = 2, 0xC200 = -3, 0x3800 = 0.5, 0x0001 = 2^-24 (the smallest
+    # denormal): 1 * 2 + 2 * (-3) = -4 with magnitude 8; 0.5 * 2^-24 = 2^-25 is kept (fp64 sums, no rounding)
+    xh = np.array([[[[0x3C00, 0x4000]]]], np.uint16)
+    wh = np.array([[[[0x4000, 0xC200]]]], np.uint16)
+    y, d = oracle.conv2d_f16_nhwc(xh, wh, 1, 0)
+    assert y.tolist() == [[[[-4.0]]]] and d.tolist() == [[[[8.0]]]]
+    y, d = oracle.conv2d_f16_nhwc(np.array([[[[0x3800]]]], np.uint16), np.array([[[[0x0001]]]], np.uint16), 1, 0)
+    assert y.tolist() == [[[[2.0 ** -25]]]] and d.tolist() == [[[[2.0 ** -25]]]]
+    assert oracle.f16_to_f32(np.array([0x7BFF, 0xFBFF, 0x0400], np.uint16)).tolist() == [65504.0, -65504.0, 2.0 ** -14]
 
 
 def test_channel_last_float_brute_force(oracle):
@@ -83,3 +92,6 @@ def test_channel_last_float_brute_force(oracle):
     ref += b.astype(np.int64)
     mag += np.abs(b).astype(np.int64)
     assert np.array_equal(y, np.maximum(ref, 0)) and np.array_equal(d, mag)
+    # the same integers as half-precision bit patterns (exact in 11 bits): the 16-bit entry points' oracle is the same sum
+    yh, dh = oracle.conv2d_f16_nhwc(x.astype(np.float16).view(np.uint16), w.astype(np.float16).view(np.uint16), stride, pad, dil, b, True)
+    assert np.array_equal(yh, y) and np.array_equal(dh, d)

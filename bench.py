@@ -328,6 +328,8 @@ LAYERS = [
     ("conv_bf16_nhwc_3x3_128to128_28x28", "conv_bf16_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
     ("conv_bf16_nhwc_3x3_s2_64to128", "conv_bf16_nhwc", (32, 64, 56, 56), 3, 2, 1, 128),
     ("conv_bf16_nhwc_1x1_256to64", "conv_bf16_nhwc", (32, 256, 56, 56), 1, 1, 0, 64),
+    ("conv_f16_nhwc_3x3_64to64", "conv_f16_nhwc", (32, 64, 56, 56), 3, 1, 1, 64),      # channel-last IEEE half, fp32 accumulation
+    ("conv_f16_nhwc_3x3_128to128_28x28", "conv_f16_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
     ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
     ("conv_s8_1x1_64to256", "conv_s8", (32, 64, 56, 56), 1, 1, 0, 256),
     ("conv_s8_requant_3x3_128to128", "conv_s8_rq", (32, 128, 28, 28), 3, 1, 1, 128),
@@ -374,6 +376,9 @@ def layer_case(idx, n_images=None, data=True):
         if kind.endswith("rq"):
             c["bias"] = rng.integers(-50000, 50000, size=c["C_out"]).astype(np.int32)
             c["scale"] = (rng.uniform(1.0, 3.0, size=c["C_out"]) * 2.0 ** -18).astype(np.float32)
+        if kind == "conv_f16_nhwc":         # (the same draws, rounded to half-precision bit patterns)
+            x = inputs.normal_f16((N, C, H, W), inputs.seed_for(7, idx))
+            w = inputs.normal_f16((c["C_out"], C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
         if "nhwc" in kind:
             x = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
             w = np.ascontiguousarray(w.transpose(0, 2, 3, 1))
@@ -391,6 +396,9 @@ def layer_case(idx, n_images=None, data=True):
         if kind == "conv_bf16_nhwc":        # (the same draws, truncated to bf16 bit patterns)
             x = inputs.normal_bf16((N, C, H, W), inputs.seed_for(7, idx))
             w = inputs.normal_bf16((c["C_out"], C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
+        if kind == "conv_f16_nhwc":         # (the same draws, rounded to half-precision bit patterns)
+            x = inputs.normal_f16((N, C, H, W), inputs.seed_for(7, idx))
+            w = inputs.normal_f16((c["C_out"], C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
         if "nhwc" in kind:
             x = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
             w = np.ascontiguousarray(w.transpose(0, 2, 3, 1))
@@ -415,11 +423,12 @@ def layer_device(torch, c):
     x = c["x"]
     kind = c["kind"]
     as_bf16 = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.bfloat16)
-    xd = as_bf16(x) if kind in ("dw_bf16", "conv_bf16_nhwc") else dev(x)
-    odt = (torch.bfloat16 if kind in ("dw_bf16", "conv_bf16_nhwc") else torch.int8 if kind.endswith("rq") else
-           torch.int32 if kind.startswith("conv_s8") else torch.float32)
+    as_f16 = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda().view(torch.float16)
+    xd = as_bf16(x) if kind in ("dw_bf16", "conv_bf16_nhwc") else as_f16(x) if kind == "conv_f16_nhwc" else dev(x)
+    odt = (torch.bfloat16 if kind in ("dw_bf16", "conv_bf16_nhwc") else torch.float16 if kind == "conv_f16_nhwc" else
+           torch.int8 if kind.endswith("rq") else torch.int32 if kind.startswith("conv_s8") else torch.float32)
     oshape = ((c["N"], c["Ho"], c["Wo"], c["C_out"]) if "nhwc" in kind else (c["N"], c["C_out"], c["Ho"], c["Wo"]))
-    d = {"x": xd, "w": as_bf16(c["w"]) if kind == "conv_bf16_nhwc" else dev(c["w"]), "bias": dev(c.get("bias")), "scale": dev(c.get("scale")),
+    d = {"x": xd, "w": as_bf16(c["w"]) if kind == "conv_bf16_nhwc" else as_f16(c["w"]) if kind == "conv_f16_nhwc" else dev(c["w"]), "bias": dev(c.get("bias")), "scale": dev(c.get("scale")),
          "y": torch.empty(oshape, dtype=odt, device="cuda")}
     if kind.startswith("block"):
         d["w_pw"], d["bias_pw"] = dev(c["w_pw"]), dev(c["bias_pw"])
@@ -456,7 +465,7 @@ def layer_call(sw, c, d, x=None, y=None):
         return sw.sw_conv2d_bias_relu(x, d["w"], d["bias"], st, p, True, out=y)
     if kind == "conv_dil":
         return sw.sw_conv2d_dilated(x, d["w"], st, p, c["dil"], out=y)
-    if kind in ("conv_nhwc", "conv_bf16_nhwc"):
+    if kind in ("conv_nhwc", "conv_bf16_nhwc", "conv_f16_nhwc"):
         return sw.sw_conv2d_nhwc(x, d["w"], st, p, 1, out=y)
     if kind == "conv_s8":
         return sw.sw_conv2d_s8(x, d["w"], st, p, out=y)
@@ -506,7 +515,7 @@ def strided_and_pooling_table(torch, sw, only=None):
                "us_cold": round(us, 2), "gbs": round(nbytes / us / 1e3, 1),
                "frac_hbm": round(nbytes / us / 1e3 / HBM_GBS, 4), "gops": round(ops / us / 1e3, 1)}
         if kind.startswith("conv") or kind.startswith("block"):
-            row["frac_mfma"] = round(ops / us / 1e6 / (MFMA_I8_TOPS if "s8" in kind else MFMA_BF16_TFLOPS if "bf16" in kind
+            row["frac_mfma"] = round(ops / us / 1e6 / (MFMA_I8_TOPS if "s8" in kind else MFMA_BF16_TFLOPS if "bf16" in kind or "f16" in kind
                                                        else MFMA_F32_TFLOPS), 4)
         rows.append(row)
         del sets, d

@@ -343,7 +343,7 @@ int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* b
                               int stride, int pad, int relu, void* hip_stream);
 
 /*
- * The multi-channel convolution on channel-last tensors in fp32 and in bf16 (paper,
+ * The multi-channel convolution on channel-last tensors in fp32, bf16 and IEEE half (paper,
  * section 3: the taps as small matrix products; section 1.1: reduced precision):
  *     x: [N,H,W,C_in];  w: [C_out,R,S,C_in];  y: [N,H_out,W_out,C_out];
  *     y[n,i,j,co] = act(sum_{r,s,ci} w[co,r,s,ci] * xz[n, i*stride+r*dilation-pad, j*stride+s*dilation-pad, ci] + bias[co])
@@ -354,13 +354,16 @@ int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* b
  * aligned); products and sums are fp32 (a product of two bf16 values is exact in
  * fp32: bf16 matrix instructions with fp32 accumulators), the bias is added in fp32,
  * and the finished value is rounded once to bf16, to nearest, ties to even.
+ * sw_conv2d_f16_nhwc: the same with IEEE half-precision bit patterns (a product of two
+ * halves is exact in fp32 as well; the one rounding to half is to nearest, ties to
+ * even, beyond 65504 to infinity, denormal results kept; denormal inputs count).
  * Note the argument order (H, W before the channel counts).  Errors as sw_conv2d.
- * Pixels of a multiple of 32 bytes (C_in % 8 == 0 in fp32, % 16 in bf16) and 16-byte
+ * Pixels of a multiple of 32 bytes (C_in % 8 == 0 in fp32, % 16 in bf16 / half) and 16-byte
  * aligned x and w run on the matrix cores, the channels in chunks of up to 128 bytes
  * per pixel (any extent, stride, dilation and C_out); every other valid shape one
- * thread per output.  bf16 with C_out % 4 == 0, 8-byte aligned y, R, S <= 32, x below
+ * thread per output.  bf16 / half with C_out % 4 == 0, 8-byte aligned y, R, S <= 32, x below
  * 2 GiB and the filters of 32 output channels within 150 KB reads its pixel operands
- * straight from x (no window in LDS), which is the faster of the two bf16 kernels.
+ * straight from x (no window in LDS), which is the faster of the two 16-bit kernels.
  */
 int sw_conv2d_nhwc(const float* x, const float* w, const float* bias, float* y,
                    int N, int H, int W, int C_in, int C_out, int R, int S,
@@ -368,6 +371,9 @@ int sw_conv2d_nhwc(const float* x, const float* w, const float* bias, float* y,
 int sw_conv2d_bf16_nhwc(const void* x, const void* w, const float* bias, void* y,
                         int N, int H, int W, int C_in, int C_out, int R, int S,
                         int stride, int pad, int dilation, int relu, void* hip_stream);
+int sw_conv2d_f16_nhwc(const void* x, const void* w, const float* bias, void* y,
+                       int N, int H, int W, int C_in, int C_out, int R, int S,
+                       int stride, int pad, int dilation, int relu, void* hip_stream);
 
 /* Output extent of one axis; <= 0 means the filter does not fit (or bad arguments). */
 int64_t sw_out_dim(int64_t in, int k, int stride, int pad);

@@ -17,7 +17,7 @@ SW_ERR_NULL, SW_ERR_SHAPE, SW_ERR_UNSUPPORTED, SW_ERR_ALIGN, SW_ERR_ALIAS, SW_ER
 SW_POOL_AVG, SW_POOL_MAX = 0, 1
 
 EXPORTS = ("sw_conv1d", "sw_pool1d", "sw_pool2d", "sw_conv2d", "sw_conv2d_depthwise", "sw_conv2d_s8",
-           "sw_conv2d_s8_requant", "sw_conv2d_s8_nhwc", "sw_conv2d_s8_nhwc_requant", "sw_conv2d_nhwc", "sw_conv2d_bf16_nhwc", "sw_conv2d_bias_relu", "sw_dw_pw_block", "sw_conv2d_depthwise_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
+           "sw_conv2d_s8_requant", "sw_conv2d_s8_nhwc", "sw_conv2d_s8_nhwc_requant", "sw_conv2d_nhwc", "sw_conv2d_bf16_nhwc", "sw_conv2d_f16_nhwc", "sw_conv2d_bias_relu", "sw_dw_pw_block", "sw_conv2d_depthwise_bias_relu", "sw_conv2d_dilated", "sw_conv2d_depthwise_dilated",
            "sw_conv2d_depthwise_bf16", "sw_conv2d_depthwise_jit", "sw_jit_prepare_depthwise", "sw_jit_compile_check",
            "sw_conv2d_depthwise_dilated_jit", "sw_jit_prepare_depthwise_dilated", "sw_jit_compile_check_dilated",
            "sw_jit_cached_kernels",
@@ -84,6 +84,8 @@ def lib() -> ctypes.CDLL:
     L.sw_conv2d_nhwc.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [vp]
     L.sw_conv2d_bf16_nhwc.restype = i32
     L.sw_conv2d_bf16_nhwc.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [vp]
+    L.sw_conv2d_f16_nhwc.restype = i32
+    L.sw_conv2d_f16_nhwc.argtypes = [vp, vp, vp, vp] + [i32] * 11 + [vp]
     L.sw_conv2d_s8_nhwc_requant.restype = i32
     L.sw_conv2d_s8_nhwc_requant.argtypes = [vp, vp, vp, vp, vp] + [i32] * 10 + [vp]
     L.sw_conv2d_s8_requant.restype = i32
@@ -153,20 +155,20 @@ def sw_conv2d_s8_nhwc(x, w, stride: int = 1, pad: int = 0, bias=None, scale=None
 def sw_conv2d_nhwc(x, w, stride: int = 1, pad: int = 0, dilation: int = 1, bias=None, relu: bool = False, out=None,
                    stream=None):
     """Channel-last convolution: x [N,H,W,C_in], w [C_out,R,S,C_in] -> y [N,H_out,W_out,C_out] = act(conv + bias[co]);
-    fp32 tensors, or bf16 tensors (torch.bfloat16: fp32 accumulation, one rounding of the result); bias [C_out] fp32."""
+    fp32 tensors, or 16-bit tensors (torch.bfloat16 / torch.float16: fp32 accumulation, one rounding of the result);
+    bias [C_out] fp32."""
     import torch
 
     N, H, W, C_in = x.shape
     C_out, R, S, C_in_w = w.shape
     if C_in_w != C_in:
         raise ValueError("channel mismatch between x and w")
-    bf = x.dtype == torch.bfloat16
-    dt = torch.bfloat16 if bf else torch.float32
-    name = "sw_conv2d_bf16_nhwc" if bf else "sw_conv2d_nhwc"
+    dt = x.dtype if x.dtype in (torch.bfloat16, torch.float16) else torch.float32
+    name = {torch.bfloat16: "sw_conv2d_bf16_nhwc", torch.float16: "sw_conv2d_f16_nhwc", torch.float32: "sw_conv2d_nhwc"}[dt]
     if out is None:
         out = torch.empty(_out_shape(name, N, sw_out_dim_dilated(H, R, stride, pad, dilation),
                                      sw_out_dim_dilated(W, S, stride, pad, dilation), C_out), dtype=dt, device=x.device)
-    fn = lib().sw_conv2d_bf16_nhwc if bf else lib().sw_conv2d_nhwc
+    fn = getattr(lib(), name)
     rc = fn(_dev(x, dt, 4, "x"), _dev(w, dt, 4, "w"), _dev(bias, torch.float32, 1, "bias") if bias is not None else None,
             _dev(out, dt, 4, "y"), N, H, W, C_in, C_out, R, S, stride, pad, dilation, 1 if relu else 0, _stream(stream))
     _check(rc, name)
@@ -180,6 +182,16 @@ def sw_conv2d_bf16_nhwc(x, w, stride: int = 1, pad: int = 0, dilation: int = 1, 
 
     if x.dtype != torch.bfloat16 or w.dtype != torch.bfloat16:
         raise TypeError("sw_conv2d_bf16_nhwc takes torch.bfloat16 tensors")
+    return sw_conv2d_nhwc(x, w, stride, pad, dilation, bias, relu, out, stream)
+
+
+def sw_conv2d_f16_nhwc(x, w, stride: int = 1, pad: int = 0, dilation: int = 1, bias=None, relu: bool = False, out=None,
+                       stream=None):
+    """sw_conv2d_nhwc on torch.float16 tensors (half precision in and out, fp32 accumulation)."""
+    import torch
+
+    if x.dtype != torch.float16 or w.dtype != torch.float16:
+        raise TypeError("sw_conv2d_f16_nhwc takes torch.float16 tensors")
     return sw_conv2d_nhwc(x, w, stride, pad, dilation, bias, relu, out, stream)
 
 

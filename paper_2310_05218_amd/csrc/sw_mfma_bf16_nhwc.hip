@@ -1,7 +1,12 @@
-// bf16 multi-channel convolution on channel-last tensors with the pixel operand read straight from global memory
-// (paper, section 3: every tap a small matrix product; section 1.1: reduced precision on the same sliding sums).
+// 16-bit (bf16 or IEEE half) multi-channel convolution on channel-last tensors with the pixel operand read straight
+// from global memory (paper, section 3: every tap a small matrix product; section 1.1: reduced precision on the same
+// sliding sums).
 //
-//   x [N, H, W, C]     w [C_out, R, S, C]     y [N, H_out, W_out, C_out]     bf16 bit patterns, fp32 sums
+//   x [N, H, W, C]     w [C_out, R, S, C]     y [N, H_out, W_out, C_out]     16-bit patterns, fp32 sums
+//
+// The two formats differ in the matrix instruction (v_mfma_f32_32x32x16_bf16 / _f16; a product of two 16-bit values
+// is exact in fp32 in both) and in the one rounding of the finished value (nearest even in both; half precision
+// overflows to infinity beyond 65504 and keeps its denormals).
 //
 // With the channel as the fastest axis, the operand of v_mfma_f32_32x32x16_bf16 for (pixel, tap, 16 channels) is, per
 // lane, 16 consecutive and 16-byte aligned bytes of x: eight channels of the pixel the tap shifts the lane's output
@@ -30,6 +35,7 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 
 constexpr size_t kLdsMax = 150 * 1024;
 constexpr int kRing = 3;                        // register sets of pixel operands (4, 6 and 8 measured no faster)
@@ -55,6 +61,11 @@ __device__ __forceinline__ unsigned bf16_rne_bits(float f)
     return u >> 16;
 }
 
+__device__ __forceinline__ unsigned f16_rne_bits(float f)
+{
+    return (unsigned)__builtin_bit_cast(unsigned short, (_Float16)f);      // v_cvt_f16_f32: nearest even
+}
+
 // wavefronts per SIMD the register file holds: accumulators, the ring of pixel operands, two sets of filter operands,
 // per-block bookkeeping and about 30 more
 constexpr int waves_per_simd(int cb, int pb, int nb)
@@ -63,7 +74,8 @@ constexpr int waves_per_simd(int cb, int pb, int nb)
     return 512 / regs > 4 ? 4 : 512 / regs < 1 ? 1 : 512 / regs;
 }
 
-template <int CB, int PB, int NB>
+// F16: IEEE half precision (else bf16)
+template <int CB, int PB, int NB, bool F16>
 __global__ __launch_bounds__(256, waves_per_simd(CB, PB, NB)) void mfma_bf16_nhwc_direct_kernel(const unsigned char* __restrict__ x,
                                                                        const unsigned char* __restrict__ w,
                                                                        unsigned short* __restrict__ y, const NdParams P)
@@ -156,9 +168,14 @@ __global__ __launch_bounds__(256, waves_per_simd(CB, PB, NB)) void mfma_bf16_nhw
 #pragma unroll
             for (int b = 0; b < PB; ++b)
 #pragma unroll
-                for (int cb = 0; cb < CB; ++cb)
-                    acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[cb]),
-                                                                         __builtin_bit_cast(bf16x8, bq[buf][b]), acc[cb][b], 0, 0, 0);
+                for (int cb = 0; cb < CB; ++cb) {
+                    if constexpr (F16)
+                        acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, a[cb]),
+                                                                            __builtin_bit_cast(halfx8, bq[buf][b]), acc[cb][b], 0, 0, 0);
+                    else
+                        acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[cb]),
+                                                                             __builtin_bit_cast(bf16x8, bq[buf][b]), acc[cb][b], 0, 0, 0);
+                }
         };
 
 #pragma unroll
@@ -201,7 +218,10 @@ __global__ __launch_bounds__(256, waves_per_simd(CB, PB, NB)) void mfma_bf16_nhw
                     if (co < P.C_out) {
                         unsigned h[4];
 #pragma unroll
-                        for (int j = 0; j < 4; ++j) h[j] = bf16_rne_bits(apply_epilogue(acc[cb][b][4 * i + j], co + j, P.ep));
+                        for (int j = 0; j < 4; ++j) {
+                            const float t = apply_epilogue(acc[cb][b][4 * i + j], co + j, P.ep);
+                            h[j] = F16 ? f16_rne_bits(t) : bf16_rne_bits(t);
+                        }
                         *reinterpret_cast<intx2*>(yp + co) = intx2{(int)(h[0] | (h[1] << 16)), (int)(h[2] | (h[3] << 16))};
                     }
                 }
@@ -256,10 +276,10 @@ NdPlan plan_direct(const Conv2dShape& s, const void* x, const void* w, const voi
     return a;
 }
 
-template <int CB, int PB, int NB>
+template <int CB, int PB, int NB, bool F16>
 hipError_t launch_direct(const void* x, const void* w, void* y, const Conv2dShape& s, NdPlan& a, const Epilogue& ep, hipStream_t st)
 {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_bf16_nhwc_direct_kernel<CB, PB, NB>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_bf16_nhwc_direct_kernel<CB, PB, NB, F16>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsMax);
     if (attr != hipSuccess) return attr;
     a.P.ep = ep;
@@ -270,7 +290,8 @@ hipError_t launch_direct(const void* x, const void* w, void* y, const Conv2dShap
     int gx = (a.P.tiles + 3) / 4;
     const int cap = (256 * per_cu + gy - 1) / gy;
     if (gx > cap) gx = cap;
-    SW_NOTED_LAUNCH(note_kernel("mfma_bf16_nhwc_direct_kernel", CB, PB), (mfma_bf16_nhwc_direct_kernel<CB, PB, NB>),
+    SW_NOTED_LAUNCH(note_kernel(F16 ? "mfma_f16_nhwc_direct_kernel" : "mfma_bf16_nhwc_direct_kernel", CB, PB),
+                    (mfma_bf16_nhwc_direct_kernel<CB, PB, NB, F16>),
                     dim3((unsigned)gx, (unsigned)gy), dim3(256), a.lds, st, static_cast<const unsigned char*>(x),
                     static_cast<const unsigned char*>(w), static_cast<unsigned short*>(y), a.P);
     return hipGetLastError();
@@ -283,12 +304,15 @@ bool mfma_bf16_nhwc_direct_supported(const void* x, const void* w, const void* y
     return plan_direct(s, x, w, y).ok;
 }
 
-hipError_t launch_mfma_bf16_nhwc_direct(const void* x, const void* w, void* y, const Conv2dShape& s, const Epilogue& ep, hipStream_t st)
+hipError_t launch_mfma_bf16_nhwc_direct(const void* x, const void* w, void* y, const Conv2dShape& s, bool f16, const Epilogue& ep,
+                                        hipStream_t st)
 {
     NdPlan a = plan_direct(s, x, w, y);
     if (!a.ok) return hipErrorInvalidValue;
-#define SW_ND(CBC, PBC) \
-    if (a.CB == CBC && a.PB == PBC) return launch_direct<CBC, PBC, kRing>(x, w, y, s, a, ep, st)
+#define SW_ND(CBC, PBC)                                                                                  \
+    if (a.CB == CBC && a.PB == PBC)                                                                      \
+        return f16 ? launch_direct<CBC, PBC, kRing, true>(x, w, y, s, a, ep, st)                         \
+                   : launch_direct<CBC, PBC, kRing, false>(x, w, y, s, a, ep, st)
     SW_ND(2, 2); SW_ND(1, 2);
 #undef SW_ND
     return hipErrorInvalidValue;

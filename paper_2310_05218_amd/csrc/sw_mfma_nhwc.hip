@@ -1,4 +1,4 @@
-// Multi-channel convolution on channel-last tensors, fp32 and bf16, on the matrix cores: any filter extent,
+// Multi-channel convolution on channel-last tensors, fp32, bf16 and IEEE half, on the matrix cores: any filter extent,
 // stride, padding and dilation (paper, section 3: the taps as small matrix products; section 1.1: reduced
 // precision applied to the same sliding formulation).
 //
@@ -6,6 +6,8 @@
 //   fp32: fp32 everywhere, v_mfma_f32_32x32x2_f32.
 //   bf16: x, w and y are bf16 bit patterns, products and sums are fp32 (v_mfma_f32_32x32x16_bf16: a bf16 product
 //         is exact in fp32), one rounding of the finished sum (+ bias, rectifier) to bf16, nearest even.
+//   half: the same with v_mfma_f32_32x32x16_f16 (a product of two halves is exact in fp32 as well) and one rounding
+//         to half precision, nearest even, overflow to infinity, denormals kept.
 //
 // With the channel as the fastest axis of both tensors the K operand of a matrix instruction is 16 consecutive
 // bytes of memory per lane (four fp32 channels = the operands of four K steps, or eight bf16 channels = one), so
@@ -29,6 +31,7 @@ typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 
 constexpr int kMaxBlocks = 8;          // 32-pixel blocks per workgroup
 constexpr int kBlocksPerWave = 4;      // a wavefront takes every second block of one 32-channel half
@@ -55,8 +58,24 @@ __device__ __forceinline__ unsigned short bf16_rne(float f)
     return (unsigned short)(u >> 16);
 }
 
-// BF: bf16 tensors (else fp32).  KS: K steps of 32 bytes per tap and chunk (CB / 32): 1, 2 or 4.
-template <bool BF, int KS>
+// the one rounding of a finished value to the tensor's 16-bit format
+template <int EK>
+__device__ __forceinline__ unsigned short round16(float f)
+{
+    if constexpr (EK == kElemF16) return __builtin_bit_cast(unsigned short, (_Float16)f);      // v_cvt_f16_f32: nearest even
+    else return bf16_rne(f);
+}
+
+// a 16-bit element widened to fp32 (exact)
+template <int EK>
+__device__ __forceinline__ float widen16(unsigned short h)
+{
+    if constexpr (EK == kElemF16) return (float)__builtin_bit_cast(_Float16, h);
+    else return __uint_as_float((unsigned)h << 16);
+}
+
+// EK: element format (Elem).  KS: K steps of 32 bytes per tap and chunk (CB / 32): 1, 2 or 4.
+template <int EK, int KS>
 __global__ __launch_bounds__(256, 1) void mfma_nhwc_kernel(const unsigned char* __restrict__ x,
                                                            const unsigned char* __restrict__ w, void* __restrict__ yv,
                                                            const NhwcFParams P)
@@ -130,7 +149,10 @@ __global__ __launch_bounds__(256, 1) void mfma_nhwc_kernel(const unsigned char* 
 #pragma unroll
             for (int b = 0; b < kBlocksPerWave; ++b)
                 if (wp + 2 * b < nblocks) {             // (wave-uniform)
-                    if constexpr (BF) {
+                    if constexpr (EK == kElemF16) {
+                        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, o.aq[k][b]),
+                                                                        __builtin_bit_cast(halfx8, o.bq[k]), acc[b], 0, 0, 0);
+                    } else if constexpr (EK == kElemBF16) {
                         acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.aq[k][b]),
                                                                          __builtin_bit_cast(bf16x8, o.bq[k]), acc[b], 0, 0, 0);
                     } else {
@@ -219,7 +241,7 @@ __global__ __launch_bounds__(256, 1) void mfma_nhwc_kernel(const unsigned char* 
             if (P.ep.bias) t += bias;
             if (P.ep.relu) t = fmaxf(t, 0.f);
             if (p < npix) {
-                if constexpr (BF) static_cast<unsigned short*>(yv)[(pix0 + p) * P.C_out + co] = bf16_rne(t);
+                if constexpr (EK != kElemF32) static_cast<unsigned short*>(yv)[(pix0 + p) * P.C_out + co] = round16<EK>(t);
                 else static_cast<float*>(yv)[(pix0 + p) * P.C_out + co] = t;
             }
         }
@@ -227,7 +249,7 @@ __global__ __launch_bounds__(256, 1) void mfma_nhwc_kernel(const unsigned char* 
 }
 
 // One thread per output, any shape: the channel loop runs over contiguous elements of both tensors.
-template <bool BF>
+template <int EK>
 __global__ __launch_bounds__(256) void direct_nhwc_kernel(const void* __restrict__ xv, const void* __restrict__ wv,
                                                           void* __restrict__ yv, Conv2dShape s, Epilogue ep)
 {
@@ -247,11 +269,11 @@ __global__ __launch_bounds__(256) void direct_nhwc_kernel(const void* __restrict
                 const int v = oj * s.stride + q * s.dil - s.pad;
                 if (v < 0 || v >= s.W) continue;
                 const int64_t xo = (((int64_t)n * s.H + h) * s.W + v) * s.C_in, wo = (((int64_t)co * s.R + r) * s.S + q) * s.C_in;
-                if constexpr (BF) {
+                if constexpr (EK != kElemF32) {
                     const unsigned short* xp = static_cast<const unsigned short*>(xv) + xo;
                     const unsigned short* wp = static_cast<const unsigned short*>(wv) + wo;
                     for (int ci = 0; ci < s.C_in; ++ci)
-                        acc = fmaf(__uint_as_float((unsigned)xp[ci] << 16), __uint_as_float((unsigned)wp[ci] << 16), acc);
+                        acc = fmaf(widen16<EK>(xp[ci]), widen16<EK>(wp[ci]), acc);
                 } else {
                     const float* xp = static_cast<const float*>(xv) + xo;
                     const float* wp = static_cast<const float*>(wv) + wo;
@@ -261,7 +283,7 @@ __global__ __launch_bounds__(256) void direct_nhwc_kernel(const void* __restrict
         }
         if (ep.bias) acc += ep.bias[co];
         if (ep.relu) acc = fmaxf(acc, 0.f);
-        if constexpr (BF) static_cast<unsigned short*>(yv)[o] = bf16_rne(acc);
+        if constexpr (EK != kElemF32) static_cast<unsigned short*>(yv)[o] = round16<EK>(acc);
         else static_cast<float*>(yv)[o] = acc;
     }
 }
@@ -329,54 +351,57 @@ NhwcFPlan plan_nhwc_f(const Conv2dShape& s, int esz)
     return a;
 }
 
-template <bool BF, int KS>
+template <int EK, int KS>
 hipError_t launch_nhwc_f(const void* x, const void* w, void* y, const NhwcFPlan& a, const Conv2dShape& s, hipStream_t st)
 {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_nhwc_kernel<BF, KS>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_nhwc_kernel<EK, KS>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBudget);
     if (attr != hipSuccess) return attr;
     dim3 grid((unsigned)a.bands, (unsigned)s.N, (unsigned)((s.C_out + 63) / 64));
-    SW_NOTED_LAUNCH(note_kernel("mfma_nhwc_kernel", (int)BF, KS), (mfma_nhwc_kernel<BF, KS>), grid, dim3(256), a.lds, st,
+    SW_NOTED_LAUNCH(note_kernel("mfma_nhwc_kernel", EK, KS), (mfma_nhwc_kernel<EK, KS>), grid, dim3(256), a.lds, st,
                     static_cast<const unsigned char*>(x), static_cast<const unsigned char*>(w), y, a.P);
     return hipGetLastError();
 }
 
 }  // namespace
 
-// esz: 4 (fp32) or 2 (bf16)
-bool mfma_nhwc_supported(const void* x, const void* w, const Conv2dShape& s, int esz)
+bool mfma_nhwc_supported(const void* x, const void* w, const Conv2dShape& s, int ek)
 {
-    return reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 && plan_nhwc_f(s, esz).ok;
+    return reinterpret_cast<uintptr_t>(x) % 16 == 0 && reinterpret_cast<uintptr_t>(w) % 16 == 0 && plan_nhwc_f(s, elem_size(ek)).ok;
 }
 
-hipError_t launch_mfma_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int esz, const Epilogue& ep,
+hipError_t launch_mfma_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep,
                             hipStream_t st)
 {
-    NhwcFPlan a = plan_nhwc_f(s, esz);
+    NhwcFPlan a = plan_nhwc_f(s, elem_size(ek));
     if (!a.ok) return hipErrorInvalidValue;
     a.P.ep = ep;
-#define SW_NHWC(BFC)                                                             \
+#define SW_NHWC(EKC)                                                             \
     do {                                                                         \
-        if (a.KS == 4) return launch_nhwc_f<BFC, 4>(x, w, y, a, s, st);          \
-        if (a.KS == 2) return launch_nhwc_f<BFC, 2>(x, w, y, a, s, st);          \
-        return launch_nhwc_f<BFC, 1>(x, w, y, a, s, st);                         \
+        if (a.KS == 4) return launch_nhwc_f<EKC, 4>(x, w, y, a, s, st);          \
+        if (a.KS == 2) return launch_nhwc_f<EKC, 2>(x, w, y, a, s, st);          \
+        return launch_nhwc_f<EKC, 1>(x, w, y, a, s, st);                         \
     } while (0)
-    if (esz == 2) SW_NHWC(true);
-    SW_NHWC(false);
+    if (ek == kElemF16) SW_NHWC(kElemF16);
+    if (ek == kElemBF16) SW_NHWC(kElemBF16);
+    SW_NHWC(kElemF32);
 #undef SW_NHWC
 }
 
-hipError_t launch_direct_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int esz, const Epilogue& ep,
+hipError_t launch_direct_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep,
                               hipStream_t st)
 {
     const int64_t total = (int64_t)s.N * s.Ho * s.Wo * s.C_out;
     int64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 64) blocks = 256 * 64;
-    if (esz == 2)
-        SW_NOTED_LAUNCH(note_kernel("direct_nhwc_kernel", 1), direct_nhwc_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, x,
-                        w, y, s, ep);
+    if (ek == kElemF16)
+        SW_NOTED_LAUNCH(note_kernel("direct_nhwc_kernel", 2), direct_nhwc_kernel<kElemF16>, dim3((unsigned)blocks), dim3(256), 0, st,
+                        x, w, y, s, ep);
+    else if (ek == kElemBF16)
+        SW_NOTED_LAUNCH(note_kernel("direct_nhwc_kernel", 1), direct_nhwc_kernel<kElemBF16>, dim3((unsigned)blocks), dim3(256), 0, st,
+                        x, w, y, s, ep);
     else
-        SW_NOTED_LAUNCH(note_kernel("direct_nhwc_kernel", 0), direct_nhwc_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st,
+        SW_NOTED_LAUNCH(note_kernel("direct_nhwc_kernel", 0), direct_nhwc_kernel<kElemF32>, dim3((unsigned)blocks), dim3(256), 0, st,
                         x, w, y, s, ep);
     return hipGetLastError();
 }

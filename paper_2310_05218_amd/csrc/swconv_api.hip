@@ -302,10 +302,11 @@ int sw_conv2d_depthwise(const float* x, const float* w, float* y, int N, int C, 
     return run_plane(x, w, y, (int64_t)N * C, 1, C, s, true, st);
 }
 
-// fp32 (esz 4) / bf16 (esz 2) convolution on channel-last tensors with the store's epilogue
+// fp32 / bf16 / half (ek: Elem) convolution on channel-last tensors with the store's epilogue
 static int run_nhwc(const void* x, const void* w, const float* bias, void* y, int N, int H, int W, int C_in, int C_out,
-                    int R, int S, int stride, int pad, int dilation, int relu, int esz, void* hip_stream)
+                    int R, int S, int stride, int pad, int dilation, int relu, int ek, void* hip_stream)
 {
+    const int esz = elem_size(ek);
     Conv2dShape s;
     const int rc = check_conv2d(x, w, y, N, C_in, C_out, H, W, R, S, stride, pad, false, (size_t)esz, (size_t)esz, &s,
                                 dilation);
@@ -315,21 +316,27 @@ static int run_nhwc(const void* x, const void* w, const float* bias, void* y, in
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const Epilogue ep{bias, relu != 0};
     if (!force_direct() && esz == 2 && mfma_bf16_nhwc_direct_supported(x, w, y, s))
-        return launch_status(launch_mfma_bf16_nhwc_direct(x, w, y, s, ep, st));
-    if (!force_direct() && mfma_nhwc_supported(x, w, s, esz)) return launch_status(launch_mfma_nhwc(x, w, y, s, esz, ep, st));
-    return launch_status(launch_direct_nhwc(x, w, y, s, esz, ep, st));
+        return launch_status(launch_mfma_bf16_nhwc_direct(x, w, y, s, ek == kElemF16, ep, st));
+    if (!force_direct() && mfma_nhwc_supported(x, w, s, ek)) return launch_status(launch_mfma_nhwc(x, w, y, s, ek, ep, st));
+    return launch_status(launch_direct_nhwc(x, w, y, s, ek, ep, st));
 }
 
 int sw_conv2d_nhwc(const float* x, const float* w, const float* bias, float* y, int N, int H, int W, int C_in, int C_out,
                    int R, int S, int stride, int pad, int dilation, int relu, void* hip_stream)
 {
-    return run_nhwc(x, w, bias, y, N, H, W, C_in, C_out, R, S, stride, pad, dilation, relu, 4, hip_stream);
+    return run_nhwc(x, w, bias, y, N, H, W, C_in, C_out, R, S, stride, pad, dilation, relu, kElemF32, hip_stream);
 }
 
 int sw_conv2d_bf16_nhwc(const void* x, const void* w, const float* bias, void* y, int N, int H, int W, int C_in, int C_out,
                         int R, int S, int stride, int pad, int dilation, int relu, void* hip_stream)
 {
-    return run_nhwc(x, w, bias, y, N, H, W, C_in, C_out, R, S, stride, pad, dilation, relu, 2, hip_stream);
+    return run_nhwc(x, w, bias, y, N, H, W, C_in, C_out, R, S, stride, pad, dilation, relu, kElemBF16, hip_stream);
+}
+
+int sw_conv2d_f16_nhwc(const void* x, const void* w, const float* bias, void* y, int N, int H, int W, int C_in, int C_out,
+                       int R, int S, int stride, int pad, int dilation, int relu, void* hip_stream)
+{
+    return run_nhwc(x, w, bias, y, N, H, W, C_in, C_out, R, S, stride, pad, dilation, relu, kElemF16, hip_stream);
 }
 
 // int8 convolution on channel-last tensors; bias/scale == nullptr and y8 == nullptr: int32 sums

@@ -112,16 +112,18 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0}, int dil = 1);
 
-// ---- fp32 / bf16 multi-channel convolution on channel-last tensors (esz: 4 or 2 bytes per element) ----------
-bool       mfma_nhwc_supported(const void* x, const void* w, const Conv2dShape& s, int esz);
-hipError_t launch_mfma_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int esz, const Epilogue& ep,
+// ---- fp32 / bf16 / half multi-channel convolution on channel-last tensors ------------------------------------
+enum Elem { kElemF32 = 0, kElemBF16 = 1, kElemF16 = 2 };      // element format of x, w and y
+constexpr int elem_size(int ek) { return ek == kElemF32 ? 4 : 2; }
+bool       mfma_nhwc_supported(const void* x, const void* w, const Conv2dShape& s, int ek);
+hipError_t launch_mfma_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep,
                             hipStream_t st);
-// bf16 with the pixel operand read straight from global memory (C_in % 16 == 0, C_out % 4 == 0, filters of the
-// channel block resident in LDS)
+// 16-bit formats with the pixel operand read straight from global memory (C_in % 16 == 0, C_out % 4 == 0, filters of
+// the channel block resident in LDS)
 bool       mfma_bf16_nhwc_direct_supported(const void* x, const void* w, const void* y, const Conv2dShape& s);
-hipError_t launch_mfma_bf16_nhwc_direct(const void* x, const void* w, void* y, const Conv2dShape& s, const Epilogue& ep,
+hipError_t launch_mfma_bf16_nhwc_direct(const void* x, const void* w, void* y, const Conv2dShape& s, bool f16, const Epilogue& ep,
                                         hipStream_t st);
-hipError_t launch_direct_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int esz, const Epilogue& ep,
+hipError_t launch_direct_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep,
                               hipStream_t st);
 
 // ---- depthwise 3x3 (stride 1, padding 1) -> pointwise 1x1 in one launch, the intermediate only in LDS

@@ -76,4 +76,18 @@ yv = oracle.bf16_to_f32(yb.view(torch.int16).cpu().numpy().view(np.uint16)).asty
 y_ref, d = oracle.conv2d_depthwise(oracle.bf16_to_f32(xb), w3, 1, 1)
 assert np.all(np.abs(yv - y_ref) <= 2e-5 * d + 2.0 ** -8 * np.abs(y_ref) + 1e-37)
 ran_direct("sw_conv2d_depthwise_bf16")
+# the 16-bit and fp32 channel-last calls on a shape their matrix-core kernels would take
+xh, wh = inputs.normal_f16((1, 10, 10, 32), 5301), inputs.normal_f16((16, 3, 3, 32), 5302, 0.1)
+h16 = lambda a, dt: torch.from_numpy(a.view(np.int16)).cuda().view(dt)
+yh = sw.sw_conv2d_f16_nhwc(h16(xh, torch.float16), h16(wh, torch.float16), 1, 1)
+y_ref, d = oracle.conv2d_f16_nhwc(xh, wh, 1, 1)
+yv = oracle.f16_to_f32(yh.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+assert np.all(np.abs(yv - y_ref) <= 2e-5 * d + 2.0 ** -11 * np.abs(y_ref) + 2.0 ** -25)
+ran_direct("sw_conv2d_f16_nhwc")
+xb2, wb2 = inputs.normal_bf16((1, 10, 10, 32), 5303), inputs.normal_bf16((16, 3, 3, 32), 5304, 0.1)
+yb2 = sw.sw_conv2d_bf16_nhwc(h16(xb2, torch.bfloat16), h16(wb2, torch.bfloat16), 1, 1)
+y_ref, d = oracle.conv2d_bf16_nhwc(xb2, wb2, 1, 1)
+yv = oracle.bf16_to_f32(yb2.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+assert np.all(np.abs(yv - y_ref) <= 2e-5 * d + 2.0 ** -8 * np.abs(y_ref) + 1e-37)
+ran_direct("sw_conv2d_bf16_nhwc")
 print("force-direct ok", flush=True)

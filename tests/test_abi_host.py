@@ -298,7 +298,7 @@ def test_binding_refuses_host_tensors(L):
 
 
 def test_float_nhwc_argument_errors(L):
-    for f, esz in ((L.sw_conv2d_nhwc, 4), (L.sw_conv2d_bf16_nhwc, 2)):
+    for f, esz in ((L.sw_conv2d_nhwc, 4), (L.sw_conv2d_bf16_nhwc, 2), (L.sw_conv2d_f16_nhwc, 2)):
         B_ = 0x2100000
         ok = (2, 8, 8, 32, 64, 3, 3, 1, 1, 1)      # N, H, W, C_in, C_out, R, S, stride, pad, dilation
         assert f(None, W_, None, Y, *ok, 0, None) == B.SW_ERR_NULL

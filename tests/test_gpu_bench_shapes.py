@@ -164,6 +164,10 @@ def test_layer(torch, sw, oracle, idx):
         y_ref, mag = oracle.conv2d_bf16_nhwc(x, w, st, p)
         yv = oracle.bf16_to_f32(y.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
         assert np.all(np.abs(yv - y_ref) <= 2e-5 * mag + 2.0 ** -8 * np.abs(y_ref) + 1e-37), name
+    elif kind == "conv_f16_nhwc":
+        y_ref, mag = oracle.conv2d_f16_nhwc(x, w, st, p)
+        yv = oracle.f16_to_f32(y.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        assert np.all(np.abs(yv - y_ref) <= 2e-5 * mag + 2.0 ** -11 * np.abs(y_ref) + 2.0 ** -25), name
     elif kind in ("conv_s8", "conv_s8_pk"):
         assert np.array_equal(y.cpu().numpy(), oracle.conv2d_s8(x, w, st, p)), name
     elif kind in ("conv_s8_rq", "conv_s8_pk_rq"):

@@ -170,6 +170,69 @@ def test_conv2d_nhwc_bf16(torch, sw, oracle, case):
             f"nhwc bf16 {case} relu={relu}: max excess {np.max(np.abs(y - y_ref) - 2e-5 * d - 2.0 ** -8 * np.abs(y_ref)):.3e}"
 
 
+def _f16_case(torch, sw, oracle, xh, wh, stride, pad, dil, bias, relu, kernel, what):
+    """One half-precision call against the oracle: |y - oracle| <= 2e-5 * D (the fp32 sums) + 2^-11 |oracle| (one rounding
+    to half precision: half a unit in the last of 11 significant bits) + 2^-25 (half the spacing of its denormals)."""
+    as_f16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+    y_ref, d = oracle.conv2d_f16_nhwc(xh, wh, stride, pad, dil, bias, relu)
+    n = y_ref.size
+    buf = torch.full((128 + n + 64,), 12345.0, dtype=torch.float16, device="cuda")
+    out = buf[128:128 + n].view(y_ref.shape)
+    sw.sw_conv2d_f16_nhwc(as_f16(xh), as_f16(wh), stride, pad, dil, None if bias is None else dev(torch, bias), relu, out=out)
+    if kernel is not None:
+        assert sw.sw_last_kernel() == kernel, sw.sw_last_kernel()
+    torch.cuda.synchronize()
+    guard = buf.view(torch.int16)
+    assert bool((guard[:128] == guard[0]).all()) and bool((guard[128 + n:] == guard[0]).all()), "write outside y"
+    y = oracle.f16_to_f32(out.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+    bound = 2e-5 * d + 2.0 ** -11 * np.abs(y_ref) + 2.0 ** -25
+    assert np.all(np.abs(y - y_ref) <= bound), f"nhwc f16 {what} relu={relu}: max excess {np.max(np.abs(y - y_ref) - bound):.3e}"
+    return y, y_ref
+
+
+@pytest.mark.parametrize("case", FLOAT_CASES, ids=lambda c: "x".join(map(str, c[:10])))
+def test_conv2d_nhwc_f16(torch, sw, oracle, case):
+    """IEEE half precision in and out, fp32 accumulation, on every shape of the bf16 cases (the same kernels with the
+    half-precision matrix instruction and rounding)."""
+    N, H, W, C_in, C_out, R, S, stride, pad, dil, _, kernel = case
+    kernel = kernel.replace("mfma_bf16_nhwc_direct", "mfma_f16_nhwc_direct").replace("mfma_nhwc_kernel<1,", "mfma_nhwc_kernel<2,") \
+        .replace("direct_nhwc_kernel<1>", "direct_nhwc_kernel<2>")
+    xh = inputs.normal_f16((N, H, W, C_in), 5231)
+    wh = inputs.normal_f16((C_out, R, S, C_in), 5232, (2.0 / (C_in * R * S)) ** 0.5)
+    b = inputs.normal_f32((C_out,), 5233, 0.5)
+    for bias, relu in ((None, False), (b, True)):
+        _f16_case(torch, sw, oracle, xh, wh, stride, pad, dil, bias, relu, kernel, case)
+
+
+@pytest.mark.parametrize("shape", [(2, 14, 14, 32, 32, "mfma_f16_nhwc_direct_kernel<1,2>"), (1, 14, 14, 32, 30, "mfma_nhwc_kernel<2,2>"),
+                                   (1, 9, 9, 12, 8, "direct_nhwc_kernel<2>")], ids=lambda s: s[5])
+def test_conv2d_nhwc_f16_denormals_and_overflow(torch, sw, oracle, shape):
+    """What half precision has and bf16 has not: denormal inputs count (activations of about 2^-16 against filters of
+    about 2^6: were the denormals flushed the sums would vanish), results below 2^-14 are kept as denormals, results
+    beyond 65504 become infinities of the right sign."""
+    N, H, W, C_in, C_out, kernel = shape
+    x_small = inputs.normal_f16((N, H, W, C_in), 5241, 2.0 ** -16)
+    assert np.mean((x_small & 0x7C00) == 0) > 0.9                      # nearly all denormal
+    w_big = inputs.normal_f16((C_out, 3, 3, C_in), 5242, 64.0)
+    y, y_ref = _f16_case(torch, sw, oracle, x_small, w_big, 1, 1, 1, None, False, kernel, "denormal x")
+    assert np.median(np.abs(y_ref)) > 2.0 ** -10 and np.count_nonzero(y) > 0.99 * y.size
+    w_small = inputs.normal_f16((C_out, 3, 3, C_in), 5243, 2.0 ** -6)
+    y, y_ref = _f16_case(torch, sw, oracle, x_small, w_small, 1, 1, 1, None, False, kernel, "denormal y")
+    assert np.max(np.abs(y_ref)) < 2.0 ** -14 and np.count_nonzero(y) > 0.5 * y.size
+    # overflow: every product 200 * 200, so a full window sums to 9 * C_in * 40000 > 65504; the sign follows the filter
+    as_f16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.float16)
+    xo = np.full((N, H, W, C_in), 200.0, np.float16).view(np.uint16)
+    wo = np.full((C_out, 3, 3, C_in), 200.0, np.float16)
+    wo[1::2] = -200.0
+    out = sw.sw_conv2d_f16_nhwc(as_f16(xo), as_f16(wo.view(np.uint16)), 1, 1)
+    assert sw.sw_last_kernel() == kernel
+    yo = out.float().cpu().numpy()
+    y_ref, _ = oracle.conv2d_f16_nhwc(xo, wo.view(np.uint16), 1, 1)
+    with np.errstate(over="ignore"):
+        assert np.array_equal(yo, y_ref.astype(np.float16).astype(np.float32)) and np.isinf(yo).all()
+    assert (yo[..., 0::2] > 0).all() and (yo[..., 1::2] < 0).all()
+
+
 def test_nhwc_is_the_channel_first_call_on_permuted_tensors(torch, sw):
     """Same sums, other layout: the two fp32 entry points agree to rounding order on a layer both take."""
     x = inputs.normal_f32((2, 64, 28, 28), 5221)

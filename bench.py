@@ -359,6 +359,7 @@ def layer_case(idx, n_images=None, data=True):
             normal_f32 = staticmethod(lambda shape, seed, std=1.0: np.zeros(shape, np.float32))
             uniform_s8 = staticmethod(lambda shape, seed: np.zeros(shape, np.int8))
             normal_bf16 = staticmethod(lambda shape, seed, std=1.0: np.zeros(shape, np.uint16))
+            normal_f16 = staticmethod(lambda shape, seed, std=1.0: np.zeros(shape, np.uint16))
 
     name, kind, shape, R, stride, pad, *more = LAYERS[idx]
     N, C, H, W = shape
@@ -376,9 +377,6 @@ def layer_case(idx, n_images=None, data=True):
         if kind.endswith("rq"):
             c["bias"] = rng.integers(-50000, 50000, size=c["C_out"]).astype(np.int32)
             c["scale"] = (rng.uniform(1.0, 3.0, size=c["C_out"]) * 2.0 ** -18).astype(np.float32)
-        if kind == "conv_f16_nhwc":         # (the same draws, rounded to half-precision bit patterns)
-            x = inputs.normal_f16((N, C, H, W), inputs.seed_for(7, idx))
-            w = inputs.normal_f16((c["C_out"], C, R, R), inputs.seed_for(7, 100 + idx), (2.0 / (C * R * R)) ** 0.5)
         if "nhwc" in kind:
             x = np.ascontiguousarray(x.transpose(0, 2, 3, 1))
             w = np.ascontiguousarray(w.transpose(0, 2, 3, 1))

@@ -246,6 +246,9 @@ static int run_conv2d(const float* x, const float* w, float* y, const Conv2dShap
         const bool any_ok = quad_ok || mfma_f32_any_supported(s);
         if (mfma_f32_supported(s) && (mfma_f32_workgroups(s) >= 160 || !any_ok))
             return launch_status(launch_mfma_f32(x, w, y, s, st, ep));
+        // few taps over whole groups of eight channels: operands by direct-to-LDS loads, the next chunk in flight
+        // while this one multiplies
+        if (mfma_f32_dma_supported(s, x, w)) return launch_status(launch_mfma_f32_dma(x, w, y, s, st, ep));
         if (quad_ok) return launch_status(launch_mfma_f32_quad(x, w, y, s, st, ep));
         if (any_ok) return launch_status(launch_mfma_f32_any(x, w, y, s, st, ep));
         if (mfma_f32_rows_supported(s, x)) return launch_status(launch_mfma_f32_rows(x, w, y, s, st, ep));

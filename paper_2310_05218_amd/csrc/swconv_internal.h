@@ -112,6 +112,12 @@ hipError_t launch_sliding_plane(const float* x, const float* w, float* y, int64_
                                 int planes_per_x, int n_filters, int H, int W, int R, int S, int pad,
                                 int Ho, int Wo, hipStream_t st, const Epilogue& ep = Epilogue{nullptr, 0}, int dil = 1);
 
+// ---- multi-channel fp32, few taps (1x1 ... 4x4), C_in % 8 == 0, any stride / padding / dilation: both operands
+// brought into LDS by direct-to-LDS loads, two stages (16-byte aligned w, tensors below 2 GiB)
+bool       mfma_f32_dma_supported(const Conv2dShape& s, const float* x, const float* w);
+hipError_t launch_mfma_f32_dma(const float* x, const float* w, float* y, const Conv2dShape& s, hipStream_t st,
+                               const Epilogue& ep = Epilogue{nullptr, 0});
+
 // ---- fp32 / bf16 / half multi-channel convolution on channel-last tensors ------------------------------------
 enum Elem { kElemF32 = 0, kElemBF16 = 1, kElemF16 = 2 };      // element format of x, w and y
 constexpr int elem_size(int ek) { return ek == kElemF32 ? 4 : 2; }

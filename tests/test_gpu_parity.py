@@ -484,6 +484,67 @@ def test_dilation_one_is_the_undilated_call(torch, sw):
     assert torch.equal(sw.sw_conv2d_dilated(x, w, 1, 1, 1), sw.sw_conv2d(x, w, 1, 1))
 
 
+DMA_KERNEL_CASES = [
+    # N, C_in, C_out, H, W, R, S, stride, pad, dilation, kernel<blocks per wavefront, channels per chunk, images and rows per tile>
+    (1, 8, 64, 12, 12, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,1,6>"),       # one chunk, two row tiles of 72 pixels
+    (2, 16, 40, 14, 14, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,1,7>"),      # two chunks, channel block with 24 dead channels
+    (3, 32, 70, 7, 7, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,2,7>"),        # two whole images per tile, the last tile with one
+    (7, 16, 64, 5, 6, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,4,5>"),        # four images per tile (120 pixels), 7 = 4 + 3
+    (2, 16, 64, 30, 41, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,1,3>"),      # blocks that span rows, ragged last block
+    (1, 24, 96, 57, 57, 3, 3, 2, 1, 1, "mfma_f32_dma_kernel<1,8,1,4>"),      # stride 2, three chunks, ragged channel block
+    (1, 8, 64, 28, 28, 3, 3, 1, 2, 2, "mfma_f32_dma_kernel<1,8,1,4>"),       # dilation 2
+    (1, 16, 64, 40, 40, 3, 3, 2, 3, 3, "mfma_f32_dma_kernel<1,8,1,4>"),      # dilation 3 with stride 2
+    (2, 64, 64, 19, 23, 1, 1, 2, 0, 1, "mfma_f32_dma_kernel<1,32,1,4>"),     # one tap at stride 2: chunks of 32 channels
+    (1, 16, 32, 20, 20, 4, 4, 1, 2, 1, "mfma_f32_dma_kernel<1,8,1,5>"),      # 16 taps, even extents
+    (1, 8, 16, 9, 200, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<2,8,1,1>"),       # rows of 200 pixels: two blocks per wavefront, four window slots
+    (5, 8, 64, 5, 5, 2, 2, 1, 0, 1, "mfma_f32_dma_kernel<1,8,5,4>"),         # 2x2, five whole images per tile
+    (2, 40, 64, 16, 16, 3, 1, 1, 1, 1, "mfma_f32_dma_kernel<1,8,1,6>"),      # a column filter; five chunks
+    (5, 8, 256, 56, 56, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<2,8,1,4>"),      # 224-pixel tiles: two blocks per wavefront, the last wavefront one
+    (1, 32, 64, 18, 18, 2, 2, 1, 0, 1, "mfma_f32_dma_kernel<1,16,1,6>"),     # 2x2: chunks of 16 channels
+    (1, 8, 64, 3, 3, 3, 3, 1, 0, 1, "mfma_f32_dma_kernel<1,8,1,1>"),         # a single output pixel
+]
+
+
+@pytest.mark.parametrize("case", DMA_KERNEL_CASES, ids=lambda c: "x".join(map(str, c[:10])))
+def test_conv2d_direct_to_lds_kernel(torch, sw, oracle, case):
+    """Few taps over whole groups of eight channels: the kernel whose operands come into LDS by direct-to-LDS loads,
+    on every tiling it has, with and without the fused epilogue."""
+    N, C_in, C_out, H, W, R, S, stride, pad, dil, kernel = case
+    x = inputs.normal_f32((N, C_in, H, W), 3401)
+    w = inputs.normal_f32((C_out, C_in, R, S), 3402, (2.0 / (C_in * R * S)) ** 0.5)
+    y_ref, d = oracle.conv2d_dilated(x, w, stride, pad, dil)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_dilated(dev(torch, x), dev(torch, w), stride, pad, dil, out=out)
+    assert sw.sw_last_kernel() == kernel, sw.sw_last_kernel()
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"direct-to-LDS kernel {case}")
+    if dil == 1 and N <= 7:
+        bias = inputs.normal_f32((C_out,), 3403, 0.7)
+        y_ref, d = oracle.conv2d_bias_relu(x, w, bias, stride, pad, True)
+        y = sw.sw_conv2d_bias_relu(dev(torch, x), dev(torch, w), dev(torch, bias), stride, pad, True)
+        assert sw.sw_last_kernel() == kernel, sw.sw_last_kernel()
+        assert_f32_parity(y.cpu().numpy(), y_ref, d, f"direct-to-LDS kernel, bias + rectifier {case}")
+
+
+def test_conv2d_direct_to_lds_kernel_needs_aligned_filters(torch, sw, oracle):
+    """Filters that do not start on a 16-byte boundary (or channel counts off the grid of eight) take the older
+    window kernels, with the same results."""
+    x = inputs.normal_f32((2, 16, 14, 14), 3411)
+    w = inputs.normal_f32((64, 16, 3, 3), 3412, 0.1)
+    y_ref, d = oracle.conv2d(x, w, 1, 1)
+    wbuf = torch.zeros(w.size + 1, device="cuda")
+    wbuf[1:] = dev(torch, w).reshape(-1)
+    y = sw.sw_conv2d(dev(torch, x), wbuf[1:].view(64, 16, 3, 3), 1, 1)
+    assert sw.sw_last_kernel().startswith("mfma_f32_quad_kernel"), sw.sw_last_kernel()
+    assert_f32_parity(y.cpu().numpy(), y_ref, d, "misaligned filters")
+    x12 = inputs.normal_f32((2, 12, 14, 14), 3413)
+    w12 = inputs.normal_f32((64, 12, 3, 3), 3414, 0.1)
+    y = sw.sw_conv2d(dev(torch, x12), dev(torch, w12), 1, 1)
+    assert sw.sw_last_kernel().startswith("mfma_f32_quad_kernel"), sw.sw_last_kernel()
+    assert_f32_parity(y.cpu().numpy(), *oracle.conv2d(x12, w12, 1, 1), "twelve channels")
+
+
 DW_BIAS_RELU_CASES = [
     # N, C, H, W, R, S, stride, pad -- one per kernel of the one-filter-per-plane dispatch
     (2, 256, 56, 56, 3, 3, 1, 1),        # whole-plane kernel, 56 x 56 specialisation

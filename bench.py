@@ -124,7 +124,11 @@ def measured_peaks(torch, sw):
                              ("fma_f32_tflops", sw.SW_PROBE_FMA_F32, 1000),
                              # plain FMAs and fp32 matrix instructions in one stream: the sum of the two rates if the
                              # pipes overlapped; measured, a round takes the sum of the two times instead
-                             ("fma_plus_mfma_f32_tflops", sw.SW_PROBE_FMA_MFMA_F32, 2000)):
+                             ("fma_plus_mfma_f32_tflops", sw.SW_PROBE_FMA_MFMA_F32, 2000),
+                             # fp32 matrix instructions fed from LDS (one 4-byte operand read behind each), one and two
+                             # wavefronts per SIMD: what a stream of them sustains once it has operands to fetch
+                             ("mfma_f32_fed_tflops", sw.SW_PROBE_MFMA_F32_FED, 4000),
+                             ("mfma_f32_fed_two_wavefronts_tflops", sw.SW_PROBE_MFMA_F32_FED2, 4000)):
         ops = sw.sw_probe(kind, iters)
         us = time_kernel(torch, lambda d: sw.sw_probe(kind, iters), [None], 10, 3)
         out[key] = round(ops / us / 1e6, 1)
@@ -700,6 +704,8 @@ def main():
                 row[SECOND_ROOF[n][1]] = round(ops / cold / 1e6 / SECOND_ROOF[n][0], 4)
             if n in MEASURED_ROOF:
                 row["frac_of_measured_" + MEASURED_ROOF[n]] = round(ops / cold / 1e6 / peaks[MEASURED_ROOF[n]], 4)
+            if n == "conv2d_64x64_3x3":      # one multiplying wavefront per SIMD: against the operand-fed stream as well
+                row["frac_of_measured_mfma_f32_fed_tflops"] = round(ops / cold / 1e6 / peaks["mfma_f32_fed_tflops"], 4)
             if bound == "hbm" or n in ALSO_HBM:
                 row["frac_hbm"] = round(nbytes / cold / 1e3 / HBM_GBS, 4)
                 row["copy_gbs_same_bytes"] = round(copy_gbs(nbytes), 1)

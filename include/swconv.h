@@ -392,7 +392,8 @@ int sw_version(void);
 
 /*
  * Measurement aids (no part of the convolution path): sw_probe enqueues a kernel that issues `iters` loop
- * turns of one kind of arithmetic instruction on every SIMD of the device and touches no memory;
+ * turns of one kind of arithmetic instruction on every SIMD of the device and touches no memory (the two
+ * "fed" kinds read their operands from LDS, one workgroup of one or two wavefronts per SIMD on every CU);
  * sw_probe_ops(kind, iters) is the number of arithmetic operations (2 per multiply-add) that launch performs.
  * Timing the launch gives the rate the chip sustains for that instruction, to quote beside the datasheet peak.
  * SW_ERR_SHAPE for iters <= 0, SW_ERR_UNSUPPORTED for an unknown kind.
@@ -401,7 +402,9 @@ typedef enum {
     SW_PROBE_MFMA_F32 = 0,  /* v_mfma_f32_32x32x2_f32                                  */
     SW_PROBE_MFMA_I8 = 1,   /* v_mfma_i32_32x32x32_i8                                  */
     SW_PROBE_FMA_F32 = 2,   /* v_fma_f32, wave-uniform multiplicand (no packed forms)  */
-    SW_PROBE_FMA_MFMA_F32 = 3 /* nine v_fma_f32, one v_mfma_f32_16x16x4_f32, ... in one stream: do the two pipes overlap? */
+    SW_PROBE_FMA_MFMA_F32 = 3, /* nine v_fma_f32, one v_mfma_f32_16x16x4_f32, ... in one stream: do the two pipes overlap? */
+    SW_PROBE_MFMA_F32_FED = 4, /* v_mfma_f32_32x32x2_f32 with one 4-byte LDS operand read behind each, one wavefront per SIMD */
+    SW_PROBE_MFMA_F32_FED2 = 5 /* the same with two wavefronts per SIMD */
 } sw_probe_kind;
 int sw_probe(int kind, int iters, void* hip_stream);
 int64_t sw_probe_ops(int kind, int iters);

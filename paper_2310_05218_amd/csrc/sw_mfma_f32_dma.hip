@@ -64,7 +64,9 @@ struct DmaParams {
 
 // Wavefronts 0 .. 3 multiply, wavefronts 4 .. 7 only load: a wavefront that issues loads sits in their issue until the
 // memory pipeline has taken them, and in a wavefront of its own that wait holds no matrix instruction back.
-template <int NBW>
+// NGT: the number of groups per chunk as a compile-time constant (0: run-time): the loop over groups is unrolled, the
+// per-K offsets stay in registers (no table reads) and all address arithmetic of a group sits in one slot.
+template <int NBW, int NGT>
 __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __restrict__ x, const float* __restrict__ w,
                                                                             float* __restrict__ y, const DmaParams P)
 {
@@ -167,8 +169,8 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
         for (int v = 0; v < 16; ++v) { acc[b][0][v] = 0.f; acc[b][1][v] = 0.f; }
 
     // One chunk on NL blocks.  Group g = K values 8g .. 8g + 7 = 8 NL matrix instructions; a wavefront issues in order, so
-    // what keeps the matrix pipe busy is other work placed BETWEEN its instructions: behind each of the first ones sit
-    // two operand reads of group g + 1 (into the other register set), the offsets of group g + 2 among them.
+    // what keeps the matrix pipe busy is other work placed BETWEEN its instructions: behind the first one sit the
+    // operand reads of group g + 1 (into the other register set) and the read of the offsets of group g + 2.
     const int arow = 16 * P.PCp;                                                // bytes per output channel's filter row
     const unsigned char* tp = smem + P.tbl_off + 16 * kk;                       // + 32 g
     __syncthreads();                                                            // (the table; the loaders pass it too)
@@ -196,14 +198,16 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
                         const int m = (t * NL + b) * 2 + h;
                         acc[b][h] = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? cur.a1[t] : cur.a0[t], cur.b[b][t], acc[b][h], 0, 0, 0);
                         __builtin_amdgcn_sched_barrier(0);
-                        // two of the 3 + 4 NL reads behind each of the first matrix instructions
+                        // everything else of the group in ONE slot: a matrix instruction that follows another issues
+                        // without a gap, one that follows anything else pays a few cycles, however much else it was
+                        if (m == 0) {
+                            nxt.a0 = *reinterpret_cast<const floatx4*>(ap0 + 32 * gn);
+                            nxt.a1 = *reinterpret_cast<const floatx4*>(ap1 + 32 * gn);
 #pragma unroll
-                        for (int item = 2 * m; item < 2 * m + 2; ++item) {
-                            if (item == 0) nxt.a0 = *reinterpret_cast<const floatx4*>(ap0 + 32 * gn);
-                            else if (item == 1) nxt.a1 = *reinterpret_cast<const floatx4*>(ap1 + 32 * gn);
-                            else if (item == 2) tl = *reinterpret_cast<const intx4*>(tp + 32 * g2);
-                            else if (item < 3 + 4 * NL)
-                                nxt.b[(item - 3) >> 2][(item - 3) & 3] = *reinterpret_cast<const float*>(bp + pixoff[(item - 3) >> 2] + tn[(item - 3) & 3]);
+                            for (int bq = 0; bq < NL; ++bq)
+#pragma unroll
+                                for (int tq = 0; tq < 4; ++tq) nxt.b[bq][tq] = *reinterpret_cast<const float*>(bp + pixoff[bq] + tn[tq]);
+                            tl = *reinterpret_cast<const intx4*>(tp + 32 * g2);
                         }
                         __builtin_amdgcn_sched_barrier(0);
                     }
@@ -223,10 +227,74 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
         }
     };
 
+    // The same with the group loop unrolled and the offsets of every K value in registers (no table reads).
+    int treg[NGT > 0 ? NGT : 1][4];
+    if constexpr (NGT > 0) {
+#pragma unroll
+        for (int g = 0; g < NGT; ++g) {
+            const intx4 t = *reinterpret_cast<const intx4*>(tp + 32 * g);
+            treg[g][0] = t[0]; treg[g][1] = t[1]; treg[g][2] = t[2]; treg[g][3] = t[3];
+        }
+    }
+    auto multiply_unrolled = [&](int stage) __attribute__((always_inline)) {
+        constexpr int NL = NBW;
+        struct Ops {
+            floatx4 a0, a1;
+            float b[NL][4];
+        };
+        const unsigned char* sf = smem + stage * P.stage_bytes;
+        const unsigned char* ap0 = sf + lj * arow + 16 * kk;
+        const unsigned char* ap1 = ap0 + 32 * arow;
+        const unsigned char* bb[NL];
+#pragma unroll
+        for (int b = 0; b < NL; ++b) bb[b] = sf + P.win_off + pixoff[b];
+        Ops ops[2];
+        ops[0].a0 = *reinterpret_cast<const floatx4*>(ap0);
+        ops[0].a1 = *reinterpret_cast<const floatx4*>(ap1);
+#pragma unroll
+        for (int b = 0; b < NL; ++b)
+#pragma unroll
+            for (int t = 0; t < 4; ++t) ops[0].b[b][t] = *reinterpret_cast<const float*>(bb[b] + treg[0][t]);
+#pragma unroll
+        for (int g = 0; g < NGT; ++g) {
+            const Ops& cur = ops[g & 1];
+            Ops& nxt = ops[(g + 1) & 1];
+            const unsigned char* addr[NL][4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int b = 0; b < NL; ++b)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const int m = (t * NL + b) * 2 + h;
+                        acc[b][h] = __builtin_amdgcn_mfma_f32_32x32x2f32(h ? cur.a1[t] : cur.a0[t], cur.b[b][t], acc[b][h], 0, 0, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (g + 1 < NGT) {
+                            if (m == 0) {
+#pragma unroll
+                                for (int bq = 0; bq < NL; ++bq)
+#pragma unroll
+                                    for (int tq = 0; tq < 4; ++tq) addr[bq][tq] = bb[bq] + treg[g + 1][tq];
+                                nxt.a0 = *reinterpret_cast<const floatx4*>(ap0 + 32 * (g + 1));
+                                nxt.a1 = *reinterpret_cast<const floatx4*>(ap1 + 32 * (g + 1));
+#pragma unroll
+                                for (int bq = 0; bq < NL; ++bq)
+#pragma unroll
+                                    for (int tq = 0; tq < 4; ++tq) nxt.b[bq][tq] = *reinterpret_cast<const float*>(addr[bq][tq]);
+                            }
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+        }
+    };
+
 #pragma unroll 1
     for (int c = 0; c < P.chunks; ++c) {
         __syncthreads();                                // barrier c
-        if (nlive > 0) multiply(std::integral_constant<int, NBW>{}, c & 1);     // (a block past the tile multiplies cell 0)
+        if (nlive > 0) {                                // (a block past the tile multiplies cell 0)
+            if constexpr (NGT > 0) multiply_unrolled(c & 1);
+            else multiply(std::integral_constant<int, NBW>{}, c & 1);
+        }
     }
 
     // ---- store: register v of a lane is output channel 8 (v / 4) + 4 kk + v % 4 of the 32-channel half, pixel lj
@@ -324,13 +392,13 @@ DmaPlan plan_dma(const Conv2dShape& s, const void* x, const void* w)
     return best;
 }
 
-template <int NBW>
+template <int NBW, int NGT>
 hipError_t launch_dma(const float* x, const float* w, float* y, const DmaPlan& a, hipStream_t st)
 {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_f32_dma_kernel<NBW>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_f32_dma_kernel<NBW, NGT>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
     if (attr != hipSuccess) return attr;
-    SW_NOTED_LAUNCH(note_kernel("mfma_f32_dma_kernel", NBW, a.P.CK, a.P.NI, a.P.TH), (mfma_f32_dma_kernel<NBW>), dim3(a.gx, a.gy), dim3(512), a.lds, st,
+    SW_NOTED_LAUNCH(note_kernel("mfma_f32_dma_kernel", NBW, a.P.CK, a.P.NI, a.P.TH), (mfma_f32_dma_kernel<NBW, NGT>), dim3(a.gx, a.gy), dim3(512), a.lds, st,
                     x, w, y, a.P);
     return hipGetLastError();
 }
@@ -344,8 +412,9 @@ hipError_t launch_mfma_f32_dma(const float* x, const float* w, float* y, const C
     DmaPlan a = plan_dma(s, x, w);
     if (!a.ok) return hipErrorInvalidValue;
     a.P.ep = ep;
-    if (a.NBW == 2) return launch_dma<2>(x, w, y, a, st);
-    return launch_dma<1>(x, w, y, a, st);
+    if (a.NBW == 2) return launch_dma<2, 0>(x, w, y, a, st);
+    if (a.P.NG == 9) return launch_dma<1, 9>(x, w, y, a, st);       // nine taps over chunks of eight channels
+    return launch_dma<1, 0>(x, w, y, a, st);
 }
 
 }  // namespace swconv

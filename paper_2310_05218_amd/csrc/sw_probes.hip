@@ -1,6 +1,7 @@
 // Measurement aids: kernels that issue one kind of arithmetic instruction and nothing else, so that a benchmark
 // can quote the rate this chip sustains (at the clock it holds under that instruction) beside the datasheet
-// peak.  They read and write no memory (the sink is only there to keep the arithmetic alive).
+// peak.  They read and write no memory (the sink is only there to keep the arithmetic alive); the "fed" probe reads
+// its operands from LDS, as every convolution kernel must.
 #include "../../include/swconv.h"
 
 #include "swconv_internal.h"
@@ -103,6 +104,38 @@ __global__ __launch_bounds__(64) void probe_fma_mfma_f32_kernel(int iters, float
     if (sink && s == 12345.678f) *sink = s;
 }
 
+// fp32 matrix instructions whose A operand comes from LDS, one 4-byte read behind each instruction, consumed four
+// instructions later (its latency hidden): what a matrix-instruction stream sustains when it is fed at the lowest
+// rate a 64-channel x 32-pixel tile allows (half an operand dword per instruction from each side).  WAVES
+// wavefronts per SIMD: one (a workgroup alone on its CU) or two.
+template <int WAVES>
+__global__ __launch_bounds__(256 * WAVES) void probe_mfma_f32_fed_kernel(int iters, float* sink)
+{
+    __shared__ float lds[4096];
+    for (int i = threadIdx.x; i < 4096; i += 256 * WAVES) lds[i] = 1.0f + i * 1e-6f;
+    __syncthreads();
+    floatx16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    const float b = 0.5f;
+    const int at = threadIdx.x & 1023;
+    float ring[4];
+    for (int r = 0; r < 4; ++r) ring[r] = lds[at + 64 * r];
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < kMfmaPerIter; ++u) {
+            acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x2f32(ring[u & 3], b, acc[u & 3], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            ring[u & 3] = lds[at + 256 * u + (it & 1023)];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    float s = 0.f;
+    for (int i = 0; i < 4; ++i) s += acc[i][0] + acc[i][15];
+    if (sink && s == 12345.678f) *sink = s;
+}
+
 }  // namespace
 
 }  // namespace swconv
@@ -120,6 +153,8 @@ int64_t sw_probe_ops(int kind, int iters)
         case SW_PROBE_MFMA_I8: return waves * iters * kMfmaPerIter * (2LL * 32 * 32 * 32);
         case SW_PROBE_FMA_F32: return waves * iters * kFmaPerIter * (2LL * 64);
         case SW_PROBE_FMA_MFMA_F32: return waves * iters * kMixRounds * (kMixFma * 2LL * 64 + 2LL * 16 * 16 * 4);
+        case SW_PROBE_MFMA_F32_FED: return 256LL * 4 * iters * kMfmaPerIter * (2LL * 32 * 32 * 2);
+        case SW_PROBE_MFMA_F32_FED2: return 256LL * 8 * iters * kMfmaPerIter * (2LL * 32 * 32 * 2);
         default: return 0;
     }
 }
@@ -143,6 +178,12 @@ int sw_probe(int kind, int iters, void* hip_stream)
         case SW_PROBE_FMA_MFMA_F32:
             SW_NOTED_LAUNCH(note_kernel("probe_fma_mfma_f32_kernel"), probe_fma_mfma_f32_kernel, dim3(kProbeGroups), dim3(64), 0, st, iters,
                             none, 1.0000001f);
+            break;
+        case SW_PROBE_MFMA_F32_FED:
+            SW_NOTED_LAUNCH(note_kernel("probe_mfma_f32_fed_kernel", 1), probe_mfma_f32_fed_kernel<1>, dim3(256), dim3(256), 0, st, iters, none);
+            break;
+        case SW_PROBE_MFMA_F32_FED2:
+            SW_NOTED_LAUNCH(note_kernel("probe_mfma_f32_fed_kernel", 2), probe_mfma_f32_fed_kernel<2>, dim3(256), dim3(512), 0, st, iters, none);
             break;
         default: return SW_ERR_UNSUPPORTED;
     }

@@ -66,10 +66,17 @@ struct DmaParams {
 // memory pipeline has taken them, and in a wavefront of its own that wait holds no matrix instruction back.
 // NGT: the number of groups per chunk as a compile-time constant (0: run-time): the loop over groups is unrolled, the
 // per-K offsets stay in registers (no table reads) and all address arithmetic of a group sits in one slot.
-template <int NBW, int NGT>
-__global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __restrict__ x, const float* __restrict__ w,
-                                                                            float* __restrict__ y, const DmaParams P)
+// BW x KS multiplying wavefronts: BW take the tile's blocks in turn (block BW b + wb), and KS wavefronts share each
+// block, every KS-th group of K values each; their partial sums meet in LDS at the end.  KS > 1 is for launches of
+// at most one workgroup per CU: two wavefronts per SIMD hide part of what the operand reads cost, and a tile of few
+// blocks still occupies every SIMD.
+template <int NBW, int NGT, int BW, int KS>
+__global__ __launch_bounds__(64 * (BW * KS + 4), KS == 1 ? 4 : 3) void mfma_f32_dma_kernel(const float* __restrict__ x,
+                                                                                          const float* __restrict__ w,
+                                                                                          float* __restrict__ y, const DmaParams P)
 {
+    constexpr int MW = BW * KS;                 // multiplying wavefronts
+    static_assert(NGT == 0 || KS == 1, "the unrolled group loop takes every group");
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -77,9 +84,9 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
     const int n0 = ig * P.NI, row0 = ty * P.TH;
     const int co0 = blockIdx.y * 64;
 
-    if (wave >= 4) {
+    if (wave >= MW) {
         // ---------------------------------------------------------------------------------------- the loaders
-        const int lw = wave - 4;
+        const int lw = wave - MW;
         const int HW = P.H * P.W;
         const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(x), 0, P.x_bytes, 0x00020000);
         const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(w), 0, P.w_bytes, 0x00020000);
@@ -130,6 +137,10 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
             if (c + 1 < P.chunks) issue(c + 1, (c + 1) & 1);
         }
         __builtin_amdgcn_s_waitcnt(0);
+        if constexpr (KS > 1) {                         // (the two barriers around the partial sums)
+            __syncthreads();
+            __syncthreads();
+        }
         return;
     }
 
@@ -138,28 +149,27 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
     // byte offset of K value e = (channel, tap) from a pixel's cell
     {
         int* tbl = reinterpret_cast<int*>(smem + P.tbl_off);
-        for (int e = tid; e < P.CK * P.RS; e += 256) {
+        for (int e = tid; e < P.CK * P.RS; e += 64 * MW) {
             const int ci = fast_div(e, P.by_RS), tap = e - ci * P.RS;
             const int r = fast_div(tap, P.by_S), s = tap - r * P.S;
             tbl[e] = 4 * (ci * P.WCp + (r * P.IW + s) * P.dil);
         }
     }
-    // this wavefront's pixel blocks: block 4b + wave of the tile
+    // this wavefront's pixel blocks: block BW b + wb of the tile
     const int HoWo = P.Ho * P.Wo;
     const int thwo = P.TH * P.Wo;
     const int valid_px = P.NI > 1 ? min(P.NI, P.N - n0) * HoWo : min(P.TH, P.Ho - row0) * P.Wo;
+    // block column; part of K (the parts of a block on neighbouring wavefronts, i.e. on different SIMDs)
+    const int wb = KS == 1 ? wave : wave / KS, kp = KS == 1 ? 0 : wave % KS;
     int nlive = 0;
     int pixoff[NBW];
-    int64_t yoff[NBW];
 #pragma unroll
     for (int b = 0; b < NBW; ++b) {
-        const int p = 32 * (4 * b + wave) + lj;
-        if (32 * (4 * b + wave) < valid_px) nlive = b + 1;
+        const int p = 32 * (BW * b + wb) + lj;
+        if (32 * (BW * b + wb) < valid_px) nlive = b + 1;
         const int i = fast_div(p, P.by_thwo), rem = p - i * thwo;
         const int ol = fast_div(rem, P.by_Wo), ow = rem - ol * P.Wo;
-        const bool ok = p < valid_px;
-        pixoff[b] = ok ? 4 * (i * P.cells_img + (ol * P.IW + ow) * P.stride) : 0;
-        yoff[b] = ok ? ((int64_t)(n0 + i) * P.C_out + co0) * HoWo + (row0 + ol) * P.Wo + ow : -1;
+        pixoff[b] = p < valid_px ? 4 * (i * P.cells_img + (ol * P.IW + ow) * P.stride) : 0;
     }
 
     floatx16 acc[NBW][2];
@@ -174,8 +184,9 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
     const int arow = 16 * P.PCp;                                                // bytes per output channel's filter row
     const unsigned char* tp = smem + P.tbl_off + 16 * kk;                       // + 32 g
     __syncthreads();                                                            // (the table; the loaders pass it too)
-    const intx4 tfirst = *reinterpret_cast<const intx4*>(tp);
-    const intx4 tsecond = *reinterpret_cast<const intx4*>(tp + (P.NG > 1 ? 32 : 0));
+    const int glast = kp + ((P.NG - 1 - kp) / KS) * KS;                         // this wavefront's last group (NG > kp)
+    const intx4 tfirst = *reinterpret_cast<const intx4*>(tp + 32 * min(kp, glast));
+    const intx4 tsecond = *reinterpret_cast<const intx4*>(tp + 32 * min(kp + KS, glast));
     auto multiply = [&](auto nl_tag, int stage) __attribute__((always_inline)) {
         constexpr int NL = decltype(nl_tag)::value;
         struct Ops {
@@ -186,9 +197,8 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
         const unsigned char* ap0 = sf + lj * arow + 16 * kk;                    // + 32 g
         const unsigned char* ap1 = ap0 + 32 * arow;                             // the upper 32 channels
         const unsigned char* bp = sf + P.win_off;
-        const int glast = P.NG - 1;
         auto group = [&](const Ops& cur, Ops& nxt, const intx4& tn, intx4& tl, int g) __attribute__((always_inline)) {
-            const int gn = min(g + 1, glast), g2 = min(g + 2, glast);
+            const int gn = min(g + KS, glast), g2 = min(g + 2 * KS, glast);
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
@@ -213,17 +223,17 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
                     }
         };
         Ops X, Y;
-        X.a0 = *reinterpret_cast<const floatx4*>(ap0);
-        X.a1 = *reinterpret_cast<const floatx4*>(ap1);
+        X.a0 = *reinterpret_cast<const floatx4*>(ap0 + 32 * kp);
+        X.a1 = *reinterpret_cast<const floatx4*>(ap1 + 32 * kp);
 #pragma unroll
         for (int b = 0; b < NL; ++b)
 #pragma unroll
             for (int t = 0; t < 4; ++t) X.b[b][t] = *reinterpret_cast<const float*>(bp + pixoff[b] + tfirst[t]);
         intx4 ta = tsecond, tb = tsecond;
 #pragma unroll 1
-        for (int g = 0; g < P.NG; g += 2) {
+        for (int g = kp; g < P.NG; g += 2 * KS) {
             group(X, Y, ta, tb, g);
-            if (g + 1 < P.NG) group(Y, X, tb, ta, g + 1);
+            if (g + KS < P.NG) group(Y, X, tb, ta, g + KS);
         }
     };
 
@@ -291,17 +301,46 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
 #pragma unroll 1
     for (int c = 0; c < P.chunks; ++c) {
         __syncthreads();                                // barrier c
-        if (nlive > 0) {                                // (a block past the tile multiplies cell 0)
+        if (nlive > 0 && kp < P.NG) {                   // (a block past the tile multiplies cell 0)
             if constexpr (NGT > 0) multiply_unrolled(c & 1);
             else multiply(std::integral_constant<int, NBW>{}, c & 1);
         }
     }
 
+    // ---- the parts of K meet in LDS (the stages are free: everybody has passed the last chunk)
+    if constexpr (KS > 1) {
+        __syncthreads();
+        float* part = reinterpret_cast<float*>(smem);           // [K part - 1][block column][block][half][register][lane]
+        if (kp > 0) {
+#pragma unroll
+            for (int b = 0; b < NBW; ++b)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        part[(((((kp - 1) * BW + wb) * NBW + b) * 2 + h) * 16 + v) * 64 + lane] = acc[b][h][v];
+        }
+        __syncthreads();
+        if (kp > 0) return;
+#pragma unroll
+        for (int q = 0; q < KS - 1; ++q)
+#pragma unroll
+            for (int b = 0; b < NBW; ++b)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[b][h][v] += part[((((q * BW + wb) * NBW + b) * 2 + h) * 16 + v) * 64 + lane];
+    }
+
     // ---- store: register v of a lane is output channel 8 (v / 4) + 4 kk + v % 4 of the 32-channel half, pixel lj
 #pragma unroll
     for (int b = 0; b < NBW; ++b) {
-        if (b >= nlive || yoff[b] < 0) continue;
-        float* yp = y + yoff[b];
+        const int p = 32 * (BW * b + wb) + lj;
+        if (b >= nlive || p >= valid_px) continue;
+        const int i = fast_div(p, P.by_thwo), rem = p - i * thwo;
+        const int ol = fast_div(rem, P.by_Wo), ow = rem - ol * P.Wo;
+        float* yp = y + ((int64_t)(n0 + i) * P.C_out + co0) * HoWo + (row0 + ol) * P.Wo + ow;
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -314,11 +353,11 @@ __global__ __launch_bounds__(512, 4) void mfma_f32_dma_kernel(const float* __res
 
 struct DmaPlan {
     bool ok = false;
-    int NBW = 0;
+    int NBW = 0, BW = 4, KS = 1;
     size_t lds = 0;
     unsigned gx = 0, gy = 0;
     double est = 0;
-    int64_t wgs = 0;
+    int64_t wgs = 0, work = 0;
     DmaParams P;
 };
 
@@ -336,10 +375,12 @@ DmaPlan plan_dma(const Conv2dShape& s, const void* x, const void* w)
     const int64_t IW = (int64_t)(s.Wo - 1) * s.stride + (int64_t)(s.S - 1) * s.dil + 1;
     const int HoWo = s.Ho * s.Wo;
     // a tile of NI whole images (tiles_y == 1) or of one of tiles_y equal runs of rows of one image (NI == 1)
-    auto consider = [&](int NBW, int NI, int tiles_y, int CK, size_t budget, bool replace) {
+    // BW block columns x KS parts of K (multiplying wavefronts), NBW blocks per wavefront
+    auto consider = [&](int NBW, int BW, int KS, int NI, int tiles_y) {
+        const int CK = CK0;
         const int PC = CK * RS / 4, PCp = PC | 1;
-        if (PCp > 4 * kMaxFI || s.C_in % CK != 0) return;
-        const int tp_max = 128 * NBW;
+        if (PCp > 4 * kMaxFI || s.C_in % CK != 0 || CK * RS / 8 < KS) return;
+        const int tp_max = 32 * BW * NBW;
         const int TH = (s.Ho + tiles_y - 1) / tiles_y;
         if ((int64_t)TH * s.Wo * NI > tp_max || (s.Ho + TH - 1) / TH != tiles_y) return;
         const int64_t IH = (int64_t)(TH - 1) * s.stride + (int64_t)(s.R - 1) * s.dil + 1;
@@ -347,18 +388,39 @@ DmaPlan plan_dma(const Conv2dShape& s, const void* x, const void* w)
         if (WC > 64 * kMaxNS) return;
         const int NS = (int)((WC + 63) / 64);
         const size_t stage = (size_t)PCp * 1024 + (size_t)CK * NS * 256;
-        const size_t lds = 2 * stage + (size_t)CK * RS * 4;
-        if (lds > budget) return;
+        const size_t lds = std::max(2 * stage + (size_t)CK * RS * 4, (size_t)(KS - 1) * BW * NBW * 8192);
+        if (lds > kLdsBudget) return;
         const int blocks = (NI * TH * s.Wo + 31) / 32;
-        const int c_wg = (blocks + 3) / 4;
         const int64_t groups = (s.N + NI - 1) / NI;
         const int64_t wgs = groups * tiles_y * co_blocks;
         if (groups * tiles_y > 2147483647LL) return;
-        // a workgroup takes c_wg block periods; the matrix pipes of a CU serve one workgroup period per period
-        const double est = std::max((double)c_wg, (double)wgs * c_wg / 256.0);
-        if (best.ok && !replace && (est > best.est || (est == best.est && wgs >= best.wgs))) return;
+        if (KS > 1 && wgs > 256) return;                // (a K split holds its CU alone)
+        // Periods (one block through all of K on one wavefront): those on a workgroup's critical path, and those of the
+        // whole launch over the chip's 1024 SIMDs -- without a K split a workgroup holds BW SIMDs for its rounds whether
+        // all of its wavefronts have a block or not, with one every wavefront works on every block.
+        const int rounds = (blocks + BW - 1) / BW;
+        const double est = KS == 1 ? std::max((double)rounds, (double)wgs * rounds * BW / 1024.0)
+                                   : std::max((double)rounds / KS, (double)wgs * blocks / 1024.0);
+        // equal estimates: the fewer block periods in all (blocks with dead lanes are wasted work), then as many CUs as
+        // possible (every CU brings its own LDS and load path), then the fewer workgroups (filters are fetched per
+        // workgroup), then the smaller split
+        const int64_t work = wgs * blocks;
+        if (best.ok) {
+            const int64_t cus = std::min<int64_t>(wgs, 256), best_cus = std::min<int64_t>(best.wgs, 256);
+            if (est > best.est) return;
+            if (est == best.est) {
+                if (work > best.work) return;
+                if (work == best.work) {
+                    if (cus < best_cus) return;
+                    if (cus == best_cus && (wgs > best.wgs || (wgs == best.wgs && KS >= best.KS))) return;
+                }
+            }
+        }
+        best.work = work;
         best.ok = true;
         best.NBW = NBW;
+        best.BW = BW;
+        best.KS = KS;
         best.lds = lds;
         best.est = est;
         best.wgs = wgs;
@@ -385,21 +447,22 @@ DmaPlan plan_dma(const Conv2dShape& s, const void* x, const void* w)
         P.by_PCp = make_fastdiv(PCp);
     };
     if (IW > 64 * kMaxNS) return best;
-    for (int NBW = 1; NBW <= 2; ++NBW) {
-        for (int NI = 2; NI <= s.N && (int64_t)NI * HoWo <= 128 * NBW; ++NI) consider(NBW, NI, 1, CK0, kLdsBudget, false);
-        for (int tiles_y = 1; tiles_y <= s.Ho; ++tiles_y) consider(NBW, 1, tiles_y, CK0, kLdsBudget, false);
+    static const int kVariants[][3] = {{1, 4, 1}, {2, 4, 1}, {1, 4, 2}, {1, 2, 4}};      // NBW, BW, KS
+    for (const auto& v : kVariants) {
+        for (int NI = 2; NI <= s.N && (int64_t)NI * HoWo <= 32 * v[1] * v[0]; ++NI) consider(v[0], v[1], v[2], NI, 1);
+        for (int tiles_y = 1; tiles_y <= s.Ho; ++tiles_y) consider(v[0], v[1], v[2], 1, tiles_y);
     }
     return best;
 }
 
-template <int NBW, int NGT>
+template <int NBW, int NGT, int BW, int KS>
 hipError_t launch_dma(const float* x, const float* w, float* y, const DmaPlan& a, hipStream_t st)
 {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_f32_dma_kernel<NBW, NGT>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_f32_dma_kernel<NBW, NGT, BW, KS>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBudget);
     if (attr != hipSuccess) return attr;
-    SW_NOTED_LAUNCH(note_kernel("mfma_f32_dma_kernel", NBW, a.P.CK, a.P.NI, a.P.TH), (mfma_f32_dma_kernel<NBW, NGT>), dim3(a.gx, a.gy), dim3(512), a.lds, st,
-                    x, w, y, a.P);
+    SW_NOTED_LAUNCH(note_kernel("mfma_f32_dma_kernel", 100 * KS + 10 * BW + NBW, a.P.CK, a.P.NI, a.P.TH),
+                    (mfma_f32_dma_kernel<NBW, NGT, BW, KS>), dim3(a.gx, a.gy), dim3(64 * (BW * KS + 4)), a.lds, st, x, w, y, a.P);
     return hipGetLastError();
 }
 
@@ -412,9 +475,11 @@ hipError_t launch_mfma_f32_dma(const float* x, const float* w, float* y, const C
     DmaPlan a = plan_dma(s, x, w);
     if (!a.ok) return hipErrorInvalidValue;
     a.P.ep = ep;
-    if (a.NBW == 2) return launch_dma<2, 0>(x, w, y, a, st);
-    if (a.P.NG == 9) return launch_dma<1, 9>(x, w, y, a, st);       // nine taps over chunks of eight channels
-    return launch_dma<1, 0>(x, w, y, a, st);
+    if (a.KS == 4) return launch_dma<1, 0, 2, 4>(x, w, y, a, st);
+    if (a.KS == 2) return launch_dma<1, 0, 4, 2>(x, w, y, a, st);
+    if (a.NBW == 2) return launch_dma<2, 0, 4, 1>(x, w, y, a, st);
+    if (a.P.NG == 9) return launch_dma<1, 9, 4, 1>(x, w, y, a, st);       // nine taps over chunks of eight channels
+    return launch_dma<1, 0, 4, 1>(x, w, y, a, st);
 }
 
 }  // namespace swconv

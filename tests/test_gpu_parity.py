@@ -485,23 +485,30 @@ def test_dilation_one_is_the_undilated_call(torch, sw):
 
 
 DMA_KERNEL_CASES = [
-    # N, C_in, C_out, H, W, R, S, stride, pad, dilation, kernel<blocks per wavefront, channels per chunk, images and rows per tile>
-    (1, 8, 64, 12, 12, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,1,6>"),       # one chunk, two row tiles of 72 pixels
-    (2, 16, 40, 14, 14, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,1,7>"),      # two chunks, channel block with 24 dead channels
-    (3, 32, 70, 7, 7, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,2,7>"),        # two whole images per tile, the last tile with one
-    (7, 16, 64, 5, 6, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,4,5>"),        # four images per tile (120 pixels), 7 = 4 + 3
-    (2, 16, 64, 30, 41, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<1,8,1,3>"),      # blocks that span rows, ragged last block
-    (1, 24, 96, 57, 57, 3, 3, 2, 1, 1, "mfma_f32_dma_kernel<1,8,1,4>"),      # stride 2, three chunks, ragged channel block
-    (1, 8, 64, 28, 28, 3, 3, 1, 2, 2, "mfma_f32_dma_kernel<1,8,1,4>"),       # dilation 2
-    (1, 16, 64, 40, 40, 3, 3, 2, 3, 3, "mfma_f32_dma_kernel<1,8,1,4>"),      # dilation 3 with stride 2
-    (2, 64, 64, 19, 23, 1, 1, 2, 0, 1, "mfma_f32_dma_kernel<1,32,1,4>"),     # one tap at stride 2: chunks of 32 channels
-    (1, 16, 32, 20, 20, 4, 4, 1, 2, 1, "mfma_f32_dma_kernel<1,8,1,5>"),      # 16 taps, even extents
-    (1, 8, 16, 9, 200, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<2,8,1,1>"),       # rows of 200 pixels: two blocks per wavefront, four window slots
-    (5, 8, 64, 5, 5, 2, 2, 1, 0, 1, "mfma_f32_dma_kernel<1,8,5,4>"),         # 2x2, five whole images per tile
-    (2, 40, 64, 16, 16, 3, 1, 1, 1, 1, "mfma_f32_dma_kernel<1,8,1,6>"),      # a column filter; five chunks
-    (5, 8, 256, 56, 56, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<2,8,1,4>"),      # 224-pixel tiles: two blocks per wavefront, the last wavefront one
-    (1, 32, 64, 18, 18, 2, 2, 1, 0, 1, "mfma_f32_dma_kernel<1,16,1,6>"),     # 2x2: chunks of 16 channels
-    (1, 8, 64, 3, 3, 3, 3, 1, 0, 1, "mfma_f32_dma_kernel<1,8,1,1>"),         # a single output pixel
+    # N, C_in, C_out, H, W, R, S, stride, pad, dilation,
+    # kernel<100 K parts + 10 block columns + blocks per wavefront, channels per chunk, images and rows per tile>
+    (1, 8, 64, 12, 12, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<421,8,1,2>"),       # one chunk, row pairs of 24 pixels
+    (2, 16, 40, 14, 14, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<421,8,1,2>"),      # two chunks, channel block with 24 dead channels
+    (3, 32, 70, 7, 7, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<421,8,1,4>"),        # tiles of four and three rows of a 7 x 7 image, ragged channel block
+    (7, 16, 64, 5, 6, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<421,8,1,5>"),        # one whole 5 x 6 image per tile
+    (2, 16, 64, 30, 41, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<421,8,1,1>"),      # one row of 41 pixels per tile: two blocks, the second ragged
+    (1, 24, 96, 57, 57, 3, 3, 2, 1, 1, "mfma_f32_dma_kernel<421,8,1,1>"),      # stride 2, three chunks, ragged channel block
+    (1, 8, 64, 28, 28, 3, 3, 1, 2, 2, "mfma_f32_dma_kernel<421,8,1,1>"),       # dilation 2
+    (1, 16, 64, 40, 40, 3, 3, 2, 3, 3, "mfma_f32_dma_kernel<421,8,1,3>"),      # dilation 3 with stride 2
+    (2, 64, 64, 19, 23, 1, 1, 2, 0, 1, "mfma_f32_dma_kernel<421,32,1,2>"),     # one tap at stride 2: chunks of 32 channels
+    (1, 16, 32, 20, 20, 4, 4, 1, 2, 1, "mfma_f32_dma_kernel<421,8,1,3>"),      # 16 taps, even extents
+    (1, 8, 16, 9, 200, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<142,8,1,1>"),       # rows of 200 pixels: two blocks per wavefront, four window slots
+    (5, 8, 64, 5, 5, 2, 2, 1, 0, 1, "mfma_f32_dma_kernel<421,8,2,4>"),         # 2x2, two whole images per tile, the last tile with one
+    (2, 40, 64, 16, 16, 3, 1, 1, 1, 1, "mfma_f32_dma_kernel<241,8,1,3>"),      # a column filter (three groups per chunk: at most two wavefronts per block); five chunks
+    (5, 8, 256, 56, 56, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<142,8,1,4>"),      # 224-pixel tiles: two blocks per wavefront, the last wavefront one
+    (1, 32, 64, 18, 18, 2, 2, 1, 0, 1, "mfma_f32_dma_kernel<421,16,1,3>"),     # 2x2: chunks of 16 channels
+    (1, 8, 64, 3, 3, 3, 3, 1, 0, 1, "mfma_f32_dma_kernel<421,8,1,1>"),         # a single output pixel
+    (40, 8, 64, 28, 28, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<141,8,1,4>"),     # more workgroups than CUs: no K split, unrolled group loop
+    (40, 16, 64, 28, 28, 2, 2, 1, 0, 1, "mfma_f32_dma_kernel<141,16,1,4>"),   # ... and the run-time group loop
+    (2, 8, 64, 7, 7, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<421,8,1,4>"),        # two blocks per tile: four wavefronts per block
+    (9, 8, 64, 4, 4, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<421,8,2,4>"),       # whole 4 x 4 images, several per tile, the last tile short
+    (6, 8, 64, 7, 9, 3, 1, 1, 0, 1, "mfma_f32_dma_kernel<241,8,2,5>"),       # three groups per chunk: two wavefronts per block; two whole images per tile
+    (600, 8, 64, 7, 7, 3, 3, 1, 1, 1, "mfma_f32_dma_kernel<141,8,2,7>"),     # two images per tile without a K split (300 workgroups)
 ]
 
 

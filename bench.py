@@ -127,6 +127,7 @@ def measured_peaks(torch, sw):
                              ("fma_plus_mfma_f32_tflops", sw.SW_PROBE_FMA_MFMA_F32, 2000),
                              # fp32 matrix instructions fed from LDS (one 4-byte operand read behind each), one and two
                              # wavefronts per SIMD: what a stream of them sustains once it has operands to fetch
+                             ("mfma_bf16_tflops", sw.SW_PROBE_MFMA_BF16, 8000),
                              ("mfma_f32_fed_tflops", sw.SW_PROBE_MFMA_F32_FED, 4000),
                              ("mfma_f32_fed_two_wavefronts_tflops", sw.SW_PROBE_MFMA_F32_FED2, 4000)):
         ops = sw.sw_probe(kind, iters)

@@ -361,9 +361,12 @@ int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* b
  * Pixels of a multiple of 32 bytes (C_in % 8 == 0 in fp32, % 16 in bf16 / half) and 16-byte
  * aligned x and w run on the matrix cores, the channels in chunks of up to 128 bytes
  * per pixel (any extent, stride, dilation and C_out); every other valid shape one
- * thread per output.  bf16 / half with C_out % 4 == 0, 8-byte aligned y, R, S <= 32, x below
- * 2 GiB and the filters of 32 output channels within 150 KB reads its pixel operands
- * straight from x (no window in LDS), which is the faster of the two 16-bit kernels.
+ * thread per output.  bf16 / half with C_out % 4 == 0, 8-byte aligned y and tensors below
+ * 2 GiB run on one of two faster kernels: filters of 32 output channels within 76 KB and
+ * tiles whose windows fit LDS beside them (3 x 3 up to 128 channels, 1 x 1 up to 1200):
+ * filters resident in LDS, windows brought in by direct-to-LDS loads a tile ahead;
+ * otherwise, with R, S <= 32 and the filters of 32 output channels within 150 KB, the
+ * pixel operands are read straight from x (no window in LDS).
  */
 int sw_conv2d_nhwc(const float* x, const float* w, const float* bias, float* y,
                    int N, int H, int W, int C_in, int C_out, int R, int S,
@@ -404,7 +407,8 @@ typedef enum {
     SW_PROBE_FMA_F32 = 2,   /* v_fma_f32, wave-uniform multiplicand (no packed forms)  */
     SW_PROBE_FMA_MFMA_F32 = 3, /* nine v_fma_f32, one v_mfma_f32_16x16x4_f32, ... in one stream: do the two pipes overlap? */
     SW_PROBE_MFMA_F32_FED = 4, /* v_mfma_f32_32x32x2_f32 with one 4-byte LDS operand read behind each, one wavefront per SIMD */
-    SW_PROBE_MFMA_F32_FED2 = 5 /* the same with two wavefronts per SIMD */
+    SW_PROBE_MFMA_F32_FED2 = 5, /* the same with two wavefronts per SIMD */
+    SW_PROBE_MFMA_BF16 = 6     /* v_mfma_f32_32x32x16_bf16 */
 } sw_probe_kind;
 int sw_probe(int kind, int iters, void* hip_stream);
 int64_t sw_probe_ops(int kind, int iters);

@@ -9,4 +9,4 @@ from .binding import (SW_POOL_AVG, SW_POOL_MAX, SwError, sw_conv1d, sw_conv2d, s
                       sw_jit_cached_kernels, sw_jit_compile_check, sw_jit_prepare_depthwise, sw_out_dim,
                       sw_pool1d, sw_pool2d, sw_version, sw_workspace_bytes, sw_out_dim_dilated, sw_last_kernel,
                       sw_s8_packed_filter_bytes, sw_s8_pack_filter, sw_conv2d_s8_packed, sw_probe,
-                      SW_PROBE_MFMA_F32, SW_PROBE_MFMA_I8, SW_PROBE_FMA_F32, SW_PROBE_FMA_MFMA_F32, SW_PROBE_MFMA_F32_FED, SW_PROBE_MFMA_F32_FED2)
+                      SW_PROBE_MFMA_F32, SW_PROBE_MFMA_I8, SW_PROBE_FMA_F32, SW_PROBE_FMA_MFMA_F32, SW_PROBE_MFMA_F32_FED, SW_PROBE_MFMA_F32_FED2, SW_PROBE_MFMA_BF16)

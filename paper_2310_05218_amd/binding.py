@@ -228,7 +228,7 @@ def sw_last_kernel() -> str:
     return lib().sw_last_kernel().decode()
 
 
-SW_PROBE_MFMA_F32, SW_PROBE_MFMA_I8, SW_PROBE_FMA_F32, SW_PROBE_FMA_MFMA_F32, SW_PROBE_MFMA_F32_FED, SW_PROBE_MFMA_F32_FED2 = 0, 1, 2, 3, 4, 5
+SW_PROBE_MFMA_F32, SW_PROBE_MFMA_I8, SW_PROBE_FMA_F32, SW_PROBE_FMA_MFMA_F32, SW_PROBE_MFMA_F32_FED, SW_PROBE_MFMA_F32_FED2, SW_PROBE_MFMA_BF16 = 0, 1, 2, 3, 4, 5, 6
 
 
 def sw_probe(kind: int, iters: int, stream=None) -> int:

@@ -1,0 +1,426 @@
+// 16-bit (bf16 or IEEE half) multi-channel convolution on channel-last tensors with both operands in LDS, the window
+// brought in by direct-to-LDS loads (paper, section 3: every tap a small matrix product whose shift is an address;
+// section 1.1: reduced precision on the same sliding sums).
+//
+//   x [N, H, W, C]     w [C_out, R, S, C]     y [N, H_out, W_out, C_out]     16-bit patterns, fp32 sums
+//
+// The kernel that reads its pixel operands straight from global memory (sw_mfma_bf16_nhwc.hip) is bound by cache-line
+// look-ups: a load instruction takes 32 bytes out of each of 32 lines.  Here a load instruction takes whole lines: the
+// rectangle of input pixels a tile touches (its window, padding included as out-of-range addresses that arrive as zeros)
+// goes to LDS in 16-byte pieces, 64 consecutive pieces per instruction, and the pixel operand of
+// v_mfma_f32_32x32x16_{bf16,f16} for (pixel, tap, 16 channels) is one 16-byte LDS read per lane at
+// cell(pixel) + (r IW + s) dilation.  A cell's NP pieces (8 channels each) are stored at slot = piece ^ key, key = the
+// cell's 128-byte row of LDS modulo NP, which spreads the eight cells a read serves per cycle over all banks whatever NP is.
+//
+// Workgroup = 32 CB output channels, persistent: it fetches the filters of its channels once ([channel][tap][C] rows as
+// they lie in w, odd row pitch in pieces) and then walks over tiles of up to 128 PB output pixels (rows of one image, or
+// whole small images), the window of the next (tile, chunk of channels) in flight while this one multiplies: four
+// wavefronts only load, four multiply (pixel block 4b + w to wavefront w, all channel blocks).  Filters are the A operand,
+// pixels the B operand: a lane of the result holds, for its pixel, groups of four consecutive output channels (8-byte
+// stores).
+#include <algorithm>
+
+#include "swconv_internal.h"
+
+namespace swconv {
+
+namespace {
+
+typedef int intx4 __attribute__((ext_vector_type(4)));
+typedef int intx2 __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+
+#define SW_LDS_PTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+constexpr size_t kLdsTotal = 156 * 1024;
+constexpr size_t kFilterMax = 76 * 1024;       // resident filters of a workgroup
+constexpr int kMaxWK = 12;                     // window loads per loading wavefront and stage
+constexpr unsigned kBeyond = 0x80000000u;
+
+struct LdsParams {
+    Epilogue ep;
+    int N, H, W, C, C_out, R, S, stride, pad, dil, Ho, Wo;
+    int NI, TH, tiles_y, tiles;    // images and output rows per tile, row tiles per image, tiles in all
+    int IH, IW, cells_img, WC;     // window rows and columns of one image, their product, cells of a window
+    int NP, chunks;                // 16-byte pieces per pixel and chunk (2, 4 or 8), chunks of 8 NP channels
+    int wloads;                    // 64-piece loads per window stage
+    int frow, fpitch;              // 16-byte pieces of an output channel's filters (R S C / 8), row pitch in LDS (odd)
+    int win_off, stage_bytes;      // window stages behind the filters
+    int out_off;                   // per multiplying wavefront: 32 pixels x (64 CB + 16) bytes for the transposed store (< 0: none)
+    unsigned x_bytes, w_bytes;
+    FastDiv by_tiles_y, by_cells_img, by_IW, by_thwo, by_Wo, by_fpitch, by_S;
+};
+
+__device__ __forceinline__ unsigned round16_bits(float f, bool f16)
+{
+    if (f16) return (unsigned)__builtin_bit_cast(unsigned short, (_Float16)f);     // v_cvt_f16_f32: nearest even
+    return (unsigned)__builtin_bit_cast(unsigned short, (__bf16)f);                // v_cvt_pk_bf16_f32: nearest even
+}
+
+// F16: IEEE half (else bf16).  CB: blocks of 32 output channels per workgroup.  PB: blocks of 32 pixels per wavefront.
+// KSC: steps of 16 channels per tap and chunk (NP / 2).
+template <bool F16, int CB, int PB, int KSC>
+__global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned char* __restrict__ x, const unsigned char* __restrict__ w,
+                                                                  unsigned short* __restrict__ y, const LdsParams P)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int co0 = blockIdx.y * (32 * CB);
+    const int steps_per_wg = ((P.tiles - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x) * P.chunks;   // (tile, chunk) steps
+    const int m = P.NP - 1, lnp = __builtin_ctz(P.NP);
+
+    // the filters, once, by every wavefront: slot q of the filter area is piece q % fpitch of output channel q / fpitch
+    {
+        const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(w), 0, P.w_bytes, 0x00020000);
+        const int floads = (32 * CB * P.fpitch + 63) >> 6;
+#pragma unroll 1
+        for (int k = wave; k < floads; k += 8) {
+            const int q = 64 * k + lane;
+            const int co = fast_div(q, P.by_fpitch), j = q - co * P.fpitch;
+            const unsigned off = (co < 32 * CB && j < P.frow && co0 + co < P.C_out) ? (unsigned)(((co0 + co) * P.frow + j) * 16) : kBeyond;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, SW_LDS_PTR(smem + 1024 * k), 16, off, 0, 0, 0);
+        }
+    }
+    if (wave >= 4) {
+        // ---------------------------------------------------------------------------------------- the loaders
+        const int lw = wave - 4;
+        const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(x), 0, P.x_bytes, 0x00020000);
+        // this lane's slot in each window load of this wavefront (loads lw, lw + 4, ...): its cell's place in the window
+        // (image, row, column) and the byte offset of its piece from the tile's origin; what changes per tile is the
+        // origin and which rows and images exist
+        int wrow[kMaxWK], wimg[kMaxWK];
+        unsigned wofs[kMaxWK];
+#pragma unroll
+        for (int k = 0; k < kMaxWK; ++k) {
+            const int q = 64 * (lw + 4 * k) + lane;
+            const int cell = q >> lnp, slot = q & m;                // (NP is a power of two)
+            const int piece = slot ^ ((cell >> (3 - lnp)) & m);
+            const int i = fast_div(cell, P.by_cells_img), rem = cell - i * P.cells_img;
+            const int e = fast_div(rem, P.by_IW), f = rem - e * P.IW;
+            const int gc = f - P.pad;
+            const bool in = cell < P.WC && gc >= 0 && gc < P.W;
+            wimg[k] = i;
+            wrow[k] = in ? e : -(1 << 20);                          // (a row that never exists)
+            wofs[k] = (unsigned)(((i * P.H + e) * P.W + gc) * (2 * P.C) + 16 * piece);
+        }
+        auto issue = [&](int step, int stage) __attribute__((always_inline)) {
+            const int tl = step / P.chunks, ch = step - tl * P.chunks;              // (wave-uniform)
+            const int tile = (int)blockIdx.x + tl * (int)gridDim.x;
+            const int ig = fast_div(tile, P.by_tiles_y), ty = tile - ig * P.tiles_y;
+            const int n0 = ig * P.NI, gr0 = ty * P.TH * P.stride - P.pad;
+            const unsigned origin = (unsigned)((n0 * P.H + gr0) * P.W * (2 * P.C) + ch * (16 * P.NP));
+            unsigned char* sw = smem + P.win_off + stage * P.stage_bytes;
+#pragma unroll
+            for (int k = 0; k < kMaxWK; ++k) {
+                if (lw + 4 * k < P.wloads) {
+                    const int gr = gr0 + wrow[k];
+                    const bool in = gr >= 0 && gr < P.H && n0 + wimg[k] < P.N;
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, SW_LDS_PTR(sw + 1024 * (lw + 4 * k)), 16, in ? origin + wofs[k] : kBeyond, 0, 0, 0);
+                }
+            }
+        };
+        if (steps_per_wg > 0) issue(0, 0);
+#pragma unroll 1
+        for (int s = 0; s < steps_per_wg; ++s) {
+            __builtin_amdgcn_s_waitcnt(0);              // this wavefront's loads of step s (and the filters) have landed
+            __syncthreads();                            // barrier s: step s is complete, step s - 1 has been multiplied
+            if (s + 1 < steps_per_wg) issue(s + 1, (s + 1) & 1);
+        }
+        __builtin_amdgcn_s_waitcnt(0);
+        return;
+    }
+
+    // -------------------------------------------------------------------------------------------- the multipliers
+    const int lj = lane & 31, kq = lane >> 5;
+    const int thwo = P.TH * P.Wo, HoWo = P.Ho * P.Wo;
+    // this wavefront's pixel blocks: block 4b + wave of the tile; the pixel's cell in the window does not depend on the tile
+    int cell0[PB], pl[PB];
+#pragma unroll
+    for (int b = 0; b < PB; ++b) {
+        const int p = 32 * (4 * b + wave) + lj;
+        const int pc = p < P.NI * thwo ? p : 0;
+        const int i = fast_div(pc, P.by_thwo), rem = pc - i * thwo;
+        const int ol = fast_div(rem, P.by_Wo), ow = rem - ol * P.Wo;
+        cell0[b] = i * P.cells_img + (ol * P.IW + ow) * P.stride;
+        pl[b] = p;
+    }
+    const unsigned char* arow = smem + (lj * P.fpitch + kq) * 16;          // + 32 cb fpitch 16 + (tap C / 8 + chunk NP + 2 ks) 16
+    const int cpt = P.C >> 3;                                              // pieces per tap in a filter row
+
+    // the lane's 16 CB output channels' biases, read once (zeros without a bias); the rectifier as a lower bound
+    float bias[CB][16];
+#pragma unroll
+    for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int co = co0 + cb * 32 + 8 * (v >> 2) + 4 * kq + (v & 3);
+            bias[cb][v] = (P.ep.bias != nullptr && co < P.C_out) ? P.ep.bias[co] : 0.f;
+        }
+    const float floor_ = P.ep.relu ? 0.f : -__builtin_inff();
+    auto finish = [&](float t, int cb, int v) __attribute__((always_inline)) {
+        return round16_bits(fmaxf(t + bias[cb][v], floor_), F16);
+    };
+
+    floatx16 acc[CB][PB];
+#pragma unroll 1
+    for (int s = 0; s < steps_per_wg; ++s) {
+        const int tl = s / P.chunks, ch = s - tl * P.chunks;               // (wave-uniform)
+        if (ch == 0) {
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int b = 0; b < PB; ++b)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[cb][b][v] = 0.f;
+        }
+        if (s == 0) __builtin_amdgcn_s_waitcnt(0);                         // (this wavefront's share of the filters)
+        // barrier s, without the fence of __syncthreads: that would wait for the stores of the tile before to be
+        // acknowledged (about 2 us per tile); nothing here reads what they wrote
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        const unsigned char* sw = smem + P.win_off + (s & 1) * P.stage_bytes;
+        const unsigned char* ab = arow + (ch * P.NP) * 16;
+        // One tap at a time: the KSC steps of 16 channels of a tap are KSC CB PB matrix instructions on KSC (CB + PB)
+        // operand reads; the reads of tap t + 1 (into the other register set) sit between the matrix instructions of
+        // tap t.  Per tap the window address costs three vector instructions per block and two per read.
+        const int taps = P.R * P.S;
+        struct Ops {
+            intx4 a[KSC][CB], b[KSC][PB];
+        };
+        Ops ops[2];
+        int r = 0, sc = 0;
+        auto read_tap = [&](Ops& o, int tap) __attribute__((always_inline)) {
+            const int toff = (r * P.IW + sc) * P.dil;
+            if (++sc == P.S) { sc = 0; ++r; }
+            const unsigned char* at = ab + tap * cpt * 16;
+#pragma unroll
+            for (int ks = 0; ks < KSC; ++ks)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb) o.a[ks][cb] = *reinterpret_cast<const intx4*>(at + (32 * cb * P.fpitch + 2 * ks) * 16);
+#pragma unroll
+            for (int b = 0; b < PB; ++b) {
+                const int cell = cell0[b] + toff;
+                const unsigned char* cb_ = sw + ((cell << lnp) << 4);
+                const int sw_ = (cell >> (3 - lnp)) & m;
+#pragma unroll
+                for (int ks = 0; ks < KSC; ++ks) o.b[ks][b] = *reinterpret_cast<const intx4*>(cb_ + (((2 * ks + kq) ^ sw_) << 4));
+            }
+        };
+        auto multiply_tap = [&](const Ops& o) __attribute__((always_inline)) {
+#pragma unroll
+            for (int ks = 0; ks < KSC; ++ks)
+#pragma unroll
+                for (int b = 0; b < PB; ++b)
+#pragma unroll
+                    for (int cb = 0; cb < CB; ++cb) {
+                        if constexpr (F16)
+                            acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, o.a[ks][cb]),
+                                                                                __builtin_bit_cast(halfx8, o.b[ks][b]), acc[cb][b], 0, 0, 0);
+                        else
+                            acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.a[ks][cb]),
+                                                                                 __builtin_bit_cast(bf16x8, o.b[ks][b]), acc[cb][b], 0, 0, 0);
+                    }
+        };
+        read_tap(ops[0], 0);
+#pragma unroll 1
+        for (int tap = 0; tap < taps; tap += 2) {
+            if (tap + 1 < taps) read_tap(ops[1], tap + 1);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply_tap(ops[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (tap + 1 < taps) {
+                if (tap + 2 < taps) read_tap(ops[0], tap + 2);
+                __builtin_amdgcn_sched_barrier(0);
+                multiply_tap(ops[1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+
+        if (ch + 1 < P.chunks) continue;
+        // ---- the tile is finished: register v of a lane is output channel 8 (v / 4) + 4 kq + v % 4 of the block
+        const int tile = (int)blockIdx.x + tl * (int)gridDim.x;
+        const int ig = fast_div(tile, P.by_tiles_y), ty = tile - ig * P.tiles_y;
+        const int n0 = ig * P.NI, row0 = ty * P.TH;
+        const int valid_px = P.NI > 1 ? min(P.NI, P.N - n0) * HoWo : min(P.TH, P.Ho - row0) * P.Wo;
+        if (P.out_off >= 0) {
+            // through LDS, so that a store instruction writes whole lines: the lane's 16 CB values go to
+            // [pixel][channel] rows of this wavefront's area (8 bytes at a time), and come back as 16-byte pieces with
+            // consecutive lanes on consecutive pieces of a pixel
+            constexpr int NC = 4 * CB;                                      // 16-byte pieces of a pixel's channels
+            constexpr int OP = 64 * CB + 16;                                // row pitch
+            unsigned char* lo = smem + P.out_off + wave * (32 * OP);
+            const int64_t tile_px0 = (int64_t)n0 * HoWo + row0 * P.Wo;
+#pragma unroll
+            for (int b = 0; b < PB; ++b) {
+                if (32 * (4 * b + wave) >= valid_px) continue;              // (wave-uniform)
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int col = cb * 32 + 8 * q + 4 * kq;
+                        unsigned h[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) h[j] = finish(acc[cb][b][4 * q + j], cb, 4 * q + j);
+                        *reinterpret_cast<intx2*>(lo + lj * OP + 2 * col) = intx2{(int)(h[0] | (h[1] << 16)), (int)(h[2] | (h[3] << 16))};
+                    }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+                for (int pass = 0; pass < NC / 2; ++pass) {
+                    const int px = lane / NC + (64 / NC) * pass, piece = lane % NC;
+                    const intx4 v = *reinterpret_cast<const intx4*>(lo + px * OP + 16 * piece);
+                    const int p = 32 * (4 * b + wave) + px;
+                    if (p < valid_px && co0 + 8 * piece < P.C_out)
+                        *reinterpret_cast<intx4*>(y + (tile_px0 + p) * P.C_out + co0 + 8 * piece) = v;
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // (the area is written again for the next block)
+            }
+            continue;
+        }
+#pragma unroll
+        for (int b = 0; b < PB; ++b) {
+            if (pl[b] >= valid_px) continue;
+            const int i = fast_div(pl[b], P.by_thwo), rem = pl[b] - i * thwo;       // (pixel of image n0 + i, rows from row0)
+            unsigned short* yp = y + ((int64_t)(n0 + i) * HoWo + row0 * P.Wo + rem) * P.C_out;
+#pragma unroll
+            for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int co = co0 + cb * 32 + 8 * q + 4 * kq;
+                    if (co < P.C_out) {
+                        unsigned h[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) h[j] = finish(acc[cb][b][4 * q + j], cb, 4 * q + j);
+                        *reinterpret_cast<intx2*>(yp + co) = intx2{(int)(h[0] | (h[1] << 16)), (int)(h[2] | (h[3] << 16))};
+                    }
+                }
+        }
+    }
+}
+
+struct LdsPlan {
+    bool ok = false;
+    int CB = 0, PB = 0;
+    size_t lds = 0;
+    unsigned gx = 0, gy = 0;
+    double est = 0;
+    int64_t tiles = 0;
+    LdsParams P;
+};
+
+LdsPlan plan_lds(const Conv2dShape& s, const void* x, const void* w, const void* y)
+{
+    LdsPlan best;
+    const int RS = s.R * s.S;
+    const int64_t x_bytes = (int64_t)s.N * s.H * s.W * s.C_in * 2, w_bytes = (int64_t)s.C_out * RS * s.C_in * 2;
+    if (s.C_in % 16 != 0 || s.C_out % 4 != 0 || x_bytes >= (1LL << 31) || w_bytes >= (1LL << 31)) return best;
+    if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0 || reinterpret_cast<uintptr_t>(y) % 8 != 0) return best;
+    if ((int64_t)s.N * s.Ho * s.Wo * s.C_out >= (1LL << 40)) return best;
+    const int frow = RS * s.C_in / 8, fpitch = frow | 1;
+    int CB = 2;
+    if ((size_t)64 * fpitch * 16 > kFilterMax || s.C_out <= 32) CB = 1;
+    if ((size_t)32 * CB * fpitch * 16 > kFilterMax) return best;
+    const size_t fbytes = ((size_t)32 * CB * fpitch * 16 + 1023) & ~(size_t)1023;
+    const int co_blocks = (s.C_out + 32 * CB - 1) / (32 * CB);
+    if (co_blocks > 65535) return best;
+    const int64_t IW = (int64_t)(s.Wo - 1) * s.stride + (int64_t)(s.S - 1) * s.dil + 1;
+    const int HoWo = s.Ho * s.Wo;
+    // the transposed store wants whole 16-byte pieces of y
+    const bool wide_out = s.C_out % 8 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
+    const size_t obytes = wide_out ? (size_t)4 * 32 * (64 * CB + 16) : 0;
+    // NP pieces of eight channels per pixel and chunk: the wider the chunk, the fewer steps; the narrower, the larger the tile LDS holds
+    auto consider = [&](int PB, int NP, int NI, int tiles_y) {
+        if (s.C_in % (8 * NP) != 0) return;
+        const int chunks = s.C_in / (8 * NP);
+        const int tp_max = 128 * PB;
+        const int TH = (s.Ho + tiles_y - 1) / tiles_y;
+        if ((int64_t)TH * s.Wo * NI > tp_max || (s.Ho + TH - 1) / TH != tiles_y) return;
+        const int64_t IH = (int64_t)(TH - 1) * s.stride + (int64_t)(s.R - 1) * s.dil + 1;
+        const int64_t WC = NI * IH * IW;
+        const int64_t wloads = (WC * NP + 63) / 64;
+        if (wloads > 4 * kMaxWK) return;
+        const size_t stage = (size_t)wloads * 1024;
+        const size_t lds = fbytes + 2 * stage + obytes;
+        if (lds > kLdsTotal) return;
+        const int blocks = (NI * TH * s.Wo + 31) / 32;
+        const int rounds = (blocks + 3) / 4;
+        const int64_t groups = (s.N + NI - 1) / NI;
+        const int64_t tiles = groups * tiles_y;
+        if (tiles > 2147483647LL) return;
+        // periods of one block through all of K: a workgroup holds four SIMDs for its rounds; 256 workgroups at a time
+        // (two blocks per wavefront halve the filter reads per matrix instruction: LDS bandwidth bounds the one-block tiles)
+        // (every wavefront multiplies PB blocks, live or not)
+        (void)rounds;
+        // (with a single tap a step is too short for two blocks to pay: measured)
+        const double est = std::max((double)PB, (double)tiles * co_blocks * PB / 256.0) * (PB == 2 ? (RS >= 4 ? 0.8 : 1.1) : 1.0) *
+                           (1.0 + 0.05 * (chunks - 1));
+        if (best.ok && (est > best.est || (est == best.est && tiles >= best.tiles))) return;
+        best.ok = true;
+        best.CB = CB;
+        best.PB = PB;
+        best.lds = lds;
+        best.est = est;
+        best.tiles = tiles;
+        best.gy = (unsigned)co_blocks;
+        best.gx = (unsigned)std::max<int64_t>(1, std::min<int64_t>(tiles, 256 / std::min(co_blocks, 256)));
+        LdsParams& P = best.P;
+        P.N = s.N; P.H = s.H; P.W = s.W; P.C = s.C_in; P.C_out = s.C_out; P.R = s.R; P.S = s.S; P.stride = s.stride;
+        P.pad = s.pad; P.dil = s.dil; P.Ho = s.Ho; P.Wo = s.Wo;
+        P.NI = NI; P.TH = TH; P.tiles_y = tiles_y; P.tiles = (int)tiles;
+        P.IH = (int)IH; P.IW = (int)IW; P.cells_img = (int)(IH * IW); P.WC = (int)WC;
+        P.NP = NP; P.chunks = chunks; P.wloads = (int)wloads;
+        P.frow = frow; P.fpitch = fpitch;
+        P.win_off = (int)fbytes; P.stage_bytes = (int)stage;
+        P.out_off = wide_out ? (int)(fbytes + 2 * stage) : -1;
+        P.x_bytes = (unsigned)x_bytes; P.w_bytes = (unsigned)w_bytes;
+        P.by_tiles_y = make_fastdiv(tiles_y);
+        P.by_cells_img = make_fastdiv(P.cells_img);
+        P.by_IW = make_fastdiv(P.IW);
+        P.by_thwo = make_fastdiv(TH * s.Wo);
+        P.by_Wo = make_fastdiv(s.Wo);
+        P.by_fpitch = make_fastdiv(fpitch);
+        P.by_S = make_fastdiv(s.S);
+    };
+    for (int PB = 1; PB <= 2; ++PB)
+        for (int NP = 8; NP >= 2; NP >>= 1) {
+            for (int NI = 2; NI <= s.N && (int64_t)NI * HoWo <= 128 * PB; ++NI) consider(PB, NP, NI, 1);
+            for (int tiles_y = 1; tiles_y <= s.Ho; ++tiles_y) consider(PB, NP, 1, tiles_y);
+        }
+    return best;
+}
+
+template <bool F16, int CB, int PB, int KSC>
+hipError_t launch_lds(const void* x, const void* w, void* y, const LdsPlan& a, hipStream_t st)
+{
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_16_nhwc_lds_kernel<F16, CB, PB, KSC>),
+                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsTotal);
+    if (attr != hipSuccess) return attr;
+    SW_NOTED_LAUNCH(note_kernel(F16 ? "mfma_f16_nhwc_lds_kernel" : "mfma_bf16_nhwc_lds_kernel", CB, PB, a.P.NI, a.P.TH),
+                    (mfma_16_nhwc_lds_kernel<F16, CB, PB, KSC>), dim3(a.gx, a.gy), dim3(512), a.lds, st,
+                    static_cast<const unsigned char*>(x), static_cast<const unsigned char*>(w), static_cast<unsigned short*>(y), a.P);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool mfma_16_nhwc_lds_supported(const void* x, const void* w, const void* y, const Conv2dShape& s) { return plan_lds(s, x, w, y).ok; }
+
+hipError_t launch_mfma_16_nhwc_lds(const void* x, const void* w, void* y, const Conv2dShape& s, bool f16, const Epilogue& ep,
+                                   hipStream_t st)
+{
+    LdsPlan a = plan_lds(s, x, w, y);
+    if (!a.ok) return hipErrorInvalidValue;
+    a.P.ep = ep;
+#define SW_L(CBC, PBC)                                                                                    \
+    if (a.CB == CBC && a.PB == PBC) {                                                                     \
+        if (a.P.NP == 8) return f16 ? launch_lds<true, CBC, PBC, 4>(x, w, y, a, st) : launch_lds<false, CBC, PBC, 4>(x, w, y, a, st); \
+        if (a.P.NP == 4) return f16 ? launch_lds<true, CBC, PBC, 2>(x, w, y, a, st) : launch_lds<false, CBC, PBC, 2>(x, w, y, a, st); \
+        return f16 ? launch_lds<true, CBC, PBC, 1>(x, w, y, a, st) : launch_lds<false, CBC, PBC, 1>(x, w, y, a, st);                  \
+    }
+    SW_L(2, 2); SW_L(2, 1); SW_L(1, 2); SW_L(1, 1);
+#undef SW_L
+    return hipErrorInvalidValue;
+}
+
+}  // namespace swconv

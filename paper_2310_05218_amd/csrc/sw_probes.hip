@@ -54,6 +54,24 @@ __global__ __launch_bounds__(64) void probe_mfma_i8_kernel(int iters, float* sin
     if (sink && s == 123456789) *sink = (float)s;
 }
 
+__global__ __launch_bounds__(64) void probe_mfma_bf16_kernel(int iters, float* sink)
+{
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    floatx16 acc[4];
+    for (int i = 0; i < 4; ++i)
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    const intx4 ai = {0x3f803f80, 0x3f003f00, (int)(0x3f800000u | threadIdx.x), 0x3f803f00}, bi = {0x3f803f80, 0x3f803f80, 0x3f003f80, 0x3f803f80};
+    const bf16x8 a = __builtin_bit_cast(bf16x8, ai), b = __builtin_bit_cast(bf16x8, bi);
+#pragma unroll 1
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < kMfmaPerIter; ++u) acc[u & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[u & 3], 0, 0, 0);
+    }
+    float s = 0.f;
+    for (int i = 0; i < 4; ++i) s += acc[i][0] + acc[i][15];
+    if (sink && s == 12345.678f) *sink = s;
+}
+
 // plain v_fma_f32 with a wave-uniform multiplicand, as in the one-filter-per-plane kernels (no packed forms)
 __global__ __launch_bounds__(64) void probe_fma_f32_kernel(int iters, float* sink, float tap0, float tap1)
 {
@@ -153,6 +171,7 @@ int64_t sw_probe_ops(int kind, int iters)
         case SW_PROBE_MFMA_I8: return waves * iters * kMfmaPerIter * (2LL * 32 * 32 * 32);
         case SW_PROBE_FMA_F32: return waves * iters * kFmaPerIter * (2LL * 64);
         case SW_PROBE_FMA_MFMA_F32: return waves * iters * kMixRounds * (kMixFma * 2LL * 64 + 2LL * 16 * 16 * 4);
+        case SW_PROBE_MFMA_BF16: return waves * iters * kMfmaPerIter * (2LL * 32 * 32 * 16);
         case SW_PROBE_MFMA_F32_FED: return 256LL * 4 * iters * kMfmaPerIter * (2LL * 32 * 32 * 2);
         case SW_PROBE_MFMA_F32_FED2: return 256LL * 8 * iters * kMfmaPerIter * (2LL * 32 * 32 * 2);
         default: return 0;
@@ -178,6 +197,9 @@ int sw_probe(int kind, int iters, void* hip_stream)
         case SW_PROBE_FMA_MFMA_F32:
             SW_NOTED_LAUNCH(note_kernel("probe_fma_mfma_f32_kernel"), probe_fma_mfma_f32_kernel, dim3(kProbeGroups), dim3(64), 0, st, iters,
                             none, 1.0000001f);
+            break;
+        case SW_PROBE_MFMA_BF16:
+            SW_NOTED_LAUNCH(note_kernel("probe_mfma_bf16_kernel"), probe_mfma_bf16_kernel, dim3(kProbeGroups), dim3(64), 0, st, iters, none);
             break;
         case SW_PROBE_MFMA_F32_FED:
             SW_NOTED_LAUNCH(note_kernel("probe_mfma_f32_fed_kernel", 1), probe_mfma_f32_fed_kernel<1>, dim3(256), dim3(256), 0, st, iters, none);

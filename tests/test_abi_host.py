@@ -328,4 +328,5 @@ def test_probe_argument_errors_and_operation_counts(L):
     assert L.sw_probe_ops(B.SW_PROBE_FMA_MFMA_F32, 3) == waves * 3 * 16 * (9 * 2 * 64 + 2 * 16 * 16 * 4)
     assert L.sw_probe_ops(B.SW_PROBE_MFMA_F32_FED, 3) == 256 * 4 * 3 * 8 * 2 * 32 * 32 * 2
     assert L.sw_probe_ops(B.SW_PROBE_MFMA_F32_FED2, 3) == 2 * L.sw_probe_ops(B.SW_PROBE_MFMA_F32_FED, 3)
+    assert L.sw_probe_ops(B.SW_PROBE_MFMA_BF16, 3) == waves * 3 * 8 * 2 * 32 * 32 * 16
     assert L.sw_probe_ops(99, 3) == 0 and L.sw_probe_ops(B.SW_PROBE_FMA_F32, 0) == 0

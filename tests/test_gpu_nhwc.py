@@ -104,26 +104,33 @@ def test_s8_nhwc_full_size_agrees_with_the_channel_first_call(torch, sw, oracle)
 # ----------------------------------------------------------------------------- fp32 and bf16, channel-last
 
 FLOAT_CASES = [
-    # N, H, W, C_in, C_out, R, S, stride, pad, dilation, kernel for fp32, kernel for bf16
-    (2, 28, 28, 64, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # two fp32 chunks of 32 channels, one bf16 chunk
-    (1, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # 4-row bands (224 pixels)
-    (2, 14, 14, 128, 96, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),   # four / two chunks, ragged channel block
-    (2, 30, 41, 16, 40, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # blocks that span rows, ragged last block
-    (1, 57, 57, 64, 128, 3, 3, 2, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),   # stride 2
-    (1, 20, 20, 16, 32, 5, 5, 1, 2, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # 25 taps: two rounds of filter pieces
+    # N, H, W, C_in, C_out, R, S, stride, pad, dilation, kernel for fp32, kernel for bf16 (the window-in-LDS kernel:
+    # <channel blocks per workgroup, pixel blocks per wavefront, images per tile, rows per tile>)
+    (2, 28, 28, 64, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,4>"),    # two fp32 chunks of 32 channels, one bf16 chunk
+    (1, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,2>"),    # 4-row bands (224 pixels)
+    (2, 14, 14, 128, 96, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<1,1,1,7>"),   # four / two chunks, ragged channel block
+    (2, 30, 41, 16, 40, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<2,1,1,3>"),    # blocks that span rows, ragged last block
+    (1, 57, 57, 64, 128, 3, 3, 2, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,1>"),   # stride 2
+    (1, 20, 20, 16, 32, 5, 5, 1, 2, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<1,1,1,5>"),    # 25 taps: two rounds of filter pieces
     (1, 12, 12, 48, 64, 7, 7, 1, 3, 1, "mfma_nhwc_kernel<0,1>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # 49 taps: LDS bounds the chunk
     (2, 19, 23, 64, 70, 1, 1, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),    # pointwise
     (1, 33, 17, 16, 5, 7, 3, 2, 3, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),     # rectangular filter, few output channels
-    (1, 28, 28, 32, 64, 3, 3, 1, 2, 2, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # dilation 2
-    (1, 40, 40, 16, 64, 3, 3, 2, 6, 6, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # dilation 6 with stride 2
+    (1, 28, 28, 32, 64, 3, 3, 1, 2, 2, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,4>"),    # dilation 2
+    (1, 40, 40, 16, 64, 3, 3, 2, 6, 6, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<2,1,1,5>"),    # dilation 6 with stride 2
     (1, 9, 300, 16, 64, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # rows wider than 256 outputs
     (1, 12, 12, 12, 16, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "direct_nhwc_kernel<1>"),    # pixels that are not whole K steps
     (1, 12, 12, 8, 16, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,1>", "direct_nhwc_kernel<1>"),     # 32 bytes per pixel in fp32, 16 in bf16
-    (1, 5, 5, 16, 8, 5, 5, 1, 0, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),       # a single output pixel
-    (16, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<2,2>"),   # enough tiles for two channel blocks per wavefront
-    (3, 21, 21, 48, 36, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # three K steps per tap (27 iterations), ragged channel block
-    (2, 16, 16, 32, 64, 2, 2, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # 8 iterations: two left over after the ring's trips
+    (1, 5, 5, 16, 8, 5, 5, 1, 0, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<1,1,1,1>"),       # a single output pixel
+    (16, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,2,1,4>"),   # enough tiles for two channel blocks per wavefront
+    (3, 21, 21, 48, 36, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<2,1,1,6>"),    # three K steps per tap (27 iterations), ragged channel block
+    (2, 16, 16, 32, 64, 2, 2, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,8>"),    # 8 iterations: two left over after the ring's trips
     (1, 20, 20, 32, 30, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,2>"),    # an output channel count the 8-byte stores do not take: window in LDS
+    (5, 7, 7, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,2,7>"),        # whole small images, several per tile, the last tile short
+    (9, 4, 4, 64, 40, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,5,4>"),    # five 4 x 4 images per tile, 9 = 5 + 4
+    # filters of 32 output channels beyond what the window-in-LDS kernel keeps resident: operands straight from global memory
+    (2, 14, 14, 160, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),     # ten K steps per tap (90 iterations)
+    (1, 16, 16, 320, 32, 2, 2, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),     # 80 iterations: two left over after the ring's trips
+    (20, 9, 300, 16, 64, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<2,2>"),     # rows too wide for a window tile, enough tiles for two channel blocks per wavefront
 ]
 
 
@@ -195,7 +202,7 @@ def test_conv2d_nhwc_f16(torch, sw, oracle, case):
     """IEEE half precision in and out, fp32 accumulation, on every shape of the bf16 cases (the same kernels with the
     half-precision matrix instruction and rounding)."""
     N, H, W, C_in, C_out, R, S, stride, pad, dil, _, kernel = case
-    kernel = kernel.replace("mfma_bf16_nhwc_direct", "mfma_f16_nhwc_direct").replace("mfma_nhwc_kernel<1,", "mfma_nhwc_kernel<2,") \
+    kernel = kernel.replace("mfma_bf16_nhwc_direct", "mfma_f16_nhwc_direct").replace("mfma_bf16_nhwc_lds", "mfma_f16_nhwc_lds").replace("mfma_nhwc_kernel<1,", "mfma_nhwc_kernel<2,") \
         .replace("direct_nhwc_kernel<1>", "direct_nhwc_kernel<2>")
     xh = inputs.normal_f16((N, H, W, C_in), 5231)
     wh = inputs.normal_f16((C_out, R, S, C_in), 5232, (2.0 / (C_in * R * S)) ** 0.5)
@@ -204,8 +211,8 @@ def test_conv2d_nhwc_f16(torch, sw, oracle, case):
         _f16_case(torch, sw, oracle, xh, wh, stride, pad, dil, bias, relu, kernel, case)
 
 
-@pytest.mark.parametrize("shape", [(2, 14, 14, 32, 32, "mfma_f16_nhwc_direct_kernel<1,2>"), (1, 14, 14, 32, 30, "mfma_nhwc_kernel<2,2>"),
-                                   (1, 9, 9, 12, 8, "direct_nhwc_kernel<2>")], ids=lambda s: s[5])
+@pytest.mark.parametrize("shape", [(2, 14, 14, 32, 32, "mfma_f16_nhwc_lds_kernel<1,1,1,7>"), (1, 9, 9, 160, 32, "mfma_f16_nhwc_direct_kernel<1,2>"),
+                                   (1, 14, 14, 32, 30, "mfma_nhwc_kernel<2,2>"), (1, 9, 9, 12, 8, "direct_nhwc_kernel<2>")], ids=lambda s: s[5])
 def test_conv2d_nhwc_f16_denormals_and_overflow(torch, sw, oracle, shape):
     """What half precision has and bf16 has not: denormal inputs count (activations of about 2^-16 against filters of
     about 2^6: were the denormals flushed the sums would vanish), results below 2^-14 are kept as denormals, results
@@ -216,7 +223,7 @@ def test_conv2d_nhwc_f16_denormals_and_overflow(torch, sw, oracle, shape):
     w_big = inputs.normal_f16((C_out, 3, 3, C_in), 5242, 64.0)
     y, y_ref = _f16_case(torch, sw, oracle, x_small, w_big, 1, 1, 1, None, False, kernel, "denormal x")
     assert np.median(np.abs(y_ref)) > 2.0 ** -10 and np.count_nonzero(y) > 0.99 * y.size
-    w_small = inputs.normal_f16((C_out, 3, 3, C_in), 5243, 2.0 ** -6)
+    w_small = inputs.normal_f16((C_out, 3, 3, C_in), 5243, 2.0 ** -6 * (32.0 / max(C_in, 32)) ** 0.5)
     y, y_ref = _f16_case(torch, sw, oracle, x_small, w_small, 1, 1, 1, None, False, kernel, "denormal y")
     assert np.max(np.abs(y_ref)) < 2.0 ** -14 and np.count_nonzero(y) > 0.5 * y.size
     # overflow: every product 200 * 200, so a full window sums to 9 * C_in * 40000 > 65504; the sign follows the filter

@@ -22,7 +22,8 @@ def timed_us(kind, iters):
 @pytest.mark.parametrize("kind, name", [(sw.SW_PROBE_MFMA_F32, "probe_mfma_f32_kernel"), (sw.SW_PROBE_MFMA_I8, "probe_mfma_i8_kernel"),
                                         (sw.SW_PROBE_FMA_F32, "probe_fma_f32_kernel"), (sw.SW_PROBE_FMA_MFMA_F32, "probe_fma_mfma_f32_kernel"),
                                         (sw.SW_PROBE_MFMA_F32_FED, "probe_mfma_f32_fed_kernel<1>"),
-                                        (sw.SW_PROBE_MFMA_F32_FED2, "probe_mfma_f32_fed_kernel<2>")])
+                                        (sw.SW_PROBE_MFMA_F32_FED2, "probe_mfma_f32_fed_kernel<2>"),
+                                        (sw.SW_PROBE_MFMA_BF16, "probe_mfma_bf16_kernel")])
 def test_probe_runs(kind, name):
     ops = sw.sw_probe(kind, 50)
     torch.cuda.synchronize()

@@ -362,9 +362,10 @@ int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* b
  * aligned x and w run on the matrix cores, the channels in chunks of up to 128 bytes
  * per pixel (any extent, stride, dilation and C_out); every other valid shape one
  * thread per output.  bf16 / half with C_out % 4 == 0, 8-byte aligned y and tensors below
- * 2 GiB run on one of two faster kernels: filters of 32 output channels within 76 KB and
- * tiles whose windows fit LDS beside them (3 x 3 up to 128 channels, 1 x 1 up to 1200):
- * filters resident in LDS, windows brought in by direct-to-LDS loads a tile ahead;
+ * 2 GiB run on one of two faster kernels.  Where a tile of output rows (at most 256
+ * outputs wide) and its window fit LDS, the windows are brought in by direct-to-LDS
+ * loads a tile ahead, the filters resident in LDS (those of 32 output channels within
+ * 76 KB: 3 x 3 up to 128 channels) or, larger, fetched chunk by chunk with the windows;
  * otherwise, with R, S <= 32 and the filters of 32 output channels within 150 KB, the
  * pixel operands are read straight from x (no window in LDS).
  */

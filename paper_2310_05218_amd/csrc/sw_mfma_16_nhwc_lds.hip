@@ -18,6 +18,11 @@
 // wavefronts only load, four multiply (pixel block 4b + w to wavefront w, all channel blocks).  Filters are the A operand,
 // pixels the B operand: a lane of the result holds, for its pixel, groups of four consecutive output channels (8-byte
 // stores).
+//
+// Filters too large to stay in LDS whole (3 x 3 from 144 input channels on, at 64 output channels per workgroup) travel
+// with the window instead: every stage carries the chunk's part of the filters, [channel][tap][NP pieces] at an odd row
+// pitch, fetched by the same loaders from L2 again for every tile.  The multipliers read them at the stage's address; all
+// else is the same code (FS, a compile-time switch, so that the resident form pays nothing for it).
 #include <algorithm>
 
 #include "swconv_internal.h"
@@ -37,6 +42,7 @@ typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 constexpr size_t kLdsTotal = 156 * 1024;
 constexpr size_t kFilterMax = 76 * 1024;       // resident filters of a workgroup
 constexpr int kMaxWK = 12;                     // window loads per loading wavefront and stage
+constexpr int kMaxFK = 12;                     // filter loads per loading wavefront and stage (filters fetched per chunk)
 constexpr unsigned kBeyond = 0x80000000u;
 
 struct LdsParams {
@@ -48,9 +54,11 @@ struct LdsParams {
     int wloads;                    // 64-piece loads per window stage
     int frow, fpitch;              // 16-byte pieces of an output channel's filters (R S C / 8), row pitch in LDS (odd)
     int win_off, stage_bytes;      // window stages behind the filters
+    int fstream;                   // the filters do not fit LDS whole: the chunk's part ([channel][tap][NP pieces], pitch fp2)
+    int fp2, fs_off, fsloads;      // travels with every window stage, fs_off bytes behind the window, in fsloads loads
     int out_off;                   // per multiplying wavefront: 32 pixels x (64 CB + 16) bytes for the transposed store (< 0: none)
     unsigned x_bytes, w_bytes;
-    FastDiv by_tiles_y, by_cells_img, by_IW, by_thwo, by_Wo, by_fpitch, by_S;
+    FastDiv by_tiles_y, by_cells_img, by_IW, by_thwo, by_Wo, by_fpitch, by_fp2;
 };
 
 __device__ __forceinline__ unsigned round16_bits(float f, bool f16)
@@ -60,8 +68,8 @@ __device__ __forceinline__ unsigned round16_bits(float f, bool f16)
 }
 
 // F16: IEEE half (else bf16).  CB: blocks of 32 output channels per workgroup.  PB: blocks of 32 pixels per wavefront.
-// KSC: steps of 16 channels per tap and chunk (NP / 2).
-template <bool F16, int CB, int PB, int KSC>
+// KSC: steps of 16 channels per tap and chunk (NP / 2).  FS: filters per chunk with the window (else resident).
+template <bool F16, int CB, int PB, int KSC, bool FS>
 __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned char* __restrict__ x, const unsigned char* __restrict__ w,
                                                                   unsigned short* __restrict__ y, const LdsParams P)
 {
@@ -73,7 +81,7 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
     const int m = P.NP - 1, lnp = __builtin_ctz(P.NP);
 
     // the filters, once, by every wavefront: slot q of the filter area is piece q % fpitch of output channel q / fpitch
-    {
+    if (!FS) {
         const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(w), 0, P.w_bytes, 0x00020000);
         const int floads = (32 * CB * P.fpitch + 63) >> 6;
 #pragma unroll 1
@@ -106,6 +114,21 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
             wrow[k] = in ? e : -(1 << 20);                          // (a row that never exists)
             wofs[k] = (unsigned)(((i * P.H + e) * P.W + gc) * (2 * P.C) + 16 * piece);
         }
+        // (filters per chunk) this lane's slot in each filter load of this wavefront: piece j % NP of tap j / NP of output
+        // channel co, j = q % fp2; byte offset in w for chunk 0
+        unsigned fofs[kMaxFK];
+        const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char*>(w), 0, P.w_bytes, 0x00020000);
+#pragma unroll
+        for (int k = 0; k < kMaxFK; ++k) {
+            fofs[k] = kBeyond;
+            if (FS) {
+                const int q = 64 * (lw + 4 * k) + lane;
+                const int co = fast_div(q, P.by_fp2), j = q - co * P.fp2;
+                const int tap = j >> lnp, piece = j & m;
+                if (co < 32 * CB && tap < P.R * P.S && co0 + co < P.C_out)
+                    fofs[k] = (unsigned)((((co0 + co) * P.R * P.S + tap) * P.C) * 2 + 16 * piece);
+            }
+        }
         auto issue = [&](int step, int stage) __attribute__((always_inline)) {
             const int tl = step / P.chunks, ch = step - tl * P.chunks;              // (wave-uniform)
             const int tile = (int)blockIdx.x + tl * (int)gridDim.x;
@@ -120,6 +143,14 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
                     const bool in = gr >= 0 && gr < P.H && n0 + wimg[k] < P.N;
                     __builtin_amdgcn_raw_ptr_buffer_load_lds(xr, SW_LDS_PTR(sw + 1024 * (lw + 4 * k)), 16, in ? origin + wofs[k] : kBeyond, 0, 0, 0);
                 }
+            }
+            if (FS) {
+                const unsigned choff = (unsigned)(ch * (16 * P.NP));
+#pragma unroll
+                for (int k = 0; k < kMaxFK; ++k)
+                    if (lw + 4 * k < P.fsloads)
+                        __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, SW_LDS_PTR(sw + P.fs_off + 1024 * (lw + 4 * k)), 16,
+                                                                 fofs[k] == kBeyond ? kBeyond : fofs[k] + choff, 0, 0, 0);
             }
         };
         if (steps_per_wg > 0) issue(0, 0);
@@ -147,8 +178,10 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
         cell0[b] = i * P.cells_img + (ol * P.IW + ow) * P.stride;
         pl[b] = p;
     }
-    const unsigned char* arow = smem + (lj * P.fpitch + kq) * 16;          // + 32 cb fpitch 16 + (tap C / 8 + chunk NP + 2 ks) 16
-    const int cpt = P.C >> 3;                                              // pieces per tap in a filter row
+    // A operand of (channel block cb, tap, step ks): resident filters: row pitch fpitch pieces, C / 8 pieces per tap, the
+    // chunk's NP pieces at chunk NP; filters per chunk: row pitch fp2, NP pieces per tap
+    const int apitch = FS ? P.fp2 : P.fpitch, cpt = FS ? P.NP : P.C >> 3;
+    const unsigned char* arow = smem + (lj * apitch + kq) * 16;            // + 32 cb apitch 16 + (tap cpt + 2 ks) 16
 
     // the lane's 16 CB output channels' biases, read once (zeros without a bias); the rectifier as a lower bound
     float bias[CB][16];
@@ -181,7 +214,7 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
         // acknowledged (about 2 us per tile); nothing here reads what they wrote
         asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
         const unsigned char* sw = smem + P.win_off + (s & 1) * P.stage_bytes;
-        const unsigned char* ab = arow + (ch * P.NP) * 16;
+        const unsigned char* ab = FS ? arow + P.win_off + (s & 1) * P.stage_bytes + P.fs_off : arow + (ch * P.NP) * 16;
         // One tap at a time: the KSC steps of 16 channels of a tap are KSC CB PB matrix instructions on KSC (CB + PB)
         // operand reads; the reads of tap t + 1 (into the other register set) sit between the matrix instructions of
         // tap t.  Per tap the window address costs three vector instructions per block and two per read.
@@ -198,7 +231,7 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
 #pragma unroll
             for (int ks = 0; ks < KSC; ++ks)
 #pragma unroll
-                for (int cb = 0; cb < CB; ++cb) o.a[ks][cb] = *reinterpret_cast<const intx4*>(at + (32 * cb * P.fpitch + 2 * ks) * 16);
+                for (int cb = 0; cb < CB; ++cb) o.a[ks][cb] = *reinterpret_cast<const intx4*>(at + (32 * cb * apitch + 2 * ks) * 16);
 #pragma unroll
             for (int b = 0; b < PB; ++b) {
                 const int cell = cell0[b] + toff;
@@ -309,7 +342,7 @@ struct LdsPlan {
     LdsParams P;
 };
 
-LdsPlan plan_lds(const Conv2dShape& s, const void* x, const void* w, const void* y)
+LdsPlan search_plan(const Conv2dShape& s, const void* x, const void* w, const void* y)
 {
     LdsPlan best;
     const int RS = s.R * s.S;
@@ -318,21 +351,24 @@ LdsPlan plan_lds(const Conv2dShape& s, const void* x, const void* w, const void*
     if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0 || reinterpret_cast<uintptr_t>(y) % 8 != 0) return best;
     if ((int64_t)s.N * s.Ho * s.Wo * s.C_out >= (1LL << 40)) return best;
     const int frow = RS * s.C_in / 8, fpitch = frow | 1;
-    int CB = 2;
-    if ((size_t)64 * fpitch * 16 > kFilterMax || s.C_out <= 32) CB = 1;
-    if ((size_t)32 * CB * fpitch * 16 > kFilterMax) return best;
-    const size_t fbytes = ((size_t)32 * CB * fpitch * 16 + 1023) & ~(size_t)1023;
-    const int co_blocks = (s.C_out + 32 * CB - 1) / (32 * CB);
-    if (co_blocks > 65535) return best;
     const int64_t IW = (int64_t)(s.Wo - 1) * s.stride + (int64_t)(s.S - 1) * s.dil + 1;
     const int HoWo = s.Ho * s.Wo;
     // the transposed store wants whole 16-byte pieces of y
     const bool wide_out = s.C_out % 8 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
-    const size_t obytes = wide_out ? (size_t)4 * 32 * (64 * CB + 16) : 0;
-    // NP pieces of eight channels per pixel and chunk: the wider the chunk, the fewer steps; the narrower, the larger the tile LDS holds
-    auto consider = [&](int PB, int NP, int NI, int tiles_y) {
+    // CB blocks of 32 output channels per workgroup; filters resident (fstream = false) or fetched per chunk with the window;
+    // NP pieces of eight channels per pixel and chunk: the wider the chunk, the fewer steps; the narrower, the larger the
+    // tile LDS holds
+    auto consider = [&](int CB, bool fstream, int PB, int NP, int NI, int tiles_y) {
         if (s.C_in % (8 * NP) != 0) return;
         const int chunks = s.C_in / (8 * NP);
+        const int co_blocks = (s.C_out + 32 * CB - 1) / (32 * CB);
+        if (co_blocks > 65535) return;
+        const int fp2 = (RS * NP) | 1;
+        const int64_t fsloads = fstream ? ((int64_t)32 * CB * fp2 + 63) / 64 : 0;
+        if (fsloads > 4 * kMaxFK) return;
+        const size_t fbytes = fstream ? 0 : ((size_t)32 * CB * fpitch * 16 + 1023) & ~(size_t)1023;
+        if (fbytes > kFilterMax) return;
+        const size_t obytes = wide_out ? (size_t)4 * 32 * (64 * CB + 16) : 0;
         const int tp_max = 128 * PB;
         const int TH = (s.Ho + tiles_y - 1) / tiles_y;
         if ((int64_t)TH * s.Wo * NI > tp_max || (s.Ho + TH - 1) / TH != tiles_y) return;
@@ -340,21 +376,18 @@ LdsPlan plan_lds(const Conv2dShape& s, const void* x, const void* w, const void*
         const int64_t WC = NI * IH * IW;
         const int64_t wloads = (WC * NP + 63) / 64;
         if (wloads > 4 * kMaxWK) return;
-        const size_t stage = (size_t)wloads * 1024;
+        const size_t stage = (size_t)(wloads + fsloads) * 1024;
         const size_t lds = fbytes + 2 * stage + obytes;
         if (lds > kLdsTotal) return;
-        const int blocks = (NI * TH * s.Wo + 31) / 32;
-        const int rounds = (blocks + 3) / 4;
         const int64_t groups = (s.N + NI - 1) / NI;
         const int64_t tiles = groups * tiles_y;
         if (tiles > 2147483647LL) return;
-        // periods of one block through all of K: a workgroup holds four SIMDs for its rounds; 256 workgroups at a time
-        // (two blocks per wavefront halve the filter reads per matrix instruction: LDS bandwidth bounds the one-block tiles)
-        // (every wavefront multiplies PB blocks, live or not)
-        (void)rounds;
-        // (with a single tap a step is too short for two blocks to pay: measured)
+        // Periods of one block through all of K: every wavefront multiplies PB blocks, live or not; 256 workgroups at a
+        // time.  Two blocks per wavefront halve the filter reads per matrix instruction (LDS bandwidth bounds the one-block
+        // tiles), but with a single tap a step is too short for them to pay (measured); one channel block per workgroup
+        // doubles the window reads per matrix instruction; filters per chunk are fetched again for every tile.
         const double est = std::max((double)PB, (double)tiles * co_blocks * PB / 256.0) * (PB == 2 ? (RS >= 4 ? 0.8 : 1.1) : 1.0) *
-                           (1.0 + 0.05 * (chunks - 1));
+                           (1.0 + 0.05 * (chunks - 1)) * (CB == 1 && s.C_out > 32 ? 1.2 : 1.0) * (fstream ? 1.3 : 1.0);
         if (best.ok && (est > best.est || (est == best.est && tiles >= best.tiles))) return;
         best.ok = true;
         best.CB = CB;
@@ -371,6 +404,7 @@ LdsPlan plan_lds(const Conv2dShape& s, const void* x, const void* w, const void*
         P.IH = (int)IH; P.IW = (int)IW; P.cells_img = (int)(IH * IW); P.WC = (int)WC;
         P.NP = NP; P.chunks = chunks; P.wloads = (int)wloads;
         P.frow = frow; P.fpitch = fpitch;
+        P.fstream = fstream ? 1 : 0; P.fp2 = fp2; P.fs_off = (int)(wloads * 1024); P.fsloads = (int)fsloads;
         P.win_off = (int)fbytes; P.stage_bytes = (int)stage;
         P.out_off = wide_out ? (int)(fbytes + 2 * stage) : -1;
         P.x_bytes = (unsigned)x_bytes; P.w_bytes = (unsigned)w_bytes;
@@ -380,24 +414,36 @@ LdsPlan plan_lds(const Conv2dShape& s, const void* x, const void* w, const void*
         P.by_thwo = make_fastdiv(TH * s.Wo);
         P.by_Wo = make_fastdiv(s.Wo);
         P.by_fpitch = make_fastdiv(fpitch);
-        P.by_S = make_fastdiv(s.S);
+        P.by_fp2 = make_fastdiv(fp2);
     };
-    for (int PB = 1; PB <= 2; ++PB)
-        for (int NP = 8; NP >= 2; NP >>= 1) {
-            for (int NI = 2; NI <= s.N && (int64_t)NI * HoWo <= 128 * PB; ++NI) consider(PB, NP, NI, 1);
-            for (int tiles_y = 1; tiles_y <= s.Ho; ++tiles_y) consider(PB, NP, 1, tiles_y);
-        }
+    for (int mode = 0; mode < 4; ++mode) {
+        const int CB = (mode & 1) ? 1 : 2;
+        const bool fstream = mode >= 2;
+        if (CB == 2 && s.C_out <= 32) continue;
+        for (int PB = 1; PB <= 2; ++PB)
+            for (int NP = 8; NP >= 2; NP >>= 1) {
+                for (int NI = 2; NI <= s.N && (int64_t)NI * HoWo <= 128 * PB; ++NI) consider(CB, fstream, PB, NP, NI, 1);
+                for (int tiles_y = 1; tiles_y <= s.Ho; ++tiles_y) consider(CB, fstream, PB, NP, 1, tiles_y);
+            }
+    }
     return best;
 }
 
-template <bool F16, int CB, int PB, int KSC>
+// (the search walks a few thousand candidates: more host time than a small layer runs for)
+LdsPlan plan_lds(const Conv2dShape& s, const void* x, const void* w, const void* y)
+{
+    thread_local PlanCache<LdsPlan> cache;
+    return cache.get(s, PlanCache<LdsPlan>::low_bits(x, w, y), [&] { return search_plan(s, x, w, y); });
+}
+
+template <bool F16, int CB, int PB, int KSC, bool FS>
 hipError_t launch_lds(const void* x, const void* w, void* y, const LdsPlan& a, hipStream_t st)
 {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_16_nhwc_lds_kernel<F16, CB, PB, KSC>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_16_nhwc_lds_kernel<F16, CB, PB, KSC, FS>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsTotal);
     if (attr != hipSuccess) return attr;
-    SW_NOTED_LAUNCH(note_kernel(F16 ? "mfma_f16_nhwc_lds_kernel" : "mfma_bf16_nhwc_lds_kernel", CB, PB, a.P.NI, a.P.TH),
-                    (mfma_16_nhwc_lds_kernel<F16, CB, PB, KSC>), dim3(a.gx, a.gy), dim3(512), a.lds, st,
+    SW_NOTED_LAUNCH(note_kernel(F16 ? "mfma_f16_nhwc_lds_kernel" : "mfma_bf16_nhwc_lds_kernel", CB + 10 * a.P.fstream, PB, a.P.NI, a.P.TH),
+                    (mfma_16_nhwc_lds_kernel<F16, CB, PB, KSC, FS>), dim3(a.gx, a.gy), dim3(512), a.lds, st,
                     static_cast<const unsigned char*>(x), static_cast<const unsigned char*>(w), static_cast<unsigned short*>(y), a.P);
     return hipGetLastError();
 }
@@ -412,13 +458,19 @@ hipError_t launch_mfma_16_nhwc_lds(const void* x, const void* w, void* y, const 
     LdsPlan a = plan_lds(s, x, w, y);
     if (!a.ok) return hipErrorInvalidValue;
     a.P.ep = ep;
-#define SW_L(CBC, PBC)                                                                                    \
-    if (a.CB == CBC && a.PB == PBC) {                                                                     \
-        if (a.P.NP == 8) return f16 ? launch_lds<true, CBC, PBC, 4>(x, w, y, a, st) : launch_lds<false, CBC, PBC, 4>(x, w, y, a, st); \
-        if (a.P.NP == 4) return f16 ? launch_lds<true, CBC, PBC, 2>(x, w, y, a, st) : launch_lds<false, CBC, PBC, 2>(x, w, y, a, st); \
-        return f16 ? launch_lds<true, CBC, PBC, 1>(x, w, y, a, st) : launch_lds<false, CBC, PBC, 1>(x, w, y, a, st);                  \
+#define SW_K(CBC, PBC, KSC, FSC) \
+    return f16 ? launch_lds<true, CBC, PBC, KSC, FSC>(x, w, y, a, st) : launch_lds<false, CBC, PBC, KSC, FSC>(x, w, y, a, st)
+#define SW_F(CBC, PBC, KSC) \
+    { if (a.P.fstream) SW_K(CBC, PBC, KSC, true); else SW_K(CBC, PBC, KSC, false); }
+#define SW_L(CBC, PBC)                        \
+    if (a.CB == CBC && a.PB == PBC) {         \
+        if (a.P.NP == 8) SW_F(CBC, PBC, 4)    \
+        if (a.P.NP == 4) SW_F(CBC, PBC, 2)    \
+        SW_F(CBC, PBC, 1)                     \
     }
     SW_L(2, 2); SW_L(2, 1); SW_L(1, 2); SW_L(1, 1);
+#undef SW_K
+#undef SW_F
 #undef SW_L
     return hipErrorInvalidValue;
 }

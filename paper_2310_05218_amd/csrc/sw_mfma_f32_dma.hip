@@ -361,7 +361,7 @@ struct DmaPlan {
     DmaParams P;
 };
 
-DmaPlan plan_dma(const Conv2dShape& s, const void* x, const void* w)
+DmaPlan search_plan(const Conv2dShape& s, const void* x, const void* w)
 {
     DmaPlan best;
     const int RS = s.R * s.S;
@@ -464,6 +464,12 @@ hipError_t launch_dma(const float* x, const float* w, float* y, const DmaPlan& a
     SW_NOTED_LAUNCH(note_kernel("mfma_f32_dma_kernel", 100 * KS + 10 * BW + NBW, a.P.CK, a.P.NI, a.P.TH),
                     (mfma_f32_dma_kernel<NBW, NGT, BW, KS>), dim3(a.gx, a.gy), dim3(64 * (BW * KS + 4)), a.lds, st, x, w, y, a.P);
     return hipGetLastError();
+}
+
+DmaPlan plan_dma(const Conv2dShape& s, const void* x, const void* w)
+{
+    thread_local PlanCache<DmaPlan> cache;
+    return cache.get(s, PlanCache<DmaPlan>::low_bits(x, w, nullptr), [&] { return search_plan(s, x, w); });
 }
 
 }  // namespace

@@ -25,6 +25,42 @@ struct Conv2dShape {
     int dil = 1;      // input positions between neighbouring taps (the any-shape fp32, run-time-extent tile and direct kernels take > 1)
 };
 
+// A launch plan found by a search over tilings costs host time that a small layer cannot hide behind its own run time.
+// Each host thread keeps the plans of the shapes it saw last.  A plan may depend on the shape and on the low four address
+// bits of up to three buffers, on nothing else.
+template <class Plan>
+struct PlanCache {
+    struct Entry {
+        bool used = false;
+        Conv2dShape s;
+        unsigned align = 0;
+        Plan plan;
+    };
+    static constexpr int kEntries = 16;
+    Entry e[kEntries];
+    int next = 0;
+    static unsigned low_bits(const void* a, const void* b, const void* c)
+    {
+        return (unsigned)(reinterpret_cast<uintptr_t>(a) & 15) | (unsigned)(reinterpret_cast<uintptr_t>(b) & 15) << 4 |
+               (unsigned)(reinterpret_cast<uintptr_t>(c) & 15) << 8;
+    }
+    static bool same(const Conv2dShape& a, const Conv2dShape& b)
+    {
+        return a.N == b.N && a.C_in == b.C_in && a.C_out == b.C_out && a.H == b.H && a.W == b.W && a.R == b.R && a.S == b.S &&
+               a.stride == b.stride && a.pad == b.pad && a.Ho == b.Ho && a.Wo == b.Wo && a.dil == b.dil;
+    }
+    template <class Search>
+    const Plan& get(const Conv2dShape& s, unsigned align, Search&& search)
+    {
+        for (int i = 0; i < kEntries; ++i)
+            if (e[i].used && e[i].align == align && same(e[i].s, s)) return e[i].plan;
+        Entry& n = e[next];
+        next = (next + 1) % kEntries;
+        n.used = true; n.s = s; n.align = align; n.plan = search();
+        return n.plan;
+    }
+};
+
 // Per-channel bias and rectifier on an fp32 sum on its way out: y = relu ? max(acc + bias[co], 0) : acc + bias[co]
 // (one fp32 addition).  bias may be null.
 struct Epilogue {

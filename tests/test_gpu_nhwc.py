@@ -127,10 +127,19 @@ FLOAT_CASES = [
     (1, 20, 20, 32, 30, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,2>"),    # an output channel count the 8-byte stores do not take: window in LDS
     (5, 7, 7, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,2,7>"),        # whole small images, several per tile, the last tile short
     (9, 4, 4, 64, 40, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,5,4>"),    # five 4 x 4 images per tile, 9 = 5 + 4
-    # filters of 32 output channels beyond what the window-in-LDS kernel keeps resident: operands straight from global memory
-    (2, 14, 14, 160, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),     # ten K steps per tap (90 iterations)
-    (1, 16, 16, 320, 32, 2, 2, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_direct_kernel<1,2>"),     # 80 iterations: two left over after the ring's trips
-    (20, 9, 300, 16, 64, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<2,2>"),     # rows too wide for a window tile, enough tiles for two channel blocks per wavefront
+    # filters too large to stay in LDS whole: the window-in-LDS kernel fetches each chunk's part with the window (first
+    # number + 10)
+    (2, 14, 14, 160, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<12,1,1,7>"),   # ten chunks of 16 channels
+    (1, 16, 16, 320, 32, 2, 2, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<11,1,1,8>"),   # one channel block, 2 x 2
+    (32, 28, 28, 128, 128, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<12,2,1,7>"),  # two pixel blocks per wavefront
+    (4, 7, 7, 256, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<12,1,2,7>"),     # two images per tile
+    (1, 15, 15, 192, 44, 3, 3, 2, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<12,1,1,8>"),   # stride 2, ragged channel block
+    (1, 14, 14, 144, 64, 3, 3, 1, 2, 2, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<12,1,1,7>"),   # dilation 2, nine chunks
+    (2, 10, 10, 96, 64, 5, 5, 1, 2, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<11,1,1,10>"),   # 25 taps
+    # rows too wide for a window tile: operands straight from global memory
+    (1, 4, 300, 160, 32, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<1,2>"),     # ten K steps per tap (90 iterations)
+    (1, 3, 300, 320, 32, 2, 2, 1, 0, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<1,2>"),     # 80 iterations: two left over after the ring's trips
+    (20, 9, 300, 16, 64, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<2,2>"),     # enough tiles for two channel blocks per wavefront
 ]
 
 
@@ -211,7 +220,8 @@ def test_conv2d_nhwc_f16(torch, sw, oracle, case):
         _f16_case(torch, sw, oracle, xh, wh, stride, pad, dil, bias, relu, kernel, case)
 
 
-@pytest.mark.parametrize("shape", [(2, 14, 14, 32, 32, "mfma_f16_nhwc_lds_kernel<1,1,1,7>"), (1, 9, 9, 160, 32, "mfma_f16_nhwc_direct_kernel<1,2>"),
+@pytest.mark.parametrize("shape", [(2, 14, 14, 32, 32, "mfma_f16_nhwc_lds_kernel<1,1,1,7>"), (1, 9, 9, 160, 32, "mfma_f16_nhwc_lds_kernel<11,1,1,9>"),
+                                   (1, 3, 300, 160, 32, "mfma_f16_nhwc_direct_kernel<1,2>"),
                                    (1, 14, 14, 32, 30, "mfma_nhwc_kernel<2,2>"), (1, 9, 9, 12, 8, "direct_nhwc_kernel<2>")], ids=lambda s: s[5])
 def test_conv2d_nhwc_f16_denormals_and_overflow(torch, sw, oracle, shape):
     """What half precision has and bf16 has not: denormal inputs count (activations of about 2^-16 against filters of

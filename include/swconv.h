@@ -361,13 +361,13 @@ int sw_conv2d_s8_nhwc_requant(const int8_t* x, const int8_t* w, const int32_t* b
  * Pixels of a multiple of 32 bytes (C_in % 8 == 0 in fp32, % 16 in bf16 / half) and 16-byte
  * aligned x and w run on the matrix cores, the channels in chunks of up to 128 bytes
  * per pixel (any extent, stride, dilation and C_out); every other valid shape one
- * thread per output.  bf16 / half with C_out % 4 == 0, 8-byte aligned y and tensors below
- * 2 GiB run on one of two faster kernels.  Where a tile of output rows (at most 256
- * outputs wide) and its window fit LDS, the windows are brought in by direct-to-LDS
- * loads a tile ahead, the filters resident in LDS (those of 32 output channels within
- * 76 KB: 3 x 3 up to 128 channels) or, larger, fetched chunk by chunk with the windows;
- * otherwise, with R, S <= 32 and the filters of 32 output channels within 150 KB, the
- * pixel operands are read straight from x (no window in LDS).
+ * thread per output.  With C_out % 4 == 0, y aligned to four elements and tensors below
+ * 2 GiB there are faster kernels.  Where a tile of output rows (at most 256 outputs wide)
+ * and its window fit LDS (all three formats), the windows are brought in by
+ * direct-to-LDS loads a tile ahead, the filters resident in LDS (those of 32 output
+ * channels within 76 KB) or, larger, fetched chunk by chunk with the windows; otherwise,
+ * bf16 / half with R, S <= 32 and the filters of 32 output channels within 150 KB read
+ * the pixel operands straight from x (no window in LDS).
  */
 int sw_conv2d_nhwc(const float* x, const float* w, const float* bias, float* y,
                    int N, int H, int W, int C_in, int C_out, int R, int S,

@@ -1,28 +1,31 @@
-// 16-bit (bf16 or IEEE half) multi-channel convolution on channel-last tensors with both operands in LDS, the window
-// brought in by direct-to-LDS loads (paper, section 3: every tap a small matrix product whose shift is an address;
-// section 1.1: reduced precision on the same sliding sums).
+// Multi-channel convolution on channel-last tensors (fp32, bf16 or IEEE half) with both operands in LDS, the window brought
+// in by direct-to-LDS loads (paper, section 3: every tap a small matrix product whose shift is an address; section 1.1:
+// reduced precision on the same sliding sums).
 //
-//   x [N, H, W, C]     w [C_out, R, S, C]     y [N, H_out, W_out, C_out]     16-bit patterns, fp32 sums
+//   x [N, H, W, C]     w [C_out, R, S, C]     y [N, H_out, W_out, C_out]     fp32 values or 16-bit patterns, fp32 sums
 //
-// The kernel that reads its pixel operands straight from global memory (sw_mfma_bf16_nhwc.hip) is bound by cache-line
-// look-ups: a load instruction takes 32 bytes out of each of 32 lines.  Here a load instruction takes whole lines: the
-// rectangle of input pixels a tile touches (its window, padding included as out-of-range addresses that arrive as zeros)
-// goes to LDS in 16-byte pieces, 64 consecutive pieces per instruction, and the pixel operand of
-// v_mfma_f32_32x32x16_{bf16,f16} for (pixel, tap, 16 channels) is one 16-byte LDS read per lane at
-// cell(pixel) + (r IW + s) dilation.  A cell's NP pieces (8 channels each) are stored at slot = piece ^ key, key = the
-// cell's 128-byte row of LDS modulo NP, which spreads the eight cells a read serves per cycle over all banks whatever NP is.
+// The kernels that read their pixel operands straight from global memory (sw_mfma_bf16_nhwc.hip) or copy the window
+// through registers (sw_mfma_nhwc.hip) are bound by cache-line look-ups and by the copy.  Here a load instruction takes
+// whole lines: the rectangle of input pixels a tile touches (its window, padding included as out-of-range addresses that
+// arrive as zeros) goes to LDS in 16-byte pieces (8 channels, fp32: 4), 64 consecutive pieces per instruction, and a lane's
+// pixel operand for (pixel, tap, step) is one 16-byte LDS read at cell(pixel) + (r IW + s) dilation: the eight channels of
+// its half of a v_mfma_f32_32x32x16_{bf16,f16}, or the four channels that four v_mfma_f32_32x32x2_f32 take one by one (K
+// index j of lane half kq = channel 4 kq + j of the step's eight: the matrix instruction does not care which channel a K
+// index stands for as long as both operands agree).  A cell's NP pieces are stored at slot = piece ^ key, key = the cell's
+// 128-byte row of LDS modulo NP, which spreads the eight cells a read serves per cycle over all banks whatever NP is.
 //
 // Workgroup = 32 CB output channels, persistent: it fetches the filters of its channels once ([channel][tap][C] rows as
 // they lie in w, odd row pitch in pieces) and then walks over tiles of up to 128 PB output pixels (rows of one image, or
 // whole small images), the window of the next (tile, chunk of channels) in flight while this one multiplies: four
 // wavefronts only load, four multiply (pixel block 4b + w to wavefront w, all channel blocks).  Filters are the A operand,
-// pixels the B operand: a lane of the result holds, for its pixel, groups of four consecutive output channels (8-byte
-// stores).
+// pixels the B operand: a lane of the result holds, for its pixel, groups of four consecutive output channels (fp32: one
+// 16-byte store; 16-bit: 8 bytes, turned into whole 16-byte pieces through LDS where C_out allows).
 //
-// Filters too large to stay in LDS whole (3 x 3 from 144 input channels on, at 64 output channels per workgroup) travel
-// with the window instead: every stage carries the chunk's part of the filters, [channel][tap][NP pieces] at an odd row
-// pitch, fetched by the same loaders from L2 again for every tile.  The multipliers read them at the stage's address; all
-// else is the same code (FS, a compile-time switch, so that the resident form pays nothing for it).
+// Filters too large to stay in LDS whole (16-bit: 3 x 3 from 144 input channels on at 64 output channels per workgroup;
+// fp32: from 72 on) travel with the window instead: every stage carries the chunk's part of the filters,
+// [channel][tap][NP pieces] at an odd row pitch, fetched by the same loaders from L2 again for every tile.  The multipliers
+// read them at the stage's address; all else is the same code (FS, a compile-time switch, so that the resident form pays
+// nothing for it).
 #include <algorithm>
 
 #include "swconv_internal.h"
@@ -34,6 +37,7 @@ namespace {
 typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
 
@@ -48,6 +52,7 @@ constexpr unsigned kBeyond = 0x80000000u;
 struct LdsParams {
     Epilogue ep;
     int N, H, W, C, C_out, R, S, stride, pad, dil, Ho, Wo;
+    int pix_bytes, cpt;            // bytes of a pixel's channels; 16-byte pieces of a tap in a filter row (C / 8, fp32: C / 4)
     int NI, TH, tiles_y, tiles;    // images and output rows per tile, row tiles per image, tiles in all
     int IH, IW, cells_img, WC;     // window rows and columns of one image, their product, cells of a window
     int NP, chunks;                // 16-byte pieces per pixel and chunk (2, 4 or 8), chunks of 8 NP channels
@@ -67,13 +72,14 @@ __device__ __forceinline__ unsigned round16_bits(float f, bool f16)
     return (unsigned)__builtin_bit_cast(unsigned short, (__bf16)f);                // v_cvt_pk_bf16_f32: nearest even
 }
 
-// F16: IEEE half (else bf16).  CB: blocks of 32 output channels per workgroup.  PB: blocks of 32 pixels per wavefront.
+// EK: element format (fp32, bf16, IEEE half).  CB: blocks of 32 output channels per workgroup.  PB: blocks of 32 pixels per wavefront.
 // KSC: steps of 16 channels per tap and chunk (NP / 2).  FS: filters per chunk with the window (else resident).
-template <bool F16, int CB, int PB, int KSC, bool FS>
-__global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned char* __restrict__ x, const unsigned char* __restrict__ w,
-                                                                  unsigned short* __restrict__ y, const LdsParams P)
+template <int EK, int CB, int PB, int KSC, bool FS>
+__global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned char* __restrict__ x, const unsigned char* __restrict__ w,
+                                                               unsigned char* __restrict__ yb, const LdsParams P)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr bool F16 = EK == kElemF16;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int co0 = blockIdx.y * (32 * CB);
@@ -112,7 +118,7 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
             const bool in = cell < P.WC && gc >= 0 && gc < P.W;
             wimg[k] = i;
             wrow[k] = in ? e : -(1 << 20);                          // (a row that never exists)
-            wofs[k] = (unsigned)(((i * P.H + e) * P.W + gc) * (2 * P.C) + 16 * piece);
+            wofs[k] = (unsigned)(((i * P.H + e) * P.W + gc) * P.pix_bytes + 16 * piece);
         }
         // (filters per chunk) this lane's slot in each filter load of this wavefront: piece j % NP of tap j / NP of output
         // channel co, j = q % fp2; byte offset in w for chunk 0
@@ -126,7 +132,7 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
                 const int co = fast_div(q, P.by_fp2), j = q - co * P.fp2;
                 const int tap = j >> lnp, piece = j & m;
                 if (co < 32 * CB && tap < P.R * P.S && co0 + co < P.C_out)
-                    fofs[k] = (unsigned)((((co0 + co) * P.R * P.S + tap) * P.C) * 2 + 16 * piece);
+                    fofs[k] = (unsigned)(((co0 + co) * P.R * P.S + tap) * P.pix_bytes + 16 * piece);
             }
         }
         auto issue = [&](int step, int stage) __attribute__((always_inline)) {
@@ -134,7 +140,7 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
             const int tile = (int)blockIdx.x + tl * (int)gridDim.x;
             const int ig = fast_div(tile, P.by_tiles_y), ty = tile - ig * P.tiles_y;
             const int n0 = ig * P.NI, gr0 = ty * P.TH * P.stride - P.pad;
-            const unsigned origin = (unsigned)((n0 * P.H + gr0) * P.W * (2 * P.C) + ch * (16 * P.NP));
+            const unsigned origin = (unsigned)((n0 * P.H + gr0) * P.W * P.pix_bytes + ch * (16 * P.NP));
             unsigned char* sw = smem + P.win_off + stage * P.stage_bytes;
 #pragma unroll
             for (int k = 0; k < kMaxWK; ++k) {
@@ -180,7 +186,7 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
     }
     // A operand of (channel block cb, tap, step ks): resident filters: row pitch fpitch pieces, C / 8 pieces per tap, the
     // chunk's NP pieces at chunk NP; filters per chunk: row pitch fp2, NP pieces per tap
-    const int apitch = FS ? P.fp2 : P.fpitch, cpt = FS ? P.NP : P.C >> 3;
+    const int apitch = FS ? P.fp2 : P.fpitch, cpt = FS ? P.NP : P.cpt;
     const unsigned char* arow = smem + (lj * apitch + kq) * 16;            // + 32 cb apitch 16 + (tap cpt + 2 ks) 16
 
     // the lane's 16 CB output channels' biases, read once (zeros without a bias); the rectifier as a lower bound
@@ -193,9 +199,8 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
             bias[cb][v] = (P.ep.bias != nullptr && co < P.C_out) ? P.ep.bias[co] : 0.f;
         }
     const float floor_ = P.ep.relu ? 0.f : -__builtin_inff();
-    auto finish = [&](float t, int cb, int v) __attribute__((always_inline)) {
-        return round16_bits(fmaxf(t + bias[cb][v], floor_), F16);
-    };
+    auto finish32 = [&](float t, int cb, int v) __attribute__((always_inline)) { return fmaxf(t + bias[cb][v], floor_); };
+    auto finish = [&](float t, int cb, int v) __attribute__((always_inline)) { return round16_bits(finish32(t, cb, v), F16); };
 
     floatx16 acc[CB][PB];
 #pragma unroll 1
@@ -243,18 +248,33 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
         };
         auto multiply_tap = [&](const Ops& o) __attribute__((always_inline)) {
 #pragma unroll
-            for (int ks = 0; ks < KSC; ++ks)
+            for (int ks = 0; ks < KSC; ++ks) {
+                if constexpr (EK == kElemF32) {
+                    // a piece is four channels: matrix instruction j of the step takes channel j of the two lane halves' pieces
 #pragma unroll
-                for (int b = 0; b < PB; ++b)
+                    for (int j = 0; j < 4; ++j)
 #pragma unroll
-                    for (int cb = 0; cb < CB; ++cb) {
-                        if constexpr (F16)
-                            acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, o.a[ks][cb]),
-                                                                                __builtin_bit_cast(halfx8, o.b[ks][b]), acc[cb][b], 0, 0, 0);
-                        else
-                            acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.a[ks][cb]),
-                                                                                 __builtin_bit_cast(bf16x8, o.b[ks][b]), acc[cb][b], 0, 0, 0);
-                    }
+                        for (int b = 0; b < PB; ++b)
+#pragma unroll
+                            for (int cb = 0; cb < CB; ++cb) {
+                                // (the whole vector is cast, then indexed: a cast of one indexed element took element 0)
+                                const floatx4 af = __builtin_bit_cast(floatx4, o.a[ks][cb]), bf = __builtin_bit_cast(floatx4, o.b[ks][b]);
+                                acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc[cb][b], 0, 0, 0);
+                            }
+                } else {
+#pragma unroll
+                    for (int b = 0; b < PB; ++b)
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb) {
+                            if constexpr (F16)
+                                acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(halfx8, o.a[ks][cb]),
+                                                                                    __builtin_bit_cast(halfx8, o.b[ks][b]), acc[cb][b], 0, 0, 0);
+                            else
+                                acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, o.a[ks][cb]),
+                                                                                     __builtin_bit_cast(bf16x8, o.b[ks][b]), acc[cb][b], 0, 0, 0);
+                        }
+                }
+            }
         };
         read_tap(ops[0], 0);
 #pragma unroll 1
@@ -277,6 +297,30 @@ __global__ __launch_bounds__(512, 2) void mfma_16_nhwc_lds_kernel(const unsigned
         const int ig = fast_div(tile, P.by_tiles_y), ty = tile - ig * P.tiles_y;
         const int n0 = ig * P.NI, row0 = ty * P.TH;
         const int valid_px = P.NI > 1 ? min(P.NI, P.N - n0) * HoWo : min(P.TH, P.Ho - row0) * P.Wo;
+        if constexpr (EK == kElemF32) {
+            // four consecutive output channels of a pixel are 16 bytes: stored as they lie in the accumulators
+            float* y = reinterpret_cast<float*>(yb);
+#pragma unroll
+            for (int b = 0; b < PB; ++b) {
+                if (pl[b] >= valid_px) continue;
+                const int i = fast_div(pl[b], P.by_thwo), rem = pl[b] - i * thwo;       // (pixel of image n0 + i, rows from row0)
+                float* yp = y + ((int64_t)(n0 + i) * HoWo + row0 * P.Wo + rem) * P.C_out;
+#pragma unroll
+                for (int cb = 0; cb < CB; ++cb)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int co = co0 + cb * 32 + 8 * q + 4 * kq;
+                        if (co < P.C_out) {
+                            floatx4 v;
+#pragma unroll
+                            for (int j = 0; j < 4; ++j) v[j] = finish32(acc[cb][b][4 * q + j], cb, 4 * q + j);
+                            *reinterpret_cast<floatx4*>(yp + co) = v;
+                        }
+                    }
+            }
+            continue;
+        }
+        unsigned short* y = reinterpret_cast<unsigned short*>(yb);
         if (P.out_off >= 0) {
             // through LDS, so that a store instruction writes whole lines: the lane's 16 CB values go to
             // [pixel][channel] rows of this wavefront's area (8 bytes at a time), and come back as 16-byte pieces with
@@ -342,25 +386,29 @@ struct LdsPlan {
     LdsParams P;
 };
 
-LdsPlan search_plan(const Conv2dShape& s, const void* x, const void* w, const void* y)
+LdsPlan search_plan(const Conv2dShape& s, int ek, const void* x, const void* w, const void* y)
 {
     LdsPlan best;
     const int RS = s.R * s.S;
-    const int64_t x_bytes = (int64_t)s.N * s.H * s.W * s.C_in * 2, w_bytes = (int64_t)s.C_out * RS * s.C_in * 2;
-    if (s.C_in % 16 != 0 || s.C_out % 4 != 0 || x_bytes >= (1LL << 31) || w_bytes >= (1LL << 31)) return best;
-    if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0 || reinterpret_cast<uintptr_t>(y) % 8 != 0) return best;
+    const int es = (int)elem_size(ek), cpp = 16 / es;      // bytes of an element, channels in a 16-byte piece
+    const int64_t x_bytes = (int64_t)s.N * s.H * s.W * s.C_in * es, w_bytes = (int64_t)s.C_out * RS * s.C_in * es;
+    // a step of the matrix instructions takes two pieces; a lane stores four consecutive output channels at once
+    if (s.C_in % (2 * cpp) != 0 || s.C_out % 4 != 0 || x_bytes >= (1LL << 31) || w_bytes >= (1LL << 31)) return best;
+    if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0 ||
+        reinterpret_cast<uintptr_t>(y) % (4 * es) != 0)
+        return best;
     if ((int64_t)s.N * s.Ho * s.Wo * s.C_out >= (1LL << 40)) return best;
-    const int frow = RS * s.C_in / 8, fpitch = frow | 1;
+    const int frow = RS * s.C_in / cpp, fpitch = frow | 1;
     const int64_t IW = (int64_t)(s.Wo - 1) * s.stride + (int64_t)(s.S - 1) * s.dil + 1;
     const int HoWo = s.Ho * s.Wo;
     // the transposed store wants whole 16-byte pieces of y
-    const bool wide_out = s.C_out % 8 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
+    const bool wide_out = es == 2 && s.C_out % 8 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
     // CB blocks of 32 output channels per workgroup; filters resident (fstream = false) or fetched per chunk with the window;
     // NP pieces of eight channels per pixel and chunk: the wider the chunk, the fewer steps; the narrower, the larger the
     // tile LDS holds
     auto consider = [&](int CB, bool fstream, int PB, int NP, int NI, int tiles_y) {
-        if (s.C_in % (8 * NP) != 0) return;
-        const int chunks = s.C_in / (8 * NP);
+        if (s.C_in % (cpp * NP) != 0) return;
+        const int chunks = s.C_in / (cpp * NP);
         const int co_blocks = (s.C_out + 32 * CB - 1) / (32 * CB);
         if (co_blocks > 65535) return;
         const int fp2 = (RS * NP) | 1;
@@ -382,12 +430,26 @@ LdsPlan search_plan(const Conv2dShape& s, const void* x, const void* w, const vo
         const int64_t groups = (s.N + NI - 1) / NI;
         const int64_t tiles = groups * tiles_y;
         if (tiles > 2147483647LL) return;
-        // Periods of one block through all of K: every wavefront multiplies PB blocks, live or not; 256 workgroups at a
-        // time.  Two blocks per wavefront halve the filter reads per matrix instruction (LDS bandwidth bounds the one-block
-        // tiles), but with a single tap a step is too short for them to pay (measured); one channel block per workgroup
-        // doubles the window reads per matrix instruction; filters per chunk are fetched again for every tile.
-        const double est = std::max((double)PB, (double)tiles * co_blocks * PB / 256.0) * (PB == 2 ? (RS >= 4 ? 0.8 : 1.1) : 1.0) *
-                           (1.0 + 0.05 * (chunks - 1)) * (CB == 1 && s.C_out > 32 ? 1.2 : 1.0) * (fstream ? 1.3 : 1.0);
+        double est;
+        if (es == 4) {
+            // fp32: the matrix instructions bound a step (64 cycles each, four per 16-byte operand pair) unless its loads
+            // take longer (about 10 bytes per clock and CU out of L2, 5 for a single tap, whose pixels come from memory
+            // once); a step costs about 1500 cycles beyond them (pipeline fill, barrier), a tile its stores.  Cycles of a
+            // workgroup: its tiles one after the other; more workgroups than CUs run in turns.
+            const double mfma = (double)RS * (NP / 2) * 4 * CB * PB * 64;
+            const double load = (double)stage / (RS == 1 ? 5.0 : 10.0);
+            const double tile_cycles = chunks * (std::max(mfma + 700, load) + 800) + 900.0 * CB * PB;
+            const int64_t gx = std::max<int64_t>(1, std::min<int64_t>(tiles, 256 / std::min(co_blocks, 256)));
+            const double turns = std::max(1.0, (double)gx * co_blocks / 256.0);
+            est = turns * (double)((tiles + gx - 1) / gx) * tile_cycles + (double)fbytes / 13.0;
+        } else {
+            // 16-bit: LDS operand reads bound a step.  Periods of one block through all of K: every wavefront multiplies PB
+            // blocks, live or not; 256 workgroups at a time.  Two blocks per wavefront halve the filter reads per matrix
+            // instruction, but with a single tap a step is too short for them to pay (measured); one channel block per
+            // workgroup doubles the window reads per matrix instruction; filters per chunk are fetched again for every tile.
+            est = std::max((double)PB, (double)tiles * co_blocks * PB / 256.0) * (PB == 2 ? (RS >= 4 ? 0.8 : 1.1) : 1.0) *
+                  (1.0 + 0.05 * (chunks - 1)) * (CB == 1 && s.C_out > 32 ? 1.2 : 1.0) * (fstream ? 1.3 : 1.0);
+        }
         if (best.ok && (est > best.est || (est == best.est && tiles >= best.tiles))) return;
         best.ok = true;
         best.CB = CB;
@@ -400,6 +462,7 @@ LdsPlan search_plan(const Conv2dShape& s, const void* x, const void* w, const vo
         LdsParams& P = best.P;
         P.N = s.N; P.H = s.H; P.W = s.W; P.C = s.C_in; P.C_out = s.C_out; P.R = s.R; P.S = s.S; P.stride = s.stride;
         P.pad = s.pad; P.dil = s.dil; P.Ho = s.Ho; P.Wo = s.Wo;
+        P.pix_bytes = s.C_in * es; P.cpt = s.C_in / cpp;
         P.NI = NI; P.TH = TH; P.tiles_y = tiles_y; P.tiles = (int)tiles;
         P.IH = (int)IH; P.IW = (int)IW; P.cells_img = (int)(IH * IW); P.WC = (int)WC;
         P.NP = NP; P.chunks = chunks; P.wloads = (int)wloads;
@@ -430,36 +493,42 @@ LdsPlan search_plan(const Conv2dShape& s, const void* x, const void* w, const vo
 }
 
 // (the search walks a few thousand candidates: more host time than a small layer runs for)
-LdsPlan plan_lds(const Conv2dShape& s, const void* x, const void* w, const void* y)
+LdsPlan plan_lds(const Conv2dShape& s, int ek, const void* x, const void* w, const void* y)
 {
-    thread_local PlanCache<LdsPlan> cache;
-    return cache.get(s, PlanCache<LdsPlan>::low_bits(x, w, y), [&] { return search_plan(s, x, w, y); });
+    thread_local PlanCache<LdsPlan> cache[3];
+    return cache[ek].get(s, PlanCache<LdsPlan>::low_bits(x, w, y), [&] { return search_plan(s, ek, x, w, y); });
 }
 
-template <bool F16, int CB, int PB, int KSC, bool FS>
+template <int EK, int CB, int PB, int KSC, bool FS>
 hipError_t launch_lds(const void* x, const void* w, void* y, const LdsPlan& a, hipStream_t st)
 {
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_16_nhwc_lds_kernel<F16, CB, PB, KSC, FS>),
+    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_nhwc_lds_kernel<EK, CB, PB, KSC, FS>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsTotal);
     if (attr != hipSuccess) return attr;
-    SW_NOTED_LAUNCH(note_kernel(F16 ? "mfma_f16_nhwc_lds_kernel" : "mfma_bf16_nhwc_lds_kernel", CB + 10 * a.P.fstream, PB, a.P.NI, a.P.TH),
-                    (mfma_16_nhwc_lds_kernel<F16, CB, PB, KSC, FS>), dim3(a.gx, a.gy), dim3(512), a.lds, st,
-                    static_cast<const unsigned char*>(x), static_cast<const unsigned char*>(w), static_cast<unsigned short*>(y), a.P);
+    SW_NOTED_LAUNCH(note_kernel(EK == kElemF32 ? "mfma_f32_nhwc_lds_kernel" : EK == kElemF16 ? "mfma_f16_nhwc_lds_kernel" : "mfma_bf16_nhwc_lds_kernel",
+                                CB + 10 * a.P.fstream, PB, a.P.NI, a.P.TH),
+                    (mfma_nhwc_lds_kernel<EK, CB, PB, KSC, FS>), dim3(a.gx, a.gy), dim3(512), a.lds, st,
+                    static_cast<const unsigned char*>(x), static_cast<const unsigned char*>(w), static_cast<unsigned char*>(y), a.P);
     return hipGetLastError();
 }
 
 }  // namespace
 
-bool mfma_16_nhwc_lds_supported(const void* x, const void* w, const void* y, const Conv2dShape& s) { return plan_lds(s, x, w, y).ok; }
-
-hipError_t launch_mfma_16_nhwc_lds(const void* x, const void* w, void* y, const Conv2dShape& s, bool f16, const Epilogue& ep,
-                                   hipStream_t st)
+bool mfma_nhwc_lds_supported(const void* x, const void* w, const void* y, const Conv2dShape& s, int ek)
 {
-    LdsPlan a = plan_lds(s, x, w, y);
+    return ek >= 0 && ek <= 2 && plan_lds(s, ek, x, w, y).ok;
+}
+
+hipError_t launch_mfma_nhwc_lds(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep, hipStream_t st)
+{
+    if (ek < 0 || ek > 2) return hipErrorInvalidValue;
+    LdsPlan a = plan_lds(s, ek, x, w, y);
     if (!a.ok) return hipErrorInvalidValue;
     a.P.ep = ep;
-#define SW_K(CBC, PBC, KSC, FSC) \
-    return f16 ? launch_lds<true, CBC, PBC, KSC, FSC>(x, w, y, a, st) : launch_lds<false, CBC, PBC, KSC, FSC>(x, w, y, a, st)
+#define SW_K(CBC, PBC, KSC, FSC)                                                                     \
+    return ek == kElemF32   ? launch_lds<kElemF32, CBC, PBC, KSC, FSC>(x, w, y, a, st)               \
+           : ek == kElemF16 ? launch_lds<kElemF16, CBC, PBC, KSC, FSC>(x, w, y, a, st)               \
+                            : launch_lds<kElemBF16, CBC, PBC, KSC, FSC>(x, w, y, a, st)
 #define SW_F(CBC, PBC, KSC) \
     { if (a.P.fstream) SW_K(CBC, PBC, KSC, true); else SW_K(CBC, PBC, KSC, false); }
 #define SW_L(CBC, PBC)                        \

@@ -318,8 +318,8 @@ static int run_nhwc(const void* x, const void* w, const float* bias, void* y, in
     if (bias && overlaps(y, (int64_t)N * C_out * s.Ho * s.Wo * esz, bias, (int64_t)C_out * 4)) return SW_ERR_ALIAS;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const Epilogue ep{bias, relu != 0};
-    if (!force_direct() && esz == 2 && mfma_16_nhwc_lds_supported(x, w, y, s))
-        return launch_status(launch_mfma_16_nhwc_lds(x, w, y, s, ek == kElemF16, ep, st));
+    if (!force_direct() && mfma_nhwc_lds_supported(x, w, y, s, ek))
+        return launch_status(launch_mfma_nhwc_lds(x, w, y, s, ek, ep, st));
     if (!force_direct() && esz == 2 && mfma_bf16_nhwc_direct_supported(x, w, y, s))
         return launch_status(launch_mfma_bf16_nhwc_direct(x, w, y, s, ek == kElemF16, ep, st));
     if (!force_direct() && mfma_nhwc_supported(x, w, s, ek)) return launch_status(launch_mfma_nhwc(x, w, y, s, ek, ep, st));

@@ -165,11 +165,10 @@ hipError_t launch_mfma_nhwc(const void* x, const void* w, void* y, const Conv2dS
 bool       mfma_bf16_nhwc_direct_supported(const void* x, const void* w, const void* y, const Conv2dShape& s);
 hipError_t launch_mfma_bf16_nhwc_direct(const void* x, const void* w, void* y, const Conv2dShape& s, bool f16, const Epilogue& ep,
                                         hipStream_t st);
-// 16-bit formats with both operands in LDS, the window by direct-to-LDS loads (C_in % 16 == 0, C_out % 4 == 0, the
-// filters of 32 output channels within 76 KB)
-bool       mfma_16_nhwc_lds_supported(const void* x, const void* w, const void* y, const Conv2dShape& s);
-hipError_t launch_mfma_16_nhwc_lds(const void* x, const void* w, void* y, const Conv2dShape& s, bool f16, const Epilogue& ep,
-                                   hipStream_t st);
+// fp32 and the 16-bit formats (ek: Elem) with both operands in LDS, the window by direct-to-LDS loads (pixels of whole
+// 32 bytes, C_out % 4 == 0, tiles of output rows at most 256 outputs wide whose windows fit LDS)
+bool       mfma_nhwc_lds_supported(const void* x, const void* w, const void* y, const Conv2dShape& s, int ek);
+hipError_t launch_mfma_nhwc_lds(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep, hipStream_t st);
 hipError_t launch_direct_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep,
                               hipStream_t st);
 

@@ -106,36 +106,40 @@ def test_s8_nhwc_full_size_agrees_with_the_channel_first_call(torch, sw, oracle)
 FLOAT_CASES = [
     # N, H, W, C_in, C_out, R, S, stride, pad, dilation, kernel for fp32, kernel for bf16 (the window-in-LDS kernel:
     # <channel blocks per workgroup, pixel blocks per wavefront, images per tile, rows per tile>)
-    (2, 28, 28, 64, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,4>"),    # two fp32 chunks of 32 channels, one bf16 chunk
-    (1, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,2>"),    # 4-row bands (224 pixels)
-    (2, 14, 14, 128, 96, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<1,1,1,7>"),   # four / two chunks, ragged channel block
-    (2, 30, 41, 16, 40, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<2,1,1,3>"),    # blocks that span rows, ragged last block
-    (1, 57, 57, 64, 128, 3, 3, 2, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,1>"),   # stride 2
-    (1, 20, 20, 16, 32, 5, 5, 1, 2, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<1,1,1,5>"),    # 25 taps: two rounds of filter pieces
+    (2, 28, 28, 64, 64, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,4>"),    # two fp32 chunks of 32 channels, one bf16 chunk
+    (1, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,2>", "mfma_bf16_nhwc_lds_kernel<2,1,1,2>"),    # 4-row bands (224 pixels)
+    (2, 14, 14, 128, 96, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,7>", "mfma_bf16_nhwc_lds_kernel<1,1,1,7>"),   # four / two chunks, ragged channel block
+    (2, 30, 41, 16, 40, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,3>", "mfma_bf16_nhwc_lds_kernel<2,1,1,3>"),    # blocks that span rows, ragged last block
+    (1, 57, 57, 64, 128, 3, 3, 2, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,2>", "mfma_bf16_nhwc_lds_kernel<2,1,1,1>"),   # stride 2
+    (1, 20, 20, 16, 32, 5, 5, 1, 2, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,5>", "mfma_bf16_nhwc_lds_kernel<1,1,1,5>"),    # 25 taps: two rounds of filter pieces
     (1, 12, 12, 48, 64, 7, 7, 1, 3, 1, "mfma_nhwc_kernel<0,1>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # 49 taps: LDS bounds the chunk
     (2, 19, 23, 64, 70, 1, 1, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,4>"),    # pointwise
     (1, 33, 17, 16, 5, 7, 3, 2, 3, 1, "mfma_nhwc_kernel<0,2>", "mfma_nhwc_kernel<1,1>"),     # rectangular filter, few output channels
-    (1, 28, 28, 32, 64, 3, 3, 1, 2, 2, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,4>"),    # dilation 2
-    (1, 40, 40, 16, 64, 3, 3, 2, 6, 6, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<2,1,1,5>"),    # dilation 6 with stride 2
+    (1, 28, 28, 32, 64, 3, 3, 1, 2, 2, "mfma_f32_nhwc_lds_kernel<11,1,1,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,4>"),    # dilation 2
+    (1, 40, 40, 16, 64, 3, 3, 2, 6, 6, "mfma_f32_nhwc_lds_kernel<11,1,1,1>", "mfma_bf16_nhwc_lds_kernel<2,1,1,5>"),    # dilation 6 with stride 2
     (1, 9, 300, 16, 64, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<1,2>"),    # rows wider than 256 outputs
     (1, 12, 12, 12, 16, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "direct_nhwc_kernel<1>"),    # pixels that are not whole K steps
-    (1, 12, 12, 8, 16, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,1>", "direct_nhwc_kernel<1>"),     # 32 bytes per pixel in fp32, 16 in bf16
-    (1, 5, 5, 16, 8, 5, 5, 1, 0, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<1,1,1,1>"),       # a single output pixel
-    (16, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,2,1,4>"),   # enough tiles for two channel blocks per wavefront
-    (3, 21, 21, 48, 36, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<2,1,1,6>"),    # three K steps per tap (27 iterations), ragged channel block
-    (2, 16, 16, 32, 64, 2, 2, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,8>"),    # 8 iterations: two left over after the ring's trips
+    (1, 12, 12, 8, 16, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,6>", "direct_nhwc_kernel<1>"),     # 32 bytes per pixel in fp32, 16 in bf16
+    (1, 5, 5, 16, 8, 5, 5, 1, 0, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,1>", "mfma_bf16_nhwc_lds_kernel<1,1,1,1>"),       # a single output pixel
+    (16, 56, 56, 32, 64, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<12,2,1,4>", "mfma_bf16_nhwc_lds_kernel<2,2,1,4>"),   # enough tiles for two channel blocks per wavefront
+    (3, 21, 21, 48, 36, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,6>", "mfma_bf16_nhwc_lds_kernel<2,1,1,6>"),    # three K steps per tap (27 iterations), ragged channel block
+    (2, 16, 16, 32, 64, 2, 2, 1, 0, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,8>", "mfma_bf16_nhwc_lds_kernel<2,1,1,8>"),    # 8 iterations: two left over after the ring's trips
     (1, 20, 20, 32, 30, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_nhwc_kernel<1,2>"),    # an output channel count the 8-byte stores do not take: window in LDS
-    (5, 7, 7, 32, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,2,7>"),        # whole small images, several per tile, the last tile short
-    (9, 4, 4, 64, 40, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<2,1,5,4>"),    # five 4 x 4 images per tile, 9 = 5 + 4
+    (5, 7, 7, 32, 64, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,2,7>", "mfma_bf16_nhwc_lds_kernel<2,1,2,7>"),        # whole small images, several per tile, the last tile short
+    (9, 4, 4, 64, 40, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,5,4>", "mfma_bf16_nhwc_lds_kernel<2,1,5,4>"),    # five 4 x 4 images per tile, 9 = 5 + 4
     # filters too large to stay in LDS whole: the window-in-LDS kernel fetches each chunk's part with the window (first
     # number + 10)
-    (2, 14, 14, 160, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<12,1,1,7>"),   # ten chunks of 16 channels
-    (1, 16, 16, 320, 32, 2, 2, 1, 0, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<11,1,1,8>"),   # one channel block, 2 x 2
-    (32, 28, 28, 128, 128, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<12,2,1,7>"),  # two pixel blocks per wavefront
-    (4, 7, 7, 256, 64, 3, 3, 1, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<12,1,2,7>"),     # two images per tile
-    (1, 15, 15, 192, 44, 3, 3, 2, 1, 1, "mfma_nhwc_kernel<0,4>", "mfma_bf16_nhwc_lds_kernel<12,1,1,8>"),   # stride 2, ragged channel block
-    (1, 14, 14, 144, 64, 3, 3, 1, 2, 2, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<12,1,1,7>"),   # dilation 2, nine chunks
-    (2, 10, 10, 96, 64, 5, 5, 1, 2, 1, "mfma_nhwc_kernel<0,2>", "mfma_bf16_nhwc_lds_kernel<11,1,1,10>"),   # 25 taps
+    (2, 14, 14, 160, 64, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,7>", "mfma_bf16_nhwc_lds_kernel<12,1,1,7>"),   # ten chunks of 16 channels
+    (1, 16, 16, 320, 32, 2, 2, 1, 0, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,8>", "mfma_bf16_nhwc_lds_kernel<11,1,1,8>"),   # one channel block, 2 x 2
+    (32, 28, 28, 128, 128, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<12,2,1,7>", "mfma_bf16_nhwc_lds_kernel<12,2,1,7>"),  # two pixel blocks per wavefront
+    (4, 7, 7, 256, 64, 3, 3, 1, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,2,7>", "mfma_bf16_nhwc_lds_kernel<12,1,2,7>"),     # two images per tile
+    (1, 15, 15, 192, 44, 3, 3, 2, 1, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,8>", "mfma_bf16_nhwc_lds_kernel<12,1,1,8>"),   # stride 2, ragged channel block
+    (1, 14, 14, 144, 64, 3, 3, 1, 2, 2, "mfma_f32_nhwc_lds_kernel<11,1,1,7>", "mfma_bf16_nhwc_lds_kernel<12,1,1,7>"),   # dilation 2, nine chunks
+    (2, 10, 10, 96, 64, 5, 5, 1, 2, 1, "mfma_f32_nhwc_lds_kernel<11,1,1,10>", "mfma_bf16_nhwc_lds_kernel<11,1,1,10>"),   # 25 taps
+    # single taps, where fp32 keeps its filters resident as well (its other cases fetch them per chunk)
+    (8, 56, 56, 64, 64, 1, 1, 1, 0, 1, "mfma_f32_nhwc_lds_kernel<2,1,1,2>", "mfma_bf16_nhwc_lds_kernel<2,1,1,2>"),
+    (16, 14, 14, 64, 96, 1, 1, 1, 0, 1, "mfma_f32_nhwc_lds_kernel<1,1,1,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,7>"),
+    (32, 56, 56, 256, 64, 1, 1, 1, 0, 1, "mfma_f32_nhwc_lds_kernel<2,2,1,4>", "mfma_bf16_nhwc_lds_kernel<2,1,1,2>"),   # eight chunks of 32 channels, two pixel blocks per wavefront
     # rows too wide for a window tile: operands straight from global memory
     (1, 4, 300, 160, 32, 3, 3, 1, 1, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<1,2>"),     # ten K steps per tap (90 iterations)
     (1, 3, 300, 320, 32, 2, 2, 1, 0, 1, "direct_nhwc_kernel<0>", "mfma_bf16_nhwc_direct_kernel<1,2>"),     # 80 iterations: two left over after the ring's trips

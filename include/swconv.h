@@ -331,8 +331,12 @@ int sw_jit_cached_kernels(void);
  * for bit.  The matrix instruction reads 16 consecutive channels per lane, which in
  * this layout are 16 consecutive bytes: nothing is transposed on the way.  Note the
  * argument order (H, W before the channel counts).  Errors as the channel-first
- * calls.  C_in a multiple of 32, 16-byte aligned x and w and the filters of 64 output
- * channels within 96 KB run on the matrix cores (any extent and stride, C_out any);
+ * calls.  C_in a multiple of 32 and 16-byte aligned x and w run on the matrix cores:
+ * with C_out % 4 == 0, y aligned to four elements, tensors below 2 GiB and tiles of
+ * output rows (at most 256 outputs wide) whose windows fit LDS, on the kernel that
+ * brings the windows in by direct-to-LDS loads a tile ahead (the one the channel-last
+ * fp32 / bf16 / half calls run on); else, with the filters of 64 output channels within
+ * 96 KB, on one that copies them through registers (any extent and stride, C_out any);
  * every other valid shape one thread per output.
  */
 int sw_conv2d_s8_nhwc(const int8_t* x, const int8_t* w, int32_t* y,

@@ -1,4 +1,4 @@
-// Multi-channel convolution on channel-last tensors (fp32, bf16 or IEEE half) with both operands in LDS, the window brought
+// Multi-channel convolution on channel-last tensors (fp32, bf16, IEEE half or int8) with both operands in LDS, the window brought
 // in by direct-to-LDS loads (paper, section 3: every tap a small matrix product whose shift is an address; section 1.1:
 // reduced precision on the same sliding sums).
 //
@@ -21,12 +21,18 @@
 // pixels the B operand: a lane of the result holds, for its pixel, groups of four consecutive output channels (fp32: one
 // 16-byte store; 16-bit: 8 bytes, turned into whole 16-byte pieces through LDS where C_out allows).
 //
+// int8 (x, w int8; exact int32 sums): a piece is 16 channels, a step of two pieces one v_mfma_i32_32x32x32_i8.  The sums
+// leave as int32 (16-byte stores, like fp32) or requantised to int8, q = clamp(rne(scale * float(sum + bias))), with the
+// workgroup's biases and scales read from LDS, as 4 bytes per lane that pass through LDS into 16-byte pieces like the 16-bit
+// results.
+//
 // Filters too large to stay in LDS whole (16-bit: 3 x 3 from 144 input channels on at 64 output channels per workgroup;
 // fp32: from 72 on) travel with the window instead: every stage carries the chunk's part of the filters,
 // [channel][tap][NP pieces] at an odd row pitch, fetched by the same loaders from L2 again for every tile.  The multipliers
 // read them at the stage's address; all else is the same code (FS, a compile-time switch, so that the resident form pays
 // nothing for it).
 #include <algorithm>
+#include <type_traits>
 
 #include "swconv_internal.h"
 
@@ -37,6 +43,7 @@ namespace {
 typedef int intx4 __attribute__((ext_vector_type(4)));
 typedef int intx2 __attribute__((ext_vector_type(2)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef int intx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
@@ -48,9 +55,13 @@ constexpr size_t kFilterMax = 76 * 1024;       // resident filters of a workgrou
 constexpr int kMaxWK = 12;                     // window loads per loading wavefront and stage
 constexpr int kMaxFK = 12;                     // filter loads per loading wavefront and stage (filters fetched per chunk)
 constexpr unsigned kBeyond = 0x80000000u;
+// formats beyond Elem's: int8 operands with exact int32 sums, leaving as int32 or requantised to int8
+constexpr int kFmtS8 = 3, kFmtS8Q = 4, kFormats = 5;
 
 struct LdsParams {
     Epilogue ep;
+    Requant rq;                    // (int8 -> int8)
+    int rq_off;                    // (int8 -> int8) 32 CB biases, then 32 CB scales, once per workgroup
     int N, H, W, C, C_out, R, S, stride, pad, dil, Ho, Wo;
     int pix_bytes, cpt;            // bytes of a pixel's channels; 16-byte pieces of a tap in a filter row (C / 8, fp32: C / 4)
     int NI, TH, tiles_y, tiles;    // images and output rows per tile, row tiles per image, tiles in all
@@ -72,7 +83,7 @@ __device__ __forceinline__ unsigned round16_bits(float f, bool f16)
     return (unsigned)__builtin_bit_cast(unsigned short, (__bf16)f);                // v_cvt_pk_bf16_f32: nearest even
 }
 
-// EK: element format (fp32, bf16, IEEE half).  CB: blocks of 32 output channels per workgroup.  PB: blocks of 32 pixels per wavefront.
+// EK: format (Elem: fp32, bf16, IEEE half; kFmtS8, kFmtS8Q).  CB: blocks of 32 output channels per workgroup.  PB: blocks of 32 pixels per wavefront.
 // KSC: steps of 16 channels per tap and chunk (NP / 2).  FS: filters per chunk with the window (else resident).
 template <int EK, int CB, int PB, int KSC, bool FS>
 __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned char* __restrict__ x, const unsigned char* __restrict__ w,
@@ -96,6 +107,14 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
             const int co = fast_div(q, P.by_fpitch), j = q - co * P.fpitch;
             const unsigned off = (co < 32 * CB && j < P.frow && co0 + co < P.C_out) ? (unsigned)(((co0 + co) * P.frow + j) * 16) : kBeyond;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(wr, SW_LDS_PTR(smem + 1024 * k), 16, off, 0, 0, 0);
+        }
+    }
+    if constexpr (EK == kFmtS8Q) {
+        // the requantisation's bias and scale of the workgroup's channels (the first barrier orders them before their use)
+        if (tid < 32 * CB) {
+            const int co = co0 + tid;
+            reinterpret_cast<int*>(smem + P.rq_off)[tid] = (P.rq.bias != nullptr && co < P.C_out) ? P.rq.bias[co] : 0;
+            reinterpret_cast<float*>(smem + P.rq_off)[32 * CB + tid] = co < P.C_out ? P.rq.scale[co] : 0.f;
         }
     }
     if (wave >= 4) {
@@ -196,13 +215,15 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             const int co = co0 + cb * 32 + 8 * (v >> 2) + 4 * kq + (v & 3);
-            bias[cb][v] = (P.ep.bias != nullptr && co < P.C_out) ? P.ep.bias[co] : 0.f;
+            if constexpr (EK < kFmtS8) bias[cb][v] = (P.ep.bias != nullptr && co < P.C_out) ? P.ep.bias[co] : 0.f;
+            else bias[cb][v] = 0.f;
         }
     const float floor_ = P.ep.relu ? 0.f : -__builtin_inff();
     auto finish32 = [&](float t, int cb, int v) __attribute__((always_inline)) { return fmaxf(t + bias[cb][v], floor_); };
     auto finish = [&](float t, int cb, int v) __attribute__((always_inline)) { return round16_bits(finish32(t, cb, v), F16); };
 
-    floatx16 acc[CB][PB];
+    using Acc = std::conditional_t<(EK >= kFmtS8), intx16, floatx16>;
+    Acc acc[CB][PB];
 #pragma unroll 1
     for (int s = 0; s < steps_per_wg; ++s) {
         const int tl = s / P.chunks, ch = s - tl * P.chunks;               // (wave-uniform)
@@ -212,7 +233,7 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
 #pragma unroll
                 for (int b = 0; b < PB; ++b)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[cb][b][v] = 0.f;
+                    for (int v = 0; v < 16; ++v) acc[cb][b][v] = 0;
         }
         if (s == 0) __builtin_amdgcn_s_waitcnt(0);                         // (this wavefront's share of the filters)
         // barrier s, without the fence of __syncthreads: that would wait for the stores of the tile before to be
@@ -261,6 +282,12 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
                                 const floatx4 af = __builtin_bit_cast(floatx4, o.a[ks][cb]), bf = __builtin_bit_cast(floatx4, o.b[ks][b]);
                                 acc[cb][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[j], bf[j], acc[cb][b], 0, 0, 0);
                             }
+                } else if constexpr (EK >= kFmtS8) {
+#pragma unroll
+                    for (int b = 0; b < PB; ++b)
+#pragma unroll
+                        for (int cb = 0; cb < CB; ++cb)
+                            acc[cb][b] = __builtin_amdgcn_mfma_i32_32x32x32_i8(o.a[ks][cb], o.b[ks][b], acc[cb][b], 0, 0, 0);
                 } else {
 #pragma unroll
                     for (int b = 0; b < PB; ++b)
@@ -297,36 +324,65 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
         const int ig = fast_div(tile, P.by_tiles_y), ty = tile - ig * P.tiles_y;
         const int n0 = ig * P.NI, row0 = ty * P.TH;
         const int valid_px = P.NI > 1 ? min(P.NI, P.N - n0) * HoWo : min(P.TH, P.Ho - row0) * P.Wo;
-        if constexpr (EK == kElemF32) {
+        if constexpr (EK == kElemF32 || EK == kFmtS8) {
             // four consecutive output channels of a pixel are 16 bytes: stored as they lie in the accumulators
-            float* y = reinterpret_cast<float*>(yb);
+            using T = std::conditional_t<EK == kFmtS8, int, float>;
+            typedef T Tx4 __attribute__((ext_vector_type(4)));
+            T* y = reinterpret_cast<T*>(yb);
 #pragma unroll
             for (int b = 0; b < PB; ++b) {
                 if (pl[b] >= valid_px) continue;
                 const int i = fast_div(pl[b], P.by_thwo), rem = pl[b] - i * thwo;       // (pixel of image n0 + i, rows from row0)
-                float* yp = y + ((int64_t)(n0 + i) * HoWo + row0 * P.Wo + rem) * P.C_out;
+                T* yp = y + ((int64_t)(n0 + i) * HoWo + row0 * P.Wo + rem) * P.C_out;
 #pragma unroll
                 for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const int co = co0 + cb * 32 + 8 * q + 4 * kq;
                         if (co < P.C_out) {
-                            floatx4 v;
+                            Tx4 v;
 #pragma unroll
-                            for (int j = 0; j < 4; ++j) v[j] = finish32(acc[cb][b][4 * q + j], cb, 4 * q + j);
-                            *reinterpret_cast<floatx4*>(yp + co) = v;
+                            for (int j = 0; j < 4; ++j) {
+                                if constexpr (EK == kFmtS8) v[j] = acc[cb][b][4 * q + j];
+                                else v[j] = finish32(acc[cb][b][4 * q + j], cb, 4 * q + j);
+                            }
+                            *reinterpret_cast<Tx4*>(yp + co) = v;
                         }
                     }
             }
             continue;
         }
-        unsigned short* y = reinterpret_cast<unsigned short*>(yb);
+        // 16-bit and requantised int8 results: four consecutive output channels of a lane are 4 OB bytes
+        constexpr int OB = EK == kFmtS8Q ? 1 : 2;
+        using Pack = std::conditional_t<EK == kFmtS8Q, int, intx2>;
+        auto pack = [&](int cb, int b, int q) __attribute__((always_inline)) {
+            if constexpr (EK == kFmtS8Q) {
+                // q = clamp(rne(scale * float(acc + bias)), relu ? 0 : -128, 127), every step in fp32 as the definition has it
+                const int c = cb * 32 + 8 * q + 4 * kq;
+                const intx4 qb = *reinterpret_cast<const intx4*>(smem + P.rq_off + 4 * c);
+                const floatx4 qs = *reinterpret_cast<const floatx4*>(smem + P.rq_off + 4 * (32 * CB + c));
+                const float lo_ = P.rq.relu ? 0.0f : -128.0f;
+                int r = 0;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float f = rintf(__int2float_rn((int)acc[cb][b][4 * q + j] + qb[j]) * qs[j]);
+                    f = fminf(fmaxf(f, lo_), 127.0f);
+                    r |= ((int)f & 255) << (8 * j);
+                }
+                return r;
+            } else {
+                unsigned h[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) h[j] = finish(acc[cb][b][4 * q + j], cb, 4 * q + j);
+                return intx2{(int)(h[0] | (h[1] << 16)), (int)(h[2] | (h[3] << 16))};
+            }
+        };
         if (P.out_off >= 0) {
             // through LDS, so that a store instruction writes whole lines: the lane's 16 CB values go to
-            // [pixel][channel] rows of this wavefront's area (8 bytes at a time), and come back as 16-byte pieces with
+            // [pixel][channel] rows of this wavefront's area (4 OB bytes at a time), and come back as 16-byte pieces with
             // consecutive lanes on consecutive pieces of a pixel
-            constexpr int NC = 4 * CB;                                      // 16-byte pieces of a pixel's channels
-            constexpr int OP = 64 * CB + 16;                                // row pitch
+            constexpr int NC = 2 * CB * OB;                                 // 16-byte pieces of a pixel's channels
+            constexpr int OP = 32 * CB * OB + 16;                           // row pitch
             unsigned char* lo = smem + P.out_off + wave * (32 * OP);
             const int64_t tile_px0 = (int64_t)n0 * HoWo + row0 * P.Wo;
 #pragma unroll
@@ -337,10 +393,7 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
 #pragma unroll
                     for (int q = 0; q < 4; ++q) {
                         const int col = cb * 32 + 8 * q + 4 * kq;
-                        unsigned h[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) h[j] = finish(acc[cb][b][4 * q + j], cb, 4 * q + j);
-                        *reinterpret_cast<intx2*>(lo + lj * OP + 2 * col) = intx2{(int)(h[0] | (h[1] << 16)), (int)(h[2] | (h[3] << 16))};
+                        *reinterpret_cast<Pack*>(lo + lj * OP + OB * col) = pack(cb, b, q);
                     }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
@@ -348,8 +401,8 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
                     const int px = lane / NC + (64 / NC) * pass, piece = lane % NC;
                     const intx4 v = *reinterpret_cast<const intx4*>(lo + px * OP + 16 * piece);
                     const int p = 32 * (4 * b + wave) + px;
-                    if (p < valid_px && co0 + 8 * piece < P.C_out)
-                        *reinterpret_cast<intx4*>(y + (tile_px0 + p) * P.C_out + co0 + 8 * piece) = v;
+                    if (p < valid_px && co0 + (16 / OB) * piece < P.C_out)
+                        *reinterpret_cast<intx4*>(yb + ((tile_px0 + p) * P.C_out + co0) * OB + 16 * piece) = v;
                 }
                 asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // (the area is written again for the next block)
             }
@@ -359,18 +412,13 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
         for (int b = 0; b < PB; ++b) {
             if (pl[b] >= valid_px) continue;
             const int i = fast_div(pl[b], P.by_thwo), rem = pl[b] - i * thwo;       // (pixel of image n0 + i, rows from row0)
-            unsigned short* yp = y + ((int64_t)(n0 + i) * HoWo + row0 * P.Wo + rem) * P.C_out;
+            unsigned char* yp = yb + ((int64_t)(n0 + i) * HoWo + row0 * P.Wo + rem) * P.C_out * OB;
 #pragma unroll
             for (int cb = 0; cb < CB; ++cb)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int co = co0 + cb * 32 + 8 * q + 4 * kq;
-                    if (co < P.C_out) {
-                        unsigned h[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) h[j] = finish(acc[cb][b][4 * q + j], cb, 4 * q + j);
-                        *reinterpret_cast<intx2*>(yp + co) = intx2{(int)(h[0] | (h[1] << 16)), (int)(h[2] | (h[3] << 16))};
-                    }
+                    if (co < P.C_out) *reinterpret_cast<Pack*>(yp + co * OB) = pack(cb, b, q);
                 }
         }
     }
@@ -390,19 +438,20 @@ LdsPlan search_plan(const Conv2dShape& s, int ek, const void* x, const void* w, 
 {
     LdsPlan best;
     const int RS = s.R * s.S;
-    const int es = (int)elem_size(ek), cpp = 16 / es;      // bytes of an element, channels in a 16-byte piece
+    const int es = ek >= kFmtS8 ? 1 : (int)elem_size(ek), cpp = 16 / es;    // bytes of an element, channels in a 16-byte piece
+    const int ob = ek == kFmtS8 ? 4 : ek == kFmtS8Q ? 1 : es;                // bytes of an output element
     const int64_t x_bytes = (int64_t)s.N * s.H * s.W * s.C_in * es, w_bytes = (int64_t)s.C_out * RS * s.C_in * es;
     // a step of the matrix instructions takes two pieces; a lane stores four consecutive output channels at once
     if (s.C_in % (2 * cpp) != 0 || s.C_out % 4 != 0 || x_bytes >= (1LL << 31) || w_bytes >= (1LL << 31)) return best;
     if (reinterpret_cast<uintptr_t>(x) % 16 != 0 || reinterpret_cast<uintptr_t>(w) % 16 != 0 ||
-        reinterpret_cast<uintptr_t>(y) % (4 * es) != 0)
+        reinterpret_cast<uintptr_t>(y) % (4 * ob) != 0)
         return best;
     if ((int64_t)s.N * s.Ho * s.Wo * s.C_out >= (1LL << 40)) return best;
     const int frow = RS * s.C_in / cpp, fpitch = frow | 1;
     const int64_t IW = (int64_t)(s.Wo - 1) * s.stride + (int64_t)(s.S - 1) * s.dil + 1;
     const int HoWo = s.Ho * s.Wo;
     // the transposed store wants whole 16-byte pieces of y
-    const bool wide_out = es == 2 && s.C_out % 8 == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
+    const bool wide_out = ob <= 2 && s.C_out % (16 / ob) == 0 && reinterpret_cast<uintptr_t>(y) % 16 == 0;
     // CB blocks of 32 output channels per workgroup; filters resident (fstream = false) or fetched per chunk with the window;
     // NP pieces of eight channels per pixel and chunk: the wider the chunk, the fewer steps; the narrower, the larger the
     // tile LDS holds
@@ -416,7 +465,7 @@ LdsPlan search_plan(const Conv2dShape& s, int ek, const void* x, const void* w, 
         if (fsloads > 4 * kMaxFK) return;
         const size_t fbytes = fstream ? 0 : ((size_t)32 * CB * fpitch * 16 + 1023) & ~(size_t)1023;
         if (fbytes > kFilterMax) return;
-        const size_t obytes = wide_out ? (size_t)4 * 32 * (64 * CB + 16) : 0;
+        const size_t obytes = (wide_out ? (size_t)4 * 32 * (32 * CB * ob + 16) : 0) + (ek == kFmtS8Q ? 512 : 0);
         const int tp_max = 128 * PB;
         const int TH = (s.Ho + tiles_y - 1) / tiles_y;
         if ((int64_t)TH * s.Wo * NI > tp_max || (s.Ho + TH - 1) / TH != tiles_y) return;
@@ -470,6 +519,7 @@ LdsPlan search_plan(const Conv2dShape& s, int ek, const void* x, const void* w, 
         P.fstream = fstream ? 1 : 0; P.fp2 = fp2; P.fs_off = (int)(wloads * 1024); P.fsloads = (int)fsloads;
         P.win_off = (int)fbytes; P.stage_bytes = (int)stage;
         P.out_off = wide_out ? (int)(fbytes + 2 * stage) : -1;
+        P.rq_off = (int)(lds - 512);
         P.x_bytes = (unsigned)x_bytes; P.w_bytes = (unsigned)w_bytes;
         P.by_tiles_y = make_fastdiv(tiles_y);
         P.by_cells_img = make_fastdiv(P.cells_img);
@@ -495,7 +545,7 @@ LdsPlan search_plan(const Conv2dShape& s, int ek, const void* x, const void* w, 
 // (the search walks a few thousand candidates: more host time than a small layer runs for)
 LdsPlan plan_lds(const Conv2dShape& s, int ek, const void* x, const void* w, const void* y)
 {
-    thread_local PlanCache<LdsPlan> cache[3];
+    thread_local PlanCache<LdsPlan> cache[kFormats];
     return cache[ek].get(s, PlanCache<LdsPlan>::low_bits(x, w, y), [&] { return search_plan(s, ek, x, w, y); });
 }
 
@@ -505,7 +555,11 @@ hipError_t launch_lds(const void* x, const void* w, void* y, const LdsPlan& a, h
     static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_nhwc_lds_kernel<EK, CB, PB, KSC, FS>),
                                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsTotal);
     if (attr != hipSuccess) return attr;
-    SW_NOTED_LAUNCH(note_kernel(EK == kElemF32 ? "mfma_f32_nhwc_lds_kernel" : EK == kElemF16 ? "mfma_f16_nhwc_lds_kernel" : "mfma_bf16_nhwc_lds_kernel",
+    SW_NOTED_LAUNCH(note_kernel(EK == kElemF32   ? "mfma_f32_nhwc_lds_kernel"
+                                : EK == kElemF16 ? "mfma_f16_nhwc_lds_kernel"
+                                : EK == kFmtS8   ? "mfma_s8_nhwc_lds_kernel"
+                                : EK == kFmtS8Q  ? "mfma_s8q_nhwc_lds_kernel"
+                                                 : "mfma_bf16_nhwc_lds_kernel",
                                 CB + 10 * a.P.fstream, PB, a.P.NI, a.P.TH),
                     (mfma_nhwc_lds_kernel<EK, CB, PB, KSC, FS>), dim3(a.gx, a.gy), dim3(512), a.lds, st,
                     static_cast<const unsigned char*>(x), static_cast<const unsigned char*>(w), static_cast<unsigned char*>(y), a.P);
@@ -519,18 +573,29 @@ bool mfma_nhwc_lds_supported(const void* x, const void* w, const void* y, const 
     return ek >= 0 && ek <= 2 && plan_lds(s, ek, x, w, y).ok;
 }
 
-hipError_t launch_mfma_nhwc_lds(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep, hipStream_t st)
+bool mfma_s8_nhwc_lds_supported(const int8_t* x, const int8_t* w, const void* y, bool requant, const Conv2dShape& s)
 {
-    if (ek < 0 || ek > 2) return hipErrorInvalidValue;
-    LdsPlan a = plan_lds(s, ek, x, w, y);
+    return s.dil == 1 && plan_lds(s, requant ? kFmtS8Q : kFmtS8, x, w, y).ok;
+}
+
+// fmt: Elem, kFmtS8 or kFmtS8Q
+static hipError_t launch_any(const void* x, const void* w, void* y, const Conv2dShape& s, int fmt, const Epilogue& ep, const Requant& rq,
+                             hipStream_t st)
+{
+    LdsPlan a = plan_lds(s, fmt, x, w, y);
     if (!a.ok) return hipErrorInvalidValue;
     a.P.ep = ep;
-#define SW_K(CBC, PBC, KSC, FSC)                                                                     \
-    return ek == kElemF32   ? launch_lds<kElemF32, CBC, PBC, KSC, FSC>(x, w, y, a, st)               \
-           : ek == kElemF16 ? launch_lds<kElemF16, CBC, PBC, KSC, FSC>(x, w, y, a, st)               \
-                            : launch_lds<kElemBF16, CBC, PBC, KSC, FSC>(x, w, y, a, st)
+    a.P.rq = rq;
+#define SW_K(CBC, PBC, KSC, FSC)                                                                    \
+    switch (fmt) {                                                                                  \
+    case kElemF32: return launch_lds<kElemF32, CBC, PBC, KSC, FSC>(x, w, y, a, st);                 \
+    case kElemBF16: return launch_lds<kElemBF16, CBC, PBC, KSC, FSC>(x, w, y, a, st);               \
+    case kElemF16: return launch_lds<kElemF16, CBC, PBC, KSC, FSC>(x, w, y, a, st);                 \
+    case kFmtS8: return launch_lds<kFmtS8, CBC, PBC, KSC, FSC>(x, w, y, a, st);                     \
+    default: return launch_lds<kFmtS8Q, CBC, PBC, KSC, FSC>(x, w, y, a, st);                        \
+    }
 #define SW_F(CBC, PBC, KSC) \
-    { if (a.P.fstream) SW_K(CBC, PBC, KSC, true); else SW_K(CBC, PBC, KSC, false); }
+    { if (a.P.fstream) { SW_K(CBC, PBC, KSC, true) } else { SW_K(CBC, PBC, KSC, false) } }
 #define SW_L(CBC, PBC)                        \
     if (a.CB == CBC && a.PB == PBC) {         \
         if (a.P.NP == 8) SW_F(CBC, PBC, 4)    \
@@ -542,6 +607,17 @@ hipError_t launch_mfma_nhwc_lds(const void* x, const void* w, void* y, const Con
 #undef SW_F
 #undef SW_L
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_mfma_nhwc_lds(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep, hipStream_t st)
+{
+    if (ek < 0 || ek > 2) return hipErrorInvalidValue;
+    return launch_any(x, w, y, s, ek, ep, Requant{nullptr, nullptr, 0}, st);
+}
+
+hipError_t launch_mfma_s8_nhwc_lds(const int8_t* x, const int8_t* w, void* y, const Requant* rq, const Conv2dShape& s, hipStream_t st)
+{
+    return launch_any(x, w, y, s, rq ? kFmtS8Q : kFmtS8, Epilogue{nullptr, 0}, rq ? *rq : Requant{nullptr, nullptr, 0}, st);
 }
 
 }  // namespace swconv

@@ -362,6 +362,8 @@ static int run_s8_nhwc(const int8_t* x, const int8_t* w, const int32_t* bias, co
             return SW_ERR_ALIAS;
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (!force_direct() && mfma_s8_nhwc_lds_supported(x, w, y8 ? static_cast<const void*>(y8) : static_cast<const void*>(y), y8 != nullptr, s))
+        return launch_status(launch_mfma_s8_nhwc_lds(x, w, y8 ? static_cast<void*>(y8) : static_cast<void*>(y), y8 ? &rq : nullptr, s, st));
     if (!force_direct() && mfma_s8_nhwc_supported(x, w, s))
         return launch_status(launch_mfma_s8_nhwc(x, w, y, y8, y8 ? &rq : nullptr, s, st));
     return launch_status(launch_direct_s8_nhwc(x, w, y, y8, y8 ? &rq : nullptr, s, st));

@@ -169,6 +169,9 @@ hipError_t launch_mfma_bf16_nhwc_direct(const void* x, const void* w, void* y, c
 // 32 bytes, C_out % 4 == 0, tiles of output rows at most 256 outputs wide whose windows fit LDS)
 bool       mfma_nhwc_lds_supported(const void* x, const void* w, const void* y, const Conv2dShape& s, int ek);
 hipError_t launch_mfma_nhwc_lds(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep, hipStream_t st);
+// the same kernel on int8 tensors: exact int32 sums, leaving as int32 (rq null) or requantised to int8 (C_in % 32 == 0)
+bool       mfma_s8_nhwc_lds_supported(const int8_t* x, const int8_t* w, const void* y, bool requant, const Conv2dShape& s);
+hipError_t launch_mfma_s8_nhwc_lds(const int8_t* x, const int8_t* w, void* y, const Requant* rq, const Conv2dShape& s, hipStream_t st);
 hipError_t launch_direct_nhwc(const void* x, const void* w, void* y, const Conv2dShape& s, int ek, const Epilogue& ep,
                               hipStream_t st);
 

@@ -31,39 +31,55 @@ def dev(torch, a):
 
 
 CASES = [
-    # N, H, W, C_in, C_out, R, S, stride, pad
-    (2, 28, 28, 128, 128, 3, 3, 1, 1),   # workload 5's layer, channel-last: 7-row bands, two channel blocks
-    (1, 28, 28, 32, 64, 3, 3, 1, 1),     # one K step
-    (2, 14, 14, 64, 96, 3, 3, 1, 1),     # the whole image in one band, ragged channel block
-    (1, 56, 56, 64, 64, 3, 3, 1, 1),     # 4-row bands (224 pixels)
-    (2, 30, 41, 32, 40, 3, 3, 1, 1),     # blocks of 32 pixels that span rows, ragged last block
-    (1, 57, 57, 64, 128, 3, 3, 2, 1),    # stride 2
-    (1, 20, 20, 32, 32, 5, 5, 1, 2),     # 25 taps
-    (2, 19, 23, 64, 70, 1, 1, 1, 0),     # pointwise
-    (1, 33, 17, 32, 5, 7, 3, 2, 3),      # rectangular filter, few output channels
-    (1, 9, 300, 32, 64, 3, 3, 1, 1),     # rows wider than 256 outputs: one thread per output
-    (1, 12, 12, 24, 16, 3, 3, 1, 1),     # C_in not a multiple of 32: one thread per output
-    (1, 5, 5, 32, 8, 5, 5, 1, 0),        # a single output pixel
+    # N, H, W, C_in, C_out, R, S, stride, pad, kernel (int32 out; the int8-out call runs its requantising twin:
+    # mfma_s8q_nhwc_lds_kernel with the same arguments, mfma_s8_nhwc_kernel<1,KS>, direct_s8_nhwc_kernel<1>)
+    (2, 28, 28, 128, 128, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<2,1,1,4>"),   # workload 5's layer, channel-last
+    (1, 28, 28, 32, 64, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<2,1,1,4>"),     # one K step
+    (2, 14, 14, 64, 96, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<2,1,1,7>"),     # the whole image in one tile, ragged channel block
+    (1, 56, 56, 64, 64, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<2,1,1,2>"),     # 2-row tiles
+    (2, 30, 41, 32, 40, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<2,1,1,3>"),     # blocks of 32 pixels that span rows, ragged last block
+    (1, 57, 57, 64, 128, 3, 3, 2, 1, "mfma_s8_nhwc_lds_kernel<2,1,1,4>"),    # stride 2
+    (1, 20, 20, 32, 32, 5, 5, 1, 2, "mfma_s8_nhwc_lds_kernel<1,1,1,5>"),     # 25 taps
+    (2, 19, 23, 64, 70, 1, 1, 1, 0, "mfma_s8_nhwc_kernel<0,2>"),     # pointwise, an output channel count off the grid of four: window copied through registers
+    (1, 33, 17, 32, 5, 7, 3, 2, 3, "mfma_s8_nhwc_kernel<0,1>"),      # rectangular filter, few output channels
+    (1, 14, 14, 128, 30, 3, 3, 1, 1, "mfma_s8_nhwc_kernel<0,4>"),    # four K steps per tap in the register-copy kernel
+    (1, 10, 10, 256, 6, 1, 1, 1, 0, "mfma_s8_nhwc_kernel<0,0>"),     # its run-time K loop
+    (1, 9, 300, 32, 64, 3, 3, 1, 1, "direct_s8_nhwc_kernel<0>"),     # rows wider than 256 outputs: one thread per output
+    (1, 12, 12, 24, 16, 3, 3, 1, 1, "direct_s8_nhwc_kernel<0>"),     # C_in not a multiple of 32: one thread per output
+    (1, 5, 5, 32, 8, 5, 5, 1, 0, "mfma_s8_nhwc_lds_kernel<1,1,1,1>"),        # a single output pixel
+    (32, 28, 28, 128, 128, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<2,2,1,7>"),  # workload 5 at full size: two pixel blocks per wavefront
+    (4, 14, 14, 256, 64, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<1,1,1,7>"),    # one channel block per workgroup
+    (2, 14, 14, 512, 64, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<12,1,1,7>"),   # filters fetched per chunk with the window
+    (8, 56, 56, 64, 256, 1, 1, 1, 0, "mfma_s8_nhwc_lds_kernel<2,1,1,2>"),    # pointwise, four channel-block rows of workgroups
+    (5, 7, 7, 64, 64, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<2,1,2,7>"),       # whole small images, two per tile, the last tile short
+    (1, 12, 12, 32, 36, 3, 3, 1, 1, "mfma_s8_nhwc_lds_kernel<2,1,1,6>"),     # C_out % 16 != 0: int8 results leave in 4-byte stores
+    (3, 9, 9, 96, 44, 3, 3, 2, 1, "mfma_s8_nhwc_lds_kernel<2,1,3,5>"),       # three images per tile, stride 2, three chunks
 ]
 
 
-@pytest.mark.parametrize("case", CASES)
+def _requant_twin(kernel):
+    return (kernel.replace("mfma_s8_nhwc_lds_kernel", "mfma_s8q_nhwc_lds_kernel").replace("mfma_s8_nhwc_kernel<0,", "mfma_s8_nhwc_kernel<1,")
+            .replace("direct_s8_nhwc_kernel<0>", "direct_s8_nhwc_kernel<1>"))
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "x".join(map(str, c[:9])))
 def test_s8_nhwc_is_bit_exact(torch, sw, oracle, case):
-    N, H, W, C_in, C_out, R, S, stride, pad = case
+    N, H, W, C_in, C_out, R, S, stride, pad, kernel = case
     x = inputs.uniform_s8((N, H, W, C_in), 5001)
     w = inputs.uniform_s8((C_out, R, S, C_in), 5002)
     y_ref = oracle.conv2d_s8_nhwc(x, w, stride, pad)
     buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.int32)
     sw.sw_conv2d_s8_nhwc(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    assert sw.sw_last_kernel() == kernel, sw.sw_last_kernel()
     torch.cuda.synchronize()
     assert_guards_intact(buf, front, n, s)
     assert np.array_equal(out.cpu().numpy(), y_ref), f"s8 nhwc {case}"
 
 
 @pytest.mark.parametrize("relu", [False, True])
-@pytest.mark.parametrize("case", CASES)
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "x".join(map(str, c[:9])))
 def test_s8_nhwc_requant_is_bit_exact(torch, sw, oracle, case, relu):
-    N, H, W, C_in, C_out, R, S, stride, pad = case
+    N, H, W, C_in, C_out, R, S, stride, pad, kernel = case
     x = inputs.uniform_s8((N, H, W, C_in), 5011)
     w = inputs.uniform_s8((C_out, R, S, C_in), 5012)
     rng = np.random.default_rng(5013)
@@ -74,6 +90,7 @@ def test_s8_nhwc_requant_is_bit_exact(torch, sw, oracle, case, relu):
     buf, out, front, n, s = guarded_empty(torch, q_ref.shape, torch.int8, fill=77)
     sw.sw_conv2d_s8_nhwc(dev(torch, x), dev(torch, w), stride, pad, bias=dev(torch, bias), scale=dev(torch, scale),
                          relu=relu, out=out)
+    assert sw.sw_last_kernel() == _requant_twin(kernel), sw.sw_last_kernel()
     torch.cuda.synchronize()
     assert_guards_intact(buf, front, n, s)
     q = out.cpu().numpy()

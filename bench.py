@@ -68,15 +68,15 @@ MEASURED_ROOF = {"conv2d_64x64_3x3": "mfma_f32_tflops", "conv2d_s8_128x128_3x3":
 TRAFFIC_SOURCE = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs made by the builder (profiles/hbm_traffic_all_kernels.txt), "
                   "not measured by this run; null where the kernel's source has changed since")
 TRAFFIC = {
-    "depthwise_3x3": (207420770, "sw_sliding_plane.hip", "1d24ebdfa6df1cef"),
-    "depthwise_7x7": (206270013, "sw_sliding_plane.hip", "1d24ebdfa6df1cef"),
-    "conv2d_64x64_3x3": (62525393, "sw_mfma_f32.hip", "20a2d4cb31e9e833"),
-    "conv2d_s8_128x128_3x3": (22110768, "sw_mfma_s8_band.hip", "efae7346fdd97c23"),
-    "conv1d_k9": (33978820, "sw_sliding1d.hip", "b574d6ab8949af6c"),
-    "avgpool1d_w8": (34240199, "sw_sliding1d.hip", "b574d6ab8949af6c"),
-    "maxpool1d_w8": (34221227, "sw_sliding1d.hip", "b574d6ab8949af6c"),
-    "conv2d_1ch_3x3": (661835, "sw_sliding_rows.hip", "0e35510846c9b8a1"),
-    "conv2d_s8_128x128_3x3_packed": (21958711, "sw_mfma_s8_band.hip", "efae7346fdd97c23"),
+    "depthwise_3x3": (207413237, "sw_sliding_plane.hip", "1d24ebdfa6df1cef"),
+    "depthwise_7x7": (206183315, "sw_sliding_plane.hip", "1d24ebdfa6df1cef"),
+    "conv2d_64x64_3x3": (62550964, "sw_mfma_f32.hip", "20a2d4cb31e9e833"),
+    "conv2d_s8_128x128_3x3": (22096535, "sw_mfma_s8_band.hip", "efae7346fdd97c23"),
+    "conv1d_k9": (33974646, "sw_sliding1d.hip", "b574d6ab8949af6c"),
+    "avgpool1d_w8": (34237947, "sw_sliding1d.hip", "b574d6ab8949af6c"),
+    "maxpool1d_w8": (34207183, "sw_sliding1d.hip", "b574d6ab8949af6c"),
+    "conv2d_1ch_3x3": (660943, "sw_sliding_rows.hip", "0e35510846c9b8a1"),
+    "conv2d_s8_128x128_3x3_packed": (21953725, "sw_mfma_s8_band.hip", "efae7346fdd97c23"),
 }
 
 

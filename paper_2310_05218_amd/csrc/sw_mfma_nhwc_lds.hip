@@ -12,7 +12,9 @@
 // its half of a v_mfma_f32_32x32x16_{bf16,f16}, or the four channels that four v_mfma_f32_32x32x2_f32 take one by one (K
 // index j of lane half kq = channel 4 kq + j of the step's eight: the matrix instruction does not care which channel a K
 // index stands for as long as both operands agree).  A cell's NP pieces are stored at slot = piece ^ key, key = the cell's
-// 128-byte row of LDS modulo NP, which spreads the eight cells a read serves per cycle over all banks whatever NP is.
+// 256-byte row of LDS modulo NP, which spreads the 16 cells a read serves per pass over all 64 banks whatever NP is (a
+// 16-byte read is served 16 consecutive lanes at a time: measured, two lanes on one bank collide if and only if their numbers
+// differ in the low four bits only).
 //
 // Workgroup = 32 CB output channels, persistent: it fetches the filters of its channels once ([channel][tap][C] rows as
 // they lie in w, odd row pitch in pieces) and then walks over tiles of up to 128 PB output pixels (rows of one image, or
@@ -130,7 +132,7 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
         for (int k = 0; k < kMaxWK; ++k) {
             const int q = 64 * (lw + 4 * k) + lane;
             const int cell = q >> lnp, slot = q & m;                // (NP is a power of two)
-            const int piece = slot ^ ((cell >> (3 - lnp)) & m);
+            const int piece = slot ^ ((cell >> (4 - lnp)) & m);
             const int i = fast_div(cell, P.by_cells_img), rem = cell - i * P.cells_img;
             const int e = fast_div(rem, P.by_IW), f = rem - e * P.IW;
             const int gc = f - P.pad;
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
             for (int b = 0; b < PB; ++b) {
                 const int cell = cell0[b] + toff;
                 const unsigned char* cb_ = sw + ((cell << lnp) << 4);
-                const int sw_ = (cell >> (3 - lnp)) & m;
+                const int sw_ = (cell >> (4 - lnp)) & m;
 #pragma unroll
                 for (int ks = 0; ks < KSC; ++ks) o.b[ks][b] = *reinterpret_cast<const intx4*>(cb_ + (((2 * ks + kq) ^ sw_) << 4));
             }

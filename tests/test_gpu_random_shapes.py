@@ -242,3 +242,93 @@ def test_depthwise_jit_random(torch, sw, oracle, case):
     torch.cuda.synchronize()
     assert_guards_intact(buf, front, n, s)
     assert_f32_parity(out.cpu().numpy(), y_ref, d, f"jit depthwise {case} N={N} C={C}")
+
+
+# ---- channel-last tensors: fp32, bf16, IEEE half, int8 (int32 and requantised int8 out) ----
+# Channel counts on and off the grids the matrix-core kernels want (whole 32-byte pixels, C_out % 4), small and ragged
+# planes, several images per tile, strides, paddings and (float formats) dilations: the window-in-LDS kernel's planner,
+# its older companions and the one-thread-per-output kernel all take their share.
+
+def _nhwc_cases(seed, n):
+    rng = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        H, W, R, S, stride, pad = _shape(rng, max_hw=34, max_k=5)
+        N = int(rng.integers(1, 7))
+        C_in = int(rng.choice([8, 16, 24, 32, 48, 64, 96, 160, 192]))
+        C_out = int(rng.choice([4, 8, 20, 30, 32, 36, 64, 72, 100, 128]))
+        dil = int(rng.choice([1, 1, 2, 3]))
+        out.append((N, H, W, C_in, C_out, R, S, stride, pad, dil, int(rng.integers(0, 100000))))
+    return out
+
+
+def _fits(H, W, R, S, pad, dil):
+    return H + 2 * pad >= dil * (R - 1) + 1 and W + 2 * pad >= dil * (S - 1) + 1
+
+
+@pytest.mark.parametrize("case", _nhwc_cases(81, 40), ids=lambda c: "x".join(map(str, c[:10])))
+def test_conv2d_nhwc_random(torch, sw, oracle, case):
+    N, H, W, C_in, C_out, R, S, stride, pad, dil, seed = case
+    if not _fits(H, W, R, S, pad, dil):
+        dil = 1
+    x = inputs.normal_f32((N, H, W, C_in), seed)
+    w = inputs.normal_f32((C_out, R, S, C_in), seed + 1, (2.0 / (C_in * R * S)) ** 0.5)
+    b = inputs.normal_f32((C_out,), seed + 2, 0.5)
+    relu = bool(seed & 1)
+    y_ref, d = oracle.conv2d_nhwc(x, w, stride, pad, dil, b, relu)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.float32)
+    sw.sw_conv2d_nhwc(dev(torch, x), dev(torch, w), stride, pad, dil, dev(torch, b), relu, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert_f32_parity(out.cpu().numpy(), y_ref, d, f"nhwc fp32 {case} ({sw.sw_last_kernel()})")
+
+
+@pytest.mark.parametrize("half", [False, True], ids=["bf16", "f16"])
+@pytest.mark.parametrize("case", _nhwc_cases(82, 40), ids=lambda c: "x".join(map(str, c[:10])))
+def test_conv2d_nhwc_16bit_random(torch, sw, oracle, case, half):
+    N, H, W, C_in, C_out, R, S, stride, pad, dil, seed = case
+    if not _fits(H, W, R, S, pad, dil):
+        dil = 1
+    gen = inputs.normal_f16 if half else inputs.normal_bf16
+    xb = gen((N, H, W, C_in), seed)
+    wb = gen((C_out, R, S, C_in), seed + 1, (2.0 / (C_in * R * S)) ** 0.5)
+    b = inputs.normal_f32((C_out,), seed + 2, 0.5)
+    relu = bool(seed & 1)
+    ref = oracle.conv2d_f16_nhwc if half else oracle.conv2d_bf16_nhwc
+    y_ref, d = ref(xb, wb, stride, pad, dil, b, relu)
+    tdt = torch.float16 if half else torch.bfloat16
+    as_t = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(tdt)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, tdt, fill=77)
+    (sw.sw_conv2d_f16_nhwc if half else sw.sw_conv2d_bf16_nhwc)(as_t(xb), as_t(wb), stride, pad, dil, dev(torch, b), relu, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    bits = out.view(torch.int16).cpu().numpy().view(np.uint16)
+    y = (oracle.f16_to_f32(bits) if half else oracle.bf16_to_f32(bits)).astype(np.float64)
+    # fp32 sums (2e-5 D) and one rounding of the result to the 16-bit format (half a unit in the last place)
+    ulp = 2.0 ** -11 if half else 2.0 ** -8
+    floor = 2.0 ** -25 if half else 1e-37
+    assert np.all(np.abs(y - y_ref) <= 2e-5 * d + ulp * np.abs(y_ref) + floor), f"nhwc 16-bit {case} ({sw.sw_last_kernel()})"
+
+
+@pytest.mark.parametrize("case", _nhwc_cases(83, 40), ids=lambda c: "x".join(map(str, c[:9])))
+def test_conv2d_s8_nhwc_random(torch, sw, oracle, case):
+    N, H, W, C_in, C_out, R, S, stride, pad, _, seed = case
+    x = inputs.uniform_s8((N, H, W, C_in), seed)
+    w = inputs.uniform_s8((C_out, R, S, C_in), seed + 1)
+    y_ref = oracle.conv2d_s8_nhwc(x, w, stride, pad)
+    buf, out, front, n, s = guarded_empty(torch, y_ref.shape, torch.int32)
+    sw.sw_conv2d_s8_nhwc(dev(torch, x), dev(torch, w), stride, pad, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert np.array_equal(out.cpu().numpy(), y_ref), f"s8 nhwc {case} ({sw.sw_last_kernel()})"
+    rng = np.random.default_rng(seed)
+    std = (C_in * R * S) ** 0.5 * 5461.0
+    bias = rng.integers(-int(std), int(std), size=C_out).astype(np.int32)
+    scale = (rng.uniform(0.5, 2.0, size=C_out) * 60.0 / std).astype(np.float32)
+    relu = bool(seed & 1)
+    q_ref = oracle.conv2d_s8_nhwc_requant(x, w, bias, scale, stride, pad, relu)
+    buf, out, front, n, s = guarded_empty(torch, q_ref.shape, torch.int8, fill=77)
+    sw.sw_conv2d_s8_nhwc(dev(torch, x), dev(torch, w), stride, pad, bias=dev(torch, bias), scale=dev(torch, scale), relu=relu, out=out)
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert np.array_equal(out.cpu().numpy(), q_ref), f"s8 nhwc requant {case} ({sw.sw_last_kernel()})"

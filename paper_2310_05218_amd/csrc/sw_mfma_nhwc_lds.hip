@@ -130,6 +130,9 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
         unsigned wofs[kMaxWK];
 #pragma unroll
         for (int k = 0; k < kMaxWK; ++k) {
+            // (wave-uniform; the uses carry the same test.  Code that runs once costs its instruction fetches: an entry
+            // is about 40 instructions, and the workgroup's first load leaves only after the last of them)
+            if (lw + 4 * k >= P.wloads) continue;
             const int q = 64 * (lw + 4 * k) + lane;
             const int cell = q >> lnp, slot = q & m;                // (NP is a power of two)
             const int piece = slot ^ ((cell >> (4 - lnp)) & m);
@@ -148,7 +151,7 @@ __global__ __launch_bounds__(512, 2) void mfma_nhwc_lds_kernel(const unsigned ch
 #pragma unroll
         for (int k = 0; k < kMaxFK; ++k) {
             fofs[k] = kBeyond;
-            if (FS) {
+            if (FS && lw + 4 * k < P.fsloads) {
                 const int q = 64 * (lw + 4 * k) + lane;
                 const int co = fast_div(q, P.by_fp2), j = q - co * P.fp2;
                 const int tap = j >> lnp, piece = j & m;

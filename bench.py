@@ -333,6 +333,7 @@ LAYERS = [
     ("conv_bf16_nhwc_3x3_128to128_28x28", "conv_bf16_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
     ("conv_bf16_nhwc_3x3_s2_64to128", "conv_bf16_nhwc", (32, 64, 56, 56), 3, 2, 1, 128),
     ("conv_bf16_nhwc_1x1_256to64", "conv_bf16_nhwc", (32, 256, 56, 56), 1, 1, 0, 64),
+    ("conv_bf16_nhwc_3x3_256to256_14x14", "conv_bf16_nhwc", (32, 256, 14, 14), 3, 1, 1, 256),
     ("conv_f16_nhwc_3x3_64to64", "conv_f16_nhwc", (32, 64, 56, 56), 3, 1, 1, 64),      # channel-last IEEE half, fp32 accumulation
     ("conv_f16_nhwc_3x3_128to128_28x28", "conv_f16_nhwc", (32, 128, 28, 28), 3, 1, 1, 128),
     ("conv_s8_3x3_s2_64to128", "conv_s8", (32, 64, 56, 56), 3, 2, 1, 128),
@@ -346,6 +347,8 @@ LAYERS = [
     ("conv_s8_nhwc_requant_3x3_128to128", "conv_s8_nhwc_rq", (32, 128, 28, 28), 3, 1, 1, 128),
     ("conv_s8_nhwc_3x3_s2_64to128", "conv_s8_nhwc", (32, 64, 56, 56), 3, 2, 1, 128),
     ("conv_s8_nhwc_1x1_64to256", "conv_s8_nhwc", (32, 64, 56, 56), 1, 1, 0, 256),
+    ("conv_s8_nhwc_3x3_256to256_14x14", "conv_s8_nhwc", (32, 256, 14, 14), 3, 1, 1, 256),
+    ("conv_nhwc_1x1_256to64", "conv_nhwc", (32, 256, 56, 56), 1, 1, 0, 64),
 ]
 
 

@@ -278,3 +278,61 @@ def test_nhwc_is_the_channel_first_call_on_permuted_tensors(torch, sw):
     y_cf = sw.sw_conv2d(dev(torch, x), dev(torch, w), 1, 1).cpu().numpy()
     y_cl = sw.sw_conv2d_nhwc(dev(torch, x.transpose(0, 2, 3, 1)), dev(torch, w.transpose(0, 2, 3, 1)), 1, 1).cpu().numpy()
     assert np.allclose(y_cl.transpose(0, 3, 1, 2), y_cf, rtol=0, atol=2e-5 * 40)
+
+
+# ----------------------------------------------------------------------------- views that are only element-aligned
+
+def _offset_view(torch, a, off):
+    """A copy of `a` that starts `off` elements into a fresh allocation (element-aligned, not 16-byte aligned)."""
+    flat = torch.empty(a.numel() + off + 8, dtype=a.dtype, device="cuda")
+    v = flat[off:off + a.numel()].view(a.shape)
+    v.copy_(a)
+    return v
+
+
+@pytest.mark.parametrize("which", ["x", "w", "y"])
+def test_conv2d_nhwc_element_aligned_views(torch, sw, oracle, which):
+    """The matrix-core kernels want 16-byte aligned operands; a view that is only element-aligned must still give the
+    oracle's result (through whichever kernel takes it), in every format, and write nothing outside y."""
+    N, H, W, C_in, C_out = 2, 14, 14, 64, 64
+    x = inputs.normal_f32((N, H, W, C_in), 5301)
+    w = inputs.normal_f32((C_out, 3, 3, C_in), 5302, 0.05)
+    y_ref, d = oracle.conv2d_nhwc(x, w, 1, 1)
+    xd, wd = dev(torch, x), dev(torch, w)
+    if which == "x": xd = _offset_view(torch, xd, 1)
+    if which == "w": wd = _offset_view(torch, wd, 1)
+    n = y_ref.size
+    off = 1 if which == "y" else 0
+    buf = torch.full((64 + off + n + 64,), 12345.0, device="cuda")
+    out = buf[64 + off:64 + off + n].view(y_ref.shape)
+    sw.sw_conv2d_nhwc(xd, wd, 1, 1, out=out)
+    torch.cuda.synchronize()
+    assert bool((buf[:64 + off] == 12345.0).all()) and bool((buf[64 + off + n:] == 12345.0).all()), "write outside y"
+    err = float(np.max(np.abs(out.cpu().numpy().astype(np.float64) - y_ref) / np.maximum(d, 1e-300)))
+    assert err <= 2e-5, f"fp32, {which} offset: {err:.3e} ({sw.sw_last_kernel()})"
+    # bf16: one element is two bytes
+    xb, wb = inputs.normal_bf16((N, H, W, C_in), 5303), inputs.normal_bf16((C_out, 3, 3, C_in), 5304, 0.05)
+    yb_ref, db = oracle.conv2d_bf16_nhwc(xb, wb, 1, 1)
+    as_bf16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)
+    xt, wt = as_bf16(xb), as_bf16(wb)
+    if which == "x": xt = _offset_view(torch, xt, 1)
+    if which == "w": wt = _offset_view(torch, wt, 1)
+    bufb = torch.full((64 + off + n + 64,), 77.0, dtype=torch.bfloat16, device="cuda")
+    outb = bufb[64 + off:64 + off + n].view(yb_ref.shape)
+    sw.sw_conv2d_bf16_nhwc(xt, wt, 1, 1, out=outb)
+    torch.cuda.synchronize()
+    assert bool((bufb[:64 + off] == 77.0).all()) and bool((bufb[64 + off + n:] == 77.0).all()), "write outside y (bf16)"
+    yv = oracle.bf16_to_f32(outb.view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+    assert np.all(np.abs(yv - yb_ref) <= 2e-5 * db + 2.0 ** -8 * np.abs(yb_ref) + 1e-37), f"bf16, {which} offset ({sw.sw_last_kernel()})"
+    # int8 in, int32 out
+    xs, ws = inputs.uniform_s8((N, H, W, C_in), 5305), inputs.uniform_s8((C_out, 3, 3, C_in), 5306)
+    ys_ref = oracle.conv2d_s8_nhwc(xs, ws, 1, 1)
+    xq, wq = dev(torch, xs), dev(torch, ws)
+    if which == "x": xq = _offset_view(torch, xq, 1)
+    if which == "w": wq = _offset_view(torch, wq, 1)
+    bufs = torch.full((64 + off + n + 64,), 12345, dtype=torch.int32, device="cuda")
+    outs = bufs[64 + off:64 + off + n].view(ys_ref.shape)
+    sw.sw_conv2d_s8_nhwc(xq, wq, 1, 1, out=outs)
+    torch.cuda.synchronize()
+    assert bool((bufs[:64 + off] == 12345).all()) and bool((bufs[64 + off + n:] == 12345).all()), "write outside y (int8)"
+    assert np.array_equal(outs.cpu().numpy(), ys_ref), f"int8, {which} offset ({sw.sw_last_kernel()})"

@@ -336,3 +336,20 @@ def test_conv2d_nhwc_element_aligned_views(torch, sw, oracle, which):
     torch.cuda.synchronize()
     assert bool((bufs[:64 + off] == 12345).all()) and bool((bufs[64 + off + n:] == 12345).all()), "write outside y (int8)"
     assert np.array_equal(outs.cpu().numpy(), ys_ref), f"int8, {which} offset ({sw.sw_last_kernel()})"
+
+
+@pytest.mark.parametrize("shape", [(2, 14, 14, 64, 64, "mfma_s8q_nhwc_lds_kernel"), (1, 10, 10, 64, 6, "mfma_s8_nhwc_kernel")],
+                         ids=lambda s: s[5])
+def test_s8_nhwc_requant_without_bias(torch, sw, oracle, shape):
+    """scale without a bias: the requantisation adds nothing before it scales (a null bias pointer in the C call)."""
+    N, H, W, C_in, C_out, kernel = shape
+    x = inputs.uniform_s8((N, H, W, C_in), 5401)
+    w = inputs.uniform_s8((C_out, 3, 3, C_in), 5402)
+    scale = np.full((C_out,), 60.0 / ((C_in * 9) ** 0.5 * 5461.0), np.float32)
+    q_ref = oracle.conv2d_s8_nhwc_requant(x, w, np.zeros(C_out, np.int32), scale, 1, 1, False)
+    buf, out, front, n, s = guarded_empty(torch, q_ref.shape, torch.int8, fill=77)
+    sw.sw_conv2d_s8_nhwc(dev(torch, x), dev(torch, w), 1, 1, scale=dev(torch, scale), out=out)
+    assert sw.sw_last_kernel().startswith(kernel), sw.sw_last_kernel()
+    torch.cuda.synchronize()
+    assert_guards_intact(buf, front, n, s)
+    assert np.array_equal(out.cpu().numpy(), q_ref)

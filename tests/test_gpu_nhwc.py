@@ -353,3 +353,31 @@ def test_s8_nhwc_requant_without_bias(torch, sw, oracle, shape):
     torch.cuda.synchronize()
     assert_guards_intact(buf, front, n, s)
     assert np.array_equal(out.cpu().numpy(), q_ref)
+
+
+def test_conv2d_bf16_nhwc_just_below_two_gib(torch, sw, oracle):
+    """x of 2.11e9 bytes, just below the 2 GiB the buffer descriptors of the window-in-LDS kernel address: byte offsets up
+    to 2^31 - 3.6e7 in its unsigned arithmetic.  A 1 x 1 filter, so that sampled output pixels can be checked by the oracle
+    on the sampled input pixels alone (the pixels as a 1 x P image)."""
+    N, H, W, C_in, C_out = 63, 128, 128, 1024, 8
+    g = torch.Generator(device="cuda"); g.manual_seed(5501)
+    x = torch.empty((N, H, W, C_in), device="cuda", dtype=torch.bfloat16)
+    for n in range(N):                                               # (image by image: no 4 GiB fp32 temporary)
+        x[n] = torch.randn((H, W, C_in), generator=g, device="cuda").bfloat16()
+    w = (torch.randn((C_out, 1, 1, C_in), generator=g, device="cuda") * 0.03).bfloat16()
+    assert x.numel() * 2 < 2 ** 31 and x.numel() * 2 > 2.1e9
+    y = sw.sw_conv2d_bf16_nhwc(x, w, 1, 0)
+    assert sw.sw_last_kernel().startswith("mfma_bf16_nhwc_lds_kernel"), sw.sw_last_kernel()
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5502)
+    P = 512
+    idx = np.stack([rng.integers(0, N, P), rng.integers(0, H, P), rng.integers(0, W, P)], axis=1)
+    idx[:4] = [[0, 0, 0], [N - 1, H - 1, W - 1], [N - 1, 0, 0], [N // 2, H - 1, 0]]          # the corners of the address range
+    ti = torch.from_numpy(idx).cuda()
+    xs = x[ti[:, 0], ti[:, 1], ti[:, 2]].view(torch.int16).cpu().numpy().view(np.uint16).reshape(1, 1, P, C_in)
+    ys = y[ti[:, 0], ti[:, 1], ti[:, 2]].view(torch.int16).cpu().numpy().view(np.uint16).reshape(1, 1, P, C_out)
+    wb = w.view(torch.int16).cpu().numpy().view(np.uint16)
+    y_ref, d = oracle.conv2d_bf16_nhwc(xs, wb, 1, 0)
+    yv = oracle.bf16_to_f32(ys).astype(np.float64)
+    assert np.all(np.abs(yv - y_ref) <= 2e-5 * d + 2.0 ** -8 * np.abs(y_ref) + 1e-37)
+    assert np.count_nonzero(yv) > 0.99 * yv.size

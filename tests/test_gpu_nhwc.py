@@ -355,19 +355,21 @@ def test_s8_nhwc_requant_without_bias(torch, sw, oracle, shape):
     assert np.array_equal(out.cpu().numpy(), q_ref)
 
 
-def test_conv2d_bf16_nhwc_just_below_two_gib(torch, sw, oracle):
-    """x of 2.11e9 bytes, just below the 2 GiB the buffer descriptors of the window-in-LDS kernel address: byte offsets up
-    to 2^31 - 3.6e7 in its unsigned arithmetic.  A 1 x 1 filter, so that sampled output pixels can be checked by the oracle
-    on the sampled input pixels alone (the pixels as a 1 x P image)."""
-    N, H, W, C_in, C_out = 63, 128, 128, 1024, 8
+@pytest.mark.parametrize("N,kernel", [(63, "mfma_bf16_nhwc_lds_kernel"), (64, "mfma_nhwc_kernel<1,")], ids=["below", "at"])
+def test_conv2d_bf16_nhwc_around_two_gib(torch, sw, oracle, N, kernel):
+    """x of 2.11e9 bytes, just below the 2 GiB the buffer descriptors of the window-in-LDS kernel address (byte offsets up
+    to 2^31 - 3.6e7 in its unsigned arithmetic), and x of exactly 2 GiB, which that kernel must leave to the one that
+    addresses image by image in 64 bits.  A 1 x 1 filter, so that sampled output pixels can be checked by the oracle on
+    the sampled input pixels alone (the pixels as a 1 x P image)."""
+    H, W, C_in, C_out = 128, 128, 1024, 8
     g = torch.Generator(device="cuda"); g.manual_seed(5501)
     x = torch.empty((N, H, W, C_in), device="cuda", dtype=torch.bfloat16)
     for n in range(N):                                               # (image by image: no 4 GiB fp32 temporary)
         x[n] = torch.randn((H, W, C_in), generator=g, device="cuda").bfloat16()
     w = (torch.randn((C_out, 1, 1, C_in), generator=g, device="cuda") * 0.03).bfloat16()
-    assert x.numel() * 2 < 2 ** 31 and x.numel() * 2 > 2.1e9
+    assert (x.numel() * 2 < 2 ** 31) == (N == 63) and x.numel() * 2 > 2.1e9
     y = sw.sw_conv2d_bf16_nhwc(x, w, 1, 0)
-    assert sw.sw_last_kernel().startswith("mfma_bf16_nhwc_lds_kernel"), sw.sw_last_kernel()
+    assert sw.sw_last_kernel().startswith(kernel), sw.sw_last_kernel()
     torch.cuda.synchronize()
     rng = np.random.default_rng(5502)
     P = 512
